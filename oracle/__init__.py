@@ -1,0 +1,41 @@
+"""CPU oracle of the swap-executor hot path.  TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, obviously-correct Python/NumPy restatement of what the path
+computes, written from the paper (SmartSwap, arXiv 2509.11076).  Only the test
+suite, the smoke check and the CPU-baseline leg of the benchmark may import
+this package; the product (the HIP library and its binding) never does, and
+this package imports nothing from the product.  All results are integers or
+bytes, so agreement with the HIP path is exact equality.
+
+What the paper fixes and what is this build's reading of it:
+
+* trace_record    - Sec. 3 (Lightweight / Detailed mode).  Record layout and
+                    hash function are this build's choice.
+* timeline_scan   - Sec. 3 last paragraph + Sec. 4.2 (memory without/with
+                    swaps, memory reduction entries).  Intra-operator event
+                    order is this build's reading.  Pinned by the live-set
+                    definition, brute force over swap sets and a closed form.
+* similarity,
+  StageMachine    - Sec. 3, Algo. 1 with m = 2, n = 5 (Sec. 6).  Pinned by a
+                    hand-derived stage table and exact threshold cases.
+* match_anchors   - Sec. 5.1 names the features only; the algorithm is this
+                    build's.  PARITY UNPINNED against the paper; pinned against
+                    a nested-loop restatement and structural invariants.
+* apply_policy,
+  link_timing     - Sec. 5 first paragraph, Sec. 4.3 (Eq. 3, swap-in
+                    pre-trigger, swap-out completion) at operator granularity
+                    with a FIFO link; a stand-in for the paper's logical-layer
+                    simulator.  PARITY UNPINNED against the paper; pinned by the
+                    schedule checker and hand-worked cases.
+* greedy_policy   - stand-in for Algo. 2 (longest-idle-first until the peak
+                    fits).  PARITY UNPINNED against the paper; pinned by brute
+                    force on tiny traces.
+* swap_out/in     - Sec. 1, 5.2: bytes leave and return unchanged.
+"""
+from .trace import fnv1a32, make_sig, TraceRecorder
+from .timeline import timeline_scan
+from .match import similarity, StageMachine, match_anchors, match_sequence, WARMUP, GENPOLICY, STABLE
+from .policy import (link_timing, apply_policy, greedy_policy, schedule_check,
+                     K_IN, K_WAIT_IN, K_OUT, K_FREE,
+                     F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED, Infeasible)
+from .swap import swap_out, swap_in, SparseArena

@@ -1,0 +1,205 @@
+"""Pins for the oracle's link timing, policy application, greedy policy and byte round trip (CPU only)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from workloads.arena import place_tensors
+from workloads.rng import SplitMix64
+from test_oracle_trace_timeline import live_set_peak, tiny_trace
+
+INSTANT = 1 << 40          # link bytes per operator so large that every transfer fits in one operator
+
+
+def test_link_timing_hand_worked_case():
+    # bpo = 100.  A: 250 bytes, out after op 0, used at 10.  B: 100 bytes, out after 0, used at 9.
+    # C: 500 bytes, out after 2, used at 4.
+    # swap-out FIFO: A occupies [100,350) -> running op 3; B [350,450) -> op 4; C [450,950) -> op 9 >= 4: invalid
+    # swap-in as late as possible: A ends at 1000, starts 750 -> op 7; B must end by 750, starts 650 -> op 6
+    t_free, t_in, late, valid = oracle.link_timing([0, 0, 2], [10, 9, 4], [250, 100, 500], 100)
+    assert t_free == [3, 4, 9] and valid == [True, True, False]
+    assert t_in[:2] == [7, 6] and late == [False, False, False]
+    # D: 150 bytes out after op 0 ([100,250) -> op 2), used at 3: must start at 300 > 300-150: LATE, t_in = 3
+    t_free, t_in, late, valid = oracle.link_timing([0], [3], [150], 100)
+    assert (t_free, t_in, late, valid) == ([2], [3], [True], [True])
+
+
+def test_link_timing_instantaneous_link():
+    t_free, t_in, late, valid = oracle.link_timing([4, 4, 7], [20, 9, 9], [10**6, 10**9, 5], INSTANT)
+    # the last item has no room: out after 7, released after 8, needed at 9 -> issued at 9 == use:
+    # valid but late; the others move inside one operator each
+    assert t_free == [5, 5, 8] and t_in == [19, 8, 9] and late == [False, False, True]
+    assert valid == [True, True, True]
+    t_free, t_in, late, valid = oracle.link_timing([7], [8], [5], INSTANT)
+    assert valid == [False]
+
+
+def applied_for(cfg, bpo, guard=0):
+    tr = W.build_trace(W.config_shape(cfg))
+    pol = W.config_swap_set(tr, cfg)
+    place_tensors(tr.tensors, guard=guard)
+    return tr, pol, oracle.apply_policy(pol, pol["ref_op"].astype(np.int64), tr.tensors, bpo, guard=guard)
+
+
+@pytest.mark.parametrize("cfg,bpo", [(1, 64 * 1024), (1, INSTANT), (2, 8 << 20), (2, 64 << 20)])
+def test_prescribed_swap_sets_give_checkable_schedules(cfg, bpo):
+    tr, pol, ap = applied_for(cfg, bpo, guard=256)
+    k = len(pol) - ap["n_dropped"]
+    assert k > 0 and len(ap["actions"]) == 4 * k
+    assert oracle.schedule_check(ap, tr.tensors, tr.op_inputs, tr.op_outputs) == []
+    # swap-out is issued at the last forward use, the wait at the first backward use (Sec. 4.3)
+    tab = tr.tensors
+    for (op, kind, tid, batch) in ap["actions"]:
+        if kind == oracle.K_OUT:
+            assert op == tab["last_fwd_use"][tid]
+        if kind == oracle.K_WAIT_IN:
+            assert op == tab["first_bwd_use"][tid]
+    # staging: 256-aligned slots with a guard before, between and after
+    offs = sorted((d[1], d[2]) for d in ap["descs_out"])
+    assert offs[0][0] == 256 and all(o % 256 == 0 for o, _ in offs)
+    for (o0, n0), (o1, _) in zip(offs, offs[1:]):
+        assert o1 == o0 + (n0 + 255) // 256 * 256 + 256
+    assert ap["staging_bytes"] == offs[-1][0] + (offs[-1][1] + 255) // 256 * 256 + 256
+    # memory effect: the timeline with the emitted policy events equals the live-set definition
+    away = {}
+    for (op, kind, tid, batch) in ap["actions"]:
+        if kind == oracle.K_FREE:
+            away.setdefault(tid, [0, 0])[0] = op
+        if kind == oracle.K_IN:
+            away.setdefault(tid, [0, 0])[1] = op
+    res = oracle.timeline_scan(tr.events, ap["policy_events"], tr.n_ops, 0, 0)
+    assert np.array_equal(res["per_op"], live_set_peak(tab, away, tr.n_ops, 0))
+    assert res["final"] == 0
+    no = oracle.timeline_scan(tr.events, None, tr.n_ops, 0, 0)
+    assert res["peak"] <= no["peak"]
+
+
+def test_schedule_checker_catches_planted_mistakes():
+    tr, pol, ap = applied_for(1, INSTANT)
+    assert oracle.schedule_check(ap, tr.tensors, tr.op_inputs, tr.op_outputs) == []
+    # a swap-in issued after its use
+    bad = dict(ap)
+    acts = list(ap["actions"])
+    i = next(i for i, a in enumerate(acts) if a[1] == oracle.K_IN)
+    acts[i] = (tr.n_ops - 1,) + acts[i][1:]
+    bad["actions"] = sorted(acts, key=lambda a: (a[0], a[1]))
+    assert oracle.schedule_check(bad, tr.tensors, tr.op_inputs, tr.op_outputs)
+    # a block released before the tensor's last forward use
+    bad = dict(ap)
+    acts = list(ap["actions"])
+    tid = acts[i][2]
+    acts = [(0,) + a[1:] if (a[2] == tid and a[1] in (oracle.K_OUT, oracle.K_FREE)) else a for a in acts]
+    bad["actions"] = sorted(acts, key=lambda a: (a[0], a[1]))
+    assert oracle.schedule_check(bad, tr.tensors, tr.op_inputs, tr.op_outputs)
+    # overlapping staging slots
+    bad = dict(ap)
+    d = list(ap["descs_out"])
+    d[1] = (d[1][0], d[0][1] + 16) + d[1][2:]
+    bad["descs_out"] = d
+    assert oracle.schedule_check(bad, tr.tensors, tr.op_inputs, tr.op_outputs)
+
+
+def test_unmatched_and_short_lived_items_are_dropped_and_counted():
+    tr = W.build_trace(W.config_shape(1))
+    pol = W.config_swap_set(tr, 1)
+    idx = pol["ref_op"].astype(np.int64)
+    idx[0] = -1                                    # matcher found no place
+    idx[1] = tr.n_ops - 1                          # an operator without that output slot
+    ap = oracle.apply_policy(pol, idx, tr.tensors, INSTANT)
+    assert ap["n_dropped"] == 2
+    assert ap["resolved"][0][3] & oracle.F_UNMATCHED and ap["resolved"][1][3] & oracle.F_UNMATCHED
+    assert len(ap["actions"]) == 4 * (len(pol) - 2)
+    # a link so slow that nothing leaves before it is needed again: everything dropped, nothing scheduled
+    ap = oracle.apply_policy(pol, pol["ref_op"].astype(np.int64), tr.tensors, 16)
+    assert ap["n_dropped"] == len(pol) and ap["actions"] == [] and ap["staging_bytes"] == 0
+    assert all(r[3] & oracle.F_ORDER for r in ap["resolved"])
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_greedy_on_tiny_traces_against_brute_force(seed):
+    tab, ev = tiny_trace(seed, n_ops=14, T=8)
+    n_ops, base = 14, 0
+    no = oracle.timeline_scan(ev, None, n_ops, base, 0)
+    # reachable floor: swap everything that can be swapped
+    cands = [i for i in range(len(tab)) if tab["last_fwd_use"][i] + 1 < tab["first_bwd_use"][i]]
+
+    def peak_of(sub):
+        away = {i: (int(tab["last_fwd_use"][i]) + 1, int(tab["first_bwd_use"][i]) - 1) for i in sub}
+        return int(live_set_peak(tab, away, n_ops, base).max())
+
+    floor = min(peak_of(sub) for r in range(len(cands) + 1) for sub in itertools.combinations(cands, r))
+    budget = (floor + no["peak"]) // 2
+    rows, ap = oracle.greedy_policy(tab, ev, n_ops, base, budget, INSTANT)
+    chosen = [r[2] for r in rows]
+    res = oracle.timeline_scan(ev, ap["policy_events"], n_ops, base, budget)
+    # the scan's verdict on the chosen set is the brute-force (live-set) peak of that set
+    assert res["peak"] == peak_of(chosen) <= budget
+    # greedy stops at the first prefix that fits: one item fewer does not fit
+    if chosen:
+        assert peak_of(chosen[:-1]) > budget
+    # with an instantaneous link the peak never rises as items are added
+    peaks = [peak_of(chosen[:i]) for i in range(len(chosen) + 1)]
+    assert all(b <= a for a, b in zip(peaks, peaks[1:]))
+    # order: longest idle span first
+    idle = [int(tab["first_bwd_use"][i]) - int(tab["last_fwd_use"][i]) for i in chosen]
+    assert idle == sorted(idle, reverse=True)
+    # below the reachable floor the generator must give up (Algo. 2, error branch)
+    with pytest.raises(oracle.Infeasible):
+        oracle.greedy_policy(tab, ev, n_ops, base, floor - 1, INSTANT)
+
+
+def test_greedy_brings_the_7b_shape_under_its_budget():
+    tr = W.build_trace(W.config_shape(3))
+    budget = 48 * 10**9
+    no = oracle.timeline_scan(tr.events, None, tr.n_ops, 0, budget)
+    assert no["peak"] > 2 * budget * 0.95            # activations about twice the budget
+    rows, ap = oracle.greedy_policy(tr.tensors, tr.events, tr.n_ops, 0, budget, 256 << 20, min_bytes=1 << 20)
+    res = oracle.timeline_scan(tr.events, ap["policy_events"], tr.n_ops, 0, budget)
+    assert res["peak"] <= budget and res["n_over"] == 0
+    assert oracle.schedule_check(ap, tr.tensors, tr.op_inputs, tr.op_outputs) == []
+    moved = sum(d[2] for d in ap["descs_out"])
+    assert moved >= no["peak"] - budget
+
+
+# ------------------------------------------------------------- byte round trip
+def test_round_trip_is_identity_and_touches_nothing_else():
+    tr, pol, ap = applied_for(1, INSTANT, guard=256)
+    arena_bytes = place_tensors(tr.tensors, guard=256)
+    ap = oracle.apply_policy(pol, pol["ref_op"].astype(np.int64), tr.tensors, INSTANT, guard=256)
+    rng = SplitMix64(1)
+    arena = rng.bytes(arena_bytes)
+    before = arena.copy()
+    staging = np.full(ap["staging_bytes"], 0xA5, dtype=np.uint8)
+    oracle.swap_out(arena, staging, ap["descs_out"])
+    assert np.array_equal(arena, before)
+    mask = np.ones(len(staging), bool)
+    for d in ap["descs_out"]:
+        assert np.array_equal(staging[d[1]:d[1] + d[2]], before[d[0]:d[0] + d[2]])
+        mask[d[1]:d[1] + d[2]] = False
+    assert (staging[mask] == 0xA5).all()                       # guards and padding untouched
+    for d in ap["descs_out"]:                                  # blocks are released and reused
+        arena[d[0]:d[0] + d[2]] = 0xEE
+    oracle.swap_in(arena, staging, ap["descs_in"])
+    assert np.array_equal(arena, before)
+
+
+def test_round_trip_into_a_different_block_and_sparse_arena():
+    descs_out = [(1000, 0, 77, 0, 0), (5000, 256, 1, 1, 0)]
+    descs_in = [(9000, 0, 77, 0, 0), (200, 256, 1, 1, 0)]
+    arena = SplitMix64(2).bytes(10000)
+    src = arena.copy()
+    staging = np.zeros(512, np.uint8)
+    oracle.swap_out(arena, staging, descs_out)
+    oracle.swap_in(arena, staging, descs_in)
+    assert np.array_equal(arena[9000:9077], src[1000:1077]) and arena[200] == src[5000]
+    keep = np.ones(10000, bool); keep[9000:9077] = False; keep[200] = False
+    assert np.array_equal(arena[keep], src[keep])
+    sp = oracle.SparseArena()
+    sp.put(1000, src[1000:1077]); sp.put(5000, src[5000:5001])
+    st2 = np.zeros(512, np.uint8)
+    oracle.swap_out(sp, st2, descs_out)
+    assert np.array_equal(st2, staging)
+    oracle.swap_in(sp, st2, descs_in)
+    assert np.array_equal(sp.read(9000, 77), src[1000:1077])
