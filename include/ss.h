@@ -1,0 +1,330 @@
+/*
+ * ss.h - C ABI of the swap-executor hot path for AMD Instinct MI355X (gfx950).
+ *
+ * The library implements the policy-application side of swap-based memory
+ * optimisation for eager-mode LLM training (SmartSwap, arXiv 2509.11076):
+ * recording an iteration as integers (Sec. 3), scanning the memory timeline
+ * with and without a policy (Sec. 3 last paragraph, Sec. 4.2), comparing and
+ * re-anchoring operator sequences (Sec. 3 Algo. 1, Sec. 5.1), turning a policy
+ * into the iteration's swap schedule (Sec. 5 first paragraph, Sec. 4.3), and
+ * moving the selected activation tensors HBM -> pinned host memory -> HBM on
+ * dedicated streams with device-side ordering against the compute stream
+ * (Sec. 5.2).
+ *
+ * Conventions
+ *  - Plain C, no exceptions cross the boundary.  Every function returns SS_OK
+ *    (0) or a negative SS_E_* code; ss_strerror() names it; the last HIP error
+ *    code is kept in the statistics.
+ *  - "host" pointers are ordinary process memory owned by the caller and only
+ *    read or written during the call.  "device" pointers are HBM addresses.
+ *    The library never allocates or frees the caller's device arena.
+ *  - The library owns: pinned host staging, its streams and events, device
+ *    copies of descriptor tables, scratch for the scan / match kernels, and the
+ *    pinned trace arrays.
+ *  - One ss_ctx per GPU; calls on one ctx come from one host thread.
+ *  - All results are integers or bytes.
+ */
+#ifndef SS_H
+#define SS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ss_ctx ss_ctx;
+
+/* ---- error codes --------------------------------------------------------- */
+enum {
+  SS_OK = 0,
+  SS_E_INVAL = -1,      /* bad argument (null pointer, out-of-range index, overflow risk) */
+  SS_E_NOMEM = -2,      /* host, pinned or device allocation failed / staging too small */
+  SS_E_HIP = -3,        /* a HIP call failed; code in ss_stats_t.last_hip_error */
+  SS_E_INFEASIBLE = -4, /* no candidate left although memory still exceeds the budget (Algo. 2) */
+  SS_E_UNMATCHED = -5,  /* reserved: an item that must match did not */
+  SS_E_ORDER = -6,      /* events not in operator order where that is required */
+  SS_E_UNIMPL = -7,
+  SS_E_STATE = -8,      /* call out of sequence (e.g. swap before a schedule is loaded) */
+  SS_E_CAPACITY = -9    /* a caller-provided output array or a configured maximum is too small */
+};
+
+/* ---- records (all little-endian, naturally aligned, no padding) ---------- */
+
+/* One dispatched operator (Sec. 3).  op_token: dense id of the operator name,
+ * 1.. in first-seen order, 0 = padding.  stack_hash: 32-bit FNV-1a of the
+ * call-stack string, computed when the string is first seen.  sig: data-type
+ * code | (n_out & 0xff) << 8 | phase << 16 (phase 0 forward, 1 backward, 2
+ * optimizer).  n_out: number of output tensors. */
+typedef struct { uint32_t op_token, stack_hash, sig, n_out; } ss_op_t;            /* 16 B */
+
+/* One allocation (delta > 0) or release (delta < 0) of the memory trace,
+ * caused by operator op_idx (Sec. 3, last paragraph). */
+typedef struct { uint32_t op_idx, tensor_id; int64_t delta; } ss_event_t;         /* 16 B */
+
+#define SS_NONE_OP 0xFFFFFFFFu
+
+/* One tensor of the current iteration.  last_fwd_use / first_bwd_use are
+ * SS_NONE_OP when there is none.  dev_off is the block's offset in the bound
+ * arena from allocation until it is released; dev_off_in the offset of the
+ * block the tensor is swapped back into (may differ). */
+typedef struct {
+  uint32_t tensor_id, dtype, producer_op, out_slot;
+  uint32_t alloc_op, last_fwd_use, first_bwd_use, free_op;
+  uint64_t dev_off, dev_off_in, nbytes;
+} ss_tensor_t;                                                                     /* 56 B */
+
+/* Identity of a policy tensor: output slot out_slot of operator ref_op of the
+ * sequence the policy was generated for (Sec. 5.1). */
+typedef struct { uint32_t ref_op, out_slot; } ss_anchor_t;                        /* 8 B */
+
+/* One policy item (Sec. 4.3, 4.4): identity plus the four points.  As input
+ * only ref_op, out_slot, tensor_id and nbytes are read; ss_apply_policy fills
+ * the rest for the current iteration. */
+typedef struct {
+  uint32_t ref_op, out_slot, tensor_id, flags;
+  uint32_t t_out;   /* swap-out is issued after this operator (last forward use)            */
+  uint32_t t_free;  /* block is released after dispatching this operator (Sec. 5.2)          */
+  uint32_t t_in;    /* swap-in is issued before this operator (pre-trigger, Sec. 4.3.1)     */
+  uint32_t t_use;   /* first backward use: compute waits for the swap-in before it          */
+  uint64_t nbytes;
+} ss_policy_item_t;                                                                /* 40 B */
+enum { SS_F_UNMATCHED = 1, SS_F_ORDER = 2, SS_F_LATE = 4, SS_F_RESIZED = 8 };
+
+/* One copy: nbytes between arena + dev_off and staging + host_off. */
+typedef struct { uint64_t dev_off, host_off, nbytes; uint32_t tensor_id, flags; } ss_desc_t; /* 32 B */
+
+/* One scheduled action.  Inside one operator index the order is
+ * IN, WAIT_IN, [the operator itself], OUT, FREE. */
+enum { SS_ACT_IN = 0, SS_ACT_WAIT_IN = 1, SS_ACT_OUT = 2, SS_ACT_FREE = 3 };
+typedef struct { uint32_t op_idx, kind, tensor_id, batch; } ss_action_t;          /* 16 B */
+
+/* ---- configuration -------------------------------------------------------- */
+enum { SS_PATH_AUTO = 0, SS_PATH_KERNEL = 1, SS_PATH_ENGINE = 2 };
+enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch_ms)          */
+       SS_CFG_POISON_FREE = 2 }; /* overwrite a block with 0xDB when its FREE action runs     */
+typedef struct {
+  uint64_t staging_bytes;     /* pinned host staging to allocate at ss_create                */
+  uint64_t link_bytes_per_op; /* link model: bytes the host link moves during one operator
+                                 (Eq. 3 with Eq. 1 at one operator per group); >= 1           */
+  uint64_t engine_min_bytes;  /* SS_PATH_AUTO: batches whose mean tensor size reaches this go
+                                 to the copy engine, smaller ones to the copy kernel          */
+  uint32_t align;             /* staging slot alignment, power of two >= 16 (default 256)    */
+  uint32_t guard_bytes;       /* untouched bytes before/after each staging slot (mult. of align) */
+  uint32_t stage_m, stage_n;  /* Algo. 1 hyper-parameters (defaults 2, 5)                    */
+  uint32_t copy_path;         /* SS_PATH_*                                                   */
+  uint32_t copy_workgroups;   /* grid size of the copy kernels (0 = default)                 */
+  uint32_t max_ops;           /* trace capacity in operators                                 */
+  uint32_t max_events;        /* trace capacity in events                                    */
+  uint32_t flags;             /* SS_CFG_*                                                    */
+  uint32_t reserved;
+} ss_config_t;
+
+/* ---- results ---------------------------------------------------------------- */
+typedef struct {
+  int64_t peak;        /* largest memory in use at any operator (>= base)                   */
+  int64_t final_total; /* total after the last event (== base for a balanced iteration)     */
+  int32_t argpeak_op;  /* first operator attaining the peak, -1 if there are no operators   */
+  uint32_t n_over;     /* operators whose memory exceeds the budget (length of the MRL)     */
+  uint32_t sorted;     /* 1 if both event lists were in operator order                      */
+  uint32_t reserved;
+} ss_scan_result_t;
+
+enum { SS_STAGE_WARMUP = 0, SS_STAGE_GENPOLICY = 1, SS_STAGE_STABLE = 2 };
+enum { SS_MATCH_STEP_STAGE = 1,  /* advance the Algo. 1 stage machine with this verdict      */
+       SS_MATCH_HISTOGRAM = 2 }; /* cosine of per-token occurrence counts instead of positions */
+typedef struct {
+  uint64_t dot, na, nb;   /* integer sums of the cosine (na: current, nb: reference)        */
+  uint32_t similar;       /* 1 if length differs by < 5 % and cosine > 95 %                 */
+  uint32_t stage;         /* stage after this call (unchanged without SS_MATCH_STEP_STAGE)  */
+  uint32_t stable_step;   /* Algo. 1 counter after this call                                */
+  uint32_t n_unmatched;   /* anchors with new_idx == -1                                     */
+} ss_match_result_t;
+
+typedef struct {
+  uint64_t staging_bytes;   /* staging the schedule needs                                    */
+  uint64_t bytes_out;       /* sum of nbytes over swap-out descriptors (== swap-in)         */
+  uint32_t n_kept, n_dropped, n_late;
+  uint32_t n_out_batches, n_in_batches, reserved;
+} ss_apply_result_t;
+
+typedef struct {
+  uint64_t bytes_out, bytes_in;         /* since ss_create                                  */
+  uint64_t kernel_batches, engine_batches;
+  uint64_t free_waits, in_waits;        /* device-side stream waits issued for FREE / WAIT_IN */
+  uint64_t ops_recorded, events_recorded;
+  int32_t last_hip_error;               /* hipError_t of the last failing HIP call, 0 if none */
+  uint32_t reserved;
+} ss_stats_t;
+
+typedef struct {
+  double d2h_gbps, h2d_gbps;            /* one direction at a time                          */
+  double bidir_d2h_gbps, bidir_h2d_gbps;/* both directions at once, per direction           */
+  double kernel_d2h_gbps, kernel_h2d_gbps; /* same buffers through the copy kernels         */
+} ss_bw_t;
+
+/* ---- life cycle -------------------------------------------------------------- */
+
+/* Fill *cfg with defaults (staging 64 MiB, link 64 MiB/op, align 256, no guard, m=2, n=5,
+ * auto path, 65536 operators, 1048576 events). */
+int ss_config_default(ss_config_t *cfg /* host, out */);
+
+/* Create a context on the current HIP device: allocates pinned staging, the
+ * swap-out / swap-in / auxiliary streams, and pinned trace arrays.
+ * SS_E_NOMEM if pinned memory is refused. */
+int ss_create(ss_ctx **out /* host, out */, const ss_config_t *cfg /* host, nullable */);
+int ss_destroy(ss_ctx *ctx);
+
+/* Bind the caller's device arena [arena, arena + arena_bytes) and the compute
+ * stream (a hipStream_t, e.g. torch.cuda.Stream.cuda_stream; NULL = the null
+ * stream).  Every dev_off is relative to `arena`.  May be called again. */
+int ss_bind(ss_ctx *ctx, void *arena /* device */, uint64_t arena_bytes, void *compute_stream);
+
+/* ---- a1: trace record (Sec. 3) ------------------------------------------------ */
+
+/* Reduce an operator's strings to integers, once: token of `name` (dense,
+ * first-seen order), FNV-1a hash of `stack`, signature.  The hot path below
+ * never sees a string (Sec. 5.1). */
+int ss_intern_op(ss_ctx *ctx, const char *name, const char *stack, uint32_t dtype,
+                 uint32_t n_out, uint32_t phase, ss_op_t *out /* host, out */);
+
+/* Start recording a new iteration (the previous one is dropped). */
+int ss_trace_begin(ss_ctx *ctx);
+
+/* Append one dispatched operator and the n_ev alloc/free events it caused.
+ * Every event's op_idx must equal the index of this operator; token 0 is
+ * refused.  SS_E_CAPACITY beyond max_ops / max_events. */
+int ss_trace_record(ss_ctx *ctx, const ss_op_t *op /* host */, const ss_event_t *ev /* host, nullable */,
+                    uint32_t n_ev);
+
+/* Borrow the recorded arrays (valid until the next ss_trace_begin / ss_destroy)
+ * and the running sum of all deltas (0 for a balanced iteration). */
+int ss_trace_view(ss_ctx *ctx, const ss_op_t **ops, uint32_t *n_ops, const ss_event_t **ev,
+                  uint64_t *n_ev, int64_t *balance);
+
+/* ---- a2: timeline scan (Sec. 3 last paragraph, Sec. 4.2) ---------------------- */
+
+/* Memory in use per operator from the alloc/free trace `ev` and, optionally,
+ * the policy-induced events `pev` (a release of nbytes at t_free, an allocation
+ * at t_in per swapped tensor).  Memory at operator t is what was held on entry
+ * plus everything t allocates; what t releases goes when t ends; a policy
+ * allocation comes first in its operator and a policy release last.
+ *   per_op[t] = base + sum(delta of operators < t) + sum(positive delta of t)
+ *   mre[t]    = max(0, per_op[t] - budget)      (memory reduction entries)
+ * timeline (nullable, n_ev + n_pe entries) receives the running total after
+ * each event in canonical order (operator, class, position in own list; class 0
+ * policy alloc, 1 trace alloc, 2 trace release, 3 policy release); it needs both
+ * lists in operator order, else SS_E_ORDER (other outputs are still valid).
+ * All arrays are host memory; per_op / mre (nullable) have n_ops entries.
+ * SS_E_INVAL if an event names an operator >= n_ops. */
+int ss_timeline_scan(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev,
+                     const ss_event_t *pev /* nullable */, uint64_t n_pe, uint32_t n_ops,
+                     int64_t base, int64_t budget, int64_t *timeline, int64_t *per_op,
+                     int64_t *mre, ss_scan_result_t *res /* host, out */);
+
+/* ---- a3: sequence match (Sec. 3 Algo. 1, Sec. 5.1) ---------------------------- */
+
+/* (i) Similarity of the current sequence `cur` to `ref`: similar iff
+ * 20 * |m - n| < n and cosine > 0.95, the cosine taken positionally with the
+ * shorter sequence zero-padded, evaluated exactly in integers
+ * (400 dot^2 > 361 na nb, dot > 0).  With SS_MATCH_STEP_STAGE the Algo. 1 stage
+ * machine (m, n from the configuration) advances with the verdict.
+ * (ii) For each anchor the operator index in `cur` that corresponds to
+ * operator ref_op of `ref`: keyed-ordinal matching, relaxing the key from
+ * (token, stack, sig) to (token, sig) to (token); a landing place must have
+ * more than out_slot outputs and the same data-type code; among anchors landing
+ * on the same (operator, slot) the lowest anchor index keeps it.
+ * new_idx[k] (int32, -1 = none) and level[k] (0..2, 255 = none) are host arrays.
+ * Limits: tokens < 2^18, n, m <= 2^23 (keeps the sums below 2^59). */
+int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, const ss_op_t *cur, uint32_t m,
+                      const ss_anchor_t *anchors /* nullable if k == 0 */, uint32_t k, uint32_t flags,
+                      int32_t *new_idx, uint8_t *level, ss_match_result_t *res /* host, out */);
+
+/* ---- a4: apply policy (Sec. 5 first paragraph; Sec. 4.3 timing) ---------------- */
+
+/* Resolve each policy item against this iteration's tensor table (the output
+ * slot out_slot of operator new_idx[a]), take t_out / t_use from the current
+ * tensor, time release and pre-trigger with the FIFO link model
+ * (link_bytes_per_op), drop what is unmatched or has no room, and build:
+ *   resolved[k]  (nullable) the items with their points and flags filled in
+ *   actions[*n_actions]     sorted by (operator, kind, queue rank); in: capacity, out: count (4 per kept item)
+ *   descs_out / descs_in    one descriptor per kept item in swap-out / swap-in issue order (capacity k)
+ *   pevents[*n_pe]          policy events for ss_timeline_scan; in: capacity, out: count (2 per kept item)
+ * and load the schedule into the context (as ss_load_schedule would).
+ * Staging offsets are the exclusive prefix sum of align_up(nbytes, align) +
+ * guard in swap-out order.  All arrays are host memory. */
+int ss_apply_policy(ss_ctx *ctx, const ss_policy_item_t *policy, uint32_t k, const int32_t *new_idx,
+                    const ss_tensor_t *tensors, uint32_t n_tensors, ss_policy_item_t *resolved,
+                    ss_action_t *actions, uint32_t *n_actions, ss_desc_t *descs_out,
+                    ss_desc_t *descs_in, ss_event_t *pevents, uint32_t *n_pe,
+                    ss_apply_result_t *res /* host, out */);
+
+/* Borrow the batch tables of the loaded schedule: starts have n_batches + 1
+ * entries; in_dep[b] is the last swap-out batch swap-in batch b depends on. */
+int ss_schedule_view(ss_ctx *ctx, const uint32_t **out_start, uint32_t *n_out_batches,
+                     const uint32_t **in_start, uint32_t *n_in_batches, const uint32_t **in_dep);
+
+/* Load a schedule given directly as descriptors and batch boundaries (host
+ * arrays; out_start has n_out_batches + 1 entries, likewise in_start; in_dep
+ * has n_in_batches entries or is NULL = each swap-in batch waits for all
+ * swap-outs).  Every descriptor is checked against the arena and the staging
+ * area, every pair of staging slots for overlap.  Requires ss_bind. */
+int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_t n_out, const uint32_t *out_start,
+                     uint32_t n_out_batches, const ss_desc_t *descs_in, uint32_t n_in,
+                     const uint32_t *in_start, uint32_t n_in_batches, const uint32_t *in_dep);
+
+/* Longest-idle-first stand-in for the policy generator (Algo. 2): add
+ * candidates (kept from forward to backward, idle span covering an
+ * over-budget operator, nbytes >= min_bytes) one at a time, longest idle span
+ * first, re-time and re-scan until the peak fits the budget.  `initial`
+ * (nullable) are items already in force.  policy_out receives the initial
+ * items followed by the added ones; in: capacity *n_policy, out: count.
+ * SS_E_INFEASIBLE when candidates run out. */
+int ss_greedy_policy(ss_ctx *ctx, const ss_tensor_t *tensors, uint32_t n_tensors, const ss_event_t *ev,
+                     uint64_t n_ev, uint32_t n_ops, int64_t base, int64_t budget, uint64_t min_bytes,
+                     const ss_policy_item_t *initial, uint32_t n_initial,
+                     ss_policy_item_t *policy_out, uint32_t *n_policy, int64_t *peak_out);
+
+/* ---- a5 / a6 / a7: swap-out, swap-in, release and wait (Sec. 5.2) --------------- */
+
+/* Enqueue swap-out batch `batch`: the swap-out stream waits (on the device) for
+ * everything enqueued so far on the compute stream, copies each tensor of the
+ * batch to its staging slot and records the batch's done-event.  Returns at
+ * once. */
+int ss_swap_out(ss_ctx *ctx, uint32_t batch);
+
+/* Enqueue swap-in batch `batch`: the swap-in stream waits for everything
+ * enqueued so far on the compute stream (the destination blocks are free from
+ * here on) and for the swap-out batches it depends on, copies each tensor
+ * from its staging slot into its dev_off, records the done-event. */
+int ss_swap_in(ss_ctx *ctx, uint32_t batch);
+
+enum { SS_SYNC_FREE = 0,    /* id = tensor: compute stream waits (device-side) for that tensor's
+                               swap-out; after this call its block may be given to later operators */
+       SS_SYNC_WAIT_IN = 1, /* id = tensor: compute stream waits (device-side) for its swap-in     */
+       SS_SYNC_DRAIN = 2 }; /* host waits for both swap streams; surfaces asynchronous errors      */
+int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id);
+
+/* ---- support ------------------------------------------------------------------- */
+
+/* Pointer into the pinned staging area (host) for checking results. */
+int ss_host_peek(ss_ctx *ctx, uint64_t host_off, uint64_t nbytes, const void **ptr);
+/* Fill the whole staging area with a byte (host side; for guard checks). */
+int ss_staging_fill(ss_ctx *ctx, int byte);
+
+/* Duration of a batch on its swap stream in ms (needs SS_CFG_TIMING and a
+ * completed batch); dir 0 = out, 1 = in.  span_ms (nullable): first start to
+ * last end over all batches of that direction enqueued since the last drain. */
+int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms);
+
+/* Host-link bandwidth measured now: pinned hipMemcpy D2H, H2D, both at once,
+ * and the same through the copy kernels; `bytes` per transfer, median of `reps`. */
+int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *out /* host, out */);
+
+int ss_get_stats(ss_ctx *ctx, ss_stats_t *out /* host, out */);
+const char *ss_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SS_H */

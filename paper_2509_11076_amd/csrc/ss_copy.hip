@@ -1,0 +1,109 @@
+// Batched gather-pack (HBM -> pinned host staging) and scatter-unpack (staging -> HBM)
+// copy kernels for gfx950.
+//
+// Swap-out moves a tensor to host memory after its last forward use, swap-in
+// brings it back before its first backward use (Sec. 1, Sec. 5.2 of the
+// SmartSwap paper).  The paper issues one framework copy per tensor; small
+// tensors then waste the link (Sec. 4.2).  Here one launch moves a whole batch
+// of variable-size tensors: the batch is cut into 64 KiB chunks, a small
+// persistent grid walks the chunks, and each workgroup finds its chunk's
+// descriptor by binary search in a chunk-prefix table staged in LDS.  All
+// traffic is 16 bytes per lane, a wavefront touching 1 KiB of consecutive
+// addresses on both sides; a byte tail handles sizes that are not multiples of
+// 16.  The staging area is host memory mapped into the device address space,
+// so the stores (swap-out) or loads (swap-in) cross the host link directly.
+//
+// The path is bound by the host link (tens of GB/s), not by HBM (8 TB/s): a few
+// dozen workgroups saturate it, which leaves the compute units to the
+// training step running on the compute stream.
+#include "ss_internal.h"
+
+namespace {
+
+constexpr uint32_t kUnroll = 8;
+constexpr uint32_t kLdsEntries = 8192;   // chunk-prefix entries staged in LDS (32 KiB)
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool TO_HOST>
+__global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
+    uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
+    const uint32_t *__restrict__ chunk0, uint32_t n_desc, uint32_t n_chunks) {
+  __shared__ uint32_t s_chunk0[kLdsEntries];
+  const uint32_t tid = threadIdx.x;
+  const bool in_lds = n_desc + 1 <= kLdsEntries;
+  if (in_lds) {
+    for (uint32_t i = tid; i <= n_desc; i += SS_COPY_THREADS) s_chunk0[i] = chunk0[i];
+    __syncthreads();
+  }
+  const uint32_t *prefix = in_lds ? s_chunk0 : chunk0;
+
+  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    // largest d with prefix[d] <= c (descriptors without chunks are skipped by construction)
+    uint32_t lo = 0, hi = n_desc;
+    while (hi - lo > 1) {
+      uint32_t mid = (lo + hi) >> 1;
+      if (prefix[mid] <= c) lo = mid; else hi = mid;
+    }
+    const ss_desc_t d = descs[lo];
+    const uint64_t off = (uint64_t)(c - prefix[lo]) * SS_CHUNK_BYTES;
+    const uint64_t left = d.nbytes - off;
+    const uint32_t n = left < SS_CHUNK_BYTES ? (uint32_t)left : SS_CHUNK_BYTES;
+    const uint8_t *src = TO_HOST ? arena + d.dev_off + off : staging + d.host_off + off;
+    uint8_t *dst = TO_HOST ? staging + d.host_off + off : arena + d.dev_off + off;
+
+    const u32x4 *src16 = reinterpret_cast<const u32x4 *>(src);
+    u32x4 *dst16 = reinterpret_cast<u32x4 *>(dst);
+    const uint32_t n16 = n >> 4;
+    for (uint32_t base = 0; base < n16; base += SS_COPY_THREADS * kUnroll) {
+      u32x4 v[kUnroll];
+#pragma unroll
+      for (uint32_t u = 0; u < kUnroll; ++u) {
+        const uint32_t i = base + u * SS_COPY_THREADS + tid;
+        if (i < n16) v[u] = __builtin_nontemporal_load(src16 + i);
+      }
+#pragma unroll
+      for (uint32_t u = 0; u < kUnroll; ++u) {
+        const uint32_t i = base + u * SS_COPY_THREADS + tid;
+        if (i < n16) __builtin_nontemporal_store(v[u], dst16 + i);
+      }
+    }
+    const uint32_t tail = n & 15u;          // only the last chunk of a tensor can have one
+    if (tid < tail) dst[(n16 << 4) + tid] = src[(n16 << 4) + tid];
+  }
+}
+
+__global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nbytes, uint32_t word) {
+  // dst is 16-byte aligned (checked by the caller)
+  const uint64_t n16 = nbytes >> 4;
+  u32x4 w = {word, word, word, word};
+  u32x4 *d16 = reinterpret_cast<u32x4 *>(dst);
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (uint64_t)gridDim.x * blockDim.x)
+    d16[i] = w;
+  if (blockIdx.x == 0 && threadIdx.x < (nbytes & 15u)) dst[(n16 << 4) + threadIdx.x] = (uint8_t)word;
+}
+
+}  // namespace
+
+void ss_launch_copy(hipStream_t s, uint32_t workgroups, bool to_host, uint8_t *arena, uint8_t *staging,
+                    const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc, uint32_t n_chunks) {
+  if (n_chunks == 0 || n_desc == 0) return;
+  uint32_t grid = workgroups < n_chunks ? workgroups : n_chunks;
+  if (to_host)
+    hipLaunchKernelGGL(ss_copy_kernel<true>, dim3(grid), dim3(SS_COPY_THREADS), 0, s, arena, staging, d_descs,
+                       d_chunk0, n_desc, n_chunks);
+  else
+    hipLaunchKernelGGL(ss_copy_kernel<false>, dim3(grid), dim3(SS_COPY_THREADS), 0, s, arena, staging, d_descs,
+                       d_chunk0, n_desc, n_chunks);
+}
+
+void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value) {
+  if (nbytes == 0) return;
+  uint32_t word = value * 0x01010101u;
+  uint64_t n16 = nbytes >> 4;
+  uint32_t grid = (uint32_t)((n16 + 255) / 256);
+  if (grid == 0) grid = 1;
+  if (grid > 1024) grid = 1024;
+  hipLaunchKernelGGL(ss_fill_kernel, dim3(grid), dim3(256), 0, s, dst, nbytes, word);
+}

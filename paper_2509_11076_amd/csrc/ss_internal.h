@@ -1,0 +1,92 @@
+// Internal declarations shared by the translation units of libss.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "ss.h"
+
+struct ss_sched {
+  std::vector<ss_desc_t> out, in;                 // host copies, issue order
+  std::vector<uint32_t> out_start, in_start;      // batch boundaries (n_batches + 1)
+  std::vector<uint32_t> in_dep;                   // per swap-in batch: last swap-out batch needed
+  std::vector<uint32_t> out_chunk0, in_chunk0;    // per descriptor: first chunk index inside its batch
+  std::unordered_map<uint32_t, uint32_t> out_of_tensor, in_of_tensor;  // tensor id -> descriptor index
+  std::vector<uint32_t> out_batch_of, in_batch_of;                      // descriptor index -> batch
+  std::vector<uint8_t> out_waited, in_waited, out_issued, in_issued;    // per batch, this iteration
+  std::vector<hipEvent_t> ev_out_done, ev_in_done, ev_out_start, ev_in_start;
+  ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
+  uint32_t *d_out_chunk0 = nullptr, *d_in_chunk0 = nullptr;
+  size_t d_cap_out = 0, d_cap_in = 0;
+  bool loaded = false;
+};
+
+struct ss_ctx {
+  ss_config_t cfg;
+  int device = 0;
+  // bound by the caller
+  uint8_t *arena = nullptr;
+  uint64_t arena_bytes = 0;
+  hipStream_t compute = nullptr;
+  bool bound = false;
+  // owned
+  uint8_t *staging = nullptr;       // pinned, host address
+  uint8_t *staging_dev = nullptr;   // same memory, device address
+  hipStream_t s_out = nullptr, s_in = nullptr, s_aux = nullptr;
+  std::vector<hipEvent_t> ev_ring;  // compute-stream markers, used round-robin
+  size_t ev_next = 0;
+  // trace
+  ss_op_t *ops = nullptr;           // pinned
+  ss_event_t *events = nullptr;     // pinned
+  uint32_t n_ops = 0;
+  uint64_t n_events = 0;
+  int64_t balance = 0;
+  std::unordered_map<std::string, uint32_t> tokens;
+  std::unordered_map<std::string, uint32_t> stacks;
+  // stage machine (Algo. 1)
+  uint32_t stage = SS_STAGE_WARMUP, stable_step = 0;
+  // scratch for scan / match (device + pinned mirrors), grown on demand
+  void *d_scratch = nullptr;
+  size_t d_scratch_bytes = 0;
+  void *h_scratch = nullptr;        // pinned
+  size_t h_scratch_bytes = 0;
+  ss_sched sched;
+  ss_stats_t stats;
+};
+
+#define SS_HIP(call)                                      \
+  do {                                                    \
+    hipError_t e__ = (call);                              \
+    if (e__ != hipSuccess) {                              \
+      ctx->stats.last_hip_error = (int32_t)e__;           \
+      (void)hipGetLastError();                            \
+      return SS_E_HIP;                                    \
+    }                                                     \
+  } while (0)
+
+static inline uint64_t ss_align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+// scratch management (ss_runtime.hip)
+int ss_scratch_reserve(ss_ctx *ctx, size_t dev_bytes, size_t host_bytes);
+
+// internal entry used by the greedy generator: timing + schedule without loading it
+struct ss_applied {
+  std::vector<ss_policy_item_t> resolved;
+  std::vector<ss_action_t> actions;
+  std::vector<ss_desc_t> out, in;
+  std::vector<uint32_t> out_start, in_start, in_dep;
+  std::vector<ss_event_t> pevents;
+  uint64_t staging_bytes = 0, bytes_out = 0;
+  uint32_t n_kept = 0, n_dropped = 0, n_late = 0;
+};
+int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32_t k, const int32_t *new_idx,
+                  const ss_tensor_t *tensors, uint32_t n_tensors, ss_applied &out);
+
+// copy kernels (ss_copy.hip)
+constexpr uint32_t SS_CHUNK_BYTES = 64 * 1024;
+constexpr uint32_t SS_COPY_THREADS = 256;
+void ss_launch_copy(hipStream_t s, uint32_t workgroups, bool to_host, uint8_t *arena, uint8_t *staging,
+                    const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc, uint32_t n_chunks);
+void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);

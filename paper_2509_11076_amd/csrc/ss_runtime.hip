@@ -1,0 +1,607 @@
+// Host runtime of libss: context, streams and events, schedule loading, and the
+// swap-out / swap-in / release calls with device-side ordering (Sec. 5.2 of the
+// SmartSwap paper: swaps run on their own stream; a swapped-out block is handed
+// back right after the operator that is running when the swap-out completes,
+// by making the compute stream wait on the device instead of polling events on
+// the host).
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+
+#include "ss_internal.h"
+
+extern "C" const char *ss_strerror(int code) {
+  switch (code) {
+    case SS_OK: return "ok";
+    case SS_E_INVAL: return "invalid argument";
+    case SS_E_NOMEM: return "out of memory (host, pinned or device) or staging too small";
+    case SS_E_HIP: return "HIP call failed (see ss_stats_t.last_hip_error)";
+    case SS_E_INFEASIBLE: return "no candidate left while memory still exceeds the budget";
+    case SS_E_UNMATCHED: return "policy item without a match";
+    case SS_E_ORDER: return "events not in operator order";
+    case SS_E_UNIMPL: return "not implemented";
+    case SS_E_STATE: return "call out of sequence";
+    case SS_E_CAPACITY: return "output array or configured capacity too small";
+    default: return "unknown error";
+  }
+}
+
+extern "C" int ss_config_default(ss_config_t *cfg) {
+  if (!cfg) return SS_E_INVAL;
+  std::memset(cfg, 0, sizeof(*cfg));
+  cfg->staging_bytes = 64ull << 20;
+  cfg->link_bytes_per_op = 64ull << 20;
+  cfg->engine_min_bytes = ~0ull;       // AUTO = copy kernel unless told otherwise
+  cfg->align = 256;
+  cfg->guard_bytes = 0;
+  cfg->stage_m = 2;
+  cfg->stage_n = 5;
+  cfg->copy_path = SS_PATH_AUTO;
+  cfg->copy_workgroups = 0;
+  cfg->max_ops = 65536;
+  cfg->max_events = 1u << 20;
+  cfg->flags = 0;
+  return SS_OK;
+}
+
+static uint32_t default_workgroups() { return 64; }
+
+extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
+  if (!out) return SS_E_INVAL;
+  *out = nullptr;
+  ss_config_t cfg;
+  ss_config_default(&cfg);
+  if (cfg_in) cfg = *cfg_in;
+  if (cfg.align < 16 || (cfg.align & (cfg.align - 1)) || cfg.guard_bytes % cfg.align ||
+      cfg.link_bytes_per_op == 0 || cfg.max_ops == 0 || cfg.max_events == 0 ||
+      cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_ENGINE)
+    return SS_E_INVAL;
+  if (cfg.copy_workgroups == 0) cfg.copy_workgroups = default_workgroups();
+  if (cfg.copy_workgroups > 4096) return SS_E_INVAL;
+
+  ss_ctx *ctx = new (std::nothrow) ss_ctx();
+  if (!ctx) return SS_E_NOMEM;
+  ctx->cfg = cfg;
+  std::memset(&ctx->stats, 0, sizeof(ctx->stats));
+  int rc = SS_OK;
+  auto fail = [&](int code, hipError_t e) {
+    ctx->stats.last_hip_error = (int32_t)e;
+    (void)hipGetLastError();
+    rc = code;
+  };
+  hipError_t e;
+  if ((e = hipGetDevice(&ctx->device)) != hipSuccess) fail(SS_E_HIP, e);
+  if (rc == SS_OK && cfg.staging_bytes) {
+    e = hipHostMalloc((void **)&ctx->staging, cfg.staging_bytes, hipHostMallocMapped | hipHostMallocPortable);
+    if (e != hipSuccess) fail(SS_E_NOMEM, e);
+    else if ((e = hipHostGetDevicePointer((void **)&ctx->staging_dev, ctx->staging, 0)) != hipSuccess)
+      fail(SS_E_HIP, e);
+  }
+  if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->ops, (size_t)cfg.max_ops * sizeof(ss_op_t),
+                                        hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
+  if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->events, (size_t)cfg.max_events * sizeof(ss_event_t),
+                                        hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
+  // all streams at the default priority
+  if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+  if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+  if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_aux, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+  for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
+    hipEvent_t ev;
+    if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) fail(SS_E_HIP, e);
+    else ctx->ev_ring.push_back(ev);
+  }
+  if (rc != SS_OK) {
+    ss_destroy(ctx);
+    return rc;
+  }
+  *out = ctx;
+  return SS_OK;
+}
+
+static void free_events(std::vector<hipEvent_t> &v) {
+  for (hipEvent_t e : v)
+    if (e) (void)hipEventDestroy(e);
+  v.clear();
+}
+
+static void sched_release(ss_sched &s) {
+  free_events(s.ev_out_done);
+  free_events(s.ev_in_done);
+  free_events(s.ev_out_start);
+  free_events(s.ev_in_start);
+  if (s.d_out) (void)hipFree(s.d_out);
+  if (s.d_in) (void)hipFree(s.d_in);
+  if (s.d_out_chunk0) (void)hipFree(s.d_out_chunk0);
+  if (s.d_in_chunk0) (void)hipFree(s.d_in_chunk0);
+  s.d_out = s.d_in = nullptr;
+  s.d_out_chunk0 = s.d_in_chunk0 = nullptr;
+  s.d_cap_out = s.d_cap_in = 0;
+  s.loaded = false;
+}
+
+extern "C" int ss_destroy(ss_ctx *ctx) {
+  if (!ctx) return SS_E_INVAL;
+  if (ctx->s_out) (void)hipStreamSynchronize(ctx->s_out);
+  if (ctx->s_in) (void)hipStreamSynchronize(ctx->s_in);
+  if (ctx->s_aux) (void)hipStreamSynchronize(ctx->s_aux);
+  sched_release(ctx->sched);
+  for (hipEvent_t ev : ctx->ev_ring) (void)hipEventDestroy(ev);
+  if (ctx->s_out) (void)hipStreamDestroy(ctx->s_out);
+  if (ctx->s_in) (void)hipStreamDestroy(ctx->s_in);
+  if (ctx->s_aux) (void)hipStreamDestroy(ctx->s_aux);
+  if (ctx->staging) (void)hipHostFree(ctx->staging);
+  if (ctx->ops) (void)hipHostFree(ctx->ops);
+  if (ctx->events) (void)hipHostFree(ctx->events);
+  if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+  if (ctx->h_scratch) (void)hipHostFree(ctx->h_scratch);
+  delete ctx;
+  return SS_OK;
+}
+
+extern "C" int ss_bind(ss_ctx *ctx, void *arena, uint64_t arena_bytes, void *compute_stream) {
+  if (!ctx || (!arena && arena_bytes) || ((uintptr_t)arena & 15u)) return SS_E_INVAL;
+  ctx->arena = (uint8_t *)arena;
+  ctx->arena_bytes = arena_bytes;
+  ctx->compute = (hipStream_t)compute_stream;
+  ctx->bound = true;
+  ctx->sched.loaded = false;     // descriptors were validated against the previous arena
+  return SS_OK;
+}
+
+int ss_scratch_reserve(ss_ctx *ctx, size_t dev_bytes, size_t host_bytes) {
+  if (dev_bytes > ctx->d_scratch_bytes) {
+    if (ctx->d_scratch) SS_HIP(hipFree(ctx->d_scratch));
+    ctx->d_scratch = nullptr;
+    ctx->d_scratch_bytes = 0;
+    size_t want = ss_align_up(dev_bytes + dev_bytes / 4, 1 << 20);
+    hipError_t e = hipMalloc(&ctx->d_scratch, want);
+    if (e != hipSuccess) {
+      ctx->stats.last_hip_error = (int32_t)e;
+      (void)hipGetLastError();
+      return SS_E_NOMEM;
+    }
+    ctx->d_scratch_bytes = want;
+  }
+  if (host_bytes > ctx->h_scratch_bytes) {
+    if (ctx->h_scratch) SS_HIP(hipHostFree(ctx->h_scratch));
+    ctx->h_scratch = nullptr;
+    ctx->h_scratch_bytes = 0;
+    size_t want = ss_align_up(host_bytes + host_bytes / 4, 1 << 20);
+    hipError_t e = hipHostMalloc(&ctx->h_scratch, want, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      ctx->stats.last_hip_error = (int32_t)e;
+      (void)hipGetLastError();
+      return SS_E_NOMEM;
+    }
+    ctx->h_scratch_bytes = want;
+  }
+  return SS_OK;
+}
+
+// ---- schedule ------------------------------------------------------------------
+
+static int check_descs(const ss_ctx *ctx, const ss_desc_t *d, uint32_t n) {
+  for (uint32_t i = 0; i < n; ++i) {
+    if ((d[i].dev_off & 15u) || (d[i].host_off & 15u)) return SS_E_INVAL;
+    if (d[i].dev_off > ctx->arena_bytes || d[i].nbytes > ctx->arena_bytes - d[i].dev_off) return SS_E_INVAL;
+    if (d[i].host_off > ctx->cfg.staging_bytes || d[i].nbytes > ctx->cfg.staging_bytes - d[i].host_off)
+      return SS_E_NOMEM;
+    if (d[i].nbytes > (1ull << 40)) return SS_E_INVAL;
+  }
+  return SS_OK;
+}
+
+static int check_batches(const uint32_t *start, uint32_t nb, uint32_t n) {
+  if (nb == 0) return n == 0 ? SS_OK : SS_E_INVAL;
+  if (!start || start[0] != 0 || start[nb] != n) return SS_E_INVAL;
+  for (uint32_t b = 0; b < nb; ++b)
+    if (start[b + 1] < start[b]) return SS_E_INVAL;
+  return SS_OK;
+}
+
+static int ensure_events(ss_ctx *ctx, std::vector<hipEvent_t> &v, size_t n, unsigned flags) {
+  while (v.size() < n) {
+    hipEvent_t e;
+    SS_HIP(hipEventCreateWithFlags(&e, flags));
+    v.push_back(e);
+  }
+  return SS_OK;
+}
+
+// chunk-prefix per descriptor, restarting at every batch; entry [start[b+1]] of a
+// batch's run is read as its sentinel, so each batch gets count + 1 entries.
+static void build_chunks(const std::vector<ss_desc_t> &d, const std::vector<uint32_t> &start,
+                         std::vector<uint32_t> &chunk0) {
+  size_t nb = start.size() ? start.size() - 1 : 0;
+  chunk0.assign(d.size() + nb, 0);
+  for (size_t b = 0; b < nb; ++b) {
+    uint32_t run = 0;
+    size_t base = start[b] + b;
+    for (uint32_t i = start[b]; i < start[b + 1]; ++i) {
+      chunk0[base + (i - start[b])] = run;
+      run += (uint32_t)((d[i].nbytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
+    }
+    chunk0[base + (start[b + 1] - start[b])] = run;
+  }
+}
+
+extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_t n_out,
+                                const uint32_t *out_start, uint32_t n_out_batches,
+                                const ss_desc_t *descs_in, uint32_t n_in, const uint32_t *in_start,
+                                uint32_t n_in_batches, const uint32_t *in_dep) {
+  if (!ctx || (n_out && !descs_out) || (n_in && !descs_in)) return SS_E_INVAL;
+  if (!ctx->bound) return SS_E_STATE;
+  int rc;
+  if ((rc = check_batches(out_start, n_out_batches, n_out)) != SS_OK) return rc;
+  if ((rc = check_batches(in_start, n_in_batches, n_in)) != SS_OK) return rc;
+  if ((rc = check_descs(ctx, descs_out, n_out)) != SS_OK) return rc;
+  if ((rc = check_descs(ctx, descs_in, n_in)) != SS_OK) return rc;
+  for (uint32_t b = 0; in_dep && b < n_in_batches; ++b)
+    if (n_out_batches == 0 || in_dep[b] >= n_out_batches) return SS_E_INVAL;
+  // staging slots of the swap-out side must be pairwise disjoint
+  {
+    std::vector<std::pair<uint64_t, uint64_t>> iv;
+    iv.reserve(n_out);
+    for (uint32_t i = 0; i < n_out; ++i)
+      if (descs_out[i].nbytes) iv.emplace_back(descs_out[i].host_off, descs_out[i].host_off + descs_out[i].nbytes);
+    std::sort(iv.begin(), iv.end());
+    for (size_t i = 1; i < iv.size(); ++i)
+      if (iv[i].first < iv[i - 1].second) return SS_E_INVAL;
+  }
+  // nothing of the previous schedule may still be in flight
+  SS_HIP(hipStreamSynchronize(ctx->s_out));
+  SS_HIP(hipStreamSynchronize(ctx->s_in));
+
+  ss_sched &s = ctx->sched;
+  s.loaded = false;
+  s.out.assign(descs_out, descs_out + n_out);
+  s.in.assign(descs_in, descs_in + n_in);
+  s.out_start.assign(out_start ? out_start : nullptr, out_start ? out_start + n_out_batches + 1 : nullptr);
+  s.in_start.assign(in_start ? in_start : nullptr, in_start ? in_start + n_in_batches + 1 : nullptr);
+  if (s.out_start.empty()) s.out_start.push_back(0);
+  if (s.in_start.empty()) s.in_start.push_back(0);
+  s.in_dep.resize(n_in_batches);
+  for (uint32_t b = 0; b < n_in_batches; ++b) s.in_dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
+  build_chunks(s.out, s.out_start, s.out_chunk0);
+  build_chunks(s.in, s.in_start, s.in_chunk0);
+  s.out_of_tensor.clear();
+  s.in_of_tensor.clear();
+  s.out_batch_of.assign(n_out, 0);
+  s.in_batch_of.assign(n_in, 0);
+  for (uint32_t b = 0; b < n_out_batches; ++b)
+    for (uint32_t i = s.out_start[b]; i < s.out_start[b + 1]; ++i) {
+      s.out_batch_of[i] = b;
+      s.out_of_tensor[s.out[i].tensor_id] = i;
+    }
+  for (uint32_t b = 0; b < n_in_batches; ++b)
+    for (uint32_t i = s.in_start[b]; i < s.in_start[b + 1]; ++i) {
+      s.in_batch_of[i] = b;
+      s.in_of_tensor[s.in[i].tensor_id] = i;
+    }
+  s.out_waited.assign(n_out_batches, 0);
+  s.out_issued.assign(n_out_batches, 0);
+  s.in_waited.assign(n_in_batches, 0);
+  s.in_issued.assign(n_in_batches, 0);
+
+  const unsigned evflags = (ctx->cfg.flags & SS_CFG_TIMING) ? hipEventDefault : hipEventDisableTiming;
+  if ((rc = ensure_events(ctx, s.ev_out_done, n_out_batches, evflags)) != SS_OK) return rc;
+  if ((rc = ensure_events(ctx, s.ev_in_done, n_in_batches, evflags)) != SS_OK) return rc;
+  if (ctx->cfg.flags & SS_CFG_TIMING) {
+    if ((rc = ensure_events(ctx, s.ev_out_start, n_out_batches, evflags)) != SS_OK) return rc;
+    if ((rc = ensure_events(ctx, s.ev_in_start, n_in_batches, evflags)) != SS_OK) return rc;
+  }
+  // device copies of descriptors and chunk tables
+  auto upload = [&](const std::vector<ss_desc_t> &d, const std::vector<uint32_t> &c, ss_desc_t *&dd,
+                    uint32_t *&dc, size_t &cap) -> int {
+    if (d.empty()) return SS_OK;
+    if (d.size() > cap) {
+      if (dd) SS_HIP(hipFree(dd));
+      if (dc) SS_HIP(hipFree(dc));
+      dd = nullptr; dc = nullptr; cap = 0;
+      size_t want = d.size() + d.size() / 2 + 64;
+      hipError_t e = hipMalloc((void **)&dd, want * sizeof(ss_desc_t));
+      if (e == hipSuccess) e = hipMalloc((void **)&dc, (2 * want + 64) * sizeof(uint32_t));
+      if (e != hipSuccess) {
+        ctx->stats.last_hip_error = (int32_t)e;
+        (void)hipGetLastError();
+        return SS_E_NOMEM;
+      }
+      cap = want;
+    }
+    if (c.size() > 2 * cap + 64) return SS_E_CAPACITY;
+    SS_HIP(hipMemcpy(dd, d.data(), d.size() * sizeof(ss_desc_t), hipMemcpyHostToDevice));
+    SS_HIP(hipMemcpy(dc, c.data(), c.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+    return SS_OK;
+  };
+  if ((rc = upload(s.out, s.out_chunk0, s.d_out, s.d_out_chunk0, s.d_cap_out)) != SS_OK) return rc;
+  if ((rc = upload(s.in, s.in_chunk0, s.d_in, s.d_in_chunk0, s.d_cap_in)) != SS_OK) return rc;
+  s.loaded = true;
+  return SS_OK;
+}
+
+extern "C" int ss_schedule_view(ss_ctx *ctx, const uint32_t **out_start, uint32_t *n_out_batches,
+                                const uint32_t **in_start, uint32_t *n_in_batches, const uint32_t **in_dep) {
+  if (!ctx) return SS_E_INVAL;
+  if (!ctx->sched.loaded) return SS_E_STATE;
+  const ss_sched &s = ctx->sched;
+  if (out_start) *out_start = s.out_start.data();
+  if (n_out_batches) *n_out_batches = (uint32_t)s.out_start.size() - 1;
+  if (in_start) *in_start = s.in_start.data();
+  if (n_in_batches) *n_in_batches = (uint32_t)s.in_start.size() - 1;
+  if (in_dep) *in_dep = s.in_dep.data();
+  return SS_OK;
+}
+
+// ---- swap-out / swap-in / release / wait ---------------------------------------
+
+static bool use_engine(const ss_ctx *ctx, const std::vector<ss_desc_t> &d, uint32_t lo, uint32_t hi) {
+  if (ctx->cfg.copy_path == SS_PATH_ENGINE) return true;
+  if (ctx->cfg.copy_path == SS_PATH_KERNEL) return false;
+  if (hi <= lo) return false;
+  uint64_t total = 0;
+  for (uint32_t i = lo; i < hi; ++i) total += d[i].nbytes;
+  return total / (hi - lo) >= ctx->cfg.engine_min_bytes;
+}
+
+// Marker events are taken round-robin from a ring much longer than the number
+// of markers in flight, so one is never re-recorded while a wait on it is pending.
+static hipEvent_t next_marker(ss_ctx *ctx) {
+  hipEvent_t ev = ctx->ev_ring[ctx->ev_next];
+  ctx->ev_next = (ctx->ev_next + 1) % ctx->ev_ring.size();
+  return ev;
+}
+
+extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
+  if (!ctx) return SS_E_INVAL;
+  ss_sched &s = ctx->sched;
+  if (!s.loaded || !ctx->bound) return SS_E_STATE;
+  if (batch + 1 >= s.out_start.size()) return SS_E_INVAL;
+  if (s.out_issued[batch]) return SS_E_STATE;
+  const uint32_t lo = s.out_start[batch], hi = s.out_start[batch + 1];
+  // the tensors' last forward use is already enqueued on the compute stream: order after it
+  hipEvent_t mark = next_marker(ctx);
+  SS_HIP(hipEventRecord(mark, ctx->compute));
+  SS_HIP(hipStreamWaitEvent(ctx->s_out, mark, 0));
+  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_out_start[batch], ctx->s_out));
+  uint64_t bytes = 0;
+  for (uint32_t i = lo; i < hi; ++i) bytes += s.out[i].nbytes;
+  if (use_engine(ctx, s.out, lo, hi)) {
+    for (uint32_t i = lo; i < hi; ++i)
+      if (s.out[i].nbytes)
+        SS_HIP(hipMemcpyAsync(ctx->staging + s.out[i].host_off, ctx->arena + s.out[i].dev_off, s.out[i].nbytes,
+                              hipMemcpyDeviceToHost, ctx->s_out));
+    ctx->stats.engine_batches++;
+  } else {
+    const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
+    const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
+    ss_launch_copy(ctx->s_out, ctx->cfg.copy_workgroups, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
+                   hi - lo, n_chunks);
+    SS_HIP(hipGetLastError());
+    ctx->stats.kernel_batches++;
+  }
+  SS_HIP(hipEventRecord(s.ev_out_done[batch], ctx->s_out));
+  s.out_issued[batch] = 1;
+  ctx->stats.bytes_out += bytes;
+  return SS_OK;
+}
+
+extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
+  if (!ctx) return SS_E_INVAL;
+  ss_sched &s = ctx->sched;
+  if (!s.loaded || !ctx->bound) return SS_E_STATE;
+  if (batch + 1 >= s.in_start.size()) return SS_E_INVAL;
+  if (s.in_issued[batch]) return SS_E_STATE;
+  const uint32_t lo = s.in_start[batch], hi = s.in_start[batch + 1];
+  if (hi > lo && !s.out_issued[s.in_dep[batch]]) return SS_E_STATE;   // its data never left
+  // destination blocks are free once the compute stream reaches this point
+  hipEvent_t mark = next_marker(ctx);
+  SS_HIP(hipEventRecord(mark, ctx->compute));
+  SS_HIP(hipStreamWaitEvent(ctx->s_in, mark, 0));
+  // staging slots must be completely written
+  if (hi > lo) SS_HIP(hipStreamWaitEvent(ctx->s_in, s.ev_out_done[s.in_dep[batch]], 0));
+  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_in_start[batch], ctx->s_in));
+  uint64_t bytes = 0;
+  for (uint32_t i = lo; i < hi; ++i) bytes += s.in[i].nbytes;
+  if (use_engine(ctx, s.in, lo, hi)) {
+    for (uint32_t i = lo; i < hi; ++i)
+      if (s.in[i].nbytes)
+        SS_HIP(hipMemcpyAsync(ctx->arena + s.in[i].dev_off, ctx->staging + s.in[i].host_off, s.in[i].nbytes,
+                              hipMemcpyHostToDevice, ctx->s_in));
+    ctx->stats.engine_batches++;
+  } else {
+    const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
+    const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
+    ss_launch_copy(ctx->s_in, ctx->cfg.copy_workgroups, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
+                   hi - lo, n_chunks);
+    SS_HIP(hipGetLastError());
+    ctx->stats.kernel_batches++;
+  }
+  SS_HIP(hipEventRecord(s.ev_in_done[batch], ctx->s_in));
+  s.in_issued[batch] = 1;
+  ctx->stats.bytes_in += bytes;
+  return SS_OK;
+}
+
+extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
+  if (!ctx) return SS_E_INVAL;
+  ss_sched &s = ctx->sched;
+  switch (what) {
+    case SS_SYNC_FREE: {
+      if (!s.loaded) return SS_E_STATE;
+      auto it = s.out_of_tensor.find(id);
+      if (it == s.out_of_tensor.end()) return SS_E_INVAL;
+      const uint32_t b = s.out_batch_of[it->second];
+      if (!s.out_issued[b]) return SS_E_STATE;   // releasing a block whose swap-out was never issued
+      if (!s.out_waited[b]) {
+        // device-side: later compute-stream work starts only after the batch has left HBM
+        SS_HIP(hipStreamWaitEvent(ctx->compute, s.ev_out_done[b], 0));
+        s.out_waited[b] = 1;
+        ctx->stats.free_waits++;
+      }
+      if (ctx->cfg.flags & SS_CFG_POISON_FREE) {
+        const ss_desc_t &d = s.out[it->second];
+        ss_launch_fill(ctx->compute, ctx->arena + d.dev_off, d.nbytes, 0xDB);
+        SS_HIP(hipGetLastError());
+      }
+      return SS_OK;
+    }
+    case SS_SYNC_WAIT_IN: {
+      if (!s.loaded) return SS_E_STATE;
+      auto it = s.in_of_tensor.find(id);
+      if (it == s.in_of_tensor.end()) return SS_E_INVAL;
+      const uint32_t b = s.in_batch_of[it->second];
+      if (!s.in_issued[b]) return SS_E_STATE;    // waiting for a swap-in that was never issued
+      if (!s.in_waited[b]) {
+        SS_HIP(hipStreamWaitEvent(ctx->compute, s.ev_in_done[b], 0));
+        s.in_waited[b] = 1;
+        ctx->stats.in_waits++;
+      }
+      return SS_OK;
+    }
+    case SS_SYNC_DRAIN: {
+      SS_HIP(hipStreamSynchronize(ctx->s_out));
+      SS_HIP(hipStreamSynchronize(ctx->s_in));
+      std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
+      std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
+      std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
+      std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
+      return SS_OK;
+    }
+    default: return SS_E_INVAL;
+  }
+}
+
+extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms) {
+  if (!ctx || dir > 1) return SS_E_INVAL;
+  if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
+  ss_sched &s = ctx->sched;
+  auto &st = dir ? s.ev_in_start : s.ev_out_start;
+  auto &dn = dir ? s.ev_in_done : s.ev_out_done;
+  const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
+  if (ms) {
+    if (batch >= nb) return SS_E_INVAL;
+    SS_HIP(hipEventElapsedTime(ms, st[batch], dn[batch]));
+  }
+  if (span_ms) {
+    if (nb == 0) { *span_ms = 0.f; return SS_OK; }
+    SS_HIP(hipEventElapsedTime(span_ms, st[0], dn[nb - 1]));
+  }
+  return SS_OK;
+}
+
+// ---- support -------------------------------------------------------------------
+
+extern "C" int ss_host_peek(ss_ctx *ctx, uint64_t host_off, uint64_t nbytes, const void **ptr) {
+  if (!ctx || !ptr) return SS_E_INVAL;
+  if (host_off > ctx->cfg.staging_bytes || nbytes > ctx->cfg.staging_bytes - host_off) return SS_E_INVAL;
+  *ptr = ctx->staging + host_off;
+  return SS_OK;
+}
+
+extern "C" int ss_staging_fill(ss_ctx *ctx, int byte) {
+  if (!ctx) return SS_E_INVAL;
+  SS_HIP(hipStreamSynchronize(ctx->s_out));
+  SS_HIP(hipStreamSynchronize(ctx->s_in));
+  if (ctx->staging) std::memset(ctx->staging, byte, ctx->cfg.staging_bytes);
+  return SS_OK;
+}
+
+extern "C" int ss_get_stats(ss_ctx *ctx, ss_stats_t *out) {
+  if (!ctx || !out) return SS_E_INVAL;
+  *out = ctx->stats;
+  return SS_OK;
+}
+
+// Host-link bandwidth as the machine delivers it now.
+extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *out) {
+  if (!ctx || !out || bytes < 4096 || reps == 0 || reps > 1000) return SS_E_INVAL;
+  bytes &= ~(uint64_t)255;
+  std::memset(out, 0, sizeof(*out));
+  uint8_t *h0 = nullptr, *h1 = nullptr, *d0 = nullptr, *d1 = nullptr, *h0d = nullptr, *h1d = nullptr;
+  ss_desc_t *dd = nullptr;
+  uint32_t *dc = nullptr;
+  hipEvent_t a0 = nullptr, a1 = nullptr, b0 = nullptr, b1 = nullptr;
+  int rc = SS_OK;
+  auto ck = [&](hipError_t e) {
+    if (e != hipSuccess && rc == SS_OK) {
+      ctx->stats.last_hip_error = (int32_t)e;
+      (void)hipGetLastError();
+      rc = SS_E_HIP;
+    }
+    return e == hipSuccess;
+  };
+  ck(hipHostMalloc((void **)&h0, bytes, hipHostMallocMapped));
+  ck(hipHostMalloc((void **)&h1, bytes, hipHostMallocMapped));
+  ck(hipMalloc((void **)&d0, bytes));
+  ck(hipMalloc((void **)&d1, bytes));
+  ck(hipMalloc((void **)&dd, 2 * sizeof(ss_desc_t)));
+  ck(hipMalloc((void **)&dc, 4 * sizeof(uint32_t)));
+  ck(hipEventCreate(&a0)); ck(hipEventCreate(&a1)); ck(hipEventCreate(&b0)); ck(hipEventCreate(&b1));
+  if (rc == SS_OK) {
+    ck(hipHostGetDevicePointer((void **)&h0d, h0, 0));
+    ck(hipHostGetDevicePointer((void **)&h1d, h1, 0));
+    std::memset(h0, 1, bytes);
+    std::memset(h1, 2, bytes);
+    ck(hipMemset(d0, 3, bytes));
+    ck(hipMemset(d1, 4, bytes));
+    ss_desc_t hd[2] = {{0, 0, bytes, 0, 0}, {0, 0, bytes, 1, 0}};
+    uint32_t hc[2] = {0, (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES)};
+    ck(hipMemcpy(dd, hd, sizeof(hd), hipMemcpyHostToDevice));
+    ck(hipMemcpy(dc, hc, sizeof(hc), hipMemcpyHostToDevice));
+    ck(hipDeviceSynchronize());
+  }
+  auto median = [](std::vector<float> &v) {
+    std::sort(v.begin(), v.end());
+    return v[v.size() / 2];
+  };
+  auto gbps = [&](float ms) { return ms > 0 ? (double)bytes / (ms * 1e-3) / 1e9 : 0.0; };
+  const uint32_t wg = ctx->cfg.copy_workgroups;
+  const uint32_t nchunks = (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
+  // mode 0: D2H engine, 1: H2D engine, 2: both engine, 3: D2H kernel, 4: H2D kernel
+  for (int mode = 0; mode < 5 && rc == SS_OK; ++mode) {
+    std::vector<float> ta, tb;
+    for (uint32_t r = 0; r < reps + 2 && rc == SS_OK; ++r) {
+      const bool d2h = (mode == 0 || mode == 2 || mode == 3), h2d = (mode == 1 || mode == 2 || mode == 4);
+      if (d2h) {
+        ck(hipEventRecord(a0, ctx->s_out));
+        if (mode == 3) {
+          ss_launch_copy(ctx->s_out, wg, true, d0, h0d, dd, dc, 1, nchunks);
+          ck(hipGetLastError());
+        } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
+        ck(hipEventRecord(a1, ctx->s_out));
+      }
+      if (h2d) {
+        ck(hipEventRecord(b0, ctx->s_in));
+        if (mode == 4) {
+          ss_launch_copy(ctx->s_in, wg, false, d1, h1d, dd, dc, 1, nchunks);
+          ck(hipGetLastError());
+        } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
+        ck(hipEventRecord(b1, ctx->s_in));
+      }
+      ck(hipStreamSynchronize(ctx->s_out));
+      ck(hipStreamSynchronize(ctx->s_in));
+      float ms;
+      if (d2h && ck(hipEventElapsedTime(&ms, a0, a1)) && r >= 2) ta.push_back(ms);
+      if (h2d && ck(hipEventElapsedTime(&ms, b0, b1)) && r >= 2) tb.push_back(ms);
+    }
+    if (rc != SS_OK) break;
+    switch (mode) {
+      case 0: out->d2h_gbps = gbps(median(ta)); break;
+      case 1: out->h2d_gbps = gbps(median(tb)); break;
+      case 2: out->bidir_d2h_gbps = gbps(median(ta)); out->bidir_h2d_gbps = gbps(median(tb)); break;
+      case 3: out->kernel_d2h_gbps = gbps(median(ta)); break;
+      case 4: out->kernel_h2d_gbps = gbps(median(tb)); break;
+    }
+  }
+  if (a0) (void)hipEventDestroy(a0);
+  if (a1) (void)hipEventDestroy(a1);
+  if (b0) (void)hipEventDestroy(b0);
+  if (b1) (void)hipEventDestroy(b1);
+  if (dd) (void)hipFree(dd);
+  if (dc) (void)hipFree(dc);
+  if (d0) (void)hipFree(d0);
+  if (d1) (void)hipFree(d1);
+  if (h0) (void)hipHostFree(h0);
+  if (h1) (void)hipHostFree(h1);
+  return rc;
+}

@@ -1,0 +1,45 @@
+"""Walk one iteration's action schedule around the caller's operators.
+
+Sec. 5 (first paragraph) of the SmartSwap paper: the executor issues the
+policy's swap operations at their designated positions of the iteration.  This
+module only sequences calls into libss (swap-out, release, swap-in, wait) around
+a caller-supplied `run_op(i)` that enqueues operator i on the compute stream.
+It holds no arithmetic of the method.
+"""
+import numpy as np
+
+from . import binding as B
+
+
+def batch_lists(actions):
+    """Per operator index the (kind, tensor_id, batch) triples, split into what runs before
+    and after the operator itself.  actions is the ACTION_DT array from ss_apply_policy."""
+    before, after = {}, {}
+    for op, kind, tid, batch in actions.tolist():
+        (before if kind in (B.SS_ACT_IN, B.SS_ACT_WAIT_IN) else after).setdefault(op, []).append((kind, tid, batch))
+    return before, after
+
+
+def run_iteration(ctx, n_ops, actions, run_op, before_after=None):
+    """Execute one iteration: for each operator, issue IN / WAIT_IN actions, run the
+    operator, then issue OUT / FREE actions; drain the swap streams at the end."""
+    before, after = before_after if before_after is not None else batch_lists(actions)
+    issued_in, issued_out = set(), set()
+    for i in range(n_ops):
+        for kind, tid, batch in before.get(i, ()):
+            if kind == B.SS_ACT_IN:
+                if batch not in issued_in:
+                    B.ss_swap_in(ctx, batch)
+                    issued_in.add(batch)
+            else:
+                B.ss_sync(ctx, B.SS_SYNC_WAIT_IN, tid)
+        if run_op is not None:
+            run_op(i)
+        for kind, tid, batch in after.get(i, ()):
+            if kind == B.SS_ACT_OUT:
+                if batch not in issued_out:
+                    B.ss_swap_out(ctx, batch)
+                    issued_out.add(batch)
+            else:
+                B.ss_sync(ctx, B.SS_SYNC_FREE, tid)
+    B.ss_sync(ctx, B.SS_SYNC_DRAIN, 0)

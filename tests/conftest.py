@@ -6,3 +6,11 @@ sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_sessionstart(session):
+    """Tests load the library that is built; only if none is there it is built first."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    if not os.path.exists(os.path.join(root, "paper_2509_11076_amd", "libss.so")):
+        from paper_2509_11076_amd.build import build_library
+        build_library(verbose=False)

@@ -1,0 +1,346 @@
+"""GPU parity: trace record, timeline scan, sequence match, policy application and greedy
+policy of the HIP library against the CPU oracle, element by element (exact equality:
+everything is integers).  All calls go through the C ABI."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from workloads.arena import place_tensors
+from workloads.rng import SplitMix64
+from helpers import record_oracle, record_lib, ops_tuples, assert_applied_equal
+from test_oracle_trace_timeline import tiny_trace, policy_events_for
+
+pytestmark = pytest.mark.gpu
+INSTANT = 1 << 40
+PERT = dict(p_drop=0.1, p_insert=0.1, moe_max=8, seq_jitter=0.15)
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2509_11076_amd.binding as B
+    return B
+
+
+@pytest.fixture()
+def ctx(P):
+    cfg = P.ss_config_default()
+    cfg.staging_bytes = 1 << 20
+    cfg.max_ops = 1 << 16
+    cfg.max_events = 1 << 18
+    c = P.ss_create(cfg)
+    yield c
+    P.ss_destroy(c)
+
+
+def make_ctx(P, **kw):
+    cfg = P.ss_config_default()
+    for k, v in kw.items():
+        setattr(cfg, k, v)
+    return P.ss_create(cfg)
+
+
+# ------------------------------------------------------------------ trace record
+@pytest.mark.parametrize("cfgno", [1, 2])
+def test_trace_record_is_byte_identical(P, ctx, cfgno):
+    tr = W.build_trace(W.config_shape(cfgno))
+    o_ops, o_ev = record_oracle(oracle.TraceRecorder(), tr)
+    l_ops, l_ev, bal = record_lib(P, ctx, tr)
+    assert np.array_equal(l_ops.view(np.uint8), o_ops.view(np.uint8))
+    assert np.array_equal(l_ev.view(np.uint8), o_ev.view(np.uint8))
+    assert bal == 0
+
+
+def test_trace_tokens_persist_across_iterations_and_errors(P, ctx):
+    rec = oracle.TraceRecorder()
+    shape = W.ModelShape("naive", 64, 3, 4, 64, 1, 4, experts0=4)
+    for it in range(3):
+        tr = W.build_trace(shape, iteration=it, perturb=PERT if it else None)
+        o_ops, o_ev = record_oracle(rec, tr)
+        l_ops, l_ev, bal = record_lib(P, ctx, tr)
+        assert np.array_equal(l_ops.view(np.uint8), o_ops.view(np.uint8))
+        assert np.array_equal(l_ev.view(np.uint8), o_ev.view(np.uint8)) and bal == 0
+    P.ss_trace_begin(ctx)
+    op = P.ss_intern_op(ctx, "x", "y", 1, 1, 0)
+    bad = np.zeros(1, P.EVENT_DT); bad["op_idx"] = 5; bad["delta"] = 8
+    with pytest.raises(P.SsError) as e:
+        P.ss_trace_record(ctx, op, bad)
+    assert e.value.code == P.SS_E_INVAL
+    zero = op.copy(); zero["op_token"] = 0
+    with pytest.raises(P.SsError):
+        P.ss_trace_record(ctx, zero)
+    small = make_ctx(P, staging_bytes=4096, max_ops=2, max_events=4)
+    try:
+        P.ss_trace_record(small, op); P.ss_trace_record(small, op)
+        with pytest.raises(P.SsError) as e:
+            P.ss_trace_record(small, op)
+        assert e.value.code == P.SS_E_CAPACITY
+    finally:
+        P.ss_destroy(small)
+
+
+# ------------------------------------------------------------------ timeline scan
+def assert_scan_equal(lib, ora, timeline=True):
+    assert lib["peak"] == ora["peak"] and lib["argpeak_op"] == ora["argpeak_op"]
+    assert lib["n_over"] == ora["n_over"] and lib["final"] == ora["final"]
+    assert np.array_equal(lib["per_op"], ora["per_op"]) and np.array_equal(lib["mre"], ora["mre"])
+    if timeline:
+        assert np.array_equal(lib["timeline"], ora["timeline"])
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_scan_tiny_traces_with_policy_events(P, ctx, seed):
+    tab, ev = tiny_trace(seed)
+    away = {i: (int(tab["last_fwd_use"][i]) + 1, int(tab["first_bwd_use"][i]))
+            for i in range(len(tab)) if i % 2 == seed % 2 and tab["last_fwd_use"][i] + 1 < tab["first_bwd_use"][i]}
+    pe = policy_events_for(tab, away)
+    pe_arr = np.array(pe, dtype=W.EVENT_DT) if pe else None
+    ora = oracle.timeline_scan(ev, pe, 12, 1000, 3000)
+    lib = P.ss_timeline_scan(ctx, ev, pe_arr, 12, 1000, 3000, want_timeline=True)
+    assert_scan_equal(lib, ora)
+
+
+@pytest.mark.parametrize("cfgno,budget", [(1, 2 << 20), (2, 4 << 30), (3, 48 * 10**9)])
+def test_scan_transformer_traces(P, ctx, cfgno, budget):
+    tr = W.build_trace(W.config_shape(cfgno))
+    ora = oracle.timeline_scan(tr.events, None, tr.n_ops, 7 << 30, budget)
+    lib = P.ss_timeline_scan(ctx, tr.events, None, tr.n_ops, 7 << 30, budget, want_timeline=True)
+    assert_scan_equal(lib, ora)
+    assert lib["sorted"] == 1
+
+
+def test_scan_stress_trace_100k_events_spanning_many_chunks(P):
+    tr, pol, _ = W.build_small_tensor_stress()
+    assert len(tr.events) == 100000
+    c = make_ctx(P, staging_bytes=4096)
+    try:
+        budget = 6 * 10**9
+        ora = oracle.timeline_scan(tr.events, None, tr.n_ops, 0, budget)
+        lib = P.ss_timeline_scan(c, tr.events, None, tr.n_ops, 0, budget, want_timeline=True)
+        assert_scan_equal(lib, ora)
+        # with the policy events of the whole swap set (40,000 more events)
+        ap = oracle.apply_policy(pol, pol["ref_op"].astype(np.int64), tr.tensors, 256 << 20)
+        pe = np.array(ap["policy_events"], dtype=W.EVENT_DT)
+        ora = oracle.timeline_scan(tr.events, pe, tr.n_ops, 0, budget)
+        lib = P.ss_timeline_scan(c, tr.events, pe, tr.n_ops, 0, budget, want_timeline=True)
+        assert_scan_equal(lib, ora)
+    finally:
+        P.ss_destroy(c)
+
+
+def test_scan_unsorted_events_edge_cases(P, ctx):
+    tab, ev = tiny_trace(5)
+    perm = SplitMix64(4).permutation(len(ev))
+    shuffled = ev[perm]
+    ora = oracle.timeline_scan(ev, None, 12, 0, 2500)
+    lib = P.ss_timeline_scan(ctx, shuffled, None, 12, 0, 2500)          # any order: per-operator results hold
+    assert_scan_equal(lib, ora, timeline=False)
+    assert lib["sorted"] == 0
+    with pytest.raises(P.SsError) as e:                                 # the timeline needs operator order
+        P.ss_timeline_scan(ctx, shuffled, None, 12, 0, 2500, want_timeline=True)
+    assert e.value.code == P.SS_E_ORDER
+    with pytest.raises(P.SsError) as e:                                 # event beyond the last operator
+        P.ss_timeline_scan(ctx, ev, None, 5, 0, 0)
+    assert e.value.code == P.SS_E_INVAL
+    # no events, no operators
+    lib = P.ss_timeline_scan(ctx, None, None, 0, 7, 0, want_timeline=True)
+    assert lib["peak"] == 7 and lib["argpeak_op"] == -1 and lib["final"] == 7
+    lib = P.ss_timeline_scan(ctx, None, None, 3, 7, 5)
+    assert lib["per_op"].tolist() == [7, 7, 7] and lib["n_over"] == 3 and lib["argpeak_op"] == 0
+    # more operators than one pass of the workgroup covers, large values
+    n_ops = 5000
+    big = np.zeros(2 * n_ops, dtype=W.EVENT_DT)
+    big["op_idx"] = np.repeat(np.arange(n_ops), 2)
+    big["delta"][0::2] = (np.arange(n_ops) % 97 + 1) * (1 << 33)
+    big["delta"][1::2] = -((np.arange(n_ops) % 89 + 1) * (1 << 32))
+    ora = oracle.timeline_scan(big, None, n_ops, -5, 1 << 40)
+    lib = P.ss_timeline_scan(ctx, big, None, n_ops, -5, 1 << 40, want_timeline=True)
+    assert_scan_equal(lib, ora)
+
+
+# ------------------------------------------------------------------ sequence match
+def traces_for_match(it, shape=None, rec=None):
+    shape = shape or W.ModelShape("naive", 64, 6, 4, 64, 1, 4, experts0=4)
+    tr0 = W.build_trace(shape, iteration=0)
+    tr1 = W.build_trace(shape, iteration=it, perturb=PERT)
+    rec = rec or oracle.TraceRecorder()
+    ref, _ = record_oracle(rec, tr0)
+    cur, _ = record_oracle(rec, tr1)
+    tab = tr0.tensors
+    keep = (tab["first_bwd_use"] != W.NONE_OP) & (tab["last_fwd_use"] != W.NONE_OP)
+    anchors = np.zeros(int(keep.sum()), dtype=W.ANCHOR_DT)
+    anchors["ref_op"] = tab["producer_op"][keep]; anchors["out_slot"] = tab["out_slot"][keep]
+    return ref, cur, anchors, tr0, tr1
+
+
+@pytest.mark.parametrize("it", [1, 2, 3])
+def test_match_perturbed_sequences(P, ctx, it):
+    ref, cur, anchors, _, _ = traces_for_match(it)
+    ora = oracle.match_sequence(ops_tuples(ref), ops_tuples(cur), anchors.tolist())
+    lib = P.ss_match_sequence(ctx, ref, cur, anchors)
+    assert (lib["dot"], lib["na"], lib["nb"], lib["similar"]) == (ora["dot"], ora["na"], ora["nb"], ora["similar"])
+    assert np.array_equal(lib["new_idx"], ora["new_idx"]) and np.array_equal(lib["level"], ora["level"])
+    assert lib["n_unmatched"] == ora["n_unmatched"]
+    # histogram reading of the cosine
+    ora_h = oracle.similarity(cur["op_token"], ref["op_token"], histogram=True)
+    lib_h = P.ss_match_sequence(ctx, ref, cur, None, flags=P.SS_MATCH_HISTOGRAM)
+    assert (lib_h["similar"], lib_h["dot"], lib_h["na"], lib_h["nb"]) == ora_h
+
+
+def test_match_full_7b_shape_varying_sequence(P, ctx):
+    ref, cur, anchors, tr0, tr1 = traces_for_match(2, W.config_shape(4))
+    assert len(ref) > 1000 and len(anchors) > 400
+    ora = oracle.match_sequence(ops_tuples(ref), ops_tuples(cur), anchors.tolist())
+    lib = P.ss_match_sequence(ctx, ref, cur, anchors)
+    assert np.array_equal(lib["new_idx"], ora["new_idx"]) and np.array_equal(lib["level"], ora["level"])
+    assert (lib["dot"], lib["na"], lib["nb"], lib["similar"]) == (ora["dot"], ora["na"], ora["nb"], ora["similar"])
+    # identical sequence: every anchor stays, level 0, similar
+    lib = P.ss_match_sequence(ctx, ref, ref, anchors)
+    assert np.array_equal(lib["new_idx"], anchors["ref_op"].astype(np.int32)) and (lib["level"] == 0).all()
+    assert lib["similar"] and lib["dot"] == lib["na"] == lib["nb"]
+
+
+def test_match_threshold_stage_machine_and_edges(P, ctx):
+    def seq(tokens):
+        a = np.zeros(len(tokens), dtype=W.OP_DT)
+        a["op_token"] = tokens; a["n_out"] = 1
+        return a
+    # exact 19/20 cosine is not similar; just above is (comparator in exact integers)
+    r = P.ss_match_sequence(ctx, seq([19, 5, 3, 2, 1]), seq([1, 0, 0, 0, 0]), None)
+    assert (r["dot"], r["na"], r["nb"], r["similar"]) == (19, 1, 400, False)
+    r = P.ss_match_sequence(ctx, seq([20, 5, 3, 2, 1]), seq([1, 0, 0, 0, 0]), None)
+    assert (r["dot"], r["na"], r["nb"], r["similar"]) == (20, 1, 439, True)
+    # length test, relative to the reference, strict
+    assert P.ss_match_sequence(ctx, seq([1] * 100), seq([1] * 104), None)["similar"]
+    assert not P.ss_match_sequence(ctx, seq([1] * 100), seq([1] * 105), None)["similar"]
+    assert P.ss_match_sequence(ctx, seq([]), seq([]), None)["similar"]
+    assert not P.ss_match_sequence(ctx, seq([]), seq([1]), None)["similar"]
+    # sums near the documented limit: 2^17-sized tokens, 2^16 operators
+    big = seq([(1 << 17) + (i % 7) for i in range(1 << 16)])
+    o = oracle.similarity(big["op_token"], big["op_token"])
+    r = P.ss_match_sequence(ctx, big, big, None)
+    assert (r["similar"], r["dot"], r["na"], r["nb"]) == o
+    with pytest.raises(P.SsError):                          # token beyond 2^18
+        P.ss_match_sequence(ctx, seq([1 << 18]), seq([1]), None)
+    # stage machine against the hand-derived table (Algo. 1, m = 2, n = 5)
+    gold = os.path.join(os.path.dirname(__file__), "golden", "stage_machine_m2_n5.txt")
+    names = {"WarmUp": P.SS_STAGE_WARMUP, "GenPolicy": P.SS_STAGE_GENPOLICY, "Stable": P.SS_STAGE_STABLE}
+    cases = {}
+    for line in open(gold):
+        if line.startswith("#") or not line.strip():
+            continue
+        c, it, sim, step, stage = line.split()
+        cases.setdefault(c, []).append((int(sim), int(step), names[stage]))
+    same, other = seq([3, 1, 4, 1, 5]), seq([9, 9, 9, 9, 9, 9, 9, 9, 9])
+    for c in sorted(cases):
+        fresh = make_ctx(P, staging_bytes=4096)
+        try:
+            for sim, step, stage in cases[c]:
+                r = P.ss_match_sequence(fresh, same, same if sim else other, None, flags=P.SS_MATCH_STEP_STAGE)
+                assert r["similar"] == bool(sim) and r["stage"] == stage and r["stable_step"] == step
+        finally:
+            P.ss_destroy(fresh)
+
+
+def test_match_relaxation_and_injectivity_cases(P, ctx):
+    def ops(rows):
+        return np.array(rows, dtype=W.OP_DT)
+    ref = ops([(1, 10, 0x101, 1), (1, 10, 0x101, 1), (2, 20, 0x201, 2)])
+    cur = ops([(1, 11, 0x101, 1), (1, 12, 0x10101, 1), (2, 20, 0x202, 2)])
+    anc = np.array([(0, 0), (1, 0), (2, 1), (2, 5), (7, 0)], dtype=W.ANCHOR_DT)
+    o_idx, o_lvl = oracle.match_anchors(ops_tuples(ref), ops_tuples(cur), anc.tolist())
+    r = P.ss_match_sequence(ctx, ref, cur, anc)
+    assert r["new_idx"].tolist() == o_idx.tolist() == [0, 1, -1, -1, -1]
+    assert r["level"].tolist() == o_lvl.tolist()
+    ref = ops([(1, 1, 1, 1), (1, 2, 1, 1)]); cur = ops([(1, 3, 1, 1)])
+    anc = np.array([(0, 0), (1, 0), (0, 0)], dtype=W.ANCHOR_DT)
+    r = P.ss_match_sequence(ctx, ref, cur, anc)
+    assert r["new_idx"].tolist() == [0, -1, -1] and r["n_unmatched"] == 2
+    # sequences longer than one wavefront strip, anchor at the very end
+    n = 300
+    ref = ops([(1 + i % 3, 7, 0x101, 1) for i in range(n)])
+    cur = ops([(9, 9, 0x101, 1)] * 70 + [(1 + i % 3, 7, 0x101, 1) for i in range(n)])
+    anc = np.array([(n - 1, 0), (0, 0), (64, 0), (63, 0)], dtype=W.ANCHOR_DT)
+    o_idx, o_lvl = oracle.match_anchors(ops_tuples(ref), ops_tuples(cur), anc.tolist())
+    r = P.ss_match_sequence(ctx, ref, cur, anc)
+    assert r["new_idx"].tolist() == o_idx.tolist() == [n - 1 + 70, 70, 134, 133]
+
+
+# ------------------------------------------------------------------ apply policy / greedy
+@pytest.mark.parametrize("cfgno,bpo,guard", [(1, 64 * 1024, 256), (1, INSTANT, 0), (1, 16, 0),
+                                             (2, 8 << 20, 0), (2, 64 << 20, 512)])
+def test_apply_policy_prescribed_sets(P, cfgno, bpo, guard):
+    import torch
+    tr = W.build_trace(W.config_shape(cfgno))
+    pol = W.config_swap_set(tr, cfgno)
+    arena_bytes = place_tensors(tr.tensors, guard=guard)
+    idx = pol["ref_op"].astype(np.int64)
+    idx[3] = -1
+    ora = oracle.apply_policy(pol, idx, tr.tensors, bpo, guard=guard)
+    c = make_ctx(P, staging_bytes=max(4096, ora["staging_bytes"]), link_bytes_per_op=bpo, guard_bytes=guard)
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+    try:
+        P.ss_bind(c, arena.data_ptr(), arena_bytes, 0)
+        lib = P.ss_apply_policy(c, pol, idx, tr.tensors)
+        assert_applied_equal(lib, P, c, ora)
+        if ora["staging_bytes"] > 4096:       # too little staging: reported, outputs still complete
+            small = make_ctx(P, staging_bytes=4096, link_bytes_per_op=bpo, guard_bytes=guard)
+            try:
+                lib = P.ss_apply_policy(small, pol, idx, tr.tensors, allow_nomem=True)
+                assert lib["rc"] == P.SS_E_NOMEM and lib["staging_bytes"] == ora["staging_bytes"]
+            finally:
+                P.ss_destroy(small)
+    finally:
+        P.ss_destroy(c)
+        del arena
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_greedy_policy_tiny(P, seed):
+    tab, ev = tiny_trace(seed, n_ops=14, T=8)
+    no = oracle.timeline_scan(ev, None, 14, 0, 0)
+    c = make_ctx(P, staging_bytes=4096, link_bytes_per_op=INSTANT)
+    try:
+        for frac in (0.9, 0.75, 0.6):
+            budget = int(no["peak"] * frac)
+            try:
+                rows, ap = oracle.greedy_policy(tab, ev, 14, 0, budget, INSTANT)
+            except oracle.Infeasible:
+                with pytest.raises(P.SsError) as e:
+                    P.ss_greedy_policy(c, tab, ev, 14, 0, budget)
+                assert e.value.code == P.SS_E_INFEASIBLE
+                continue
+            pol, peak = P.ss_greedy_policy(c, tab, ev, 14, 0, budget)
+            assert [tuple(int(x) for x in r) for r in pol.tolist()] == rows
+            assert peak == oracle.timeline_scan(ev, ap["policy_events"], 14, 0, budget)["peak"] <= budget
+    finally:
+        P.ss_destroy(c)
+
+
+def test_greedy_policy_7b_shape_and_apply(P):
+    tr = W.build_trace(W.config_shape(3))
+    budget, bpo = 48 * 10**9, 256 << 20
+    rows, ap0 = oracle.greedy_policy(tr.tensors, tr.events, tr.n_ops, 0, budget, bpo, min_bytes=1 << 20)
+    c = make_ctx(P, staging_bytes=4096, link_bytes_per_op=bpo)
+    try:
+        pol, peak = P.ss_greedy_policy(c, tr.tensors, tr.events, tr.n_ops, 0, budget, min_bytes=1 << 20)
+        assert [tuple(int(x) for x in r) for r in pol.tolist()] == rows
+        assert peak <= budget
+        # arena placement under the policy, then the full schedule
+        swapped = {r[2]: (r[5], r[6]) for r in ap0["resolved"]}
+        arena_bytes = place_tensors(tr.tensors, swapped=swapped)
+        assert arena_bytes <= budget * 1.1
+        ora = oracle.apply_policy(pol, pol["ref_op"].astype(np.int64), tr.tensors, bpo)
+        # 50 GB of staging is not allocated here: the schedule is returned, not loaded
+        lib = P.ss_apply_policy(c, pol, pol["ref_op"].astype(np.int32), tr.tensors, allow_nomem=True)
+        assert lib["rc"] == P.SS_E_NOMEM
+        from helpers import applied_as_arrays
+        o = applied_as_arrays(ora)
+        for key in ("resolved", "actions", "descs_out", "descs_in", "policy_events"):
+            assert np.array_equal(lib[key].view(np.uint8), o[key].view(np.uint8)), key
+        assert lib["staging_bytes"] == ora["staging_bytes"] > 40 * 10**9
+        assert oracle.schedule_check(ora, tr.tensors, tr.op_inputs, tr.op_outputs) == []
+    finally:
+        P.ss_destroy(c)
