@@ -161,6 +161,7 @@ typedef struct {
   double d2h_gbps, h2d_gbps;            /* one direction at a time                          */
   double bidir_d2h_gbps, bidir_h2d_gbps;/* both directions at once, per direction           */
   double kernel_d2h_gbps, kernel_h2d_gbps; /* same buffers through the copy kernels         */
+  double kernel_bidir_d2h_gbps, kernel_bidir_h2d_gbps; /* copy kernels, both directions at once */
 } ss_bw_t;
 
 /* ---- life cycle -------------------------------------------------------------- */
@@ -323,6 +324,9 @@ int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *out /* host
 
 int ss_get_stats(ss_ctx *ctx, ss_stats_t *out /* host, out */);
 const char *ss_strerror(int code);
+/* The last HIP failure seen by the calling thread (also when no context survived it):
+ * returns the hipError_t, its name, and the library source position that saw it. */
+int ss_last_hip_error(const char **name, const char **file, int *line);
 
 #ifdef __cplusplus
 }

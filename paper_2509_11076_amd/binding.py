@@ -16,6 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libss.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError("libss.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
                       "(or python paper_2509_11076_amd/build.py) first; there is no CPU fallback")
+# PyTorch ships its own HIP runtime.  libss must bind to that same copy (one runtime per
+# process: streams and device pointers are shared with torch), so torch is loaded first.
+import torch  # noqa: E402,F401
 _lib = C.CDLL(LIB_PATH)
 
 # ---- record layouts (mirror include/ss.h) ------------------------------------
@@ -79,13 +82,17 @@ class ss_stats_t(C.Structure):
 class ss_bw_t(C.Structure):
     _fields_ = [("d2h_gbps", C.c_double), ("h2d_gbps", C.c_double), ("bidir_d2h_gbps", C.c_double),
                 ("bidir_h2d_gbps", C.c_double), ("kernel_d2h_gbps", C.c_double),
-                ("kernel_h2d_gbps", C.c_double)]
+                ("kernel_h2d_gbps", C.c_double), ("kernel_bidir_d2h_gbps", C.c_double),
+                ("kernel_bidir_h2d_gbps", C.c_double)]
 
 
 class SsError(RuntimeError):
     def __init__(self, code, where):
         self.code = code
-        super().__init__("%s: %s (%d)" % (where, ss_strerror(code), code))
+        msg = "%s: %s (%d)" % (where, ss_strerror(code), code)
+        if code in (SS_E_HIP, SS_E_NOMEM):
+            msg += " [last HIP error: %s]" % (ss_last_hip_error(),)
+        super().__init__(msg)
 
 
 _P = C.c_void_p
@@ -125,11 +132,20 @@ for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)          # AttributeError here = the library lacks a declared symbol
     _f.argtypes = _args
     _f.restype = C.c_int
-EXPORTS = sorted(list(_SIGS) + ["ss_strerror"])
+_lib.ss_last_hip_error.restype = C.c_int
+_lib.ss_last_hip_error.argtypes = [C.POINTER(C.c_char_p), C.POINTER(C.c_char_p), C.POINTER(C.c_int)]
+EXPORTS = sorted(list(_SIGS) + ["ss_strerror", "ss_last_hip_error"])
 
 
 def ss_strerror(code):
     return _lib.ss_strerror(int(code)).decode()
+
+
+def ss_last_hip_error():
+    """(hipError_t, name, source file, line) of the calling thread's last failing HIP call"""
+    name, file, line = C.c_char_p(), C.c_char_p(), C.c_int()
+    code = _lib.ss_last_hip_error(C.byref(name), C.byref(file), C.byref(line))
+    return code, (name.value or b"").decode(), os.path.basename((file.value or b"").decode()), line.value
 
 
 def _ck(rc, where):
@@ -189,6 +205,28 @@ def ss_trace_record(ctx, op, events=None):
     op = _arr(np.asarray(op).reshape(1), OP_DT)
     ev = _arr(events, EVENT_DT)
     _ck(_lib.ss_trace_record(ctx, _ptr(op), _ptr(ev), 0 if ev is None else len(ev)), "ss_trace_record")
+
+
+def ss_trace_record_prepared(ctx, ops, events):
+    """Marshal a whole trace once: returns a list of zero-argument callables, one per operator,
+    each of which is exactly one ss_trace_record call (for dispatch loops that must not pay
+    NumPy slicing per operator).  `events` must be in operator order."""
+    ops = _arr(ops, OP_DT)
+    ev = _arr(events, EVENT_DT)
+    bounds = np.searchsorted(ev["op_idx"], np.arange(len(ops) + 1))
+    f = _lib.ss_trace_record
+    op0, ev0 = ops.ctypes.data, ev.ctypes.data if len(ev) else 0
+    calls = []
+    for i in range(len(ops)):
+        n = int(bounds[i + 1] - bounds[i])
+        calls.append((_P(op0 + 16 * i), _P(ev0 + 16 * int(bounds[i])) if n else None, n))
+    keep = (ops, ev)           # the arrays must outlive the pointers
+
+    def record(i, _f=f, _c=calls, _ctx=ctx, _keep=keep):
+        rc = _f(_ctx, *_c[i])
+        if rc != SS_OK:
+            raise SsError(rc, "ss_trace_record")
+    return record
 
 
 def ss_trace_view(ctx):

@@ -56,11 +56,15 @@ struct ss_ctx {
   ss_stats_t stats;
 };
 
+// last failing HIP call of this thread: code, source file and line (ss_runtime.hip)
+void ss_note_hip_error(int code, const char *file, int line);
+
 #define SS_HIP(call)                                      \
   do {                                                    \
     hipError_t e__ = (call);                              \
     if (e__ != hipSuccess) {                              \
       ctx->stats.last_hip_error = (int32_t)e__;           \
+      ss_note_hip_error((int)e__, __FILE__, __LINE__);    \
       (void)hipGetLastError();                            \
       return SS_E_HIP;                                    \
     }                                                     \

@@ -10,6 +10,22 @@
 
 #include "ss_internal.h"
 
+static thread_local int t_hip_code = 0, t_hip_line = 0;
+static thread_local const char *t_hip_file = "";
+
+void ss_note_hip_error(int code, const char *file, int line) {
+  t_hip_code = code;
+  t_hip_file = file;
+  t_hip_line = line;
+}
+
+extern "C" int ss_last_hip_error(const char **name, const char **file, int *line) {
+  if (name) *name = hipGetErrorName((hipError_t)t_hip_code);
+  if (file) *file = t_hip_file;
+  if (line) *line = t_hip_line;
+  return t_hip_code;
+}
+
 extern "C" const char *ss_strerror(int code) {
   switch (code) {
     case SS_OK: return "ok";
@@ -64,11 +80,15 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
   ctx->cfg = cfg;
   std::memset(&ctx->stats, 0, sizeof(ctx->stats));
   int rc = SS_OK;
-  auto fail = [&](int code, hipError_t e) {
+  int fail_line = 0;
+  auto fail_at = [&](int code, hipError_t e, int line) {
     ctx->stats.last_hip_error = (int32_t)e;
+    ss_note_hip_error((int)e, __FILE__, line);
     (void)hipGetLastError();
     rc = code;
+    fail_line = line;
   };
+#define fail(code, e) fail_at(code, e, __LINE__)
   hipError_t e;
   if ((e = hipGetDevice(&ctx->device)) != hipSuccess) fail(SS_E_HIP, e);
   if (rc == SS_OK && cfg.staging_bytes) {
@@ -90,6 +110,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) fail(SS_E_HIP, e);
     else ctx->ev_ring.push_back(ev);
   }
+#undef fail
   if (rc != SS_OK) {
     ss_destroy(ctx);
     return rc;
@@ -157,6 +178,7 @@ int ss_scratch_reserve(ss_ctx *ctx, size_t dev_bytes, size_t host_bytes) {
     hipError_t e = hipMalloc(&ctx->d_scratch, want);
     if (e != hipSuccess) {
       ctx->stats.last_hip_error = (int32_t)e;
+      ss_note_hip_error((int)e, __FILE__, __LINE__);
       (void)hipGetLastError();
       return SS_E_NOMEM;
     }
@@ -170,6 +192,7 @@ int ss_scratch_reserve(ss_ctx *ctx, size_t dev_bytes, size_t host_bytes) {
     hipError_t e = hipHostMalloc(&ctx->h_scratch, want, hipHostMallocDefault);
     if (e != hipSuccess) {
       ctx->stats.last_hip_error = (int32_t)e;
+      ss_note_hip_error((int)e, __FILE__, __LINE__);
       (void)hipGetLastError();
       return SS_E_NOMEM;
     }
@@ -303,6 +326,7 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
       if (e == hipSuccess) e = hipMalloc((void **)&dc, (2 * want + 64) * sizeof(uint32_t));
       if (e != hipSuccess) {
         ctx->stats.last_hip_error = (int32_t)e;
+        ss_note_hip_error((int)e, __FILE__, __LINE__);
         (void)hipGetLastError();
         return SS_E_NOMEM;
       }
@@ -525,6 +549,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
   auto ck = [&](hipError_t e) {
     if (e != hipSuccess && rc == SS_OK) {
       ctx->stats.last_hip_error = (int32_t)e;
+      ss_note_hip_error((int)e, __FILE__, 0);
       (void)hipGetLastError();
       rc = SS_E_HIP;
     }
@@ -557,14 +582,15 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
   auto gbps = [&](float ms) { return ms > 0 ? (double)bytes / (ms * 1e-3) / 1e9 : 0.0; };
   const uint32_t wg = ctx->cfg.copy_workgroups;
   const uint32_t nchunks = (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
-  // mode 0: D2H engine, 1: H2D engine, 2: both engine, 3: D2H kernel, 4: H2D kernel
-  for (int mode = 0; mode < 5 && rc == SS_OK; ++mode) {
+  // mode 0: D2H engine, 1: H2D engine, 2: both engine, 3: D2H kernel, 4: H2D kernel, 5: both kernel
+  for (int mode = 0; mode < 6 && rc == SS_OK; ++mode) {
     std::vector<float> ta, tb;
     for (uint32_t r = 0; r < reps + 2 && rc == SS_OK; ++r) {
-      const bool d2h = (mode == 0 || mode == 2 || mode == 3), h2d = (mode == 1 || mode == 2 || mode == 4);
+      const bool d2h = (mode == 0 || mode == 2 || mode == 3 || mode == 5);
+      const bool h2d = (mode == 1 || mode == 2 || mode == 4 || mode == 5);
       if (d2h) {
         ck(hipEventRecord(a0, ctx->s_out));
-        if (mode == 3) {
+        if (mode == 3 || mode == 5) {
           ss_launch_copy(ctx->s_out, wg, true, d0, h0d, dd, dc, 1, nchunks);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
@@ -572,7 +598,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       }
       if (h2d) {
         ck(hipEventRecord(b0, ctx->s_in));
-        if (mode == 4) {
+        if (mode == 4 || mode == 5) {
           ss_launch_copy(ctx->s_in, wg, false, d1, h1d, dd, dc, 1, nchunks);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
@@ -591,6 +617,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       case 2: out->bidir_d2h_gbps = gbps(median(ta)); out->bidir_h2d_gbps = gbps(median(tb)); break;
       case 3: out->kernel_d2h_gbps = gbps(median(ta)); break;
       case 4: out->kernel_h2d_gbps = gbps(median(tb)); break;
+      case 5: out->kernel_bidir_d2h_gbps = gbps(median(ta)); out->kernel_bidir_h2d_gbps = gbps(median(tb)); break;
     }
   }
   if (a0) (void)hipEventDestroy(a0);

@@ -1,0 +1,91 @@
+"""GPU end-to-end: the synthetic training step with swapping on gives bit-identical compute
+results to the same step with swapping off (Sec. 1: swapping costs no accuracy), with real block
+reuse in a budget-sized arena and poison written over every released block."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2509_11076_amd.binding as B
+    return B, torch
+
+
+def run(B, torch, cfgno, swap, iters, **kw):
+    from workloads.harness import SwapRun
+    r = SwapRun(B, torch, cfgno, swap=swap, flags=B.SS_CFG_POISON_FREE if swap else 0, **kw)
+    try:
+        for _ in range(iters):
+            r.step() if swap else r.step_noswap()
+        chk, grad = r.compute.result()
+        info = dict(arena=r.arena_bytes, bytes=r.bytes_each_way, stats=B.ss_get_stats(r.ctx),
+                    plan=r.last, tr=r.tr, policy=r.policy)
+        return chk, grad, info
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_toy_step_swap_on_equals_swap_off(env, path):
+    B, torch = env
+    chk0, g0, i0 = run(B, torch, 1, False, 1)
+    chk1, g1, i1 = run(B, torch, 1, True, 1, bpo=64 * 1024, copy_path=path)
+    assert i1["bytes"] > 1_500_000 and i1["stats"]["bytes_out"] == i1["stats"]["bytes_in"] == i1["bytes"]
+    assert i1["stats"]["free_waits"] > 0 and i1["stats"]["in_waits"] > 0
+    assert np.array_equal(chk0, chk1) and np.array_equal(g0, g1)
+    assert i1["arena"] < i0["arena"]                     # released blocks were reused
+    assert (chk0 != 0).sum() >= 20
+    # the plan the library made is the oracle's
+    tr, pol = i1["tr"], i1["policy"]
+    ora = oracle.apply_policy(pol, pol["ref_op"].astype(np.int64), tr.tensors, 64 * 1024)
+    from helpers import applied_as_arrays
+    o = applied_as_arrays(ora)
+    assert np.array_equal(i1["plan"]["applied"]["actions"].view(np.uint8), o["actions"].view(np.uint8))
+    osc = oracle.timeline_scan(tr.events, ora["policy_events"], tr.n_ops, 0, 1 << 62)
+    assert i1["plan"]["scan"]["peak"] == osc["peak"]
+
+
+def test_1p3b_shape_three_iterations_swap_on_equals_swap_off(env):
+    """configuration 2: every other layer's activations (about 3 GB) leave and return, 3 iterations"""
+    B, torch = env
+    chk0, g0, i0 = run(B, torch, 2, False, 3)
+    chk1, g1, i1 = run(B, torch, 2, True, 3, bpo=8 << 20)
+    assert 2.9e9 < i1["bytes"] < 3.3e9
+    assert i1["stats"]["bytes_out"] == 3 * i1["bytes"] == i1["stats"]["bytes_in"]
+    assert np.array_equal(chk0, chk1) and np.array_equal(g0, g1)
+    assert i1["plan"]["match"]["similar"] and i1["plan"]["match"]["stage"] == B.SS_STAGE_GENPOLICY
+    assert i1["plan"]["match"]["n_unmatched"] == 0
+
+
+def test_7b_shape_small_scale_greedy_budget(env):
+    """configuration 3 at reduced width (hidden 512, seq 512, 8 layers): activations about twice
+    the budget, greedy policy, arena no larger than the budget allows, results unchanged"""
+    B, torch = env
+    from workloads.harness import SwapRun
+    shape = W.ModelShape("naive", 512, 8, 8, 512, 1, 4)
+    tr0 = W.build_trace(shape)
+    no = oracle.timeline_scan(tr0.events, None, tr0.n_ops, 0, 0)
+    budget = no["peak"] // 2
+    res = []
+    for swap in (False, True):
+        r = SwapRun(B, torch, 3, swap=swap, trace=W.build_trace(shape), budget=budget if swap else None,
+                    bpo=4 << 20, min_bytes=1 << 16, flags=B.SS_CFG_POISON_FREE if swap else 0)
+        try:
+            for _ in range(2):
+                r.step() if swap else r.step_noswap()
+            res.append((r.compute.result(), r.arena_bytes, r.last, r.policy, r.tr))
+        finally:
+            r.close()
+    (c0, g0), a0, _, _, _ = res[0]
+    (c1, g1), a1, plan, pol, tr = res[1]
+    assert np.array_equal(c0, c1) and np.array_equal(g0, g1)
+    assert plan["scan"]["peak"] <= budget and plan["scan"]["n_over"] == 0
+    assert a1 <= budget * 1.15 and a1 < a0 * 0.65
+    rows, _ = oracle.greedy_policy(tr.tensors, tr.events, tr.n_ops, 0, budget, 4 << 20, min_bytes=1 << 16)
+    assert [tuple(int(x) for x in p) for p in pol.tolist()] == rows

@@ -1,0 +1,127 @@
+"""Benchmark / test harness: one configuration set up end to end, then stepped.
+
+Plays the training framework around the swap executor: builds the synthetic
+trace, owns the device arena (placing tensors first-fit over their residency
+intervals, so released blocks are really reused), runs the synthetic compute
+stream, and calls the library at the points an eager-mode dispatch loop would
+(Sec. 3, Sec. 5).  It computes nothing of the method itself.
+"""
+import time
+
+import numpy as np
+
+from . import transformer as T
+from .arena import place_tensors
+from .layouts import ANCHOR_DT, NONE_OP
+from .small_tensor import build_small_tensor_stress
+
+
+class SwapRun:
+    """cfgno 1..3, 5 with a fixed operator sequence (configuration 4 re-plans per iteration, see
+    VaryingRun).  swap=False gives the no-swap baseline on an arena that holds everything."""
+
+    def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
+                 copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
+                 policy=None, engine_min_bytes=None):
+        from .compute import SyntheticCompute
+        self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
+        if trace is not None:
+            self.tr, pol = trace, policy
+        elif cfgno == 5:
+            self.tr, pol, _ = build_small_tensor_stress(seed=seed)
+        else:
+            self.tr = T.build_trace(T.config_shape(cfgno), seed=seed)
+            pol = T.config_swap_set(self.tr, cfgno) if cfgno in (1, 2) else None
+        tr = self.tr
+        cfg = B.ss_config_default()
+        cfg.link_bytes_per_op = bpo
+        cfg.copy_path = copy_path
+        cfg.copy_workgroups = copy_workgroups
+        cfg.flags = flags
+        cfg.guard_bytes = guard
+        cfg.max_ops = max(65536, tr.n_ops)
+        cfg.max_events = max(1 << 20, len(tr.events))
+        if engine_min_bytes is not None:
+            cfg.engine_min_bytes = engine_min_bytes
+        self.budget = budget if budget is not None else (1 << 62)
+        self.stream = torch.cuda.current_stream()
+
+        # a probing context without staging: policy and timing do not depend on addresses
+        cfg.staging_bytes = 0
+        probe = B.ss_create(cfg)
+        try:
+            self.ops = np.stack([B.ss_intern_op(probe, tr.op_name[i], tr.op_stack[i], tr.op_dtype[i],
+                                                len(tr.op_outputs[i]), tr.op_phase[i])
+                                 for i in range(tr.n_ops)]) if tr.n_ops else np.zeros(0, B.OP_DT)
+            if swap and pol is None:
+                pol, _ = B.ss_greedy_policy(probe, tr.tensors, tr.events, tr.n_ops, 0, self.budget, min_bytes)
+            if not swap:
+                pol = pol[:0] if pol is not None else np.zeros(0, B.POLICY_DT)
+            self.policy = pol
+            self.anchors = np.zeros(len(pol), dtype=ANCHOR_DT)
+            self.anchors["ref_op"] = pol["ref_op"]; self.anchors["out_slot"] = pol["out_slot"]
+            ap = B.ss_apply_policy(probe, pol, pol["ref_op"].astype(np.int32), tr.tensors, allow_nomem=True)
+        finally:
+            B.ss_destroy(probe)
+        res = ap["resolved"]
+        kept = (res["flags"] & (B.SS_F_UNMATCHED | B.SS_F_ORDER)) == 0
+        swapped = {int(r["tensor_id"]): (int(r["t_free"]), int(r["t_in"])) for r in res[kept]}
+        if cfgno == 5 and trace is None:
+            self.arena_bytes = 64 * 10**9          # placement is prescribed by the configuration
+        else:
+            self.arena_bytes = place_tensors(tr.tensors, swapped=swapped, guard=guard)
+        self.staging_bytes = max(4096, int(ap["staging_bytes"]))
+        cfg.staging_bytes = self.staging_bytes
+        self.ctx = B.ss_create(cfg)
+        # the library interns per context: same strings, same order, same integers
+        for i in range(tr.n_ops):
+            B.ss_intern_op(self.ctx, tr.op_name[i], tr.op_stack[i], tr.op_dtype[i], len(tr.op_outputs[i]),
+                           tr.op_phase[i])
+        self.arena = torch.empty(self.arena_bytes, dtype=torch.uint8, device="cuda")
+        B.ss_bind(self.ctx, self.arena.data_ptr(), self.arena_bytes, self.stream.cuda_stream)
+        self.compute = SyntheticCompute(tr, self.arena, seed=seed, gemm_scale=gemm_scale) if compute else None
+        if self.compute is not None:
+            self.compute.mark_swapped(swapped.keys())
+        self.record = B.ss_trace_record_prepared(self.ctx, self.ops, tr.events)
+        self.ref_ops = self.ops.copy()
+        self.bytes_each_way = int(ap["bytes_out"])
+        self.last = {}
+
+    def close(self):
+        if self.ctx is not None:
+            self.B.ss_destroy(self.ctx)
+            self.ctx = None
+        self.arena = None
+        self.compute = None
+
+    def plan(self):
+        """per-iteration trace work before the operators run: match (a3), apply (a4), scan (a2)"""
+        B, tr = self.B, self.tr
+        m = B.ss_match_sequence(self.ctx, self.ref_ops, self.ops, self.anchors, flags=B.SS_MATCH_STEP_STAGE)
+        ap = B.ss_apply_policy(self.ctx, self.policy, m["new_idx"], tr.tensors)
+        sc = B.ss_timeline_scan(self.ctx, tr.events, ap["policy_events"], tr.n_ops, 0, self.budget,
+                                want_timeline=False, want_per_op=False)
+        from paper_2509_11076_amd.executor import batch_lists
+        self.last = dict(match=m, applied=ap, scan=sc, lists=batch_lists(ap["actions"]))
+        return self.last
+
+    def step(self):
+        """one training iteration: plan, then dispatch every operator with trace recording (a1) and
+        the scheduled swap actions (a5-a7) around it"""
+        from paper_2509_11076_amd.executor import run_iteration
+        B = self.B
+        plan = self.plan()
+        B.ss_trace_begin(self.ctx)
+        rec, comp = self.record, self.compute
+
+        def run_op(i):
+            rec(i)
+            if comp is not None:
+                comp.run_op(i)
+        run_iteration(self.ctx, self.tr.n_ops, plan["applied"]["actions"], run_op, plan["lists"])
+
+    def step_noswap(self):
+        """the same operators with no swap executor at all (baseline for the overhead figure)"""
+        comp = self.compute
+        for i in range(self.tr.n_ops):
+            comp.run_op(i)
