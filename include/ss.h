@@ -89,7 +89,7 @@ typedef struct {
   uint32_t t_use;   /* first backward use: compute waits for the swap-in before it          */
   uint64_t nbytes;
 } ss_policy_item_t;                                                                /* 40 B */
-enum { SS_F_UNMATCHED = 1, SS_F_ORDER = 2, SS_F_LATE = 4, SS_F_RESIZED = 8 };
+enum { SS_F_UNMATCHED = 1, SS_F_ORDER = 2, SS_F_LATE = 4, SS_F_RESIZED = 8, SS_F_FORCED = 16 };
 
 /* One copy: nbytes between arena + dev_off and staging + host_off. */
 typedef struct { uint64_t dev_off, host_off, nbytes; uint32_t tensor_id, flags; } ss_desc_t; /* 32 B */
@@ -102,11 +102,18 @@ typedef struct { uint32_t op_idx, kind, tensor_id, batch; } ss_action_t;        
 /* ---- configuration -------------------------------------------------------- */
 enum { SS_PATH_AUTO = 0, SS_PATH_KERNEL = 1, SS_PATH_ENGINE = 2 };
 enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch_ms)          */
-       SS_CFG_POISON_FREE = 2 }; /* overwrite a block with 0xDB when its FREE action runs     */
+       SS_CFG_POISON_FREE = 2,   /* overwrite a block with 0xDB when its FREE action runs     */
+       SS_CFG_KEEP_LATE = 4,     /* keep items whose swap-out cannot finish before their first
+                                    backward use (released and re-fetched around that use, the
+                                    compute stream waiting) instead of dropping them            */
+       SS_CFG_SYSTEM_FENCE = 8 };/* ordering events carry a system-scope fence (default: device
+                                    scope; the host reads staging only after a synchronisation) */
 typedef struct {
   uint64_t staging_bytes;     /* pinned host staging to allocate at ss_create                */
   uint64_t link_bytes_per_op; /* link model: bytes the host link moves during one operator
                                  (Eq. 3 with Eq. 1 at one operator per group); >= 1           */
+  uint64_t prefetch_bytes_per_op; /* same for the swap-in queue only (0 = link_bytes_per_op); a smaller
+                                 value pre-triggers swap-ins with more margin (Sec. 4.3.1)       */
   uint64_t engine_min_bytes;  /* SS_PATH_AUTO: batches whose mean tensor size reaches this go
                                  to the copy engine, smaller ones to the copy kernel          */
   uint32_t align;             /* staging slot alignment, power of two >= 16 (default 256)    */
@@ -114,10 +121,13 @@ typedef struct {
   uint32_t stage_m, stage_n;  /* Algo. 1 hyper-parameters (defaults 2, 5)                    */
   uint32_t copy_path;         /* SS_PATH_*                                                   */
   uint32_t copy_workgroups;   /* grid size of the copy kernels (0 = default)                 */
+  uint32_t copy_workgroups_out; /* grid size of the swap-out copy kernel (0 = copy_workgroups) */
+  uint32_t copy_unroll;       /* 16-byte accesses in flight per lane: 2, 4 or 8 (0 = 8)      */
   uint32_t max_ops;           /* trace capacity in operators                                 */
   uint32_t max_events;        /* trace capacity in events                                    */
   uint32_t flags;             /* SS_CFG_*                                                    */
   uint32_t reserved;
+  uint32_t reserved2[2];
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */
@@ -246,10 +256,14 @@ int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, const ss_op_t
 /* Resolve each policy item against this iteration's tensor table (the output
  * slot out_slot of operator new_idx[a]), take t_out / t_use from the current
  * tensor, time release and pre-trigger with the FIFO link model
- * (link_bytes_per_op), drop what is unmatched or has no room, and build:
+ * (link_bytes_per_op for the swap-out queue, prefetch_bytes_per_op for the swap-in queue;
+ * no swap-in is issued before the last swap-out of the set), drop what is unmatched or has
+ * no room (or keep it forced around its use with SS_CFG_KEEP_LATE), and build:
  *   resolved[k]  (nullable) the items with their points and flags filled in
  *   actions[*n_actions]     sorted by (operator, kind, queue rank); in: capacity, out: count (4 per kept item)
- *   descs_out / descs_in    one descriptor per kept item in swap-out / swap-in issue order (capacity k)
+ *   descs_out / descs_in    one descriptor per kept item in swap-out / swap-in issue order (capacity k);
+ *                           a swap-out batch = items issued after the same operator, a swap-in batch =
+ *                           items issued before the same operator and first used by the same operator
  *   pevents[*n_pe]          policy events for ss_timeline_scan; in: capacity, out: count (2 per kept item)
  * and load the schedule into the context (as ss_load_schedule would).
  * Staging offsets are the exclusive prefix sum of align_up(nbytes, align) +
@@ -317,6 +331,10 @@ int ss_staging_fill(ss_ctx *ctx, int byte);
  * completed batch); dir 0 = out, 1 = in.  span_ms (nullable): first start to
  * last end over all batches of that direction enqueued since the last drain. */
 int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms);
+
+/* Start and end of a batch on its swap stream, in ms since the start of swap-out batch 0 of
+ * the same iteration (needs SS_CFG_TIMING; all batches involved must have completed). */
+int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *start_ms, float *end_ms);
 
 /* Host-link bandwidth measured now: pinned hipMemcpy D2H, H2D, both at once,
  * and the same through the copy kernels; `bytes` per transfer, median of `reps`. */

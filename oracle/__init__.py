@@ -37,5 +37,5 @@ from .timeline import timeline_scan
 from .match import similarity, StageMachine, match_anchors, match_sequence, WARMUP, GENPOLICY, STABLE
 from .policy import (link_timing, apply_policy, greedy_policy, schedule_check,
                      K_IN, K_WAIT_IN, K_OUT, K_FREE,
-                     F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED, Infeasible)
+                     F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED, F_FORCED, Infeasible)
 from .swap import swap_out, swap_in, SparseArena

@@ -21,10 +21,18 @@ FIFO link per direction.  Time is measured in link bytes: operator t occupies
   swap-in queue, as late as possible, items ordered by (t_use, policy index)
   descending:
       end = min(t_use * bpo, start of the item placed before); start = end - nbytes
-      floor_ = (t_free + 1) * bpo; if start < floor_: start = floor_, item is LATE
+      floor_ = max(t_free + 1, t_peak) * bpo with t_peak = 1 + the largest t_out of the set
+      (no swap-in before the last swap-out is issued); if start < floor_: start = floor_, item is LATE
       t_in = start // bpo
-  An item is valid iff t_out <= t_free < t_in <= t_use; otherwise it is
-  dropped (flag ORDER) and keeps no link time in the swap-in queue.
+  (the swap-in queue may be given its own bytes-per-operator, bpo_in, in place of bpo:
+  a smaller value pre-triggers the swap-ins with more margin)
+  An item is valid iff t_out <= t_free < t_in <= t_use.  An item whose swap-out
+  cannot complete before its first backward use (t_free >= t_use) saves no
+  memory; by default it is dropped (flag ORDER) and keeps no link time in the
+  swap-in queue.  With keep_late (a prescribed swap set that must be executed
+  whatever it costs; Sec. 4.3.1 accepts latency rather than giving up) it is
+  kept instead with t_free = t_use - 1, flags FORCED and LATE: released and
+  re-fetched around its use, the compute stream waiting for the round trip.
 
 PARITY UNPINNED against the paper (it prints no worked example of its
 simulator); pinned by the schedule checker, hand-worked cases and brute force.
@@ -33,7 +41,7 @@ import numpy as np
 
 NONE_OP = 0xFFFFFFFF
 K_IN, K_WAIT_IN, K_OUT, K_FREE = 0, 1, 2, 3           # order inside one operator
-F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED = 1, 2, 4, 8
+F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED, F_FORCED = 1, 2, 4, 8, 16
 
 
 class Infeasible(Exception):
@@ -44,14 +52,16 @@ def _align_up(x, a):
     return (x + a - 1) // a * a
 
 
-def link_timing(t_out, t_use, nbytes, bpo):
-    """Per item: (t_free, t_in, late, valid).  Inputs are equal-length integer lists."""
+def link_timing(t_out, t_use, nbytes, bpo, keep_late=False, bpo_in=None):
+    """Per item: (t_free, t_in, late, valid[, forced]).  Inputs are equal-length integer lists.
+    With keep_late a fifth list, forced, is returned as well."""
     k = len(t_out)
     bpo = int(bpo)
     t_free = [0] * k
     t_in = [0] * k
     late = [False] * k
     valid = [True] * k
+    forced = [False] * k
     link_free = 0
     for i in sorted(range(k), key=lambda i: (t_out[i], i)):
         ready = (t_out[i] + 1) * bpo
@@ -60,7 +70,19 @@ def link_timing(t_out, t_use, nbytes, bpo):
         link_free = end
         t_free[i] = (end - 1) // bpo
         if not (t_free[i] < t_use[i]):
-            valid[i] = False
+            if keep_late:
+                t_free[i] = t_use[i] - 1
+                forced[i] = True
+            else:
+                valid[i] = False
+    # the swap-in queue may assume another link share per operator (bpo_in): a smaller value
+    # stacks the swap-ins earlier, i.e. pre-triggers them with more margin (Sec. 4.3.1)
+    bpo = int(bpo_in) if bpo_in else bpo
+    # no swap-in is issued before the last swap-out has been issued: before that point memory is
+    # still climbing to its peak, and a swap-in there would only fight the swap-outs for the link
+    # (Sec. 4.3.1: the search for a swap-in slot does not go back beyond the peak-memory period)
+    outs = [t_out[i] for i in range(k) if valid[i]]
+    t_peak = max(outs) + 1 if outs else 0
     next_start = None
     for i in sorted(range(k), key=lambda i: (t_use[i], i), reverse=True):
         if not valid[i]:
@@ -69,16 +91,18 @@ def link_timing(t_out, t_use, nbytes, bpo):
         if next_start is not None and next_start < end:
             end = next_start
         start = end - nbytes[i]
-        floor_ = (t_free[i] + 1) * bpo
+        floor_ = max(t_free[i] + 1, t_peak) * bpo
         if start < floor_:
             start = floor_
             late[i] = True
         t_in[i] = start // bpo
         next_start = start
+    if keep_late:
+        return t_free, t_in, late, valid, forced
     return t_free, t_in, late, valid
 
 
-def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0):
+def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0, keep_late=False, bpo_in=None):
     """Turn a policy plus this iteration's tensor table into the action schedule.
 
     policy rows: ref_op, out_slot, tensor_id, flags, t_out, t_free, t_in, t_use, nbytes
@@ -119,7 +143,11 @@ def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0):
     t_out = [int(tensors[cur[a]]["last_fwd_use"]) for a in live]
     t_use = [int(tensors[cur[a]]["first_bwd_use"]) for a in live]
     nb = [int(tensors[cur[a]]["nbytes"]) for a in live]
-    t_free, t_in, late, valid = link_timing(t_out, t_use, nb, bpo)
+    if keep_late:
+        t_free, t_in, late, valid, forced = link_timing(t_out, t_use, nb, bpo, keep_late=True, bpo_in=bpo_in)
+    else:
+        t_free, t_in, late, valid = link_timing(t_out, t_use, nb, bpo, bpo_in=bpo_in)
+        forced = [False] * len(live)
 
     resolved = []
     kept = []        # (a, row, t_out, t_free, t_in, t_use, nbytes)
@@ -131,6 +159,8 @@ def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0):
             continue
         if late[pos]:
             flags[a] |= F_LATE
+        if forced[pos]:
+            flags[a] |= F_FORCED
         if nb[pos] != int(policy[a]["nbytes"]):
             flags[a] |= F_RESIZED
         info[a] = (cur[a], t_out[pos], t_free[pos], t_in[pos], t_use[pos], nb[pos])
@@ -175,7 +205,7 @@ def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0):
     descs_in, in_batch_start, in_batch_of, in_dep = [], [0], {}, []
     prev = None
     for a in in_issue:
-        row, ti = info[a][0], info[a][3]
+        row, ti = info[a][0], (info[a][3], info[a][4])       # a batch: same issue point and same first use
         if prev is not None and ti != prev:
             in_batch_start.append(len(descs_in))
         if prev is None or ti != prev:
@@ -217,7 +247,7 @@ def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0):
 
 
 def greedy_policy(tensors, events, n_ops, base, budget, bpo, min_bytes=0, initial=None,
-                  align=256, guard=0):
+                  align=256, guard=0, keep_late=False, bpo_in=None):
     """Longest-idle-first swap set that brings the timeline peak within the budget.
 
     Stand-in for Algo. 2 (Sec. 4.4): the memory reduction list is the set of
@@ -248,7 +278,7 @@ def greedy_policy(tensors, events, n_ops, base, budget, bpo, min_bytes=0, initia
         return a
 
     rows = [tuple(int(x) for x in r) for r in (initial if initial is not None else [])]
-    applied = apply_policy(as_struct(rows), identity_idx(rows), tensors, bpo, align, guard)
+    applied = apply_policy(as_struct(rows), identity_idx(rows), tensors, bpo, align, guard, keep_late, bpo_in)
     scan = timeline_scan(events, applied["policy_events"], n_ops, base, budget)
     if scan["peak"] <= budget:
         return rows, applied
@@ -267,7 +297,7 @@ def greedy_policy(tensors, events, n_ops, base, budget, bpo, min_bytes=0, initia
     cands.sort()
     for (_, negn, tid, prod, slot) in cands:
         rows.append((prod, slot, tid, 0, 0, 0, 0, 0, -negn))
-        applied = apply_policy(as_struct(rows), identity_idx(rows), tensors, bpo, align, guard)
+        applied = apply_policy(as_struct(rows), identity_idx(rows), tensors, bpo, align, guard, keep_late, bpo_in)
         scan = timeline_scan(events, applied["policy_events"], n_ops, base, budget)
         if scan["peak"] <= budget:
             return rows, applied

@@ -40,20 +40,21 @@ SS_OK = 0
  SS_E_STATE, SS_E_CAPACITY) = range(-1, -10, -1)
 SS_ACT_IN, SS_ACT_WAIT_IN, SS_ACT_OUT, SS_ACT_FREE = 0, 1, 2, 3
 SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE = 0, 1, 2
-SS_CFG_TIMING, SS_CFG_POISON_FREE = 1, 2
+SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE = 1, 2, 4, 8
 SS_SYNC_FREE, SS_SYNC_WAIT_IN, SS_SYNC_DRAIN = 0, 1, 2
 SS_MATCH_STEP_STAGE, SS_MATCH_HISTOGRAM = 1, 2
 SS_STAGE_WARMUP, SS_STAGE_GENPOLICY, SS_STAGE_STABLE = 0, 1, 2
-SS_F_UNMATCHED, SS_F_ORDER, SS_F_LATE, SS_F_RESIZED = 1, 2, 4, 8
+SS_F_UNMATCHED, SS_F_ORDER, SS_F_LATE, SS_F_RESIZED, SS_F_FORCED = 1, 2, 4, 8, 16
 SS_NONE_OP = 0xFFFFFFFF
 
 
 class ss_config_t(C.Structure):
     _fields_ = [("staging_bytes", C.c_uint64), ("link_bytes_per_op", C.c_uint64),
-                ("engine_min_bytes", C.c_uint64), ("align", C.c_uint32), ("guard_bytes", C.c_uint32),
+                ("prefetch_bytes_per_op", C.c_uint64), ("engine_min_bytes", C.c_uint64), ("align", C.c_uint32), ("guard_bytes", C.c_uint32),
                 ("stage_m", C.c_uint32), ("stage_n", C.c_uint32), ("copy_path", C.c_uint32),
-                ("copy_workgroups", C.c_uint32), ("max_ops", C.c_uint32), ("max_events", C.c_uint32),
-                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
+                ("copy_workgroups", C.c_uint32), ("copy_workgroups_out", C.c_uint32),
+                ("copy_unroll", C.c_uint32), ("max_ops", C.c_uint32), ("max_events", C.c_uint32),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32), ("reserved2", C.c_uint32 * 2)]
 
 
 class ss_scan_result_t(C.Structure):
@@ -125,6 +126,7 @@ _SIGS = {
     "ss_host_peek": [_P, C.c_uint64, C.c_uint64, C.POINTER(_P)],
     "ss_staging_fill": [_P, C.c_int],
     "ss_batch_ms": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
+    "ss_batch_window": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
     "ss_bw_probe": [_P, C.c_uint64, C.c_uint32, C.POINTER(ss_bw_t)],
     "ss_get_stats": [_P, C.POINTER(ss_stats_t)],
 }
@@ -363,6 +365,12 @@ def ss_batch_ms(ctx, direction, batch=None):
     _ck(_lib.ss_batch_ms(ctx, int(direction), 0 if batch is None else int(batch),
                          C.byref(ms) if batch is not None else None, C.byref(span)), "ss_batch_ms")
     return (ms.value if batch is not None else None), span.value
+
+
+def ss_batch_window(ctx, direction, batch):
+    a, b = C.c_float(), C.c_float()
+    _ck(_lib.ss_batch_window(ctx, int(direction), int(batch), C.byref(a), C.byref(b)), "ss_batch_window")
+    return a.value, b.value
 
 
 def ss_bw_probe(ctx, nbytes=1 << 30, reps=10):

@@ -20,12 +20,12 @@
 
 namespace {
 
-constexpr uint32_t kUnroll = 8;
 constexpr uint32_t kLdsEntries = 8192;   // chunk-prefix entries staged in LDS (32 KiB)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <bool TO_HOST>
+// kUnroll 16-byte accesses are in flight per lane before the first store is issued.
+template <bool TO_HOST, uint32_t kUnroll, bool kPlain = false>
 __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
     uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
     const uint32_t *__restrict__ chunk0, uint32_t n_desc, uint32_t n_chunks) {
@@ -60,12 +60,12 @@ __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
 #pragma unroll
       for (uint32_t u = 0; u < kUnroll; ++u) {
         const uint32_t i = base + u * SS_COPY_THREADS + tid;
-        if (i < n16) v[u] = __builtin_nontemporal_load(src16 + i);
+        if (i < n16) v[u] = kPlain ? src16[i] : __builtin_nontemporal_load(src16 + i);
       }
 #pragma unroll
       for (uint32_t u = 0; u < kUnroll; ++u) {
         const uint32_t i = base + u * SS_COPY_THREADS + tid;
-        if (i < n16) __builtin_nontemporal_store(v[u], dst16 + i);
+        if (i < n16) { if (kPlain) dst16[i] = v[u]; else __builtin_nontemporal_store(v[u], dst16 + i); }
       }
     }
     const uint32_t tail = n & 15u;          // only the last chunk of a tensor can have one
@@ -86,16 +86,25 @@ __global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nby
 
 }  // namespace
 
-void ss_launch_copy(hipStream_t s, uint32_t workgroups, bool to_host, uint8_t *arena, uint8_t *staging,
-                    const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc, uint32_t n_chunks) {
+void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
+                    uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc,
+                    uint32_t n_chunks) {
   if (n_chunks == 0 || n_desc == 0) return;
-  uint32_t grid = workgroups < n_chunks ? workgroups : n_chunks;
-  if (to_host)
-    hipLaunchKernelGGL(ss_copy_kernel<true>, dim3(grid), dim3(SS_COPY_THREADS), 0, s, arena, staging, d_descs,
-                       d_chunk0, n_desc, n_chunks);
-  else
-    hipLaunchKernelGGL(ss_copy_kernel<false>, dim3(grid), dim3(SS_COPY_THREADS), 0, s, arena, staging, d_descs,
-                       d_chunk0, n_desc, n_chunks);
+  const dim3 grid(workgroups < n_chunks ? workgroups : n_chunks), block(SS_COPY_THREADS);
+#define SS_LAUNCH(TH, U)                                                                                  \
+  hipLaunchKernelGGL((ss_copy_kernel<TH, U>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, n_desc, \
+                     n_chunks)
+  if (unroll == 7) {   // experiment: plain (temporal) loads and stores, 8 in flight
+    if (to_host) hipLaunchKernelGGL((ss_copy_kernel<true, 8, true>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, n_desc, n_chunks);
+    else hipLaunchKernelGGL((ss_copy_kernel<false, 8, true>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, n_desc, n_chunks);
+    return;
+  }
+  if (to_host) {
+    if (unroll <= 2) SS_LAUNCH(true, 2); else if (unroll <= 4) SS_LAUNCH(true, 4); else SS_LAUNCH(true, 8);
+  } else {
+    if (unroll <= 2) SS_LAUNCH(false, 2); else if (unroll <= 4) SS_LAUNCH(false, 4); else SS_LAUNCH(false, 8);
+  }
+#undef SS_LAUNCH
 }
 
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value) {

@@ -91,6 +91,7 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
 // copy kernels (ss_copy.hip)
 constexpr uint32_t SS_CHUNK_BYTES = 64 * 1024;
 constexpr uint32_t SS_COPY_THREADS = 256;
-void ss_launch_copy(hipStream_t s, uint32_t workgroups, bool to_host, uint8_t *arena, uint8_t *staging,
-                    const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc, uint32_t n_chunks);
+void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
+                    uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc,
+                    uint32_t n_chunks);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);

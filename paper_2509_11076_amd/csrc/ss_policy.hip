@@ -21,7 +21,7 @@ struct Live {
   uint32_t row;      // row in the tensor table
   uint64_t t_out, t_use, nbytes;
   uint64_t t_free = 0, t_in = 0;
-  bool late = false, valid = true;
+  bool late = false, valid = true, forced = false;
 };
 
 typedef unsigned __int128 u128;
@@ -39,8 +39,10 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
     index[r] = {((uint64_t)tensors[r].producer_op << 32) | tensors[r].out_slot, r};
     if (tensors[r].first_bwd_use != SS_NONE_OP) max_op = std::max(max_op, tensors[r].first_bwd_use);
   }
+  const uint64_t bpo_in = cfg.prefetch_bytes_per_op ? cfg.prefetch_bytes_per_op : bpo;
   // link times are kept below 2^63
   if ((u128)(max_op + 2ull) * bpo >= ((u128)1 << 62)) return SS_E_INVAL;
+  if ((u128)(max_op + 2ull) * bpo_in >= ((u128)1 << 62)) return SS_E_INVAL;
   std::sort(index.begin(), index.end());
   auto find_row = [&](uint32_t op, uint32_t slot, uint32_t &row) {
     const uint64_t key = ((uint64_t)op << 32) | slot;
@@ -92,26 +94,39 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
     if (end >= (1ull << 62)) return SS_E_INVAL;
     link_free = end;
     L.t_free = (end - 1) / bpo;          // the operator running when the last byte lands
-    if (!(L.t_free < L.t_use)) L.valid = false;
+    if (!(L.t_free < L.t_use)) {
+      if (cfg.flags & SS_CFG_KEEP_LATE) {      // must be executed anyway: released and re-fetched around its use
+        L.t_free = L.t_use - 1;
+        L.forced = true;
+      } else {
+        L.valid = false;                       // saves no memory: dropped
+      }
+    }
   }
   // swap-in queue: as late as possible, walking (t_use, policy index) downwards
   std::sort(ord.begin(), ord.end(), [&](uint32_t x, uint32_t y) {
     return live[x].t_use != live[y].t_use ? live[x].t_use > live[y].t_use : live[x].a > live[y].a;
   });
+  // No swap-in is issued before the last swap-out has been issued: until then memory is still
+  // climbing to its peak and a swap-in would only fight the swap-outs for the link (Sec. 4.3.1:
+  // the search for a swap-in slot does not go back beyond the peak-memory period).
+  uint64_t t_peak = 0;
+  for (const Live &L : live)
+    if (L.valid) t_peak = std::max(t_peak, L.t_out + 1);
   bool have_next = false;
   int64_t next_start = 0;
   for (uint32_t i : ord) {
     Live &L = live[i];
     if (!L.valid) continue;
-    int64_t end = (int64_t)(L.t_use * bpo);
+    int64_t end = (int64_t)(L.t_use * bpo_in);
     if (have_next && next_start < end) end = next_start;
     int64_t start = end - (int64_t)L.nbytes;
-    const int64_t floor_ = (int64_t)((L.t_free + 1) * bpo);
+    const int64_t floor_ = (int64_t)(std::max(L.t_free + 1, t_peak) * bpo_in);
     if (start < floor_) {
       start = floor_;
       L.late = true;
     }
-    L.t_in = (uint64_t)start / bpo;
+    L.t_in = (uint64_t)start / bpo_in;
     next_start = start;
     have_next = true;
   }
@@ -125,6 +140,7 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
       continue;
     }
     if (L.late) flags[L.a] |= SS_F_LATE;
+    if (L.forced) flags[L.a] |= SS_F_FORCED;
     if (L.nbytes != policy[L.a].nbytes) flags[L.a] |= SS_F_RESIZED;
     kept.push_back(i);
   }
@@ -183,7 +199,7 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
     out.out.push_back(ss_desc_t{t.dev_off, host_off[i], live[i].nbytes, t.tensor_id, flags[live[i].a]});
   }
   out.out_start.push_back((uint32_t)out.out.size());
-  // swap-in batches: everything issued before the same operator, in swap-in queue order
+  // swap-in batches: issued before the same operator and first used by the same operator, in swap-in queue order
   std::vector<uint32_t> in_issue(kept);
   std::sort(in_issue.begin(), in_issue.end(), [&](uint32_t x, uint32_t y) {
     return live[x].t_in != live[y].t_in ? live[x].t_in < live[y].t_in : in_rank[x] < in_rank[y];
@@ -191,7 +207,9 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
   out.in_start.assign(1, 0);
   for (size_t p = 0; p < in_issue.size(); ++p) {
     const uint32_t i = in_issue[p];
-    const bool fresh = p == 0 || live[i].t_in != live[in_issue[p - 1]].t_in;
+    // a batch: same issue point and same first use (so a wait covers only what that use needs)
+    const bool fresh = p == 0 || live[i].t_in != live[in_issue[p - 1]].t_in ||
+                       live[i].t_use != live[in_issue[p - 1]].t_use;
     if (p && fresh) out.in_start.push_back((uint32_t)out.in.size());
     if (fresh) out.in_dep.push_back(0);
     const uint32_t b = (uint32_t)out.in_start.size() - 1;

@@ -62,6 +62,13 @@ extern "C" int ss_config_default(ss_config_t *cfg) {
 
 static uint32_t default_workgroups() { return 64; }
 
+// Ordering events only order work on this device (compute stream <-> swap streams); the host
+// reads staging only after a stream synchronisation.  So they need no system-scope fence,
+// which would write back and invalidate the L2 at every marker.
+static unsigned fence_flag(const ss_config_t &cfg) {
+  return (cfg.flags & SS_CFG_SYSTEM_FENCE) ? 0u : (unsigned)hipEventDisableSystemFence;
+}
+
 extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
   if (!out) return SS_E_INVAL;
   *out = nullptr;
@@ -73,7 +80,9 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
       cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_ENGINE)
     return SS_E_INVAL;
   if (cfg.copy_workgroups == 0) cfg.copy_workgroups = default_workgroups();
-  if (cfg.copy_workgroups > 4096) return SS_E_INVAL;
+  if (cfg.copy_workgroups_out == 0) cfg.copy_workgroups_out = cfg.copy_workgroups;
+  if (cfg.copy_unroll == 0) cfg.copy_unroll = 8;
+  if (cfg.copy_workgroups > 4096 || cfg.copy_workgroups_out > 4096 || cfg.copy_unroll > 8) return SS_E_INVAL;
 
   ss_ctx *ctx = new (std::nothrow) ss_ctx();
   if (!ctx) return SS_E_NOMEM;
@@ -107,7 +116,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
   if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_aux, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
   for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
     hipEvent_t ev;
-    if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) fail(SS_E_HIP, e);
+    if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming | fence_flag(cfg))) != hipSuccess) fail(SS_E_HIP, e);
     else ctx->ev_ring.push_back(ev);
   }
 #undef fail
@@ -306,7 +315,8 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
   s.in_waited.assign(n_in_batches, 0);
   s.in_issued.assign(n_in_batches, 0);
 
-  const unsigned evflags = (ctx->cfg.flags & SS_CFG_TIMING) ? hipEventDefault : hipEventDisableTiming;
+  const unsigned evflags = ((ctx->cfg.flags & SS_CFG_TIMING) ? hipEventDefault : hipEventDisableTiming) |
+                           fence_flag(ctx->cfg);
   if ((rc = ensure_events(ctx, s.ev_out_done, n_out_batches, evflags)) != SS_OK) return rc;
   if ((rc = ensure_events(ctx, s.ev_in_done, n_in_batches, evflags)) != SS_OK) return rc;
   if (ctx->cfg.flags & SS_CFG_TIMING) {
@@ -398,7 +408,7 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
   } else {
     const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
     const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
-    ss_launch_copy(ctx->s_out, ctx->cfg.copy_workgroups, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
+    ss_launch_copy(ctx->s_out, ctx->cfg.copy_workgroups_out, ctx->cfg.copy_unroll, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
                    hi - lo, n_chunks);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
@@ -435,7 +445,7 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
   } else {
     const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
     const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
-    ss_launch_copy(ctx->s_in, ctx->cfg.copy_workgroups, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
+    ss_launch_copy(ctx->s_in, ctx->cfg.copy_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
                    hi - lo, n_chunks);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
@@ -513,6 +523,19 @@ extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms,
   return SS_OK;
 }
 
+extern "C" int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *start_ms, float *end_ms) {
+  if (!ctx || dir > 1 || !start_ms || !end_ms) return SS_E_INVAL;
+  if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
+  ss_sched &s = ctx->sched;
+  auto &st = dir ? s.ev_in_start : s.ev_out_start;
+  auto &dn = dir ? s.ev_in_done : s.ev_out_done;
+  const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
+  if (batch >= nb || s.out_start.size() < 2) return SS_E_INVAL;
+  SS_HIP(hipEventElapsedTime(start_ms, s.ev_out_start[0], st[batch]));
+  SS_HIP(hipEventElapsedTime(end_ms, s.ev_out_start[0], dn[batch]));
+  return SS_OK;
+}
+
 // ---- support -------------------------------------------------------------------
 
 extern "C" int ss_host_peek(ss_ctx *ctx, uint64_t host_off, uint64_t nbytes, const void **ptr) {
@@ -580,7 +603,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
     return v[v.size() / 2];
   };
   auto gbps = [&](float ms) { return ms > 0 ? (double)bytes / (ms * 1e-3) / 1e9 : 0.0; };
-  const uint32_t wg = ctx->cfg.copy_workgroups;
+  const uint32_t wg = ctx->cfg.copy_workgroups, wgo = ctx->cfg.copy_workgroups_out;
   const uint32_t nchunks = (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
   // mode 0: D2H engine, 1: H2D engine, 2: both engine, 3: D2H kernel, 4: H2D kernel, 5: both kernel
   for (int mode = 0; mode < 6 && rc == SS_OK; ++mode) {
@@ -591,7 +614,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       if (d2h) {
         ck(hipEventRecord(a0, ctx->s_out));
         if (mode == 3 || mode == 5) {
-          ss_launch_copy(ctx->s_out, wg, true, d0, h0d, dd, dc, 1, nchunks);
+          ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, 1, nchunks);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
         ck(hipEventRecord(a1, ctx->s_out));
@@ -599,7 +622,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       if (h2d) {
         ck(hipEventRecord(b0, ctx->s_in));
         if (mode == 4 || mode == 5) {
-          ss_launch_copy(ctx->s_in, wg, false, d1, h1d, dd, dc, 1, nchunks);
+          ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, 1, nchunks);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
         ck(hipEventRecord(b1, ctx->s_in));

@@ -297,6 +297,31 @@ def test_apply_policy_prescribed_sets(P, cfgno, bpo, guard):
         del arena
 
 
+def test_apply_policy_keep_late_slow_link(P):
+    """a link too slow for the prescribed set: dropped by default, forced around the use with KEEP_LATE"""
+    import torch
+    tr = W.build_trace(W.config_shape(2))
+    pol = W.config_swap_set(tr, 2)
+    arena_bytes = place_tensors(tr.tensors)
+    idx = pol["ref_op"].astype(np.int64)
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+    for flags, keep, bin_ in ((0, False, 0), (P.SS_CFG_KEEP_LATE, True, 0), (P.SS_CFG_KEEP_LATE, True, 1 << 20),
+                              (0, False, 3 << 20)):
+        ora = oracle.apply_policy(pol, idx, tr.tensors, 4 << 20, keep_late=keep, bpo_in=bin_ or None)
+        c = make_ctx(P, staging_bytes=max(4096, ora["staging_bytes"]), link_bytes_per_op=4 << 20, flags=flags,
+                     prefetch_bytes_per_op=bin_)
+        try:
+            P.ss_bind(c, arena.data_ptr(), arena_bytes, 0)
+            lib = P.ss_apply_policy(c, pol, idx, tr.tensors)
+            assert_applied_equal(lib, P, c, ora)
+            assert (lib["n_dropped"] == 0) == keep
+            n_forced = int(((lib["resolved"]["flags"] & P.SS_F_FORCED) != 0).sum())
+            assert n_forced == sum(1 for r in ora["resolved"] if r[3] & oracle.F_FORCED)
+            assert (n_forced > 10) == keep
+        finally:
+            P.ss_destroy(c)
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_greedy_policy_tiny(P, seed):
     tab, ev = tiny_trace(seed, n_ops=14, T=8)

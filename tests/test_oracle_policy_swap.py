@@ -26,6 +26,50 @@ def test_link_timing_hand_worked_case():
     assert (t_free, t_in, late, valid) == ([2], [3], [True], [True])
 
 
+def test_link_timing_keep_late_hand_worked_case():
+    # same three items as above, but C must be executed although its swap-out ends during op 9 > use at 4:
+    # forced release after op 3, swap-in floor (3+1)*100 = 400 = its deadline: issued at op 4 == use, LATE
+    t_free, t_in, late, valid, forced = oracle.link_timing([0, 0, 2], [10, 9, 4], [250, 100, 500], 100,
+                                                           keep_late=True)
+    assert t_free == [3, 4, 3] and t_in == [7, 6, 4]
+    assert late == [False, False, True] and valid == [True] * 3 and forced == [False, False, True]
+
+
+def test_link_timing_with_a_smaller_share_for_the_swap_in_queue():
+    # out queue at 100 bytes/op as in the first case; in queue planned at 50 bytes/op:
+    # A (250 B, use 10): ends 500, starts 250 -> op 5.  B (100 B, use 9): ends min(450, 250) = 250,
+    # starts 150, but must not start before (t_free 4 + 1) * 50 = 250 -> LATE, op 5.
+    t_free, t_in, late, valid = oracle.link_timing([0, 0], [10, 9], [250, 100], 100, bpo_in=50)
+    assert t_free == [3, 4] and t_in == [5, 5] and late == [False, True] and valid == [True, True]
+
+
+def test_no_swap_in_is_issued_before_the_last_swap_out():
+    # X: 10 bytes, out after op 0, used at 20.  Y: 10 bytes, out after op 10 (t_free 11), used at 12.
+    # The swap-in queue is planned with 1 byte per operator, so it would like to start X at op 10;
+    # the last swap-out is issued after op 10, so nothing comes in before op 11: X at 11 (LATE),
+    # Y cannot come in before its own release + 1 = 12 (LATE).
+    t_free, t_in, late, valid = oracle.link_timing([0, 10], [20, 12], [10, 10], 100, bpo_in=1)
+    assert t_free == [1, 11] and t_in == [11, 12] and late == [True, True] and valid == [True, True]
+
+
+def test_keep_late_executes_the_whole_prescribed_set():
+    tr = W.build_trace(W.config_shape(2))
+    pol = W.config_swap_set(tr, 2)
+    idx = pol["ref_op"].astype(np.int64)
+    slow = 4 << 20                                  # a link that cannot keep up with every other layer
+    drop = oracle.apply_policy(pol, idx, tr.tensors, slow)
+    keep = oracle.apply_policy(pol, idx, tr.tensors, slow, keep_late=True)
+    assert drop["n_dropped"] > 10 and keep["n_dropped"] == 0
+    assert oracle.schedule_check(keep, tr.tensors, tr.op_inputs, tr.op_outputs) == []
+    forced = [r for r in keep["resolved"] if r[3] & oracle.F_FORCED]
+    assert len(forced) == drop["n_dropped"]
+    assert all(r[5] == r[7] - 1 and r[6] == r[7] and r[3] & oracle.F_LATE for r in forced)
+    # a forced item gives no memory back: same peak as dropping it
+    p_keep = oracle.timeline_scan(tr.events, keep["policy_events"], tr.n_ops, 0, 0)["peak"]
+    p_drop = oracle.timeline_scan(tr.events, drop["policy_events"], tr.n_ops, 0, 0)["peak"]
+    assert p_keep == p_drop
+
+
 def test_link_timing_instantaneous_link():
     t_free, t_in, late, valid = oracle.link_timing([4, 4, 7], [20, 9, 9], [10**6, 10**9, 5], INSTANT)
     # the last item has no room: out after 7, released after 8, needed at 9 -> issued at 9 == use:

@@ -22,7 +22,7 @@ class SwapRun:
 
     def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
                  copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
-                 policy=None, engine_min_bytes=None):
+                 policy=None, engine_min_bytes=None, bpo_in=0):
         from .compute import SyntheticCompute
         self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
         if trace is not None:
@@ -35,6 +35,7 @@ class SwapRun:
         tr = self.tr
         cfg = B.ss_config_default()
         cfg.link_bytes_per_op = bpo
+        cfg.prefetch_bytes_per_op = bpo_in
         cfg.copy_path = copy_path
         cfg.copy_workgroups = copy_workgroups
         cfg.flags = flags
@@ -70,6 +71,8 @@ class SwapRun:
             self.arena_bytes = 64 * 10**9          # placement is prescribed by the configuration
         else:
             self.arena_bytes = place_tensors(tr.tensors, swapped=swapped, guard=guard)
+        self.n_forced = int(((res["flags"] & B.SS_F_FORCED) != 0).sum())
+        self.n_dropped = int(ap["n_dropped"])
         self.staging_bytes = max(4096, int(ap["staging_bytes"]))
         cfg.staging_bytes = self.staging_bytes
         self.ctx = B.ss_create(cfg)
