@@ -114,20 +114,21 @@ typedef struct {
                                  (Eq. 3 with Eq. 1 at one operator per group); >= 1           */
   uint64_t prefetch_bytes_per_op; /* same for the swap-in queue only (0 = link_bytes_per_op); a smaller
                                  value pre-triggers swap-ins with more margin (Sec. 4.3.1)       */
-  uint64_t engine_min_bytes;  /* SS_PATH_AUTO: batches whose mean tensor size reaches this go
-                                 to the copy engine, smaller ones to the copy kernel          */
+  uint64_t engine_min_bytes;  /* SS_PATH_AUTO: swap-out batches always go to the copy kernel; swap-in
+                                 batches whose mean tensor size reaches this go to the copy engine,
+                                 smaller ones to the copy kernel (default 4 MiB)              */
   uint32_t align;             /* staging slot alignment, power of two >= 16 (default 256)    */
   uint32_t guard_bytes;       /* untouched bytes before/after each staging slot (mult. of align) */
   uint32_t stage_m, stage_n;  /* Algo. 1 hyper-parameters (defaults 2, 5)                    */
-  uint32_t copy_path;         /* SS_PATH_*                                                   */
+  uint32_t copy_path;         /* SS_PATH_* for swap-out batches                              */
+  uint32_t copy_path_in;      /* SS_PATH_* for swap-in batches                               */
   uint32_t copy_workgroups;   /* grid size of the copy kernels (0 = default)                 */
   uint32_t copy_workgroups_out; /* grid size of the swap-out copy kernel (0 = copy_workgroups) */
   uint32_t copy_unroll;       /* 16-byte accesses in flight per lane: 2, 4 or 8 (0 = 8)      */
   uint32_t max_ops;           /* trace capacity in operators                                 */
   uint32_t max_events;        /* trace capacity in events                                    */
   uint32_t flags;             /* SS_CFG_*                                                    */
-  uint32_t reserved;
-  uint32_t reserved2[2];
+  uint32_t reserved[2];
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */
@@ -177,7 +178,7 @@ typedef struct {
 /* ---- life cycle -------------------------------------------------------------- */
 
 /* Fill *cfg with defaults (staging 64 MiB, link 64 MiB/op, align 256, no guard, m=2, n=5,
- * auto path, 65536 operators, 1048576 events). */
+ * auto paths, 65536 operators, 1048576 events). */
 int ss_config_default(ss_config_t *cfg /* host, out */);
 
 /* Create a context on the current HIP device: allocates pinned staging, the

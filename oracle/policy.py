@@ -23,7 +23,9 @@ FIFO link per direction.  Time is measured in link bytes: operator t occupies
       end = min(t_use * bpo, start of the item placed before); start = end - nbytes
       floor_ = max(t_free + 1, t_peak) * bpo with t_peak = 1 + the largest t_out of the set
       (no swap-in before the last swap-out is issued); if start < floor_: start = floor_, item is LATE
-      t_in = start // bpo
+      t_in = start // bpo; finally, walking (t_use, policy index) upwards, t_in = max(t_in, t_in of
+      the item before): the swap-in stream is first-in first-out, so an item needed later is never
+      issued ahead of one needed earlier
   (the swap-in queue may be given its own bytes-per-operator, bpo_in, in place of bpo:
   a smaller value pre-triggers the swap-ins with more margin)
   An item is valid iff t_out <= t_free < t_in <= t_use.  An item whose swap-out
@@ -97,6 +99,13 @@ def link_timing(t_out, t_use, nbytes, bpo, keep_late=False, bpo_in=None):
             late[i] = True
         t_in[i] = start // bpo
         next_start = start
+    # the swap-in stream is first-in first-out: an item needed later is never issued before one
+    # needed earlier (the release-point floor can otherwise put it ahead in the queue)
+    run = 0
+    for i in sorted(range(k), key=lambda i: (t_use[i], i)):
+        if valid[i]:
+            t_in[i] = max(t_in[i], run)
+            run = t_in[i]
     if keep_late:
         return t_free, t_in, late, valid, forced
     return t_free, t_in, late, valid

@@ -52,9 +52,10 @@ class ss_config_t(C.Structure):
     _fields_ = [("staging_bytes", C.c_uint64), ("link_bytes_per_op", C.c_uint64),
                 ("prefetch_bytes_per_op", C.c_uint64), ("engine_min_bytes", C.c_uint64), ("align", C.c_uint32), ("guard_bytes", C.c_uint32),
                 ("stage_m", C.c_uint32), ("stage_n", C.c_uint32), ("copy_path", C.c_uint32),
+                ("copy_path_in", C.c_uint32),
                 ("copy_workgroups", C.c_uint32), ("copy_workgroups_out", C.c_uint32),
                 ("copy_unroll", C.c_uint32), ("max_ops", C.c_uint32), ("max_events", C.c_uint32),
-                ("flags", C.c_uint32), ("reserved", C.c_uint32), ("reserved2", C.c_uint32 * 2)]
+                ("flags", C.c_uint32), ("reserved", C.c_uint32 * 2)]
 
 
 class ss_scan_result_t(C.Structure):

@@ -25,7 +25,7 @@ constexpr uint32_t kLdsEntries = 8192;   // chunk-prefix entries staged in LDS (
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // kUnroll 16-byte accesses are in flight per lane before the first store is issued.
-template <bool TO_HOST, uint32_t kUnroll, bool kPlain = false>
+template <bool TO_HOST, uint32_t kUnroll>
 __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
     uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
     const uint32_t *__restrict__ chunk0, uint32_t n_desc, uint32_t n_chunks) {
@@ -60,12 +60,12 @@ __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
 #pragma unroll
       for (uint32_t u = 0; u < kUnroll; ++u) {
         const uint32_t i = base + u * SS_COPY_THREADS + tid;
-        if (i < n16) v[u] = kPlain ? src16[i] : __builtin_nontemporal_load(src16 + i);
+        if (i < n16) v[u] = __builtin_nontemporal_load(src16 + i);
       }
 #pragma unroll
       for (uint32_t u = 0; u < kUnroll; ++u) {
         const uint32_t i = base + u * SS_COPY_THREADS + tid;
-        if (i < n16) { if (kPlain) dst16[i] = v[u]; else __builtin_nontemporal_store(v[u], dst16 + i); }
+        if (i < n16) __builtin_nontemporal_store(v[u], dst16 + i);
       }
     }
     const uint32_t tail = n & 15u;          // only the last chunk of a tensor can have one
@@ -94,11 +94,6 @@ void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to
 #define SS_LAUNCH(TH, U)                                                                                  \
   hipLaunchKernelGGL((ss_copy_kernel<TH, U>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, n_desc, \
                      n_chunks)
-  if (unroll == 7) {   // experiment: plain (temporal) loads and stores, 8 in flight
-    if (to_host) hipLaunchKernelGGL((ss_copy_kernel<true, 8, true>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, n_desc, n_chunks);
-    else hipLaunchKernelGGL((ss_copy_kernel<false, 8, true>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, n_desc, n_chunks);
-    return;
-  }
   if (to_host) {
     if (unroll <= 2) SS_LAUNCH(true, 2); else if (unroll <= 4) SS_LAUNCH(true, 4); else SS_LAUNCH(true, 8);
   } else {

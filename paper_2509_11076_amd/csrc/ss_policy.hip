@@ -130,6 +130,17 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
     next_start = start;
     have_next = true;
   }
+  // The swap-in stream is first-in first-out: an item needed later is never issued before one
+  // needed earlier (the release-point floor can otherwise put it ahead in the queue).
+  {
+    uint64_t run = 0;
+    for (auto it = ord.rbegin(); it != ord.rend(); ++it) {     // (t_use, policy index) ascending
+      Live &L = live[*it];
+      if (!L.valid) continue;
+      L.t_in = std::max(L.t_in, run);
+      run = L.t_in;
+    }
+  }
 
   // keep what satisfies t_out <= t_free < t_in <= t_use
   std::vector<uint32_t> kept;        // indices into live

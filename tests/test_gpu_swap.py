@@ -63,6 +63,7 @@ def test_toy_config_round_trip_with_guards_and_poison(P, torch, path, bpo):
     host_arena = arena.cpu().numpy().copy()
     ctx = make_ctx(P, staging_bytes=ora["staging_bytes"], link_bytes_per_op=bpo, guard_bytes=guard,
                    copy_path=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE,
+                   copy_path_in=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE,
                    flags=P.SS_CFG_POISON_FREE | P.SS_CFG_TIMING)
     try:
         P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
@@ -119,7 +120,8 @@ def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
     arena = random_arena(torch, arena_bytes, 7)
     host_arena = arena.cpu().numpy().copy()
     ctx = make_ctx(P, staging_bytes=staging_bytes, align=16,
-                   copy_path=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE)
+                   copy_path=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE,
+                   copy_path_in=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE)
     try:
         P.ss_bind(ctx, arena.data_ptr(), arena_bytes, 0)
         P.ss_load_schedule(ctx, descs, out_start, descs_in, in_start, None)

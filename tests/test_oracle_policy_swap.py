@@ -49,7 +49,24 @@ def test_no_swap_in_is_issued_before_the_last_swap_out():
     # the last swap-out is issued after op 10, so nothing comes in before op 11: X at 11 (LATE),
     # Y cannot come in before its own release + 1 = 12 (LATE).
     t_free, t_in, late, valid = oracle.link_timing([0, 10], [20, 12], [10, 10], 100, bpo_in=1)
-    assert t_free == [1, 11] and t_in == [11, 12] and late == [True, True] and valid == [True, True]
+    assert t_free == [1, 11] and late == [True, True] and valid == [True, True]
+    # ... and X, needed after Y, is not issued ahead of Y in the first-in first-out swap-in stream
+    assert t_in == [12, 12]
+
+
+def test_swap_in_issue_order_follows_order_of_need():
+    # P: out after op 0, used at 30, 10 bytes.  Q: out after op 20 (released after 21), used at 25.
+    # Planned at 1 byte/op the queue wants P at 20, then clamps both to the last swap-out (21);
+    # Q cannot come before 22.  P is needed after Q, so it must not be issued before Q: 22 as well.
+    t_free, t_in, late, valid = oracle.link_timing([0, 20], [30, 25], [10, 10], 100, bpo_in=1)
+    assert t_free == [1, 21] and t_in == [22, 22]
+    tr = W.build_trace(W.config_shape(2))
+    pol = W.config_swap_set(tr, 2)
+    ap = oracle.apply_policy(pol, pol["ref_op"].astype(np.int64), tr.tensors, 13 << 20, keep_late=True,
+                             bpo_in=4 << 20)
+    by_need = sorted((r[7], r[6]) for r in ap["resolved"] if not r[3] & 3)       # (t_use, t_in)
+    assert all(b[1] >= a[1] for a, b in zip(by_need, by_need[1:]))
+    assert oracle.schedule_check(ap, tr.tensors, tr.op_inputs, tr.op_outputs) == []
 
 
 def test_keep_late_executes_the_whole_prescribed_set():

@@ -22,7 +22,7 @@ class SwapRun:
 
     def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
                  copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
-                 policy=None, engine_min_bytes=None, bpo_in=0):
+                 policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None):
         from .compute import SyntheticCompute
         self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
         if trace is not None:
@@ -37,7 +37,10 @@ class SwapRun:
         cfg.link_bytes_per_op = bpo
         cfg.prefetch_bytes_per_op = bpo_in
         cfg.copy_path = copy_path
+        cfg.copy_path_in = copy_path if copy_path_in is None else copy_path_in
         cfg.copy_workgroups = copy_workgroups
+        cfg.copy_workgroups_out = copy_workgroups_out
+        cfg.copy_unroll = copy_unroll
         cfg.flags = flags
         cfg.guard_bytes = guard
         cfg.max_ops = max(65536, tr.n_ops)
