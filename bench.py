@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2])
     ap.add_argument("--path", default="auto", choices=["auto", "kernel", "engine"])
+    ap.add_argument("--path-in", default=None, choices=["auto", "kernel", "engine"],
+                    help="copy path of the swap-in direction (default: same as --path)")
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--bpo", type=int, default=0,
                     help="link model: bytes the link moves per operator; 0 = link peak x no-swap step time / "
@@ -90,7 +92,9 @@ def main():
     from workloads.harness import SwapRun
 
     torch.cuda.set_device(0)
-    path = {"auto": B.SS_PATH_AUTO, "kernel": B.SS_PATH_KERNEL, "engine": B.SS_PATH_ENGINE}[args.path]
+    paths = {"auto": B.SS_PATH_AUTO, "kernel": B.SS_PATH_KERNEL, "engine": B.SS_PATH_ENGINE}
+    path = paths[args.path]
+    path_in = paths[args.path_in or args.path]
 
     # host-link peak, measured now (pinned hipMemcpy; 1 GiB transfers)
     pcfg = B.ss_config_default()
@@ -131,7 +135,7 @@ def main():
     if args.bpo <= 0:
         bpo = max(1, int(link * t_noswap / base_n_ops))
         for _ in range(max(1, args.calibrate)):
-            trial = SwapRun(B, torch, args.config, swap=True, bpo=bpo, bpo_in=bpo_in, copy_path=path,
+            trial = SwapRun(B, torch, args.config, swap=True, bpo=bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
                             copy_workgroups=args.workgroups, flags=flags)
             t_trial = timed(trial, trial.step, 3, 2)
             calib.append({"link_bytes_per_op": bpo, "ms_per_step": round(t_trial * 1e3, 2),
@@ -144,7 +148,7 @@ def main():
                 break
             bpo = nxt
         args.bpo = min(calib, key=lambda c: c["ms_per_step"])["link_bytes_per_op"]
-    run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path,
+    run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
                   copy_workgroups=args.workgroups, flags=flags)
     n_forced, n_dropped_setup = run.n_forced, run.n_dropped
     st0 = None
@@ -181,11 +185,22 @@ def main():
     t_floor = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9), bytes_way / (bw["h2d_gbps"] * 1e9))
     # the last tensors to leave are the first needed back (LIFO), so the two directions hardly overlap:
     t_floor_serial = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9) + bytes_way / (bw["h2d_gbps"] * 1e9))
-    n_launch = len(out_ms) + len(in_ms)
-    avg_launch_ms = (sum(out_ms) + sum(in_ms)) / n_launch
-    bytes_per_launch = 2 * bytes_way * args.steps / n_launch
-    link_achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    # roofline of the copy kernel: only the launches that really were kernel launches
+    n_out_l, n_in_l = len(out_ms), len(in_ms)
+    out_by_kernel = path != B.SS_PATH_ENGINE                      # AUTO sends swap-outs to the kernel
+    engine_in = engine_batches - (0 if out_by_kernel else n_out_l)
+    in_by_kernel = engine_in == 0                                 # a mix of paths is left out of the figure
+    k_ms = (out_ms if out_by_kernel else []) + (in_ms if in_by_kernel else [])
+    k_bytes = bytes_way * args.steps * (int(out_by_kernel) + int(in_by_kernel))
+    if k_ms:
+        avg_launch_ms = sum(k_ms) / len(k_ms)
+        bytes_per_launch = k_bytes / len(k_ms)
+        link_achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    else:
+        avg_launch_ms = bytes_per_launch = link_achieved = 0.0
     link_peak = max(bw["d2h_gbps"], bw["h2d_gbps"])
+    which = ("pack launches (swap-out)" if out_by_kernel else "") + \
+            (" and " if out_by_kernel and in_by_kernel else "") + ("unpack launches (swap-in)" if in_by_kernel else "")
     line = {
         "metric": "swap GB/s (D2H+H2D) as % of host-link peak; step-time overhead vs no-swap",
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -196,7 +211,8 @@ def main():
                    if args.config == 2 else "config 1: toy 2-layer block, layer-0 activations swapped",
                    "ops_per_step": n_ops, "tensors_swapped": int(applied["n_kept"]),
                    "bytes_each_way": bytes_way, "out_batches": int(applied["n_out_batches"]),
-                   "in_batches": int(applied["n_in_batches"]), "copy_path": args.path,
+                   "in_batches": int(applied["n_in_batches"]), "copy_path_out": args.path,
+                   "copy_path_in": args.path_in or args.path,
                    "kernel_launches": int(kernel_batches), "engine_batches": int(engine_batches),
                    "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "policy_mode": args.policy_mode,
                    "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),
@@ -216,8 +232,9 @@ def main():
                       "overhead_vs_floor_out_then_in_pct": round(100 * (t_step / t_floor_serial - 1), 1)},
         "roofline": {"bound": "host_link", "achieved": round(link_achieved, 2), "peak": round(link_peak, 2),
                      "unit": "GB/s", "frac": round(link_achieved / link_peak, 4), "traffic": None,
-                     "kernel": "ss_copy_kernel (pack and unpack launches)",
+                     "kernel": "ss_copy_kernel, " + (which or "no kernel launches in this run"),
                      "avg_launch_ms": round(avg_launch_ms, 4), "bytes_per_launch": int(bytes_per_launch),
+                     "launches_timed": len(k_ms),
                      "hbm": {"achieved": round(link_achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                              "frac": round(link_achieved / HBM_PEAK_GBPS, 5)}},
     }
