@@ -25,6 +25,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# Memory traffic of one pack launch over its algorithmic bytes (read from HBM + written to the
+# host), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy of known size
+# (profiles/ss_copy_kernel_config2_hbm_traffic.md).
+PACK_TRAFFIC_RATIO = 1.013
 
 
 def cpu_baseline(cfgno, bpo):
@@ -80,6 +84,10 @@ def main():
                          "backward use are dropped")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--swap-only", action="store_true",
+                    help="counter-collection mode: the same swap schedule without the compute stream's work, "
+                         "no baseline, no link-model fitting (keeps a rocprofv3 --pmc run short)")
+    ap.add_argument("--probe-reps", type=int, default=10)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the swap executor has no inter-GPU step); "
@@ -101,8 +109,26 @@ def main():
     pcfg.staging_bytes = 4096
     pcfg.copy_workgroups = args.workgroups
     pctx = B.ss_create(pcfg)
-    bw = B.ss_bw_probe(pctx, 1 << 30, 10)
+    bw = B.ss_bw_probe(pctx, 1 << 30, args.probe_reps)
     B.ss_destroy(pctx)
+    print("link probe done", file=sys.stderr, flush=True)
+
+    if args.swap_only:
+        run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo if args.bpo > 0 else 10 << 20,
+                      bpo_in=4 << 20, copy_path=path, copy_path_in=path_in, copy_workgroups=args.workgroups,
+                      flags=B.SS_CFG_TIMING | B.SS_CFG_KEEP_LATE, compute=False)
+        for _ in range(args.warmup + args.steps):
+            run.step()
+            print("swap-only step done", file=sys.stderr, flush=True)
+        torch.cuda.synchronize()
+        nob = run.last["applied"]["n_out_batches"]
+        out_ms = [B.ss_batch_ms(run.ctx, 0, b)[0] for b in range(nob)]
+        print(json.dumps({"mode": "swap-only", "bytes_each_way": run.bytes_each_way, "out_batches": int(nob),
+                          "in_batches": int(run.last["applied"]["n_in_batches"]),
+                          "avg_pack_launch_ms": round(sum(out_ms) / len(out_ms), 4),
+                          "bytes_per_pack_launch": run.bytes_each_way // nob}), flush=True)
+        run.close()
+        return
 
     def timed(run, fn, steps, warmup):
         for _ in range(warmup):
@@ -121,6 +147,7 @@ def main():
     base.close()
     del base
     torch.cuda.empty_cache()
+    print("no-swap baseline done: %.1f ms/step" % (t_noswap * 1e3), file=sys.stderr, flush=True)
 
     # Link model.  Eq. 1 spreads the measured iteration time evenly over the operators and Eq. 3
     # turns bytes into time, so bytes-per-operator = link peak x iteration time / operators.  The
@@ -140,6 +167,7 @@ def main():
             t_trial = timed(trial, trial.step, 3, 2)
             calib.append({"link_bytes_per_op": bpo, "ms_per_step": round(t_trial * 1e3, 2),
                           "forced": trial.n_forced, "dropped": trial.n_dropped})
+            print("link-model fit: %d bytes/op -> %.1f ms/step" % (bpo, t_trial * 1e3), file=sys.stderr, flush=True)
             trial.close()
             del trial
             torch.cuda.empty_cache()
@@ -231,7 +259,9 @@ def main():
                       "floor_out_then_in_ms": round(t_floor_serial * 1e3, 3),
                       "overhead_vs_floor_out_then_in_pct": round(100 * (t_step / t_floor_serial - 1), 1)},
         "roofline": {"bound": "host_link", "achieved": round(link_achieved, 2), "peak": round(link_peak, 2),
-                     "unit": "GB/s", "frac": round(link_achieved / link_peak, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(link_achieved / link_peak, 4),
+                     "traffic": int(PACK_TRAFFIC_RATIO * 2 * bytes_per_launch) if out_by_kernel else None,
+                     "traffic_note": "bytes per launch at the L2 (HBM read + host write), algorithmic = 2 x bytes_per_launch",
                      "kernel": "ss_copy_kernel, " + (which or "no kernel launches in this run"),
                      "avg_launch_ms": round(avg_launch_ms, 4), "bytes_per_launch": int(bytes_per_launch),
                      "launches_timed": len(k_ms),
