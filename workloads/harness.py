@@ -131,3 +131,108 @@ class SwapRun:
         comp = self.compute
         for i in range(self.tr.n_ops):
             comp.run_op(i)
+
+
+class VaryingRun:
+    """Configuration 4: the operator sequence changes every iteration; the policy made for
+    iteration 0 is re-anchored online, topped up if it no longer fits the budget, and executed.
+
+    One planning context (no staging, never bound) holds the intern table and the stage machine;
+    one executing context holds the staging area and is re-bound to the arena every iteration.
+    """
+
+    def __init__(self, B, torch, shape, budget, bpo, bpo_in=0, min_bytes=0, perturb=None, seed=2509,
+                 flags=0, compute=True, gemm_scale=1.0, arena_slack=1.25, staging_slack=1.4):
+        self.B, self.torch, self.shape = B, torch, shape
+        self.budget, self.min_bytes, self.perturb, self.seed = budget, min_bytes, perturb, seed
+        self.do_compute, self.gemm_scale = compute, gemm_scale
+        cfg = B.ss_config_default()
+        cfg.link_bytes_per_op = bpo
+        cfg.prefetch_bytes_per_op = bpo_in
+        cfg.flags = flags
+        cfg.staging_bytes = 0
+        self.cfg = cfg
+        self.plan_ctx = B.ss_create(cfg)
+        tr0 = T.build_trace(shape, seed=seed, iteration=0)
+        self.ref_ops = self.intern(tr0)
+        pol, _ = B.ss_greedy_policy(self.plan_ctx, tr0.tensors, tr0.events, tr0.n_ops, 0, budget, min_bytes)
+        self.ref_policy = pol
+        self.anchors = np.zeros(len(pol), dtype=ANCHOR_DT)
+        self.anchors["ref_op"] = pol["ref_op"]; self.anchors["out_slot"] = pol["out_slot"]
+        ap = B.ss_apply_policy(self.plan_ctx, pol, pol["ref_op"].astype(np.int32), tr0.tensors, allow_nomem=True)
+        cfg2 = B.ss_config_default()
+        for f, _t in cfg._fields_:
+            setattr(cfg2, f, getattr(cfg, f))
+        cfg2.staging_bytes = int(ap["staging_bytes"] * staging_slack) + (1 << 20)
+        self.exec_ctx = B.ss_create(cfg2) if compute else None      # planning alone needs no staging
+        self.staging_bytes = cfg2.staging_bytes
+        self.arena = None
+        self.arena_cap = int(budget * arena_slack)
+        if compute:
+            self.arena = torch.empty(self.arena_cap, dtype=torch.uint8, device="cuda")
+        self.stream = torch.cuda.current_stream()
+
+    def intern(self, tr):
+        B = self.B
+        if tr.n_ops == 0:
+            return np.zeros(0, B.OP_DT)
+        return np.stack([B.ss_intern_op(self.plan_ctx, tr.op_name[i], tr.op_stack[i], tr.op_dtype[i],
+                                        len(tr.op_outputs[i]), tr.op_phase[i]) for i in range(tr.n_ops)])
+
+    def close(self):
+        for c in (self.plan_ctx, self.exec_ctx):
+            if c is not None:
+                self.B.ss_destroy(c)
+        self.plan_ctx = self.exec_ctx = None
+        self.arena = None
+
+    def plan(self, it):
+        """trace of iteration `it`, re-anchored policy, top-up; returns everything a checker needs"""
+        B = self.B
+        tr = T.build_trace(self.shape, seed=self.seed, iteration=it, perturb=self.perturb if it else None)
+        ops = self.intern(tr)
+        m = B.ss_match_sequence(self.plan_ctx, self.ref_ops, ops, self.anchors, flags=B.SS_MATCH_STEP_STAGE)
+        ap = B.ss_apply_policy(self.plan_ctx, self.ref_policy, m["new_idx"], tr.tensors, allow_nomem=True)
+        sc = B.ss_timeline_scan(self.plan_ctx, tr.events, ap["policy_events"], tr.n_ops, 0, self.budget,
+                                want_per_op=False)
+        # the kept items in this iteration's coordinates
+        res = ap["resolved"]
+        kept = (res["flags"] & (B.SS_F_UNMATCHED | B.SS_F_ORDER)) == 0
+        cur = res[kept].copy()
+        cur["ref_op"] = m["new_idx"][kept]
+        cur["flags"] = 0
+        cur["t_out"] = cur["t_free"] = cur["t_in"] = cur["t_use"] = 0
+        topped = 0
+        final = cur
+        if sc["peak"] > self.budget:
+            final, _ = B.ss_greedy_policy(self.plan_ctx, tr.tensors, tr.events, tr.n_ops, 0, self.budget,
+                                          self.min_bytes, initial=cur)
+            topped = len(final) - len(cur)
+        ap2 = B.ss_apply_policy(self.plan_ctx, final, final["ref_op"].astype(np.int32), tr.tensors,
+                                allow_nomem=True)
+        sc2 = B.ss_timeline_scan(self.plan_ctx, tr.events, ap2["policy_events"], tr.n_ops, 0, self.budget,
+                                 want_per_op=False)
+        return dict(trace=tr, ops=ops, match=m, applied_ref=ap, scan_ref=sc, carried=cur, final=final,
+                    topped=topped, applied=ap2, scan=sc2)
+
+    def execute(self, p):
+        """place this iteration's tensors, bind, load the schedule, run the operators with swapping"""
+        from .compute import SyntheticCompute
+        from paper_2509_11076_amd.executor import run_iteration, batch_lists
+        B, tr = self.B, p["trace"]
+        res = p["applied"]["resolved"]
+        kept = (res["flags"] & (B.SS_F_UNMATCHED | B.SS_F_ORDER)) == 0
+        swapped = {int(r["tensor_id"]): (int(r["t_free"]), int(r["t_in"])) for r in res[kept]}
+        used = place_tensors(tr.tensors, swapped=swapped, capacity=self.arena_cap)
+        B.ss_bind(self.exec_ctx, self.arena.data_ptr(), self.arena_cap, self.stream.cuda_stream)
+        ap = B.ss_apply_policy(self.exec_ctx, p["final"], p["final"]["ref_op"].astype(np.int32), tr.tensors)
+        comp = SyntheticCompute(tr, self.arena, seed=self.seed, gemm_scale=self.gemm_scale)
+        comp.mark_swapped(swapped.keys())
+        rec = B.ss_trace_record_prepared(self.exec_ctx, p["ops"], tr.events)
+        B.ss_trace_begin(self.exec_ctx)
+
+        def run_op(i):
+            rec(i)
+            comp.run_op(i)
+        run_iteration(self.exec_ctx, tr.n_ops, ap["actions"], run_op, batch_lists(ap["actions"]))
+        return comp.result(), used, ap
