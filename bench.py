@@ -70,7 +70,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2])
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 5],
+                    help="2 is the headline workload; 1, 3, 5 report the other fixed-sequence configurations")
     ap.add_argument("--path", default="auto", choices=["auto", "kernel", "engine"])
     ap.add_argument("--path-in", default=None, choices=["auto", "kernel", "engine"],
                     help="copy path of the swap-in direction (default: same as --path)")
@@ -140,14 +141,27 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    extra = {}
+    if args.config == 3:       # 7B shape under a 48 GB budget: greedy policy, link share fixed so that it fits
+        extra = dict(budget=48 * 10**9, min_bytes=1 << 20)
+        if args.bpo <= 0:
+            args.bpo = 256 << 20
+    has_compute = args.config != 5
+    if args.config == 5:       # small-tensor stress: no model around it
+        extra = dict(compute=False)
+        if args.bpo <= 0:
+            args.bpo = 256 << 20
     # the same step without any swapping
-    base = SwapRun(B, torch, args.config, swap=False)
-    t_noswap = timed(base, base.step_noswap, args.steps, args.warmup)
-    base_n_ops = base.tr.n_ops
-    base.close()
-    del base
-    torch.cuda.empty_cache()
-    print("no-swap baseline done: %.1f ms/step" % (t_noswap * 1e3), file=sys.stderr, flush=True)
+    if has_compute:
+        base = SwapRun(B, torch, args.config, swap=False)
+        t_noswap = timed(base, base.step_noswap, args.steps, args.warmup)
+        base_n_ops = base.tr.n_ops
+        base.close()
+        del base
+        torch.cuda.empty_cache()
+        print("no-swap baseline done: %.1f ms/step" % (t_noswap * 1e3), file=sys.stderr, flush=True)
+    else:
+        t_noswap, base_n_ops = 1e-9, 1
 
     # Link model.  Eq. 1 spreads the measured iteration time evenly over the operators and Eq. 3
     # turns bytes into time, so bytes-per-operator = link peak x iteration time / operators.  The
@@ -158,7 +172,7 @@ def main():
     link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
     calib = []
     # the swap-in queue is planned with the no-swap operator time: operators never run faster than that
-    bpo_in = max(1, int(link * t_noswap / base_n_ops))
+    bpo_in = max(1, int(link * t_noswap / base_n_ops)) if args.config in (1, 2) else 0
     if args.bpo <= 0:
         bpo = max(1, int(link * t_noswap / base_n_ops))
         for _ in range(max(1, args.calibrate)):
@@ -177,7 +191,7 @@ def main():
             bpo = nxt
         args.bpo = min(calib, key=lambda c: c["ms_per_step"])["link_bytes_per_op"]
     run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
-                  copy_workgroups=args.workgroups, flags=flags)
+                  copy_workgroups=args.workgroups, flags=flags, **extra)
     n_forced, n_dropped_setup = run.n_forced, run.n_dropped
     st0 = None
     for _ in range(args.warmup):
@@ -234,9 +248,14 @@ def main():
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(t_step * 1e3, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": "config 2: 1.3B-shape decoder (hidden 2048, 24 layers, seq 2048, mb 1, bf16), "
-                               "activations of every other layer swapped, synthetic bf16 GEMMs on the compute stream"
-                   if args.config == 2 else "config 1: toy 2-layer block, layer-0 activations swapped",
+        "config": {"workload": {
+            1: "config 1: toy 2-layer block, layer-0 activations swapped",
+            2: "config 2: 1.3B-shape decoder (hidden 2048, 24 layers, seq 2048, mb 1, bf16), "
+               "activations of every other layer swapped, synthetic bf16 GEMMs on the compute stream",
+            3: "config 3: 7B-shape decoder (hidden 4096, 32 layers, seq 4096, mb 1, bf16), 97 GiB of activations "
+               "under a 48 GB budget, longest-idle-first policy, synthetic bf16 GEMMs on the compute stream",
+            5: "config 5: 20,000 tensors of 4 KiB..4 MiB at random places of a 64 GB arena, two random orders, "
+               "no compute stream work"}[args.config],
                    "ops_per_step": n_ops, "tensors_swapped": int(applied["n_kept"]),
                    "bytes_each_way": bytes_way, "out_batches": int(applied["n_out_batches"]),
                    "in_batches": int(applied["n_in_batches"]), "copy_path_out": args.path,
@@ -268,7 +287,10 @@ def main():
                      "hbm": {"achieved": round(link_achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                              "frac": round(link_achieved / HBM_PEAK_GBPS, 5)}},
     }
-    if not args.no_cpu_baseline:
+    if not has_compute:
+        for k in ("noswap_ms", "overhead_vs_noswap_pct", "floor_ms", "overhead_vs_floor_pct"):
+            line["step_time"][k] = None
+    if not args.no_cpu_baseline and args.config in (1, 2):
         line["cpu_baseline"] = cpu_baseline(args.config, args.bpo)
     print(json.dumps(line), flush=True)
 
