@@ -217,6 +217,9 @@ def main():
     kernel_batches = st1["kernel_batches"] - st0["kernel_batches"]
     engine_batches = st1["engine_batches"] - st0["engine_batches"]
     n_ops = run.tr.n_ops
+    hl = run.host_ms_log[-args.steps:]
+    trace_work = {k: round(sum(h[k] for h in hl) / len(hl), 3) for k in ("match", "apply", "scan")}
+    n_events = len(run.tr.events)
     run.close()
 
     value = 2 * bytes_way / t_step / 1e9
@@ -264,6 +267,9 @@ def main():
                    "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "policy_mode": args.policy_mode,
                    "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),
                    "stage": int(match["stage"]), "anchors_unmatched": int(match["n_unmatched"])},
+        "trace_work_host_ms_per_step": dict(trace_work, note="wall time of the call incl. host<->device copies and "
+                                            "synchronisation; %d operators, %d events, %d anchors"
+                                            % (n_ops, n_events, int(applied["n_kept"]) + n_dropped_setup)),
         "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
         "pct_of_link_peak": {
             "d2h_while_copying": round(100 * d2h_busy / bw["d2h_gbps"], 1),

@@ -92,6 +92,7 @@ class SwapRun:
         self.ref_ops = self.ops.copy()
         self.bytes_each_way = int(ap["bytes_out"])
         self.last = {}
+        self.host_ms_log = []
 
     def close(self):
         if self.ctx is not None:
@@ -103,12 +104,18 @@ class SwapRun:
     def plan(self):
         """per-iteration trace work before the operators run: match (a3), apply (a4), scan (a2)"""
         B, tr = self.B, self.tr
+        t0 = time.perf_counter()
         m = B.ss_match_sequence(self.ctx, self.ref_ops, self.ops, self.anchors, flags=B.SS_MATCH_STEP_STAGE)
+        t1 = time.perf_counter()
         ap = B.ss_apply_policy(self.ctx, self.policy, m["new_idx"], tr.tensors)
+        t2 = time.perf_counter()
         sc = B.ss_timeline_scan(self.ctx, tr.events, ap["policy_events"], tr.n_ops, 0, self.budget,
                                 want_timeline=False, want_per_op=False)
+        t3 = time.perf_counter()
         from paper_2509_11076_amd.executor import batch_lists
-        self.last = dict(match=m, applied=ap, scan=sc, lists=batch_lists(ap["actions"]))
+        self.last = dict(match=m, applied=ap, scan=sc, lists=batch_lists(ap["actions"]),
+                         host_ms=dict(match=(t1 - t0) * 1e3, apply=(t2 - t1) * 1e3, scan=(t3 - t2) * 1e3))
+        self.host_ms_log.append(self.last["host_ms"])
         return self.last
 
     def step(self):
