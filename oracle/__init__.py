@@ -31,6 +31,9 @@ What the paper fixes and what is this build's reading of it:
                     fits).  PARITY UNPINNED against the paper; pinned by brute
                     force on tiny traces.
 * swap_out/in     - Sec. 1, 5.2: bytes leave and return unchanged.
+* generate_policy - Sec. 4 (Eq. 1-3, Algo. 2): logical layers, MRL, candidate list, simulator.
+                    PARITY UNPINNED against the paper (no worked example in it); pinned by
+                    hand-worked cases, invariants and brute force.
 """
 from .trace import fnv1a32, make_sig, TraceRecorder
 from .timeline import timeline_scan
@@ -39,3 +42,4 @@ from .policy import (link_timing, apply_policy, greedy_policy, schedule_check,
                      K_IN, K_WAIT_IN, K_OUT, K_FREE,
                      F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED, F_FORCED, Infeasible)
 from .swap import swap_out, swap_in, SparseArena
+from .generator import generate_policy, logical_layers

@@ -111,7 +111,8 @@ def link_timing(t_out, t_use, nbytes, bpo, keep_late=False, bpo_in=None):
     return t_free, t_in, late, valid
 
 
-def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0, keep_late=False, bpo_in=None):
+def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0, keep_late=False, bpo_in=None,
+                 policy_points=False):
     """Turn a policy plus this iteration's tensor table into the action schedule.
 
     policy rows: ref_op, out_slot, tensor_id, flags, t_out, t_free, t_in, t_use, nbytes
@@ -152,7 +153,28 @@ def apply_policy(policy, new_idx, tensors, bpo, align=256, guard=0, keep_late=Fa
     t_out = [int(tensors[cur[a]]["last_fwd_use"]) for a in live]
     t_use = [int(tensors[cur[a]]["first_bwd_use"]) for a in live]
     nb = [int(tensors[cur[a]]["nbytes"]) for a in live]
-    if keep_late:
+    if policy_points:
+        # the generator already fixed release and pre-trigger points (Sec. 4.3, 4.4): keep them, moved
+        # along with the tensor's own last forward use / first backward use in this iteration
+        t_free, t_in, late, valid, forced = [], [], [], [], []
+        for pos, a in enumerate(live):
+            p = policy[a]
+            tf = int(p["t_free"]) + t_out[pos] - int(p["t_out"])
+            ti = int(p["t_in"]) + t_use[pos] - int(p["t_use"])
+            ok = t_out[pos] <= tf < ti <= t_use[pos]
+            fz = False
+            if not ok and keep_late:
+                tf = min(max(tf, t_out[pos]), t_use[pos] - 1)
+                ti = min(max(ti, tf + 1), t_use[pos])
+                ok, fz = True, True
+            t_free.append(tf); t_in.append(ti); valid.append(ok); forced.append(fz)
+            late.append(bool(int(p["flags"]) & F_LATE) or fz)
+        run = 0                                  # first-in first-out order of need, as in link_timing
+        for pos in sorted(range(len(live)), key=lambda q: (t_use[q], live[q])):
+            if valid[pos]:
+                t_in[pos] = max(t_in[pos], run)
+                run = t_in[pos]
+    elif keep_late:
         t_free, t_in, late, valid, forced = link_timing(t_out, t_use, nb, bpo, keep_late=True, bpo_in=bpo_in)
     else:
         t_free, t_in, late, valid = link_timing(t_out, t_use, nb, bpo, bpo_in=bpo_in)

@@ -5,7 +5,6 @@
 // by making the compute stream wait on the device instead of polling events on
 // the host).
 #include <algorithm>
-#include <chrono>
 #include <cstring>
 
 #include "ss_internal.h"
@@ -90,13 +89,11 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
   ctx->cfg = cfg;
   std::memset(&ctx->stats, 0, sizeof(ctx->stats));
   int rc = SS_OK;
-  int fail_line = 0;
   auto fail_at = [&](int code, hipError_t e, int line) {
     ctx->stats.last_hip_error = (int32_t)e;
     ss_note_hip_error((int)e, __FILE__, line);
     (void)hipGetLastError();
     rc = code;
-    fail_line = line;
   };
 #define fail(code, e) fail_at(code, e, __LINE__)
   hipError_t e;
