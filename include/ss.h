@@ -106,8 +106,12 @@ enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch
        SS_CFG_KEEP_LATE = 4,     /* keep items whose swap-out cannot finish before their first
                                     backward use (released and re-fetched around that use, the
                                     compute stream waiting) instead of dropping them            */
-       SS_CFG_SYSTEM_FENCE = 8 };/* ordering events carry a system-scope fence (default: device
+       SS_CFG_SYSTEM_FENCE = 8,  /* ordering events carry a system-scope fence (default: device
                                     scope; the host reads staging only after a synchronisation) */
+       SS_CFG_POLICY_POINTS = 16 };/* ss_apply_policy keeps each item's own t_free / t_in (as made by
+                                    ss_generate_policy), moved along with the tensor's last forward /
+                                    first backward use, instead of re-timing with the link model  */
+
 typedef struct {
   uint64_t staging_bytes;     /* pinned host staging to allocate at ss_create                */
   uint64_t link_bytes_per_op; /* link model: bytes the host link moves during one operator
@@ -300,6 +304,40 @@ int ss_greedy_policy(ss_ctx *ctx, const ss_tensor_t *tensors, uint32_t n_tensors
                      uint64_t n_ev, uint32_t n_ops, int64_t base, int64_t budget, uint64_t min_bytes,
                      const ss_policy_item_t *initial, uint32_t n_initial,
                      ss_policy_item_t *policy_out, uint32_t *n_policy, int64_t *peak_out);
+
+/* ---- policy generator (Sec. 4: Eq. 1-3, Algo. 2) ---------------------------------- */
+
+typedef struct {
+  uint32_t g_fwd, g_bwd;  /* number of logical layers the forward / backward operators are cut into */
+  uint32_t c_num, c_den;  /* C of Eq. 2 as a fraction                                               */
+  uint64_t min_bytes;     /* tensors smaller than this are never candidates                         */
+} ss_gen_params_t;
+
+typedef struct {
+  int64_t peak_no_swap;        /* timeline scan without a policy                                    */
+  int64_t peak_with_policy;    /* timeline scan with the generated policy's own points              */
+  uint32_t n_over_with_policy; /* operators still above the limit under that scan                   */
+  uint32_t n_rounds;           /* passes of the Algo. 2 loop                                        */
+  uint32_t n_items, n_late;
+  uint64_t bytes;              /* sum of nbytes of the items                                        */
+} ss_gen_result_t;
+
+/* Generate a swap policy as Sec. 4 describes.  The memory without swaps comes from a timeline scan
+ * of `ev`; every operator above `limit` gets a memory reduction entry; candidates (kept from
+ * forward to backward, >= min_bytes, spanning at least one entry) are ranked by Eq. 2; the simulator
+ * places each swap-in in a logical layer before the first backward use that still has time left
+ * (Eq. 1 gives a layer link_bytes_per_op x its operator count, Eq. 3 makes a transfer cost its
+ * size), never back into the peak period, subtracts the tensor from the entries it covers, and
+ * repeats until no entry is left (SS_E_INFEASIBLE when candidates run out first); finally every
+ * swap-out is given the first layer with time left from its last forward use on, which fixes the
+ * release point.  Operator phases are read from ops[].sig >> 16.
+ * policy_out receives the items in the order they were committed, with t_out, t_free, t_in, t_use
+ * filled (use SS_CFG_POLICY_POINTS to have ss_apply_policy keep them); in: capacity *n_policy,
+ * out: count.  All arrays are host memory. */
+int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
+                       uint32_t n_tensors, const ss_event_t *ev, uint64_t n_ev, int64_t base, int64_t limit,
+                       const ss_gen_params_t *params, ss_policy_item_t *policy_out, uint32_t *n_policy,
+                       ss_gen_result_t *res /* host, out */);
 
 /* ---- a5 / a6 / a7: swap-out, swap-in, release and wait (Sec. 5.2) --------------- */
 

@@ -40,7 +40,7 @@ SS_OK = 0
  SS_E_STATE, SS_E_CAPACITY) = range(-1, -10, -1)
 SS_ACT_IN, SS_ACT_WAIT_IN, SS_ACT_OUT, SS_ACT_FREE = 0, 1, 2, 3
 SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE = 0, 1, 2
-SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE = 1, 2, 4, 8
+SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE, SS_CFG_POLICY_POINTS = 1, 2, 4, 8, 16
 SS_SYNC_FREE, SS_SYNC_WAIT_IN, SS_SYNC_DRAIN = 0, 1, 2
 SS_MATCH_STEP_STAGE, SS_MATCH_HISTOGRAM = 1, 2
 SS_STAGE_WARMUP, SS_STAGE_GENPOLICY, SS_STAGE_STABLE = 0, 1, 2
@@ -72,6 +72,17 @@ class ss_apply_result_t(C.Structure):
     _fields_ = [("staging_bytes", C.c_uint64), ("bytes_out", C.c_uint64), ("n_kept", C.c_uint32),
                 ("n_dropped", C.c_uint32), ("n_late", C.c_uint32), ("n_out_batches", C.c_uint32),
                 ("n_in_batches", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class ss_gen_params_t(C.Structure):
+    _fields_ = [("g_fwd", C.c_uint32), ("g_bwd", C.c_uint32), ("c_num", C.c_uint32), ("c_den", C.c_uint32),
+                ("min_bytes", C.c_uint64)]
+
+
+class ss_gen_result_t(C.Structure):
+    _fields_ = [("peak_no_swap", C.c_int64), ("peak_with_policy", C.c_int64),
+                ("n_over_with_policy", C.c_uint32), ("n_rounds", C.c_uint32), ("n_items", C.c_uint32),
+                ("n_late", C.c_uint32), ("bytes", C.c_uint64)]
 
 
 class ss_stats_t(C.Structure):
@@ -121,6 +132,8 @@ _SIGS = {
     "ss_load_schedule": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P],
     "ss_greedy_policy": [_P, _P, C.c_uint32, _P, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_uint64,
                          _P, C.c_uint32, _P, C.POINTER(C.c_uint32), C.POINTER(C.c_int64)],
+    "ss_generate_policy": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint64, C.c_int64, C.c_int64,
+                           C.POINTER(ss_gen_params_t), _P, C.POINTER(C.c_uint32), C.POINTER(ss_gen_result_t)],
     "ss_swap_out": [_P, C.c_uint32],
     "ss_swap_in": [_P, C.c_uint32],
     "ss_sync": [_P, C.c_uint32, C.c_uint32],
@@ -333,6 +346,20 @@ def ss_greedy_policy(ctx, tensors, events, n_ops, base, budget, min_bytes=0, ini
                               int(min_bytes), _ptr(ini), 0 if ini is None else len(ini), _ptr(out),
                               C.byref(n), C.byref(peak)), "ss_greedy_policy")
     return out[:n.value], peak.value
+
+
+def ss_generate_policy(ctx, ops, tensors, events, base, limit, g_fwd, g_bwd, c_num=1, c_den=1, min_bytes=0):
+    ops = _arr(ops, OP_DT)
+    tab = _arr(tensors, TENSOR_DT)
+    ev = _arr(events, EVENT_DT)
+    prm = ss_gen_params_t(int(g_fwd), int(g_bwd), int(c_num), int(c_den), int(min_bytes))
+    out = np.zeros(len(tab), dtype=POLICY_DT)
+    n = C.c_uint32(len(out))
+    res = ss_gen_result_t()
+    _ck(_lib.ss_generate_policy(ctx, _ptr(ops), len(ops), _ptr(tab), len(tab), _ptr(ev), len(ev), int(base),
+                                int(limit), C.byref(prm), _ptr(out), C.byref(n), C.byref(res)),
+        "ss_generate_policy")
+    return out[:n.value], {f: getattr(res, f) for f, _ in ss_gen_result_t._fields_}
 
 
 def ss_swap_out(ctx, batch):

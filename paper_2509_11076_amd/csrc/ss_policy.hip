@@ -79,66 +79,99 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
     live.push_back(L);
   }
 
-  // swap-out queue: FIFO in (t_out, policy index) order
-  std::vector<uint32_t> ord(live.size());
-  std::iota(ord.begin(), ord.end(), 0u);
-  std::sort(ord.begin(), ord.end(), [&](uint32_t x, uint32_t y) {
-    return live[x].t_out != live[y].t_out ? live[x].t_out < live[y].t_out : live[x].a < live[y].a;
-  });
-  uint64_t link_free = 0;
-  for (uint32_t i : ord) {
-    Live &L = live[i];
-    const uint64_t ready = (L.t_out + 1) * bpo;
-    const uint64_t start = std::max(ready, link_free);
-    const uint64_t end = start + L.nbytes;
-    if (end >= (1ull << 62)) return SS_E_INVAL;
-    link_free = end;
-    L.t_free = (end - 1) / bpo;          // the operator running when the last byte lands
-    if (!(L.t_free < L.t_use)) {
-      if (cfg.flags & SS_CFG_KEEP_LATE) {      // must be executed anyway: released and re-fetched around its use
-        L.t_free = L.t_use - 1;
+  if (cfg.flags & SS_CFG_POLICY_POINTS) {
+    // The generator already fixed release and pre-trigger points (Sec. 4.3, 4.4): keep them, moved
+    // along with the tensor's own last forward use / first backward use in this iteration.
+    for (Live &L : live) {
+      const ss_policy_item_t &p = policy[L.a];
+      int64_t tf = (int64_t)p.t_free + (int64_t)L.t_out - (int64_t)p.t_out;
+      int64_t ti = (int64_t)p.t_in + (int64_t)L.t_use - (int64_t)p.t_use;
+      bool ok = (int64_t)L.t_out <= tf && tf < ti && ti <= (int64_t)L.t_use;
+      if (!ok && (cfg.flags & SS_CFG_KEEP_LATE)) {
+        tf = std::min(std::max(tf, (int64_t)L.t_out), (int64_t)L.t_use - 1);
+        ti = std::min(std::max(ti, tf + 1), (int64_t)L.t_use);
+        ok = true;
         L.forced = true;
-      } else {
-        L.valid = false;                       // saves no memory: dropped
       }
+      L.valid = ok;
+      L.t_free = ok ? (uint64_t)tf : 0;
+      L.t_in = ok ? (uint64_t)ti : 0;
+      L.late = (p.flags & SS_F_LATE) != 0 || L.forced;
     }
-  }
-  // swap-in queue: as late as possible, walking (t_use, policy index) downwards
-  std::sort(ord.begin(), ord.end(), [&](uint32_t x, uint32_t y) {
-    return live[x].t_use != live[y].t_use ? live[x].t_use > live[y].t_use : live[x].a > live[y].a;
-  });
-  // No swap-in is issued before the last swap-out has been issued: until then memory is still
-  // climbing to its peak and a swap-in would only fight the swap-outs for the link (Sec. 4.3.1:
-  // the search for a swap-in slot does not go back beyond the peak-memory period).
-  uint64_t t_peak = 0;
-  for (const Live &L : live)
-    if (L.valid) t_peak = std::max(t_peak, L.t_out + 1);
-  bool have_next = false;
-  int64_t next_start = 0;
-  for (uint32_t i : ord) {
-    Live &L = live[i];
-    if (!L.valid) continue;
-    int64_t end = (int64_t)(L.t_use * bpo_in);
-    if (have_next && next_start < end) end = next_start;
-    int64_t start = end - (int64_t)L.nbytes;
-    const int64_t floor_ = (int64_t)(std::max(L.t_free + 1, t_peak) * bpo_in);
-    if (start < floor_) {
-      start = floor_;
-      L.late = true;
-    }
-    L.t_in = (uint64_t)start / bpo_in;
-    next_start = start;
-    have_next = true;
-  }
-  // The swap-in stream is first-in first-out: an item needed later is never issued before one
-  // needed earlier (the release-point floor can otherwise put it ahead in the queue).
-  {
-    uint64_t run = 0;
-    for (auto it = ord.rbegin(); it != ord.rend(); ++it) {     // (t_use, policy index) ascending
-      Live &L = live[*it];
+    std::vector<uint32_t> need(live.size());
+    std::iota(need.begin(), need.end(), 0u);
+    std::sort(need.begin(), need.end(), [&](uint32_t x, uint32_t y) {
+      return live[x].t_use != live[y].t_use ? live[x].t_use < live[y].t_use : live[x].a < live[y].a;
+    });
+    uint64_t run = 0;                              // first-in first-out order of need
+    for (uint32_t i : need) {
+      Live &L = live[i];
       if (!L.valid) continue;
       L.t_in = std::max(L.t_in, run);
       run = L.t_in;
+    }
+  } else {
+    // swap-out queue: FIFO in (t_out, policy index) order
+    std::vector<uint32_t> ord(live.size());
+    std::iota(ord.begin(), ord.end(), 0u);
+    std::sort(ord.begin(), ord.end(), [&](uint32_t x, uint32_t y) {
+      return live[x].t_out != live[y].t_out ? live[x].t_out < live[y].t_out : live[x].a < live[y].a;
+    });
+    uint64_t link_free = 0;
+    for (uint32_t i : ord) {
+      Live &L = live[i];
+      const uint64_t ready = (L.t_out + 1) * bpo;
+      const uint64_t start = std::max(ready, link_free);
+      const uint64_t end = start + L.nbytes;
+      if (end >= (1ull << 62)) return SS_E_INVAL;
+      link_free = end;
+      L.t_free = (end - 1) / bpo;          // the operator running when the last byte lands
+      if (!(L.t_free < L.t_use)) {
+        if (cfg.flags & SS_CFG_KEEP_LATE) {      // must be executed anyway: released and re-fetched around its use
+          L.t_free = L.t_use - 1;
+          L.forced = true;
+        } else {
+          L.valid = false;                       // saves no memory: dropped
+        }
+      }
+    }
+    // swap-in queue: as late as possible, walking (t_use, policy index) downwards
+    std::sort(ord.begin(), ord.end(), [&](uint32_t x, uint32_t y) {
+      return live[x].t_use != live[y].t_use ? live[x].t_use > live[y].t_use : live[x].a > live[y].a;
+    });
+    // No swap-in is issued before the last swap-out has been issued: until then memory is still
+    // climbing to its peak and a swap-in would only fight the swap-outs for the link (Sec. 4.3.1:
+    // the search for a swap-in slot does not go back beyond the peak-memory period).
+    uint64_t t_peak = 0;
+    for (const Live &L : live)
+      if (L.valid) t_peak = std::max(t_peak, L.t_out + 1);
+    bool have_next = false;
+    int64_t next_start = 0;
+    for (uint32_t i : ord) {
+      Live &L = live[i];
+      if (!L.valid) continue;
+      int64_t end = (int64_t)(L.t_use * bpo_in);
+      if (have_next && next_start < end) end = next_start;
+      int64_t start = end - (int64_t)L.nbytes;
+      const int64_t floor_ = (int64_t)(std::max(L.t_free + 1, t_peak) * bpo_in);
+      if (start < floor_) {
+        start = floor_;
+        L.late = true;
+      }
+      L.t_in = (uint64_t)start / bpo_in;
+      next_start = start;
+      have_next = true;
+    }
+    // The swap-in stream is first-in first-out: an item needed later is never issued before one
+    // needed earlier (the release-point floor can otherwise put it ahead in the queue).
+    {
+      uint64_t run = 0;
+      for (auto it = ord.rbegin(); it != ord.rend(); ++it) {     // (t_use, policy index) ascending
+        Live &L = live[*it];
+        if (!L.valid) continue;
+        L.t_in = std::max(L.t_in, run);
+        run = L.t_in;
+      }
     }
   }
 
