@@ -76,13 +76,18 @@ def main():
     ap.add_argument("--path-in", default=None, choices=["auto", "kernel", "engine"],
                     help="copy path of the swap-in direction (default: same as --path)")
     ap.add_argument("--workgroups", type=int, default=0)
+    ap.add_argument("--workgroups-out", type=int, default=0,
+                    help="grid of the swap-out (pack) launches alone; 0 = same as --workgroups")
     ap.add_argument("--bpo", type=int, default=0,
                     help="link model: bytes the link moves per operator; 0 = link peak x no-swap step time / "
                          "operators per step, both measured in this run (Eq. 1 and Eq. 3 of the paper)")
-    ap.add_argument("--policy-mode", default="execute-all", choices=["execute-all", "link-aware"],
+    ap.add_argument("--policy-mode", default="execute-all", choices=["execute-all", "link-aware", "generated"],
                     help="execute-all: every tensor of the prescribed set is swapped even where the link "
                          "cannot hide it; link-aware: items whose swap-out cannot finish before their "
-                         "backward use are dropped")
+                         "backward use are dropped; generated: the library's policy generator (Sec. 4) picks "
+                         "the swap set for a memory limit (configurations 2 and 3) and its own points are kept")
+    ap.add_argument("--limit-frac", type=float, default=0.7,
+                    help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--swap-only", action="store_true",
@@ -146,6 +151,23 @@ def main():
         extra = dict(budget=48 * 10**9, min_bytes=1 << 20)
         if args.bpo <= 0:
             args.bpo = 256 << 20
+    if args.policy_mode == "generated":
+        # the paper's generator (Sec. 4) picks the swap set for a memory limit instead of the
+        # configuration prescribing it; one logical layer per decoder layer and phase
+        if args.config not in (2, 3):
+            sys.exit("--policy-mode generated: configurations 2 and 3 only")
+        from workloads import transformer as T
+        shape = T.config_shape(args.config)
+        extra = dict(min_bytes=1 << 16, generator=dict(g_fwd=shape.layers, g_bwd=shape.layers, c_num=1, c_den=1))
+        if args.config == 2:
+            tr_ = T.build_trace(shape)
+            sctx = B.ss_create(pcfg)
+            extra["budget"] = int(args.limit_frac * B.ss_timeline_scan(sctx, tr_.events, None, tr_.n_ops, 0, 1 << 62,
+                                                                      want_per_op=False)["peak"])
+            B.ss_destroy(sctx)
+            del tr_
+        else:
+            extra["budget"] = 48 * 10**9
     has_compute = args.config != 5
     if args.config == 5:       # small-tensor stress: no model around it
         extra = dict(compute=False)
@@ -177,7 +199,7 @@ def main():
         bpo = max(1, int(link * t_noswap / base_n_ops))
         for _ in range(max(1, args.calibrate)):
             trial = SwapRun(B, torch, args.config, swap=True, bpo=bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
-                            copy_workgroups=args.workgroups, flags=flags)
+                            copy_workgroups=args.workgroups, copy_workgroups_out=args.workgroups_out, flags=flags, **extra)
             t_trial = timed(trial, trial.step, 3, 2)
             calib.append({"link_bytes_per_op": bpo, "ms_per_step": round(t_trial * 1e3, 2),
                           "forced": trial.n_forced, "dropped": trial.n_dropped})
@@ -191,8 +213,8 @@ def main():
             bpo = nxt
         args.bpo = min(calib, key=lambda c: c["ms_per_step"])["link_bytes_per_op"]
     run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
-                  copy_workgroups=args.workgroups, flags=flags, **extra)
-    n_forced, n_dropped_setup = run.n_forced, run.n_dropped
+                  copy_workgroups=args.workgroups, copy_workgroups_out=args.workgroups_out, flags=flags, **extra)
+    n_forced, n_dropped_setup, run_generated = run.n_forced, run.n_dropped, run.generated
     st0 = None
     for _ in range(args.warmup):
         run.step()
@@ -258,13 +280,16 @@ def main():
             3: "config 3: 7B-shape decoder (hidden 4096, 32 layers, seq 4096, mb 1, bf16), 97 GiB of activations "
                "under a 48 GB budget, longest-idle-first policy, synthetic bf16 GEMMs on the compute stream",
             5: "config 5: 20,000 tensors of 4 KiB..4 MiB at random places of a 64 GB arena, two random orders, "
-               "no compute stream work"}[args.config],
+               "no compute stream work"}[args.config] +
+            (" [swap set chosen by the policy generator for the memory limit instead]"
+             if args.policy_mode == "generated" else ""),
                    "ops_per_step": n_ops, "tensors_swapped": int(applied["n_kept"]),
                    "bytes_each_way": bytes_way, "out_batches": int(applied["n_out_batches"]),
                    "in_batches": int(applied["n_in_batches"]), "copy_path_out": args.path,
                    "copy_path_in": args.path_in or args.path,
                    "kernel_launches": int(kernel_batches), "engine_batches": int(engine_batches),
                    "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "policy_mode": args.policy_mode,
+                   "memory_limit_bytes": extra.get("budget"), "generator": run_generated,
                    "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),
                    "stage": int(match["stage"]), "anchors_unmatched": int(match["n_unmatched"])},
         "trace_work_host_ms_per_step": dict(trace_work, note="wall time of the call incl. host<->device copies and "
@@ -296,7 +321,7 @@ def main():
     if not has_compute:
         for k in ("noswap_ms", "overhead_vs_noswap_pct", "floor_ms", "overhead_vs_floor_pct"):
             line["step_time"][k] = None
-    if not args.no_cpu_baseline and args.config in (1, 2):
+    if not args.no_cpu_baseline and args.config in (1, 2) and args.policy_mode != "generated":
         line["cpu_baseline"] = cpu_baseline(args.config, args.bpo)
     print(json.dumps(line), flush=True)
 

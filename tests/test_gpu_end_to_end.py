@@ -89,3 +89,31 @@ def test_7b_shape_small_scale_greedy_budget(env):
     assert a1 <= budget * 1.15 and a1 < a0 * 0.65
     rows, _ = oracle.greedy_policy(tr.tensors, tr.events, tr.n_ops, 0, budget, 4 << 20, min_bytes=1 << 16)
     assert [tuple(int(x) for x in p) for p in pol.tolist()] == rows
+
+
+def test_generated_policy_executes_with_unchanged_results(env):
+    """Sec. 4 -> Sec. 5 on the 1.3B shape: the generator picks what to swap for a limit of 70 % of
+    the no-swap peak, the executor runs that policy with its own release / pre-trigger points"""
+    B, torch = env
+    from workloads.harness import SwapRun
+    tr0 = W.build_trace(W.config_shape(2))
+    no = oracle.timeline_scan(tr0.events, None, tr0.n_ops, 0, 0)
+    limit, bpo = int(no["peak"] * 0.7), 16 << 20
+    gen = dict(g_fwd=24, g_bwd=24, c_num=1, c_den=1)
+    chk0, g0, i0 = run(B, torch, 2, False, 2)
+    r = SwapRun(B, torch, 2, swap=True, budget=limit, bpo=bpo, min_bytes=1 << 16, generator=gen,
+                flags=B.SS_CFG_POISON_FREE)
+    try:
+        for _ in range(2):
+            r.step()
+        chk1, g1 = r.compute.result()
+        plan, pol, arena_bytes, st = r.last, r.policy, r.arena_bytes, B.ss_get_stats(r.ctx)
+        info = r.generated
+    finally:
+        r.close()
+    assert np.array_equal(chk0, chk1) and np.array_equal(g0, g1)
+    items, _ = oracle.generate_policy(tr0.tensors, no["per_op"], list(tr0.op_phase), limit, bpo, 24, 24, 1, 1, 1 << 16)
+    assert [tuple(int(x) for x in p) for p in pol.tolist()] == items and len(items) > 10
+    assert info["n_over_with_policy"] == 0 and plan["scan"]["peak"] == info["peak_with_policy"] <= limit
+    assert plan["applied"]["n_dropped"] == 0 and arena_bytes <= limit * 1.1 < i0["arena"]
+    assert st["bytes_out"] == st["bytes_in"] == 2 * sum(it[8] for it in items)

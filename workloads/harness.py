@@ -22,7 +22,7 @@ class SwapRun:
 
     def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
                  copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
-                 policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None):
+                 policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None, generator=None):
         from .compute import SyntheticCompute
         self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
         if trace is not None:
@@ -32,6 +32,10 @@ class SwapRun:
         else:
             self.tr = T.build_trace(T.config_shape(cfgno), seed=seed)
             pol = T.config_swap_set(self.tr, cfgno) if cfgno in (1, 2) else None
+        if generator is not None:           # dict(g_fwd, g_bwd[, c_num, c_den]): the library's generator picks the set
+            pol = None
+            flags |= B.SS_CFG_POLICY_POINTS
+        self.generated = None
         tr = self.tr
         cfg = B.ss_config_default()
         cfg.link_bytes_per_op = bpo
@@ -57,7 +61,10 @@ class SwapRun:
             self.ops = np.stack([B.ss_intern_op(probe, tr.op_name[i], tr.op_stack[i], tr.op_dtype[i],
                                                 len(tr.op_outputs[i]), tr.op_phase[i])
                                  for i in range(tr.n_ops)]) if tr.n_ops else np.zeros(0, B.OP_DT)
-            if swap and pol is None:
+            if swap and pol is None and generator is not None:
+                pol, self.generated = B.ss_generate_policy(probe, self.ops, tr.tensors, tr.events, 0, self.budget,
+                                                           min_bytes=min_bytes, **generator)
+            elif swap and pol is None:
                 pol, _ = B.ss_greedy_policy(probe, tr.tensors, tr.events, tr.n_ops, 0, self.budget, min_bytes)
             if not swap:
                 pol = pol[:0] if pol is not None else np.zeros(0, B.POLICY_DT)
