@@ -34,6 +34,10 @@ What the paper fixes and what is this build's reading of it:
 * generate_policy - Sec. 4 (Eq. 1-3, Algo. 2): logical layers, MRL, candidate list, simulator.
                     PARITY UNPINNED against the paper (no worked example in it); pinned by
                     hand-worked cases, invariants and brute force.
+* align, align_anchors - longest common subsequence of two operator sequences (textbook dynamic
+                    programme) and the canonical alignment read off its table; the matcher's fourth
+                    level.  Not in the paper (Sec. 5.1 gives no algorithm): PARITY UNPINNED against
+                    it; pinned by textbook examples, brute force and closed forms.
 """
 from .trace import fnv1a32, make_sig, TraceRecorder
 from .timeline import timeline_scan
@@ -43,3 +47,4 @@ from .policy import (link_timing, apply_policy, greedy_policy, schedule_check,
                      F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED, F_FORCED, Infeasible)
 from .swap import swap_out, swap_in, SparseArena
 from .generator import generate_policy, logical_layers
+from .align import align, align_anchors, lcs_table, LEVEL_ALIGN
