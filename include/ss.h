@@ -147,7 +147,10 @@ typedef struct {
 
 enum { SS_STAGE_WARMUP = 0, SS_STAGE_GENPOLICY = 1, SS_STAGE_STABLE = 2 };
 enum { SS_MATCH_STEP_STAGE = 1,  /* advance the Algo. 1 stage machine with this verdict      */
-       SS_MATCH_HISTOGRAM = 2 }; /* cosine of per-token occurrence counts instead of positions */
+       SS_MATCH_HISTOGRAM = 2,   /* cosine of per-token occurrence counts instead of positions */
+       SS_MATCH_ALIGN = 4 };     /* anchors land where the alignment of the two sequences pairs their
+                                    operator (as ss_align_sequence), level SS_LEVEL_ALIGN           */
+enum { SS_LEVEL_ALIGN = 3 };
 typedef struct {
   uint64_t dot, na, nb;   /* integer sums of the cosine (na: current, nb: reference)        */
   uint32_t similar;       /* 1 if length differs by < 5 % and cosine > 95 %                 */
@@ -155,6 +158,13 @@ typedef struct {
   uint32_t stable_step;   /* Algo. 1 counter after this call                                */
   uint32_t n_unmatched;   /* anchors with new_idx == -1                                     */
 } ss_match_result_t;
+
+typedef struct {
+  uint32_t lcs;           /* length of the longest common subsequence                       */
+  uint32_t distance;      /* insertions + deletions turning ref into cur: n + m - 2 lcs     */
+  uint32_t n_keys;        /* distinct (op_token, stack_hash, sig) in cur                    */
+  uint32_t n_unmatched;   /* anchors with new_idx == -1                                     */
+} ss_align_result_t;
 
 typedef struct {
   uint64_t staging_bytes;   /* staging the schedule needs                                    */
@@ -255,6 +265,22 @@ int ss_timeline_scan(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev,
 int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, const ss_op_t *cur, uint32_t m,
                       const ss_anchor_t *anchors /* nullable if k == 0 */, uint32_t k, uint32_t flags,
                       int32_t *new_idx, uint8_t *level, ss_match_result_t *res /* host, out */);
+
+/* Align the current sequence with the reference one as a whole (Sec. 5.1: identification must
+ * survive minor variations of the sequence; the paper gives no algorithm, this is the build's).
+ * Two operators are equal when (op_token, stack_hash, sig) are equal.  The longest common
+ * subsequence is computed on the GPU; of the optimal alignments the one read from the end of both
+ * sequences is taken: equal operators pair, otherwise step back in cur if that loses nothing, else
+ * in ref.  ref_to_cur[i] (nullable, n_ref entries) = operator of cur paired with ref[i], or -1.
+ * An anchor lands on the operator its ref_op is paired with if that operator has more than
+ * out_slot outputs (level SS_LEVEL_ALIGN), else -1 / 255.  Unlike the keyed ordinals of
+ * ss_match_sequence this does not misland when an operator with the anchor's own key was dropped or
+ * inserted earlier in the sequence.  Limits: n_ref, n_cur <= 65536 and n_ref * ceil(n_cur / 64) * 8
+ * bytes <= 1 GiB (SS_E_CAPACITY).  All arrays are host memory. */
+int ss_align_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n_ref, const ss_op_t *cur, uint32_t n_cur,
+                      const ss_anchor_t *anchors /* nullable if n_anchors == 0 */, uint32_t n_anchors,
+                      int32_t *ref_to_cur, int32_t *new_idx, uint8_t *level,
+                      ss_align_result_t *res /* host, out */);
 
 /* ---- a4: apply policy (Sec. 5 first paragraph; Sec. 4.3 timing) ---------------- */
 

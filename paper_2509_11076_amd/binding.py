@@ -42,7 +42,8 @@ SS_ACT_IN, SS_ACT_WAIT_IN, SS_ACT_OUT, SS_ACT_FREE = 0, 1, 2, 3
 SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE = 0, 1, 2
 SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE, SS_CFG_POLICY_POINTS = 1, 2, 4, 8, 16
 SS_SYNC_FREE, SS_SYNC_WAIT_IN, SS_SYNC_DRAIN = 0, 1, 2
-SS_MATCH_STEP_STAGE, SS_MATCH_HISTOGRAM = 1, 2
+SS_MATCH_STEP_STAGE, SS_MATCH_HISTOGRAM, SS_MATCH_ALIGN = 1, 2, 4
+SS_LEVEL_ALIGN = 3
 SS_STAGE_WARMUP, SS_STAGE_GENPOLICY, SS_STAGE_STABLE = 0, 1, 2
 SS_F_UNMATCHED, SS_F_ORDER, SS_F_LATE, SS_F_RESIZED, SS_F_FORCED = 1, 2, 4, 8, 16
 SS_NONE_OP = 0xFFFFFFFF
@@ -72,6 +73,10 @@ class ss_apply_result_t(C.Structure):
     _fields_ = [("staging_bytes", C.c_uint64), ("bytes_out", C.c_uint64), ("n_kept", C.c_uint32),
                 ("n_dropped", C.c_uint32), ("n_late", C.c_uint32), ("n_out_batches", C.c_uint32),
                 ("n_in_batches", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class ss_align_result_t(C.Structure):
+    _fields_ = [("lcs", C.c_uint32), ("distance", C.c_uint32), ("n_keys", C.c_uint32), ("n_unmatched", C.c_uint32)]
 
 
 class ss_gen_params_t(C.Structure):
@@ -132,6 +137,8 @@ _SIGS = {
     "ss_load_schedule": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P],
     "ss_greedy_policy": [_P, _P, C.c_uint32, _P, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_uint64,
                          _P, C.c_uint32, _P, C.POINTER(C.c_uint32), C.POINTER(C.c_int64)],
+    "ss_align_sequence": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, _P, _P,
+                          C.POINTER(ss_align_result_t)],
     "ss_generate_policy": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint64, C.c_int64, C.c_int64,
                            C.POINTER(ss_gen_params_t), _P, C.POINTER(C.c_uint32), C.POINTER(ss_gen_result_t)],
     "ss_swap_out": [_P, C.c_uint32],
@@ -286,6 +293,23 @@ def ss_match_sequence(ctx, ref, cur, anchors, flags=0):
                                _ptr(new_idx), _ptr(level), C.byref(res)), "ss_match_sequence")
     return dict(similar=bool(res.similar), dot=res.dot, na=res.na, nb=res.nb, stage=res.stage,
                 stable_step=res.stable_step, new_idx=new_idx, level=level, n_unmatched=res.n_unmatched)
+
+
+def ss_align_sequence(ctx, ref, cur, anchors=None):
+    ref = _arr(ref, OP_DT)
+    cur = _arr(cur, OP_DT)
+    anc = _arr(anchors, ANCHOR_DT)
+    k = 0 if anc is None else len(anc)
+    n = 0 if ref is None else len(ref)
+    m = 0 if cur is None else len(cur)
+    ref_to_cur = np.full(n, -2, dtype=np.int32)
+    new_idx = np.full(k, -1, dtype=np.int32)
+    level = np.full(k, 255, dtype=np.uint8)
+    res = ss_align_result_t()
+    _ck(_lib.ss_align_sequence(ctx, _ptr(ref), n, _ptr(cur), m, _ptr(anc), k, _ptr(ref_to_cur), _ptr(new_idx),
+                               _ptr(level), C.byref(res)), "ss_align_sequence")
+    return dict(ref_to_cur=ref_to_cur, new_idx=new_idx, level=level, lcs=res.lcs, distance=res.distance,
+                n_keys=res.n_keys, n_unmatched=res.n_unmatched)
 
 
 def ss_apply_policy(ctx, policy, new_idx, tensors, allow_nomem=False):

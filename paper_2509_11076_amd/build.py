@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["ss_runtime.hip", "ss_copy.hip", "ss_trace.hip", "ss_scan.hip", "ss_match.hip", "ss_policy.hip", "ss_generator.hip"]
+SOURCES = ["ss_runtime.hip", "ss_copy.hip", "ss_trace.hip", "ss_scan.hip", "ss_match.hip", "ss_policy.hip", "ss_generator.hip", "ss_align.hip"]
 LIB = os.path.join(HERE, "libss.so")
 
 

@@ -95,3 +95,10 @@ void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to
                     uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc,
                     uint32_t n_chunks);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
+
+// sequence aligner (ss_align.hip): ref_to_cur has n entries
+int ss_align_core(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, const ss_op_t *cur, uint32_t m,
+                  int32_t *ref_to_cur, uint32_t *lcs, uint32_t *n_keys_out);
+void ss_align_anchors(const ss_op_t *ref, uint32_t n, const ss_op_t *cur, const int32_t *ref_to_cur,
+                      const ss_anchor_t *anchors, uint32_t k, int32_t *new_idx, uint8_t *level,
+                      uint32_t *n_unmatched);

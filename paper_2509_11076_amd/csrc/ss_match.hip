@@ -240,7 +240,8 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
     }
     SS_HIP(hipGetLastError());
   }
-  if (k) {
+  const bool aligned = (flags & SS_MATCH_ALIGN) != 0;
+  if (k && !aligned) {
     const uint32_t grid = (k + 3) / 4;                    // 4 wavefronts (anchors) per workgroup
     hipLaunchKernelGGL(ss_anchor_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m,
                        (const ss_anchor_t *)(d + o_anc), k, (int32_t *)(d + o_land), d + o_lvl);
@@ -251,7 +252,7 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
   }
   uint8_t *h = (uint8_t *)ctx->h_scratch;
   SS_HIP(hipMemcpyAsync(h, d + o_small, 64, hipMemcpyDeviceToHost, s));
-  if (k) {
+  if (k && !aligned) {
     SS_HIP(hipMemcpyAsync(new_idx, d + o_idx, (size_t)k * 4, hipMemcpyDeviceToHost, s));
     SS_HIP(hipMemcpyAsync(level, d + o_level, k, hipMemcpyDeviceToHost, s));
   }
@@ -278,6 +279,13 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
   if (flags & SS_MATCH_STEP_STAGE) stage_step(ctx, similar);
   res->stage = ctx->stage;
   res->stable_step = ctx->stable_step;
-  res->n_unmatched = k ? unm : 0;
+  res->n_unmatched = (k && !aligned) ? unm : 0;
+  if (k && aligned) {                                      // the scratch is free again: the stream is idle
+    std::vector<int32_t> ref_to_cur(n);
+    uint32_t lcs = 0;
+    rc = ss_align_core(ctx, ref, n, cur, m, ref_to_cur.data(), &lcs, nullptr);
+    if (rc != SS_OK) return rc;
+    ss_align_anchors(ref, n, cur, ref_to_cur.data(), anchors, k, new_idx, level, &res->n_unmatched);
+  }
   return SS_OK;
 }
