@@ -35,10 +35,13 @@ def assert_applied(lib, ora):
     assert lib["staging_bytes"] == ora["staging_bytes"] and lib["n_dropped"] == ora["n_dropped"]
 
 
-def oracle_plan(rec, ref_ops, ref_policy, anchors, tr, budget, bpo, bpo_in, min_bytes):
+def oracle_plan(rec, ref_ops, ref_policy, anchors, tr, budget, bpo, bpo_in, min_bytes, aligned=False):
     """the same per-iteration planning sequence as VaryingRun.plan, on the oracle"""
     cur_ops, _ = record_oracle(rec, tr)
     m = oracle.match_sequence(ops_tuples(ref_ops), ops_tuples(cur_ops), anchors)
+    if aligned:        # anchors through the sequence aligner; the similarity verdict stays
+        al = oracle.align_anchors(ops_tuples(ref_ops), ops_tuples(cur_ops), anchors)
+        m = dict(m, new_idx=al["new_idx"], level=al["level"], n_unmatched=int((al["new_idx"] < 0).sum()))
     ap = oracle.apply_policy(ref_policy, m["new_idx"], tr.tensors, bpo, bpo_in=bpo_in)
     sc = oracle.timeline_scan(tr.events, ap["policy_events"], tr.n_ops, 0, budget)
     carried = []
@@ -69,7 +72,8 @@ def check_plan(p, o):
 
 
 @pytest.mark.timeout(900)
-def test_varying_sequence_20_iterations_reduced_width(env):
+@pytest.mark.parametrize("aligned", [False, True])
+def test_varying_sequence_20_iterations_reduced_width(env, aligned):
     """configuration 4 at reduced width (hidden 512, seq 512, 8 layers, 4 branch operators): every
     iteration is planned online, checked against the oracle, executed, and compared with no swapping"""
     B, torch = env
@@ -80,7 +84,7 @@ def test_varying_sequence_20_iterations_reduced_width(env):
     no = oracle.timeline_scan(tr0.events, None, tr0.n_ops, 0, 0)
     budget, bpo, bpo_in, min_bytes = int(no["peak"] * 0.55), 4 << 20, 2 << 20, 1 << 16
     run = VaryingRun(B, torch, shape, budget, bpo, bpo_in=bpo_in, min_bytes=min_bytes, perturb=PERT,
-                     flags=B.SS_CFG_POISON_FREE, arena_slack=1.6)
+                     flags=B.SS_CFG_POISON_FREE, arena_slack=1.6, match_flags=B.SS_MATCH_ALIGN if aligned else 0)
     big = torch.empty(int(no["peak"] * 2.2), dtype=torch.uint8, device="cuda")
     rec = oracle.TraceRecorder()
     ref_ops, _ = record_oracle(rec, tr0)
@@ -95,7 +99,7 @@ def test_varying_sequence_20_iterations_reduced_width(env):
         for it in range(20):
             p = run.plan(it)
             tr = p["trace"]
-            o = oracle_plan(rec, ref_ops, ref_policy, anchors, tr, budget, bpo, bpo_in, min_bytes)
+            o = oracle_plan(rec, ref_ops, ref_policy, anchors, tr, budget, bpo, bpo_in, min_bytes, aligned)
             check_plan(p, o)
             assert p["match"]["stage"] == sm.step_verdict(o["match"]["similar"])
             assert p["scan"]["peak"] <= budget
@@ -120,14 +124,16 @@ def test_varying_sequence_20_iterations_reduced_width(env):
 
 
 @pytest.mark.timeout(1100)
-def test_varying_sequence_full_7b_shape_planning(env):
+@pytest.mark.parametrize("aligned", [False, True])
+def test_varying_sequence_full_7b_shape_planning(env, aligned):
     """configuration 4 at full size (7B shape, 48 GB budget): record, match, apply, scan and top-up of
     every iteration equal the oracle's (no bytes are moved here)"""
     B, torch = env
     from workloads.harness import VaryingRun
     shape = W.config_shape(4)
     budget, bpo, bpo_in, min_bytes = 48 * 10**9, 256 << 20, 0, 1 << 20
-    run = VaryingRun(B, torch, shape, budget, bpo, bpo_in=bpo_in, min_bytes=min_bytes, perturb=PERT, compute=False)
+    run = VaryingRun(B, torch, shape, budget, bpo, bpo_in=bpo_in, min_bytes=min_bytes, perturb=PERT, compute=False,
+                     match_flags=B.SS_MATCH_ALIGN if aligned else 0)
     tr0 = W.build_trace(shape)
     rec = oracle.TraceRecorder()
     ref_ops, _ = record_oracle(rec, tr0)
@@ -139,10 +145,10 @@ def test_varying_sequence_full_7b_shape_planning(env):
     try:
         for it in range(20):
             p = run.plan(it)
-            o = oracle_plan(rec, ref_ops, ref_policy, anchors, p["trace"], budget, bpo, bpo_in, min_bytes)
+            o = oracle_plan(rec, ref_ops, ref_policy, anchors, p["trace"], budget, bpo, bpo_in, min_bytes, aligned)
             check_plan(p, o)
             assert p["scan"]["peak"] <= budget
-            print("iteration", it, "ops", p["trace"].n_ops, "seq", p["trace"].seq, "unmatched",
+            print("aligned", aligned, "iteration", it, "ops", p["trace"].n_ops, "seq", p["trace"].seq, "unmatched",
                   p["match"]["n_unmatched"], "topped up", p["topped"], "peak GB", p["scan"]["peak"] / 1e9, flush=True)
     finally:
         run.close()

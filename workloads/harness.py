@@ -156,10 +156,11 @@ class VaryingRun:
     """
 
     def __init__(self, B, torch, shape, budget, bpo, bpo_in=0, min_bytes=0, perturb=None, seed=2509,
-                 flags=0, compute=True, gemm_scale=1.0, arena_slack=1.25, staging_slack=1.4):
+                 flags=0, compute=True, gemm_scale=1.0, arena_slack=1.25, staging_slack=1.4, match_flags=0):
         self.B, self.torch, self.shape = B, torch, shape
         self.budget, self.min_bytes, self.perturb, self.seed = budget, min_bytes, perturb, seed
         self.do_compute, self.gemm_scale = compute, gemm_scale
+        self.match_flags = match_flags      # e.g. SS_MATCH_ALIGN: anchors through the sequence aligner
         cfg = B.ss_config_default()
         cfg.link_bytes_per_op = bpo
         cfg.prefetch_bytes_per_op = bpo_in
@@ -205,7 +206,8 @@ class VaryingRun:
         B = self.B
         tr = T.build_trace(self.shape, seed=self.seed, iteration=it, perturb=self.perturb if it else None)
         ops = self.intern(tr)
-        m = B.ss_match_sequence(self.plan_ctx, self.ref_ops, ops, self.anchors, flags=B.SS_MATCH_STEP_STAGE)
+        m = B.ss_match_sequence(self.plan_ctx, self.ref_ops, ops, self.anchors,
+                                flags=B.SS_MATCH_STEP_STAGE | self.match_flags)
         ap = B.ss_apply_policy(self.plan_ctx, self.ref_policy, m["new_idx"], tr.tensors, allow_nomem=True)
         sc = B.ss_timeline_scan(self.plan_ctx, tr.events, ap["policy_events"], tr.n_ops, 0, self.budget,
                                 want_per_op=False)
