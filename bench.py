@@ -86,6 +86,10 @@ def main():
                          "cannot hide it; link-aware: items whose swap-out cannot finish before their "
                          "backward use are dropped; generated: the library's policy generator (Sec. 4) picks "
                          "the swap set for a memory limit (configurations 2 and 3) and its own points are kept")
+    ap.add_argument("--timing", default="link-model", choices=["link-model", "policy-points"],
+                    help="--policy-mode generated: release and pre-trigger points from the operator-granular link "
+                         "model fed with per-phase operator times measured in this run (default), or the "
+                         "generator's own logical-layer points")
     ap.add_argument("--limit-frac", type=float, default=0.7,
                     help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
@@ -158,7 +162,8 @@ def main():
             sys.exit("--policy-mode generated: configurations 2 and 3 only")
         from workloads import transformer as T
         shape = T.config_shape(args.config)
-        extra = dict(min_bytes=1 << 16, generator=dict(g_fwd=shape.layers, g_bwd=shape.layers, c_num=1, c_den=1))
+        extra = dict(min_bytes=1 << 16, generator=dict(g_fwd=shape.layers, g_bwd=shape.layers, c_num=1, c_den=1),
+                     policy_points=args.timing == "policy-points")
         if args.config == 2:
             tr_ = T.build_trace(shape)
             sctx = B.ss_create(pcfg)
@@ -178,12 +183,30 @@ def main():
         base = SwapRun(B, torch, args.config, swap=False)
         t_noswap = timed(base, base.step_noswap, args.steps, args.warmup)
         base_n_ops = base.tr.n_ops
+        # forward / backward split of the no-swap step (two markers): operators of the forward pass are
+        # several times shorter than those of the backward pass, which Eq. 1's even spread ignores
+        ph = list(base.tr.op_phase)
+        first_bwd = ph.index(1) if 1 in ph else len(ph)
+        ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev3[0].record()
+        for i in range(base.tr.n_ops):
+            if i == first_bwd:
+                ev3[1].record()
+            base.compute.run_op(i)
+        if first_bwd == len(ph):
+            ev3[1].record()
+        ev3[2].record()
+        torch.cuda.synchronize()
+        t_fwd, t_bwd = ev3[0].elapsed_time(ev3[1]) * 1e-3, ev3[1].elapsed_time(ev3[2]) * 1e-3
+        n_fwd, n_bwd = max(1, first_bwd), max(1, len(ph) - first_bwd)
         base.close()
         del base
         torch.cuda.empty_cache()
         print("no-swap baseline done: %.1f ms/step" % (t_noswap * 1e3), file=sys.stderr, flush=True)
     else:
         t_noswap, base_n_ops = 1e-9, 1
+        t_fwd = t_bwd = 0.0
+        n_fwd = n_bwd = 1
 
     # Link model.  Eq. 1 spreads the measured iteration time evenly over the operators and Eq. 3
     # turns bytes into time, so bytes-per-operator = link peak x iteration time / operators.  The
@@ -195,6 +218,13 @@ def main():
     calib = []
     # the swap-in queue is planned with the no-swap operator time: operators never run faster than that
     bpo_in = max(1, int(link * t_noswap / base_n_ops)) if args.config in (1, 2) else 0
+    if args.policy_mode == "generated" and args.timing == "link-model" and args.bpo <= 0:
+        # swap-outs queue up during the forward pass, swap-ins during the backward pass: each queue gets
+        # that pass's measured bytes per operator (with 10 % margin); the generator's Eq. 1 keeps the
+        # whole-iteration average
+        extra["generator"]["bpo"] = max(1, int(link * t_noswap / base_n_ops))
+        args.bpo = max(1, int(0.9 * link * t_fwd / n_fwd))
+        bpo_in = max(1, int(0.9 * link * t_bwd / n_bwd))
     if args.bpo <= 0:
         bpo = max(1, int(link * t_noswap / base_n_ops))
         for _ in range(max(1, args.calibrate)):
@@ -212,6 +242,23 @@ def main():
                 break
             bpo = nxt
         args.bpo = min(calib, key=lambda c: c["ms_per_step"])["link_bytes_per_op"]
+    # grid of the pack launches: a grid that saturates the link delays every kernel launched beside it,
+    # a small one (8 workgroups, about 3/4 of the link rate) hardly does; which wins depends on whether
+    # the step is bound by the link or by the compute stream, so both are measured and the faster kept
+    grid_fits = []
+    if has_compute and args.workgroups_out == 0 and args.calibrate > 0:
+        for wgo in (0, 8):
+            trial = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path,
+                            copy_path_in=path_in, copy_workgroups=args.workgroups, copy_workgroups_out=wgo,
+                            flags=flags, **extra)
+            t_trial = timed(trial, trial.step, 3, 2)
+            grid_fits.append({"workgroups_out": wgo or "default", "ms_per_step": round(t_trial * 1e3, 2)})
+            print("pack grid fit: %s -> %.1f ms/step" % (wgo or "default", t_trial * 1e3), file=sys.stderr, flush=True)
+            trial.close()
+            del trial
+            torch.cuda.empty_cache()
+        if grid_fits[1]["ms_per_step"] < 0.98 * grid_fits[0]["ms_per_step"]:
+            args.workgroups_out = 8
     run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
                   copy_workgroups=args.workgroups, copy_workgroups_out=args.workgroups_out, flags=flags, **extra)
     n_forced, n_dropped_setup, run_generated = run.n_forced, run.n_dropped, run.generated
@@ -288,7 +335,10 @@ def main():
                    "in_batches": int(applied["n_in_batches"]), "copy_path_out": args.path,
                    "copy_path_in": args.path_in or args.path,
                    "kernel_launches": int(kernel_batches), "engine_batches": int(engine_batches),
-                   "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "policy_mode": args.policy_mode,
+                   "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "pack_grid_fits": grid_fits,
+                   "pack_workgroups": args.workgroups_out or args.workgroups or "default (64)", "policy_mode": args.policy_mode,
+                   "timing": args.timing if args.policy_mode == "generated" else "link-model",
+                   "noswap_forward_ms": round(t_fwd * 1e3, 2), "noswap_backward_ms": round(t_bwd * 1e3, 2),
                    "memory_limit_bytes": extra.get("budget"), "generator": run_generated,
                    "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),
                    "stage": int(match["stage"]), "anchors_unmatched": int(match["n_unmatched"])},

@@ -22,7 +22,8 @@ class SwapRun:
 
     def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
                  copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
-                 policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None, generator=None):
+                 policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None, generator=None,
+                 policy_points=True):
         from .compute import SyntheticCompute
         self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
         if trace is not None:
@@ -34,7 +35,8 @@ class SwapRun:
             pol = T.config_swap_set(self.tr, cfgno) if cfgno in (1, 2) else None
         if generator is not None:           # dict(g_fwd, g_bwd[, c_num, c_den]): the library's generator picks the set
             pol = None
-            flags |= B.SS_CFG_POLICY_POINTS
+            if policy_points:               # else the generator only selects; the link model times the items
+                flags |= B.SS_CFG_POLICY_POINTS
         self.generated = None
         tr = self.tr
         cfg = B.ss_config_default()
@@ -62,8 +64,22 @@ class SwapRun:
                                                 len(tr.op_outputs[i]), tr.op_phase[i])
                                  for i in range(tr.n_ops)]) if tr.n_ops else np.zeros(0, B.OP_DT)
             if swap and pol is None and generator is not None:
-                pol, self.generated = B.ss_generate_policy(probe, self.ops, tr.tensors, tr.events, 0, self.budget,
-                                                           min_bytes=min_bytes, **generator)
+                gen = dict(generator)
+                gen_bpo = gen.pop("bpo", None)      # Eq. 1 of the generator may use another time per operator
+                gctx = probe
+                if gen_bpo:
+                    cfg.link_bytes_per_op = int(gen_bpo)
+                    gctx = B.ss_create(cfg)
+                    cfg.link_bytes_per_op = bpo
+                    for i in range(tr.n_ops):
+                        B.ss_intern_op(gctx, tr.op_name[i], tr.op_stack[i], tr.op_dtype[i], len(tr.op_outputs[i]),
+                                       tr.op_phase[i])
+                try:
+                    pol, self.generated = B.ss_generate_policy(gctx, self.ops, tr.tensors, tr.events, 0, self.budget,
+                                                               min_bytes=min_bytes, **gen)
+                finally:
+                    if gctx is not probe:
+                        B.ss_destroy(gctx)
             elif swap and pol is None:
                 pol, _ = B.ss_greedy_policy(probe, tr.tensors, tr.events, tr.n_ops, 0, self.budget, min_bytes)
             if not swap:
