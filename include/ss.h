@@ -223,6 +223,15 @@ int ss_trace_begin(ss_ctx *ctx);
 int ss_trace_record(ss_ctx *ctx, const ss_op_t *op /* host */, const ss_event_t *ev /* host, nullable */,
                     uint32_t n_ev);
 
+/* For dispatch hooks that learn things only after the operator has been recorded (its outputs
+ * when it returns, the allocator's calls while it runs; Sec. 3 Detailed mode):
+ * ss_trace_event appends one alloc (+) / free (-) event to the most recently recorded operator
+ * (SS_E_ORDER before the first operator of the iteration, SS_E_CAPACITY beyond max_events);
+ * ss_trace_amend sets the data-type code and output count of recorded operator op_idx (the
+ * phase and the token stay). */
+int ss_trace_event(ss_ctx *ctx, uint32_t tensor_id, int64_t delta);
+int ss_trace_amend(ss_ctx *ctx, uint32_t op_idx, uint32_t dtype, uint32_t n_out);
+
 /* Borrow the recorded arrays (valid until the next ss_trace_begin / ss_destroy)
  * and the running sum of all deltas (0 for a balanced iteration). */
 int ss_trace_view(ss_ctx *ctx, const ss_op_t **ops, uint32_t *n_ops, const ss_event_t **ev,

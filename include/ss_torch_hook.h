@@ -1,0 +1,53 @@
+/* Online profiler hook inside PyTorch (SmartSwap, Sec. 3: a hook at the operator dispatch point,
+ * working in Lightweight or Detailed mode).  Exported by libss_torch_hook.so, which links the
+ * PyTorch libraries of the running process and libss.so; plain C ABI, no torch types.
+ *
+ * After ss_hook_install every operator PyTorch dispatches in this process (ATen's RecordFunction,
+ * scope FUNCTION: forward operators and those the autograd nodes run) is appended to `ctx`'s trace
+ * with ss_trace_record, in dispatch order:
+ *   SS_HOOK_LIGHTWEIGHT  the token of the operator's name and the current phase; nothing else
+ *   SS_HOOK_DETAILED     also a 32-bit hash of the innermost 8 Python frames (0 on threads the
+ *                        interpreter does not know, i.e. the autograd engine's), the data-type code and
+ *                        the number of tensor outputs (set when the operator returns, ss_trace_amend),
+ *                        and the caching allocator's alloc / completed-free calls as events of the
+ *                        operator running at that moment (ss_trace_event; the sizes asked for,
+ *                        before the allocator rounds them; ids counted from 0 per iteration)
+ * Data-type codes: 1 bf16, 2 fp32, 3 u8, 4 fp16, 5 i64, 6 i32, 7 bool, 8 fp64, 15 other, 0 no tensor.
+ * One context at a time; calls are serialised by a lock.  The context must outlive the hook:
+ * call ss_hook_remove before ss_destroy. */
+#ifndef SS_TORCH_HOOK_H
+#define SS_TORCH_HOOK_H
+#include <stdint.h>
+
+#include "ss.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SS_HOOK_OFF = 0, SS_HOOK_LIGHTWEIGHT = 1, SS_HOOK_DETAILED = 2 };
+
+typedef struct {
+  uint64_t ops, events;                  /* recorded since the library was loaded            */
+  uint64_t dropped_ops, dropped_events;  /* refused by ss_trace_record / ss_trace_event (capacity) */
+  uint64_t foreign_frees;                /* frees of blocks allocated before the iteration began
+                                            (recorded too, under an id of their own)         */
+  uint64_t errors;
+} ss_hook_stats_t;
+
+/* Register the callbacks (once per process) and direct them to ctx.  SS_E_INVAL on a bad mode. */
+int ss_hook_install(ss_ctx *ctx, int mode);
+/* Switch mode without touching the registration (Algo. 1: Detailed only while a policy is needed). */
+int ss_hook_set_mode(int mode);
+/* The training loop says where it is: 0 forward, 1 backward, 2 optimizer (goes into sig >> 16). */
+int ss_hook_set_phase(uint32_t phase);
+/* ss_trace_begin on the hooked context, event ids restart at 0, phase 0. */
+int ss_hook_begin_iteration(void);
+/* Unregister the operator callback and forget the context. */
+int ss_hook_remove(void);
+int ss_hook_get_stats(ss_hook_stats_t *out /* host, out */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

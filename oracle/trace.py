@@ -66,6 +66,19 @@ class TraceRecorder:
         self.ops.append(tuple(int(x) for x in op))
         self.events.extend((int(a), int(b), int(c)) for (a, b, c) in events)
 
+    def event(self, tensor_id, delta):
+        """An alloc/free event that becomes known after its operator was recorded (the allocator
+        is called while the operator runs): it belongs to the most recently recorded operator."""
+        if not self.ops:
+            raise ValueError("no operator recorded yet")
+        self.events.append((len(self.ops) - 1, int(tensor_id), int(delta)))
+
+    def amend(self, op_idx, dtype, n_out):
+        """Data type and output count of an operator are known when it returns: set them on its
+        record; token, call-stack hash and phase stay."""
+        tok, stack, sig, _ = self.ops[op_idx]
+        self.ops[op_idx] = (tok, stack, make_sig(dtype, n_out, sig >> 16), int(n_out))
+
     def balance(self):
         """Sum of all deltas of the iteration; 0 for a balanced iteration."""
         return sum(d for (_, _, d) in self.events)

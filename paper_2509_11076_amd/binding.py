@@ -137,6 +137,8 @@ _SIGS = {
     "ss_load_schedule": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P],
     "ss_greedy_policy": [_P, _P, C.c_uint32, _P, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_uint64,
                          _P, C.c_uint32, _P, C.POINTER(C.c_uint32), C.POINTER(C.c_int64)],
+    "ss_trace_event": [_P, C.c_uint32, C.c_int64],
+    "ss_trace_amend": [_P, C.c_uint32, C.c_uint32, C.c_uint32],
     "ss_align_sequence": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, _P, _P,
                           C.POINTER(ss_align_result_t)],
     "ss_generate_policy": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint64, C.c_int64, C.c_int64,
@@ -250,6 +252,14 @@ def ss_trace_record_prepared(ctx, ops, events):
         if rc != SS_OK:
             raise SsError(rc, "ss_trace_record")
     return record
+
+
+def ss_trace_event(ctx, tensor_id, delta):
+    _ck(_lib.ss_trace_event(ctx, int(tensor_id), int(delta)), "ss_trace_event")
+
+
+def ss_trace_amend(ctx, op_idx, dtype, n_out):
+    _ck(_lib.ss_trace_amend(ctx, int(op_idx), int(dtype), int(n_out)), "ss_trace_amend")
 
 
 def ss_trace_view(ctx):

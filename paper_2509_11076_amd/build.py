@@ -41,6 +41,31 @@ def build_library(verbose=True):
     return LIB
 
 
+HOOK_LIB = os.path.join(HERE, "libss_torch_hook.so")
+
+
+def build_hook(verbose=True):
+    """Compile the PyTorch dispatch hook (host C++ only) against the installed PyTorch and libss.so."""
+    import sysconfig
+    import torch
+    from torch.utils import cpp_extension as ce
+    tlib = os.path.join(os.path.dirname(torch.__file__), "lib")
+    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
+           "-D__HIP_PLATFORM_AMD__=1", "-DUSE_ROCM=1",
+           "-D_GLIBCXX_USE_CXX11_ABI=%d" % int(torch._C._GLIBCXX_USE_CXX11_ABI)]
+    cmd += ["-I" + p for p in ce.include_paths()]
+    cmd += ["-I/opt/rocm/include", "-I" + sysconfig.get_paths()["include"],
+            "-I" + os.path.join(ROOT, "include"), os.path.join(HERE, "csrc", "ss_torch_hook.cpp"),
+            "-o", HOOK_LIB, "-L" + tlib, "-L" + HERE, "-ltorch_cpu", "-lc10", "-lc10_hip", "-lss",
+            "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + tlib]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return HOOK_LIB
+
+
 if __name__ == "__main__":
     build_library()
     print("built", LIB)
+    build_hook()
+    print("built", HOOK_LIB)

@@ -71,6 +71,24 @@ extern "C" int ss_trace_record(ss_ctx *ctx, const ss_op_t *op, const ss_event_t 
   return SS_OK;
 }
 
+extern "C" int ss_trace_event(ss_ctx *ctx, uint32_t tensor_id, int64_t delta) {
+  if (!ctx) return SS_E_INVAL;
+  if (ctx->n_ops == 0) return SS_E_ORDER;
+  if (ctx->n_events >= ctx->cfg.max_events) return SS_E_CAPACITY;
+  ctx->events[ctx->n_events++] = ss_event_t{ctx->n_ops - 1, tensor_id, delta};
+  ctx->balance += delta;
+  ctx->stats.events_recorded++;
+  return SS_OK;
+}
+
+extern "C" int ss_trace_amend(ss_ctx *ctx, uint32_t op_idx, uint32_t dtype, uint32_t n_out) {
+  if (!ctx || op_idx >= ctx->n_ops) return SS_E_INVAL;
+  ss_op_t &o = ctx->ops[op_idx];
+  o.sig = (o.sig & 0xFFFF0000u) | (dtype & 0xFFu) | ((n_out & 0xFFu) << 8);
+  o.n_out = n_out;
+  return SS_OK;
+}
+
 extern "C" int ss_trace_view(ss_ctx *ctx, const ss_op_t **ops, uint32_t *n_ops, const ss_event_t **ev,
                              uint64_t *n_ev, int64_t *balance) {
   if (!ctx) return SS_E_INVAL;

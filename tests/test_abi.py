@@ -27,6 +27,20 @@ def test_every_declared_symbol_is_exported_and_bound():
         assert callable(getattr(B, n)), "binding lacks %s" % n
 
 
+def test_hook_library_exports_what_its_header_declares():
+    import paper_2509_11076_amd.torch_hook as H
+    text = open(os.path.join(ROOT, "include", "ss_torch_hook.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(ss_hook_[a-z_0-9]+)\s*\(", text)))
+    assert len(names) == 6 and names == sorted(H.EXPORTS)
+    lib = ctypes.CDLL(H.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n) and callable(getattr(H, n))
+    assert H.ss_hook_get_stats()["ops"] == 0          # nothing is hooked until ss_hook_install
+    with pytest.raises(H.B.SsError):
+        H.ss_hook_set_mode(7)
+
+
 def test_record_layouts_match_the_header_sizes():
     import paper_2509_11076_amd.binding as B
     import workloads as W

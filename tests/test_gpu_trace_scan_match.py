@@ -71,6 +71,26 @@ def test_trace_tokens_persist_across_iterations_and_errors(P, ctx):
     zero = op.copy(); zero["op_token"] = 0
     with pytest.raises(P.SsError):
         P.ss_trace_record(ctx, zero)
+    # events and output counts that arrive after the operator was recorded (dispatch hooks)
+    rec2 = oracle.TraceRecorder()
+    P.ss_trace_begin(ctx)
+    with pytest.raises(P.SsError) as e:
+        P.ss_trace_event(ctx, 0, 8)
+    assert e.value.code == P.SS_E_ORDER
+    for i, (nm, ph) in enumerate((("x", 0), ("z", 1), ("x", 2))):
+        P.ss_trace_record(ctx, P.ss_intern_op(ctx, nm, "y", 0, 0, ph))
+        rec2.record(rec2.intern(nm, "y", 0, 0, ph))
+        for tid, d in ((3 * i, 4096), (3 * i + 1, -512)):
+            P.ss_trace_event(ctx, tid, d)
+            rec2.event(tid, d)
+        P.ss_trace_amend(ctx, i, 4 + i, i + 1)
+        rec2.amend(i, 4 + i, i + 1)
+    l_ops, l_ev, bal = P.ss_trace_view(ctx)
+    assert np.array_equal(l_ops["sig"], rec2.ops_array()["sig"]) and np.array_equal(l_ops["n_out"], rec2.ops_array()["n_out"])
+    assert np.array_equal(l_ev.view(np.uint8), rec2.events_array().view(np.uint8)) and bal == rec2.balance()
+    with pytest.raises(P.SsError) as e:
+        P.ss_trace_amend(ctx, 3, 1, 1)
+    assert e.value.code == P.SS_E_INVAL
     small = make_ctx(P, staging_bytes=4096, max_ops=2, max_events=4)
     try:
         P.ss_trace_record(small, op); P.ss_trace_record(small, op)

@@ -106,6 +106,24 @@ def policy_events_for(tab, away):
     return sorted(pe, key=lambda e: (e[0], e[2] < 0))
 
 
+def test_late_events_and_amended_records_equal_recording_them_at_once():
+    """a hook learns an operator's outputs and its allocations after it recorded the operator: the
+    recorder then ends up exactly where recording everything at once would have put it"""
+    a, b = oracle.TraceRecorder(), oracle.TraceRecorder()
+    with pytest.raises(ValueError):
+        a.event(0, 8)                                  # no operator yet
+    a.record(a.intern("aten::mm", "s", 1, 2, 0), [(0, 0, 4096), (0, 1, 512)])
+    a.record(a.intern("aten::add", "s", 2, 1, 1), [(1, 0, -4096)])
+    b.record(b.intern("aten::mm", "s", 0, 0, 0))
+    b.event(0, 4096); b.event(1, 512)
+    b.amend(0, 1, 2)
+    b.record(b.intern("aten::add", "s", 0, 0, 1))
+    b.amend(1, 2, 1)
+    b.event(0, -4096)
+    assert a.ops == b.ops and a.events == b.events and b.balance() == 512
+    assert b.ops[1][2] >> 16 == 1                      # the phase survives an amendment
+
+
 def test_scan_equals_library_cumsum_and_balance():
     tr = W.build_trace(W.config_shape(2))
     base = 12345
