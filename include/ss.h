@@ -257,6 +257,16 @@ int ss_timeline_scan(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev,
                      int64_t base, int64_t budget, int64_t *timeline, int64_t *per_op,
                      int64_t *mre, ss_scan_result_t *res /* host, out */);
 
+/* k scans of the same trace, each under its own policy events, in one kernel launch (one
+ * workgroup per scan): candidate policies are checked against the memory limit together
+ * (Sec. 4.4 generates several policies and keeps one).  pev holds the k lists back to back,
+ * list c being pev[pe_start[c] .. pe_start[c+1]) (pe_start has k + 1 entries, pe_start[0] = 0);
+ * res has k entries; per_op (nullable) k * n_ops entries, scan c at per_op + c * n_ops.  Same
+ * definitions and errors as ss_timeline_scan; no timeline.  k <= 4096.  Host memory. */
+int ss_timeline_scan_batch(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev, const ss_event_t *pev,
+                           const uint64_t *pe_start, uint32_t k, uint32_t n_ops, int64_t base,
+                           int64_t budget, int64_t *per_op, ss_scan_result_t *res /* host, out */);
+
 /* ---- a3: sequence match (Sec. 3 Algo. 1, Sec. 5.1) ---------------------------- */
 
 /* (i) Similarity of the current sequence `cur` to `ref`: similar iff

@@ -137,6 +137,7 @@ _SIGS = {
     "ss_load_schedule": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P],
     "ss_greedy_policy": [_P, _P, C.c_uint32, _P, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_uint64,
                          _P, C.c_uint32, _P, C.POINTER(C.c_uint32), C.POINTER(C.c_int64)],
+    "ss_timeline_scan_batch": [_P, _P, C.c_uint64, _P, _P, C.c_uint32, C.c_uint32, C.c_int64, C.c_int64, _P, _P],
     "ss_trace_event": [_P, C.c_uint32, C.c_int64],
     "ss_trace_amend": [_P, C.c_uint32, C.c_uint32, C.c_uint32],
     "ss_align_sequence": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, _P, _P,
@@ -289,6 +290,27 @@ def ss_timeline_scan(ctx, events, policy_events, n_ops, base, budget, want_timel
                               tlp, _ptr(per_op), _ptr(mre), C.byref(res)), "ss_timeline_scan")
     return dict(timeline=tl, per_op=per_op, mre=mre, peak=res.peak, argpeak_op=res.argpeak_op,
                 n_over=res.n_over, final=res.final_total, sorted=res.sorted)
+
+
+def ss_timeline_scan_batch(ctx, events, policy_event_lists, n_ops, base, budget, want_per_op=False):
+    """policy_event_lists: one EVENT_DT array (or None) per candidate; returns a list of result dicts"""
+    ev = _arr(events, EVENT_DT)
+    lists = [np.zeros(0, EVENT_DT) if p is None else _arr(p, EVENT_DT) for p in policy_event_lists]
+    k = len(lists)
+    start = np.zeros(k + 1, dtype=np.uint64)
+    start[1:] = np.cumsum([len(p) for p in lists])
+    pev = np.concatenate(lists) if k and int(start[-1]) else np.zeros(0, EVENT_DT)
+    res = (ss_scan_result_t * max(1, k))()
+    per_op = np.zeros((k, n_ops), dtype=np.int64) if want_per_op else None
+    pp = None if per_op is None or per_op.size == 0 else per_op.ctypes.data_as(_P)
+    _ck(_lib.ss_timeline_scan_batch(ctx, _ptr(ev), 0 if ev is None else len(ev), _ptr(pev), _ptr(start), k, int(n_ops),
+                                    int(base), int(budget), pp, C.cast(res, _P)), "ss_timeline_scan_batch")
+    out = []
+    for c in range(k):
+        r = res[c]
+        out.append(dict(peak=r.peak, final=r.final_total, argpeak_op=r.argpeak_op, n_over=r.n_over,
+                        per_op=None if per_op is None else per_op[c]))
+    return out
 
 
 def ss_match_sequence(ctx, ref, cur, anchors, flags=0):

@@ -150,6 +150,50 @@ def test_scan_stress_trace_100k_events_spanning_many_chunks(P):
         P.ss_destroy(c)
 
 
+def test_scan_batch_of_candidate_policies_in_one_launch(P, ctx):
+    """many candidate policies against one trace: every scan of the batch equals the oracle's scan of
+    that candidate alone"""
+    tr = W.build_trace(W.config_shape(2))
+    tab = tr.tensors
+    keep = np.nonzero((tab["first_bwd_use"] != W.NONE_OP) & (tab["last_fwd_use"] != W.NONE_OP)
+                      & (tab["last_fwd_use"] + 1 < tab["first_bwd_use"]))[0]
+    rng = SplitMix64(4, 9)
+    cands = []
+    for c in range(19):
+        away = {}
+        for row in keep:
+            if rng.randint(19) < c:                   # candidate c swaps about c/19 of the tensors
+                lf, fb = int(tab["last_fwd_use"][row]), int(tab["first_bwd_use"][row])
+                tf = lf + rng.randint(fb - lf)
+                away[int(tab["tensor_id"][row])] = (tf, tf + 1 + rng.randint(fb - tf))
+        pe = policy_events_for(tab, away)
+        a = np.zeros(len(pe), dtype=W.EVENT_DT)
+        for i, e in enumerate(pe):
+            a[i] = e
+        cands.append(a)
+    no = oracle.timeline_scan(tr.events, None, tr.n_ops, 7, 0)
+    budget = int(no["peak"] * 0.7)
+    lib = P.ss_timeline_scan_batch(ctx, tr.events, cands, tr.n_ops, 7, budget, want_per_op=True)
+    assert len(lib) == 19
+    peaks = []
+    for c, a in enumerate(cands):
+        ora = oracle.timeline_scan(tr.events, a, tr.n_ops, 7, budget)
+        assert (lib[c]["peak"], lib[c]["argpeak_op"], lib[c]["n_over"], lib[c]["final"]) == \
+            (ora["peak"], ora["argpeak_op"], ora["n_over"], ora["final"]), c
+        assert np.array_equal(lib[c]["per_op"], ora["per_op"])
+        peaks.append(ora["peak"])
+    assert lib[0]["peak"] == no["peak"] and min(peaks) < 0.8 * no["peak"] and len(set(peaks)) > 10
+    # tiny traces, empty candidate lists, no candidates, an operator out of range in one candidate
+    tab, ev = tiny_trace(3)
+    one = P.ss_timeline_scan_batch(ctx, ev, [None, None], 12, 0, 1 << 40)
+    assert one[0]["peak"] == one[1]["peak"] == oracle.timeline_scan(ev, None, 12, 0, 1 << 40)["peak"]
+    assert P.ss_timeline_scan_batch(ctx, ev, [], 12, 0, 0) == []
+    bad = np.zeros(1, dtype=W.EVENT_DT); bad[0] = (12, 0, 8)
+    with pytest.raises(P.SsError) as e:
+        P.ss_timeline_scan_batch(ctx, ev, [None, bad], 12, 0, 0)
+    assert e.value.code == P.SS_E_INVAL
+
+
 def test_scan_unsorted_events_edge_cases(P, ctx):
     tab, ev = tiny_trace(5)
     perm = SplitMix64(4).permutation(len(ev))
