@@ -81,11 +81,14 @@ def main():
     ap.add_argument("--bpo", type=int, default=0,
                     help="link model: bytes the link moves per operator; 0 = link peak x no-swap step time / "
                          "operators per step, both measured in this run (Eq. 1 and Eq. 3 of the paper)")
-    ap.add_argument("--policy-mode", default="execute-all", choices=["execute-all", "link-aware", "generated"],
+    ap.add_argument("--policy-mode", default="execute-all", choices=["execute-all", "link-aware", "generated", "staged"],
                     help="execute-all: every tensor of the prescribed set is swapped even where the link "
                          "cannot hide it; link-aware: items whose swap-out cannot finish before their "
                          "backward use are dropped; generated: the library's policy generator (Sec. 4) picks "
-                         "the swap set for a memory limit (configurations 2 and 3) and its own points are kept")
+                         "the swap set for a memory limit (configurations 2 and 3) and its own points are kept; "
+                         "staged: the loop of Algo. 1 (WarmUp without swapping, GenPolicy with a new generated "
+                         "policy per iteration, Stable with the fastest of them), --steps iterations after it "
+                         "settles")
     ap.add_argument("--timing", default="link-model", choices=["link-model", "policy-points"],
                     help="--policy-mode generated: release and pre-trigger points from the operator-granular link "
                          "model fed with per-phase operator times measured in this run (default), or the "
@@ -138,6 +141,45 @@ def main():
                           "avg_pack_launch_ms": round(sum(out_ms) / len(out_ms), 4),
                           "bytes_per_pack_launch": run.bytes_each_way // nob}), flush=True)
         run.close()
+        return
+
+    if args.policy_mode == "staged":
+        from workloads.harness import StagedRun
+        from workloads import transformer as T
+        if args.config not in (2, 3):
+            sys.exit("--policy-mode staged: configurations 2 and 3 only")
+        shape = T.config_shape(args.config)
+        tr0 = T.build_trace(shape)
+        link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
+        run = StagedRun(B, torch, lambda it: tr0, limit_frac=args.limit_frac, link_bytes_per_s=link,
+                        g_fwd=shape.layers, g_bwd=shape.layers, min_bytes=1 << 16, flags=B.SS_CFG_TIMING)
+        log = []
+        for it in range(9 + args.steps):
+            e = run.iteration(it)
+            e.pop("result")
+            log.append(e)
+            print("iteration %d stage %d: %.1f ms, %d tensors, %.0f MB each way" %
+                  (it, e["stage"], e["ms"], e["n_items"], e["bytes"] / 1e6), file=sys.stderr, flush=True)
+        run.close()
+        stable = [e for e in log if e["stage"] == 2]
+        warm = [e for e in log if e["stage"] == 0][1:]
+        t_stable = sum(e["ms"] for e in stable) / len(stable) * 1e-3
+        t_warm = sum(e["ms"] for e in warm) / len(warm) * 1e-3
+        print(json.dumps({
+            "metric": "swap GB/s (D2H+H2D) as % of host-link peak; step-time overhead vs no-swap",
+            "value": round(2 * stable[0]["bytes"] / t_stable / 1e9, 3), "unit": "GB/s", "n_gpus": 1,
+            "steps": len(stable), "warmup": 9, "ms_per_step": round(t_stable * 1e3, 3), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "config %d trace under the stage loop of Algo. 1 (m = 2, n = 5): WarmUp without "
+                                   "swapping, GenPolicy with one generated policy per iteration, Stable with the "
+                                   "fastest; memory limit %.2f x the no-swap peak" % (args.config, args.limit_frac),
+                       "policy_mode": "staged", "chosen_candidate": stable[0]["candidate"],
+                       "bytes_each_way": stable[0]["bytes"], "tensors_swapped": stable[0]["n_items"],
+                       "peak_bytes_with_policy": stable[0]["peak"]},
+            "step_time": {"warmup_noswap_ms": round(t_warm * 1e3, 3), "stable_ms": round(t_stable * 1e3, 3),
+                          "overhead_vs_noswap_pct": round(100 * (t_stable / t_warm - 1), 1)},
+            "iterations": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in e.items()} for e in log],
+            "link_peak_measured": {k: round(v, 2) for k, v in bw.items()}}), flush=True)
         return
 
     def timed(run, fn, steps, warmup):

@@ -117,3 +117,52 @@ def test_generated_policy_executes_with_unchanged_results(env):
     assert info["n_over_with_policy"] == 0 and plan["scan"]["peak"] == info["peak_with_policy"] <= limit
     assert plan["applied"]["n_dropped"] == 0 and arena_bytes <= limit * 1.1 < i0["arena"]
     assert st["bytes_out"] == st["bytes_in"] == 2 * sum(it[8] for it in items)
+
+
+@pytest.mark.timeout(600)
+def test_stage_loop_generates_selects_and_regenerates(env):
+    """Algo. 1 end to end (m = 2, n = 5): three WarmUp iterations without swapping, six GenPolicy
+    iterations each with a freshly generated policy, Stable with the fastest of them; a changed
+    operator sequence sends the loop back to WarmUp and it settles again.  Every iteration's compute
+    results equal those of the same trace without swapping."""
+    B, torch = env
+    from workloads.harness import StagedRun
+    from workloads.compute import SyntheticCompute
+    from workloads.arena import place_tensors
+    shape_a = W.ModelShape("naive", 512, 8, 8, 512, 1, 4)
+    shape_b = W.ModelShape("naive", 512, 8, 8, 512, 1, 4, experts0=2)      # two more operators per layer
+
+    def trace_of(it):
+        return W.build_trace(shape_a if it < 12 else shape_b)
+    run = StagedRun(B, torch, trace_of, limit_frac=0.7, link_bytes_per_s=57e9, g_fwd=8, g_bwd=8, min_bytes=1 << 16,
+                    flags=B.SS_CFG_POISON_FREE)
+    big = torch.empty(int(place_tensors(trace_of(12).tensors) * 1.2), dtype=torch.uint8, device="cuda")
+    expect = {}
+    for key, it in (("a", 0), ("b", 12)):
+        tr = trace_of(it)
+        place_tensors(tr.tensors)
+        comp = SyntheticCompute(tr, big)
+        for i in range(tr.n_ops):
+            comp.run_op(i)
+        expect[key] = comp.result()
+    try:
+        log = [run.iteration(it) for it in range(23)]
+    finally:
+        run.close()
+    W_, G, S = 0, 1, 2
+    assert [e["stage"] for e in log] == [W_] * 3 + [G] * 6 + [S] * 4 + [W_] * 3 + [G] * 6 + [S]
+    assert [e["similar"] for e in log] == [True] * 12 + [False] + [True] * 10
+    for e in log:
+        chk, grad = e["result"]
+        want = expect["a" if e["it"] < 12 else "b"]
+        assert np.array_equal(chk, want[0]) and np.array_equal(grad, want[1]), e["it"]
+    assert all(e["bytes"] == 0 for e in log if e["stage"] == W_)
+    assert all(e["bytes"] > 0 and e["unmatched"] == 0 for e in log if e["stage"] != W_ and e["it"] != 12)
+    # iteration 12 ran the old policy on the new sequence: re-anchored by the aligner, still correct
+    assert log[12]["bytes"] > 0
+    # Stable keeps the fastest of the six candidates of its own GenPolicy stage
+    for first_g, first_s in ((3, 9), (16, 22)):
+        times = [log[i]["ms"] for i in range(first_g, first_g + 6)]
+        assert log[first_s]["candidate"] == int(np.argmin(times))
+    no_a = oracle.timeline_scan(trace_of(0).events, None, trace_of(0).n_ops, 0, 0)["peak"]
+    assert all(e["peak"] <= 0.7 * no_a * 1.02 for e in log[3:12])

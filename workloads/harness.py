@@ -268,3 +268,139 @@ class VaryingRun:
             comp.run_op(i)
         run_iteration(self.exec_ctx, tr.n_ops, ap["actions"], run_op, batch_lists(ap["actions"]))
         return comp.result(), used, ap
+
+
+class StagedRun:
+    """The whole loop of Sec. 3 - Sec. 5 driven by the stage machine of Algo. 1.
+
+    WarmUp: the iteration runs without swapping (no policy is trusted yet).  GenPolicy: every
+    iteration a new policy is generated from the previous iteration's trace and its measured time
+    (Eq. 1), re-anchored on the current sequence, executed and timed.  Stable: the fastest of the
+    generated policies is kept (Sec. 6: with n = 5 several policies are generated and the best is
+    selected) and re-anchored every iteration.  A sequence that is no longer similar sends the
+    machine back to WarmUp and the candidates are dropped.
+
+    trace_of(it) -> Trace gives iteration it's operators (what a dispatch hook would have recorded).
+    """
+    WARMUP, GENPOLICY, STABLE = 0, 1, 2
+
+    def __init__(self, B, torch, trace_of, limit_frac, link_bytes_per_s, g_fwd, g_bwd, min_bytes=0, c_num=1,
+                 c_den=1, seed=2509, flags=0, gemm_scale=1.0, match_flags=None, staging_bytes=None,
+                 arena_bytes=None):
+        self.B, self.torch, self.trace_of = B, torch, trace_of
+        self.limit_frac, self.link = limit_frac, link_bytes_per_s
+        self.gen = dict(g_fwd=g_fwd, g_bwd=g_bwd, c_num=c_num, c_den=c_den, min_bytes=min_bytes)
+        self.seed, self.gemm_scale = seed, gemm_scale
+        self.match_flags = B.SS_MATCH_ALIGN if match_flags is None else match_flags
+        tr0 = trace_of(0)
+        self.arena_cap = arena_bytes or int(place_tensors(tr0.tensors) * 1.3)
+        self.arena = torch.empty(self.arena_cap, dtype=torch.uint8, device="cuda")
+        self.cfg = B.ss_config_default()
+        self.cfg.flags = flags | B.SS_CFG_POLICY_POINTS | B.SS_CFG_KEEP_LATE
+        self.cfg.max_ops = max(65536, 2 * tr0.n_ops)
+        self.cfg.max_events = max(1 << 20, 4 * len(tr0.events))
+        self.cfg.staging_bytes = staging_bytes or int(0.6 * self.arena_cap)
+        self.ctx = B.ss_create(self.cfg)
+        self.stream = torch.cuda.current_stream()
+        self.stage = self.WARMUP
+        self.prev = None            # (trace, ops, ms) of the previous iteration
+        self.candidates = []        # dicts(policy, ref_ops, ms, info)
+        self.best = None
+        self.log = []
+
+    def close(self):
+        if self.ctx is not None:
+            self.B.ss_destroy(self.ctx)
+            self.ctx = None
+        self.arena = None
+
+    def _intern(self, tr):
+        B = self.B
+        return np.stack([B.ss_intern_op(self.ctx, tr.op_name[i], tr.op_stack[i], tr.op_dtype[i],
+                                        len(tr.op_outputs[i]), tr.op_phase[i]) for i in range(tr.n_ops)])
+
+    def _generate(self):
+        """a policy from the previous iteration's trace, Eq. 1 fed with its measured time"""
+        B = self.B
+        tr, ops, ms = self.prev
+        no = B.ss_timeline_scan(self.ctx, tr.events, None, tr.n_ops, 0, 1 << 62, want_per_op=False)
+        limit = int(self.limit_frac * no["peak"])
+        self.cfg.link_bytes_per_op = max(1, int(self.link * ms * 1e-3 / max(1, tr.n_ops)))
+        # the generator reads the link share from the context: a short-lived one with this iteration's value
+        cfg = B.ss_config_default()
+        cfg.staging_bytes = 0
+        cfg.link_bytes_per_op = self.cfg.link_bytes_per_op
+        cfg.max_ops, cfg.max_events = self.cfg.max_ops, self.cfg.max_events
+        g = B.ss_create(cfg)
+        try:
+            pol, info = B.ss_generate_policy(g, ops, tr.tensors, tr.events, 0, limit, **self.gen)
+        finally:
+            B.ss_destroy(g)
+        return dict(policy=pol, ref_ops=ops, ms=None, info=info, limit=limit,
+                    link_bytes_per_op=cfg.link_bytes_per_op)
+
+    def iteration(self, it):
+        from .compute import SyntheticCompute
+        from paper_2509_11076_amd.executor import run_iteration, batch_lists
+        B, torch = self.B, self.torch
+        tr = self.trace_of(it)
+        ops = self._intern(tr)
+        stage = self.stage
+        cand = None
+        if stage == self.GENPOLICY and self.prev is not None:
+            cand = self._generate()
+            self.candidates.append(cand)
+        elif stage == self.STABLE:
+            if self.best is None:
+                self.best = min(self.candidates, key=lambda c: c["ms"])
+            cand = self.best
+        unmatched = 0
+        if cand is not None and len(cand["policy"]):
+            pol = cand["policy"]
+            anchors = np.zeros(len(pol), dtype=ANCHOR_DT)
+            anchors["ref_op"] = pol["ref_op"]; anchors["out_slot"] = pol["out_slot"]
+            m = B.ss_match_sequence(self.ctx, cand["ref_ops"], ops, anchors, flags=self.match_flags)
+            new_idx, unmatched = m["new_idx"], int(m["n_unmatched"])
+        else:
+            pol, new_idx = np.zeros(0, B.POLICY_DT), np.zeros(0, np.int32)
+        # placement needs the release / pre-trigger points: a dry application first
+        place_tensors(tr.tensors)
+        dry = B.ss_apply_policy(self.ctx, pol, new_idx, tr.tensors, allow_nomem=True)
+        res = dry["resolved"]
+        kept = (res["flags"] & (B.SS_F_UNMATCHED | B.SS_F_ORDER)) == 0
+        swapped = {int(r["tensor_id"]): (int(r["t_free"]), int(r["t_in"])) for r in res[kept]}
+        used = place_tensors(tr.tensors, swapped=swapped, capacity=self.arena_cap)
+        B.ss_bind(self.ctx, self.arena.data_ptr(), self.arena_cap, self.stream.cuda_stream)
+        ap = B.ss_apply_policy(self.ctx, pol, new_idx, tr.tensors)
+        sc = B.ss_timeline_scan(self.ctx, tr.events, ap["policy_events"], tr.n_ops, 0, 1 << 62, want_per_op=False)
+        comp = SyntheticCompute(tr, self.arena, seed=self.seed, gemm_scale=self.gemm_scale)
+        comp.mark_swapped(swapped.keys())
+        rec = B.ss_trace_record_prepared(self.ctx, ops, tr.events)
+        lists = batch_lists(ap["actions"])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.ss_trace_begin(self.ctx)
+
+        def run_op(i):
+            rec(i)
+            comp.run_op(i)
+        run_iteration(self.ctx, tr.n_ops, ap["actions"], run_op, lists)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
+        if stage == self.GENPOLICY and cand is not None:
+            cand["ms"] = ms
+        cand_no = None if cand is None else [i for i, c in enumerate(self.candidates) if c is cand][0]
+        # Algo. 1: the finished iteration's sequence against the previous one decides the next stage
+        prev_ops = self.prev[1] if self.prev is not None else ops
+        v = B.ss_match_sequence(self.ctx, prev_ops, ops, None, flags=B.SS_MATCH_STEP_STAGE)
+        if not v["similar"]:
+            self.candidates, self.best = [], None
+        self.stage = int(v["stage"])
+        self.prev = (tr, ops, ms)
+        entry = dict(it=it, stage=stage, next_stage=self.stage, similar=bool(v["similar"]), ms=ms,
+                     n_items=int(ap["n_kept"]), bytes=int(ap["bytes_out"]), unmatched=unmatched, peak=int(sc["peak"]),
+                     arena_used=int(used),
+                     candidate=cand_no,
+                     result=comp.result())
+        self.log.append(entry)
+        return entry
