@@ -222,11 +222,15 @@ class VaryingRun:
         B = self.B
         tr = T.build_trace(self.shape, seed=self.seed, iteration=it, perturb=self.perturb if it else None)
         ops = self.intern(tr)
+        t0 = time.perf_counter()
         m = B.ss_match_sequence(self.plan_ctx, self.ref_ops, ops, self.anchors,
                                 flags=B.SS_MATCH_STEP_STAGE | self.match_flags)
+        t1 = time.perf_counter()
         ap = B.ss_apply_policy(self.plan_ctx, self.ref_policy, m["new_idx"], tr.tensors, allow_nomem=True)
+        t2 = time.perf_counter()
         sc = B.ss_timeline_scan(self.plan_ctx, tr.events, ap["policy_events"], tr.n_ops, 0, self.budget,
                                 want_per_op=False)
+        t3 = time.perf_counter()
         # the kept items in this iteration's coordinates
         res = ap["resolved"]
         kept = (res["flags"] & (B.SS_F_UNMATCHED | B.SS_F_ORDER)) == 0
@@ -244,8 +248,11 @@ class VaryingRun:
                                 allow_nomem=True)
         sc2 = B.ss_timeline_scan(self.plan_ctx, tr.events, ap2["policy_events"], tr.n_ops, 0, self.budget,
                                  want_per_op=False)
+        t4 = time.perf_counter()
         return dict(trace=tr, ops=ops, match=m, applied_ref=ap, scan_ref=sc, carried=cur, final=final,
-                    topped=topped, applied=ap2, scan=sc2)
+                    topped=topped, applied=ap2, scan=sc2,
+                    host_ms=dict(match=(t1 - t0) * 1e3, apply=(t2 - t1) * 1e3, scan=(t3 - t2) * 1e3,
+                                 top_up_apply_scan=(t4 - t3) * 1e3))
 
     def execute(self, p):
         """place this iteration's tensors, bind, load the schedule, run the operators with swapping"""
