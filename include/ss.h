@@ -384,6 +384,17 @@ int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss
                        const ss_gen_params_t *params, ss_policy_item_t *policy_out, uint32_t *n_policy,
                        ss_gen_result_t *res /* host, out */);
 
+/* Several parameter sets at once (Sec. 4.4 / Sec. 6: several policies are generated and one is
+ * kept): one policy per set, all of them scanned with their own release / pre-trigger points in one
+ * batched launch, and the best returned: no operator over the limit first (else fewest such
+ * operators), then fewest LATE items, then fewest bytes, then the lowest index.  Sets for which the
+ * generator runs out of candidates are skipped; SS_E_INFEASIBLE if that happens to all.
+ * *chosen receives the index of the winning set, res its result. */
+int ss_generate_policy_best(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
+                            uint32_t n_tensors, const ss_event_t *ev, uint64_t n_ev, int64_t base, int64_t limit,
+                            const ss_gen_params_t *params, uint32_t n_params, ss_policy_item_t *policy_out,
+                            uint32_t *n_policy, uint32_t *chosen, ss_gen_result_t *res /* host, out */);
+
 /* ---- a5 / a6 / a7: swap-out, swap-in, release and wait (Sec. 5.2) --------------- */
 
 /* Enqueue swap-out batch `batch`: the swap-out stream waits (on the device) for

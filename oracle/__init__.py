@@ -46,5 +46,5 @@ from .policy import (link_timing, apply_policy, greedy_policy, schedule_check,
                      K_IN, K_WAIT_IN, K_OUT, K_FREE,
                      F_UNMATCHED, F_ORDER, F_LATE, F_RESIZED, F_FORCED, Infeasible)
 from .swap import swap_out, swap_in, SparseArena
-from .generator import generate_policy, logical_layers
+from .generator import generate_policy, generate_policy_best, logical_layers
 from .align import align, align_anchors, lcs_table, LEVEL_ALIGN

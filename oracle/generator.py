@@ -164,3 +164,31 @@ def generate_policy(tensors, per_op_memory, phases, limit, bpo, g_fwd, g_bwd, c_
                       int(t["last_fwd_use"]), c["t_free"], c["t_in"], int(t["first_bwd_use"]), int(t["nbytes"])))
     return items, dict(rounds=rounds, residual=dict(mrl),
                        layers=[(L["first"], L["end"], L["type"], L["remaining"]) for L in layers])
+
+
+def generate_policy_best(tensors, events, n_ops, base, phases, limit, bpo, param_sets):
+    """Several parameter sets (dicts g_fwd, g_bwd, c_num, c_den, min_bytes): one policy each, each
+    scanned with its own points, the best kept: no operator over the limit first (else fewest such
+    operators), then fewest LATE items, then fewest bytes, then the lowest index.  Infeasible sets
+    are skipped.  Returns (items, chosen index, dict(peak, n_over, n_late, bytes))."""
+    from .timeline import timeline_scan
+    mem = timeline_scan(events, None, n_ops, base, limit)["per_op"]
+    best = None
+    for c, p in enumerate(param_sets):
+        try:
+            items, _ = generate_policy(tensors, mem, phases, limit, bpo, p["g_fwd"], p["g_bwd"], p.get("c_num", 1),
+                                       p.get("c_den", 1), p.get("min_bytes", 0))
+        except Infeasible:
+            continue
+        pe = []
+        for it in items:
+            pe += [(it[5], it[2], -it[8]), (it[6], it[2], it[8])]
+        pe.sort(key=lambda e: e[0])
+        sc = timeline_scan(events, pe, n_ops, base, limit)
+        key = (sc["n_over"], sum(1 for it in items if it[3] & F_LATE), sum(it[8] for it in items), c)
+        if best is None or key < best[0]:
+            best = (key, items, c, sc)
+    if best is None:
+        raise Infeasible("every parameter set runs out of candidates")
+    key, items, c, sc = best
+    return items, c, dict(peak=sc["peak"], n_over=key[0], n_late=key[1], bytes=key[2])

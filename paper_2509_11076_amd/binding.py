@@ -144,6 +144,9 @@ _SIGS = {
                           C.POINTER(ss_align_result_t)],
     "ss_generate_policy": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint64, C.c_int64, C.c_int64,
                            C.POINTER(ss_gen_params_t), _P, C.POINTER(C.c_uint32), C.POINTER(ss_gen_result_t)],
+    "ss_generate_policy_best": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint64, C.c_int64, C.c_int64,
+                                _P, C.c_uint32, _P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                C.POINTER(ss_gen_result_t)],
     "ss_swap_out": [_P, C.c_uint32],
     "ss_swap_in": [_P, C.c_uint32],
     "ss_sync": [_P, C.c_uint32, C.c_uint32],
@@ -416,6 +419,24 @@ def ss_generate_policy(ctx, ops, tensors, events, base, limit, g_fwd, g_bwd, c_n
                                 int(limit), C.byref(prm), _ptr(out), C.byref(n), C.byref(res)),
         "ss_generate_policy")
     return out[:n.value], {f: getattr(res, f) for f, _ in ss_gen_result_t._fields_}
+
+
+def ss_generate_policy_best(ctx, ops, tensors, events, base, limit, param_sets):
+    """param_sets: list of dicts(g_fwd, g_bwd[, c_num, c_den, min_bytes]); returns (policy, result, chosen)"""
+    ops = _arr(ops, OP_DT)
+    tab = _arr(tensors, TENSOR_DT)
+    ev = _arr(events, EVENT_DT)
+    prm = (ss_gen_params_t * max(1, len(param_sets)))()
+    for i, d in enumerate(param_sets):
+        prm[i] = ss_gen_params_t(int(d["g_fwd"]), int(d["g_bwd"]), int(d.get("c_num", 1)), int(d.get("c_den", 1)),
+                                 int(d.get("min_bytes", 0)))
+    out = np.zeros(len(tab), dtype=POLICY_DT)
+    n, chosen = C.c_uint32(len(out)), C.c_uint32(0)
+    res = ss_gen_result_t()
+    _ck(_lib.ss_generate_policy_best(ctx, _ptr(ops), len(ops), _ptr(tab), len(tab), _ptr(ev), len(ev), int(base),
+                                     int(limit), C.cast(prm, _P), len(param_sets), _ptr(out), C.byref(n),
+                                     C.byref(chosen), C.byref(res)), "ss_generate_policy_best")
+    return out[:n.value], {f: getattr(res, f) for f, _ in ss_gen_result_t._fields_}, chosen.value
 
 
 def ss_swap_out(ctx, batch):

@@ -57,27 +57,17 @@ void build_layers(const std::vector<uint32_t> &phase, uint32_t g_fwd, uint32_t g
 
 }  // namespace
 
-extern "C" int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
-                                  uint32_t n_tensors, const ss_event_t *ev, uint64_t n_ev, int64_t base,
-                                  int64_t limit, const ss_gen_params_t *params, ss_policy_item_t *policy_out,
-                                  uint32_t *n_policy, ss_gen_result_t *res) {
-  if (!ctx || !params || !n_policy || !res || (n_ops && !ops) || (n_tensors && !tensors)) return SS_E_INVAL;
-  if (*n_policy && !policy_out) return SS_E_INVAL;
+// The generator proper: per_op is the memory without swaps (n_ops entries).  Fills `items` in commit
+// order and the counters of `res` that do not need a scan.
+static int generate_core(uint64_t bpo, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
+                         uint32_t n_tensors, const std::vector<int64_t> &per_op, int64_t limit,
+                         const ss_gen_params_t *params, std::vector<ss_policy_item_t> &items,
+                         std::vector<ss_event_t> &pe, ss_gen_result_t *res) {
   if (params->c_den == 0 || params->g_fwd == 0 || params->g_bwd == 0) return SS_E_INVAL;
-  const uint64_t bpo = ctx->cfg.link_bytes_per_op;
-  if ((u128)bpo * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
-  std::memset(res, 0, sizeof(*res));
-
-  // memory without swaps -> memory reduction list (Sec. 4.2)
-  std::vector<int64_t> per_op(n_ops), excess(n_ops, 0);
-  ss_scan_result_t sr;
-  int rc = ss_timeline_scan(ctx, ev, n_ev, nullptr, 0, n_ops, base, limit, nullptr, per_op.data(), nullptr, &sr);
-  if (rc != SS_OK) return rc;
-  res->peak_no_swap = sr.peak;
+  std::vector<int64_t> excess(n_ops, 0);
   uint32_t n_entries = 0;
   for (uint32_t t = 0; t < n_ops; ++t)
     if (per_op[t] > limit) { excess[t] = per_op[t] - limit; ++n_entries; }
-
   std::vector<uint32_t> phase(n_ops);
   for (uint32_t i = 0; i < n_ops; ++i) phase[i] = std::min<uint32_t>(ops[i].sig >> 16, 2u);
   std::vector<Layer> layers;
@@ -190,8 +180,8 @@ extern "C" int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_op
     c.t_free = std::min<uint32_t>(std::max<uint32_t>(end_op, t.last_fwd_use + 1), c.t_in - 1);
   }
 
-  if (chosen.size() > *n_policy) return SS_E_CAPACITY;
-  std::vector<ss_event_t> pe;
+  items.clear();
+  pe.clear();
   pe.reserve(2 * chosen.size());
   for (size_t i = 0; i < chosen.size(); ++i) {
     const Chosen &c = chosen[i];
@@ -202,19 +192,91 @@ extern "C" int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_op
     p.flags = c.late ? SS_F_LATE : 0;
     p.t_out = t.last_fwd_use; p.t_free = c.t_free; p.t_in = c.t_in; p.t_use = t.first_bwd_use;
     p.nbytes = t.nbytes;
-    policy_out[i] = p;
+    items.push_back(p);
     res->bytes += t.nbytes;
     res->n_late += c.late;
     pe.push_back(ss_event_t{c.t_free, t.tensor_id, -(int64_t)t.nbytes});
     pe.push_back(ss_event_t{c.t_in, t.tensor_id, (int64_t)t.nbytes});
   }
-  *n_policy = (uint32_t)chosen.size();
   res->n_items = (uint32_t)chosen.size();
-  // what the release points really give: scan with the policy's own events
   std::stable_sort(pe.begin(), pe.end(), [](const ss_event_t &a, const ss_event_t &b) { return a.op_idx < b.op_idx; });
-  rc = ss_timeline_scan(ctx, ev, n_ev, pe.data(), pe.size(), n_ops, base, limit, nullptr, nullptr, nullptr, &sr);
+  return SS_OK;
+}
+
+extern "C" int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
+                                  uint32_t n_tensors, const ss_event_t *ev, uint64_t n_ev, int64_t base,
+                                  int64_t limit, const ss_gen_params_t *params, ss_policy_item_t *policy_out,
+                                  uint32_t *n_policy, ss_gen_result_t *res) {
+  uint32_t chosen = 0;
+  return ss_generate_policy_best(ctx, ops, n_ops, tensors, n_tensors, ev, n_ev, base, limit, params, 1, policy_out,
+                                 n_policy, &chosen, res);
+}
+
+extern "C" int ss_generate_policy_best(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
+                                       uint32_t n_tensors, const ss_event_t *ev, uint64_t n_ev, int64_t base,
+                                       int64_t limit, const ss_gen_params_t *params, uint32_t n_params,
+                                       ss_policy_item_t *policy_out, uint32_t *n_policy, uint32_t *chosen,
+                                       ss_gen_result_t *res) {
+  if (!ctx || !params || !n_params || !n_policy || !chosen || !res || (n_ops && !ops) || (n_tensors && !tensors))
+    return SS_E_INVAL;
+  if (*n_policy && !policy_out) return SS_E_INVAL;
+  const uint64_t bpo = ctx->cfg.link_bytes_per_op;
+  if ((u128)bpo * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
+  for (uint32_t c = 0; c < n_params; ++c)
+    if (params[c].c_den == 0 || params[c].g_fwd == 0 || params[c].g_bwd == 0) return SS_E_INVAL;
+  std::memset(res, 0, sizeof(*res));
+
+  // memory without swaps -> memory reduction list (Sec. 4.2)
+  std::vector<int64_t> per_op(n_ops);
+  ss_scan_result_t sr;
+  int rc = ss_timeline_scan(ctx, ev, n_ev, nullptr, 0, n_ops, base, limit, nullptr, per_op.data(), nullptr, &sr);
   if (rc != SS_OK) return rc;
-  res->peak_with_policy = sr.peak;
-  res->n_over_with_policy = sr.n_over;
+  const int64_t peak_no_swap = sr.peak;
+
+  struct Cand { std::vector<ss_policy_item_t> items; std::vector<ss_event_t> pe; ss_gen_result_t r; int rc; };
+  std::vector<Cand> cands(n_params);
+  std::vector<ss_event_t> all_pe;
+  std::vector<uint64_t> pe_start(n_params + 1, 0);
+  bool any = false;
+  for (uint32_t c = 0; c < n_params; ++c) {
+    std::memset(&cands[c].r, 0, sizeof(ss_gen_result_t));
+    cands[c].rc = generate_core(bpo, ops, n_ops, tensors, n_tensors, per_op, limit, &params[c], cands[c].items,
+                                cands[c].pe, &cands[c].r);
+    if (cands[c].rc != SS_OK && cands[c].rc != SS_E_INFEASIBLE) return cands[c].rc;
+    if (cands[c].rc != SS_OK) cands[c].pe.clear();
+    any = any || cands[c].rc == SS_OK;
+    all_pe.insert(all_pe.end(), cands[c].pe.begin(), cands[c].pe.end());
+    pe_start[c + 1] = all_pe.size();
+  }
+  if (!any) return SS_E_INFEASIBLE;
+  // what the release points really give: every candidate scanned with its own events, one launch
+  std::vector<ss_scan_result_t> scans(n_params);
+  rc = ss_timeline_scan_batch(ctx, ev, n_ev, all_pe.data(), pe_start.data(), n_params, n_ops, base, limit, nullptr,
+                              scans.data());
+  if (rc != SS_OK) return rc;
+  int best = -1;
+  for (uint32_t c = 0; c < n_params; ++c) {
+    if (cands[c].rc != SS_OK) continue;
+    cands[c].r.peak_no_swap = peak_no_swap;
+    cands[c].r.peak_with_policy = scans[c].peak;
+    cands[c].r.n_over_with_policy = scans[c].n_over;
+    if (best < 0) { best = (int)c; continue; }
+    const ss_gen_result_t &x = cands[c].r, &y = cands[best].r;
+    // within the limit first, then fewer items that cost latency, then fewer bytes over the link
+    const bool xf = x.n_over_with_policy == 0, yf = y.n_over_with_policy == 0;
+    if (xf != yf) { if (xf) best = (int)c; continue; }
+    if (!xf && x.n_over_with_policy != y.n_over_with_policy) {
+      if (x.n_over_with_policy < y.n_over_with_policy) best = (int)c;
+      continue;
+    }
+    if (x.n_late != y.n_late) { if (x.n_late < y.n_late) best = (int)c; continue; }
+    if (x.bytes < y.bytes) best = (int)c;
+  }
+  const Cand &w = cands[(size_t)best];
+  if (w.items.size() > *n_policy) return SS_E_CAPACITY;
+  if (!w.items.empty()) std::memcpy(policy_out, w.items.data(), w.items.size() * sizeof(ss_policy_item_t));
+  *n_policy = (uint32_t)w.items.size();
+  *chosen = (uint32_t)best;
+  *res = w.r;
   return SS_OK;
 }

@@ -208,3 +208,46 @@ def test_generated_policy_on_varying_sequence(P, keep):
             assert ora["n_dropped"] == sum(1 for r in ora["resolved"] if r[3] & (oracle.F_UNMATCHED | oracle.F_ORDER))
     finally:
         P.ss_destroy(c)
+
+
+def test_best_of_several_parameter_sets_with_one_batched_scan(P):
+    """ss_generate_policy_best against the oracle's selection: the hand-worked trace at three link
+    speeds, and the 1.3B shape over a grid of layer counts and values of C"""
+    phases = [0] * 12 + [1] * 12
+    tab = table([(0, 1, 22, 23, 250), (1, 2, 20, 21, 100), (9, 10, 13, 14, 40), (8, 8, W.NONE_OP, 15, 300)])
+    ev = W.transformer.events_of(tab)
+    ops = ops_with_phases(phases)
+    cases = [(100, [dict(g_fwd=4, g_bwd=4, min_bytes=1000), dict(g_fwd=1, g_bwd=1), dict(g_fwd=4, g_bwd=4),
+                    dict(g_fwd=4, g_bwd=4, c_num=0)], 2),
+             (80, [dict(g_fwd=4, g_bwd=4), dict(g_fwd=3, g_bwd=3), dict(g_fwd=3, g_bwd=4)], 1),
+             (90, [dict(g_fwd=4, g_bwd=6), dict(g_fwd=4, g_bwd=4)], 1)]
+    for bpo, sets, want in cases:
+        c = make_ctx(P, staging_bytes=4096, link_bytes_per_op=bpo)
+        try:
+            items, chosen, info = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, bpo, sets)
+            pol, res, got = P.ss_generate_policy_best(c, ops, tab, ev, 0, 400, sets)
+            assert got == chosen == want and rows_of(pol) == items
+            assert (res["peak_with_policy"], res["n_over_with_policy"], res["n_late"], res["bytes"]) == \
+                (info["peak"], info["n_over"], info["n_late"], info["bytes"])
+            with pytest.raises(P.SsError) as e:
+                P.ss_generate_policy_best(c, ops, tab, ev, 0, 400, [dict(g_fwd=4, g_bwd=4, min_bytes=1000)])
+            assert e.value.code == P.SS_E_INFEASIBLE
+        finally:
+            P.ss_destroy(c)
+    tr = W.build_trace(W.config_shape(2))
+    no = oracle.timeline_scan(tr.events, None, tr.n_ops, 0, 0)
+    sets = [dict(g_fwd=g, g_bwd=g2, c_num=cn, c_den=2, min_bytes=1 << 16)
+            for g in (6, 12, 24, 48) for g2 in (12, 24) for cn in (0, 2, 8)]
+    for frac, bpo in ((0.8, 8 << 20), (0.6, 32 << 20)):
+        limit = int(no["peak"] * frac)
+        c = make_ctx(P, staging_bytes=4096, link_bytes_per_op=bpo)
+        try:
+            ops, ev, _ = record_lib(P, c, tr)
+            items, chosen, info = oracle.generate_policy_best(tr.tensors, ev, tr.n_ops, 0, list(tr.op_phase), limit,
+                                                              bpo, sets)
+            pol, res, got = P.ss_generate_policy_best(c, ops, tr.tensors, ev, 0, limit, sets)
+            assert got == chosen and rows_of(pol) == items and len(items) > 5
+            assert (res["peak_with_policy"], res["n_over_with_policy"], res["n_late"], res["bytes"]) == \
+                (info["peak"], info["n_over"], info["n_late"], info["bytes"])
+        finally:
+            P.ss_destroy(c)

@@ -177,3 +177,34 @@ def test_generated_points_survive_policy_application():
     shifted["first_bwd_use"] = np.where(shifted["first_bwd_use"] == W.NONE_OP, W.NONE_OP, shifted["first_bwd_use"] + 3)
     ap2 = oracle.apply_policy(pol, pol["ref_op"].astype(np.int64) + 3, shifted, 256 << 20, policy_points=True)
     assert [r[4:8] for r in ap2["resolved"]] == [tuple(x + 3 for x in r[4:8]) for r in ap["resolved"]]
+
+
+def test_best_of_several_parameter_sets():
+    """the selection rule on the hand-worked trace: sets that run out of candidates are skipped, a
+    set that keeps the limit beats one that does not, then fewer LATE items, then fewer bytes"""
+    phases = [0] * 12 + [1] * 12
+    tab = table([(0, 1, 22, 23, 250), (1, 2, 20, 21, 100), (9, 10, 13, 14, 40), (8, 8, W.NONE_OP, 15, 300)])
+    ev = W.transformer.events_of(tab)
+    sets = [dict(g_fwd=4, g_bwd=4, min_bytes=1000),          # no candidate reaches 1000 bytes: skipped
+            dict(g_fwd=1, g_bwd=1),                          # one layer per phase: swap-ins land inside the peak, skipped
+            dict(g_fwd=4, g_bwd=4),                          # the hand-worked case: A and B, 350 bytes, on time
+            dict(g_fwd=4, g_bwd=4, c_num=0)]                 # same items (size plays no role here): index decides
+    items, chosen, info = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 100, sets)
+    assert chosen == 2 and info == dict(peak=info["peak"], n_over=0, n_late=0, bytes=350)
+    assert sorted(it[2] for it in items) == [0, 1]
+    # every set on its own, by hand of the rule
+    mem = live_set_peak(tab, {}, 24, 0)
+    with pytest.raises(Infeasible):
+        oracle.generate_policy(tab, mem, phases, 400, 100, 4, 4, min_bytes=1000)
+    with pytest.raises(Infeasible):
+        oracle.generate_policy(tab, mem, phases, 400, 100, 1, 1)
+    # 80 link bytes per operator: 4 + 4 layers leave 8 operators over the limit (A is released late),
+    # 3 + 3 and 3 + 4 layers keep it, both with one LATE item and the same bytes: the lower index wins
+    sets80 = [dict(g_fwd=4, g_bwd=4), dict(g_fwd=3, g_bwd=3), dict(g_fwd=3, g_bwd=4)]
+    items, chosen, info = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 80, sets80)
+    assert chosen == 1 and (info["n_over"], info["n_late"], info["bytes"]) == (0, 1, 350)
+    assert oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 80, sets80[:1])[2]["n_over"] == 8
+    # 90 per operator: both keep the limit; 4 + 6 layers need one LATE item, 4 + 4 none: fewer LATE wins
+    items, chosen, info = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 90,
+                                                      [dict(g_fwd=4, g_bwd=6), dict(g_fwd=4, g_bwd=4)])
+    assert chosen == 1 and (info["n_over"], info["n_late"]) == (0, 0)
