@@ -78,3 +78,12 @@ def test_product_does_not_import_the_oracle():
             if f.endswith(".py"):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "paper_2509_11076_amd" not in src, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """the build is for one GPU: asking the benchmark for more ends with a message, before any GPU work"""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
