@@ -93,6 +93,9 @@ def main():
                     help="--policy-mode generated: release and pre-trigger points from the operator-granular link "
                          "model fed with per-phase operator times measured in this run (default), or the "
                          "generator's own logical-layer points")
+    ap.add_argument("--phase-eq1", action="store_true",
+                    help="--timing policy-points: Eq. 1 applied to the forward and the backward pass separately "
+                         "(their measured times), with fewer forward layers; default: Eq. 1 as printed")
     ap.add_argument("--limit-frac", type=float, default=0.7,
                     help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
@@ -309,6 +312,18 @@ def main():
         extra["generator"]["bpo"] = max(1, int(link * t_noswap / base_n_ops))
         args.bpo = max(1, int(0.9 * link * t_fwd / n_fwd))
         bpo_in = max(1, int(0.9 * link * t_bwd / n_bwd))
+    if args.policy_mode == "generated" and args.timing == "policy-points" and args.phase_eq1 and has_compute:
+        # Eq. 1 per phase: a forward operator is several times shorter than a backward one here; the
+        # forward operators are cut into as many logical layers as still hold the largest candidate
+        from workloads import transformer as T
+        tab_ = T.build_trace(T.config_shape(args.config)).tensors
+        keep_ = (tab_["first_bwd_use"] != 0xFFFFFFFF) & (tab_["last_fwd_use"] != 0xFFFFFFFF)
+        biggest = int(tab_["nbytes"][keep_].max())
+        f_bpo, b_bpo = max(1, int(link * t_fwd / n_fwd)), max(1, int(link * t_bwd / n_bwd))
+        extra["generator"]["phase_bytes_per_op"] = (f_bpo, b_bpo, b_bpo)
+        extra["generator"]["g_fwd"] = max(1, min(extra["generator"]["g_fwd"], int(n_fwd * f_bpo // (3 * biggest // 2))))
+        if args.bpo <= 0:
+            args.bpo = max(1, int(link * t_noswap / base_n_ops))      # not used by the generator's own points
     if args.bpo <= 0:
         bpo = max(1, int(link * t_noswap / base_n_ops))
         for _ in range(max(1, args.calibrate)):
@@ -422,6 +437,7 @@ def main():
                    "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "pack_grid_fits": grid_fits,
                    "pack_workgroups": args.workgroups_out or args.workgroups or "default (64)", "policy_mode": args.policy_mode,
                    "timing": args.timing if args.policy_mode == "generated" else "link-model",
+                   "generator_params": {k: v for k, v in extra.get("generator", {}).items()} or None,
                    "noswap_forward_ms": round(t_fwd * 1e3, 2), "noswap_backward_ms": round(t_bwd * 1e3, 2),
                    "memory_limit_bytes": extra.get("budget"), "generator": run_generated,
                    "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),

@@ -356,6 +356,9 @@ typedef struct {
   uint32_t g_fwd, g_bwd;  /* number of logical layers the forward / backward operators are cut into */
   uint32_t c_num, c_den;  /* C of Eq. 2 as a fraction                                               */
   uint64_t min_bytes;     /* tensors smaller than this are never candidates                         */
+  uint64_t phase_bytes_per_op[3]; /* Eq. 1 per phase: link bytes per forward / backward / optimizer
+                             operator (link peak x that phase's measured time / its operator count);
+                             0 = the context's link_bytes_per_op, i.e. Eq. 1 as printed          */
 } ss_gen_params_t;
 
 typedef struct {

@@ -7,7 +7,9 @@ paper and the pins are hand-worked cases, invariants and brute force):
 
  * Time is counted in link bytes, so Eq. 3 (T_swap = S / B) makes T_swap = S and Eq. 1
    (T_group = T_iter / N_iter * N_group) makes a layer's time budget bpo * N_group with
-   bpo = B * T_iter / N_iter.  Everything stays in integers.
+   bpo = B * T_iter / N_iter.  Everything stays in integers.  Optionally bpo is given per phase
+   (B * T_phase / N_phase): Eq. 1 applied to the forward, backward and optimizer operators
+   separately, for hardware on which a forward operator is several times shorter than a backward one.
  * Logical layers (Sec. 4.1, 4.3): the forward operators, in execution order, are cut into
    g_fwd groups of (almost) equal operator count, group g taking positions
    [g * n // G, (g + 1) * n // G); the backward operators likewise into g_bwd groups; all
@@ -49,8 +51,11 @@ class Infeasible(Exception):
 
 def logical_layers(phases, g_fwd, g_bwd, bpo):
     """phases: per operator 0 forward / 1 backward / 2 optimizer.  Returns (layers, layer_of) with
-    layers = list of dicts(first, end, type, remaining) in operator order and layer_of[op]."""
+    layers = list of dicts(first, end, type, remaining) in operator order and layer_of[op].
+    bpo: link bytes per operator, one number (Eq. 1 as printed: the iteration time spread evenly
+    over all operators) or three, one per phase (Eq. 1 applied to each phase's own measured time)."""
     n = len(phases)
+    bpo3 = tuple(int(b) for b in bpo) if isinstance(bpo, (tuple, list)) else (int(bpo),) * 3
     layers = []
     for ph, G in ((0, g_fwd), (1, g_bwd), (2, 1)):
         idx = [i for i in range(n) if phases[i] == ph]
@@ -61,7 +66,7 @@ def logical_layers(phases, g_fwd, g_bwd, bpo):
             lo, hi = g * len(idx) // G, (g + 1) * len(idx) // G
             if hi > lo:
                 layers.append(dict(first=idx[lo], end=idx[hi - 1] + 1, type=ph,
-                                   remaining=bpo * (hi - lo), ops=idx[lo:hi]))
+                                   remaining=bpo3[ph] * (hi - lo), ops=idx[lo:hi]))
     layers.sort(key=lambda L: L["first"])
     layer_of = [0] * n
     for li, L in enumerate(layers):
@@ -175,9 +180,10 @@ def generate_policy_best(tensors, events, n_ops, base, phases, limit, bpo, param
     mem = timeline_scan(events, None, n_ops, base, limit)["per_op"]
     best = None
     for c, p in enumerate(param_sets):
+        per_phase = tuple(int(b) or int(bpo) for b in p.get("phase_bytes_per_op") or (0, 0, 0))
         try:
-            items, _ = generate_policy(tensors, mem, phases, limit, bpo, p["g_fwd"], p["g_bwd"], p.get("c_num", 1),
-                                       p.get("c_den", 1), p.get("min_bytes", 0))
+            items, _ = generate_policy(tensors, mem, phases, limit, per_phase, p["g_fwd"], p["g_bwd"],
+                                       p.get("c_num", 1), p.get("c_den", 1), p.get("min_bytes", 0))
         except Infeasible:
             continue
         pe = []

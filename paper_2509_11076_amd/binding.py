@@ -81,7 +81,7 @@ class ss_align_result_t(C.Structure):
 
 class ss_gen_params_t(C.Structure):
     _fields_ = [("g_fwd", C.c_uint32), ("g_bwd", C.c_uint32), ("c_num", C.c_uint32), ("c_den", C.c_uint32),
-                ("min_bytes", C.c_uint64)]
+                ("min_bytes", C.c_uint64), ("phase_bytes_per_op", C.c_uint64 * 3)]
 
 
 class ss_gen_result_t(C.Structure):
@@ -407,11 +407,19 @@ def ss_greedy_policy(ctx, tensors, events, n_ops, base, budget, min_bytes=0, ini
     return out[:n.value], peak.value
 
 
-def ss_generate_policy(ctx, ops, tensors, events, base, limit, g_fwd, g_bwd, c_num=1, c_den=1, min_bytes=0):
+def _gen_params(g_fwd, g_bwd, c_num=1, c_den=1, min_bytes=0, phase_bytes_per_op=None):
+    p = ss_gen_params_t(int(g_fwd), int(g_bwd), int(c_num), int(c_den), int(min_bytes))
+    for i, b in enumerate(phase_bytes_per_op or ()):
+        p.phase_bytes_per_op[i] = int(b)
+    return p
+
+
+def ss_generate_policy(ctx, ops, tensors, events, base, limit, g_fwd, g_bwd, c_num=1, c_den=1, min_bytes=0,
+                       phase_bytes_per_op=None):
     ops = _arr(ops, OP_DT)
     tab = _arr(tensors, TENSOR_DT)
     ev = _arr(events, EVENT_DT)
-    prm = ss_gen_params_t(int(g_fwd), int(g_bwd), int(c_num), int(c_den), int(min_bytes))
+    prm = _gen_params(g_fwd, g_bwd, c_num, c_den, min_bytes, phase_bytes_per_op)
     out = np.zeros(len(tab), dtype=POLICY_DT)
     n = C.c_uint32(len(out))
     res = ss_gen_result_t()
@@ -428,8 +436,7 @@ def ss_generate_policy_best(ctx, ops, tensors, events, base, limit, param_sets):
     ev = _arr(events, EVENT_DT)
     prm = (ss_gen_params_t * max(1, len(param_sets)))()
     for i, d in enumerate(param_sets):
-        prm[i] = ss_gen_params_t(int(d["g_fwd"]), int(d["g_bwd"]), int(d.get("c_num", 1)), int(d.get("c_den", 1)),
-                                 int(d.get("min_bytes", 0)))
+        prm[i] = _gen_params(**d)
     out = np.zeros(len(tab), dtype=POLICY_DT)
     n, chosen = C.c_uint32(len(out)), C.c_uint32(0)
     res = ss_gen_result_t()

@@ -25,7 +25,7 @@ struct Chosen {
 typedef unsigned __int128 u128;
 
 // Cut the operators of each phase, in execution order, into groups of (almost) equal count.
-void build_layers(const std::vector<uint32_t> &phase, uint32_t g_fwd, uint32_t g_bwd, uint64_t bpo,
+void build_layers(const std::vector<uint32_t> &phase, uint32_t g_fwd, uint32_t g_bwd, const uint64_t bpo[3],
                   std::vector<Layer> &layers, std::vector<uint32_t> &layer_of) {
   const uint32_t n = (uint32_t)phase.size();
   struct Raw { Layer L; std::vector<uint32_t> ops; };
@@ -41,7 +41,7 @@ void build_layers(const std::vector<uint32_t> &phase, uint32_t g_fwd, uint32_t g
       const size_t lo = (size_t)(g * idx.size() / G), hi = (size_t)((g + 1) * idx.size() / G);
       if (hi <= lo) continue;
       Raw r;
-      r.L = Layer{idx[lo], idx[hi - 1] + 1, ph, (int64_t)(bpo * (hi - lo))};
+      r.L = Layer{idx[lo], idx[hi - 1] + 1, ph, (int64_t)(bpo[ph] * (hi - lo))};
       r.ops.assign(idx.begin() + lo, idx.begin() + hi);
       raw.push_back(std::move(r));
     }
@@ -72,7 +72,9 @@ static int generate_core(uint64_t bpo, const ss_op_t *ops, uint32_t n_ops, const
   for (uint32_t i = 0; i < n_ops; ++i) phase[i] = std::min<uint32_t>(ops[i].sig >> 16, 2u);
   std::vector<Layer> layers;
   std::vector<uint32_t> layer_of;
-  build_layers(phase, params->g_fwd, params->g_bwd, bpo, layers, layer_of);
+  uint64_t bpo3[3];
+  for (int ph = 0; ph < 3; ++ph) bpo3[ph] = params->phase_bytes_per_op[ph] ? params->phase_bytes_per_op[ph] : bpo;
+  build_layers(phase, params->g_fwd, params->g_bwd, bpo3, layers, layer_of);
 
   // entries the tensor can be away from: operators t with last_fwd_use + 1 < t < first_bwd_use
   auto span_count = [&](const ss_tensor_t &t, int64_t &last) {
@@ -222,8 +224,11 @@ extern "C" int ss_generate_policy_best(ss_ctx *ctx, const ss_op_t *ops, uint32_t
   if (*n_policy && !policy_out) return SS_E_INVAL;
   const uint64_t bpo = ctx->cfg.link_bytes_per_op;
   if ((u128)bpo * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
-  for (uint32_t c = 0; c < n_params; ++c)
+  for (uint32_t c = 0; c < n_params; ++c) {
     if (params[c].c_den == 0 || params[c].g_fwd == 0 || params[c].g_bwd == 0) return SS_E_INVAL;
+    for (int ph = 0; ph < 3; ++ph)
+      if ((u128)params[c].phase_bytes_per_op[ph] * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
+  }
   std::memset(res, 0, sizeof(*res));
 
   // memory without swaps -> memory reduction list (Sec. 4.2)

@@ -47,17 +47,20 @@ def policy_events_of(items):
     return sorted(pe, key=lambda e: e[0])
 
 
-def check_against_oracle(P, c, ops, phases, tab, ev, n_ops, limit, bpo, g_fwd, g_bwd, c_num=1, c_den=1, min_bytes=0):
-    """runs both; returns the oracle's items, or None when both report infeasibility"""
+def check_against_oracle(P, c, ops, phases, tab, ev, n_ops, limit, bpo, g_fwd, g_bwd, c_num=1, c_den=1, min_bytes=0,
+                         per_phase=None):
+    """runs both; returns the oracle's items, or None when both report infeasibility.
+    per_phase: link bytes per forward / backward / optimizer operator (0 = bpo)"""
     mem = oracle.timeline_scan(ev, None, n_ops, 0, limit)["per_op"]
+    obpo = bpo if per_phase is None else tuple(b or bpo for b in per_phase)
     try:
-        items, info = oracle.generate_policy(tab, mem, phases, limit, bpo, g_fwd, g_bwd, c_num, c_den, min_bytes)
+        items, info = oracle.generate_policy(tab, mem, phases, limit, obpo, g_fwd, g_bwd, c_num, c_den, min_bytes)
     except oracle.generator.Infeasible:
         with pytest.raises(P.SsError) as e:
-            P.ss_generate_policy(c, ops, tab, ev, 0, limit, g_fwd, g_bwd, c_num, c_den, min_bytes)
+            P.ss_generate_policy(c, ops, tab, ev, 0, limit, g_fwd, g_bwd, c_num, c_den, min_bytes, per_phase)
         assert e.value.code == P.SS_E_INFEASIBLE
         return None
-    pol, res = P.ss_generate_policy(c, ops, tab, ev, 0, limit, g_fwd, g_bwd, c_num, c_den, min_bytes)
+    pol, res = P.ss_generate_policy(c, ops, tab, ev, 0, limit, g_fwd, g_bwd, c_num, c_den, min_bytes, per_phase)
     assert rows_of(pol) == items
     assert res["n_items"] == len(items) and res["n_rounds"] == len(info["rounds"])
     assert res["n_late"] == sum(1 for it in items if it[3] & oracle.F_LATE)
@@ -81,6 +84,10 @@ def test_hand_worked_case(P):
         # release points 2 and 5 lie before operator 8, pre-triggers 15 and 18 after operator 14
         assert res["peak_with_policy"] <= 400 and res["n_over_with_policy"] == 0
         check_against_oracle(P, c, ops_with_phases(phases), phases, tab, ev, 24, 400, 100, 4, 4)
+        # forward operators three times shorter than the average: A is released inside the peak
+        slow_fwd = check_against_oracle(P, c, ops_with_phases(phases), phases, tab, ev, 24, 400, 100, 4, 4,
+                                        per_phase=(34, 166, 100))
+        assert {it[2]: (it[5], it[6]) for it in slow_fwd} == {0: (14, 18), 1: (3, 15)}
     finally:
         P.ss_destroy(c)
 
@@ -107,6 +114,9 @@ def test_tiny_traces_limits_links_and_layer_counts(P, seed):
                         items = check_against_oracle(P, c, ops, phases, tab, ev, n_ops, int(peak * frac), bpo,
                                                      g[0], g[1], cnum, cden)
                         seen.add(None if items is None else len(items))
+                    # Eq. 1 per phase: forward operators a third, backward ones twice the link share
+                    check_against_oracle(P, c, ops, phases, tab, ev, n_ops, int(peak * frac), bpo, g[0], g[1],
+                                         per_phase=(max(1, bpo // 3), 2 * bpo, 0))
         finally:
             P.ss_destroy(c)
     assert None in seen and 0 in seen and len(seen) >= 4   # infeasible, nothing to do, real policies
@@ -155,6 +165,9 @@ def test_transformer_shapes_generate_apply_and_scan(P, cfgno, frac, bpo, g):
         assert items, "limit below the peak must need a policy"
         pol, res = P.ss_generate_policy(c, ops, tr.tensors, ev, 0, limit, g, g, 1, 1, 1 << 16)
         assert res["n_over_with_policy"] == 0 and res["peak_with_policy"] <= limit
+        # the forward pass five times faster than the backward pass, fewer forward layers
+        check_against_oracle(P, c, ops, phases, tr.tensors, ev, tr.n_ops, limit, bpo, max(1, g // 4), g, 1, 1, 1 << 16,
+                             per_phase=(bpo // 3, bpo * 5 // 3, bpo))
 
         # same sequence: identity mapping; points kept exactly
         idx = pol["ref_op"].astype(np.int64)

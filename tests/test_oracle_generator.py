@@ -27,6 +27,15 @@ def test_logical_layers_even_groups_and_budget():
     assert [(L["first"], L["end"]) for L in layers] == [(0, 1), (1, 2), (2, 3)]
 
 
+def test_logical_layers_with_a_time_per_operator_of_each_phase():
+    """Eq. 1 applied per phase: a forward operator worth 10 link bytes, a backward one 50, optimizer 5"""
+    phases = [0] * 10 + [1] * 7 + [2] * 3
+    layers, _ = oracle.logical_layers(phases, 4, 3, (10, 50, 5))
+    assert [L["remaining"] for L in layers] == [20, 30, 20, 30, 100, 100, 150, 15]
+    same, _ = oracle.logical_layers(phases, 4, 3, (100, 100, 100))
+    assert [L["remaining"] for L in same] == [L["remaining"] for L in oracle.logical_layers(phases, 4, 3, 100)[0]]
+
+
 def table(rows):
     t = np.zeros(len(rows), dtype=W.TENSOR_DT)
     for i, (prod, lf, fb, fr, n) in enumerate(rows):
@@ -208,3 +217,25 @@ def test_best_of_several_parameter_sets():
     items, chosen, info = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 90,
                                                       [dict(g_fwd=4, g_bwd=6), dict(g_fwd=4, g_bwd=4)])
     assert chosen == 1 and (info["n_over"], info["n_late"]) == (0, 0)
+
+
+def test_per_phase_time_moves_release_points_later_in_a_fast_forward_pass():
+    """the hand-worked trace with forward operators three times shorter than the average: a forward
+    layer of 3 operators now has room for 3 x 34 = 102 bytes only, so A (250 bytes) finds no forward
+    layer and is released late, B (100) fits the first layer"""
+    phases = [0] * 12 + [1] * 12
+    tab = table([(0, 1, 22, 23, 250), (1, 2, 20, 21, 100), (9, 10, 13, 14, 40), (8, 8, W.NONE_OP, 15, 300)])
+    mem = live_set_peak(tab, {}, 24, 0)
+    items, info = oracle.generate_policy(tab, mem, phases, 400, (34, 166, 100), 4, 4)
+    got = {it[2]: it for it in items}
+    # swap-ins as before (backward layers have 3 x 166 = 498): A before operator 18, B before operator 15.
+    # swap-outs in order A, B: A's layer [0,3) has 102, not more than 250; neither has any forward layer;
+    # backward layers [12,15) has 498: A is released after operator 14 - inside the peak.  B then: layer
+    # [0,3) 102 > 100: that layer ends with operator 2, B's own last forward use, so the release comes
+    # after the operator that follows it, 3.
+    assert got[0] == (0, 0, 0, 0, 1, 14, 18, 22, 250)
+    assert got[1] == (1, 0, 1, 0, 2, 3, 15, 20, 100)
+    pe = sorted([(it[5], it[2], -it[8]) for it in items] + [(it[6], it[2], it[8]) for it in items], key=lambda e: e[0])
+    ev = W.transformer.events_of(tab)
+    after = oracle.timeline_scan(ev, pe, 24, 0, 400)
+    assert after["n_over"] == 7          # operators 8..14 still hold A: the scan of the finished policy says so
