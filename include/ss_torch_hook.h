@@ -45,6 +45,17 @@ int ss_hook_set_phase(uint32_t phase);
 int ss_hook_begin_iteration(void);
 /* Unregister the operator callback and forget the context. */
 int ss_hook_remove(void);
+/* Detailed mode's tensor table of the current iteration (Sec. 3: per tensor its pointer, type and
+ * uses): one row per block the allocator handed out since ss_hook_begin_iteration, in allocation
+ * order (tensor_id = the id of its events).  producer_op / alloc_op = the operator running when it was
+ * allocated, out_slot = its rank among that operator's allocations, dtype = type code of the first
+ * output tensor seen in it, last_fwd_use = the last forward-phase operator that had it among its
+ * inputs (the producer if none; SS_NONE_OP for blocks allocated after the forward phase),
+ * first_bwd_use = the first later-phase operator that had it among its inputs (else SS_NONE_OP),
+ * free_op = the operator running when it was released (the last operator if it is still held),
+ * nbytes = the size asked for; offsets are 0.  In: *n = capacity, out: count; SS_E_CAPACITY with
+ * the needed count in *n if out is too small. */
+int ss_hook_tensor_table(ss_tensor_t *out /* host */, uint32_t *n);
 int ss_hook_get_stats(ss_hook_stats_t *out /* host, out */);
 
 #ifdef __cplusplus

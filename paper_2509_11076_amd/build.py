@@ -52,6 +52,7 @@ def build_hook(verbose=True):
     tlib = os.path.join(os.path.dirname(torch.__file__), "lib")
     cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
            "-D__HIP_PLATFORM_AMD__=1", "-DUSE_ROCM=1",
+           "-DNDEBUG",      # as PyTorch's own build: its inline debug checks read members a release build never sets
            "-D_GLIBCXX_USE_CXX11_ABI=%d" % int(torch._C._GLIBCXX_USE_CXX11_ABI)]
     cmd += ["-I" + p for p in ce.include_paths()]
     cmd += ["-I/opt/rocm/include", "-I" + sysconfig.get_paths()["include"],

@@ -13,6 +13,7 @@
 
 #include <atomic>
 #include <cstring>
+#include <map>
 #include <mutex>
 #include <string>
 #include <unordered_map>
@@ -36,6 +37,11 @@ struct Hook {
   std::unordered_multimap<uint64_t, Named> by_name;
   std::unordered_map<uint64_t, uint32_t> live;        // allocator address -> event tensor id
   uint32_t next_id = 0;
+  // Detailed mode's tensor table: one row per block allocated in this iteration, its uses filled in
+  // from the operators' input lists
+  std::vector<ss_tensor_t> table;
+  std::map<uint64_t, uint32_t> by_addr;               // start address of a live block -> row
+  uint32_t slot_op = SS_NONE_OP, slot_next = 0;       // output slots count up within one operator
   ss_hook_stats_t st{};
 };
 Hook g;
@@ -124,6 +130,28 @@ std::unique_ptr<at::ObserverContext> on_start(const at::RecordFunction &fn) {
   }
   g.st.ops++;
   if (mode != SS_HOOK_DETAILED) return nullptr;
+  {
+    const uint32_t phase = op.sig >> 16;
+    auto use = [&](const at::Tensor &t) {
+      if (!t.defined() || !t.has_storage()) return;
+      const uint64_t p = (uint64_t)(uintptr_t)t.storage().data();
+      auto it2 = g.by_addr.upper_bound(p);
+      if (it2 == g.by_addr.begin()) return;
+      --it2;
+      ss_tensor_t &row = g.table[it2->second];
+      if (p >= it2->first + row.nbytes) return;          // a block from before the iteration
+      if (phase == 0) {
+        if (row.last_fwd_use != SS_NONE_OP && idx > row.last_fwd_use) row.last_fwd_use = idx;
+      } else if (row.first_bwd_use == SS_NONE_OP) {
+        row.first_bwd_use = idx;
+      }
+    };
+    for (const c10::IValue &v : fn.inputs()) {
+      if (v.isTensor()) use(v.toTensor());
+      else if (v.isTensorList())
+        for (const at::Tensor &t : v.toTensorVector()) use(t);
+    }
+  }
   auto c = std::make_unique<OpCtx>();
   c->op_idx = idx;
   c->recorded = true;
@@ -142,6 +170,11 @@ void on_end(const at::RecordFunction &fn, at::ObserverContext *raw) {
   }
   std::lock_guard<std::mutex> lock(g.mu);
   if (g.ctx && ss_trace_amend(g.ctx, c->op_idx, dtype, n_out) != SS_OK) g.st.errors++;
+  for (const c10::IValue &v : fn.outputs()) {             // the blocks the outputs live in get their type
+    if (!v.isTensor() || !v.toTensor().defined() || !v.toTensor().has_storage()) continue;
+    auto it = g.by_addr.find((uint64_t)(uintptr_t)v.toTensor().storage().data());
+    if (it != g.by_addr.end() && g.table[it->second].dtype == 0) g.table[it->second].dtype = dtype_code(v.toTensor());
+  }
 }
 
 void on_allocator(const c10::hip::HIPCachingAllocator::TraceEntry &e) {
@@ -151,11 +184,31 @@ void on_allocator(const c10::hip::HIPCachingAllocator::TraceEntry &e) {
   std::lock_guard<std::mutex> lock(g.mu);
   if (!g.ctx) return;
   int rc;
+  uint32_t cur_op = 0;
+  ss_trace_view(g.ctx, nullptr, &cur_op, nullptr, nullptr, nullptr);
   if (e.action_ == TE::ALLOC) {
     const uint32_t id = g.next_id++;
     g.live[(uint64_t)e.addr_] = id;
     rc = ss_trace_event(g.ctx, id, (int64_t)e.size_);
+    if (rc == SS_OK) {                                    // cur_op >= 1: the running operator is cur_op - 1
+      const uint32_t op = cur_op - 1;
+      if (g.slot_op != op) { g.slot_op = op; g.slot_next = 0; }
+      const ss_op_t *ops = nullptr;
+      ss_trace_view(g.ctx, &ops, nullptr, nullptr, nullptr, nullptr);
+      const bool fwd = (ops[op].sig >> 16) == 0;
+      ss_tensor_t row{};
+      row.tensor_id = id; row.producer_op = op; row.out_slot = g.slot_next++; row.alloc_op = op;
+      row.last_fwd_use = fwd ? op : SS_NONE_OP; row.first_bwd_use = SS_NONE_OP; row.free_op = SS_NONE_OP;
+      row.nbytes = (uint64_t)e.size_;
+      g.by_addr[(uint64_t)e.addr_] = (uint32_t)g.table.size();
+      g.table.push_back(row);
+    }
   } else {
+    auto bt = g.by_addr.find((uint64_t)e.addr_);
+    if (bt != g.by_addr.end()) {
+      if (cur_op) g.table[bt->second].free_op = cur_op - 1;
+      g.by_addr.erase(bt);
+    }
     auto it = g.live.find((uint64_t)e.addr_);
     if (it == g.live.end()) {          // allocated before this iteration's record began: an id of its own
       g.st.foreign_frees++;
@@ -183,7 +236,7 @@ void register_callback(int mode) {
     g.have_cb = false;
   }
   if (mode == SS_HOOK_OFF) return;
-  auto cb = mode == SS_HOOK_DETAILED ? at::RecordFunctionCallback(on_start, on_end).needsOutputs(true)
+  auto cb = mode == SS_HOOK_DETAILED ? at::RecordFunctionCallback(on_start, on_end).needsInputs(true).needsOutputs(true)
                                      : at::RecordFunctionCallback(on_start, nullptr);
   g.handle = at::addGlobalCallback(cb.scopes({at::RecordScope::FUNCTION}));
   g.have_cb = true;
@@ -221,6 +274,9 @@ extern "C" int ss_hook_begin_iteration(void) {
   if (!g.ctx) return SS_E_INVAL;
   g.live.clear();
   g.next_id = 0;
+  g.table.clear();
+  g.by_addr.clear();
+  g.slot_op = SS_NONE_OP;
   g.phase.store(0);
   return ss_trace_begin(g.ctx);
 }
@@ -232,6 +288,22 @@ extern "C" int ss_hook_remove(void) {
   g.ctx = nullptr;
   g.by_name.clear();
   g.live.clear();
+  return SS_OK;
+}
+
+extern "C" int ss_hook_tensor_table(ss_tensor_t *out, uint32_t *n) {
+  if (!n || (*n && !out)) return SS_E_INVAL;
+  std::lock_guard<std::mutex> lock(g.mu);
+  if (!g.ctx) return SS_E_STATE;
+  const uint32_t have = (uint32_t)g.table.size();
+  if (*n < have) { *n = have; return SS_E_CAPACITY; }
+  uint32_t n_ops = 0;
+  ss_trace_view(g.ctx, nullptr, &n_ops, nullptr, nullptr, nullptr);
+  for (uint32_t i = 0; i < have; ++i) {
+    out[i] = g.table[i];
+    if (out[i].free_op == SS_NONE_OP && n_ops) out[i].free_op = n_ops - 1;   // still held when the iteration ends
+  }
+  *n = have;
   return SS_OK;
 }
 

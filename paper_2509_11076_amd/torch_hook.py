@@ -22,7 +22,8 @@ class ss_hook_stats_t(C.Structure):
 
 _SIGS = {"ss_hook_install": [C.c_void_p, C.c_int], "ss_hook_set_mode": [C.c_int],
          "ss_hook_set_phase": [C.c_uint32], "ss_hook_begin_iteration": [], "ss_hook_remove": [],
-         "ss_hook_get_stats": [C.POINTER(ss_hook_stats_t)]}
+         "ss_hook_get_stats": [C.POINTER(ss_hook_stats_t)],
+         "ss_hook_tensor_table": [C.c_void_p, C.POINTER(C.c_uint32)]}
 for _n, _a in _SIGS.items():
     getattr(_lib, _n).argtypes = _a
     getattr(_lib, _n).restype = C.c_int
@@ -52,6 +53,18 @@ def ss_hook_begin_iteration():
 
 def ss_hook_remove():
     _ck(_lib.ss_hook_remove(), "ss_hook_remove")
+
+
+def ss_hook_tensor_table():
+    import numpy as np
+    n = C.c_uint32(0)
+    rc = _lib.ss_hook_tensor_table(None, C.byref(n))
+    if rc not in (0, B.SS_E_CAPACITY):
+        _ck(rc, "ss_hook_tensor_table")
+    out = np.zeros(n.value, dtype=B.TENSOR_DT)
+    if n.value:
+        _ck(_lib.ss_hook_tensor_table(out.ctypes.data_as(C.c_void_p), C.byref(n)), "ss_hook_tensor_table")
+    return out[:n.value]
 
 
 def ss_hook_get_stats():

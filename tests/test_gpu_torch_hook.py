@@ -162,3 +162,77 @@ def test_detailed_mode_memory_trace_matches_the_allocator(env):
         H.ss_hook_remove()
         tr.hook = None
         B.ss_destroy(ctx)
+
+
+def test_detailed_mode_tensor_table_feeds_the_policy_generator(env):
+    """the trace of a real training step goes through the same generator as the synthetic ones: table
+    and events agree with each other, saved activations are found, and the policy generated from them
+    equals the oracle's on the same table"""
+    torch, B, H, _ = env
+    from paper_2509_11076_amd.hook_overhead import Trainer
+    # activations must outweigh parameters and gradients for swapping to lower the peak at all
+    tr = Trainer(argparse.Namespace(vocab=1000, hidden=128, layers=3, heads=4, seq=256, batch=8))
+    for _ in range(3):
+        tr.step()
+    ctx = make_ctx(B)
+    tr.hook = H
+    try:
+        H.ss_hook_install(ctx, H.SS_HOOK_DETAILED)
+        tr.step()
+        tr.opt.zero_grad(set_to_none=True)
+        torch.cuda.synchronize()
+        base = torch.cuda.memory_stats()["requested_bytes.all.current"]
+        tr.step()
+        torch.cuda.synchronize()
+        ops, ev, bal = B.ss_trace_view(ctx)
+        tab = H.ss_hook_tensor_table()
+        n_ops = len(ops)
+        # one row per allocation, in allocation order, sizes and operators as in the event list
+        allocs = ev[ev["delta"] > 0]
+        assert len(tab) == len(allocs) and np.array_equal(tab["tensor_id"], allocs["tensor_id"])
+        assert np.array_equal(tab["nbytes"].astype(np.int64), allocs["delta"]) and np.array_equal(tab["alloc_op"], allocs["op_idx"])
+        frees = {int(e["tensor_id"]): int(e["op_idx"]) for e in ev[ev["delta"] < 0]}
+        for row in tab:
+            assert int(row["free_op"]) == frees.get(int(row["tensor_id"]), n_ops - 1)
+            assert row["alloc_op"] <= row["free_op"]
+        # out slots count up within an operator
+        for op in np.unique(tab["producer_op"]):
+            assert tab["out_slot"][tab["producer_op"] == op].tolist() == list(range(int((tab["producer_op"] == op).sum())))
+        # saved activations: allocated in forward, read again in backward, and all of it in order
+        ph = ops["sig"] >> 16
+        saved = tab[(tab["last_fwd_use"] != 0xFFFFFFFF) & (tab["first_bwd_use"] != 0xFFFFFFFF)]
+        assert len(saved) >= 3 * 6                                   # several per decoder layer
+        assert (saved["alloc_op"] <= saved["last_fwd_use"]).all() and (saved["last_fwd_use"] < saved["first_bwd_use"]).all()
+        assert (saved["first_bwd_use"] <= saved["free_op"]).all()
+        assert (ph[saved["last_fwd_use"]] == 0).all() and (ph[saved["first_bwd_use"]] >= 1).all()
+        assert (saved["dtype"] != 0).sum() > 0.8 * len(saved)
+        # the generator on the real trace: 3 + 3 logical layers (the model has 3 decoder layers)
+        no = B.ss_timeline_scan(ctx, ev, None, n_ops, base, 1 << 62)
+        cfg = B.ss_config_default()
+        cfg.staging_bytes = 4096
+        cfg.link_bytes_per_op = 1 << 20
+        g = B.ss_create(cfg)
+        feasible = 0
+        try:
+            for frac in (0.98, 0.95, 0.9, 0.8, 0.6):
+                limit = base + int(frac * (no["peak"] - base))
+                mem = oracle.timeline_scan(ev, None, n_ops, base, limit)["per_op"]
+                try:
+                    items, _ = oracle.generate_policy(tab, mem, [int(p) for p in ph], limit, 1 << 20, 3, 3, min_bytes=4096)
+                except oracle.generator.Infeasible:
+                    with pytest.raises(B.SsError) as e:
+                        B.ss_generate_policy(g, ops, tab, ev, base, limit, 3, 3, min_bytes=4096)
+                    assert e.value.code == B.SS_E_INFEASIBLE
+                    continue
+                pol, res = B.ss_generate_policy(g, ops, tab, ev, base, limit, 3, 3, min_bytes=4096)
+                assert [tuple(int(x) for x in r) for r in pol.tolist()] == items and len(items) > 0
+                assert res["peak_no_swap"] == no["peak"] and res["bytes"] == sum(it[8] for it in items)
+                assert res["peak_with_policy"] < no["peak"]
+                feasible += 1
+        finally:
+            B.ss_destroy(g)
+        assert feasible >= 1, "peak at operator %d of %d, phase %d" % (no["argpeak_op"], n_ops, int(ph[no["argpeak_op"]]))
+    finally:
+        H.ss_hook_remove()
+        tr.hook = None
+        B.ss_destroy(ctx)
