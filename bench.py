@@ -103,6 +103,10 @@ def main():
     ap.add_argument("--swap-only", action="store_true",
                     help="counter-collection mode: the same swap schedule without the compute stream's work, "
                          "no baseline, no link-model fitting (keeps a rocprofv3 --pmc run short)")
+    ap.add_argument("--reuse-interval", action="store_true",
+                    help="memory-block reuse interval (Sec. 6.4): operators dispatched between a tensor's swap-out "
+                         "and the release of its block, with the device-side release of this library and with a "
+                         "host-polled release (stock recordStream) emulated on the same run")
     ap.add_argument("--probe-reps", type=int, default=10)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -225,6 +229,72 @@ def main():
                           "overhead_vs_noswap_pct": round(100 * (t_stable / t_warm - 1), 1)},
             "iterations": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in e.items()} for e in log],
             "link_peak_measured": {k: round(v, 2) for k, v in bw.items()}}), flush=True)
+        return
+
+    if args.reuse_interval:
+        from paper_2509_11076_amd.executor import run_iteration
+        link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
+        base = SwapRun(B, torch, args.config, swap=False)
+        for _ in range(3):
+            base.step_noswap()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            base.step_noswap()
+        torch.cuda.synchronize()
+        t_ns = (time.perf_counter() - t0) / 5
+        n_ops = base.tr.n_ops
+        base.close()
+        del base
+        torch.cuda.empty_cache()
+        run = SwapRun(B, torch, args.config, swap=True, bpo=max(1, int(link * 2 * t_ns / n_ops)),
+                      bpo_in=max(1, int(link * t_ns / n_ops)), copy_path=path, copy_path_in=path_in,
+                      flags=B.SS_CFG_TIMING | B.SS_CFG_KEEP_LATE)
+        for _ in range(3):
+            run.step()
+        torch.cuda.synchronize()
+        plan = run.plan()
+        acts = plan["applied"]["actions"]
+        issue_op, free_op = {}, {}
+        for op, kind, tid, batch in acts.tolist():
+            if kind == B.SS_ACT_OUT:
+                issue_op.setdefault(batch, op)
+            elif kind == B.SS_ACT_FREE:
+                free_op[batch] = max(free_op.get(batch, 0), op)
+        B.ss_trace_begin(run.ctx)
+        seen_done, pending, n_query, t_query = {}, [], 0, 0.0
+
+        def run_op(i):
+            nonlocal n_query, t_query
+            run.record(i)
+            run.compute.run_op(i)
+            # what a host-polled release does at every dispatch: query the events of blocks in flight
+            for b in sorted(issue_op):
+                if issue_op[b] < i and b not in seen_done and b not in pending:
+                    pending.append(b)
+            q0 = time.perf_counter()
+            for b in list(pending):
+                n_query += 1
+                if B.ss_batch_done(run.ctx, 0, b):
+                    seen_done[b] = i
+                    pending.remove(b)
+            t_query += time.perf_counter() - q0
+        t0 = time.perf_counter()
+        run_iteration(run.ctx, run.tr.n_ops, acts, run_op, plan["lists"])
+        torch.cuda.synchronize()
+        t_step = time.perf_counter() - t0
+        ours = np.array([free_op[b] - issue_op[b] for b in sorted(issue_op)])
+        stock = np.array([seen_done.get(b, run.tr.n_ops) - issue_op[b] for b in sorted(issue_op)])
+        run.close()
+
+        def dist(a):
+            return {"mean": round(float(a.mean()), 1), "p50": int(np.percentile(a, 50)), "p90": int(np.percentile(a, 90)),
+                    "p99": int(np.percentile(a, 99)), "max": int(a.max())}
+        print(json.dumps({"mode": "reuse-interval", "config": args.config, "swap_out_batches": len(ours),
+                          "ops_per_step": run.tr.n_ops, "step_ms": round(t_step * 1e3, 2),
+                          "device_side_release_ops": dist(ours), "host_polled_release_ops": dist(stock),
+                          "host_polled_event_queries_per_step": n_query,
+                          "host_polled_query_ms_per_step": round(t_query * 1e3, 3)}), flush=True)
         return
 
     def timed(run, fn, steps, warmup):

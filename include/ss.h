@@ -324,6 +324,12 @@ int ss_apply_policy(ss_ctx *ctx, const ss_policy_item_t *policy, uint32_t k, con
                     ss_desc_t *descs_in, ss_event_t *pevents, uint32_t *n_pe,
                     ss_apply_result_t *res /* host, out */);
 
+/* Host-side, non-blocking: has swap-out (dir 0) / swap-in (dir 1) batch `batch` of this iteration
+ * finished?  *done = 1 / 0.  SS_E_STATE if it has not been issued.  This is the event query a
+ * host-polled release (the stock recordStream of Sec. 5.2) performs at every allocation; the executor
+ * itself never calls it. */
+int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *done /* host, out */);
+
 /* Borrow the batch tables of the loaded schedule: starts have n_batches + 1
  * entries; in_dep[b] is the last swap-out batch swap-in batch b depends on. */
 int ss_schedule_view(ss_ctx *ctx, const uint32_t **out_start, uint32_t *n_out_batches,

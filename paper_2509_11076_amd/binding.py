@@ -138,6 +138,7 @@ _SIGS = {
     "ss_greedy_policy": [_P, _P, C.c_uint32, _P, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_uint64,
                          _P, C.c_uint32, _P, C.POINTER(C.c_uint32), C.POINTER(C.c_int64)],
     "ss_timeline_scan_batch": [_P, _P, C.c_uint64, _P, _P, C.c_uint32, C.c_uint32, C.c_int64, C.c_int64, _P, _P],
+    "ss_batch_done": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_int)],
     "ss_trace_event": [_P, C.c_uint32, C.c_int64],
     "ss_trace_amend": [_P, C.c_uint32, C.c_uint32, C.c_uint32],
     "ss_align_sequence": [_P, _P, C.c_uint32, _P, C.c_uint32, _P, C.c_uint32, _P, _P, _P,
@@ -256,6 +257,12 @@ def ss_trace_record_prepared(ctx, ops, events):
         if rc != SS_OK:
             raise SsError(rc, "ss_trace_record")
     return record
+
+
+def ss_batch_done(ctx, direction, batch):
+    d = C.c_int(0)
+    _ck(_lib.ss_batch_done(ctx, int(direction), int(batch), C.byref(d)), "ss_batch_done")
+    return bool(d.value)
 
 
 def ss_trace_event(ctx, tensor_id, delta):

@@ -553,6 +553,24 @@ extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms,
   return SS_OK;
 }
 
+extern "C" int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *done) {
+  if (!ctx || dir > 1 || !done) return SS_E_INVAL;
+  ss_sched &s = ctx->sched;
+  if (!s.loaded) return SS_E_STATE;
+  const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
+  if (batch >= nb) return SS_E_INVAL;
+  if (!(dir ? s.in_issued[batch] : s.out_issued[batch])) return SS_E_STATE;
+  const hipError_t e = hipEventQuery(dir ? s.ev_in_done[batch] : s.ev_out_done[batch]);
+  if (e == hipErrorNotReady) {
+    (void)hipGetLastError();
+    *done = 0;
+    return SS_OK;
+  }
+  SS_HIP(e);
+  *done = 1;
+  return SS_OK;
+}
+
 extern "C" int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *start_ms, float *end_ms) {
   if (!ctx || dir > 1 || !start_ms || !end_ms) return SS_E_INVAL;
   if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;

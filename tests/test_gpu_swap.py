@@ -176,7 +176,19 @@ def test_schedule_validation_and_call_order_errors(P, torch):
         with pytest.raises(P.SsError) as e:                  # release before its swap-out was issued
             P.ss_sync(ctx, P.SS_SYNC_FREE, 0)
         assert e.value.code == P.SS_E_STATE
+        with pytest.raises(P.SsError) as e:                  # host-side query of a batch not issued yet
+            P.ss_batch_done(ctx, 0, 0)
+        assert e.value.code == P.SS_E_STATE
         P.ss_swap_out(ctx, 0)
+        torch.cuda.synchronize()                             # the null stream; the swap stream is not blocking
+        import time
+        t_end = time.time() + 10
+        while not P.ss_batch_done(ctx, 0, 0) and time.time() < t_end:
+            time.sleep(0.001)
+        assert P.ss_batch_done(ctx, 0, 0)                    # 8 KiB leave within moments
+        with pytest.raises(P.SsError) as e:
+            P.ss_batch_done(ctx, 0, 7)
+        assert e.value.code == P.SS_E_INVAL
         with pytest.raises(P.SsError) as e:                  # twice in one iteration
             P.ss_swap_out(ctx, 0)
         assert e.value.code == P.SS_E_STATE
