@@ -339,11 +339,21 @@ class StagedRun:
         cfg.link_bytes_per_op = self.cfg.link_bytes_per_op
         cfg.max_ops, cfg.max_events = self.cfg.max_ops, self.cfg.max_events
         g = B.ss_create(cfg)
+        # the generator's open constants (layer counts, C of Eq. 2) are varied around the given ones; all
+        # candidates are checked against the limit in one batched scan and the best one is run
+        sets = []
+        for div in (1, 2, 4):
+            for c_mul in (1, 4):
+                d = dict(self.gen)
+                d["g_fwd"] = max(1, d["g_fwd"] // div)
+                d["g_bwd"] = max(1, d["g_bwd"] // div)
+                d["c_num"] = d["c_num"] * c_mul
+                sets.append(d)
         try:
-            pol, info = B.ss_generate_policy(g, ops, tr.tensors, tr.events, 0, limit, **self.gen)
+            pol, info, chosen = B.ss_generate_policy_best(g, ops, tr.tensors, tr.events, 0, limit, sets)
         finally:
             B.ss_destroy(g)
-        return dict(policy=pol, ref_ops=ops, ms=None, info=info, limit=limit,
+        return dict(policy=pol, ref_ops=ops, ms=None, info=info, limit=limit, params=sets[chosen],
                     link_bytes_per_op=cfg.link_bytes_per_op)
 
     def iteration(self, it):
