@@ -107,6 +107,9 @@ def main():
                     help="memory-block reuse interval (Sec. 6.4): operators dispatched between a tensor's swap-out "
                          "and the release of its block, with the device-side release of this library and with a "
                          "host-polled release (stock recordStream) emulated on the same run")
+    ap.add_argument("--path-table", action="store_true",
+                    help="GB/s of one batch of equal-size tensors at scattered arena offsets, per size class, "
+                         "copy kernel against per-tensor copy-engine calls, both directions (no compute stream work)")
     ap.add_argument("--probe-reps", type=int, default=10)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -229,6 +232,49 @@ def main():
                           "overhead_vs_noswap_pct": round(100 * (t_stable / t_warm - 1), 1)},
             "iterations": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in e.items()} for e in log],
             "link_peak_measured": {k: round(v, 2) for k, v in bw.items()}}), flush=True)
+        return
+
+    if args.path_table:
+        from workloads.layouts import DESC_DT
+        from workloads.rng import SplitMix64
+        arena_bytes = 8 << 30
+        arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+        rows = []
+        for size in (4 << 10, 64 << 10, 1 << 20, 16 << 20, 256 << 20):
+            n = max(4, min(20000, (1 << 30) // size))
+            rng = SplitMix64(size, 3)
+            slots = arena_bytes // size
+            picks = sorted(set(rng.randint(slots) for _ in range(2 * n)))[:n]       # scattered, disjoint
+            rng2 = SplitMix64(size, 4)
+            order = sorted(range(len(picks)), key=lambda i: rng2.randint(1 << 30))  # shuffled issue order
+            d = np.zeros(len(picks), dtype=DESC_DT)
+            for k, i in enumerate(order):
+                d[k] = (picks[i] * size, k * size, size, k, 0)
+            start = np.array([0, len(d)], dtype=np.uint32)
+            row = {"tensor_bytes": size, "tensors": len(d), "batch_bytes": int(size * len(d))}
+            for pname, pcode in (("kernel", B.SS_PATH_KERNEL), ("engine", B.SS_PATH_ENGINE)):
+                cfg = B.ss_config_default()
+                cfg.staging_bytes = int(size * len(d))
+                cfg.copy_path = cfg.copy_path_in = pcode
+                cfg.flags = B.SS_CFG_TIMING
+                ctx = B.ss_create(cfg)
+                B.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+                B.ss_load_schedule(ctx, d, start, d, start)
+                out_ms, in_ms = [], []
+                for rep in range(4):
+                    B.ss_swap_out(ctx, 0)
+                    B.ss_swap_in(ctx, 0)
+                    B.ss_sync(ctx, B.SS_SYNC_DRAIN)
+                    if rep:
+                        out_ms.append(B.ss_batch_ms(ctx, 0, 0)[0])
+                        in_ms.append(B.ss_batch_ms(ctx, 1, 0)[0])
+                B.ss_destroy(ctx)
+                row[pname + "_d2h_gbps"] = round(row["batch_bytes"] / (min(out_ms) * 1e-3) / 1e9, 2)
+                row[pname + "_h2d_gbps"] = round(row["batch_bytes"] / (min(in_ms) * 1e-3) / 1e9, 2)
+            rows.append(row)
+            print(row, file=sys.stderr, flush=True)
+        print(json.dumps({"mode": "path-table", "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
+                          "rows": rows}), flush=True)
         return
 
     if args.reuse_interval:
