@@ -6,8 +6,9 @@
 // SmartSwap paper).  The paper issues one framework copy per tensor; small
 // tensors then waste the link (Sec. 4.2).  Here one launch moves a whole batch
 // of variable-size tensors: the batch is cut into 64 KiB chunks, a small
-// persistent grid walks the chunks, and each workgroup finds its chunk's
-// descriptor by binary search in a chunk-prefix table staged in LDS.  All
+// persistent grid walks the chunks, and each workgroup looks its chunk's
+// descriptor up in a per-chunk table built when the schedule is loaded (two
+// dependent loads per chunk, no search, no LDS).  All
 // traffic is 16 bytes per lane, a wavefront touching 1 KiB of consecutive
 // addresses on both sides; a byte tail handles sizes that are not multiples of
 // 16.  The staging area is host memory mapped into the device address space,
@@ -20,33 +21,19 @@
 
 namespace {
 
-constexpr uint32_t kLdsEntries = 8192;   // chunk-prefix entries staged in LDS (32 KiB)
-
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // kUnroll 16-byte accesses are in flight per lane before the first store is issued.
 template <bool TO_HOST, uint32_t kUnroll>
 __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
     uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
-    const uint32_t *__restrict__ chunk0, uint32_t n_desc, uint32_t n_chunks) {
-  __shared__ uint32_t s_chunk0[kLdsEntries];
+    const uint32_t *__restrict__ chunk0, const uint32_t *__restrict__ chunk_desc, uint32_t n_chunks) {
   const uint32_t tid = threadIdx.x;
-  const bool in_lds = n_desc + 1 <= kLdsEntries;
-  if (in_lds) {
-    for (uint32_t i = tid; i <= n_desc; i += SS_COPY_THREADS) s_chunk0[i] = chunk0[i];
-    __syncthreads();
-  }
-  const uint32_t *prefix = in_lds ? s_chunk0 : chunk0;
-
   for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-    // largest d with prefix[d] <= c (descriptors without chunks are skipped by construction)
-    uint32_t lo = 0, hi = n_desc;
-    while (hi - lo > 1) {
-      uint32_t mid = (lo + hi) >> 1;
-      if (prefix[mid] <= c) lo = mid; else hi = mid;
-    }
+    // chunk_desc[c]: the descriptor chunk c belongs to; chunk0[d]: first chunk of descriptor d
+    const uint32_t lo = chunk_desc[c];
     const ss_desc_t d = descs[lo];
-    const uint64_t off = (uint64_t)(c - prefix[lo]) * SS_CHUNK_BYTES;
+    const uint64_t off = (uint64_t)(c - chunk0[lo]) * SS_CHUNK_BYTES;
     const uint64_t left = d.nbytes - off;
     const uint32_t n = left < SS_CHUNK_BYTES ? (uint32_t)left : SS_CHUNK_BYTES;
     const uint8_t *src = TO_HOST ? arena + d.dev_off + off : staging + d.host_off + off;
@@ -87,13 +74,13 @@ __global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nby
 }  // namespace
 
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
-                    uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc,
-                    uint32_t n_chunks) {
-  if (n_chunks == 0 || n_desc == 0) return;
+                    uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,
+                    const uint32_t *d_chunk_desc, uint32_t n_chunks) {
+  if (n_chunks == 0) return;
   const dim3 grid(workgroups < n_chunks ? workgroups : n_chunks), block(SS_COPY_THREADS);
 #define SS_LAUNCH(TH, U)                                                                                  \
-  hipLaunchKernelGGL((ss_copy_kernel<TH, U>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, n_desc, \
-                     n_chunks)
+  hipLaunchKernelGGL((ss_copy_kernel<TH, U>), grid, block, 0, s, arena, staging, d_descs, d_chunk0,        \
+                     d_chunk_desc, n_chunks)
   if (to_host) {
     if (unroll <= 2) SS_LAUNCH(true, 2); else if (unroll <= 4) SS_LAUNCH(true, 4); else SS_LAUNCH(true, 8);
   } else {

@@ -13,13 +13,16 @@ struct ss_sched {
   std::vector<uint32_t> out_start, in_start;      // batch boundaries (n_batches + 1)
   std::vector<uint32_t> in_dep;                   // per swap-in batch: last swap-out batch needed
   std::vector<uint32_t> out_chunk0, in_chunk0;    // per descriptor: first chunk index inside its batch
+  std::vector<uint32_t> out_cdesc, in_cdesc;      // per chunk: descriptor index inside its batch
+  std::vector<uint64_t> out_cbase, in_cbase;      // per batch: where its chunks start in *_cdesc
   std::unordered_map<uint32_t, uint32_t> out_of_tensor, in_of_tensor;  // tensor id -> descriptor index
   std::vector<uint32_t> out_batch_of, in_batch_of;                      // descriptor index -> batch
   std::vector<uint8_t> out_waited, in_waited, out_issued, in_issued;    // per batch, this iteration
   std::vector<hipEvent_t> ev_out_done, ev_in_done, ev_out_start, ev_in_start;
   ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
   uint32_t *d_out_chunk0 = nullptr, *d_in_chunk0 = nullptr;
-  size_t d_cap_out = 0, d_cap_in = 0;
+  uint32_t *d_out_cdesc = nullptr, *d_in_cdesc = nullptr;
+  size_t d_cap_out = 0, d_cap_in = 0, d_ccap_out = 0, d_ccap_in = 0;
   bool loaded = false;
 };
 
@@ -92,8 +95,8 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
 constexpr uint32_t SS_CHUNK_BYTES = 64 * 1024;
 constexpr uint32_t SS_COPY_THREADS = 256;
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
-                    uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0, uint32_t n_desc,
-                    uint32_t n_chunks);
+                    uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,
+                    const uint32_t *d_chunk_desc, uint32_t n_chunks);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
 
 // sequence aligner (ss_align.hip): ref_to_cur has n entries

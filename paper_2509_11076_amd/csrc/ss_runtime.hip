@@ -141,6 +141,10 @@ static void sched_release(ss_sched &s) {
   if (s.d_in) (void)hipFree(s.d_in);
   if (s.d_out_chunk0) (void)hipFree(s.d_out_chunk0);
   if (s.d_in_chunk0) (void)hipFree(s.d_in_chunk0);
+  if (s.d_out_cdesc) (void)hipFree(s.d_out_cdesc);
+  if (s.d_in_cdesc) (void)hipFree(s.d_in_cdesc);
+  s.d_out_cdesc = s.d_in_cdesc = nullptr;
+  s.d_ccap_out = s.d_ccap_in = 0;
   s.d_out = s.d_in = nullptr;
   s.d_out_chunk0 = s.d_in_chunk0 = nullptr;
   s.d_cap_out = s.d_cap_in = 0;
@@ -240,19 +244,28 @@ static int ensure_events(ss_ctx *ctx, std::vector<hipEvent_t> &v, size_t n, unsi
 
 // chunk-prefix per descriptor, restarting at every batch; entry [start[b+1]] of a
 // batch's run is read as its sentinel, so each batch gets count + 1 entries.
+// cdesc lists, batch after batch, the descriptor (counted from the batch's first) of every chunk;
+// cbase[b] is where batch b's chunks start in it.
 static void build_chunks(const std::vector<ss_desc_t> &d, const std::vector<uint32_t> &start,
-                         std::vector<uint32_t> &chunk0) {
+                         std::vector<uint32_t> &chunk0, std::vector<uint32_t> &cdesc,
+                         std::vector<uint64_t> &cbase) {
   size_t nb = start.size() ? start.size() - 1 : 0;
   chunk0.assign(d.size() + nb, 0);
+  cdesc.clear();
+  cbase.assign(nb + 1, 0);
   for (size_t b = 0; b < nb; ++b) {
     uint32_t run = 0;
     size_t base = start[b] + b;
+    cbase[b] = cdesc.size();
     for (uint32_t i = start[b]; i < start[b + 1]; ++i) {
       chunk0[base + (i - start[b])] = run;
-      run += (uint32_t)((d[i].nbytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
+      const uint32_t n = (uint32_t)((d[i].nbytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
+      cdesc.insert(cdesc.end(), n, i - start[b]);
+      run += n;
     }
     chunk0[base + (start[b + 1] - start[b])] = run;
   }
+  cbase[nb] = cdesc.size();
 }
 
 extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_t n_out,
@@ -312,8 +325,8 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
   if (s.in_start.empty()) s.in_start.push_back(0);
   s.in_dep.resize(n_in_batches);
   for (uint32_t b = 0; b < n_in_batches; ++b) s.in_dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
-  build_chunks(s.out, s.out_start, s.out_chunk0);
-  build_chunks(s.in, s.in_start, s.in_chunk0);
+  build_chunks(s.out, s.out_start, s.out_chunk0, s.out_cdesc, s.out_cbase);
+  build_chunks(s.in, s.in_start, s.in_chunk0, s.in_cdesc, s.in_cbase);
   s.out_of_tensor.clear();
   s.in_of_tensor.clear();
   s.out_batch_of.assign(n_out, 0);
@@ -367,6 +380,26 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
   };
   if ((rc = upload(s.out, s.out_chunk0, s.d_out, s.d_out_chunk0, s.d_cap_out)) != SS_OK) return rc;
   if ((rc = upload(s.in, s.in_chunk0, s.d_in, s.d_in_chunk0, s.d_cap_in)) != SS_OK) return rc;
+  auto upload_map = [&](const std::vector<uint32_t> &m, uint32_t *&dm, size_t &cap) -> int {
+    if (m.empty()) return SS_OK;
+    if (m.size() > cap) {
+      if (dm) SS_HIP(hipFree(dm));
+      dm = nullptr; cap = 0;
+      const size_t want = m.size() + m.size() / 4 + 1024;
+      hipError_t e = hipMalloc((void **)&dm, want * sizeof(uint32_t));
+      if (e != hipSuccess) {
+        ctx->stats.last_hip_error = (int32_t)e;
+        ss_note_hip_error((int)e, __FILE__, __LINE__);
+        (void)hipGetLastError();
+        return SS_E_NOMEM;
+      }
+      cap = want;
+    }
+    SS_HIP(hipMemcpy(dm, m.data(), m.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+    return SS_OK;
+  };
+  if ((rc = upload_map(s.out_cdesc, s.d_out_cdesc, s.d_ccap_out)) != SS_OK) return rc;
+  if ((rc = upload_map(s.in_cdesc, s.d_in_cdesc, s.d_ccap_in)) != SS_OK) return rc;
   s.loaded = true;
   return SS_OK;
 }
@@ -439,7 +472,7 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
     const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
     const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
     ss_launch_copy(ctx->s_out, ctx->cfg.copy_workgroups_out, ctx->cfg.copy_unroll, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
-                   hi - lo, n_chunks);
+                   s.d_out_cdesc + s.out_cbase[batch], n_chunks);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
@@ -476,7 +509,7 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
     const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
     const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
     ss_launch_copy(ctx->s_in, ctx->cfg.copy_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
-                   hi - lo, n_chunks);
+                   s.d_in_cdesc + s.in_cbase[batch], n_chunks);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
@@ -614,7 +647,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
   std::memset(out, 0, sizeof(*out));
   uint8_t *h0 = nullptr, *h1 = nullptr, *d0 = nullptr, *d1 = nullptr, *h0d = nullptr, *h1d = nullptr;
   ss_desc_t *dd = nullptr;
-  uint32_t *dc = nullptr;
+  uint32_t *dc = nullptr, *dm = nullptr;
   hipEvent_t a0 = nullptr, a1 = nullptr, b0 = nullptr, b1 = nullptr;
   int rc = SS_OK;
   auto ck = [&](hipError_t e) {
@@ -632,6 +665,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
   ck(hipMalloc((void **)&d1, bytes));
   ck(hipMalloc((void **)&dd, 2 * sizeof(ss_desc_t)));
   ck(hipMalloc((void **)&dc, 4 * sizeof(uint32_t)));
+  ck(hipMalloc((void **)&dm, ((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES) * sizeof(uint32_t)));
   ck(hipEventCreate(&a0)); ck(hipEventCreate(&a1)); ck(hipEventCreate(&b0)); ck(hipEventCreate(&b1));
   if (rc == SS_OK) {
     ck(hipHostGetDevicePointer((void **)&h0d, h0, 0));
@@ -644,6 +678,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
     uint32_t hc[2] = {0, (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES)};
     ck(hipMemcpy(dd, hd, sizeof(hd), hipMemcpyHostToDevice));
     ck(hipMemcpy(dc, hc, sizeof(hc), hipMemcpyHostToDevice));
+    ck(hipMemset(dm, 0, ((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES) * sizeof(uint32_t)));   // every chunk: descriptor 0
     ck(hipDeviceSynchronize());
   }
   auto median = [](std::vector<float> &v) {
@@ -662,7 +697,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       if (d2h) {
         ck(hipEventRecord(a0, ctx->s_out));
         if (mode == 3 || mode == 5) {
-          ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, 1, nchunks);
+          ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
         ck(hipEventRecord(a1, ctx->s_out));
@@ -670,7 +705,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       if (h2d) {
         ck(hipEventRecord(b0, ctx->s_in));
         if (mode == 4 || mode == 5) {
-          ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, 1, nchunks);
+          ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
         ck(hipEventRecord(b1, ctx->s_in));
@@ -697,6 +732,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
   if (b1) (void)hipEventDestroy(b1);
   if (dd) (void)hipFree(dd);
   if (dc) (void)hipFree(dc);
+  if (dm) (void)hipFree(dm);
   if (d0) (void)hipFree(d0);
   if (d1) (void)hipFree(d1);
   if (h0) (void)hipHostFree(h0);
