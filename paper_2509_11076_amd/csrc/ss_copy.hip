@@ -5,7 +5,8 @@
 // brings it back before its first backward use (Sec. 1, Sec. 5.2 of the
 // SmartSwap paper).  The paper issues one framework copy per tensor; small
 // tensors then waste the link (Sec. 4.2).  Here one launch moves a whole batch
-// of variable-size tensors: the batch is cut into 64 KiB chunks, a small
+// of variable-size tensors: the batch is cut into chunks (64 KiB, smaller for a
+// small batch so that every workgroup of the grid has work), a small
 // persistent grid walks the chunks, and each workgroup looks its chunk's
 // descriptor up in a per-chunk table built when the schedule is loaded (two
 // dependent loads per chunk, no search, no LDS).  All
@@ -27,15 +28,17 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <bool TO_HOST, uint32_t kUnroll>
 __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
     uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
-    const uint32_t *__restrict__ chunk0, const uint32_t *__restrict__ chunk_desc, uint32_t n_chunks) {
+    const uint32_t *__restrict__ chunk0, const uint32_t *__restrict__ chunk_desc, uint32_t n_chunks,
+    uint32_t chunk_shift) {
+  const uint32_t chunk_bytes = 1u << chunk_shift;     // 4 KiB .. 64 KiB, chosen per batch
   const uint32_t tid = threadIdx.x;
   for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
     // chunk_desc[c]: the descriptor chunk c belongs to; chunk0[d]: first chunk of descriptor d
     const uint32_t lo = chunk_desc[c];
     const ss_desc_t d = descs[lo];
-    const uint64_t off = (uint64_t)(c - chunk0[lo]) * SS_CHUNK_BYTES;
+    const uint64_t off = (uint64_t)(c - chunk0[lo]) << chunk_shift;
     const uint64_t left = d.nbytes - off;
-    const uint32_t n = left < SS_CHUNK_BYTES ? (uint32_t)left : SS_CHUNK_BYTES;
+    const uint32_t n = left < chunk_bytes ? (uint32_t)left : chunk_bytes;
     const uint8_t *src = TO_HOST ? arena + d.dev_off + off : staging + d.host_off + off;
     uint8_t *dst = TO_HOST ? staging + d.host_off + off : arena + d.dev_off + off;
 
@@ -75,12 +78,12 @@ __global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nby
 
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
                     uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,
-                    const uint32_t *d_chunk_desc, uint32_t n_chunks) {
+                    const uint32_t *d_chunk_desc, uint32_t n_chunks, uint32_t chunk_shift) {
   if (n_chunks == 0) return;
   const dim3 grid(workgroups < n_chunks ? workgroups : n_chunks), block(SS_COPY_THREADS);
 #define SS_LAUNCH(TH, U)                                                                                  \
   hipLaunchKernelGGL((ss_copy_kernel<TH, U>), grid, block, 0, s, arena, staging, d_descs, d_chunk0,        \
-                     d_chunk_desc, n_chunks)
+                     d_chunk_desc, n_chunks, chunk_shift)
   if (to_host) {
     if (unroll <= 2) SS_LAUNCH(true, 2); else if (unroll <= 4) SS_LAUNCH(true, 4); else SS_LAUNCH(true, 8);
   } else {

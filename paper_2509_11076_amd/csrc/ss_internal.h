@@ -15,6 +15,7 @@ struct ss_sched {
   std::vector<uint32_t> out_chunk0, in_chunk0;    // per descriptor: first chunk index inside its batch
   std::vector<uint32_t> out_cdesc, in_cdesc;      // per chunk: descriptor index inside its batch
   std::vector<uint64_t> out_cbase, in_cbase;      // per batch: where its chunks start in *_cdesc
+  std::vector<uint8_t> out_shift, in_shift;       // per batch: log2 of its chunk size
   std::unordered_map<uint32_t, uint32_t> out_of_tensor, in_of_tensor;  // tensor id -> descriptor index
   std::vector<uint32_t> out_batch_of, in_batch_of;                      // descriptor index -> batch
   std::vector<uint8_t> out_waited, in_waited, out_issued, in_issued;    // per batch, this iteration
@@ -92,11 +93,12 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
                   const ss_tensor_t *tensors, uint32_t n_tensors, ss_applied &out);
 
 // copy kernels (ss_copy.hip)
-constexpr uint32_t SS_CHUNK_BYTES = 64 * 1024;
+constexpr uint32_t SS_CHUNK_SHIFT = 16, SS_CHUNK_SHIFT_MIN = 12;
+constexpr uint32_t SS_CHUNK_BYTES = 1u << SS_CHUNK_SHIFT;   // 64 KiB; small batches use down to 4 KiB
 constexpr uint32_t SS_COPY_THREADS = 256;
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
                     uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,
-                    const uint32_t *d_chunk_desc, uint32_t n_chunks);
+                    const uint32_t *d_chunk_desc, uint32_t n_chunks, uint32_t chunk_shift);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
 
 // sequence aligner (ss_align.hip): ref_to_cur has n entries

@@ -246,20 +246,31 @@ static int ensure_events(ss_ctx *ctx, std::vector<hipEvent_t> &v, size_t n, unsi
 // batch's run is read as its sentinel, so each batch gets count + 1 entries.
 // cdesc lists, batch after batch, the descriptor (counted from the batch's first) of every chunk;
 // cbase[b] is where batch b's chunks start in it.
+// A batch is cut into 64 KiB chunks unless that gives fewer than 256 of them (four per workgroup of
+// the default grid): then the chunk size is halved down to 4 KiB, so that a batch of a few small
+// tensors still spreads over the grid instead of running on two or three workgroups.
 static void build_chunks(const std::vector<ss_desc_t> &d, const std::vector<uint32_t> &start,
                          std::vector<uint32_t> &chunk0, std::vector<uint32_t> &cdesc,
-                         std::vector<uint64_t> &cbase) {
+                         std::vector<uint64_t> &cbase, std::vector<uint8_t> &shift) {
   size_t nb = start.size() ? start.size() - 1 : 0;
   chunk0.assign(d.size() + nb, 0);
   cdesc.clear();
   cbase.assign(nb + 1, 0);
+  shift.assign(nb, (uint8_t)SS_CHUNK_SHIFT);
   for (size_t b = 0; b < nb; ++b) {
+    uint32_t sh = SS_CHUNK_SHIFT;
+    for (; sh > SS_CHUNK_SHIFT_MIN; --sh) {
+      uint64_t total = 0;
+      for (uint32_t i = start[b]; i < start[b + 1]; ++i) total += (d[i].nbytes + (1ull << sh) - 1) >> sh;
+      if (total >= 256) break;
+    }
+    shift[b] = (uint8_t)sh;
     uint32_t run = 0;
     size_t base = start[b] + b;
     cbase[b] = cdesc.size();
     for (uint32_t i = start[b]; i < start[b + 1]; ++i) {
       chunk0[base + (i - start[b])] = run;
-      const uint32_t n = (uint32_t)((d[i].nbytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
+      const uint32_t n = (uint32_t)((d[i].nbytes + (1ull << sh) - 1) >> sh);
       cdesc.insert(cdesc.end(), n, i - start[b]);
       run += n;
     }
@@ -325,8 +336,8 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
   if (s.in_start.empty()) s.in_start.push_back(0);
   s.in_dep.resize(n_in_batches);
   for (uint32_t b = 0; b < n_in_batches; ++b) s.in_dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
-  build_chunks(s.out, s.out_start, s.out_chunk0, s.out_cdesc, s.out_cbase);
-  build_chunks(s.in, s.in_start, s.in_chunk0, s.in_cdesc, s.in_cbase);
+  build_chunks(s.out, s.out_start, s.out_chunk0, s.out_cdesc, s.out_cbase, s.out_shift);
+  build_chunks(s.in, s.in_start, s.in_chunk0, s.in_cdesc, s.in_cbase, s.in_shift);
   s.out_of_tensor.clear();
   s.in_of_tensor.clear();
   s.out_batch_of.assign(n_out, 0);
@@ -472,7 +483,7 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
     const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
     const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
     ss_launch_copy(ctx->s_out, ctx->cfg.copy_workgroups_out, ctx->cfg.copy_unroll, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
-                   s.d_out_cdesc + s.out_cbase[batch], n_chunks);
+                   s.d_out_cdesc + s.out_cbase[batch], n_chunks, s.out_shift[batch]);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
@@ -509,7 +520,7 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
     const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
     const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
     ss_launch_copy(ctx->s_in, ctx->cfg.copy_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
-                   s.d_in_cdesc + s.in_cbase[batch], n_chunks);
+                   s.d_in_cdesc + s.in_cbase[batch], n_chunks, s.in_shift[batch]);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
@@ -697,7 +708,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       if (d2h) {
         ck(hipEventRecord(a0, ctx->s_out));
         if (mode == 3 || mode == 5) {
-          ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks);
+          ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
         ck(hipEventRecord(a1, ctx->s_out));
@@ -705,7 +716,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
       if (h2d) {
         ck(hipEventRecord(b0, ctx->s_in));
         if (mode == 4 || mode == 5) {
-          ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks);
+          ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
           ck(hipGetLastError());
         } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
         ck(hipEventRecord(b1, ctx->s_in));
