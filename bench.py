@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 # Memory traffic of one pack launch over its algorithmic bytes (read from HBM + written to the
 # host), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy of known size
 # (profiles/ss_copy_kernel_config2_hbm_traffic.md).
-PACK_TRAFFIC_RATIO = 1.013
+PACK_TRAFFIC_RATIO = 1.011
 
 
 def cpu_baseline(cfgno, bpo):
