@@ -118,9 +118,8 @@ typedef struct {
                                  (Eq. 3 with Eq. 1 at one operator per group); >= 1           */
   uint64_t prefetch_bytes_per_op; /* same for the swap-in queue only (0 = link_bytes_per_op); a smaller
                                  value pre-triggers swap-ins with more margin (Sec. 4.3.1)       */
-  uint64_t engine_min_bytes;  /* SS_PATH_AUTO: swap-out batches always go to the copy kernel; swap-in
-                                 batches whose mean tensor size reaches this go to the copy engine,
-                                 smaller ones to the copy kernel (default 4 MiB)              */
+  uint64_t engine_min_bytes;  /* SS_PATH_AUTO: swap-in batches whose mean tensor size reaches this go to
+                                 the copy engine, smaller ones to the copy kernel (default 4 MiB) */
   uint32_t align;             /* staging slot alignment, power of two >= 16 (default 256)    */
   uint32_t guard_bytes;       /* untouched bytes before/after each staging slot (mult. of align) */
   uint32_t stage_m, stage_n;  /* Algo. 1 hyper-parameters (defaults 2, 5)                    */
@@ -132,7 +131,10 @@ typedef struct {
   uint32_t max_ops;           /* trace capacity in operators                                 */
   uint32_t max_events;        /* trace capacity in events                                    */
   uint32_t flags;             /* SS_CFG_*                                                    */
-  uint32_t reserved[2];
+  uint64_t engine_min_bytes_out; /* SS_PATH_AUTO: the same for swap-out batches (default 32 MiB: below
+                                 that the copy engine falls far behind the link inside a running
+                                 training step, above it it reaches the link peak and, unlike a copy
+                                 kernel, does not delay the compute stream's launches); 0 = never   */
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */

@@ -56,7 +56,7 @@ class ss_config_t(C.Structure):
                 ("copy_path_in", C.c_uint32),
                 ("copy_workgroups", C.c_uint32), ("copy_workgroups_out", C.c_uint32),
                 ("copy_unroll", C.c_uint32), ("max_ops", C.c_uint32), ("max_events", C.c_uint32),
-                ("flags", C.c_uint32), ("reserved", C.c_uint32 * 2)]
+                ("flags", C.c_uint32), ("engine_min_bytes_out", C.c_uint64)]
 
 
 class ss_scan_result_t(C.Structure):

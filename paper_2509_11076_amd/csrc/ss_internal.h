@@ -24,6 +24,8 @@ struct ss_sched {
   uint32_t *d_out_chunk0 = nullptr, *d_in_chunk0 = nullptr;
   uint32_t *d_out_cdesc = nullptr, *d_in_cdesc = nullptr;
   size_t d_cap_out = 0, d_cap_in = 0, d_ccap_out = 0, d_ccap_in = 0;
+  bool out_all_large = false;                     // every swap-out batch reaches engine_min_bytes_out (mean tensor size)
+  int64_t last_engine_out = -1;                   // last swap-out batch of this iteration that went by copy engine
   bool loaded = false;
 };
 

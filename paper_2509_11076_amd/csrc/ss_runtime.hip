@@ -47,6 +47,7 @@ extern "C" int ss_config_default(ss_config_t *cfg) {
   cfg->staging_bytes = 64ull << 20;
   cfg->link_bytes_per_op = 64ull << 20;
   cfg->engine_min_bytes = 4ull << 20;
+  cfg->engine_min_bytes_out = 32ull << 20;
   cfg->align = 256;
   cfg->guard_bytes = 0;
   cfg->stage_m = 2;
@@ -324,6 +325,7 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
       std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
       std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
       std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
+      s.last_engine_out = -1;
       return SS_OK;
     }
   }
@@ -356,6 +358,14 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
   s.out_issued.assign(n_out_batches, 0);
   s.in_waited.assign(n_in_batches, 0);
   s.in_issued.assign(n_in_batches, 0);
+  s.last_engine_out = -1;
+  s.out_all_large = ctx->cfg.engine_min_bytes_out != 0 && n_out_batches != 0;
+  for (uint32_t b = 0; b < n_out_batches && s.out_all_large; ++b) {
+    uint64_t total = 0;
+    const uint32_t cnt = s.out_start[b + 1] - s.out_start[b];
+    for (uint32_t i = s.out_start[b]; i < s.out_start[b + 1]; ++i) total += s.out[i].nbytes;
+    if (cnt && total / cnt < ctx->cfg.engine_min_bytes_out) s.out_all_large = false;
+  }
 
   const unsigned evflags = ((ctx->cfg.flags & SS_CFG_TIMING) ? hipEventDefault : hipEventDisableTiming) |
                            fence_flag(ctx->cfg);
@@ -437,15 +447,21 @@ extern "C" int ss_schedule_view(ss_ctx *ctx, const uint32_t **out_start, uint32_
 //  - large tensors coming back (swap-in) while the training step computes: the copy engine
 //    runs at full link rate and leaves the compute stream alone, whereas a copy kernel that
 //    saturates the link delays every concurrent kernel launch -> engine;
-//  - large tensors leaving (swap-out) under a running compute stream: engine copies fell to
-//    about 15 GB/s there, the copy kernel holds 50-55 GB/s -> kernel.
-// SS_PATH_AUTO therefore means: swap-out always by kernel; swap-in by engine once the batch's
-// mean tensor size reaches engine_min_bytes, else by kernel.
+//  - tensors leaving (swap-out) under a running compute stream: engine copies of 8-16 MiB fell to
+//    about 15 GB/s there while the copy kernel holds 50-55 GB/s -> kernel; from 32 MiB on the
+//    engine reaches the link peak (93-99 %) and leaves the compute stream alone -> engine.
+//    Engine and kernel swap-outs must not alternate on the stream: configuration 2 with its 32 and
+//    64 MiB tensors by engine and its 8 and 16 MiB tensors by kernel took 215 ms against 126 ms all
+//    by kernel.
+// SS_PATH_AUTO therefore means: a swap-in batch goes by engine once its mean tensor size reaches
+// engine_min_bytes, else by kernel; the swap-out side goes by engine as a whole if every batch of the
+// schedule reaches engine_min_bytes_out, else by kernel as a whole.
 static bool use_engine(const ss_ctx *ctx, uint32_t path, bool to_host, const std::vector<ss_desc_t> &d,
                        uint32_t lo, uint32_t hi) {
   if (path == SS_PATH_ENGINE) return true;
   if (path == SS_PATH_KERNEL) return false;
-  if (to_host || hi <= lo) return false;
+  if (to_host) return ctx->sched.out_all_large;        // one path for the whole swap-out side (see above)
+  if (hi <= lo) return false;
   uint64_t total = 0;
   for (uint32_t i = lo; i < hi; ++i) total += d[i].nbytes;
   return total / (hi - lo) >= ctx->cfg.engine_min_bytes;
@@ -479,6 +495,7 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
         SS_HIP(hipMemcpyAsync(ctx->staging + s.out[i].host_off, ctx->arena + s.out[i].dev_off, s.out[i].nbytes,
                               hipMemcpyDeviceToHost, ctx->s_out));
     ctx->stats.engine_batches++;
+    s.last_engine_out = batch;
   } else {
     const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
     const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
@@ -507,6 +524,10 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
   SS_HIP(hipStreamWaitEvent(ctx->s_in, mark, 0));
   // staging slots must be completely written
   if (hi > lo) SS_HIP(hipStreamWaitEvent(ctx->s_in, s.ev_out_done[s.in_dep[batch]], 0));
+  // a copy-engine swap-out collapses to a quarter of the link rate as soon as anything flows the
+  // other way: no swap-in starts before the engine swap-outs issued so far have finished
+  if (s.last_engine_out >= 0 && (hi <= lo || (int64_t)s.in_dep[batch] < s.last_engine_out))
+    SS_HIP(hipStreamWaitEvent(ctx->s_in, s.ev_out_done[(size_t)s.last_engine_out], 0));
   if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_in_start[batch], ctx->s_in));
   uint64_t bytes = 0;
   for (uint32_t i = lo; i < hi; ++i) bytes += s.in[i].nbytes;
@@ -573,6 +594,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
       std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
       std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
       std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
+      s.last_engine_out = -1;
       return SS_OK;
     }
     default: return SS_E_INVAL;
