@@ -516,8 +516,9 @@ def main():
     t_floor_serial = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9) + bytes_way / (bw["h2d_gbps"] * 1e9))
     # roofline of the copy kernel: only the launches that really were kernel launches
     n_out_l, n_in_l = len(out_ms), len(in_ms)
-    out_by_kernel = path != B.SS_PATH_ENGINE                      # AUTO sends swap-outs to the kernel
-    engine_in = engine_batches - (0 if out_by_kernel else n_out_l)
+    engine_out = st1["engine_batches_out"] - st0["engine_batches_out"]
+    out_by_kernel = engine_out == 0                               # a mix of paths does not occur on this side
+    engine_in = engine_batches - engine_out
     in_by_kernel = engine_in == 0                                 # a mix of paths is left out of the figure
     k_ms = (out_ms if out_by_kernel else []) + (in_ms if in_by_kernel else [])
     k_bytes = bytes_way * args.steps * (int(out_by_kernel) + int(in_by_kernel))
@@ -550,6 +551,8 @@ def main():
                    "in_batches": int(applied["n_in_batches"]), "copy_path_out": args.path,
                    "copy_path_in": args.path_in or args.path,
                    "kernel_launches": int(kernel_batches), "engine_batches": int(engine_batches),
+                   "swap_out_by": "copy kernel" if out_by_kernel else "copy engine",
+                   "swap_in_by": "copy kernel" if in_by_kernel else ("copy engine" if engine_in == n_in_l else "both"),
                    "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "pack_grid_fits": grid_fits,
                    "pack_workgroups": args.workgroups_out or args.workgroups or "default (64)", "policy_mode": args.policy_mode,
                    "timing": args.timing if args.policy_mode == "generated" else "link-model",

@@ -181,7 +181,7 @@ typedef struct {
   uint64_t free_waits, in_waits;        /* device-side stream waits issued for FREE / WAIT_IN */
   uint64_t ops_recorded, events_recorded;
   int32_t last_hip_error;               /* hipError_t of the last failing HIP call, 0 if none */
-  uint32_t reserved;
+  uint32_t engine_batches_out;          /* of engine_batches, the swap-out ones             */
 } ss_stats_t;
 
 typedef struct {

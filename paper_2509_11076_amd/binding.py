@@ -94,7 +94,7 @@ class ss_stats_t(C.Structure):
     _fields_ = [("bytes_out", C.c_uint64), ("bytes_in", C.c_uint64), ("kernel_batches", C.c_uint64),
                 ("engine_batches", C.c_uint64), ("free_waits", C.c_uint64), ("in_waits", C.c_uint64),
                 ("ops_recorded", C.c_uint64), ("events_recorded", C.c_uint64),
-                ("last_hip_error", C.c_int32), ("reserved", C.c_uint32)]
+                ("last_hip_error", C.c_int32), ("engine_batches_out", C.c_uint32)]
 
 
 class ss_bw_t(C.Structure):

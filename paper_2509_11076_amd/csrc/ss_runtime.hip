@@ -495,6 +495,7 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
         SS_HIP(hipMemcpyAsync(ctx->staging + s.out[i].host_off, ctx->arena + s.out[i].dev_off, s.out[i].nbytes,
                               hipMemcpyDeviceToHost, ctx->s_out));
     ctx->stats.engine_batches++;
+    ctx->stats.engine_batches_out++;
     s.last_engine_out = batch;
   } else {
     const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
