@@ -240,3 +240,45 @@ def test_small_tensor_stress_reduced(P, torch):
             assert np.array_equal(got, sp.read(d[0], d[2])) and np.array_equal(got, before[d[3]])
     finally:
         P.ss_destroy(ctx)
+
+
+def test_auto_path_of_the_swap_out_side_follows_the_smallest_batch(P, torch):
+    """SS_PATH_AUTO: a schedule whose swap-out batches all reach engine_min_bytes_out goes by copy
+    engine as a whole, one with a smaller batch goes by copy kernel as a whole; the bytes are the
+    same either way"""
+    big = 32 << 20
+    arena_bytes = 4 * big
+    arena = random_arena(torch, arena_bytes, 5)
+    want = arena.clone()
+    for sizes, engine_out in (((big, big + 4096), True), ((big, big + 4096, 1 << 20), False)):
+        d = np.zeros(len(sizes), dtype=W.DESC_DT)
+        off = 0
+        for i, n in enumerate(sizes):
+            d[i] = (off, off, n, i, 0)
+            off += (n + 255) // 256 * 256
+        start = np.arange(len(sizes) + 1, dtype=np.uint32)           # one batch per tensor
+        ctx = make_ctx(P, staging_bytes=off)
+        try:
+            P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+            P.ss_load_schedule(ctx, d, start, d, start)
+            for b in range(len(sizes)):
+                P.ss_swap_out(ctx, b)
+            for i in range(len(sizes)):
+                P.ss_sync(ctx, P.SS_SYNC_FREE, i)
+            arena.zero_()                                            # the blocks are free: overwrite them
+            for b in range(len(sizes)):
+                P.ss_swap_in(ctx, b)
+            for i in range(len(sizes)):
+                P.ss_sync(ctx, P.SS_SYNC_WAIT_IN, i)
+            P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+            torch.cuda.synchronize()
+            st = P.ss_get_stats(ctx)
+            assert st["engine_batches_out"] == (len(sizes) if engine_out else 0)
+            assert st["kernel_batches"] == (0 if engine_out else len(sizes) + 1)   # + the 1 MiB swap-in
+            assert st["bytes_out"] == st["bytes_in"] == sum(sizes)
+            for i, n in enumerate(sizes):
+                o = int(d["dev_off"][i])
+                assert torch.equal(arena[o:o + n], want[o:o + n]), i
+        finally:
+            P.ss_destroy(ctx)
+        arena.copy_(want)
