@@ -239,3 +239,26 @@ def test_per_phase_time_moves_release_points_later_in_a_fast_forward_pass():
     ev = W.transformer.events_of(tab)
     after = oracle.timeline_scan(ev, pe, 24, 0, 400)
     assert after["n_over"] == 7          # operators 8..14 still hold A: the scan of the finished policy says so
+
+
+def test_moved_points_that_no_longer_fit_are_dropped_or_clamped():
+    """a policy item made for a tensor used at operators 2 .. 20 (released after 5, back before 15)
+    meets a tensor that is now used at 2 .. 8: the pre-trigger point moves with the use (15 - 12 = 3)
+    and lands before the release point 5 - the item is dropped, or, when every item must be executed,
+    clamped around the use and marked forced"""
+    pol = np.zeros(1, dtype=W.POLICY_DT)
+    pol[0] = (1, 0, 0, 0, 2, 5, 15, 20, 4096)
+    tab = table([(1, 2, 8, 9, 4096)])
+    tab["producer_op"] = 1
+    ap = oracle.apply_policy(pol, [1], tab, 1 << 30, policy_points=True)
+    assert ap["n_dropped"] == 1 and ap["actions"] == [] and ap["resolved"][0][3] & oracle.F_ORDER
+    ap = oracle.apply_policy(pol, [1], tab, 1 << 30, policy_points=True, keep_late=True)
+    r = ap["resolved"][0]
+    # t_free keeps 5 (inside 2 .. 7), t_in = max(3, t_free + 1) = 6
+    assert ap["n_dropped"] == 0 and (r[4], r[5], r[6], r[7]) == (2, 5, 6, 8)
+    assert r[3] & oracle.F_FORCED and r[3] & oracle.F_LATE
+    # uses so close that nothing fits between them: released after the last forward use, back at the use
+    tab2 = table([(1, 2, 3, 4, 4096)])
+    tab2["producer_op"] = 1
+    r = oracle.apply_policy(pol, [1], tab2, 1 << 30, policy_points=True, keep_late=True)["resolved"][0]
+    assert (r[4], r[5], r[6], r[7]) == (2, 2, 3, 3)
