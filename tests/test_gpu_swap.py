@@ -282,3 +282,44 @@ def test_auto_path_of_the_swap_out_side_follows_the_smallest_batch(P, torch):
         finally:
             P.ss_destroy(ctx)
         arena.copy_(want)
+
+
+def test_link_probe_and_batch_windows(P, torch):
+    """ss_bw_probe reports all eight rates of the host link (loose sanity bounds: no figure of merit
+    is asserted here); ss_batch_window orders the batches of a direction; argument errors"""
+    ctx = make_ctx(P, staging_bytes=8 << 20, flags=P.SS_CFG_TIMING)
+    try:
+        bw = P.ss_bw_probe(ctx, 64 << 20, 3)
+        assert set(bw) == {"d2h_gbps", "h2d_gbps", "bidir_d2h_gbps", "bidir_h2d_gbps", "kernel_d2h_gbps",
+                           "kernel_h2d_gbps", "kernel_bidir_d2h_gbps", "kernel_bidir_h2d_gbps"}
+        assert all(0.5 < v < 500 for v in bw.values()), bw
+        for bad in ((1024, 3), (64 << 20, 0), (64 << 20, 1001)):
+            with pytest.raises(P.SsError) as e:
+                P.ss_bw_probe(ctx, *bad)
+            assert e.value.code == P.SS_E_INVAL
+        n = 4 << 20
+        arena = random_arena(torch, 2 * n, 3)
+        want = arena.clone()
+        d = np.zeros(2, dtype=W.DESC_DT)
+        d[0] = (0, 0, n, 0, 0)
+        d[1] = (n, n, n, 1, 0)
+        start = np.arange(3, dtype=np.uint32)
+        P.ss_bind(ctx, arena.data_ptr(), 2 * n, torch.cuda.current_stream().cuda_stream)
+        P.ss_load_schedule(ctx, d, start, d, start)
+        for b in range(2):
+            P.ss_swap_out(ctx, b)
+        for b in range(2):
+            P.ss_swap_in(ctx, b)
+        P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+        torch.cuda.synchronize()
+        w = [P.ss_batch_window(ctx, dr, b) for dr in (0, 1) for b in (0, 1)]
+        assert w[0][0] == 0.0 and all(s <= e for s, e in w)
+        assert w[0][1] <= w[1][0] and w[2][1] <= w[3][0]          # one stream per direction: in order
+        assert w[1][1] <= w[2][0]                                  # a swap-in starts after the swap-out it reads
+        ms, span = P.ss_batch_ms(ctx, 0, 1)
+        assert 0 < ms <= span
+        with pytest.raises(P.SsError):
+            P.ss_batch_window(ctx, 0, 2)
+        assert torch.equal(arena, want)
+    finally:
+        P.ss_destroy(ctx)
