@@ -48,3 +48,16 @@ from .policy import (link_timing, apply_policy, greedy_policy, schedule_check,
 from .swap import swap_out, swap_in, SparseArena
 from .generator import generate_policy, generate_policy_best, logical_layers
 from .align import align, align_anchors, lcs_table, LEVEL_ALIGN
+
+# The library's call names for the steps that have a one-to-one counterpart here, so that a parity
+# test can address both sides by the same name (recording is TraceRecorder.record; the ordering
+# calls of the executor have no arithmetic to restate).
+ss_timeline_scan = timeline_scan
+ss_match_sequence = match_sequence
+ss_apply_policy = apply_policy
+ss_greedy_policy = greedy_policy
+ss_generate_policy = generate_policy
+ss_generate_policy_best = generate_policy_best
+ss_align_sequence = align_anchors
+ss_swap_out = swap_out
+ss_swap_in = swap_in
