@@ -106,10 +106,8 @@ def ragged_schedule(seed, n, arena_bytes, max_bytes):
     return descs, host + 256
 
 
-@pytest.mark.parametrize("path", ["kernel", "engine"])
-def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
-    arena_bytes = 8 << 20
-    descs, staging_bytes = ragged_schedule(3, 40, arena_bytes // 2, 200000)
+def ragged_round_trip(P, torch, path, seed=3, n=40, max_bytes=200000, arena_bytes=8 << 20, **cfg):
+    descs, staging_bytes = ragged_schedule(seed, n, arena_bytes // 2, max_bytes)
     n = len(descs)
     out_start = np.array([0, 0, 7, 7, 20, n, n], dtype=np.uint32)       # batches 0, 2 and 5 are empty
     # swap-in to other blocks (upper half of the arena), in another order and batching
@@ -121,7 +119,7 @@ def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
     host_arena = arena.cpu().numpy().copy()
     ctx = make_ctx(P, staging_bytes=staging_bytes, align=16,
                    copy_path=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE,
-                   copy_path_in=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE)
+                   copy_path_in=P.SS_PATH_KERNEL if path == "kernel" else P.SS_PATH_ENGINE, **cfg)
     try:
         P.ss_bind(ctx, arena.data_ptr(), arena_bytes, 0)
         P.ss_load_schedule(ctx, descs, out_start, descs_in, in_start, None)
@@ -138,6 +136,26 @@ def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
         assert np.array_equal(arena.cpu().numpy(), host_arena)
     finally:
         P.ss_destroy(ctx)
+
+
+@pytest.mark.parametrize("path", ["kernel", "engine"])
+def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
+    ragged_round_trip(P, torch, path)
+
+
+@pytest.mark.parametrize("workgroups,workgroups_out,unroll", [(1, 1, 1), (3, 5, 2), (64, 8, 4), (4096, 4096, 8), (0, 0, 0)])
+def test_every_launch_shape_within_the_limits_moves_the_same_bytes(P, torch, workgroups, workgroups_out, unroll):
+    """grids from one workgroup to the maximum, every unroll depth, tensors of up to 40 chunks in batches
+    whose chunk size differs; and once with system-scope ordering events"""
+    ragged_round_trip(P, torch, "kernel", seed=5, n=60, max_bytes=2500000, arena_bytes=256 << 20,
+                      copy_workgroups=workgroups, copy_workgroups_out=workgroups_out, copy_unroll=unroll)
+    if workgroups == 0:
+        ragged_round_trip(P, torch, "kernel", seed=6, n=60, max_bytes=300000, arena_bytes=64 << 20,
+                          flags=P.SS_CFG_SYSTEM_FENCE)
+        for bad in (dict(copy_workgroups=4097), dict(copy_unroll=9), dict(copy_workgroups_out=5000)):
+            with pytest.raises(P.SsError) as e:
+                make_ctx(P, staging_bytes=4096, **bad)
+            assert e.value.code == P.SS_E_INVAL
 
 
 def test_schedule_validation_and_call_order_errors(P, torch):
