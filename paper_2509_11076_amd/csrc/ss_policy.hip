@@ -26,6 +26,33 @@ struct Live {
 
 typedef unsigned __int128 u128;
 
+// Stable sort of idx by key[idx[i]] ascending: least-significant-digit radix passes of 11 bits,
+// skipping digits in which all keys agree.  Every ordering below is "by an operator index, ties by an
+// order the list already has", so a stable pass over a pre-ordered list replaces a comparison sort
+// (20,000 items: 0.1 ms instead of 2 ms per ordering).
+template <class K>
+void stable_sort_by(std::vector<uint32_t> &idx, const std::vector<K> &key, std::vector<uint32_t> &tmp) {
+  const size_t n = idx.size();
+  if (n < 2) return;
+  K differ = 0;
+  for (size_t i = 1; i < n; ++i) differ |= key[idx[i]] ^ key[idx[0]];
+  tmp.resize(n);
+  for (unsigned shift = 0; shift < 8 * sizeof(K); shift += 11) {
+    if (((differ >> shift) & 2047) == 0) continue;
+    uint32_t count[2049] = {0};
+    for (size_t i = 0; i < n; ++i) count[((key[idx[i]] >> shift) & 2047) + 1]++;
+    for (unsigned d = 0; d < 2048; ++d) count[d + 1] += count[d];
+    for (size_t i = 0; i < n; ++i) tmp[count[(key[idx[i]] >> shift) & 2047]++] = idx[i];
+    idx.swap(tmp);
+  }
+}
+
+std::vector<uint32_t> identity(size_t n) {
+  std::vector<uint32_t> v(n);
+  std::iota(v.begin(), v.end(), 0u);
+  return v;
+}
+
 }  // namespace
 
 int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32_t k, const int32_t *new_idx,
@@ -33,22 +60,26 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
   const uint64_t bpo = cfg.link_bytes_per_op;
   const uint64_t align = cfg.align, guard = cfg.guard_bytes;
   // (producer operator, output slot) -> row of the tensor table
-  std::vector<std::pair<uint64_t, uint32_t>> index(n_tensors);
+  std::vector<uint64_t> row_key(n_tensors);
+  std::vector<uint32_t> scratch;
   uint32_t max_op = 0;
   for (uint32_t r = 0; r < n_tensors; ++r) {
-    index[r] = {((uint64_t)tensors[r].producer_op << 32) | tensors[r].out_slot, r};
+    row_key[r] = ((uint64_t)tensors[r].producer_op << 32) | tensors[r].out_slot;
     if (tensors[r].first_bwd_use != SS_NONE_OP) max_op = std::max(max_op, tensors[r].first_bwd_use);
   }
   const uint64_t bpo_in = cfg.prefetch_bytes_per_op ? cfg.prefetch_bytes_per_op : bpo;
   // link times are kept below 2^63
   if ((u128)(max_op + 2ull) * bpo >= ((u128)1 << 62)) return SS_E_INVAL;
   if ((u128)(max_op + 2ull) * bpo_in >= ((u128)1 << 62)) return SS_E_INVAL;
-  std::sort(index.begin(), index.end());
+  std::vector<uint32_t> rows_sorted = identity(n_tensors);     // by (key, row)
+  stable_sort_by(rows_sorted, row_key, scratch);
+  std::vector<uint64_t> keys_sorted(n_tensors);
+  for (uint32_t i = 0; i < n_tensors; ++i) keys_sorted[i] = row_key[rows_sorted[i]];
   auto find_row = [&](uint32_t op, uint32_t slot, uint32_t &row) {
     const uint64_t key = ((uint64_t)op << 32) | slot;
-    auto it = std::lower_bound(index.begin(), index.end(), std::make_pair(key, 0u));
-    if (it == index.end() || it->first != key) return false;
-    row = it->second;
+    auto it = std::lower_bound(keys_sorted.begin(), keys_sorted.end(), key);
+    if (it == keys_sorted.end() || *it != key) return false;
+    row = rows_sorted[it - keys_sorted.begin()];
     return true;
   };
 
@@ -79,6 +110,13 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
     live.push_back(L);
   }
 
+  // live is in policy-index order, so a stable ordering by an operator index alone is "(operator, policy index)"
+  std::vector<uint64_t> k_out(live.size()), k_use(live.size());
+  for (size_t i = 0; i < live.size(); ++i) {
+    k_out[i] = live[i].t_out;
+    k_use[i] = live[i].t_use;
+  }
+
   if (cfg.flags & SS_CFG_POLICY_POINTS) {
     // The generator already fixed release and pre-trigger points (Sec. 4.3, 4.4): keep them, moved
     // along with the tensor's own last forward use / first backward use in this iteration.
@@ -98,11 +136,8 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
       L.t_in = ok ? (uint64_t)ti : 0;
       L.late = (p.flags & SS_F_LATE) != 0 || L.forced;
     }
-    std::vector<uint32_t> need(live.size());
-    std::iota(need.begin(), need.end(), 0u);
-    std::sort(need.begin(), need.end(), [&](uint32_t x, uint32_t y) {
-      return live[x].t_use != live[y].t_use ? live[x].t_use < live[y].t_use : live[x].a < live[y].a;
-    });
+    std::vector<uint32_t> need = identity(live.size());
+    stable_sort_by(need, k_use, scratch);            // (t_use, policy index)
     uint64_t run = 0;                              // first-in first-out order of need
     for (uint32_t i : need) {
       Live &L = live[i];
@@ -112,11 +147,8 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
     }
   } else {
     // swap-out queue: FIFO in (t_out, policy index) order
-    std::vector<uint32_t> ord(live.size());
-    std::iota(ord.begin(), ord.end(), 0u);
-    std::sort(ord.begin(), ord.end(), [&](uint32_t x, uint32_t y) {
-      return live[x].t_out != live[y].t_out ? live[x].t_out < live[y].t_out : live[x].a < live[y].a;
-    });
+    std::vector<uint32_t> ord = identity(live.size());
+    stable_sort_by(ord, k_out, scratch);             // (t_out, policy index)
     uint64_t link_free = 0;
     for (uint32_t i : ord) {
       Live &L = live[i];
@@ -136,9 +168,9 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
       }
     }
     // swap-in queue: as late as possible, walking (t_use, policy index) downwards
-    std::sort(ord.begin(), ord.end(), [&](uint32_t x, uint32_t y) {
-      return live[x].t_use != live[y].t_use ? live[x].t_use > live[y].t_use : live[x].a > live[y].a;
-    });
+    ord = identity(live.size());
+    stable_sort_by(ord, k_use, scratch);             // (t_use, policy index) upwards ...
+    std::reverse(ord.begin(), ord.end());            // ... walked downwards
     // No swap-in is issued before the last swap-out has been issued: until then memory is still
     // climbing to its peak and a swap-in would only fight the swap-outs for the link (Sec. 4.3.1:
     // the search for a swap-in slot does not go back beyond the peak-memory period).
@@ -212,15 +244,8 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
 
   // queue ranks
   std::vector<uint32_t> out_order(kept), in_order(kept);
-  std::sort(out_order.begin(), out_order.end(), [&](uint32_t x, uint32_t y) {
-    return live[x].t_out != live[y].t_out ? live[x].t_out < live[y].t_out : live[x].a < live[y].a;
-  });
-  std::sort(in_order.begin(), in_order.end(), [&](uint32_t x, uint32_t y) {
-    return live[x].t_use != live[y].t_use ? live[x].t_use < live[y].t_use : live[x].a < live[y].a;
-  });
-  std::vector<uint32_t> out_rank(live.size(), 0), in_rank(live.size(), 0);
-  for (uint32_t r = 0; r < out_order.size(); ++r) out_rank[out_order[r]] = r;
-  for (uint32_t r = 0; r < in_order.size(); ++r) in_rank[in_order[r]] = r;
+  stable_sort_by(out_order, k_out, scratch);         // kept is in policy-index order: (t_out, policy index)
+  stable_sort_by(in_order, k_use, scratch);          // (t_use, policy index)
 
   // staging slots: exclusive prefix sum of aligned sizes (+ guard) in swap-out order
   std::vector<uint64_t> host_off(live.size(), 0);
@@ -244,10 +269,12 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
   }
   out.out_start.push_back((uint32_t)out.out.size());
   // swap-in batches: issued before the same operator and first used by the same operator, in swap-in queue order
-  std::vector<uint32_t> in_issue(kept);
-  std::sort(in_issue.begin(), in_issue.end(), [&](uint32_t x, uint32_t y) {
-    return live[x].t_in != live[y].t_in ? live[x].t_in < live[y].t_in : in_rank[x] < in_rank[y];
-  });
+  std::vector<uint32_t> in_issue(in_order);          // in swap-in rank order; now by (t_in, rank)
+  {
+    std::vector<uint64_t> k_in(live.size());
+    for (size_t i = 0; i < live.size(); ++i) k_in[i] = live[i].t_in;
+    stable_sort_by(in_issue, k_in, scratch);
+  }
   out.in_start.assign(1, 0);
   for (size_t p = 0; p < in_issue.size(); ++p) {
     const uint32_t i = in_issue[p];
@@ -264,44 +291,50 @@ int ss_apply_core(const ss_config_t &cfg, const ss_policy_item_t *policy, uint32
   }
   out.in_start.push_back((uint32_t)out.in.size());
 
-  // actions, sorted by (operator, kind, queue rank)
-  struct Keyed { uint64_t op; uint32_t kind, rank; ss_action_t act; };
-  std::vector<Keyed> acts;
-  acts.reserve(4 * kept.size());
-  for (uint32_t i : kept) {
-    const Live &L = live[i];
-    const uint32_t tid = tensors[L.row].tensor_id;
-    acts.push_back({L.t_in, SS_ACT_IN, in_rank[i], {(uint32_t)L.t_in, SS_ACT_IN, tid, in_batch[i]}});
-    acts.push_back({L.t_use, SS_ACT_WAIT_IN, in_rank[i], {(uint32_t)L.t_use, SS_ACT_WAIT_IN, tid, in_batch[i]}});
-    acts.push_back({L.t_out, SS_ACT_OUT, out_rank[i], {(uint32_t)L.t_out, SS_ACT_OUT, tid, out_batch[i]}});
-    acts.push_back({L.t_free, SS_ACT_FREE, out_rank[i], {(uint32_t)L.t_free, SS_ACT_FREE, tid, out_batch[i]}});
+  // actions, sorted by (operator, kind, queue rank): listed kind after kind (IN < WAIT_IN < OUT < FREE)
+  // in rank order, then ordered by operator alone with a stable pass
+  {
+    const size_t nk = kept.size();
+    std::vector<ss_action_t> list;
+    list.reserve(4 * nk);
+    std::vector<uint64_t> op_of;
+    op_of.reserve(4 * nk);
+    auto push = [&](uint64_t op, uint32_t kind, uint32_t i, uint32_t batch) {
+      list.push_back(ss_action_t{(uint32_t)op, kind, tensors[live[i].row].tensor_id, batch});
+      op_of.push_back(op);
+    };
+    static_assert(SS_ACT_IN < SS_ACT_WAIT_IN && SS_ACT_WAIT_IN < SS_ACT_OUT && SS_ACT_OUT < SS_ACT_FREE, "kind order");
+    for (uint32_t i : in_order) push(live[i].t_in, SS_ACT_IN, i, in_batch[i]);
+    for (uint32_t i : in_order) push(live[i].t_use, SS_ACT_WAIT_IN, i, in_batch[i]);
+    for (uint32_t i : out_order) push(live[i].t_out, SS_ACT_OUT, i, out_batch[i]);
+    for (uint32_t i : out_order) push(live[i].t_free, SS_ACT_FREE, i, out_batch[i]);
+    std::vector<uint32_t> order = identity(list.size());
+    stable_sort_by(order, op_of, scratch);
+    out.actions.reserve(list.size());
+    for (uint32_t j : order) out.actions.push_back(list[j]);
   }
-  std::sort(acts.begin(), acts.end(), [](const Keyed &x, const Keyed &y) {
-    if (x.op != y.op) return x.op < y.op;
-    if (x.kind != y.kind) return x.kind < y.kind;
-    return x.rank < y.rank;
-  });
-  out.actions.reserve(acts.size());
-  for (const Keyed &x : acts) out.actions.push_back(x.act);
 
   // policy events for the timeline scan: release at t_free, allocation at t_in; operator
   // order, allocations first inside an operator, then swap-out rank
-  struct KeyedEv { uint64_t op; uint32_t neg, rank; ss_event_t ev; };
-  std::vector<KeyedEv> pe;
-  pe.reserve(2 * kept.size());
-  for (uint32_t i : kept) {
-    const Live &L = live[i];
-    const uint32_t tid = tensors[L.row].tensor_id;
-    pe.push_back({L.t_free, 1, out_rank[i], {(uint32_t)L.t_free, tid, -(int64_t)L.nbytes}});
-    pe.push_back({L.t_in, 0, out_rank[i], {(uint32_t)L.t_in, tid, (int64_t)L.nbytes}});
+  {
+    const size_t nk = kept.size();
+    std::vector<ss_event_t> list;
+    list.reserve(2 * nk);
+    std::vector<uint64_t> op_of;
+    op_of.reserve(2 * nk);
+    for (uint32_t i : out_order) {
+      list.push_back(ss_event_t{(uint32_t)live[i].t_in, tensors[live[i].row].tensor_id, (int64_t)live[i].nbytes});
+      op_of.push_back(live[i].t_in);
+    }
+    for (uint32_t i : out_order) {
+      list.push_back(ss_event_t{(uint32_t)live[i].t_free, tensors[live[i].row].tensor_id, -(int64_t)live[i].nbytes});
+      op_of.push_back(live[i].t_free);
+    }
+    std::vector<uint32_t> order = identity(list.size());
+    stable_sort_by(order, op_of, scratch);
+    out.pevents.reserve(list.size());
+    for (uint32_t j : order) out.pevents.push_back(list[j]);
   }
-  std::sort(pe.begin(), pe.end(), [](const KeyedEv &x, const KeyedEv &y) {
-    if (x.op != y.op) return x.op < y.op;
-    if (x.neg != y.neg) return x.neg < y.neg;
-    return x.rank < y.rank;
-  });
-  out.pevents.reserve(pe.size());
-  for (const KeyedEv &x : pe) out.pevents.push_back(x.ev);
   return SS_OK;
 }
 

@@ -289,10 +289,36 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
   int rc;
   if ((rc = check_batches(out_start, n_out_batches, n_out)) != SS_OK) return rc;
   if ((rc = check_batches(in_start, n_in_batches, n_in)) != SS_OK) return rc;
-  if ((rc = check_descs(ctx, descs_out, n_out)) != SS_OK) return rc;
-  if ((rc = check_descs(ctx, descs_in, n_in)) != SS_OK) return rc;
   for (uint32_t b = 0; in_dep && b < n_in_batches; ++b)
     if (n_out_batches == 0 || in_dep[b] >= n_out_batches) return SS_E_INVAL;
+  ss_sched &s = ctx->sched;
+  // the same schedule as the one already loaded (a fixed operator sequence in the Stable stage): it was
+  // validated against this arena and staging area when it was loaded; device tables, chunk tables and
+  // events stay, only the per-iteration state starts over
+  {
+    std::vector<uint32_t> dep(n_in_batches);
+    for (uint32_t b = 0; b < n_in_batches; ++b) dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
+    const bool same =
+        s.loaded && s.out.size() == n_out && s.in.size() == n_in && s.out_start.size() == (size_t)n_out_batches + 1 &&
+        s.in_start.size() == (size_t)n_in_batches + 1 && s.in_dep == dep &&
+        (n_out == 0 || std::memcmp(s.out.data(), descs_out, (size_t)n_out * sizeof(ss_desc_t)) == 0) &&
+        (n_in == 0 || std::memcmp(s.in.data(), descs_in, (size_t)n_in * sizeof(ss_desc_t)) == 0) &&
+        (n_out_batches == 0 || std::memcmp(s.out_start.data(), out_start, ((size_t)n_out_batches + 1) * 4) == 0) &&
+        (n_in_batches == 0 || std::memcmp(s.in_start.data(), in_start, ((size_t)n_in_batches + 1) * 4) == 0);
+    if (same) {
+      // nothing of the previous iteration may still be in flight
+      SS_HIP(hipStreamSynchronize(ctx->s_out));
+      SS_HIP(hipStreamSynchronize(ctx->s_in));
+      std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
+      std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
+      std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
+      std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
+      s.last_engine_out = -1;
+      return SS_OK;
+    }
+  }
+  if ((rc = check_descs(ctx, descs_out, n_out)) != SS_OK) return rc;
+  if ((rc = check_descs(ctx, descs_in, n_in)) != SS_OK) return rc;
   // staging slots of the swap-out side must be pairwise disjoint
   {
     std::vector<std::pair<uint64_t, uint64_t>> iv;
@@ -307,28 +333,6 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
   SS_HIP(hipStreamSynchronize(ctx->s_out));
   SS_HIP(hipStreamSynchronize(ctx->s_in));
 
-  ss_sched &s = ctx->sched;
-  // the same schedule as the one already loaded (a fixed operator sequence in the Stable stage):
-  // device tables, chunk tables and events stay; only the per-iteration state starts over
-  {
-    std::vector<uint32_t> dep(n_in_batches);
-    for (uint32_t b = 0; b < n_in_batches; ++b) dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
-    const bool same =
-        s.loaded && s.out.size() == n_out && s.in.size() == n_in && s.out_start.size() == (size_t)n_out_batches + 1 &&
-        s.in_start.size() == (size_t)n_in_batches + 1 && s.in_dep == dep &&
-        (n_out == 0 || std::memcmp(s.out.data(), descs_out, (size_t)n_out * sizeof(ss_desc_t)) == 0) &&
-        (n_in == 0 || std::memcmp(s.in.data(), descs_in, (size_t)n_in * sizeof(ss_desc_t)) == 0) &&
-        (n_out_batches == 0 || std::memcmp(s.out_start.data(), out_start, ((size_t)n_out_batches + 1) * 4) == 0) &&
-        (n_in_batches == 0 || std::memcmp(s.in_start.data(), in_start, ((size_t)n_in_batches + 1) * 4) == 0);
-    if (same) {
-      std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
-      std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
-      std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
-      std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
-      s.last_engine_out = -1;
-      return SS_OK;
-    }
-  }
   s.loaded = false;
   s.out.assign(descs_out, descs_out + n_out);
   s.in.assign(descs_in, descs_in + n_in);

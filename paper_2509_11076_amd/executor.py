@@ -13,10 +13,24 @@ from . import binding as B
 
 def batch_lists(actions):
     """Per operator index the (kind, tensor_id, batch) triples, split into what runs before
-    and after the operator itself.  actions is the ACTION_DT array from ss_apply_policy."""
+    and after the operator itself.  actions is the ACTION_DT array from ss_apply_policy, sorted by
+    (operator, kind) with IN < WAIT_IN < OUT < FREE, so every (operator, before/after) group is one
+    contiguous run of it."""
     before, after = {}, {}
-    for op, kind, tid, batch in actions.tolist():
-        (before if kind in (B.SS_ACT_IN, B.SS_ACT_WAIT_IN) else after).setdefault(op, []).append((kind, tid, batch))
+    n = len(actions)
+    if n == 0:
+        return before, after
+    ops = actions["op_idx"].astype(np.int64)
+    late = actions["kind"] >= B.SS_ACT_OUT                  # OUT and FREE come after the operator
+    group = 2 * ops + late
+    cuts = np.flatnonzero(np.diff(group)) + 1
+    starts = np.concatenate(([0], cuts)).tolist()
+    ends = np.concatenate((cuts, [n])).tolist()
+    triples = list(zip(actions["kind"].tolist(), actions["tensor_id"].tolist(), actions["batch"].tolist()))
+    gl = group.tolist()
+    for s, e in zip(starts, ends):
+        g = gl[s]
+        (after if g & 1 else before).setdefault(g >> 1, []).extend(triples[s:e])
     return before, after
 
 
