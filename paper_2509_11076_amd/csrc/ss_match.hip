@@ -161,22 +161,53 @@ __global__ __launch_bounds__(256) void ss_anchor_kernel(const ss_op_t *__restric
 }
 
 // Among anchors landing on the same (operator, slot) only the lowest anchor index keeps it.
-__global__ __launch_bounds__(256) void ss_injective_kernel(const ss_anchor_t *__restrict__ anchors, uint32_t k,
-                                                           const int32_t *__restrict__ land,
-                                                           const uint8_t *__restrict__ lvl, int32_t *new_idx,
-                                                           uint8_t *level, uint32_t *n_unmatched) {
+// Two passes over an open-addressing table of at least 2k slots keyed by (operator, slot): every
+// landed anchor finds or claims its key's slot (compare-and-swap, linear probing) and lowers the
+// slot's owner to its own index (integer minimum: any order, same result); then an anchor keeps its
+// landing exactly if it owns its slot.  Linear in k (20,000 anchors: all earlier anchors compared one
+// by one took 2 ms).
+constexpr unsigned long long kEmptyKey = ~0ull;
+
+__global__ __launch_bounds__(256) void ss_claim_kernel(const ss_anchor_t *__restrict__ anchors, uint32_t k,
+                                                       const int32_t *__restrict__ land,
+                                                       unsigned long long *keys, uint32_t *owner,
+                                                       uint32_t *__restrict__ slot_of, uint32_t mask,
+                                                       uint32_t shift) {
   const uint32_t a = blockIdx.x * blockDim.x + threadIdx.x;
   if (a >= k) return;
-  int32_t j = land[a];
-  uint8_t L = lvl[a];
-  if (j >= 0) {
-    const uint32_t s = anchors[a].out_slot;
-    for (uint32_t a2 = 0; a2 < a; ++a2)
-      if (land[a2] == j && anchors[a2].out_slot == s) { j = -1; L = 255; break; }
+  const int32_t j = land[a];
+  if (j < 0) return;
+  const unsigned long long key = ((unsigned long long)(uint32_t)j << 32) | anchors[a].out_slot;   // j < 2^31: never kEmptyKey
+  uint32_t h = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> shift);
+  // at most k distinct keys in more than 2k slots: a free or matching slot is met within mask + 1 probes
+  for (uint32_t probe = 0; probe <= mask; ++probe) {
+    const unsigned long long seen = atomicCAS(keys + h, kEmptyKey, key);
+    if (seen == kEmptyKey || seen == key) {
+      atomicMin(owner + h, a);
+      slot_of[a] = h;
+      return;
+    }
+    h = (h + 1) & mask;
   }
-  new_idx[a] = j;
-  level[a] = L;
-  if (j < 0) atomicAdd(n_unmatched, 1u);
+}
+
+__global__ __launch_bounds__(256) void ss_injective_kernel(uint32_t k, const int32_t *__restrict__ land,
+                                                           const uint8_t *__restrict__ lvl,
+                                                           const uint32_t *__restrict__ slot_of,
+                                                           const uint32_t *__restrict__ owner, int32_t *new_idx,
+                                                           uint8_t *level, uint32_t *n_unmatched) {
+  const uint32_t a = blockIdx.x * blockDim.x + threadIdx.x;
+  bool lost = false;
+  if (a < k) {
+    int32_t j = land[a];
+    uint8_t L = lvl[a];
+    if (j >= 0 && owner[slot_of[a]] != a) { j = -1; L = 255; }
+    new_idx[a] = j;
+    level[a] = L;
+    lost = j < 0;
+  }
+  const uint64_t m = __ballot(lost);
+  if ((threadIdx.x & 63) == 0 && m) atomicAdd(n_unmatched, (uint32_t)__popcll(m));
 }
 
 }  // namespace
@@ -213,6 +244,11 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
   const size_t o_lvl = take(k), o_level = take(k);
   const size_t o_small = take(64);                       // 3 x u64 sums, flags, n_unmatched
   const size_t o_hist = take(hist ? 2 * (size_t)kTokenLimit * 4 : 0);
+  // table of the injectivity pass: a power of two of at least 2k slots; keys, then owners, back to back
+  uint32_t bits = 6;
+  while ((1ull << bits) < 2ull * k) ++bits;
+  const size_t slots = (size_t)1 << bits;
+  const size_t o_keys = take(k ? slots * 8 : 0), o_owner = take(k ? slots * 4 : 0), o_slot = take((size_t)k * 4);
   int rc = ss_scratch_reserve(ctx, off, 512);
   if (rc != SS_OK) return rc;
   uint8_t *d = (uint8_t *)ctx->d_scratch;
@@ -245,8 +281,12 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
     const uint32_t grid = (k + 3) / 4;                    // 4 wavefronts (anchors) per workgroup
     hipLaunchKernelGGL(ss_anchor_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m,
                        (const ss_anchor_t *)(d + o_anc), k, (int32_t *)(d + o_land), d + o_lvl);
-    hipLaunchKernelGGL(ss_injective_kernel, dim3((k + 255) / 256), dim3(256), 0, s,
-                       (const ss_anchor_t *)(d + o_anc), k, (const int32_t *)(d + o_land), d + o_lvl,
+    ss_launch_fill(s, d + o_keys, slots * 12, 0xFF);      // every key empty, every owner "nobody" (slots * 8 is a multiple of 256)
+    hipLaunchKernelGGL(ss_claim_kernel, dim3((k + 255) / 256), dim3(256), 0, s, (const ss_anchor_t *)(d + o_anc), k,
+                       (const int32_t *)(d + o_land), (unsigned long long *)(d + o_keys), (uint32_t *)(d + o_owner),
+                       (uint32_t *)(d + o_slot), (uint32_t)(slots - 1), 64u - bits);
+    hipLaunchKernelGGL(ss_injective_kernel, dim3((k + 255) / 256), dim3(256), 0, s, k, (const int32_t *)(d + o_land),
+                       d + o_lvl, (const uint32_t *)(d + o_slot), (const uint32_t *)(d + o_owner),
                        (int32_t *)(d + o_idx), d + o_level, d_unm);
     SS_HIP(hipGetLastError());
   }

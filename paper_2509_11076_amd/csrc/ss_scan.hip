@@ -96,18 +96,60 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a) {
   __threadfence();
   __syncthreads();
 
-  // phase 1: gather class sums and counts per operator (integer atomics: any order, same result)
+  // phase 1: gather class sums and counts per operator (integer atomics: any order, same result).
+  // Neighbouring events mostly belong to the same operator, and 64 lanes adding to one address are
+  // served one after the other: so each wavefront first folds every run of equal operators among its
+  // 64 consecutive events (two wavefront prefix sums, two ballots) and only the first lane of a run
+  // adds the run's totals.
   uint32_t bad = 0;
+  const int lane = tid & 63;
+  const uint64_t below = lane ? (~0ull >> (64 - lane)) : 0ull;           // bits of the lanes before this one
   for (int list = 0; list < 2; ++list) {
     const ss_event_t *L = list ? a.pev : a.ev;
     const uint64_t cnt = list ? a.n_pe : a.n_ev;
-    for (uint64_t e = tid; e < cnt; e += kThreads) {
-      const ss_event_t x = L[e];
-      if (x.op_idx >= n) { bad |= 1u; continue; }
-      if (e > 0 && L[e - 1].op_idx > x.op_idx) bad |= 2u;
-      const int c = event_class(list != 0, x.delta);
-      add_i64(a.csum + (uint64_t)c * n + x.op_idx, x.delta);
-      atomicAdd(a.ccnt + (uint64_t)c * n + x.op_idx, 1u);
+    const int cpos = list ? 0 : 1, cneg = list ? 3 : 2;
+    for (uint64_t e0 = 0; e0 < cnt; e0 += kThreads) {                    // uniform trip count: shuffles inside
+      const uint64_t e = e0 + tid;
+      const bool in = e < cnt;
+      ss_event_t x = {0xFFFFFFFFu, 0, 0};
+      if (in) x = L[e];
+      const bool live = in && x.op_idx < n;
+      if (in && !live) bad |= 1u;
+      uint32_t prev = (uint32_t)__shfl_up((int)x.op_idx, 1, 64);
+      if (lane == 0) prev = (in && e > 0) ? L[e - 1].op_idx : 0u;
+      if (in && e > 0 && prev > x.op_idx) bad |= 2u;
+      const bool head = lane == 0 || prev != x.op_idx;
+      const bool is_pos = x.delta >= 0;
+      const uint64_t H = __ballot(head);
+      const uint64_t P = __ballot(live && is_pos), N = __ballot(live && !is_pos);
+      // inclusive wavefront prefix sums of the positive and of the negative deltas
+      int64_t ip = live && is_pos ? x.delta : 0, ineg = live && !is_pos ? x.delta : 0;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int64_t op_ = shfl_up_i64(ip, d), on_ = shfl_up_i64(ineg, d);
+        if (lane >= d) { ip += op_; ineg += on_; }
+      }
+      const uint64_t later_heads = H & ~below & ~(1ull << lane);
+      const int end = later_heads ? __ffsll((unsigned long long)later_heads) - 1 : 64;   // one past the run's last lane
+      int64_t bp = shfl_up_i64(ip, 1), bn = shfl_up_i64(ineg, 1);        // totals before this lane
+      if (lane == 0) { bp = 0; bn = 0; }
+      const int last = end - 1;
+      const int64_t ep = (int64_t)(((uint64_t)(uint32_t)__shfl((int)(uint32_t)((uint64_t)ip >> 32), last, 64) << 32) |
+                                   (uint32_t)__shfl((int)(uint32_t)(uint64_t)ip, last, 64));
+      const int64_t en = (int64_t)(((uint64_t)(uint32_t)__shfl((int)(uint32_t)((uint64_t)ineg >> 32), last, 64) << 32) |
+                                   (uint32_t)__shfl((int)(uint32_t)(uint64_t)ineg, last, 64));
+      if (head && live) {
+        const uint64_t run = (end == 64 ? ~0ull : ((1ull << end) - 1)) & ~below;
+        const uint32_t np = (uint32_t)__popcll(P & run), nn = (uint32_t)__popcll(N & run);
+        if (np) {
+          add_i64(a.csum + (uint64_t)cpos * n + x.op_idx, ep - bp);
+          atomicAdd(a.ccnt + (uint64_t)cpos * n + x.op_idx, np);
+        }
+        if (nn) {
+          add_i64(a.csum + (uint64_t)cneg * n + x.op_idx, en - bn);
+          atomicAdd(a.ccnt + (uint64_t)cneg * n + x.op_idx, nn);
+        }
+      }
     }
   }
   if (bad) atomicOr(&s_flags, bad);

@@ -332,6 +332,60 @@ def test_match_relaxation_and_injectivity_cases(P, ctx):
     assert r["new_idx"].tolist() == o_idx.tolist() == [n - 1 + 70, 70, 134, 133]
 
 
+def test_match_many_anchors_on_few_landings(P, ctx):
+    """thousands of anchors drawn (with repetition) from a few hundred (operator, slot) pairs, some
+    of them beyond the operator's outputs or beyond the sequence: for every landing the lowest
+    anchor index keeps it, all later ones lose it"""
+    rng = SplitMix64(21, 4)
+    n = 700
+    ops = np.zeros(n, dtype=W.OP_DT)
+    ops["op_token"] = [1 + rng.randint(40) for _ in range(n)]
+    ops["stack_hash"] = [rng.randint(3) for _ in range(n)]
+    ops["sig"] = 0x0101
+    ops["n_out"] = [1 + rng.randint(3) for _ in range(n)]
+    cur = np.concatenate([ops[:200], ops[230:]])                      # thirty operators missing
+    k = 6000
+    anc = np.zeros(k, dtype=W.ANCHOR_DT)
+    anc["ref_op"] = [rng.randint(n + 5) if rng.randint(8) == 0 else rng.randint(60) * 11 for _ in range(k)]
+    anc["out_slot"] = [rng.randint(4) for _ in range(k)]
+    o_idx, o_lvl = oracle.match_anchors(ops_tuples(ops), ops_tuples(cur), anc.tolist())
+    r = P.ss_match_sequence(ctx, ops, cur, anc)
+    assert np.array_equal(r["new_idx"], o_idx) and np.array_equal(r["level"], o_lvl)
+    assert r["n_unmatched"] == int((o_idx < 0).sum()) > k // 2
+    kept = r["new_idx"] >= 0
+    assert 100 < kept.sum() < 1000
+    pairs = set(zip(r["new_idx"][kept].tolist(), anc["out_slot"][kept].tolist()))
+    assert len(pairs) == kept.sum()                                   # injective
+
+
+def test_scan_long_runs_of_one_operator_sorted_and_not(P, ctx):
+    """runs of one operator's events far longer than a wavefront and a workgroup pass, runs of length
+    one, operators without events; once in operator order, once with whole runs moved out of order"""
+    rng = SplitMix64(33, 2)
+    n_ops = 300
+    runs = []
+    for t in range(n_ops):
+        length = [0, 1, 2, 63, 64, 65, 130, 1500, 2300][rng.randint(9)]
+        ev = np.zeros(length, dtype=W.EVENT_DT)
+        ev["op_idx"] = t
+        ev["tensor_id"] = np.arange(length)
+        ev["delta"] = [(1 + rng.randint(1 << 20)) * (1 if rng.randint(3) else -1) for _ in range(length)]
+        runs.append(ev)
+    ev = np.concatenate(runs)
+    assert len(ev) > 100000
+    pe = np.zeros(4000, dtype=W.EVENT_DT)
+    pe["op_idx"] = np.sort(np.array([rng.randint(n_ops) for _ in range(4000)]))
+    pe["delta"] = [(1 + rng.randint(1 << 22)) * (1 if rng.randint(2) else -1) for _ in range(4000)]
+    ora = oracle.timeline_scan(ev, pe, n_ops, 11, 1 << 28)
+    lib = P.ss_timeline_scan(ctx, ev, pe, n_ops, 11, 1 << 28, want_timeline=True)
+    assert_scan_equal(lib, ora)
+    order = SplitMix64(5).permutation(n_ops)
+    moved = np.concatenate([runs[i] for i in order])
+    lib = P.ss_timeline_scan(ctx, moved, pe, n_ops, 11, 1 << 28)
+    assert_scan_equal(lib, ora, timeline=False)
+    assert lib["sorted"] == 0
+
+
 # ------------------------------------------------------------------ apply policy / greedy
 @pytest.mark.parametrize("cfgno,bpo,guard", [(1, 64 * 1024, 256), (1, INSTANT, 0), (1, 16, 0),
                                              (2, 8 << 20, 0), (2, 64 << 20, 512)])
