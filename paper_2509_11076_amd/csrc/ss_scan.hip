@@ -108,46 +108,63 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a) {
     const ss_event_t *L = list ? a.pev : a.ev;
     const uint64_t cnt = list ? a.n_pe : a.n_ev;
     const int cpos = list ? 0 : 1, cneg = list ? 3 : 2;
-    for (uint64_t e0 = 0; e0 < cnt; e0 += kThreads) {                    // uniform trip count: shuffles inside
-      const uint64_t e = e0 + tid;
-      const bool in = e < cnt;
-      ss_event_t x = {0xFFFFFFFFu, 0, 0};
-      if (in) x = L[e];
-      const bool live = in && x.op_idx < n;
-      if (in && !live) bad |= 1u;
-      uint32_t prev = (uint32_t)__shfl_up((int)x.op_idx, 1, 64);
-      if (lane == 0) prev = (in && e > 0) ? L[e - 1].op_idx : 0u;
-      if (in && e > 0 && prev > x.op_idx) bad |= 2u;
-      const bool head = lane == 0 || prev != x.op_idx;
-      const bool is_pos = x.delta >= 0;
-      const uint64_t H = __ballot(head);
-      const uint64_t P = __ballot(live && is_pos), N = __ballot(live && !is_pos);
-      // inclusive wavefront prefix sums of the positive and of the negative deltas
-      int64_t ip = live && is_pos ? x.delta : 0, ineg = live && !is_pos ? x.delta : 0;
+    constexpr int kAhead = 4;            // events in flight per lane: the loop is bound by load latency
+    for (uint64_t g0 = 0; g0 < cnt; g0 += (uint64_t)kAhead * kThreads) {
+      ss_event_t xs[kAhead];
+      uint32_t before0[kAhead];          // lane 0 only: operator of the event before the wavefront's first
 #pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const int64_t op_ = shfl_up_i64(ip, d), on_ = shfl_up_i64(ineg, d);
-        if (lane >= d) { ip += op_; ineg += on_; }
-      }
-      const uint64_t later_heads = H & ~below & ~(1ull << lane);
-      const int end = later_heads ? __ffsll((unsigned long long)later_heads) - 1 : 64;   // one past the run's last lane
-      int64_t bp = shfl_up_i64(ip, 1), bn = shfl_up_i64(ineg, 1);        // totals before this lane
-      if (lane == 0) { bp = 0; bn = 0; }
-      const int last = end - 1;
-      const int64_t ep = (int64_t)(((uint64_t)(uint32_t)__shfl((int)(uint32_t)((uint64_t)ip >> 32), last, 64) << 32) |
-                                   (uint32_t)__shfl((int)(uint32_t)(uint64_t)ip, last, 64));
-      const int64_t en = (int64_t)(((uint64_t)(uint32_t)__shfl((int)(uint32_t)((uint64_t)ineg >> 32), last, 64) << 32) |
-                                   (uint32_t)__shfl((int)(uint32_t)(uint64_t)ineg, last, 64));
-      if (head && live) {
-        const uint64_t run = (end == 64 ? ~0ull : ((1ull << end) - 1)) & ~below;
-        const uint32_t np = (uint32_t)__popcll(P & run), nn = (uint32_t)__popcll(N & run);
-        if (np) {
-          add_i64(a.csum + (uint64_t)cpos * n + x.op_idx, ep - bp);
-          atomicAdd(a.ccnt + (uint64_t)cpos * n + x.op_idx, np);
+      for (int u = 0; u < kAhead; ++u) {
+        const uint64_t e = g0 + (uint64_t)u * kThreads + tid;
+        xs[u] = ss_event_t{0xFFFFFFFFu, 0, 0};
+        before0[u] = 0;
+        if (e < cnt) {
+          xs[u] = L[e];
+          if (lane == 0 && e > 0) before0[u] = L[e - 1].op_idx;
         }
-        if (nn) {
-          add_i64(a.csum + (uint64_t)cneg * n + x.op_idx, en - bn);
-          atomicAdd(a.ccnt + (uint64_t)cneg * n + x.op_idx, nn);
+      }
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) {
+        const uint64_t e0 = g0 + (uint64_t)u * kThreads;
+        if (e0 >= cnt) break;                                            // uniform: shuffles inside
+        const uint64_t e = e0 + tid;
+        const bool in = e < cnt;
+        const ss_event_t x = xs[u];
+        const bool live = in && x.op_idx < n;
+        if (in && !live) bad |= 1u;
+        uint32_t prev = (uint32_t)__shfl_up((int)x.op_idx, 1, 64);
+        if (lane == 0) prev = before0[u];
+        if (in && e > 0 && prev > x.op_idx) bad |= 2u;
+        const bool head = lane == 0 || prev != x.op_idx;
+        const bool is_pos = x.delta >= 0;
+        const uint64_t H = __ballot(head);
+        const uint64_t P = __ballot(live && is_pos), N = __ballot(live && !is_pos);
+        // inclusive wavefront prefix sums of the positive and of the negative deltas
+        int64_t ip = live && is_pos ? x.delta : 0, ineg = live && !is_pos ? x.delta : 0;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const int64_t op_ = shfl_up_i64(ip, d), on_ = shfl_up_i64(ineg, d);
+          if (lane >= d) { ip += op_; ineg += on_; }
+        }
+        const uint64_t later_heads = H & ~below & ~(1ull << lane);
+        const int end = later_heads ? __ffsll((unsigned long long)later_heads) - 1 : 64;   // one past the run's last lane
+        int64_t bp = shfl_up_i64(ip, 1), bn = shfl_up_i64(ineg, 1);      // totals before this lane
+        if (lane == 0) { bp = 0; bn = 0; }
+        const int last = end - 1;
+        const int64_t ep = (int64_t)(((uint64_t)(uint32_t)__shfl((int)(uint32_t)((uint64_t)ip >> 32), last, 64) << 32) |
+                                     (uint32_t)__shfl((int)(uint32_t)(uint64_t)ip, last, 64));
+        const int64_t en = (int64_t)(((uint64_t)(uint32_t)__shfl((int)(uint32_t)((uint64_t)ineg >> 32), last, 64) << 32) |
+                                     (uint32_t)__shfl((int)(uint32_t)(uint64_t)ineg, last, 64));
+        if (head && live) {
+          const uint64_t run = (end == 64 ? ~0ull : ((1ull << end) - 1)) & ~below;
+          const uint32_t np = (uint32_t)__popcll(P & run), nn = (uint32_t)__popcll(N & run);
+          if (np) {
+            add_i64(a.csum + (uint64_t)cpos * n + x.op_idx, ep - bp);
+            atomicAdd(a.ccnt + (uint64_t)cpos * n + x.op_idx, np);
+          }
+          if (nn) {
+            add_i64(a.csum + (uint64_t)cneg * n + x.op_idx, en - bn);
+            atomicAdd(a.ccnt + (uint64_t)cneg * n + x.op_idx, nn);
+          }
         }
       }
     }
