@@ -14,7 +14,8 @@
  * Conventions
  *  - Plain C, no exceptions cross the boundary.  Every function returns SS_OK
  *    (0) or a negative SS_E_* code; ss_strerror() names it; the last HIP error
- *    code is kept in the statistics.
+ *    code is kept in the statistics.  A failed host allocation inside the
+ *    library comes back as SS_E_NOMEM.
  *  - "host" pointers are ordinary process memory owned by the caller and only
  *    read or written during the call.  "device" pointers are HBM addresses.
  *    The library never allocates or frees the caller's device arena.

@@ -35,7 +35,9 @@ typedef struct {
   uint64_t errors;
 } ss_hook_stats_t;
 
-/* Register the callbacks (once per process) and direct them to ctx.  SS_E_INVAL on a bad mode. */
+/* Register the callbacks (once per process) and direct them to ctx.  SS_E_INVAL on a bad mode;
+ * SS_E_STATE (here, in ss_hook_set_mode and in ss_hook_remove) if PyTorch raised an error while
+ * the callbacks were registered or removed: no exception leaves these functions. */
 int ss_hook_install(ss_ctx *ctx, int mode);
 /* Switch mode without touching the registration (Algo. 1: Detailed only while a policy is needed). */
 int ss_hook_set_mode(int mode);

@@ -204,20 +204,22 @@ void ss_align_anchors(const ss_op_t *ref, uint32_t n, const ss_op_t *cur, const 
 extern "C" int ss_align_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n_ref, const ss_op_t *cur,
                                  uint32_t n_cur, const ss_anchor_t *anchors, uint32_t n_anchors,
                                  int32_t *ref_to_cur, int32_t *new_idx, uint8_t *level, ss_align_result_t *res) {
-  if (!ctx || !res || (n_ref && !ref) || (n_cur && !cur)) return SS_E_INVAL;
-  if (n_anchors && (!anchors || !new_idx || !level)) return SS_E_INVAL;
-  std::vector<int32_t> local;
-  if (!ref_to_cur) {
-    local.resize(n_ref);
-    ref_to_cur = local.data();
-  }
-  std::memset(res, 0, sizeof(*res));
-  uint32_t lcs = 0, n_keys = 0;
-  int rc = ss_align_core(ctx, ref, n_ref, cur, n_cur, ref_to_cur, &lcs, &n_keys);
-  if (rc != SS_OK) return rc;
-  res->lcs = lcs;
-  res->distance = n_ref + n_cur - 2 * lcs;
-  res->n_keys = n_keys;
-  ss_align_anchors(ref, n_ref, cur, ref_to_cur, anchors, n_anchors, new_idx, level, &res->n_unmatched);
-  return SS_OK;
+  return ss_guard([&]() -> int {
+    if (!ctx || !res || (n_ref && !ref) || (n_cur && !cur)) return SS_E_INVAL;
+    if (n_anchors && (!anchors || !new_idx || !level)) return SS_E_INVAL;
+    std::vector<int32_t> local;
+    if (!ref_to_cur) {
+      local.resize(n_ref);
+      ref_to_cur = local.data();
+    }
+    std::memset(res, 0, sizeof(*res));
+    uint32_t lcs = 0, n_keys = 0;
+    int rc = ss_align_core(ctx, ref, n_ref, cur, n_cur, ref_to_cur, &lcs, &n_keys);
+    if (rc != SS_OK) return rc;
+    res->lcs = lcs;
+    res->distance = n_ref + n_cur - 2 * lcs;
+    res->n_keys = n_keys;
+    ss_align_anchors(ref, n_ref, cur, ref_to_cur, anchors, n_anchors, new_idx, level, &res->n_unmatched);
+    return SS_OK;
+  });
 }

@@ -209,9 +209,11 @@ extern "C" int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_op
                                   uint32_t n_tensors, const ss_event_t *ev, uint64_t n_ev, int64_t base,
                                   int64_t limit, const ss_gen_params_t *params, ss_policy_item_t *policy_out,
                                   uint32_t *n_policy, ss_gen_result_t *res) {
-  uint32_t chosen = 0;
-  return ss_generate_policy_best(ctx, ops, n_ops, tensors, n_tensors, ev, n_ev, base, limit, params, 1, policy_out,
-                                 n_policy, &chosen, res);
+  return ss_guard([&]() -> int {
+    uint32_t chosen = 0;
+    return ss_generate_policy_best(ctx, ops, n_ops, tensors, n_tensors, ev, n_ev, base, limit, params, 1, policy_out,
+                                   n_policy, &chosen, res);
+  });
 }
 
 extern "C" int ss_generate_policy_best(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
@@ -219,69 +221,71 @@ extern "C" int ss_generate_policy_best(ss_ctx *ctx, const ss_op_t *ops, uint32_t
                                        int64_t limit, const ss_gen_params_t *params, uint32_t n_params,
                                        ss_policy_item_t *policy_out, uint32_t *n_policy, uint32_t *chosen,
                                        ss_gen_result_t *res) {
-  if (!ctx || !params || !n_params || !n_policy || !chosen || !res || (n_ops && !ops) || (n_tensors && !tensors))
-    return SS_E_INVAL;
-  if (*n_policy && !policy_out) return SS_E_INVAL;
-  const uint64_t bpo = ctx->cfg.link_bytes_per_op;
-  if ((u128)bpo * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
-  for (uint32_t c = 0; c < n_params; ++c) {
-    if (params[c].c_den == 0 || params[c].g_fwd == 0 || params[c].g_bwd == 0) return SS_E_INVAL;
-    for (int ph = 0; ph < 3; ++ph)
-      if ((u128)params[c].phase_bytes_per_op[ph] * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
-  }
-  std::memset(res, 0, sizeof(*res));
-
-  // memory without swaps -> memory reduction list (Sec. 4.2)
-  std::vector<int64_t> per_op(n_ops);
-  ss_scan_result_t sr;
-  int rc = ss_timeline_scan(ctx, ev, n_ev, nullptr, 0, n_ops, base, limit, nullptr, per_op.data(), nullptr, &sr);
-  if (rc != SS_OK) return rc;
-  const int64_t peak_no_swap = sr.peak;
-
-  struct Cand { std::vector<ss_policy_item_t> items; std::vector<ss_event_t> pe; ss_gen_result_t r; int rc; };
-  std::vector<Cand> cands(n_params);
-  std::vector<ss_event_t> all_pe;
-  std::vector<uint64_t> pe_start(n_params + 1, 0);
-  bool any = false;
-  for (uint32_t c = 0; c < n_params; ++c) {
-    std::memset(&cands[c].r, 0, sizeof(ss_gen_result_t));
-    cands[c].rc = generate_core(bpo, ops, n_ops, tensors, n_tensors, per_op, limit, &params[c], cands[c].items,
-                                cands[c].pe, &cands[c].r);
-    if (cands[c].rc != SS_OK && cands[c].rc != SS_E_INFEASIBLE) return cands[c].rc;
-    if (cands[c].rc != SS_OK) cands[c].pe.clear();
-    any = any || cands[c].rc == SS_OK;
-    all_pe.insert(all_pe.end(), cands[c].pe.begin(), cands[c].pe.end());
-    pe_start[c + 1] = all_pe.size();
-  }
-  if (!any) return SS_E_INFEASIBLE;
-  // what the release points really give: every candidate scanned with its own events, one launch
-  std::vector<ss_scan_result_t> scans(n_params);
-  rc = ss_timeline_scan_batch(ctx, ev, n_ev, all_pe.data(), pe_start.data(), n_params, n_ops, base, limit, nullptr,
-                              scans.data());
-  if (rc != SS_OK) return rc;
-  int best = -1;
-  for (uint32_t c = 0; c < n_params; ++c) {
-    if (cands[c].rc != SS_OK) continue;
-    cands[c].r.peak_no_swap = peak_no_swap;
-    cands[c].r.peak_with_policy = scans[c].peak;
-    cands[c].r.n_over_with_policy = scans[c].n_over;
-    if (best < 0) { best = (int)c; continue; }
-    const ss_gen_result_t &x = cands[c].r, &y = cands[best].r;
-    // within the limit first, then fewer items that cost latency, then fewer bytes over the link
-    const bool xf = x.n_over_with_policy == 0, yf = y.n_over_with_policy == 0;
-    if (xf != yf) { if (xf) best = (int)c; continue; }
-    if (!xf && x.n_over_with_policy != y.n_over_with_policy) {
-      if (x.n_over_with_policy < y.n_over_with_policy) best = (int)c;
-      continue;
+  return ss_guard([&]() -> int {
+    if (!ctx || !params || !n_params || !n_policy || !chosen || !res || (n_ops && !ops) || (n_tensors && !tensors))
+      return SS_E_INVAL;
+    if (*n_policy && !policy_out) return SS_E_INVAL;
+    const uint64_t bpo = ctx->cfg.link_bytes_per_op;
+    if ((u128)bpo * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
+    for (uint32_t c = 0; c < n_params; ++c) {
+      if (params[c].c_den == 0 || params[c].g_fwd == 0 || params[c].g_bwd == 0) return SS_E_INVAL;
+      for (int ph = 0; ph < 3; ++ph)
+        if ((u128)params[c].phase_bytes_per_op[ph] * (n_ops + 1ull) >= ((u128)1 << 62)) return SS_E_INVAL;
     }
-    if (x.n_late != y.n_late) { if (x.n_late < y.n_late) best = (int)c; continue; }
-    if (x.bytes < y.bytes) best = (int)c;
-  }
-  const Cand &w = cands[(size_t)best];
-  if (w.items.size() > *n_policy) return SS_E_CAPACITY;
-  if (!w.items.empty()) std::memcpy(policy_out, w.items.data(), w.items.size() * sizeof(ss_policy_item_t));
-  *n_policy = (uint32_t)w.items.size();
-  *chosen = (uint32_t)best;
-  *res = w.r;
-  return SS_OK;
+    std::memset(res, 0, sizeof(*res));
+
+    // memory without swaps -> memory reduction list (Sec. 4.2)
+    std::vector<int64_t> per_op(n_ops);
+    ss_scan_result_t sr;
+    int rc = ss_timeline_scan(ctx, ev, n_ev, nullptr, 0, n_ops, base, limit, nullptr, per_op.data(), nullptr, &sr);
+    if (rc != SS_OK) return rc;
+    const int64_t peak_no_swap = sr.peak;
+
+    struct Cand { std::vector<ss_policy_item_t> items; std::vector<ss_event_t> pe; ss_gen_result_t r; int rc; };
+    std::vector<Cand> cands(n_params);
+    std::vector<ss_event_t> all_pe;
+    std::vector<uint64_t> pe_start(n_params + 1, 0);
+    bool any = false;
+    for (uint32_t c = 0; c < n_params; ++c) {
+      std::memset(&cands[c].r, 0, sizeof(ss_gen_result_t));
+      cands[c].rc = generate_core(bpo, ops, n_ops, tensors, n_tensors, per_op, limit, &params[c], cands[c].items,
+                                  cands[c].pe, &cands[c].r);
+      if (cands[c].rc != SS_OK && cands[c].rc != SS_E_INFEASIBLE) return cands[c].rc;
+      if (cands[c].rc != SS_OK) cands[c].pe.clear();
+      any = any || cands[c].rc == SS_OK;
+      all_pe.insert(all_pe.end(), cands[c].pe.begin(), cands[c].pe.end());
+      pe_start[c + 1] = all_pe.size();
+    }
+    if (!any) return SS_E_INFEASIBLE;
+    // what the release points really give: every candidate scanned with its own events, one launch
+    std::vector<ss_scan_result_t> scans(n_params);
+    rc = ss_timeline_scan_batch(ctx, ev, n_ev, all_pe.data(), pe_start.data(), n_params, n_ops, base, limit, nullptr,
+                                scans.data());
+    if (rc != SS_OK) return rc;
+    int best = -1;
+    for (uint32_t c = 0; c < n_params; ++c) {
+      if (cands[c].rc != SS_OK) continue;
+      cands[c].r.peak_no_swap = peak_no_swap;
+      cands[c].r.peak_with_policy = scans[c].peak;
+      cands[c].r.n_over_with_policy = scans[c].n_over;
+      if (best < 0) { best = (int)c; continue; }
+      const ss_gen_result_t &x = cands[c].r, &y = cands[best].r;
+      // within the limit first, then fewer items that cost latency, then fewer bytes over the link
+      const bool xf = x.n_over_with_policy == 0, yf = y.n_over_with_policy == 0;
+      if (xf != yf) { if (xf) best = (int)c; continue; }
+      if (!xf && x.n_over_with_policy != y.n_over_with_policy) {
+        if (x.n_over_with_policy < y.n_over_with_policy) best = (int)c;
+        continue;
+      }
+      if (x.n_late != y.n_late) { if (x.n_late < y.n_late) best = (int)c; continue; }
+      if (x.bytes < y.bytes) best = (int)c;
+    }
+    const Cand &w = cands[(size_t)best];
+    if (w.items.size() > *n_policy) return SS_E_CAPACITY;
+    if (!w.items.empty()) std::memcpy(policy_out, w.items.data(), w.items.size() * sizeof(ss_policy_item_t));
+    *n_policy = (uint32_t)w.items.size();
+    *chosen = (uint32_t)best;
+    *res = w.r;
+    return SS_OK;
+  });
 }

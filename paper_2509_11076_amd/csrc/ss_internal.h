@@ -2,11 +2,28 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <new>
+#include <stdexcept>
 #include <string>
 #include <unordered_map>
 #include <vector>
 
 #include "ss.h"
+
+// No C++ exception crosses the C boundary: an entry point that allocates host memory through the
+// standard library runs its body inside this, and a failed allocation comes back as SS_E_NOMEM.
+template <class Body>
+inline int ss_guard(Body &&body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    return SS_E_NOMEM;
+  } catch (const std::length_error &) {
+    return SS_E_NOMEM;
+  } catch (...) {
+    return SS_E_INVAL;
+  }
+}
 
 struct ss_sched {
   std::vector<ss_desc_t> out, in;                 // host copies, issue order

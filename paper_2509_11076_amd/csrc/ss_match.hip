@@ -232,100 +232,102 @@ static void stage_step(ss_ctx *ctx, bool similar) {
 extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, const ss_op_t *cur, uint32_t m,
                                  const ss_anchor_t *anchors, uint32_t k, uint32_t flags, int32_t *new_idx,
                                  uint8_t *level, ss_match_result_t *res) {
-  if (!ctx || !res || (n && !ref) || (m && !cur)) return SS_E_INVAL;
-  if (k && (!anchors || !new_idx || !level)) return SS_E_INVAL;
-  if (n > kLenLimit || m > kLenLimit || k > (1u << 24)) return SS_E_INVAL;
-  const bool hist = (flags & SS_MATCH_HISTOGRAM) != 0;
-  size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += ss_align_up(bytes, 256); return o; };
-  const size_t o_ref = take((size_t)n * sizeof(ss_op_t)), o_cur = take((size_t)m * sizeof(ss_op_t));
-  const size_t o_anc = take((size_t)k * sizeof(ss_anchor_t));
-  const size_t o_land = take((size_t)k * 4), o_idx = take((size_t)k * 4);
-  const size_t o_lvl = take(k), o_level = take(k);
-  const size_t o_small = take(64);                       // 3 x u64 sums, flags, n_unmatched
-  const size_t o_hist = take(hist ? 2 * (size_t)kTokenLimit * 4 : 0);
-  // table of the injectivity pass: a power of two of at least 2k slots; keys, then owners, back to back
-  uint32_t bits = 6;
-  while ((1ull << bits) < 2ull * k) ++bits;
-  const size_t slots = (size_t)1 << bits;
-  const size_t o_keys = take(k ? slots * 8 : 0), o_owner = take(k ? slots * 4 : 0), o_slot = take((size_t)k * 4);
-  int rc = ss_scratch_reserve(ctx, off, 512);
-  if (rc != SS_OK) return rc;
-  uint8_t *d = (uint8_t *)ctx->d_scratch;
-  hipStream_t s = ctx->s_aux;
-  if (n) SS_HIP(hipMemcpyAsync(d + o_ref, ref, (size_t)n * sizeof(ss_op_t), hipMemcpyHostToDevice, s));
-  if (m) SS_HIP(hipMemcpyAsync(d + o_cur, cur, (size_t)m * sizeof(ss_op_t), hipMemcpyHostToDevice, s));
-  if (k) SS_HIP(hipMemcpyAsync(d + o_anc, anchors, (size_t)k * sizeof(ss_anchor_t), hipMemcpyHostToDevice, s));
-  // zero the small counters (and histograms) with a fill kernel: safe under graph capture too
-  ss_launch_fill(s, d + o_small, 64, 0);
-  if (hist) ss_launch_fill(s, d + o_hist, 2 * (size_t)kTokenLimit * 4, 0);
-  SS_HIP(hipGetLastError());
-  unsigned long long *sums = (unsigned long long *)(d + o_small);
-  uint32_t *dflags = (uint32_t *)(d + o_small + 32), *d_unm = (uint32_t *)(d + o_small + 40);
-  const ss_op_t *dref = (const ss_op_t *)(d + o_ref), *dcur = (const ss_op_t *)(d + o_cur);
-  const uint32_t len = n > m ? n : m;
-  if (len) {
-    uint32_t grid = (len + 255) / 256;
-    if (grid > 256) grid = 256;
-    if (!hist) {
-      hipLaunchKernelGGL(ss_cosine_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m, sums, dflags);
-    } else {
-      uint32_t *h_ref = (uint32_t *)(d + o_hist), *h_cur = h_ref + kTokenLimit;
-      hipLaunchKernelGGL(ss_histogram_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m, h_ref, h_cur, dflags);
-      hipLaunchKernelGGL(ss_histdot_kernel, dim3(256), dim3(256), 0, s, h_ref, h_cur, kTokenLimit, sums);
-    }
-    SS_HIP(hipGetLastError());
-  }
-  const bool aligned = (flags & SS_MATCH_ALIGN) != 0;
-  if (k && !aligned) {
-    const uint32_t grid = (k + 3) / 4;                    // 4 wavefronts (anchors) per workgroup
-    hipLaunchKernelGGL(ss_anchor_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m,
-                       (const ss_anchor_t *)(d + o_anc), k, (int32_t *)(d + o_land), d + o_lvl);
-    ss_launch_fill(s, d + o_keys, slots * 12, 0xFF);      // every key empty, every owner "nobody" (slots * 8 is a multiple of 256)
-    hipLaunchKernelGGL(ss_claim_kernel, dim3((k + 255) / 256), dim3(256), 0, s, (const ss_anchor_t *)(d + o_anc), k,
-                       (const int32_t *)(d + o_land), (unsigned long long *)(d + o_keys), (uint32_t *)(d + o_owner),
-                       (uint32_t *)(d + o_slot), (uint32_t)(slots - 1), 64u - bits);
-    hipLaunchKernelGGL(ss_injective_kernel, dim3((k + 255) / 256), dim3(256), 0, s, k, (const int32_t *)(d + o_land),
-                       d + o_lvl, (const uint32_t *)(d + o_slot), (const uint32_t *)(d + o_owner),
-                       (int32_t *)(d + o_idx), d + o_level, d_unm);
-    SS_HIP(hipGetLastError());
-  }
-  uint8_t *h = (uint8_t *)ctx->h_scratch;
-  SS_HIP(hipMemcpyAsync(h, d + o_small, 64, hipMemcpyDeviceToHost, s));
-  if (k && !aligned) {
-    SS_HIP(hipMemcpyAsync(new_idx, d + o_idx, (size_t)k * 4, hipMemcpyDeviceToHost, s));
-    SS_HIP(hipMemcpyAsync(level, d + o_level, k, hipMemcpyDeviceToHost, s));
-  }
-  SS_HIP(hipStreamSynchronize(s));
-  uint64_t sm[3];
-  uint32_t fl, unm;
-  std::memcpy(sm, h, 24);
-  std::memcpy(&fl, h + 32, 4);
-  std::memcpy(&unm, h + 40, 4);
-  if (fl & 1u) return SS_E_INVAL;                          // a token beyond 2^18
-  res->dot = sm[0]; res->na = sm[1]; res->nb = sm[2];
-  bool similar;
-  if (n == 0 && m == 0) {
-    similar = true;
-  } else {
-    const uint64_t diff = n > m ? n - m : m - n;
-    const bool len_ok = 20ull * diff < (uint64_t)n;
-    // cos > 0.95  <=>  dot > 0 and 400 dot^2 > 361 na nb; sums < 2^59, so both sides < 2^127
-    const unsigned __int128 lhs = (unsigned __int128)400 * sm[0] * sm[0];
-    const unsigned __int128 rhs = (unsigned __int128)361 * sm[1] * sm[2];
-    similar = len_ok && sm[0] > 0 && lhs > rhs;
-  }
-  res->similar = similar ? 1u : 0u;
-  if (flags & SS_MATCH_STEP_STAGE) stage_step(ctx, similar);
-  res->stage = ctx->stage;
-  res->stable_step = ctx->stable_step;
-  res->n_unmatched = (k && !aligned) ? unm : 0;
-  if (k && aligned) {                                      // the scratch is free again: the stream is idle
-    std::vector<int32_t> ref_to_cur(n);
-    uint32_t lcs = 0;
-    rc = ss_align_core(ctx, ref, n, cur, m, ref_to_cur.data(), &lcs, nullptr);
+  return ss_guard([&]() -> int {
+    if (!ctx || !res || (n && !ref) || (m && !cur)) return SS_E_INVAL;
+    if (k && (!anchors || !new_idx || !level)) return SS_E_INVAL;
+    if (n > kLenLimit || m > kLenLimit || k > (1u << 24)) return SS_E_INVAL;
+    const bool hist = (flags & SS_MATCH_HISTOGRAM) != 0;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += ss_align_up(bytes, 256); return o; };
+    const size_t o_ref = take((size_t)n * sizeof(ss_op_t)), o_cur = take((size_t)m * sizeof(ss_op_t));
+    const size_t o_anc = take((size_t)k * sizeof(ss_anchor_t));
+    const size_t o_land = take((size_t)k * 4), o_idx = take((size_t)k * 4);
+    const size_t o_lvl = take(k), o_level = take(k);
+    const size_t o_small = take(64);                       // 3 x u64 sums, flags, n_unmatched
+    const size_t o_hist = take(hist ? 2 * (size_t)kTokenLimit * 4 : 0);
+    // table of the injectivity pass: a power of two of at least 2k slots; keys, then owners, back to back
+    uint32_t bits = 6;
+    while ((1ull << bits) < 2ull * k) ++bits;
+    const size_t slots = (size_t)1 << bits;
+    const size_t o_keys = take(k ? slots * 8 : 0), o_owner = take(k ? slots * 4 : 0), o_slot = take((size_t)k * 4);
+    int rc = ss_scratch_reserve(ctx, off, 512);
     if (rc != SS_OK) return rc;
-    ss_align_anchors(ref, n, cur, ref_to_cur.data(), anchors, k, new_idx, level, &res->n_unmatched);
-  }
-  return SS_OK;
+    uint8_t *d = (uint8_t *)ctx->d_scratch;
+    hipStream_t s = ctx->s_aux;
+    if (n) SS_HIP(hipMemcpyAsync(d + o_ref, ref, (size_t)n * sizeof(ss_op_t), hipMemcpyHostToDevice, s));
+    if (m) SS_HIP(hipMemcpyAsync(d + o_cur, cur, (size_t)m * sizeof(ss_op_t), hipMemcpyHostToDevice, s));
+    if (k) SS_HIP(hipMemcpyAsync(d + o_anc, anchors, (size_t)k * sizeof(ss_anchor_t), hipMemcpyHostToDevice, s));
+    // zero the small counters (and histograms) with a fill kernel: safe under graph capture too
+    ss_launch_fill(s, d + o_small, 64, 0);
+    if (hist) ss_launch_fill(s, d + o_hist, 2 * (size_t)kTokenLimit * 4, 0);
+    SS_HIP(hipGetLastError());
+    unsigned long long *sums = (unsigned long long *)(d + o_small);
+    uint32_t *dflags = (uint32_t *)(d + o_small + 32), *d_unm = (uint32_t *)(d + o_small + 40);
+    const ss_op_t *dref = (const ss_op_t *)(d + o_ref), *dcur = (const ss_op_t *)(d + o_cur);
+    const uint32_t len = n > m ? n : m;
+    if (len) {
+      uint32_t grid = (len + 255) / 256;
+      if (grid > 256) grid = 256;
+      if (!hist) {
+        hipLaunchKernelGGL(ss_cosine_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m, sums, dflags);
+      } else {
+        uint32_t *h_ref = (uint32_t *)(d + o_hist), *h_cur = h_ref + kTokenLimit;
+        hipLaunchKernelGGL(ss_histogram_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m, h_ref, h_cur, dflags);
+        hipLaunchKernelGGL(ss_histdot_kernel, dim3(256), dim3(256), 0, s, h_ref, h_cur, kTokenLimit, sums);
+      }
+      SS_HIP(hipGetLastError());
+    }
+    const bool aligned = (flags & SS_MATCH_ALIGN) != 0;
+    if (k && !aligned) {
+      const uint32_t grid = (k + 3) / 4;                    // 4 wavefronts (anchors) per workgroup
+      hipLaunchKernelGGL(ss_anchor_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m,
+                         (const ss_anchor_t *)(d + o_anc), k, (int32_t *)(d + o_land), d + o_lvl);
+      ss_launch_fill(s, d + o_keys, slots * 12, 0xFF);      // every key empty, every owner "nobody" (slots * 8 is a multiple of 256)
+      hipLaunchKernelGGL(ss_claim_kernel, dim3((k + 255) / 256), dim3(256), 0, s, (const ss_anchor_t *)(d + o_anc), k,
+                         (const int32_t *)(d + o_land), (unsigned long long *)(d + o_keys), (uint32_t *)(d + o_owner),
+                         (uint32_t *)(d + o_slot), (uint32_t)(slots - 1), 64u - bits);
+      hipLaunchKernelGGL(ss_injective_kernel, dim3((k + 255) / 256), dim3(256), 0, s, k, (const int32_t *)(d + o_land),
+                         d + o_lvl, (const uint32_t *)(d + o_slot), (const uint32_t *)(d + o_owner),
+                         (int32_t *)(d + o_idx), d + o_level, d_unm);
+      SS_HIP(hipGetLastError());
+    }
+    uint8_t *h = (uint8_t *)ctx->h_scratch;
+    SS_HIP(hipMemcpyAsync(h, d + o_small, 64, hipMemcpyDeviceToHost, s));
+    if (k && !aligned) {
+      SS_HIP(hipMemcpyAsync(new_idx, d + o_idx, (size_t)k * 4, hipMemcpyDeviceToHost, s));
+      SS_HIP(hipMemcpyAsync(level, d + o_level, k, hipMemcpyDeviceToHost, s));
+    }
+    SS_HIP(hipStreamSynchronize(s));
+    uint64_t sm[3];
+    uint32_t fl, unm;
+    std::memcpy(sm, h, 24);
+    std::memcpy(&fl, h + 32, 4);
+    std::memcpy(&unm, h + 40, 4);
+    if (fl & 1u) return SS_E_INVAL;                          // a token beyond 2^18
+    res->dot = sm[0]; res->na = sm[1]; res->nb = sm[2];
+    bool similar;
+    if (n == 0 && m == 0) {
+      similar = true;
+    } else {
+      const uint64_t diff = n > m ? n - m : m - n;
+      const bool len_ok = 20ull * diff < (uint64_t)n;
+      // cos > 0.95  <=>  dot > 0 and 400 dot^2 > 361 na nb; sums < 2^59, so both sides < 2^127
+      const unsigned __int128 lhs = (unsigned __int128)400 * sm[0] * sm[0];
+      const unsigned __int128 rhs = (unsigned __int128)361 * sm[1] * sm[2];
+      similar = len_ok && sm[0] > 0 && lhs > rhs;
+    }
+    res->similar = similar ? 1u : 0u;
+    if (flags & SS_MATCH_STEP_STAGE) stage_step(ctx, similar);
+    res->stage = ctx->stage;
+    res->stable_step = ctx->stable_step;
+    res->n_unmatched = (k && !aligned) ? unm : 0;
+    if (k && aligned) {                                      // the scratch is free again: the stream is idle
+      std::vector<int32_t> ref_to_cur(n);
+      uint32_t lcs = 0;
+      rc = ss_align_core(ctx, ref, n, cur, m, ref_to_cur.data(), &lcs, nullptr);
+      if (rc != SS_OK) return rc;
+      ss_align_anchors(ref, n, cur, ref_to_cur.data(), anchors, k, new_idx, level, &res->n_unmatched);
+    }
+    return SS_OK;
+  });
 }

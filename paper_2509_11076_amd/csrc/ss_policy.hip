@@ -343,95 +343,98 @@ extern "C" int ss_apply_policy(ss_ctx *ctx, const ss_policy_item_t *policy, uint
                                ss_action_t *actions, uint32_t *n_actions, ss_desc_t *descs_out,
                                ss_desc_t *descs_in, ss_event_t *pevents, uint32_t *n_pe,
                                ss_apply_result_t *res) {
-  if (!ctx || !res || !n_actions || !n_pe) return SS_E_INVAL;
-  if (k && (!policy || !new_idx || !actions || !descs_out || !descs_in || !pevents)) return SS_E_INVAL;
-  if (n_tensors && !tensors) return SS_E_INVAL;
-  ss_applied ap;
-  int rc = ss_apply_core(ctx->cfg, policy, k, new_idx, tensors, n_tensors, ap);
-  if (rc != SS_OK) return rc;
-  if (ap.actions.size() > *n_actions || ap.pevents.size() > *n_pe) return SS_E_CAPACITY;
-  if (resolved && k) std::memcpy(resolved, ap.resolved.data(), (size_t)k * sizeof(ss_policy_item_t));
-  if (!ap.actions.empty()) std::memcpy(actions, ap.actions.data(), ap.actions.size() * sizeof(ss_action_t));
-  if (!ap.out.empty()) std::memcpy(descs_out, ap.out.data(), ap.out.size() * sizeof(ss_desc_t));
-  if (!ap.in.empty()) std::memcpy(descs_in, ap.in.data(), ap.in.size() * sizeof(ss_desc_t));
-  if (!ap.pevents.empty()) std::memcpy(pevents, ap.pevents.data(), ap.pevents.size() * sizeof(ss_event_t));
-  *n_actions = (uint32_t)ap.actions.size();
-  *n_pe = (uint32_t)ap.pevents.size();
-  std::memset(res, 0, sizeof(*res));
-  res->staging_bytes = ap.staging_bytes;
-  res->bytes_out = ap.bytes_out;
-  res->n_kept = ap.n_kept;
-  res->n_dropped = ap.n_dropped;
-  res->n_late = ap.n_late;
-  res->n_out_batches = (uint32_t)ap.out_start.size() - 1;
-  res->n_in_batches = (uint32_t)ap.in_start.size() - 1;
-  if (ap.staging_bytes > ctx->cfg.staging_bytes) return SS_E_NOMEM;
-  if (!ctx->bound) return SS_OK;          // schedule computed; nothing to load it against yet
-  return ss_load_schedule(ctx, ap.out.data(), (uint32_t)ap.out.size(), ap.out_start.data(), res->n_out_batches,
-                          ap.in.data(), (uint32_t)ap.in.size(), ap.in_start.data(), res->n_in_batches,
-                          ap.in_dep.data());
+  return ss_guard([&]() -> int {
+    if (!ctx || !res || !n_actions || !n_pe) return SS_E_INVAL;
+    if (k && (!policy || !new_idx || !actions || !descs_out || !descs_in || !pevents)) return SS_E_INVAL;
+    if (n_tensors && !tensors) return SS_E_INVAL;
+    ss_applied ap;
+    int rc = ss_apply_core(ctx->cfg, policy, k, new_idx, tensors, n_tensors, ap);
+    if (rc != SS_OK) return rc;
+    if (ap.actions.size() > *n_actions || ap.pevents.size() > *n_pe) return SS_E_CAPACITY;
+    if (resolved && k) std::memcpy(resolved, ap.resolved.data(), (size_t)k * sizeof(ss_policy_item_t));
+    if (!ap.actions.empty()) std::memcpy(actions, ap.actions.data(), ap.actions.size() * sizeof(ss_action_t));
+    if (!ap.out.empty()) std::memcpy(descs_out, ap.out.data(), ap.out.size() * sizeof(ss_desc_t));
+    if (!ap.in.empty()) std::memcpy(descs_in, ap.in.data(), ap.in.size() * sizeof(ss_desc_t));
+    if (!ap.pevents.empty()) std::memcpy(pevents, ap.pevents.data(), ap.pevents.size() * sizeof(ss_event_t));
+    *n_actions = (uint32_t)ap.actions.size();
+    *n_pe = (uint32_t)ap.pevents.size();
+    std::memset(res, 0, sizeof(*res));
+    res->staging_bytes = ap.staging_bytes;
+    res->bytes_out = ap.bytes_out;
+    res->n_kept = ap.n_kept;
+    res->n_dropped = ap.n_dropped;
+    res->n_late = ap.n_late;
+    res->n_out_batches = (uint32_t)ap.out_start.size() - 1;
+    res->n_in_batches = (uint32_t)ap.in_start.size() - 1;
+    if (ap.staging_bytes > ctx->cfg.staging_bytes) return SS_E_NOMEM;
+    if (!ctx->bound) return SS_OK;          // schedule computed; nothing to load it against yet
+    return ss_load_schedule(ctx, ap.out.data(), (uint32_t)ap.out.size(), ap.out_start.data(), res->n_out_batches,
+                            ap.in.data(), (uint32_t)ap.in.size(), ap.in_start.data(), res->n_in_batches,
+                            ap.in_dep.data());
+  });
 }
 
 extern "C" int ss_greedy_policy(ss_ctx *ctx, const ss_tensor_t *tensors, uint32_t n_tensors, const ss_event_t *ev,
                                 uint64_t n_ev, uint32_t n_ops, int64_t base, int64_t budget, uint64_t min_bytes,
                                 const ss_policy_item_t *initial, uint32_t n_initial,
                                 ss_policy_item_t *policy_out, uint32_t *n_policy, int64_t *peak_out) {
-  if (!ctx || !n_policy || (n_tensors && !tensors) || (n_initial && !initial)) return SS_E_INVAL;
-  if (*n_policy && !policy_out) return SS_E_INVAL;
-  const uint32_t cap = *n_policy;
-  std::vector<ss_policy_item_t> rows(initial, initial + n_initial);
-  std::vector<int32_t> idx;
-  std::vector<int64_t> mre(n_ops);
-  ss_scan_result_t sr;
-  ss_applied ap;
-  auto evaluate = [&](bool want_mre) -> int {
-    idx.resize(rows.size());
-    for (size_t i = 0; i < rows.size(); ++i) idx[i] = (int32_t)rows[i].ref_op;   // same iteration: identity
-    int rc = ss_apply_core(ctx->cfg, rows.data(), (uint32_t)rows.size(), idx.data(), tensors, n_tensors, ap);
+  return ss_guard([&]() -> int {
+    if (!ctx || !n_policy || (n_tensors && !tensors) || (n_initial && !initial)) return SS_E_INVAL;
+    if (*n_policy && !policy_out) return SS_E_INVAL;
+    const uint32_t cap = *n_policy;
+    std::vector<ss_policy_item_t> rows(initial, initial + n_initial);
+    std::vector<int32_t> idx;
+    std::vector<int64_t> mre(n_ops);
+    ss_scan_result_t sr;
+    ss_applied ap;
+    auto evaluate = [&](bool want_mre) -> int {
+      idx.resize(rows.size());
+      for (size_t i = 0; i < rows.size(); ++i) idx[i] = (int32_t)rows[i].ref_op;   // same iteration: identity
+      int rc = ss_apply_core(ctx->cfg, rows.data(), (uint32_t)rows.size(), idx.data(), tensors, n_tensors, ap);
+      if (rc != SS_OK) return rc;
+      return ss_timeline_scan(ctx, ev, n_ev, ap.pevents.data(), ap.pevents.size(), n_ops, base, budget, nullptr,
+                              nullptr, want_mre ? mre.data() : nullptr, &sr);
+    };
+    auto finish = [&]() -> int {
+      if (rows.size() > cap) return SS_E_CAPACITY;
+      if (!rows.empty()) std::memcpy(policy_out, rows.data(), rows.size() * sizeof(ss_policy_item_t));
+      *n_policy = (uint32_t)rows.size();
+      if (peak_out) *peak_out = sr.peak;
+      return SS_OK;
+    };
+    int rc = evaluate(true);
     if (rc != SS_OK) return rc;
-    return ss_timeline_scan(ctx, ev, n_ev, ap.pevents.data(), ap.pevents.size(), n_ops, base, budget, nullptr,
-                            nullptr, want_mre ? mre.data() : nullptr, &sr);
-  };
-  auto finish = [&]() -> int {
-    if (rows.size() > cap) return SS_E_CAPACITY;
-    if (!rows.empty()) std::memcpy(policy_out, rows.data(), rows.size() * sizeof(ss_policy_item_t));
-    *n_policy = (uint32_t)rows.size();
-    if (peak_out) *peak_out = sr.peak;
-    return SS_OK;
-  };
-  int rc = evaluate(true);
-  if (rc != SS_OK) return rc;
-  if (sr.peak <= budget) return finish();
+    if (sr.peak <= budget) return finish();
 
-  // candidates: kept from forward to backward with room for a round trip, not too small, not
-  // already chosen, idle span covering at least one over-budget operator (Sec. 4.2)
-  std::vector<uint32_t> over_prefix(n_ops + 1, 0);        // over_prefix[t] = #over-budget operators < t
-  for (uint32_t t = 0; t < n_ops; ++t) over_prefix[t + 1] = over_prefix[t] + (mre[t] > 0);
-  std::vector<uint8_t> chosen(n_tensors, 0);
-  {
-    std::vector<std::pair<uint32_t, uint32_t>> by_id(n_tensors);
-    for (uint32_t r = 0; r < n_tensors; ++r) by_id[r] = {tensors[r].tensor_id, r};
-    std::sort(by_id.begin(), by_id.end());
-    for (const ss_policy_item_t &p : rows) {
-      auto it = std::lower_bound(by_id.begin(), by_id.end(), std::make_pair(p.tensor_id, 0u));
-      if (it != by_id.end() && it->first == p.tensor_id) chosen[it->second] = 1;
+    // candidates: kept from forward to backward with room for a round trip, not too small, not
+    // already chosen, idle span covering at least one over-budget operator (Sec. 4.2)
+    std::vector<uint32_t> over_prefix(n_ops + 1, 0);        // over_prefix[t] = #over-budget operators < t
+    for (uint32_t t = 0; t < n_ops; ++t) over_prefix[t + 1] = over_prefix[t] + (mre[t] > 0);
+    std::vector<uint8_t> chosen(n_tensors, 0);
+    {
+      std::vector<std::pair<uint32_t, uint32_t>> by_id(n_tensors);
+      for (uint32_t r = 0; r < n_tensors; ++r) by_id[r] = {tensors[r].tensor_id, r};
+      std::sort(by_id.begin(), by_id.end());
+      for (const ss_policy_item_t &p : rows) {
+        auto it = std::lower_bound(by_id.begin(), by_id.end(), std::make_pair(p.tensor_id, 0u));
+        if (it != by_id.end() && it->first == p.tensor_id) chosen[it->second] = 1;
+      }
     }
-  }
-  std::vector<uint32_t> cand;
-  for (uint32_t r = 0; r < n_tensors; ++r) {
-    const ss_tensor_t &t = tensors[r];
-    if (t.last_fwd_use == SS_NONE_OP || t.first_bwd_use == SS_NONE_OP) continue;
-    if (!((uint64_t)t.last_fwd_use + 1 < t.first_bwd_use) || t.first_bwd_use > n_ops) continue;
-    if (t.nbytes < min_bytes || chosen[r]) continue;
-    if (over_prefix[t.first_bwd_use] - over_prefix[t.last_fwd_use + 1] == 0) continue;
-    cand.push_back(r);
-  }
-  std::sort(cand.begin(), cand.end(), [&](uint32_t x, uint32_t y) {
-    const ss_tensor_t &a = tensors[x], &b = tensors[y];
-    const uint32_t ia = a.first_bwd_use - a.last_fwd_use, ib = b.first_bwd_use - b.last_fwd_use;
-    if (ia != ib) return ia > ib;                          // longest idle span first
-    if (a.nbytes != b.nbytes) return a.nbytes > b.nbytes;  // then larger first
-    return a.tensor_id < b.tensor_id;
+    std::vector<uint32_t> cand;
+    for (uint32_t r = 0; r < n_tensors; ++r) {
+      const ss_tensor_t &t = tensors[r];
+      if (t.last_fwd_use == SS_NONE_OP || t.first_bwd_use == SS_NONE_OP) continue;
+      if (!((uint64_t)t.last_fwd_use + 1 < t.first_bwd_use) || t.first_bwd_use > n_ops) continue;
+      if (t.nbytes < min_bytes || chosen[r]) continue;
+      if (over_prefix[t.first_bwd_use] - over_prefix[t.last_fwd_use + 1] == 0) continue;
+      cand.push_back(r);
+    }
+    std::sort(cand.begin(), cand.end(), [&](uint32_t x, uint32_t y) {
+      const ss_tensor_t &a = tensors[x], &b = tensors[y];
+      const uint32_t ia = a.first_bwd_use - a.last_fwd_use, ib = b.first_bwd_use - b.last_fwd_use;
+      if (ia != ib) return ia > ib;                          // longest idle span first
+      if (a.nbytes != b.nbytes) return a.nbytes > b.nbytes;  // then larger first
+      return a.tensor_id < b.tensor_id;
   });
   for (uint32_t r : cand) {
     const ss_tensor_t &t = tensors[r];
@@ -444,4 +447,5 @@ extern "C" int ss_greedy_policy(ss_ctx *ctx, const ss_tensor_t *tensors, uint32_
   }
   if (peak_out) *peak_out = sr.peak;
   return SS_E_INFEASIBLE;
+  });
 }

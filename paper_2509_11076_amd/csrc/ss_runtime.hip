@@ -71,60 +71,62 @@ static unsigned fence_flag(const ss_config_t &cfg) {
 }
 
 extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
-  if (!out) return SS_E_INVAL;
-  *out = nullptr;
-  ss_config_t cfg;
-  ss_config_default(&cfg);
-  if (cfg_in) cfg = *cfg_in;
-  if (cfg.align < 16 || (cfg.align & (cfg.align - 1)) || cfg.guard_bytes % cfg.align ||
-      cfg.link_bytes_per_op == 0 || cfg.max_ops == 0 || cfg.max_events == 0 ||
-      cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_ENGINE || cfg.copy_path_in > SS_PATH_ENGINE)
-    return SS_E_INVAL;
-  if (cfg.copy_workgroups == 0) cfg.copy_workgroups = default_workgroups();
-  if (cfg.copy_workgroups_out == 0) cfg.copy_workgroups_out = cfg.copy_workgroups;
-  if (cfg.copy_unroll == 0) cfg.copy_unroll = 8;
-  if (cfg.copy_workgroups > 4096 || cfg.copy_workgroups_out > 4096 || cfg.copy_unroll > 8) return SS_E_INVAL;
+  return ss_guard([&]() -> int {
+    if (!out) return SS_E_INVAL;
+    *out = nullptr;
+    ss_config_t cfg;
+    ss_config_default(&cfg);
+    if (cfg_in) cfg = *cfg_in;
+    if (cfg.align < 16 || (cfg.align & (cfg.align - 1)) || cfg.guard_bytes % cfg.align ||
+        cfg.link_bytes_per_op == 0 || cfg.max_ops == 0 || cfg.max_events == 0 ||
+        cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_ENGINE || cfg.copy_path_in > SS_PATH_ENGINE)
+      return SS_E_INVAL;
+    if (cfg.copy_workgroups == 0) cfg.copy_workgroups = default_workgroups();
+    if (cfg.copy_workgroups_out == 0) cfg.copy_workgroups_out = cfg.copy_workgroups;
+    if (cfg.copy_unroll == 0) cfg.copy_unroll = 8;
+    if (cfg.copy_workgroups > 4096 || cfg.copy_workgroups_out > 4096 || cfg.copy_unroll > 8) return SS_E_INVAL;
 
-  ss_ctx *ctx = new (std::nothrow) ss_ctx();
-  if (!ctx) return SS_E_NOMEM;
-  ctx->cfg = cfg;
-  std::memset(&ctx->stats, 0, sizeof(ctx->stats));
-  int rc = SS_OK;
-  auto fail_at = [&](int code, hipError_t e, int line) {
-    ctx->stats.last_hip_error = (int32_t)e;
-    ss_note_hip_error((int)e, __FILE__, line);
-    (void)hipGetLastError();
-    rc = code;
-  };
+    ss_ctx *ctx = new (std::nothrow) ss_ctx();
+    if (!ctx) return SS_E_NOMEM;
+    ctx->cfg = cfg;
+    std::memset(&ctx->stats, 0, sizeof(ctx->stats));
+    int rc = SS_OK;
+    auto fail_at = [&](int code, hipError_t e, int line) {
+      ctx->stats.last_hip_error = (int32_t)e;
+      ss_note_hip_error((int)e, __FILE__, line);
+      (void)hipGetLastError();
+      rc = code;
+    };
 #define fail(code, e) fail_at(code, e, __LINE__)
-  hipError_t e;
-  if ((e = hipGetDevice(&ctx->device)) != hipSuccess) fail(SS_E_HIP, e);
-  if (rc == SS_OK && cfg.staging_bytes) {
-    e = hipHostMalloc((void **)&ctx->staging, cfg.staging_bytes, hipHostMallocMapped | hipHostMallocPortable);
-    if (e != hipSuccess) fail(SS_E_NOMEM, e);
-    else if ((e = hipHostGetDevicePointer((void **)&ctx->staging_dev, ctx->staging, 0)) != hipSuccess)
-      fail(SS_E_HIP, e);
-  }
-  if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->ops, (size_t)cfg.max_ops * sizeof(ss_op_t),
-                                        hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
-  if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->events, (size_t)cfg.max_events * sizeof(ss_event_t),
-                                        hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
-  // all streams at the default priority
-  if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
-  if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
-  if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_aux, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
-  for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
-    hipEvent_t ev;
-    if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming | fence_flag(cfg))) != hipSuccess) fail(SS_E_HIP, e);
-    else ctx->ev_ring.push_back(ev);
-  }
+    hipError_t e;
+    if ((e = hipGetDevice(&ctx->device)) != hipSuccess) fail(SS_E_HIP, e);
+    if (rc == SS_OK && cfg.staging_bytes) {
+      e = hipHostMalloc((void **)&ctx->staging, cfg.staging_bytes, hipHostMallocMapped | hipHostMallocPortable);
+      if (e != hipSuccess) fail(SS_E_NOMEM, e);
+      else if ((e = hipHostGetDevicePointer((void **)&ctx->staging_dev, ctx->staging, 0)) != hipSuccess)
+        fail(SS_E_HIP, e);
+    }
+    if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->ops, (size_t)cfg.max_ops * sizeof(ss_op_t),
+                                          hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
+    if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->events, (size_t)cfg.max_events * sizeof(ss_event_t),
+                                          hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
+    // all streams at the default priority
+    if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+    if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+    if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_aux, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+    for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
+      hipEvent_t ev;
+      if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming | fence_flag(cfg))) != hipSuccess) fail(SS_E_HIP, e);
+      else ctx->ev_ring.push_back(ev);
+    }
 #undef fail
-  if (rc != SS_OK) {
-    ss_destroy(ctx);
-    return rc;
-  }
-  *out = ctx;
-  return SS_OK;
+    if (rc != SS_OK) {
+      ss_destroy(ctx);
+      return rc;
+    }
+    *out = ctx;
+    return SS_OK;
+  });
 }
 
 static void free_events(std::vector<hipEvent_t> &v) {
@@ -284,149 +286,151 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
                                 const uint32_t *out_start, uint32_t n_out_batches,
                                 const ss_desc_t *descs_in, uint32_t n_in, const uint32_t *in_start,
                                 uint32_t n_in_batches, const uint32_t *in_dep) {
-  if (!ctx || (n_out && !descs_out) || (n_in && !descs_in)) return SS_E_INVAL;
-  if (!ctx->bound) return SS_E_STATE;
-  int rc;
-  if ((rc = check_batches(out_start, n_out_batches, n_out)) != SS_OK) return rc;
-  if ((rc = check_batches(in_start, n_in_batches, n_in)) != SS_OK) return rc;
-  for (uint32_t b = 0; in_dep && b < n_in_batches; ++b)
-    if (n_out_batches == 0 || in_dep[b] >= n_out_batches) return SS_E_INVAL;
-  ss_sched &s = ctx->sched;
-  // the same schedule as the one already loaded (a fixed operator sequence in the Stable stage): it was
-  // validated against this arena and staging area when it was loaded; device tables, chunk tables and
-  // events stay, only the per-iteration state starts over
-  {
-    std::vector<uint32_t> dep(n_in_batches);
-    for (uint32_t b = 0; b < n_in_batches; ++b) dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
-    const bool same =
-        s.loaded && s.out.size() == n_out && s.in.size() == n_in && s.out_start.size() == (size_t)n_out_batches + 1 &&
-        s.in_start.size() == (size_t)n_in_batches + 1 && s.in_dep == dep &&
-        (n_out == 0 || std::memcmp(s.out.data(), descs_out, (size_t)n_out * sizeof(ss_desc_t)) == 0) &&
-        (n_in == 0 || std::memcmp(s.in.data(), descs_in, (size_t)n_in * sizeof(ss_desc_t)) == 0) &&
-        (n_out_batches == 0 || std::memcmp(s.out_start.data(), out_start, ((size_t)n_out_batches + 1) * 4) == 0) &&
-        (n_in_batches == 0 || std::memcmp(s.in_start.data(), in_start, ((size_t)n_in_batches + 1) * 4) == 0);
-    if (same) {
-      // nothing of the previous iteration may still be in flight
-      SS_HIP(hipStreamSynchronize(ctx->s_out));
-      SS_HIP(hipStreamSynchronize(ctx->s_in));
-      std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
-      std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
-      std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
-      std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
-      s.last_engine_out = -1;
+  return ss_guard([&]() -> int {
+    if (!ctx || (n_out && !descs_out) || (n_in && !descs_in)) return SS_E_INVAL;
+    if (!ctx->bound) return SS_E_STATE;
+    int rc;
+    if ((rc = check_batches(out_start, n_out_batches, n_out)) != SS_OK) return rc;
+    if ((rc = check_batches(in_start, n_in_batches, n_in)) != SS_OK) return rc;
+    for (uint32_t b = 0; in_dep && b < n_in_batches; ++b)
+      if (n_out_batches == 0 || in_dep[b] >= n_out_batches) return SS_E_INVAL;
+    ss_sched &s = ctx->sched;
+    // the same schedule as the one already loaded (a fixed operator sequence in the Stable stage): it was
+    // validated against this arena and staging area when it was loaded; device tables, chunk tables and
+    // events stay, only the per-iteration state starts over
+    {
+      std::vector<uint32_t> dep(n_in_batches);
+      for (uint32_t b = 0; b < n_in_batches; ++b) dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
+      const bool same =
+          s.loaded && s.out.size() == n_out && s.in.size() == n_in && s.out_start.size() == (size_t)n_out_batches + 1 &&
+          s.in_start.size() == (size_t)n_in_batches + 1 && s.in_dep == dep &&
+          (n_out == 0 || std::memcmp(s.out.data(), descs_out, (size_t)n_out * sizeof(ss_desc_t)) == 0) &&
+          (n_in == 0 || std::memcmp(s.in.data(), descs_in, (size_t)n_in * sizeof(ss_desc_t)) == 0) &&
+          (n_out_batches == 0 || std::memcmp(s.out_start.data(), out_start, ((size_t)n_out_batches + 1) * 4) == 0) &&
+          (n_in_batches == 0 || std::memcmp(s.in_start.data(), in_start, ((size_t)n_in_batches + 1) * 4) == 0);
+      if (same) {
+        // nothing of the previous iteration may still be in flight
+        SS_HIP(hipStreamSynchronize(ctx->s_out));
+        SS_HIP(hipStreamSynchronize(ctx->s_in));
+        std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
+        std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
+        std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
+        std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
+        s.last_engine_out = -1;
+        return SS_OK;
+      }
+    }
+    if ((rc = check_descs(ctx, descs_out, n_out)) != SS_OK) return rc;
+    if ((rc = check_descs(ctx, descs_in, n_in)) != SS_OK) return rc;
+    // staging slots of the swap-out side must be pairwise disjoint
+    {
+      std::vector<std::pair<uint64_t, uint64_t>> iv;
+      iv.reserve(n_out);
+      for (uint32_t i = 0; i < n_out; ++i)
+        if (descs_out[i].nbytes) iv.emplace_back(descs_out[i].host_off, descs_out[i].host_off + descs_out[i].nbytes);
+      std::sort(iv.begin(), iv.end());
+      for (size_t i = 1; i < iv.size(); ++i)
+        if (iv[i].first < iv[i - 1].second) return SS_E_INVAL;
+    }
+    // nothing of the previous schedule may still be in flight
+    SS_HIP(hipStreamSynchronize(ctx->s_out));
+    SS_HIP(hipStreamSynchronize(ctx->s_in));
+
+    s.loaded = false;
+    s.out.assign(descs_out, descs_out + n_out);
+    s.in.assign(descs_in, descs_in + n_in);
+    s.out_start.assign(out_start ? out_start : nullptr, out_start ? out_start + n_out_batches + 1 : nullptr);
+    s.in_start.assign(in_start ? in_start : nullptr, in_start ? in_start + n_in_batches + 1 : nullptr);
+    if (s.out_start.empty()) s.out_start.push_back(0);
+    if (s.in_start.empty()) s.in_start.push_back(0);
+    s.in_dep.resize(n_in_batches);
+    for (uint32_t b = 0; b < n_in_batches; ++b) s.in_dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
+    build_chunks(s.out, s.out_start, s.out_chunk0, s.out_cdesc, s.out_cbase, s.out_shift);
+    build_chunks(s.in, s.in_start, s.in_chunk0, s.in_cdesc, s.in_cbase, s.in_shift);
+    s.out_of_tensor.clear();
+    s.in_of_tensor.clear();
+    s.out_batch_of.assign(n_out, 0);
+    s.in_batch_of.assign(n_in, 0);
+    for (uint32_t b = 0; b < n_out_batches; ++b)
+      for (uint32_t i = s.out_start[b]; i < s.out_start[b + 1]; ++i) {
+        s.out_batch_of[i] = b;
+        s.out_of_tensor[s.out[i].tensor_id] = i;
+      }
+    for (uint32_t b = 0; b < n_in_batches; ++b)
+      for (uint32_t i = s.in_start[b]; i < s.in_start[b + 1]; ++i) {
+        s.in_batch_of[i] = b;
+        s.in_of_tensor[s.in[i].tensor_id] = i;
+      }
+    s.out_waited.assign(n_out_batches, 0);
+    s.out_issued.assign(n_out_batches, 0);
+    s.in_waited.assign(n_in_batches, 0);
+    s.in_issued.assign(n_in_batches, 0);
+    s.last_engine_out = -1;
+    s.out_all_large = ctx->cfg.engine_min_bytes_out != 0 && n_out_batches != 0;
+    for (uint32_t b = 0; b < n_out_batches && s.out_all_large; ++b) {
+      uint64_t total = 0;
+      const uint32_t cnt = s.out_start[b + 1] - s.out_start[b];
+      for (uint32_t i = s.out_start[b]; i < s.out_start[b + 1]; ++i) total += s.out[i].nbytes;
+      if (cnt && total / cnt < ctx->cfg.engine_min_bytes_out) s.out_all_large = false;
+    }
+
+    const unsigned evflags = ((ctx->cfg.flags & SS_CFG_TIMING) ? hipEventDefault : hipEventDisableTiming) |
+                             fence_flag(ctx->cfg);
+    if ((rc = ensure_events(ctx, s.ev_out_done, n_out_batches, evflags)) != SS_OK) return rc;
+    if ((rc = ensure_events(ctx, s.ev_in_done, n_in_batches, evflags)) != SS_OK) return rc;
+    if (ctx->cfg.flags & SS_CFG_TIMING) {
+      if ((rc = ensure_events(ctx, s.ev_out_start, n_out_batches, evflags)) != SS_OK) return rc;
+      if ((rc = ensure_events(ctx, s.ev_in_start, n_in_batches, evflags)) != SS_OK) return rc;
+    }
+    // device copies of descriptors and chunk tables
+    auto upload = [&](const std::vector<ss_desc_t> &d, const std::vector<uint32_t> &c, ss_desc_t *&dd,
+                      uint32_t *&dc, size_t &cap) -> int {
+      if (d.empty()) return SS_OK;
+      if (d.size() > cap) {
+        if (dd) SS_HIP(hipFree(dd));
+        if (dc) SS_HIP(hipFree(dc));
+        dd = nullptr; dc = nullptr; cap = 0;
+        size_t want = d.size() + d.size() / 2 + 64;
+        hipError_t e = hipMalloc((void **)&dd, want * sizeof(ss_desc_t));
+        if (e == hipSuccess) e = hipMalloc((void **)&dc, (2 * want + 64) * sizeof(uint32_t));
+        if (e != hipSuccess) {
+          ctx->stats.last_hip_error = (int32_t)e;
+          ss_note_hip_error((int)e, __FILE__, __LINE__);
+          (void)hipGetLastError();
+          return SS_E_NOMEM;
+        }
+        cap = want;
+      }
+      if (c.size() > 2 * cap + 64) return SS_E_CAPACITY;
+      SS_HIP(hipMemcpy(dd, d.data(), d.size() * sizeof(ss_desc_t), hipMemcpyHostToDevice));
+      SS_HIP(hipMemcpy(dc, c.data(), c.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
       return SS_OK;
-    }
-  }
-  if ((rc = check_descs(ctx, descs_out, n_out)) != SS_OK) return rc;
-  if ((rc = check_descs(ctx, descs_in, n_in)) != SS_OK) return rc;
-  // staging slots of the swap-out side must be pairwise disjoint
-  {
-    std::vector<std::pair<uint64_t, uint64_t>> iv;
-    iv.reserve(n_out);
-    for (uint32_t i = 0; i < n_out; ++i)
-      if (descs_out[i].nbytes) iv.emplace_back(descs_out[i].host_off, descs_out[i].host_off + descs_out[i].nbytes);
-    std::sort(iv.begin(), iv.end());
-    for (size_t i = 1; i < iv.size(); ++i)
-      if (iv[i].first < iv[i - 1].second) return SS_E_INVAL;
-  }
-  // nothing of the previous schedule may still be in flight
-  SS_HIP(hipStreamSynchronize(ctx->s_out));
-  SS_HIP(hipStreamSynchronize(ctx->s_in));
-
-  s.loaded = false;
-  s.out.assign(descs_out, descs_out + n_out);
-  s.in.assign(descs_in, descs_in + n_in);
-  s.out_start.assign(out_start ? out_start : nullptr, out_start ? out_start + n_out_batches + 1 : nullptr);
-  s.in_start.assign(in_start ? in_start : nullptr, in_start ? in_start + n_in_batches + 1 : nullptr);
-  if (s.out_start.empty()) s.out_start.push_back(0);
-  if (s.in_start.empty()) s.in_start.push_back(0);
-  s.in_dep.resize(n_in_batches);
-  for (uint32_t b = 0; b < n_in_batches; ++b) s.in_dep[b] = in_dep ? in_dep[b] : (n_out_batches ? n_out_batches - 1 : 0);
-  build_chunks(s.out, s.out_start, s.out_chunk0, s.out_cdesc, s.out_cbase, s.out_shift);
-  build_chunks(s.in, s.in_start, s.in_chunk0, s.in_cdesc, s.in_cbase, s.in_shift);
-  s.out_of_tensor.clear();
-  s.in_of_tensor.clear();
-  s.out_batch_of.assign(n_out, 0);
-  s.in_batch_of.assign(n_in, 0);
-  for (uint32_t b = 0; b < n_out_batches; ++b)
-    for (uint32_t i = s.out_start[b]; i < s.out_start[b + 1]; ++i) {
-      s.out_batch_of[i] = b;
-      s.out_of_tensor[s.out[i].tensor_id] = i;
-    }
-  for (uint32_t b = 0; b < n_in_batches; ++b)
-    for (uint32_t i = s.in_start[b]; i < s.in_start[b + 1]; ++i) {
-      s.in_batch_of[i] = b;
-      s.in_of_tensor[s.in[i].tensor_id] = i;
-    }
-  s.out_waited.assign(n_out_batches, 0);
-  s.out_issued.assign(n_out_batches, 0);
-  s.in_waited.assign(n_in_batches, 0);
-  s.in_issued.assign(n_in_batches, 0);
-  s.last_engine_out = -1;
-  s.out_all_large = ctx->cfg.engine_min_bytes_out != 0 && n_out_batches != 0;
-  for (uint32_t b = 0; b < n_out_batches && s.out_all_large; ++b) {
-    uint64_t total = 0;
-    const uint32_t cnt = s.out_start[b + 1] - s.out_start[b];
-    for (uint32_t i = s.out_start[b]; i < s.out_start[b + 1]; ++i) total += s.out[i].nbytes;
-    if (cnt && total / cnt < ctx->cfg.engine_min_bytes_out) s.out_all_large = false;
-  }
-
-  const unsigned evflags = ((ctx->cfg.flags & SS_CFG_TIMING) ? hipEventDefault : hipEventDisableTiming) |
-                           fence_flag(ctx->cfg);
-  if ((rc = ensure_events(ctx, s.ev_out_done, n_out_batches, evflags)) != SS_OK) return rc;
-  if ((rc = ensure_events(ctx, s.ev_in_done, n_in_batches, evflags)) != SS_OK) return rc;
-  if (ctx->cfg.flags & SS_CFG_TIMING) {
-    if ((rc = ensure_events(ctx, s.ev_out_start, n_out_batches, evflags)) != SS_OK) return rc;
-    if ((rc = ensure_events(ctx, s.ev_in_start, n_in_batches, evflags)) != SS_OK) return rc;
-  }
-  // device copies of descriptors and chunk tables
-  auto upload = [&](const std::vector<ss_desc_t> &d, const std::vector<uint32_t> &c, ss_desc_t *&dd,
-                    uint32_t *&dc, size_t &cap) -> int {
-    if (d.empty()) return SS_OK;
-    if (d.size() > cap) {
-      if (dd) SS_HIP(hipFree(dd));
-      if (dc) SS_HIP(hipFree(dc));
-      dd = nullptr; dc = nullptr; cap = 0;
-      size_t want = d.size() + d.size() / 2 + 64;
-      hipError_t e = hipMalloc((void **)&dd, want * sizeof(ss_desc_t));
-      if (e == hipSuccess) e = hipMalloc((void **)&dc, (2 * want + 64) * sizeof(uint32_t));
-      if (e != hipSuccess) {
-        ctx->stats.last_hip_error = (int32_t)e;
-        ss_note_hip_error((int)e, __FILE__, __LINE__);
-        (void)hipGetLastError();
-        return SS_E_NOMEM;
+    };
+    if ((rc = upload(s.out, s.out_chunk0, s.d_out, s.d_out_chunk0, s.d_cap_out)) != SS_OK) return rc;
+    if ((rc = upload(s.in, s.in_chunk0, s.d_in, s.d_in_chunk0, s.d_cap_in)) != SS_OK) return rc;
+    auto upload_map = [&](const std::vector<uint32_t> &m, uint32_t *&dm, size_t &cap) -> int {
+      if (m.empty()) return SS_OK;
+      if (m.size() > cap) {
+        if (dm) SS_HIP(hipFree(dm));
+        dm = nullptr; cap = 0;
+        const size_t want = m.size() + m.size() / 4 + 1024;
+        hipError_t e = hipMalloc((void **)&dm, want * sizeof(uint32_t));
+        if (e != hipSuccess) {
+          ctx->stats.last_hip_error = (int32_t)e;
+          ss_note_hip_error((int)e, __FILE__, __LINE__);
+          (void)hipGetLastError();
+          return SS_E_NOMEM;
+        }
+        cap = want;
       }
-      cap = want;
-    }
-    if (c.size() > 2 * cap + 64) return SS_E_CAPACITY;
-    SS_HIP(hipMemcpy(dd, d.data(), d.size() * sizeof(ss_desc_t), hipMemcpyHostToDevice));
-    SS_HIP(hipMemcpy(dc, c.data(), c.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+      SS_HIP(hipMemcpy(dm, m.data(), m.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+      return SS_OK;
+    };
+    if ((rc = upload_map(s.out_cdesc, s.d_out_cdesc, s.d_ccap_out)) != SS_OK) return rc;
+    if ((rc = upload_map(s.in_cdesc, s.d_in_cdesc, s.d_ccap_in)) != SS_OK) return rc;
+    s.loaded = true;
     return SS_OK;
-  };
-  if ((rc = upload(s.out, s.out_chunk0, s.d_out, s.d_out_chunk0, s.d_cap_out)) != SS_OK) return rc;
-  if ((rc = upload(s.in, s.in_chunk0, s.d_in, s.d_in_chunk0, s.d_cap_in)) != SS_OK) return rc;
-  auto upload_map = [&](const std::vector<uint32_t> &m, uint32_t *&dm, size_t &cap) -> int {
-    if (m.empty()) return SS_OK;
-    if (m.size() > cap) {
-      if (dm) SS_HIP(hipFree(dm));
-      dm = nullptr; cap = 0;
-      const size_t want = m.size() + m.size() / 4 + 1024;
-      hipError_t e = hipMalloc((void **)&dm, want * sizeof(uint32_t));
-      if (e != hipSuccess) {
-        ctx->stats.last_hip_error = (int32_t)e;
-        ss_note_hip_error((int)e, __FILE__, __LINE__);
-        (void)hipGetLastError();
-        return SS_E_NOMEM;
-      }
-      cap = want;
-    }
-    SS_HIP(hipMemcpy(dm, m.data(), m.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
-    return SS_OK;
-  };
-  if ((rc = upload_map(s.out_cdesc, s.d_out_cdesc, s.d_ccap_out)) != SS_OK) return rc;
-  if ((rc = upload_map(s.in_cdesc, s.d_in_cdesc, s.d_ccap_in)) != SS_OK) return rc;
-  s.loaded = true;
-  return SS_OK;
+  });
 }
 
 extern "C" int ss_schedule_view(ss_ctx *ctx, const uint32_t **out_start, uint32_t *n_out_batches,
@@ -680,100 +684,102 @@ extern "C" int ss_get_stats(ss_ctx *ctx, ss_stats_t *out) {
 
 // Host-link bandwidth as the machine delivers it now.
 extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *out) {
-  if (!ctx || !out || bytes < 4096 || reps == 0 || reps > 1000) return SS_E_INVAL;
-  bytes &= ~(uint64_t)255;
-  std::memset(out, 0, sizeof(*out));
-  uint8_t *h0 = nullptr, *h1 = nullptr, *d0 = nullptr, *d1 = nullptr, *h0d = nullptr, *h1d = nullptr;
-  ss_desc_t *dd = nullptr;
-  uint32_t *dc = nullptr, *dm = nullptr;
-  hipEvent_t a0 = nullptr, a1 = nullptr, b0 = nullptr, b1 = nullptr;
-  int rc = SS_OK;
-  auto ck = [&](hipError_t e) {
-    if (e != hipSuccess && rc == SS_OK) {
-      ctx->stats.last_hip_error = (int32_t)e;
-      ss_note_hip_error((int)e, __FILE__, 0);
-      (void)hipGetLastError();
-      rc = SS_E_HIP;
-    }
-    return e == hipSuccess;
-  };
-  ck(hipHostMalloc((void **)&h0, bytes, hipHostMallocMapped));
-  ck(hipHostMalloc((void **)&h1, bytes, hipHostMallocMapped));
-  ck(hipMalloc((void **)&d0, bytes));
-  ck(hipMalloc((void **)&d1, bytes));
-  ck(hipMalloc((void **)&dd, 2 * sizeof(ss_desc_t)));
-  ck(hipMalloc((void **)&dc, 4 * sizeof(uint32_t)));
-  ck(hipMalloc((void **)&dm, ((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES) * sizeof(uint32_t)));
-  ck(hipEventCreate(&a0)); ck(hipEventCreate(&a1)); ck(hipEventCreate(&b0)); ck(hipEventCreate(&b1));
-  if (rc == SS_OK) {
-    ck(hipHostGetDevicePointer((void **)&h0d, h0, 0));
-    ck(hipHostGetDevicePointer((void **)&h1d, h1, 0));
-    std::memset(h0, 1, bytes);
-    std::memset(h1, 2, bytes);
-    ck(hipMemset(d0, 3, bytes));
-    ck(hipMemset(d1, 4, bytes));
-    ss_desc_t hd[2] = {{0, 0, bytes, 0, 0}, {0, 0, bytes, 1, 0}};
-    uint32_t hc[2] = {0, (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES)};
-    ck(hipMemcpy(dd, hd, sizeof(hd), hipMemcpyHostToDevice));
-    ck(hipMemcpy(dc, hc, sizeof(hc), hipMemcpyHostToDevice));
-    ck(hipMemset(dm, 0, ((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES) * sizeof(uint32_t)));   // every chunk: descriptor 0
-    ck(hipDeviceSynchronize());
-  }
-  auto median = [](std::vector<float> &v) {
-    std::sort(v.begin(), v.end());
-    return v[v.size() / 2];
-  };
-  auto gbps = [&](float ms) { return ms > 0 ? (double)bytes / (ms * 1e-3) / 1e9 : 0.0; };
-  const uint32_t wg = ctx->cfg.copy_workgroups, wgo = ctx->cfg.copy_workgroups_out;
-  const uint32_t nchunks = (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
-  // mode 0: D2H engine, 1: H2D engine, 2: both engine, 3: D2H kernel, 4: H2D kernel, 5: both kernel
-  for (int mode = 0; mode < 6 && rc == SS_OK; ++mode) {
-    std::vector<float> ta, tb;
-    for (uint32_t r = 0; r < reps + 2 && rc == SS_OK; ++r) {
-      const bool d2h = (mode == 0 || mode == 2 || mode == 3 || mode == 5);
-      const bool h2d = (mode == 1 || mode == 2 || mode == 4 || mode == 5);
-      if (d2h) {
-        ck(hipEventRecord(a0, ctx->s_out));
-        if (mode == 3 || mode == 5) {
-          ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
-          ck(hipGetLastError());
-        } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
-        ck(hipEventRecord(a1, ctx->s_out));
+  return ss_guard([&]() -> int {
+    if (!ctx || !out || bytes < 4096 || reps == 0 || reps > 1000) return SS_E_INVAL;
+    bytes &= ~(uint64_t)255;
+    std::memset(out, 0, sizeof(*out));
+    uint8_t *h0 = nullptr, *h1 = nullptr, *d0 = nullptr, *d1 = nullptr, *h0d = nullptr, *h1d = nullptr;
+    ss_desc_t *dd = nullptr;
+    uint32_t *dc = nullptr, *dm = nullptr;
+    hipEvent_t a0 = nullptr, a1 = nullptr, b0 = nullptr, b1 = nullptr;
+    int rc = SS_OK;
+    auto ck = [&](hipError_t e) {
+      if (e != hipSuccess && rc == SS_OK) {
+        ctx->stats.last_hip_error = (int32_t)e;
+        ss_note_hip_error((int)e, __FILE__, 0);
+        (void)hipGetLastError();
+        rc = SS_E_HIP;
       }
-      if (h2d) {
-        ck(hipEventRecord(b0, ctx->s_in));
-        if (mode == 4 || mode == 5) {
-          ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
-          ck(hipGetLastError());
-        } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
-        ck(hipEventRecord(b1, ctx->s_in));
+      return e == hipSuccess;
+    };
+    ck(hipHostMalloc((void **)&h0, bytes, hipHostMallocMapped));
+    ck(hipHostMalloc((void **)&h1, bytes, hipHostMallocMapped));
+    ck(hipMalloc((void **)&d0, bytes));
+    ck(hipMalloc((void **)&d1, bytes));
+    ck(hipMalloc((void **)&dd, 2 * sizeof(ss_desc_t)));
+    ck(hipMalloc((void **)&dc, 4 * sizeof(uint32_t)));
+    ck(hipMalloc((void **)&dm, ((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES) * sizeof(uint32_t)));
+    ck(hipEventCreate(&a0)); ck(hipEventCreate(&a1)); ck(hipEventCreate(&b0)); ck(hipEventCreate(&b1));
+    if (rc == SS_OK) {
+      ck(hipHostGetDevicePointer((void **)&h0d, h0, 0));
+      ck(hipHostGetDevicePointer((void **)&h1d, h1, 0));
+      std::memset(h0, 1, bytes);
+      std::memset(h1, 2, bytes);
+      ck(hipMemset(d0, 3, bytes));
+      ck(hipMemset(d1, 4, bytes));
+      ss_desc_t hd[2] = {{0, 0, bytes, 0, 0}, {0, 0, bytes, 1, 0}};
+      uint32_t hc[2] = {0, (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES)};
+      ck(hipMemcpy(dd, hd, sizeof(hd), hipMemcpyHostToDevice));
+      ck(hipMemcpy(dc, hc, sizeof(hc), hipMemcpyHostToDevice));
+      ck(hipMemset(dm, 0, ((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES) * sizeof(uint32_t)));   // every chunk: descriptor 0
+      ck(hipDeviceSynchronize());
+    }
+    auto median = [](std::vector<float> &v) {
+      std::sort(v.begin(), v.end());
+      return v[v.size() / 2];
+    };
+    auto gbps = [&](float ms) { return ms > 0 ? (double)bytes / (ms * 1e-3) / 1e9 : 0.0; };
+    const uint32_t wg = ctx->cfg.copy_workgroups, wgo = ctx->cfg.copy_workgroups_out;
+    const uint32_t nchunks = (uint32_t)((bytes + SS_CHUNK_BYTES - 1) / SS_CHUNK_BYTES);
+    // mode 0: D2H engine, 1: H2D engine, 2: both engine, 3: D2H kernel, 4: H2D kernel, 5: both kernel
+    for (int mode = 0; mode < 6 && rc == SS_OK; ++mode) {
+      std::vector<float> ta, tb;
+      for (uint32_t r = 0; r < reps + 2 && rc == SS_OK; ++r) {
+        const bool d2h = (mode == 0 || mode == 2 || mode == 3 || mode == 5);
+        const bool h2d = (mode == 1 || mode == 2 || mode == 4 || mode == 5);
+        if (d2h) {
+          ck(hipEventRecord(a0, ctx->s_out));
+          if (mode == 3 || mode == 5) {
+            ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
+            ck(hipGetLastError());
+          } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
+          ck(hipEventRecord(a1, ctx->s_out));
+        }
+        if (h2d) {
+          ck(hipEventRecord(b0, ctx->s_in));
+          if (mode == 4 || mode == 5) {
+            ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
+            ck(hipGetLastError());
+          } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
+          ck(hipEventRecord(b1, ctx->s_in));
+        }
+        ck(hipStreamSynchronize(ctx->s_out));
+        ck(hipStreamSynchronize(ctx->s_in));
+        float ms;
+        if (d2h && ck(hipEventElapsedTime(&ms, a0, a1)) && r >= 2) ta.push_back(ms);
+        if (h2d && ck(hipEventElapsedTime(&ms, b0, b1)) && r >= 2) tb.push_back(ms);
       }
-      ck(hipStreamSynchronize(ctx->s_out));
-      ck(hipStreamSynchronize(ctx->s_in));
-      float ms;
-      if (d2h && ck(hipEventElapsedTime(&ms, a0, a1)) && r >= 2) ta.push_back(ms);
-      if (h2d && ck(hipEventElapsedTime(&ms, b0, b1)) && r >= 2) tb.push_back(ms);
+      if (rc != SS_OK) break;
+      switch (mode) {
+        case 0: out->d2h_gbps = gbps(median(ta)); break;
+        case 1: out->h2d_gbps = gbps(median(tb)); break;
+        case 2: out->bidir_d2h_gbps = gbps(median(ta)); out->bidir_h2d_gbps = gbps(median(tb)); break;
+        case 3: out->kernel_d2h_gbps = gbps(median(ta)); break;
+        case 4: out->kernel_h2d_gbps = gbps(median(tb)); break;
+        case 5: out->kernel_bidir_d2h_gbps = gbps(median(ta)); out->kernel_bidir_h2d_gbps = gbps(median(tb)); break;
+      }
     }
-    if (rc != SS_OK) break;
-    switch (mode) {
-      case 0: out->d2h_gbps = gbps(median(ta)); break;
-      case 1: out->h2d_gbps = gbps(median(tb)); break;
-      case 2: out->bidir_d2h_gbps = gbps(median(ta)); out->bidir_h2d_gbps = gbps(median(tb)); break;
-      case 3: out->kernel_d2h_gbps = gbps(median(ta)); break;
-      case 4: out->kernel_h2d_gbps = gbps(median(tb)); break;
-      case 5: out->kernel_bidir_d2h_gbps = gbps(median(ta)); out->kernel_bidir_h2d_gbps = gbps(median(tb)); break;
-    }
-  }
-  if (a0) (void)hipEventDestroy(a0);
-  if (a1) (void)hipEventDestroy(a1);
-  if (b0) (void)hipEventDestroy(b0);
-  if (b1) (void)hipEventDestroy(b1);
-  if (dd) (void)hipFree(dd);
-  if (dc) (void)hipFree(dc);
-  if (dm) (void)hipFree(dm);
-  if (d0) (void)hipFree(d0);
-  if (d1) (void)hipFree(d1);
-  if (h0) (void)hipHostFree(h0);
-  if (h1) (void)hipHostFree(h1);
-  return rc;
+    if (a0) (void)hipEventDestroy(a0);
+    if (a1) (void)hipEventDestroy(a1);
+    if (b0) (void)hipEventDestroy(b0);
+    if (b1) (void)hipEventDestroy(b1);
+    if (dd) (void)hipFree(dd);
+    if (dc) (void)hipFree(dc);
+    if (dm) (void)hipFree(dm);
+    if (d0) (void)hipFree(d0);
+    if (d1) (void)hipFree(d1);
+    if (h0) (void)hipHostFree(h0);
+    if (h1) (void)hipHostFree(h1);
+    return rc;
+  });
 }

@@ -322,120 +322,124 @@ __global__ __launch_bounds__(kThreads) void ss_scan_batch_kernel(const ScanArgs 
 extern "C" int ss_timeline_scan_batch(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev, const ss_event_t *pev,
                                       const uint64_t *pe_start, uint32_t k, uint32_t n_ops, int64_t base,
                                       int64_t budget, int64_t *per_op, ss_scan_result_t *res) {
-  if (!ctx || (k && (!res || !pe_start)) || (n_ev && !ev)) return SS_E_INVAL;
-  if (k == 0) return SS_OK;
-  if (k > 4096 || n_ops > (1u << 23)) return SS_E_INVAL;
-  const uint64_t n_pe = pe_start[k];
-  for (uint32_t c = 0; c < k; ++c)
-    if (pe_start[c] > pe_start[c + 1]) return SS_E_INVAL;
-  if (pe_start[0] != 0 || (n_pe && !pev) || n_ev + n_pe >= (1ull << 31)) return SS_E_INVAL;
-  const uint64_t n = n_ops;
-  size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += ss_align_up(bytes, 256); return o; };
-  const size_t o_ev = take(n_ev * sizeof(ss_event_t)), o_pev = take(n_pe * sizeof(ss_event_t));
-  const size_t o_args = take((size_t)k * sizeof(ScanArgs)), o_res = take((size_t)k * sizeof(ss_scan_result_t));
-  const size_t o_flags = take((size_t)k * 4);
-  const size_t per_scan = ss_align_up(4 * n * 8, 256) + 3 * ss_align_up(n * 8, 256) + ss_align_up(4 * n * 4, 256) +
-                          ss_align_up(n * 4, 256);
-  const size_t o_work = take((size_t)k * per_scan);
-  const size_t host_bytes = (size_t)k * (sizeof(ScanArgs) + sizeof(ss_scan_result_t) + 4) + 1024;
-  int rc = ss_scratch_reserve(ctx, off, host_bytes);
-  if (rc != SS_OK) return rc;
-  uint8_t *d = (uint8_t *)ctx->d_scratch, *h = (uint8_t *)ctx->h_scratch;
-  hipStream_t s = ctx->s_aux;
-  if (n_ev) SS_HIP(hipMemcpyAsync(d + o_ev, ev, n_ev * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
-  if (n_pe) SS_HIP(hipMemcpyAsync(d + o_pev, pev, n_pe * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
-  ScanArgs *ha = (ScanArgs *)h;                       // pinned: argument blocks, then results and flags
-  for (uint32_t c = 0; c < k; ++c) {
-    uint8_t *w = d + o_work + (size_t)c * per_scan;
-    size_t wo = 0;
-    auto wtake = [&](size_t bytes) { uint8_t *p = w + wo; wo += ss_align_up(bytes, 256); return p; };
-    ScanArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.ev = (const ss_event_t *)(d + o_ev); a.n_ev = n_ev;
-    a.pev = (const ss_event_t *)(d + o_pev) + pe_start[c]; a.n_pe = pe_start[c + 1] - pe_start[c];
-    a.n_ops = n_ops; a.want_timeline = 0;
-    a.base = base; a.budget = budget;
-    a.csum = (int64_t *)wtake(4 * n * 8);
-    a.before = (int64_t *)wtake(n * 8);
-    a.per_op = (int64_t *)wtake(n * 8);
-    a.mre = (int64_t *)wtake(n * 8);
-    a.ccnt = (uint32_t *)wtake(4 * n * 4);
-    a.evstart = (uint32_t *)wtake(n * 4);
-    a.res = (ss_scan_result_t *)(d + o_res) + c;
-    a.flags = (uint32_t *)(d + o_flags) + c;
-    ha[c] = a;
-  }
-  SS_HIP(hipMemcpyAsync(d + o_args, ha, (size_t)k * sizeof(ScanArgs), hipMemcpyHostToDevice, s));
-  hipLaunchKernelGGL(ss_scan_batch_kernel, dim3(k), dim3(kThreads), 0, s, (const ScanArgs *)(d + o_args));
-  SS_HIP(hipGetLastError());
-  uint8_t *hres = h + ss_align_up((size_t)k * sizeof(ScanArgs), 256);
-  uint8_t *hflags = hres + (size_t)k * sizeof(ss_scan_result_t);
-  SS_HIP(hipMemcpyAsync(hres, d + o_res, (size_t)k * sizeof(ss_scan_result_t), hipMemcpyDeviceToHost, s));
-  SS_HIP(hipMemcpyAsync(hflags, d + o_flags, (size_t)k * 4, hipMemcpyDeviceToHost, s));
-  SS_HIP(hipStreamSynchronize(s));
-  for (uint32_t c = 0; c < k; ++c) {
-    uint32_t fl;
-    std::memcpy(&fl, hflags + 4 * (size_t)c, 4);
-    if (fl & 1u) return SS_E_INVAL;
-  }
-  std::memcpy(res, hres, (size_t)k * sizeof(ss_scan_result_t));
-  if (per_op && n) {
+  return ss_guard([&]() -> int {
+    if (!ctx || (k && (!res || !pe_start)) || (n_ev && !ev)) return SS_E_INVAL;
+    if (k == 0) return SS_OK;
+    if (k > 4096 || n_ops > (1u << 23)) return SS_E_INVAL;
+    const uint64_t n_pe = pe_start[k];
     for (uint32_t c = 0; c < k; ++c)
-      SS_HIP(hipMemcpyAsync(per_op + (size_t)c * n, ha[c].per_op, n * 8, hipMemcpyDeviceToHost, s));
+      if (pe_start[c] > pe_start[c + 1]) return SS_E_INVAL;
+    if (pe_start[0] != 0 || (n_pe && !pev) || n_ev + n_pe >= (1ull << 31)) return SS_E_INVAL;
+    const uint64_t n = n_ops;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += ss_align_up(bytes, 256); return o; };
+    const size_t o_ev = take(n_ev * sizeof(ss_event_t)), o_pev = take(n_pe * sizeof(ss_event_t));
+    const size_t o_args = take((size_t)k * sizeof(ScanArgs)), o_res = take((size_t)k * sizeof(ss_scan_result_t));
+    const size_t o_flags = take((size_t)k * 4);
+    const size_t per_scan = ss_align_up(4 * n * 8, 256) + 3 * ss_align_up(n * 8, 256) + ss_align_up(4 * n * 4, 256) +
+                            ss_align_up(n * 4, 256);
+    const size_t o_work = take((size_t)k * per_scan);
+    const size_t host_bytes = (size_t)k * (sizeof(ScanArgs) + sizeof(ss_scan_result_t) + 4) + 1024;
+    int rc = ss_scratch_reserve(ctx, off, host_bytes);
+    if (rc != SS_OK) return rc;
+    uint8_t *d = (uint8_t *)ctx->d_scratch, *h = (uint8_t *)ctx->h_scratch;
+    hipStream_t s = ctx->s_aux;
+    if (n_ev) SS_HIP(hipMemcpyAsync(d + o_ev, ev, n_ev * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
+    if (n_pe) SS_HIP(hipMemcpyAsync(d + o_pev, pev, n_pe * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
+    ScanArgs *ha = (ScanArgs *)h;                       // pinned: argument blocks, then results and flags
+    for (uint32_t c = 0; c < k; ++c) {
+      uint8_t *w = d + o_work + (size_t)c * per_scan;
+      size_t wo = 0;
+      auto wtake = [&](size_t bytes) { uint8_t *p = w + wo; wo += ss_align_up(bytes, 256); return p; };
+      ScanArgs a;
+      std::memset(&a, 0, sizeof(a));
+      a.ev = (const ss_event_t *)(d + o_ev); a.n_ev = n_ev;
+      a.pev = (const ss_event_t *)(d + o_pev) + pe_start[c]; a.n_pe = pe_start[c + 1] - pe_start[c];
+      a.n_ops = n_ops; a.want_timeline = 0;
+      a.base = base; a.budget = budget;
+      a.csum = (int64_t *)wtake(4 * n * 8);
+      a.before = (int64_t *)wtake(n * 8);
+      a.per_op = (int64_t *)wtake(n * 8);
+      a.mre = (int64_t *)wtake(n * 8);
+      a.ccnt = (uint32_t *)wtake(4 * n * 4);
+      a.evstart = (uint32_t *)wtake(n * 4);
+      a.res = (ss_scan_result_t *)(d + o_res) + c;
+      a.flags = (uint32_t *)(d + o_flags) + c;
+      ha[c] = a;
+    }
+    SS_HIP(hipMemcpyAsync(d + o_args, ha, (size_t)k * sizeof(ScanArgs), hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(ss_scan_batch_kernel, dim3(k), dim3(kThreads), 0, s, (const ScanArgs *)(d + o_args));
+    SS_HIP(hipGetLastError());
+    uint8_t *hres = h + ss_align_up((size_t)k * sizeof(ScanArgs), 256);
+    uint8_t *hflags = hres + (size_t)k * sizeof(ss_scan_result_t);
+    SS_HIP(hipMemcpyAsync(hres, d + o_res, (size_t)k * sizeof(ss_scan_result_t), hipMemcpyDeviceToHost, s));
+    SS_HIP(hipMemcpyAsync(hflags, d + o_flags, (size_t)k * 4, hipMemcpyDeviceToHost, s));
     SS_HIP(hipStreamSynchronize(s));
-  }
-  return SS_OK;
+    for (uint32_t c = 0; c < k; ++c) {
+      uint32_t fl;
+      std::memcpy(&fl, hflags + 4 * (size_t)c, 4);
+      if (fl & 1u) return SS_E_INVAL;
+    }
+    std::memcpy(res, hres, (size_t)k * sizeof(ss_scan_result_t));
+    if (per_op && n) {
+      for (uint32_t c = 0; c < k; ++c)
+        SS_HIP(hipMemcpyAsync(per_op + (size_t)c * n, ha[c].per_op, n * 8, hipMemcpyDeviceToHost, s));
+      SS_HIP(hipStreamSynchronize(s));
+    }
+    return SS_OK;
+  });
 }
 
 extern "C" int ss_timeline_scan(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev, const ss_event_t *pev,
                                 uint64_t n_pe, uint32_t n_ops, int64_t base, int64_t budget,
                                 int64_t *timeline, int64_t *per_op, int64_t *mre, ss_scan_result_t *res) {
-  if (!ctx || !res || (n_ev && !ev) || (n_pe && !pev)) return SS_E_INVAL;
-  if (n_ops > (1u << 23) || n_ev + n_pe >= (1ull << 31)) return SS_E_INVAL;
-  const uint64_t E = n_ev + n_pe;
-  const uint64_t n = n_ops;
-  // device layout (8-byte aligned pieces first)
-  size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += ss_align_up(bytes, 256); return o; };
-  const size_t o_ev = take(n_ev * sizeof(ss_event_t)), o_pev = take(n_pe * sizeof(ss_event_t));
-  const size_t o_csum = take(4 * n * 8), o_before = take(n * 8), o_segsum = take(4 * n * 8);
-  const size_t o_sumx = take(E * 8), o_perop = take(n * 8), o_mre = take(n * 8), o_tl = take(E * 8);
-  const size_t o_ccnt = take(4 * n * 4), o_evstart = take(n * 4), o_segcnt = take(4 * n * 4);
-  const size_t o_cntx = take(E * 4), o_res = take(sizeof(ss_scan_result_t)), o_flags = take(4);
-  int rc = ss_scratch_reserve(ctx, off, 512);
-  if (rc != SS_OK) return rc;
-  uint8_t *d = (uint8_t *)ctx->d_scratch;
-  hipStream_t s = ctx->s_aux;
-  if (n_ev) SS_HIP(hipMemcpyAsync(d + o_ev, ev, n_ev * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
-  if (n_pe) SS_HIP(hipMemcpyAsync(d + o_pev, pev, n_pe * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
-  ScanArgs a;
-  a.ev = (const ss_event_t *)(d + o_ev); a.n_ev = n_ev;
-  a.pev = (const ss_event_t *)(d + o_pev); a.n_pe = n_pe;
-  a.n_ops = n_ops; a.want_timeline = timeline != nullptr;
-  a.base = base; a.budget = budget;
-  a.csum = (int64_t *)(d + o_csum); a.ccnt = (uint32_t *)(d + o_ccnt);
-  a.before = (int64_t *)(d + o_before); a.evstart = (uint32_t *)(d + o_evstart);
-  a.segsum = (int64_t *)(d + o_segsum); a.segcnt = (uint32_t *)(d + o_segcnt);
-  a.sumx = (int64_t *)(d + o_sumx); a.cntx = (uint32_t *)(d + o_cntx);
-  a.per_op = (int64_t *)(d + o_perop); a.mre = (int64_t *)(d + o_mre);
-  a.timeline = (int64_t *)(d + o_tl);
-  a.res = (ss_scan_result_t *)(d + o_res); a.flags = (uint32_t *)(d + o_flags);
-  hipLaunchKernelGGL(ss_scan_kernel, dim3(1), dim3(kThreads), 0, s, a);
-  SS_HIP(hipGetLastError());
-  uint8_t *h = (uint8_t *)ctx->h_scratch;            // pinned: result + flags
-  SS_HIP(hipMemcpyAsync(h, d + o_res, sizeof(ss_scan_result_t), hipMemcpyDeviceToHost, s));
-  SS_HIP(hipMemcpyAsync(h + 256, d + o_flags, 4, hipMemcpyDeviceToHost, s));
-  SS_HIP(hipStreamSynchronize(s));
-  uint32_t flags;
-  std::memcpy(&flags, h + 256, 4);
-  if (flags & 1u) return SS_E_INVAL;
-  std::memcpy(res, h, sizeof(*res));
-  if (per_op && n) SS_HIP(hipMemcpyAsync(per_op, d + o_perop, n * 8, hipMemcpyDeviceToHost, s));
-  if (mre && n) SS_HIP(hipMemcpyAsync(mre, d + o_mre, n * 8, hipMemcpyDeviceToHost, s));
-  const bool tl_ok = timeline && !(flags & 2u);
-  if (tl_ok && E) SS_HIP(hipMemcpyAsync(timeline, d + o_tl, E * 8, hipMemcpyDeviceToHost, s));
-  SS_HIP(hipStreamSynchronize(s));
-  if (timeline && !tl_ok) return SS_E_ORDER;
-  return SS_OK;
+  return ss_guard([&]() -> int {
+    if (!ctx || !res || (n_ev && !ev) || (n_pe && !pev)) return SS_E_INVAL;
+    if (n_ops > (1u << 23) || n_ev + n_pe >= (1ull << 31)) return SS_E_INVAL;
+    const uint64_t E = n_ev + n_pe;
+    const uint64_t n = n_ops;
+    // device layout (8-byte aligned pieces first)
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += ss_align_up(bytes, 256); return o; };
+    const size_t o_ev = take(n_ev * sizeof(ss_event_t)), o_pev = take(n_pe * sizeof(ss_event_t));
+    const size_t o_csum = take(4 * n * 8), o_before = take(n * 8), o_segsum = take(4 * n * 8);
+    const size_t o_sumx = take(E * 8), o_perop = take(n * 8), o_mre = take(n * 8), o_tl = take(E * 8);
+    const size_t o_ccnt = take(4 * n * 4), o_evstart = take(n * 4), o_segcnt = take(4 * n * 4);
+    const size_t o_cntx = take(E * 4), o_res = take(sizeof(ss_scan_result_t)), o_flags = take(4);
+    int rc = ss_scratch_reserve(ctx, off, 512);
+    if (rc != SS_OK) return rc;
+    uint8_t *d = (uint8_t *)ctx->d_scratch;
+    hipStream_t s = ctx->s_aux;
+    if (n_ev) SS_HIP(hipMemcpyAsync(d + o_ev, ev, n_ev * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
+    if (n_pe) SS_HIP(hipMemcpyAsync(d + o_pev, pev, n_pe * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
+    ScanArgs a;
+    a.ev = (const ss_event_t *)(d + o_ev); a.n_ev = n_ev;
+    a.pev = (const ss_event_t *)(d + o_pev); a.n_pe = n_pe;
+    a.n_ops = n_ops; a.want_timeline = timeline != nullptr;
+    a.base = base; a.budget = budget;
+    a.csum = (int64_t *)(d + o_csum); a.ccnt = (uint32_t *)(d + o_ccnt);
+    a.before = (int64_t *)(d + o_before); a.evstart = (uint32_t *)(d + o_evstart);
+    a.segsum = (int64_t *)(d + o_segsum); a.segcnt = (uint32_t *)(d + o_segcnt);
+    a.sumx = (int64_t *)(d + o_sumx); a.cntx = (uint32_t *)(d + o_cntx);
+    a.per_op = (int64_t *)(d + o_perop); a.mre = (int64_t *)(d + o_mre);
+    a.timeline = (int64_t *)(d + o_tl);
+    a.res = (ss_scan_result_t *)(d + o_res); a.flags = (uint32_t *)(d + o_flags);
+    hipLaunchKernelGGL(ss_scan_kernel, dim3(1), dim3(kThreads), 0, s, a);
+    SS_HIP(hipGetLastError());
+    uint8_t *h = (uint8_t *)ctx->h_scratch;            // pinned: result + flags
+    SS_HIP(hipMemcpyAsync(h, d + o_res, sizeof(ss_scan_result_t), hipMemcpyDeviceToHost, s));
+    SS_HIP(hipMemcpyAsync(h + 256, d + o_flags, 4, hipMemcpyDeviceToHost, s));
+    SS_HIP(hipStreamSynchronize(s));
+    uint32_t flags;
+    std::memcpy(&flags, h + 256, 4);
+    if (flags & 1u) return SS_E_INVAL;
+    std::memcpy(res, h, sizeof(*res));
+    if (per_op && n) SS_HIP(hipMemcpyAsync(per_op, d + o_perop, n * 8, hipMemcpyDeviceToHost, s));
+    if (mre && n) SS_HIP(hipMemcpyAsync(mre, d + o_mre, n * 8, hipMemcpyDeviceToHost, s));
+    const bool tl_ok = timeline && !(flags & 2u);
+    if (tl_ok && E) SS_HIP(hipMemcpyAsync(timeline, d + o_tl, E * 8, hipMemcpyDeviceToHost, s));
+    SS_HIP(hipStreamSynchronize(s));
+    if (timeline && !tl_ok) return SS_E_ORDER;
+    return SS_OK;
+  });
 }

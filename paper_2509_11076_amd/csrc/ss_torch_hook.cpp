@@ -15,6 +15,7 @@
 #include <cstring>
 #include <map>
 #include <mutex>
+#include <new>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -242,25 +243,43 @@ void register_callback(int mode) {
   g.have_cb = true;
 }
 
+// PyTorch reports failures by C++ exceptions (c10::Error); none may cross the C boundary
+template <class Body>
+int guarded(Body &&body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    return SS_E_NOMEM;
+  } catch (...) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.st.errors++;
+    return SS_E_STATE;
+  }
+}
+
 }  // namespace
 
 extern "C" int ss_hook_install(ss_ctx *ctx, int mode) {
   if (!ctx || mode < SS_HOOK_OFF || mode > SS_HOOK_DETAILED) return SS_E_INVAL;
-  {
-    std::lock_guard<std::mutex> lock(g.mu);
-    if (g.ctx != ctx) g.by_name.clear();       // tokens are per context
-    g.ctx = ctx;
-  }
-  register_callback(mode);
-  g.mode.store(mode);
-  return SS_OK;
+  return guarded([&]() -> int {
+    {
+      std::lock_guard<std::mutex> lock(g.mu);
+      if (g.ctx != ctx) g.by_name.clear();       // tokens are per context
+      g.ctx = ctx;
+    }
+    register_callback(mode);
+    g.mode.store(mode);
+    return SS_OK;
+  });
 }
 
 extern "C" int ss_hook_set_mode(int mode) {
   if (mode < SS_HOOK_OFF || mode > SS_HOOK_DETAILED) return SS_E_INVAL;
-  if (mode != g.mode.load()) register_callback(mode);
-  g.mode.store(mode);
-  return SS_OK;
+  return guarded([&]() -> int {
+    if (mode != g.mode.load()) register_callback(mode);
+    g.mode.store(mode);
+    return SS_OK;
+  });
 }
 
 extern "C" int ss_hook_set_phase(uint32_t phase) {
@@ -282,13 +301,15 @@ extern "C" int ss_hook_begin_iteration(void) {
 }
 
 extern "C" int ss_hook_remove(void) {
-  g.mode.store(SS_HOOK_OFF);
-  register_callback(SS_HOOK_OFF);
-  std::lock_guard<std::mutex> lock(g.mu);
-  g.ctx = nullptr;
-  g.by_name.clear();
-  g.live.clear();
-  return SS_OK;
+  return guarded([&]() -> int {
+    g.mode.store(SS_HOOK_OFF);
+    register_callback(SS_HOOK_OFF);
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.ctx = nullptr;
+    g.by_name.clear();
+    g.live.clear();
+    return SS_OK;
+  });
 }
 
 extern "C" int ss_hook_tensor_table(ss_tensor_t *out, uint32_t *n) {

@@ -19,29 +19,31 @@ static uint32_t fnv1a_32(const char *s) {
 
 extern "C" int ss_intern_op(ss_ctx *ctx, const char *name, const char *stack, uint32_t dtype, uint32_t n_out,
                             uint32_t phase, ss_op_t *out) {
-  if (!ctx || !name || !stack || !out || dtype > 0xFF || phase > 0xFFFF) return SS_E_INVAL;
-  auto it = ctx->tokens.find(name);
-  uint32_t tok;
-  if (it == ctx->tokens.end()) {
-    tok = (uint32_t)ctx->tokens.size() + 1;       // 0 stays the padding token
-    if (tok >= (1u << 18)) return SS_E_CAPACITY;  // keeps the cosine sums inside 64 bits
-    ctx->tokens.emplace(name, tok);
-  } else {
-    tok = it->second;
-  }
-  auto st = ctx->stacks.find(stack);
-  uint32_t h;
-  if (st == ctx->stacks.end()) {
-    h = fnv1a_32(stack);
-    ctx->stacks.emplace(stack, h);
-  } else {
-    h = st->second;
-  }
-  out->op_token = tok;
-  out->stack_hash = h;
-  out->sig = (dtype & 0xFFu) | ((n_out & 0xFFu) << 8) | (phase << 16);
-  out->n_out = n_out;
-  return SS_OK;
+  return ss_guard([&]() -> int {
+    if (!ctx || !name || !stack || !out || dtype > 0xFF || phase > 0xFFFF) return SS_E_INVAL;
+    auto it = ctx->tokens.find(name);
+    uint32_t tok;
+    if (it == ctx->tokens.end()) {
+      tok = (uint32_t)ctx->tokens.size() + 1;       // 0 stays the padding token
+      if (tok >= (1u << 18)) return SS_E_CAPACITY;  // keeps the cosine sums inside 64 bits
+      ctx->tokens.emplace(name, tok);
+    } else {
+      tok = it->second;
+    }
+    auto st = ctx->stacks.find(stack);
+    uint32_t h;
+    if (st == ctx->stacks.end()) {
+      h = fnv1a_32(stack);
+      ctx->stacks.emplace(stack, h);
+    } else {
+      h = st->second;
+    }
+    out->op_token = tok;
+    out->stack_hash = h;
+    out->sig = (dtype & 0xFFu) | ((n_out & 0xFFu) << 8) | (phase << 16);
+    out->n_out = n_out;
+    return SS_OK;
+  });
 }
 
 extern "C" int ss_trace_begin(ss_ctx *ctx) {
