@@ -72,17 +72,18 @@ def test_hand_worked_generation():
     assert [L[3] for L in info["layers"]] == [50, 200, 300, 300, 300, 200, 50, 300]
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_feasibility_and_peak_against_brute_force(seed):
     """one operator per layer and an instantaneous link: the generator succeeds exactly when swapping
     everything fits, and the memory the timeline scan sees under its policy is within the limit"""
     tab, ev = tiny_trace(seed, n_ops=16, T=9)
     n_ops = 16
     phases = [0] * 8 + [1] * 8
-    for i in range(len(tab)):       # keep uses inside their phases
+    for i in range(len(tab)):       # keep uses inside their phases, and the tensor alive at its uses
         tab["last_fwd_use"][i] = min(int(tab["last_fwd_use"][i]), 7)
         tab["first_bwd_use"][i] = max(int(tab["first_bwd_use"][i]), 8)
         tab["free_op"][i] = max(int(tab["free_op"][i]), int(tab["first_bwd_use"][i]))
+        tab["alloc_op"][i] = tab["producer_op"][i] = min(int(tab["alloc_op"][i]), int(tab["last_fwd_use"][i]))
     mem = live_set_peak(tab, {}, n_ops, 0)
 
     def window(i):                  # best case: away strictly between lf + 1 and fb - 1

@@ -178,7 +178,7 @@ def test_unmatched_and_short_lived_items_are_dropped_and_counted():
     assert all(r[3] & oracle.F_ORDER for r in ap["resolved"])
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_greedy_on_tiny_traces_against_brute_force(seed):
     tab, ev = tiny_trace(seed, n_ops=14, T=8)
     n_ops, base = 14, 0
@@ -186,29 +186,43 @@ def test_greedy_on_tiny_traces_against_brute_force(seed):
     # reachable floor: swap everything that can be swapped
     cands = [i for i in range(len(tab)) if tab["last_fwd_use"][i] + 1 < tab["first_bwd_use"][i]]
 
-    def peak_of(sub):
-        away = {i: (int(tab["last_fwd_use"][i]) + 1, int(tab["first_bwd_use"][i]) - 1) for i in sub}
+    def peak_of(sub, t_in_at_use=False):
+        # instantaneous link: released after the operator following the last forward use, back one
+        # operator before the first backward use (or, at the latest, at that use itself)
+        away = {i: (int(tab["last_fwd_use"][i]) + 1, int(tab["first_bwd_use"][i]) - (0 if t_in_at_use else 1)) for i in sub}
         return int(live_set_peak(tab, away, n_ops, base).max())
 
-    floor = min(peak_of(sub) for r in range(len(cands) + 1) for sub in itertools.combinations(cands, r))
+    subsets = [sub for r in range(len(cands) + 1) for sub in itertools.combinations(cands, r)]
+    floor = min(peak_of(sub) for sub in subsets)
     budget = (floor + no["peak"]) // 2
     rows, ap = oracle.greedy_policy(tab, ev, n_ops, base, budget, INSTANT)
     chosen = [r[2] for r in rows]
     res = oracle.timeline_scan(ev, ap["policy_events"], n_ops, base, budget)
-    # the scan's verdict on the chosen set is the brute-force (live-set) peak of that set
-    assert res["peak"] == peak_of(chosen) <= budget
+    # the scan's verdict on the chosen set is the brute-force (live-set) peak of that set at the points
+    # the schedule gives its items (a swap-in held back behind the last swap-out comes later than fb - 1)
+    points = {r[2]: (r[5], r[6]) for r in ap["resolved"]}
+    assert res["peak"] == int(live_set_peak(tab, points, n_ops, base).max()) <= budget
+    assert all(points[i][0] == tab["last_fwd_use"][i] + 1 and
+               tab["first_bwd_use"][i] - 1 <= points[i][1] <= tab["first_bwd_use"][i] for i in chosen)
     # greedy stops at the first prefix that fits: one item fewer does not fit
     if chosen:
-        assert peak_of(chosen[:-1]) > budget
+        # greedy_policy with rows already in force and no budget pressure just times those rows
+        _, ap1 = oracle.greedy_policy(tab, ev, n_ops, base, 1 << 60, INSTANT, initial=rows[:-1])
+        less = {r[2]: (r[5], r[6]) for r in ap1["resolved"]}
+        assert int(live_set_peak(tab, less, n_ops, base).max()) > budget
     # with an instantaneous link the peak never rises as items are added
-    peaks = [peak_of(chosen[:i]) for i in range(len(chosen) + 1)]
-    assert all(b <= a for a, b in zip(peaks, peaks[1:]))
+    peaks = []
+    for i in range(len(rows) + 1):
+        _, api = oracle.greedy_policy(tab, ev, n_ops, base, 1 << 60, INSTANT, initial=rows[:i])
+        peaks.append(int(live_set_peak(tab, {r[2]: (r[5], r[6]) for r in api["resolved"]}, n_ops, base).max()))
+    assert peaks[0] == no["peak"] and all(b <= a for a, b in zip(peaks, peaks[1:]))
     # order: longest idle span first
     idle = [int(tab["first_bwd_use"][i]) - int(tab["last_fwd_use"][i]) for i in chosen]
     assert idle == sorted(idle, reverse=True)
-    # below the reachable floor the generator must give up (Algo. 2, error branch)
+    # below what any timing of any subset can reach the generator must give up (Algo. 2, error branch)
+    unreachable = min(peak_of(sub, t_in_at_use=True) for sub in subsets) - 1
     with pytest.raises(oracle.Infeasible):
-        oracle.greedy_policy(tab, ev, n_ops, base, floor - 1, INSTANT)
+        oracle.greedy_policy(tab, ev, n_ops, base, unreachable, INSTANT)
 
 
 def test_greedy_brings_the_7b_shape_under_its_budget():
