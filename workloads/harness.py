@@ -310,7 +310,7 @@ class StagedRun:
         self.ctx = B.ss_create(self.cfg)
         self.stream = torch.cuda.current_stream()
         self.stage = self.WARMUP
-        self.prev = None            # (trace, ops, ms) of the previous iteration
+        self.prev = None            # (trace, ops, ms, forward ms, backward ms) of the previous iteration
         self.candidates = []        # dicts(policy, ref_ops, ms, info)
         self.best = None
         self.log = []
@@ -329,7 +329,7 @@ class StagedRun:
     def _generate(self):
         """a policy from the previous iteration's trace, Eq. 1 fed with its measured time"""
         B = self.B
-        tr, ops, ms = self.prev
+        tr, ops, ms, ms_fwd, ms_bwd = self.prev
         no = B.ss_timeline_scan(self.ctx, tr.events, None, tr.n_ops, 0, 1 << 62, want_per_op=False)
         limit = int(self.limit_frac * no["peak"])
         self.cfg.link_bytes_per_op = max(1, int(self.link * ms * 1e-3 / max(1, tr.n_ops)))
@@ -349,12 +349,29 @@ class StagedRun:
                 d["g_bwd"] = max(1, d["g_bwd"] // div)
                 d["c_num"] = d["c_num"] * c_mul
                 sets.append(d)
+        # Every other candidate applies Eq. 1 to the forward and the backward pass separately (their
+        # measured times): the operators of the two passes differ several times in length, which the
+        # even spread over the whole iteration ignores.  Which kind wins is decided by the measured
+        # step time in the Stable stage.
+        per_phase = len(self.candidates) % 2 == 1 and ms_fwd > 0 and ms_bwd > 0
+        if per_phase:
+            ph = np.asarray(tr.op_phase)
+            n_fwd, n_bwd = max(1, int((ph == 0).sum())), max(1, int((ph != 0).sum()))
+            f_bpo = max(1, int(self.link * ms_fwd * 1e-3 / n_fwd))
+            b_bpo = max(1, int(self.link * ms_bwd * 1e-3 / n_bwd))
+            tab = tr.tensors
+            both = (tab["first_bwd_use"] != NONE_OP) & (tab["last_fwd_use"] != NONE_OP)
+            biggest = int(tab["nbytes"][both].max()) if both.any() else 1
+            for d in sets:
+                d["phase_bytes_per_op"] = (f_bpo, b_bpo, b_bpo)
+                # a forward layer must still hold the largest candidate's transfer
+                d["g_fwd"] = max(1, min(d["g_fwd"], int(n_fwd * f_bpo // (3 * biggest // 2))))
         try:
             pol, info, chosen = B.ss_generate_policy_best(g, ops, tr.tensors, tr.events, 0, limit, sets)
         finally:
             B.ss_destroy(g)
         return dict(policy=pol, ref_ops=ops, ms=None, info=info, limit=limit, params=sets[chosen],
-                    link_bytes_per_op=cfg.link_bytes_per_op)
+                    link_bytes_per_op=cfg.link_bytes_per_op, per_phase=per_phase)
 
     def iteration(self, it):
         from .compute import SyntheticCompute
@@ -394,16 +411,25 @@ class StagedRun:
         comp.mark_swapped(swapped.keys())
         rec = B.ss_trace_record_prepared(self.ctx, ops, tr.events)
         lists = batch_lists(ap["actions"])
+        phases = list(tr.op_phase)
+        first_bwd = phases.index(1) if 1 in phases else -1
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(3)]    # start, first backward operator, end
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         B.ss_trace_begin(self.ctx)
+        marks[0].record()
 
         def run_op(i):
+            if i == first_bwd:
+                marks[1].record()
             rec(i)
             comp.run_op(i)
         run_iteration(self.ctx, tr.n_ops, ap["actions"], run_op, lists)
+        marks[2].record()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3
+        ms_fwd = marks[0].elapsed_time(marks[1]) if first_bwd >= 0 else 0.0
+        ms_bwd = marks[1].elapsed_time(marks[2]) if first_bwd >= 0 else 0.0
         if stage == self.GENPOLICY and cand is not None:
             cand["ms"] = ms
         cand_no = None if cand is None else [i for i, c in enumerate(self.candidates) if c is cand][0]
@@ -413,11 +439,11 @@ class StagedRun:
         if not v["similar"]:
             self.candidates, self.best = [], None
         self.stage = int(v["stage"])
-        self.prev = (tr, ops, ms)
+        self.prev = (tr, ops, ms, ms_fwd, ms_bwd)
         entry = dict(it=it, stage=stage, next_stage=self.stage, similar=bool(v["similar"]), ms=ms,
                      n_items=int(ap["n_kept"]), bytes=int(ap["bytes_out"]), unmatched=unmatched, peak=int(sc["peak"]),
                      arena_used=int(used),
-                     candidate=cand_no,
+                     candidate=cand_no, per_phase=None if cand is None else bool(cand.get("per_phase")),
                      result=comp.result())
         self.log.append(entry)
         return entry
