@@ -440,6 +440,52 @@ def test_apply_policy_keep_late_slow_link(P):
             P.ss_destroy(c)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_apply_policy_random_tiny_policies_links_and_options(P, seed):
+    """a random subset of a tiny random trace as policy (items without a match, a tensor claimed twice),
+    a random link share per direction, with and without keeping late items, with and without the
+    policy's own points: every output array equal to the oracle's, byte for byte"""
+    import torch
+    rng = SplitMix64(seed, 31)
+    tab, ev = tiny_trace(seed)
+    if seed % 2:                  # every other trace with all forward uses before all backward uses
+        for i in range(len(tab)):
+            tab["last_fwd_use"][i] = min(int(tab["last_fwd_use"][i]), 5)
+            tab["first_bwd_use"][i] = max(int(tab["first_bwd_use"][i]), 7)
+            tab["free_op"][i] = max(int(tab["free_op"][i]), int(tab["first_bwd_use"][i]))
+            tab["alloc_op"][i] = tab["producer_op"][i] = min(int(tab["alloc_op"][i]), int(tab["last_fwd_use"][i]))
+    arena_bytes = place_tensors(tab)
+    rows = []
+    for t in tab:
+        if rng.randint(3):
+            lf, fb = int(t["last_fwd_use"]), int(t["first_bwd_use"])
+            t_free = lf + rng.randint(max(1, fb - lf))
+            t_in = min(fb, t_free + 1 + rng.randint(max(1, fb - t_free)))
+            rows.append((int(t["producer_op"]), int(t["out_slot"]), int(t["tensor_id"]), 0, lf, t_free, t_in, fb,
+                         int(t["nbytes"])))
+    if rows and rng.randint(2):
+        rows.append(rows[0])
+    pol = np.array(rows, dtype=W.POLICY_DT) if rows else np.zeros(0, dtype=W.POLICY_DT)
+    idx = np.array([r[0] if rng.randint(6) else -1 for r in rows], dtype=np.int64)
+    bpo = [64, 700, 3000, 1 << 40][rng.randint(4)]
+    bpo_in = [0, 64, 900][rng.randint(3)]
+    keep = bool(rng.randint(2))
+    points = bool(rng.randint(2))
+    ora = oracle.apply_policy(pol, idx, tab, bpo, keep_late=keep, bpo_in=bpo_in or None, policy_points=points)
+    flags = (P.SS_CFG_KEEP_LATE if keep else 0) | (P.SS_CFG_POLICY_POINTS if points else 0)
+    c = make_ctx(P, staging_bytes=max(4096, ora["staging_bytes"]), link_bytes_per_op=bpo, prefetch_bytes_per_op=bpo_in,
+                 flags=flags)
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+    try:
+        P.ss_bind(c, arena.data_ptr(), arena_bytes, 0)
+        lib = P.ss_apply_policy(c, pol, idx, tab)
+        assert_applied_equal(lib, P, c, ora)
+        assert lib["n_late"] == sum(1 for r in ora["resolved"] if r[3] & oracle.F_LATE
+                                    and not r[3] & (oracle.F_UNMATCHED | oracle.F_ORDER))
+    finally:
+        P.ss_destroy(c)
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_greedy_policy_tiny(P, seed):
     tab, ev = tiny_trace(seed, n_ops=14, T=8)

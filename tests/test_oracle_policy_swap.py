@@ -137,6 +137,55 @@ def test_prescribed_swap_sets_give_checkable_schedules(cfg, bpo):
     assert res["peak"] <= no["peak"]
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_random_policies_links_and_options_give_checkable_schedules(seed):
+    """tiny random traces, a random subset as policy (some items unmatched, some claimed twice), a random
+    link share per direction, with and without keeping late items: whatever the timing, nobody touches a
+    tensor while it is away, every kept item has its four actions in causal order, staging slots are
+    disjoint, and the scan with the emitted events equals the live-set definition at the emitted points"""
+    rng = SplitMix64(seed, 31)
+    n_ops = 14
+    tab, ev = tiny_trace(seed, n_ops=n_ops, T=9)
+    if seed % 2:                  # every other trace with all forward uses before all backward uses
+        for i in range(len(tab)):
+            tab["last_fwd_use"][i] = min(int(tab["last_fwd_use"][i]), 6)
+            tab["first_bwd_use"][i] = max(int(tab["first_bwd_use"][i]), 8)
+            tab["free_op"][i] = max(int(tab["free_op"][i]), int(tab["first_bwd_use"][i]))
+            tab["alloc_op"][i] = tab["producer_op"][i] = min(int(tab["alloc_op"][i]), int(tab["last_fwd_use"][i]))
+        ev = W.transformer.events_of(tab)
+    op_in = [[] for _ in range(n_ops)]
+    op_out = [[] for _ in range(n_ops)]
+    for t in tab:
+        tid = int(t["tensor_id"])
+        op_out[int(t["producer_op"])].append(tid)
+        for u in {int(t["last_fwd_use"]), int(t["first_bwd_use"]), int(t["free_op"])}:
+            op_in[u].append(tid)
+    rows = []
+    for t in tab:
+        if rng.randint(3):
+            rows.append((int(t["producer_op"]), int(t["out_slot"]), int(t["tensor_id"]), 0, 0, 0, 0, 0, int(t["nbytes"])))
+    if rows and rng.randint(2):
+        rows.append(rows[0])                                  # the same tensor claimed twice
+    pol = np.array(rows, dtype=W.POLICY_DT) if rows else np.zeros(0, dtype=W.POLICY_DT)
+    idx = [r[0] if rng.randint(6) else -1 for r in rows]      # now and then an item without a match
+    bpo = [64, 700, 3000, 1 << 40][rng.randint(4)]
+    bpo_in = [None, 64, 900][rng.randint(3)]
+    keep = bool(rng.randint(2))
+    ap = oracle.apply_policy(pol, idx, tab, bpo, keep_late=keep, bpo_in=bpo_in)
+    assert oracle.schedule_check(ap, tab, op_in, op_out) == []
+    kept = [r for r in ap["resolved"] if not r[3] & (oracle.F_UNMATCHED | oracle.F_ORDER)]
+    assert len(kept) + ap["n_dropped"] == len(rows) and len(ap["actions"]) == 4 * len(kept)
+    assert len({r[2] for r in kept}) == len(kept)             # a tensor is swapped once
+    phased = max(int(t["last_fwd_use"]) for t in tab) < min(int(t["first_bwd_use"]) for t in tab)
+    if keep and phased:           # forward uses before backward uses: only unmatched and doubly claimed items go
+        assert ap["n_dropped"] == sum(1 for i in idx if i < 0) + sum(
+            1 for a, r in enumerate(rows) if idx[a] >= 0 and any(idx[b] >= 0 and rows[b][2] == r[2] for b in range(a)))
+    points = {r[2]: (r[5], r[6]) for r in kept}
+    res = oracle.timeline_scan(ev, ap["policy_events"], n_ops, 0, 0)
+    assert np.array_equal(res["per_op"], live_set_peak(tab, points, n_ops, 0))
+    assert res["final"] == 0
+
+
 def test_schedule_checker_catches_planted_mistakes():
     tr, pol, ap = applied_for(1, INSTANT)
     assert oracle.schedule_check(ap, tr.tensors, tr.op_inputs, tr.op_outputs) == []
