@@ -284,7 +284,7 @@ def main():
         return
 
     if args.reuse_interval:
-        from paper_2509_11076_amd.executor import run_iteration
+        from paper_2509_11076_amd.executor import run_iteration_dispatch
         link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
         base = SwapRun(B, torch, args.config, swap=False)
         for _ in range(3):
@@ -332,7 +332,7 @@ def main():
                     pending.remove(b)
             t_query += time.perf_counter() - q0
         t0 = time.perf_counter()
-        run_iteration(run.ctx, run.tr.n_ops, acts, run_op, plan["lists"])
+        run_iteration_dispatch(run.ctx, run.tr.n_ops, run_op, plan["points"])
         torch.cuda.synchronize()
         t_step = time.perf_counter() - t0
         ours = np.array([free_op[b] - issue_op[b] for b in sorted(issue_op)])

@@ -427,6 +427,17 @@ enum { SS_SYNC_FREE = 0,    /* id = tensor: compute stream waits (device-side) f
        SS_SYNC_DRAIN = 2 }; /* host waits for both swap streams; surfaces asynchronous errors      */
 int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id);
 
+/* Sec. 5, first paragraph: "dispatch the swap operations at the designated positions".  Issues, in
+ * schedule order, every action that the schedule loaded by the last ss_apply_policy holds for
+ * operator op_idx: when = 0, the ones that come before the operator is enqueued (SS_ACT_IN through
+ * ss_swap_in once per batch, SS_ACT_WAIT_IN through ss_sync); when = 1, the ones that come after it
+ * (SS_ACT_OUT through ss_swap_out once per batch, SS_ACT_FREE through ss_sync).  One call per side
+ * of an operator replaces one call per action; an operator without actions costs a table lookup.
+ * SS_E_STATE if no schedule made by ss_apply_policy is loaded (ss_load_schedule carries no actions),
+ * SS_E_INVAL for when > 1; the first failing action's code otherwise (actions after it are not
+ * issued). */
+int ss_dispatch(ss_ctx *ctx, uint32_t op_idx, uint32_t when);
+
 /* ---- support ------------------------------------------------------------------- */
 
 /* Pointer into the pinned staging area (host) for checking results. */

@@ -151,6 +151,7 @@ _SIGS = {
     "ss_swap_out": [_P, C.c_uint32],
     "ss_swap_in": [_P, C.c_uint32],
     "ss_sync": [_P, C.c_uint32, C.c_uint32],
+    "ss_dispatch": [_P, C.c_uint32, C.c_uint32],
     "ss_host_peek": [_P, C.c_uint64, C.c_uint64, C.POINTER(_P)],
     "ss_staging_fill": [_P, C.c_int],
     "ss_batch_ms": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
@@ -463,6 +464,11 @@ def ss_swap_in(ctx, batch):
 
 def ss_sync(ctx, what, ident=0):
     _ck(_lib.ss_sync(ctx, int(what), int(ident)), "ss_sync")
+
+
+def ss_dispatch(ctx, op_idx, when):
+    """every scheduled action before (when = 0) or after (when = 1) operator op_idx"""
+    _ck(_lib.ss_dispatch(ctx, int(op_idx), int(when)), "ss_dispatch")
 
 
 def ss_host_peek(ctx, host_off, nbytes):

@@ -44,6 +44,11 @@ struct ss_sched {
   bool out_all_large = false;                     // every swap-out batch reaches engine_min_bytes_out (mean tensor size)
   int64_t last_engine_out = -1;                   // last swap-out batch of this iteration that went by copy engine
   bool loaded = false;
+  // the action schedule of the last ss_apply_policy, for ss_dispatch: actions in schedule order and,
+  // per operator, where its "before" and "after" runs start (act_start has 2 * n + 1 entries)
+  std::vector<ss_action_t> actions;
+  std::vector<uint32_t> act_start;
+  bool have_actions = false;
 };
 
 struct ss_ctx {

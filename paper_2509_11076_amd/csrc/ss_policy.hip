@@ -368,9 +368,20 @@ extern "C" int ss_apply_policy(ss_ctx *ctx, const ss_policy_item_t *policy, uint
     res->n_in_batches = (uint32_t)ap.in_start.size() - 1;
     if (ap.staging_bytes > ctx->cfg.staging_bytes) return SS_E_NOMEM;
     if (!ctx->bound) return SS_OK;          // schedule computed; nothing to load it against yet
-    return ss_load_schedule(ctx, ap.out.data(), (uint32_t)ap.out.size(), ap.out_start.data(), res->n_out_batches,
-                            ap.in.data(), (uint32_t)ap.in.size(), ap.in_start.data(), res->n_in_batches,
-                            ap.in_dep.data());
+    rc = ss_load_schedule(ctx, ap.out.data(), (uint32_t)ap.out.size(), ap.out_start.data(), res->n_out_batches,
+                          ap.in.data(), (uint32_t)ap.in.size(), ap.in_start.data(), res->n_in_batches,
+                          ap.in_dep.data());
+    if (rc != SS_OK) return rc;
+    // keep the actions for ss_dispatch: they are sorted by (operator, kind), so the actions before an
+    // operator (IN, WAIT_IN) and those after it (OUT, FREE) are two consecutive runs
+    ss_sched &s = ctx->sched;
+    s.actions = ap.actions;
+    const uint64_t groups = s.actions.empty() ? 0 : 2ull * ((uint64_t)s.actions.back().op_idx + 1);
+    s.act_start.assign(groups + 1, 0);
+    for (const ss_action_t &a : s.actions) s.act_start[2ull * a.op_idx + (a.kind >= SS_ACT_OUT ? 1 : 0) + 1]++;
+    for (uint64_t g = 0; g < groups; ++g) s.act_start[g + 1] += s.act_start[g];
+    s.have_actions = true;
+    return SS_OK;
   });
 }
 

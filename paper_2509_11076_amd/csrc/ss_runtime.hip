@@ -295,6 +295,7 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     for (uint32_t b = 0; in_dep && b < n_in_batches; ++b)
       if (n_out_batches == 0 || in_dep[b] >= n_out_batches) return SS_E_INVAL;
     ss_sched &s = ctx->sched;
+    s.have_actions = false;       // a schedule loaded here carries no actions; ss_apply_policy adds them
     // the same schedule as the one already loaded (a fixed operator sequence in the Stable stage): it was
     // validated against this arena and staging area when it was loaded; device tables, chunk tables and
     // events stay, only the per-iteration state starts over
@@ -608,6 +609,27 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
     }
     default: return SS_E_INVAL;
   }
+}
+
+extern "C" int ss_dispatch(ss_ctx *ctx, uint32_t op_idx, uint32_t when) {
+  if (!ctx || when > 1) return SS_E_INVAL;
+  ss_sched &s = ctx->sched;
+  if (!s.loaded || !s.have_actions) return SS_E_STATE;
+  const uint64_t g = 2ull * op_idx + when;
+  if (g + 1 >= s.act_start.size()) return SS_OK;          // beyond the last operator with actions
+  for (uint32_t a = s.act_start[g]; a < s.act_start[g + 1]; ++a) {
+    const ss_action_t &act = s.actions[a];
+    int rc = SS_OK;
+    switch (act.kind) {
+      case SS_ACT_IN: if (!s.in_issued[act.batch]) rc = ss_swap_in(ctx, act.batch); break;
+      case SS_ACT_WAIT_IN: rc = ss_sync(ctx, SS_SYNC_WAIT_IN, act.tensor_id); break;
+      case SS_ACT_OUT: if (!s.out_issued[act.batch]) rc = ss_swap_out(ctx, act.batch); break;
+      case SS_ACT_FREE: rc = ss_sync(ctx, SS_SYNC_FREE, act.tensor_id); break;
+      default: rc = SS_E_INVAL;
+    }
+    if (rc != SS_OK) return rc;
+  }
+  return SS_OK;
 }
 
 extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms) {

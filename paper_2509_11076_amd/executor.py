@@ -35,8 +35,8 @@ def batch_lists(actions):
 
 
 def run_iteration(ctx, n_ops, actions, run_op, before_after=None):
-    """Execute one iteration: for each operator, issue IN / WAIT_IN actions, run the
-    operator, then issue OUT / FREE actions; drain the swap streams at the end."""
+    """Execute one iteration with one library call per action: for each operator, issue IN / WAIT_IN
+    actions, run the operator, then issue OUT / FREE actions; drain the swap streams at the end."""
     before, after = before_after if before_after is not None else batch_lists(actions)
     issued_in, issued_out = set(), set()
     for i in range(n_ops):
@@ -56,4 +56,28 @@ def run_iteration(ctx, n_ops, actions, run_op, before_after=None):
                     issued_out.add(batch)
             else:
                 B.ss_sync(ctx, B.SS_SYNC_FREE, tid)
+    B.ss_sync(ctx, B.SS_SYNC_DRAIN, 0)
+
+
+def dispatch_points(actions):
+    """The operators that have actions before them and those that have actions after them (two sets),
+    so that the loop below calls into the library only where something is scheduled."""
+    if len(actions) == 0:
+        return frozenset(), frozenset()
+    late = actions["kind"] >= B.SS_ACT_OUT
+    return (frozenset(np.unique(actions["op_idx"][~late]).tolist()),
+            frozenset(np.unique(actions["op_idx"][late]).tolist()))
+
+
+def run_iteration_dispatch(ctx, n_ops, run_op, points):
+    """Execute one iteration of the schedule that the last ss_apply_policy loaded, with ss_dispatch:
+    one library call per side of an operator that has actions, the actions themselves issued natively."""
+    before, after = points
+    for i in range(n_ops):
+        if i in before:
+            B.ss_dispatch(ctx, i, 0)
+        if run_op is not None:
+            run_op(i)
+        if i in after:
+            B.ss_dispatch(ctx, i, 1)
     B.ss_sync(ctx, B.SS_SYNC_DRAIN, 0)

@@ -87,6 +87,59 @@ def test_toy_config_round_trip_with_guards_and_poison(P, torch, path, bpo):
         P.ss_destroy(ctx)
 
 
+def test_native_dispatch_equals_the_per_action_loop(P, torch):
+    """ss_dispatch issues the schedule's actions operator by operator: the toy configuration run with it
+    leaves the same staging image, the same arena (poisoned blocks included) and the same statistics as
+    one library call per action; and what it refuses"""
+    from paper_2509_11076_amd.executor import run_iteration, run_iteration_dispatch, dispatch_points
+    tr = W.build_trace(W.config_shape(1))
+    pol = W.config_swap_set(tr, 1)
+    idx = pol["ref_op"].astype(np.int64)
+    ora = oracle.apply_policy(pol, idx, tr.tensors, 64 * 1024)
+    swapped = {r[2]: (r[5], r[6]) for r in ora["resolved"] if not r[3] & 3}
+    arena_bytes = place_tensors(tr.tensors, swapped=swapped)
+    ora = oracle.apply_policy(pol, idx, tr.tensors, 64 * 1024)
+    images = []
+    for native in (False, True):
+        arena = random_arena(torch, arena_bytes, 2509)
+        ctx = make_ctx(P, staging_bytes=ora["staging_bytes"], link_bytes_per_op=64 * 1024, flags=P.SS_CFG_POISON_FREE)
+        try:
+            with pytest.raises(P.SsError) as e:                     # nothing loaded yet
+                P.ss_dispatch(ctx, 0, 0)
+            assert e.value.code == P.SS_E_STATE
+            P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+            lib = P.ss_apply_policy(ctx, pol, idx, tr.tensors)
+            P.ss_staging_fill(ctx, 0xA5)
+            if native:
+                with pytest.raises(P.SsError) as e:
+                    P.ss_dispatch(ctx, 0, 2)
+                assert e.value.code == P.SS_E_INVAL
+                P.ss_dispatch(ctx, 1 << 30, 1)                      # far beyond the last action: nothing to do
+                before, after = dispatch_points(lib["actions"])
+                assert before and after and max(before | after) < tr.n_ops
+                run_iteration_dispatch(ctx, tr.n_ops, None, (before, after))
+            else:
+                run_iteration(ctx, tr.n_ops, lib["actions"], None)
+            torch.cuda.synchronize()
+            st = P.ss_get_stats(ctx)
+            images.append((P.ss_host_peek(ctx, 0, ora["staging_bytes"]).copy(), arena.cpu().numpy(),
+                           {k: st[k] for k in ("bytes_out", "bytes_in", "kernel_batches", "engine_batches", "free_waits", "in_waits")}))
+            if native:                                              # a schedule loaded without actions cannot be dispatched
+                os_, is_, dep = P.ss_schedule_view(ctx)
+                P.ss_load_schedule(ctx, lib["descs_out"], os_, lib["descs_in"], is_, dep)
+                with pytest.raises(P.SsError) as e:
+                    P.ss_dispatch(ctx, 0, 1)
+                assert e.value.code == P.SS_E_STATE
+        finally:
+            P.ss_destroy(ctx)
+    assert np.array_equal(images[0][0], images[1][0]) and np.array_equal(images[0][1], images[1][1])
+    assert images[0][2] == images[1][2] and images[0][2]["bytes_out"] == sum(d[2] for d in ora["descs_out"]) > 0
+    host_arena = random_arena(torch, arena_bytes, 2509).cpu().numpy().copy()
+    staging = np.full(ora["staging_bytes"], 0xA5, dtype=np.uint8)
+    oracle_execute(host_arena, staging, ora, poison=0xDB)
+    assert np.array_equal(images[1][0], staging) and np.array_equal(images[1][1], host_arena)
+
+
 def ragged_schedule(seed, n, arena_bytes, max_bytes):
     """descriptors with every awkward size: 0, 1, 15, 16, 17, chunk-1, chunk, chunk+1, several chunks + tail"""
     rng = SplitMix64(seed, 9)

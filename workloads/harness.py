@@ -135,8 +135,8 @@ class SwapRun:
         sc = B.ss_timeline_scan(self.ctx, tr.events, ap["policy_events"], tr.n_ops, 0, self.budget,
                                 want_timeline=False, want_per_op=False)
         t3 = time.perf_counter()
-        from paper_2509_11076_amd.executor import batch_lists
-        self.last = dict(match=m, applied=ap, scan=sc, lists=batch_lists(ap["actions"]),
+        from paper_2509_11076_amd.executor import dispatch_points
+        self.last = dict(match=m, applied=ap, scan=sc, points=dispatch_points(ap["actions"]),
                          host_ms=dict(match=(t1 - t0) * 1e3, apply=(t2 - t1) * 1e3, scan=(t3 - t2) * 1e3))
         self.host_ms_log.append(self.last["host_ms"])
         return self.last
@@ -144,7 +144,7 @@ class SwapRun:
     def step(self):
         """one training iteration: plan, then dispatch every operator with trace recording (a1) and
         the scheduled swap actions (a5-a7) around it"""
-        from paper_2509_11076_amd.executor import run_iteration
+        from paper_2509_11076_amd.executor import run_iteration_dispatch
         B = self.B
         plan = self.plan()
         B.ss_trace_begin(self.ctx)
@@ -154,7 +154,7 @@ class SwapRun:
             rec(i)
             if comp is not None:
                 comp.run_op(i)
-        run_iteration(self.ctx, self.tr.n_ops, plan["applied"]["actions"], run_op, plan["lists"])
+        run_iteration_dispatch(self.ctx, self.tr.n_ops, run_op, plan["points"])
 
     def step_noswap(self):
         """the same operators with no swap executor at all (baseline for the overhead figure)"""
@@ -257,7 +257,7 @@ class VaryingRun:
     def execute(self, p):
         """place this iteration's tensors, bind, load the schedule, run the operators with swapping"""
         from .compute import SyntheticCompute
-        from paper_2509_11076_amd.executor import run_iteration, batch_lists
+        from paper_2509_11076_amd.executor import run_iteration_dispatch, dispatch_points
         B, tr = self.B, p["trace"]
         res = p["applied"]["resolved"]
         kept = (res["flags"] & (B.SS_F_UNMATCHED | B.SS_F_ORDER)) == 0
@@ -273,7 +273,7 @@ class VaryingRun:
         def run_op(i):
             rec(i)
             comp.run_op(i)
-        run_iteration(self.exec_ctx, tr.n_ops, ap["actions"], run_op, batch_lists(ap["actions"]))
+        run_iteration_dispatch(self.exec_ctx, tr.n_ops, run_op, dispatch_points(ap["actions"]))
         return comp.result(), used, ap
 
 
@@ -375,7 +375,7 @@ class StagedRun:
 
     def iteration(self, it):
         from .compute import SyntheticCompute
-        from paper_2509_11076_amd.executor import run_iteration, batch_lists
+        from paper_2509_11076_amd.executor import run_iteration_dispatch, dispatch_points
         B, torch = self.B, self.torch
         tr = self.trace_of(it)
         ops = self._intern(tr)
@@ -410,7 +410,7 @@ class StagedRun:
         comp = SyntheticCompute(tr, self.arena, seed=self.seed, gemm_scale=self.gemm_scale)
         comp.mark_swapped(swapped.keys())
         rec = B.ss_trace_record_prepared(self.ctx, ops, tr.events)
-        lists = batch_lists(ap["actions"])
+        points = dispatch_points(ap["actions"])
         phases = list(tr.op_phase)
         first_bwd = phases.index(1) if 1 in phases else -1
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(3)]    # start, first backward operator, end
@@ -424,7 +424,7 @@ class StagedRun:
                 marks[1].record()
             rec(i)
             comp.run_op(i)
-        run_iteration(self.ctx, tr.n_ops, ap["actions"], run_op, lists)
+        run_iteration_dispatch(self.ctx, tr.n_ops, run_op, points)
         marks[2].record()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3
