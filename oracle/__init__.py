@@ -19,25 +19,27 @@ What the paper fixes and what is this build's reading of it:
   StageMachine    - Sec. 3, Algo. 1 with m = 2, n = 5 (Sec. 6).  Pinned by a
                     hand-derived stage table and exact threshold cases.
 * match_anchors   - Sec. 5.1 names the features only; the algorithm is this
-                    build's.  PARITY UNPINNED against the paper; pinned against
-                    a nested-loop restatement and structural invariants.
+                    build's (there is nothing of the paper's to compare with).
+                    Pinned by hand cases, an online-counter formulation, the
+                    paper's failure case (inserted operators) and invariants.
 * apply_policy,
   link_timing     - Sec. 5 first paragraph, Sec. 4.3 (Eq. 3, swap-in
                     pre-trigger, swap-out completion) at operator granularity
                     with a FIFO link; a stand-in for the paper's logical-layer
-                    simulator.  PARITY UNPINNED against the paper; pinned by the
-                    schedule checker and hand-worked cases.
+                    simulator (this build's; the paper prints no values for it).
+                    Pinned by hand-worked cases, the schedule checker (also on
+                    random policies) and the live-set definition.
 * greedy_policy   - stand-in for Algo. 2 (longest-idle-first until the peak
-                    fits).  PARITY UNPINNED against the paper; pinned by brute
-                    force on tiny traces.
+                    fits; this build's).  Pinned by brute force over all
+                    subsets on tiny traces.
 * swap_out/in     - Sec. 1, 5.2: bytes leave and return unchanged.
 * generate_policy - Sec. 4 (Eq. 1-3, Algo. 2): logical layers, MRL, candidate list, simulator.
-                    PARITY UNPINNED against the paper (no worked example in it); pinned by
-                    hand-worked cases, invariants and brute force.
+                    The paper prints no worked example; pinned by a case worked by hand from
+                    its steps, the order Eq. 2 prescribes, invariants and brute force.
 * align, align_anchors - longest common subsequence of two operator sequences (textbook dynamic
                     programme) and the canonical alignment read off its table; the matcher's fourth
-                    level.  Not in the paper (Sec. 5.1 gives no algorithm): PARITY UNPINNED against
-                    it; pinned by textbook examples, brute force and closed forms.
+                    level.  Not in the paper (Sec. 5.1 gives no algorithm); pinned by textbook
+                    examples, brute force over all subsequences and closed forms.
 """
 from .trace import fnv1a32, make_sig, TraceRecorder
 from .timeline import timeline_scan

@@ -8,7 +8,8 @@ ordinal shifts.  Aligning the two sequences as a whole does not: this module is 
 dynamic programme for the longest common subsequence (equivalently the edit distance with insertions
 and deletions only, n + m - 2 LCS), written out plainly.
 
-Definitions fixed here (this build's; PARITY UNPINNED against the paper, which has no aligner):
+Definitions fixed here (this build's: the paper has no aligner; pinned by textbook examples, brute
+force over all subsequences and closed forms):
  * two operators are equal when (op_token, stack_hash, sig) are equal;
  * L[i][j] = LCS length of ref[:i] and cur[:j];
    L[i][j] = L[i-1][j-1] + 1 if ref[i-1] == cur[j-1] else max(L[i-1][j], L[i][j-1]);

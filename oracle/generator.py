@@ -2,8 +2,8 @@
 list with the score of Eq. 2, the swap simulator, and the loop of Algo. 2.
 
 Steps follow the paper's order and notation.  What it leaves open is fixed as follows (each is
-this build's reading; the paper prints no worked example, so PARITY IS UNPINNED against the
-paper and the pins are hand-worked cases, invariants and brute force):
+this build's reading; the paper prints no worked example, so the pins are a case worked by hand from
+its steps, the order Eq. 2 prescribes, invariants and brute force):
 
  * Time is counted in link bytes, so Eq. 3 (T_swap = S / B) makes T_swap = S and Eq. 1
    (T_group = T_iter / N_iter * N_group) makes a layer's time budget bpo * N_group with

@@ -36,8 +36,9 @@ FIFO link per direction.  Time is measured in link bytes: operator t occupies
   kept instead with t_free = t_use - 1, flags FORCED and LATE: released and
   re-fetched around its use, the compute stream waiting for the round trip.
 
-PARITY UNPINNED against the paper (it prints no worked example of its
-simulator); pinned by the schedule checker, hand-worked cases and brute force.
+The paper prints no worked example of its simulator to compare with; pinned by
+hand-worked cases, the schedule checker (also on random policies), the live-set
+definition of the memory the schedule leaves, and brute force over subsets.
 """
 import numpy as np
 
