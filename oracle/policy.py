@@ -343,7 +343,8 @@ def schedule_check(applied, tensors, op_inputs, op_outputs):
     Checks: every kept item has exactly one IN, WAIT_IN, OUT, FREE in that
     causal order; no operator reads or writes a tensor while it is away
     (t_free < t < t_in); staging slots are pairwise disjoint; actions are
-    sorted; batches cover the descriptors.
+    sorted; batches cover the descriptors, hold what their actions say, do not
+    mix issue points, and swap-in batches depend on the right swap-out batch.
     """
     problems = []
     acts = applied["actions"]
@@ -384,4 +385,40 @@ def schedule_check(applied, tensors, op_inputs, op_outputs):
         if starts[0] != 0 or starts[-1] != n or any(b <= a for a, b in zip(starts, starts[1:])):
             if not (n == 0 and starts == [0]):
                 problems.append("%s batches do not partition the descriptors" % name)
+                return problems
+    # batches: the batch an action names holds that tensor's descriptor; a swap-out batch is what leaves
+    # after one operator, a swap-in batch what is issued before one operator for one first use; a
+    # swap-in batch depends on the last swap-out batch that holds one of its tensors
+    def batch_of(descs, starts):
+        out = {}
+        for b in range(len(starts) - 1):
+            for d in descs[starts[b]:starts[b + 1]]:
+                out[d[3]] = b
+        return out
+    ob = batch_of(applied["descs_out"], applied["out_batch_start"])
+    ib = batch_of(applied["descs_in"], applied["in_batch_start"])
+    for (op, kind, tid, batch) in acts:
+        want = ib.get(tid) if kind in (K_IN, K_WAIT_IN) else ob.get(tid)
+        if want != batch:
+            problems.append("action %r names batch %d, its descriptor is in batch %r" % ((op, kind, tid), batch, want))
+    ok_tids = [tid for tid, d in per.items() if all(len(d.get(kd, [])) == 1 for kd in (K_IN, K_WAIT_IN, K_OUT, K_FREE))]
+    for name, table_, key in (("out", ob, lambda d: (d[K_OUT][0],)), ("in", ib, lambda d: (d[K_IN][0], d[K_WAIT_IN][0]))):
+        seen, last = {}, None
+        for tid in ok_tids:
+            if tid in table_:
+                seen.setdefault(table_[tid], set()).add(key(per[tid]))
+        for b in sorted(seen):
+            if len(seen[b]) != 1:
+                problems.append("%s batch %d mixes issue points %r" % (name, b, sorted(seen[b])))
+            elif last is not None and next(iter(seen[b])) == last:
+                problems.append("%s batches %d and %d have the same issue point" % (name, b - 1, b))
+            last = next(iter(seen[b])) if len(seen[b]) == 1 else None
+    if "in_dep" in applied:
+        want = {}
+        for tid, b in ib.items():
+            if tid in ob:
+                want[b] = max(want.get(b, 0), ob[tid])
+        got = list(applied["in_dep"])
+        if got != [want.get(b, 0) for b in range(len(got))] or len(got) != len(applied["in_batch_start"]) - 1:
+            problems.append("swap-in batches depend on %r, their tensors leave in %r" % (got, want))
     return problems
