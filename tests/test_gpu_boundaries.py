@@ -23,7 +23,7 @@ def P():
 def test_scan_canonical_order_and_one_byte_excess(P):
     c = make_ctx(P, staging_bytes=4096)
     try:
-        ev = np.array([(0, 1, 100), (1, 3, 30), (1, 2, -20), (2, 1, -80)], dtype=W.EVENT_DT)
+        ev = np.array([(0, 1, 100), (1, 2, -20), (1, 3, 30), (2, 1, -80)], dtype=W.EVENT_DT)   # release listed first
         pe = np.array([(1, 8, 50), (1, 9, -10)], dtype=W.EVENT_DT)
         lib = P.ss_timeline_scan(c, ev, pe, 3, 7, 156, want_timeline=True)
         assert lib["timeline"].tolist() == [107, 157, 187, 167, 157, 77]

@@ -16,7 +16,7 @@ BIG = 1 << 40
 # ------------------------------------------------------------------ timeline
 def test_canonical_order_inside_one_operator():
     """policy allocation, trace allocations, trace frees, policy free - whatever the order of the lists"""
-    ev = [(1, 3, 30), (0, 1, 100), (1, 2, -20), (2, 1, -80)]
+    ev = [(0, 1, 100), (1, 2, -20), (1, 3, 30), (2, 1, -80)]       # the release listed before the allocation
     pe = [(1, 9, -10), (1, 8, 50)]
     res = oracle.timeline_scan(ev, pe, 3, 7, 156)
     # operator 0: 107; operator 1: +50 (policy), +30 (trace), -20 (trace), -10 (policy); operator 2: -80
