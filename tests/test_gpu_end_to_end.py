@@ -51,6 +51,21 @@ def test_toy_step_swap_on_equals_swap_off(env, path):
     assert i1["plan"]["scan"]["peak"] == osc["peak"]
 
 
+def test_toy_step_on_a_stream_of_the_callers_own(env):
+    """the compute stream handed to ss_bind need not be the default one: the same step on a stream the
+    caller created (default priority) gives the same results, swapping or not"""
+    B, torch = env
+    chk0, g0, _ = run(B, torch, 1, False, 2)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chk1, g1, i1 = run(B, torch, 1, True, 2, bpo=64 * 1024, copy_path=1)
+        side.synchronize()
+    torch.cuda.current_stream().wait_stream(side)
+    assert i1["stats"]["bytes_out"] == 2 * i1["bytes"] > 0 and i1["stats"]["free_waits"] > 0
+    assert np.array_equal(chk0, chk1) and np.array_equal(g0, g1)
+
+
 def test_1p3b_shape_three_iterations_swap_on_equals_swap_off(env):
     """configuration 2: every other layer's activations (about 3 GB) leave and return, 3 iterations"""
     B, torch = env
