@@ -270,6 +270,26 @@ int ss_timeline_scan_batch(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev, con
                            const uint64_t *pe_start, uint32_t k, uint32_t n_ops, int64_t base,
                            int64_t budget, int64_t *per_op, ss_scan_result_t *res /* host, out */);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the scan of ss_timeline_scan with nothing allocated, copied or waited
+ * for.  Inputs and outputs are the caller's DEVICE arrays (same meaning, sizes and nullability as
+ * above; d_res is required); the kernel's scratch is a static device array of 9.75 MiB that every GPU
+ * the library runs on holds until the process ends.  The call enqueues one kernel on `stream` (a
+ * hipStream_t of the context's device, which must be current; NULL = the null stream) and returns;
+ * results are valid once that stream has reached the kernel's end.
+ * Limits: n_ops <= 65,536 and n_ev + n_pe <= 262,144, else SS_E_CAPACITY (nothing is enqueued).
+ * Errors the kernel finds are reported in d_res->reserved: bit 0 = an event names an operator
+ * >= n_ops (no other output is meaningful), bit 1 = a list is not in operator order (d_res->sorted
+ * is 0 and the timeline is not written; the other outputs are valid).
+ * All calls on one GPU share the one scratch array: calls that overlap in time on the same GPU
+ * (different streams, different contexts) race; the kernel clears what it needs itself, so calls
+ * in sequence need nothing between them. */
+int ss_timeline_scan_static(ss_ctx *ctx, void *stream, const ss_event_t *d_ev /* device */, uint64_t n_ev,
+                            const ss_event_t *d_pev /* device, nullable */, uint64_t n_pe, uint32_t n_ops,
+                            int64_t base, int64_t budget, int64_t *d_timeline /* device, nullable */,
+                            int64_t *d_per_op /* device, nullable */, int64_t *d_mre /* device, nullable */,
+                            ss_scan_result_t *d_res /* device, out */);
+
 /* ---- a3: sequence match (Sec. 3 Algo. 1, Sec. 5.1) ---------------------------- */
 
 /* (i) Similarity of the current sequence `cur` to `ref`: similar iff

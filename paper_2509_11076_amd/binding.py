@@ -138,6 +138,7 @@ _SIGS = {
     "ss_greedy_policy": [_P, _P, C.c_uint32, _P, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_uint64,
                          _P, C.c_uint32, _P, C.POINTER(C.c_uint32), C.POINTER(C.c_int64)],
     "ss_timeline_scan_batch": [_P, _P, C.c_uint64, _P, _P, C.c_uint32, C.c_uint32, C.c_int64, C.c_int64, _P, _P],
+    "ss_timeline_scan_static": [_P, _P, _P, C.c_uint64, _P, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, _P, _P, _P, _P],
     "ss_batch_done": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_int)],
     "ss_trace_event": [_P, C.c_uint32, C.c_int64],
     "ss_trace_amend": [_P, C.c_uint32, C.c_uint32, C.c_uint32],
@@ -301,6 +302,16 @@ def ss_timeline_scan(ctx, events, policy_events, n_ops, base, budget, want_timel
                               tlp, _ptr(per_op), _ptr(mre), C.byref(res)), "ss_timeline_scan")
     return dict(timeline=tl, per_op=per_op, mre=mre, peak=res.peak, argpeak_op=res.argpeak_op,
                 n_over=res.n_over, final=res.final_total, sorted=res.sorted)
+
+
+def ss_timeline_scan_static(ctx, stream, d_ev, n_ev, d_pev, n_pe, n_ops, base, budget, d_timeline, d_per_op, d_mre,
+                            d_res):
+    """every d_* is a device address (int, 0 = NULL); only enqueues: synchronise the stream before reading"""
+    def p(x):
+        return _P(int(x)) if x else None
+    _ck(_lib.ss_timeline_scan_static(ctx, p(stream), p(d_ev), int(n_ev), p(d_pev), int(n_pe), int(n_ops), int(base),
+                                     int(budget), p(d_timeline), p(d_per_op), p(d_mre), p(d_res)),
+        "ss_timeline_scan_static")
 
 
 def ss_timeline_scan_batch(ctx, events, policy_event_lists, n_ops, base, budget, want_per_op=False):

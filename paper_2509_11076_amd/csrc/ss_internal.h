@@ -102,6 +102,8 @@ static inline uint64_t ss_align_up(uint64_t x, uint64_t a) { return (x + a - 1) 
 
 // scratch management (ss_runtime.hip)
 int ss_scratch_reserve(ss_ctx *ctx, size_t dev_bytes, size_t host_bytes);
+// address of the static scratch array of ss_timeline_scan_static on the context's device (ss_scan.hip)
+int ss_scan_static_init(ss_ctx *ctx);
 
 // internal entry used by the greedy generator: timing + schedule without loading it
 struct ss_applied {

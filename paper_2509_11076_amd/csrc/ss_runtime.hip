@@ -100,6 +100,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
 #define fail(code, e) fail_at(code, e, __LINE__)
     hipError_t e;
     if ((e = hipGetDevice(&ctx->device)) != hipSuccess) fail(SS_E_HIP, e);
+    if (rc == SS_OK) rc = ss_scan_static_init(ctx);
     if (rc == SS_OK && cfg.staging_bytes) {
       e = hipHostMalloc((void **)&ctx->staging, cfg.staging_bytes, hipHostMallocMapped | hipHostMallocPortable);
       if (e != hipSuccess) fail(SS_E_NOMEM, e);

@@ -38,6 +38,7 @@ struct ScanArgs {
   int64_t *per_op, *mre, *timeline;
   ss_scan_result_t *res;
   uint32_t *flags;  // bit 0: event names an operator >= n_ops; bit 1: a list is not in operator order
+  int res_flags;    // also report the flags in res->reserved (for callers that read nothing but res)
 };
 
 __device__ inline int64_t shfl_up_i64(int64_t v, int d) {
@@ -174,7 +175,13 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a) {
   __syncthreads();
   const uint32_t flags = s_flags;
   if (flags & 1u) {                       // an operator index out of range: nothing else is meaningful
-    if (tid == 0) *a.flags = flags;
+    if (tid == 0) {
+      *a.flags = flags;
+      if (a.res_flags) {
+        ss_scan_result_t r = {a.base, a.base, -1, 0, 0, flags};
+        *a.res = r;
+      }
+    }
     return;
   }
 
@@ -239,7 +246,7 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a) {
       r.argpeak_op = n ? (int32_t)bt : -1;
       r.n_over = oc;
       r.sorted = (flags & 2u) ? 0u : 1u;
-      r.reserved = 0;
+      r.reserved = a.res_flags ? flags : 0;
       *a.res = r;
       *a.flags = flags;
     }
@@ -318,6 +325,94 @@ __global__ __launch_bounds__(kThreads) void ss_scan_batch_kernel(const ScanArgs 
 }
 
 }  // namespace
+
+// ---- the scan for callers that cannot allocate ------------------------------------------------
+//
+// Same kernel, but its scratch (per-operator class sums and counts, entry totals, event
+// positions, per-event class prefixes) lives in a static device array instead of memory the
+// library allocates, and inputs and outputs are the caller's device arrays: the call only
+// enqueues one kernel on the caller's stream.
+
+constexpr uint32_t kStaticMaxOps = 65536;
+constexpr uint64_t kStaticMaxEvents = 262144;
+constexpr size_t kStaticBytes =
+    2 * (4ull * kStaticMaxOps * 8)        // csum, segsum
+    + 1ull * kStaticMaxOps * 8            // before
+    + 2 * (4ull * kStaticMaxOps * 4)      // ccnt, segcnt
+    + 1ull * kStaticMaxOps * 4            // evstart
+    + kStaticMaxEvents * 8                // sumx
+    + kStaticMaxEvents * 4                // cntx
+    + 256;                                // flags
+static __device__ __align__(256) uint8_t scratch[kStaticBytes];
+
+// Address of `scratch` on each device (the name itself is only a host-side handle): resolved once
+// per device, with that device current.
+constexpr int kMaxDevices = 64;
+static uint8_t *g_scratch_ptr[kMaxDevices];
+
+static int static_scratch_ptr(int device, uint8_t **out, hipError_t *err) {
+  *err = hipSuccess;
+  if (device < 0 || device >= kMaxDevices) return SS_E_INVAL;
+  if (!g_scratch_ptr[device]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      *err = e;
+      return SS_E_HIP;
+    }
+    g_scratch_ptr[device] = (uint8_t *)p;
+  }
+  *out = g_scratch_ptr[device];
+  return SS_OK;
+}
+
+int ss_scan_static_init(ss_ctx *ctx) {
+  uint8_t *p;
+  hipError_t e;
+  const int rc = static_scratch_ptr(ctx->device, &p, &e);
+  if (rc == SS_E_HIP) SS_HIP(e);
+  return rc;
+}
+
+extern "C" int ss_timeline_scan_static(ss_ctx *ctx, void *stream, const ss_event_t *d_ev, uint64_t n_ev,
+                                       const ss_event_t *d_pev, uint64_t n_pe, uint32_t n_ops, int64_t base,
+                                       int64_t budget, int64_t *d_timeline, int64_t *d_per_op, int64_t *d_mre,
+                                       ss_scan_result_t *d_res) {
+  if (!ctx || !d_res || (n_ev && !d_ev) || (n_pe && !d_pev)) return SS_E_INVAL;
+  if (n_ops > kStaticMaxOps || n_ev > kStaticMaxEvents || n_pe > kStaticMaxEvents || n_ev + n_pe > kStaticMaxEvents)
+    return SS_E_CAPACITY;
+  int dev = -1;
+  SS_HIP(hipGetDevice(&dev));
+  if (dev != ctx->device) return SS_E_STATE;          // the context's copy of the array is on its own device
+  uint8_t *d = nullptr;
+  hipError_t e;
+  const int rc = static_scratch_ptr(dev, &d, &e);
+  if (rc == SS_E_HIP) SS_HIP(e);
+  if (rc != SS_OK) return rc;
+  const uint64_t n = kStaticMaxOps, E = kStaticMaxEvents;    // fixed layout: every piece at its maximum
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += bytes; return o; };
+  ScanArgs a;
+  a.ev = d_ev; a.n_ev = n_ev;
+  a.pev = d_pev; a.n_pe = n_pe;
+  a.n_ops = n_ops; a.want_timeline = d_timeline != nullptr;
+  a.base = base; a.budget = budget;
+  a.csum = (int64_t *)(d + take(4 * n * 8));
+  a.segsum = (int64_t *)(d + take(4 * n * 8));
+  a.before = (int64_t *)(d + take(n * 8));
+  a.sumx = (int64_t *)(d + take(E * 8));
+  a.ccnt = (uint32_t *)(d + take(4 * n * 4));
+  a.segcnt = (uint32_t *)(d + take(4 * n * 4));
+  a.evstart = (uint32_t *)(d + take(n * 4));
+  a.cntx = (uint32_t *)(d + take(E * 4));
+  a.flags = (uint32_t *)(d + take(256));
+  a.per_op = d_per_op; a.mre = d_mre; a.timeline = d_timeline;
+  a.res = d_res;
+  a.res_flags = 1;
+  hipLaunchKernelGGL(ss_scan_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream, a);
+  SS_HIP(hipGetLastError());
+  return SS_OK;
+}
 
 extern "C" int ss_timeline_scan_batch(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev, const ss_event_t *pev,
                                       const uint64_t *pe_start, uint32_t k, uint32_t n_ops, int64_t base,
@@ -413,6 +508,7 @@ extern "C" int ss_timeline_scan(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev
     if (n_ev) SS_HIP(hipMemcpyAsync(d + o_ev, ev, n_ev * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
     if (n_pe) SS_HIP(hipMemcpyAsync(d + o_pev, pev, n_pe * sizeof(ss_event_t), hipMemcpyHostToDevice, s));
     ScanArgs a;
+    a.res_flags = 0;
     a.ev = (const ss_event_t *)(d + o_ev); a.n_ev = n_ev;
     a.pev = (const ss_event_t *)(d + o_pev); a.n_pe = n_pe;
     a.n_ops = n_ops; a.want_timeline = timeline != nullptr;
