@@ -37,8 +37,7 @@ def cpu_baseline(cfgno, bpo):
     import oracle
     import workloads as W
     from workloads.arena import place_tensors
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import record_oracle, ops_tuples, oracle_execute
+    record_oracle, ops_tuples, oracle_execute = oracle.record_trace, oracle.ops_tuples, oracle.execute_schedule
     tr = W.build_trace(W.config_shape(cfgno))
     pol = W.config_swap_set(tr, cfgno)
     idx = pol["ref_op"].astype(np.int64)

@@ -43,9 +43,8 @@ enum {
   SS_E_NOMEM = -2,      /* host, pinned or device allocation failed / staging too small */
   SS_E_HIP = -3,        /* a HIP call failed; code in ss_stats_t.last_hip_error */
   SS_E_INFEASIBLE = -4, /* no candidate left although memory still exceeds the budget (Algo. 2) */
-  SS_E_UNMATCHED = -5,  /* reserved: an item that must match did not */
+  /* -5 and -7 are not used */
   SS_E_ORDER = -6,      /* events not in operator order where that is required */
-  SS_E_UNIMPL = -7,
   SS_E_STATE = -8,      /* call out of sequence (e.g. swap before a schedule is loaded) */
   SS_E_CAPACITY = -9    /* a caller-provided output array or a configured maximum is too small */
 };
@@ -447,8 +446,7 @@ enum { SS_SYNC_FREE = 0,    /* id = tensor: compute stream waits (device-side) f
        SS_SYNC_DRAIN = 2 }; /* host waits for both swap streams; surfaces asynchronous errors      */
 int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id);
 
-/* Sec. 5, first paragraph: "dispatch the swap operations at the designated positions".  Issues, in
- * schedule order, every action that the schedule loaded by the last ss_apply_policy holds for
+/* The executor's step at one operator (Sec. 5, first paragraph): issues, in schedule order, every action that the schedule loaded by the last ss_apply_policy holds for
  * operator op_idx: when = 0, the ones that come before the operator is enqueued (SS_ACT_IN through
  * ss_swap_in once per batch, SS_ACT_WAIT_IN through ss_sync); when = 1, the ones that come after it
  * (SS_ACT_OUT through ss_swap_out once per batch, SS_ACT_FREE through ss_sync).  One call per side

@@ -50,6 +50,7 @@ from .policy import (link_timing, apply_policy, greedy_policy, schedule_check,
 from .swap import swap_out, swap_in, SparseArena
 from .generator import generate_policy, generate_policy_best, logical_layers
 from .align import align, align_anchors, lcs_table, LEVEL_ALIGN
+from .drive import events_by_op, record_trace, ops_tuples, execute_schedule
 
 # The library's call names for the steps that have a one-to-one counterpart here, so that a parity
 # test can address both sides by the same name (recording is TraceRecorder.record; the ordering

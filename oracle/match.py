@@ -83,19 +83,21 @@ class StageMachine:
         return self.step_verdict(similar, tokens)
 
     def step_verdict(self, similar, tokens=None):
-        stage = self.prev_stage
-        if similar:
-            self.stable_step += 1
-            if self.prev_stage == WARMUP and self.stable_step > self.m:
-                stage, self.stable_step = GENPOLICY, 0
-            elif self.prev_stage == GENPOLICY and self.stable_step > self.n:
-                stage = STABLE
+        """One finished iteration.  Similar iterations are counted; WarmUp hands over to GenPolicy once
+        the count exceeds m (and the count starts again), GenPolicy to Stable once it exceeds n (the
+        count runs on); Stable stays.  One dissimilar iteration returns any stage to WarmUp, count 0."""
+        if not similar:
+            self.prev_stage, self.stable_step = WARMUP, 0
         else:
-            stage, self.stable_step = WARMUP, 0
-        self.prev_stage = stage
+            self.stable_step += 1
+            leave_after = {WARMUP: self.m, GENPOLICY: self.n}.get(self.prev_stage)
+            if leave_after is not None and self.stable_step > leave_after:
+                if self.prev_stage == WARMUP:
+                    self.stable_step = 0
+                self.prev_stage = {WARMUP: GENPOLICY, GENPOLICY: STABLE}[self.prev_stage]
         if tokens is not None:
             self.prev_tokens = tokens
-        return stage
+        return self.prev_stage
 
 
 def _key(op, level):

@@ -36,8 +36,7 @@ DESC_DT = np.dtype([("dev_off", "<u8"), ("host_off", "<u8"), ("nbytes", "<u8"),
 ACTION_DT = np.dtype([("op_idx", "<u4"), ("kind", "<u4"), ("tensor_id", "<u4"), ("batch", "<u4")])
 
 SS_OK = 0
-(SS_E_INVAL, SS_E_NOMEM, SS_E_HIP, SS_E_INFEASIBLE, SS_E_UNMATCHED, SS_E_ORDER, SS_E_UNIMPL,
- SS_E_STATE, SS_E_CAPACITY) = range(-1, -10, -1)
+SS_E_INVAL, SS_E_NOMEM, SS_E_HIP, SS_E_INFEASIBLE, SS_E_ORDER, SS_E_STATE, SS_E_CAPACITY = -1, -2, -3, -4, -6, -8, -9
 SS_ACT_IN, SS_ACT_WAIT_IN, SS_ACT_OUT, SS_ACT_FREE = 0, 1, 2, 3
 SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE = 0, 1, 2
 SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE, SS_CFG_POLICY_POINTS = 1, 2, 4, 8, 16

@@ -212,20 +212,28 @@ __global__ __launch_bounds__(256) void ss_injective_kernel(uint32_t k, const int
 
 }  // namespace
 
-// Algo. 1, one step.  Counter first, then the strict comparisons; a stage that
-// neither transition changes stays what it was.
+// The stage machine of Algo. 1 as a table: a stage is left for `next` once more than `patience`
+// consecutive similar iterations have been counted in it (the count includes the current one), and the
+// count starts over if `restart` is set; a stage without a row entry to leave (Stable) only counts.
+// Any dissimilar iteration sends every stage back to WarmUp with the count at zero.
+struct StagePromotion { bool leaves; uint32_t next; bool restart; };
+
 static void stage_step(ss_ctx *ctx, bool similar) {
-  if (similar) {
-    ctx->stable_step += 1;
-    if (ctx->stage == SS_STAGE_WARMUP && ctx->stable_step > ctx->cfg.stage_m) {
-      ctx->stage = SS_STAGE_GENPOLICY;
-      ctx->stable_step = 0;
-    } else if (ctx->stage == SS_STAGE_GENPOLICY && ctx->stable_step > ctx->cfg.stage_n) {
-      ctx->stage = SS_STAGE_STABLE;
-    }
-  } else {
+  if (!similar) {
     ctx->stage = SS_STAGE_WARMUP;
     ctx->stable_step = 0;
+    return;
+  }
+  const uint32_t patience[3] = {ctx->cfg.stage_m, ctx->cfg.stage_n, 0};
+  static const StagePromotion promote[3] = {
+      /* WarmUp    */ {true, SS_STAGE_GENPOLICY, true},
+      /* GenPolicy */ {true, SS_STAGE_STABLE, false},
+      /* Stable    */ {false, SS_STAGE_STABLE, false}};
+  const uint32_t from = ctx->stage;
+  ctx->stable_step += 1;
+  if (from <= SS_STAGE_STABLE && promote[from].leaves && ctx->stable_step > patience[from]) {
+    ctx->stage = promote[from].next;
+    if (promote[from].restart) ctx->stable_step = 0;
   }
 }
 

@@ -32,9 +32,7 @@ extern "C" const char *ss_strerror(int code) {
     case SS_E_NOMEM: return "out of memory (host, pinned or device) or staging too small";
     case SS_E_HIP: return "HIP call failed (see ss_stats_t.last_hip_error)";
     case SS_E_INFEASIBLE: return "no candidate left while memory still exceeds the budget";
-    case SS_E_UNMATCHED: return "policy item without a match";
     case SS_E_ORDER: return "events not in operator order";
-    case SS_E_UNIMPL: return "not implemented";
     case SS_E_STATE: return "call out of sequence";
     case SS_E_CAPACITY: return "output array or configured capacity too small";
     default: return "unknown error";
@@ -477,8 +475,9 @@ static bool use_engine(const ss_ctx *ctx, uint32_t path, bool to_host, const std
   return total / (hi - lo) >= ctx->cfg.engine_min_bytes;
 }
 
-// Marker events are taken round-robin from a ring much longer than the number
-// of markers in flight, so one is never re-recorded while a wait on it is pending.
+// Marker events are taken round-robin from a ring.  Re-recording one is safe however many waits on
+// it are still pending: hipStreamWaitEvent captures the event's state (its most recent record) at the
+// moment it is called, so a later record does not change what an earlier wait waits for.
 static hipEvent_t next_marker(ss_ctx *ctx) {
   hipEvent_t ev = ctx->ev_ring[ctx->ev_next];
   ctx->ev_next = (ctx->ev_next + 1) % ctx->ev_ring.size();

@@ -5,18 +5,9 @@ import oracle
 import workloads as W
 
 
-def events_by_op(tr):
-    ev = tr.events
-    bounds = np.searchsorted(ev["op_idx"], np.arange(tr.n_ops + 1))
-    return [ev[bounds[i]:bounds[i + 1]] for i in range(tr.n_ops)]
-
-
-def record_oracle(rec, tr):
-    rec.begin()
-    for i, evs in enumerate(events_by_op(tr)):
-        op = rec.intern(tr.op_name[i], tr.op_stack[i], tr.op_dtype[i], len(tr.op_outputs[i]), tr.op_phase[i])
-        rec.record(op, [tuple(e) for e in evs.tolist()])
-    return rec.ops_array(), rec.events_array()
+from oracle import events_by_op, ops_tuples                    # noqa: E402,F401
+from oracle import record_trace as record_oracle                # noqa: E402,F401
+from oracle import execute_schedule as oracle_execute           # noqa: E402,F401
 
 
 def record_lib(P, ctx, tr):
@@ -26,10 +17,6 @@ def record_lib(P, ctx, tr):
                             tr.op_phase[i])
         P.ss_trace_record(ctx, op, evs if len(evs) else None)
     return P.ss_trace_view(ctx)
-
-
-def ops_tuples(ops):
-    return [tuple(int(x) for x in o) for o in ops.tolist()]
 
 
 def applied_as_arrays(ap):
@@ -61,37 +48,85 @@ def assert_applied_equal(lib, P, ctx, ora):
         assert np.array_equal(dep, o["in_dep"])
 
 
-def oracle_execute(arena, staging, ap, poison=None, writes=None):
-    """Sequential reading of an action schedule on NumPy byte arrays.
+class WindowStaging:
+    """A staging area of which only the windows ever written are kept, so that oracle.swap_out can
+    write a slot at its real offset of a 50 GB staging area without 50 GB of host memory."""
 
-    ap: oracle.apply_policy result.  poison: byte written over a block at its
-    FREE action (or None).  writes: optional dict op_idx -> list of
-    (dev_off, bytes) the operator itself writes into the arena.
+    def __init__(self):
+        self.win = {}
+
+    def __setitem__(self, sl, data):
+        self.win[(int(sl.start), int(sl.stop))] = np.array(data, dtype=np.uint8, copy=True)
+
+    def __getitem__(self, sl):
+        return self.win[(int(sl.start), int(sl.stop))]
+
+
+class ByteProbe:
+    """Byte parity of sampled swapped tensors inside a running iteration, against the oracle.
+
+    For every sampled tensor the bytes of its block are captured on the compute stream right after the
+    operator of its last forward use (what swap-out must carry away) and right before the operator of its
+    first backward use (what swap-in must have brought back, into dev_off_in).  check() then applies
+    oracle.swap_out / oracle.swap_in to the captured source and compares: the staging slot (read through
+    ss_host_peek) with the oracle's staging window, the returned block with the oracle's arena block.
     """
-    os_, is_ = ap["out_batch_start"], ap["in_batch_start"]
-    d_out = {d[3]: d for d in ap["descs_out"]}
-    done_out, done_in = set(), set()
-    acts = ap["actions"]
-    i = 0
-    n_ops = (max(a[0] for a in acts) + 1) if acts else 0
-    if writes:
-        n_ops = max(n_ops, max(writes) + 1)
-    for op in range(n_ops):
-        while i < len(acts) and acts[i][0] == op and acts[i][1] in (oracle.K_IN, oracle.K_WAIT_IN):
-            _, kind, tid, b = acts[i]
-            if kind == oracle.K_IN and b not in done_in:
-                oracle.swap_in(arena, staging, ap["descs_in"][is_[b]:is_[b + 1]])
-                done_in.add(b)
-            i += 1
-        for (off, data) in (writes or {}).get(op, ()):
-            arena[off:off + len(data)] = data
-        while i < len(acts) and acts[i][0] == op:
-            _, kind, tid, b = acts[i]
-            if kind == oracle.K_OUT and b not in done_out:
-                oracle.swap_out(arena, staging, ap["descs_out"][os_[b]:os_[b + 1]])
-                done_out.add(b)
-            elif kind == oracle.K_FREE and poison is not None:
-                d = d_out[tid]
-                arena[d[0]:d[0] + d[2]] = poison
-            i += 1
-    assert i == len(acts)
+
+    def __init__(self, torch, arena, applied, sample_ids):
+        self.torch, self.arena = torch, arena
+        res = applied["resolved"]
+        self.items = {int(r["tensor_id"]): r for r in res if int(r["tensor_id"]) in sample_ids
+                      and not int(r["flags"]) & 3}
+        self.d_out = {int(d["tensor_id"]): d for d in applied["descs_out"] if int(d["tensor_id"]) in self.items}
+        self.d_in = {int(d["tensor_id"]): d for d in applied["descs_in"] if int(d["tensor_id"]) in self.items}
+        self.at_out, self.at_use = {}, {}
+        for tid, r in self.items.items():
+            self.at_out.setdefault(int(r["t_out"]), []).append(tid)
+            self.at_use.setdefault(int(r["t_use"]), []).append(tid)
+        self.src, self.back = {}, {}
+
+    def before_op(self, i):
+        for tid in self.at_use.get(i, ()):
+            d = self.d_in[tid]
+            self.back[tid] = self.arena[int(d["dev_off"]):int(d["dev_off"]) + int(d["nbytes"])].clone()
+
+    def after_op(self, i):
+        for tid in self.at_out.get(i, ()):
+            d = self.d_out[tid]
+            self.src[tid] = self.arena[int(d["dev_off"]):int(d["dev_off"]) + int(d["nbytes"])].clone()
+
+    def check(self, P, ctx):
+        """after the iteration has drained; returns the number of bytes compared each way"""
+        assert set(self.src) == set(self.back) == set(self.items) and self.items
+        total = 0
+        for tid in sorted(self.items):
+            do, di = self.d_out[tid], self.d_in[tid]
+            n = int(do["nbytes"])
+            src = self.src[tid].cpu().numpy()
+            sp = oracle.SparseArena()
+            sp.put(int(do["dev_off"]), src)
+            st = WindowStaging()
+            oracle.swap_out(sp, st, [tuple(int(x) for x in do.tolist())])
+            want = st[slice(int(do["host_off"]), int(do["host_off"]) + n)]
+            got = P.ss_host_peek(ctx, int(do["host_off"]), n)
+            assert np.array_equal(got, want), "staging slot of tensor %d" % tid
+            sp2 = oracle.SparseArena()
+            oracle.swap_in(sp2, st, [tuple(int(x) for x in di.tolist())])
+            assert np.array_equal(self.back[tid].cpu().numpy(), sp2.read(int(di["dev_off"]), n)), \
+                "returned block of tensor %d" % tid
+            total += n
+        return total
+
+
+def stratified_sample(applied, per_class, seed):
+    """tensor ids of swapped tensors: `per_class` of every distinct size, chosen by a seeded shuffle"""
+    from workloads.rng import SplitMix64
+    by_size = {}
+    for d in applied["descs_out"]:
+        by_size.setdefault(int(d["nbytes"]), []).append(int(d["tensor_id"]))
+    out = set()
+    for k, size in enumerate(sorted(by_size)):
+        ids = by_size[size]
+        perm = SplitMix64(seed, k).permutation(len(ids))
+        out.update(ids[j] for j in list(perm)[:per_class])
+    return out

@@ -394,3 +394,61 @@ def test_link_probe_and_batch_windows(P, torch):
         assert torch.equal(arena, want)
     finally:
         P.ss_destroy(ctx)
+
+
+@pytest.mark.timeout(300)
+def test_copy_kernel_on_gib_tensors_and_a_batch_above_4_gib(P, torch):
+    """the copy kernel itself (both directions forced to it) on tensors of the budgeted configurations'
+    sizes in ONE batch of 4.66 GiB: 1 GiB + 15 bytes, 1 GiB, 2 GiB (chunk offsets beyond 32 bits),
+    512 MiB - 16, 128 MiB + 1, 32 MiB, at scattered places of a 7 GiB arena; the staging image (with
+    guards) and the arena after the return into other blocks equal the oracle's byte copies"""
+    G = 1 << 30
+    sizes = [G + 15, G, 2 * G, (512 << 20) - 16, (128 << 20) + 1, 32 << 20, 1 << 20]
+    guard = 256
+    arena_bytes = 7 * G
+    arena = random_arena(torch, arena_bytes, 77)
+    # scattered, unordered source blocks; the tensors return into the mirror-image order of blocks
+    order = [3, 0, 5, 2, 6, 1, 4]
+    src_off, off = {}, 4096
+    for i in order:
+        src_off[i] = off
+        off += (sizes[i] + 4095) // 4096 * 4096 + 8192
+    assert off <= arena_bytes
+    dst_off, off = {}, 4096
+    for i in reversed(order):
+        dst_off[i] = off
+        off += (sizes[i] + 4095) // 4096 * 4096 + 8192
+    d_out = np.zeros(len(sizes), dtype=W.DESC_DT)
+    d_in = np.zeros(len(sizes), dtype=W.DESC_DT)
+    h = guard
+    for i, n in enumerate(sizes):
+        d_out[i] = (src_off[i], h, n, i, 0)
+        d_in[len(sizes) - 1 - i] = (dst_off[i], h, n, i, 0)
+        h += (n + 255) // 256 * 256 + guard
+    start = np.array([0, len(sizes)], dtype=np.uint32)
+    assert sum(sizes) > 4 * G
+    host = arena.cpu().numpy().copy()
+    ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_KERNEL, copy_path_in=P.SS_PATH_KERNEL, guard_bytes=guard)
+    try:
+        P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+        P.ss_staging_fill(ctx, 0xA5)
+        P.ss_load_schedule(ctx, d_out, start, d_in, start)
+        P.ss_swap_out(ctx, 0)
+        for i in range(len(sizes)):
+            P.ss_sync(ctx, P.SS_SYNC_FREE, i)
+        arena.fill_(0x3C)                       # compute stream: the released blocks are overwritten
+        P.ss_swap_in(ctx, 0)
+        for i in range(len(sizes)):
+            P.ss_sync(ctx, P.SS_SYNC_WAIT_IN, i)
+        P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+        torch.cuda.synchronize()
+        staging = np.full(h, 0xA5, dtype=np.uint8)
+        oracle.swap_out(host, staging, [tuple(int(x) for x in r) for r in d_out.tolist()])
+        assert np.array_equal(P.ss_host_peek(ctx, 0, h), staging)
+        host[:] = 0x3C
+        oracle.swap_in(host, staging, [tuple(int(x) for x in r) for r in d_in.tolist()])
+        assert np.array_equal(arena.cpu().numpy(), host)
+        st = P.ss_get_stats(ctx)
+        assert st["engine_batches"] == 0 and st["kernel_batches"] == 2
+    finally:
+        P.ss_destroy(ctx)

@@ -116,6 +116,9 @@ class SwapRun:
         self.bytes_each_way = int(ap["bytes_out"])
         self.last = {}
         self.host_ms_log = []
+        # optional callbacks of a checker: before_op(i) runs after the actions scheduled before operator i
+        # and before the operator itself, after_op(i) after the operator and before the actions after it
+        self.before_op = self.after_op = None
 
     def close(self):
         if self.ctx is not None:
@@ -148,12 +151,16 @@ class SwapRun:
         B = self.B
         plan = self.plan()
         B.ss_trace_begin(self.ctx)
-        rec, comp = self.record, self.compute
+        rec, comp, pre, post = self.record, self.compute, self.before_op, self.after_op
 
         def run_op(i):
             rec(i)
+            if pre is not None:
+                pre(i)
             if comp is not None:
                 comp.run_op(i)
+            if post is not None:
+                post(i)
         run_iteration_dispatch(self.ctx, self.tr.n_ops, run_op, plan["points"])
 
     def step_noswap(self):
@@ -172,7 +179,8 @@ class VaryingRun:
     """
 
     def __init__(self, B, torch, shape, budget, bpo, bpo_in=0, min_bytes=0, perturb=None, seed=2509,
-                 flags=0, compute=True, gemm_scale=1.0, arena_slack=1.25, staging_slack=1.4, match_flags=0):
+                 flags=0, compute=True, gemm_scale=1.0, arena_slack=1.25, staging_slack=1.4, match_flags=0,
+                 copy_path=0, copy_path_in=None, staging_bytes=None):
         self.B, self.torch, self.shape = B, torch, shape
         self.budget, self.min_bytes, self.perturb, self.seed = budget, min_bytes, perturb, seed
         self.do_compute, self.gemm_scale = compute, gemm_scale
@@ -181,6 +189,8 @@ class VaryingRun:
         cfg.link_bytes_per_op = bpo
         cfg.prefetch_bytes_per_op = bpo_in
         cfg.flags = flags
+        cfg.copy_path = copy_path
+        cfg.copy_path_in = copy_path if copy_path_in is None else copy_path_in
         cfg.staging_bytes = 0
         self.cfg = cfg
         self.plan_ctx = B.ss_create(cfg)
@@ -194,7 +204,7 @@ class VaryingRun:
         cfg2 = B.ss_config_default()
         for f, _t in cfg._fields_:
             setattr(cfg2, f, getattr(cfg, f))
-        cfg2.staging_bytes = int(ap["staging_bytes"] * staging_slack) + (1 << 20)
+        cfg2.staging_bytes = staging_bytes or int(ap["staging_bytes"] * staging_slack) + (1 << 20)
         self.exec_ctx = B.ss_create(cfg2) if compute else None      # planning alone needs no staging
         self.staging_bytes = cfg2.staging_bytes
         self.arena = None
@@ -254,8 +264,10 @@ class VaryingRun:
                     host_ms=dict(match=(t1 - t0) * 1e3, apply=(t2 - t1) * 1e3, scan=(t3 - t2) * 1e3,
                                  top_up_apply_scan=(t4 - t3) * 1e3))
 
-    def execute(self, p):
-        """place this iteration's tensors, bind, load the schedule, run the operators with swapping"""
+    def execute(self, p, checker=None):
+        """place this iteration's tensors, bind, load the schedule, run the operators with swapping.
+        checker (optional): called as checker(tr, ap) once the schedule is loaded; returns (before_op,
+        after_op) callbacks run around every operator on the compute stream"""
         from .compute import SyntheticCompute
         from paper_2509_11076_amd.executor import run_iteration_dispatch, dispatch_points
         B, tr = self.B, p["trace"]
@@ -269,10 +281,15 @@ class VaryingRun:
         comp.mark_swapped(swapped.keys())
         rec = B.ss_trace_record_prepared(self.exec_ctx, p["ops"], tr.events)
         B.ss_trace_begin(self.exec_ctx)
+        pre, post = checker(tr, ap) if checker is not None else (None, None)
 
         def run_op(i):
             rec(i)
+            if pre is not None:
+                pre(i)
             comp.run_op(i)
+            if post is not None:
+                post(i)
         run_iteration_dispatch(self.exec_ctx, tr.n_ops, run_op, dispatch_points(ap["actions"]))
         return comp.result(), used, ap
 
