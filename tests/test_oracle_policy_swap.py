@@ -97,6 +97,47 @@ def test_link_timing_instantaneous_link():
     assert valid == [False]
 
 
+def instant_rule(t_out, t_use):
+    """Release and pre-trigger points under a link so fast that every transfer fits inside one operator,
+    written out from the rule itself (nothing here calls the oracle): a block is released after the
+    operator that follows the swap-out's issue point; a swap-in is issued one operator before the use,
+    but not before the last swap-out of the set has been issued, not before the item's own release, and,
+    walking the items in order of need (first use, then index), never before an item needed earlier."""
+    k = len(t_out)
+    t_free = [t_out[i] + 1 for i in range(k)]
+    after_last_out = max(t_out) + 1 if k else 0
+    t_in = [max(t_use[i] - 1, after_last_out, t_free[i] + 1) for i in range(k)]
+    run = 0
+    for i in sorted(range(k), key=lambda i: (t_use[i], i)):
+        t_in[i] = run = max(t_in[i], run)
+    return t_free, t_in
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_link_timing_instantaneous_link_equals_the_rule(seed):
+    rng = SplitMix64(seed, 41)
+    k = 1 + rng.randint(9)
+    t_out = [rng.randint(12) for _ in range(k)]
+    # each item has room for its own round trip; uses may come before the set's last swap-out is issued
+    # (then the swap-in lands after the use, which policy application later rejects) and may coincide
+    t_use = [t_out[i] + 2 + rng.randint(8) for i in range(k)]
+    nbytes = [1 + rng.randint(1 << 30) for _ in range(k)]
+    want_free, want_in = instant_rule(t_out, t_use)
+    t_free, t_in, late, valid = oracle.link_timing(t_out, t_use, nbytes, INSTANT)
+    assert valid == [True] * k and t_free == want_free and t_in == want_in
+
+
+def test_link_timing_instantaneous_link_rule_by_hand():
+    # two items used by the same operator 12; the first leaves after operator 10 (released after 11, so not
+    # back before 12), the second after operator 0 and could be back at 11 - but it is needed no earlier
+    # than the first and queues behind it: 12 as well.  A third, used at 9 before the last swap-out (after
+    # operator 10) has been issued, is held until 11: past its use.
+    assert instant_rule([10, 0, 0], [12, 12, 9]) == ([11, 1, 1], [12, 12, 11])
+    t_free, t_in, late, valid = oracle.link_timing([10, 0, 0], [12, 12, 9], [5, 5, 5], INSTANT)
+    assert (t_free, t_in) == ([11, 1, 1], [12, 12, 11])
+    assert late == [True, False, True]          # LATE marks the items the two floors held back, not the queueing
+
+
 def applied_for(cfg, bpo, guard=0):
     tr = W.build_trace(W.config_shape(cfg))
     pol = W.config_swap_set(tr, cfg)
@@ -247,23 +288,22 @@ def test_greedy_on_tiny_traces_against_brute_force(seed):
     rows, ap = oracle.greedy_policy(tab, ev, n_ops, base, budget, INSTANT)
     chosen = [r[2] for r in rows]
     res = oracle.timeline_scan(ev, ap["policy_events"], n_ops, base, budget)
-    # the scan's verdict on the chosen set is the brute-force (live-set) peak of that set at the points
-    # the schedule gives its items (a swap-in held back behind the last swap-out comes later than fb - 1)
-    points = {r[2]: (r[5], r[6]) for r in ap["resolved"]}
-    assert res["peak"] == int(live_set_peak(tab, points, n_ops, base).max()) <= budget
-    assert all(points[i][0] == tab["last_fwd_use"][i] + 1 and
-               tab["first_bwd_use"][i] - 1 <= points[i][1] <= tab["first_bwd_use"][i] for i in chosen)
-    # greedy stops at the first prefix that fits: one item fewer does not fit
+    # the points every chosen item must get under an instantaneous link, from the rule written out above
+    # (not read from the oracle's output), and the oracle's points compared with them one by one
+    def rule_points(ids):
+        tf, ti = instant_rule([int(tab["last_fwd_use"][i]) for i in ids], [int(tab["first_bwd_use"][i]) for i in ids])
+        return {i: (tf[q], ti[q]) for q, i in enumerate(ids)}
+    want = rule_points(chosen)
+    got = {r[2]: (r[5], r[6]) for r in ap["resolved"]}
+    assert got == want and all(not r[3] & (oracle.F_UNMATCHED | oracle.F_ORDER) for r in ap["resolved"])
+    # the scan's verdict on the chosen set is the brute-force (live-set) peak of that set at those points
+    assert res["peak"] == int(live_set_peak(tab, want, n_ops, base).max()) <= budget
+    assert all(want[i][1] <= tab["first_bwd_use"][i] for i in chosen)
+    # greedy stops at the first prefix that fits: one item fewer, timed by the same rule, does not fit
     if chosen:
-        # greedy_policy with rows already in force and no budget pressure just times those rows
-        _, ap1 = oracle.greedy_policy(tab, ev, n_ops, base, 1 << 60, INSTANT, initial=rows[:-1])
-        less = {r[2]: (r[5], r[6]) for r in ap1["resolved"]}
-        assert int(live_set_peak(tab, less, n_ops, base).max()) > budget
+        assert int(live_set_peak(tab, rule_points(chosen[:-1]), n_ops, base).max()) > budget
     # with an instantaneous link the peak never rises as items are added
-    peaks = []
-    for i in range(len(rows) + 1):
-        _, api = oracle.greedy_policy(tab, ev, n_ops, base, 1 << 60, INSTANT, initial=rows[:i])
-        peaks.append(int(live_set_peak(tab, {r[2]: (r[5], r[6]) for r in api["resolved"]}, n_ops, base).max()))
+    peaks = [int(live_set_peak(tab, rule_points(chosen[:i]), n_ops, base).max()) for i in range(len(chosen) + 1)]
     assert peaks[0] == no["peak"] and all(b <= a for a, b in zip(peaks, peaks[1:]))
     # order: longest idle span first
     idle = [int(tab["first_bwd_use"][i]) - int(tab["last_fwd_use"][i]) for i in chosen]
