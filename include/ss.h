@@ -108,9 +108,12 @@ enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch
                                     compute stream waiting) instead of dropping them            */
        SS_CFG_SYSTEM_FENCE = 8,  /* ordering events carry a system-scope fence (default: device
                                     scope; the host reads staging only after a synchronisation) */
-       SS_CFG_POLICY_POINTS = 16 };/* ss_apply_policy keeps each item's own t_free / t_in (as made by
+       SS_CFG_POLICY_POINTS = 16,/* ss_apply_policy keeps each item's own t_free / t_in (as made by
                                     ss_generate_policy), moved along with the tensor's last forward /
                                     first backward use, instead of re-timing with the link model  */
+       SS_CFG_STALL_TIMING = 32 };/* measurement mode: one more event on the compute stream before every
+                                    device-side wait, and SS_SYNC_DRAIN also waits for the compute stream
+                                    and adds the waits' durations to ss_stats_t.stall_*_ms          */
 
 typedef struct {
   uint64_t staging_bytes;     /* pinned host staging to allocate at ss_create                */
@@ -135,6 +138,11 @@ typedef struct {
                                  that the copy engine falls far behind the link inside a running
                                  training step, above it it reaches the link peak and, unlike a copy
                                  kernel, does not delay the compute stream's launches); 0 = never   */
+  uint32_t out_streams;       /* streams the copy-kernel swap-out batches take in turn, 1..4 (0 = 2): with
+                                 two, a launch's set-up and its wait for free compute units hide behind the
+                                 launch before it, which is still moving data                      */
+  uint32_t in_streams;        /* the same for copy-kernel swap-in batches (0 = 2); copy-engine batches of
+                                 either direction always use one stream                            */
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */
@@ -182,6 +190,18 @@ typedef struct {
   uint64_t ops_recorded, events_recorded;
   int32_t last_hip_error;               /* hipError_t of the last failing HIP call, 0 if none */
   uint32_t engine_batches_out;          /* of engine_batches, the swap-out ones             */
+  /* anchors placed by ss_match_sequence / ss_align_sequence since ss_create, by the level that placed
+   * them: [0] (token, stack, sig), [1] (token, sig), [2] (token), [3] sequence alignment, [4] unmatched */
+  uint64_t match_levels[5];
+  /* memory-block reuse interval of the loaded schedule (Sec. 6.4): per swapped tensor the number of
+   * operators between issuing its swap-out and releasing its block (t_free - t_out); bucket b counts
+   * the tensors with floor(log2(interval + 1)) == b (b = 15: that or more); sum and count give the mean */
+  uint32_t reuse_hist[16];
+  uint64_t reuse_sum, reuse_count;
+  /* with SS_CFG_STALL_TIMING: time the compute stream spent inside the device-side waits of
+   * SS_SYNC_FREE / SS_SYNC_WAIT_IN (from the moment it reached the wait to the end of the batch it
+   * waited for, 0 if that had already ended), summed over the iterations drained so far */
+  double stall_free_ms, stall_wait_in_ms;
 } ss_stats_t;
 
 typedef struct {

@@ -40,6 +40,7 @@ SS_E_INVAL, SS_E_NOMEM, SS_E_HIP, SS_E_INFEASIBLE, SS_E_ORDER, SS_E_STATE, SS_E_
 SS_ACT_IN, SS_ACT_WAIT_IN, SS_ACT_OUT, SS_ACT_FREE = 0, 1, 2, 3
 SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE = 0, 1, 2
 SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE, SS_CFG_POLICY_POINTS = 1, 2, 4, 8, 16
+SS_CFG_STALL_TIMING = 32
 SS_SYNC_FREE, SS_SYNC_WAIT_IN, SS_SYNC_DRAIN = 0, 1, 2
 SS_MATCH_STEP_STAGE, SS_MATCH_HISTOGRAM, SS_MATCH_ALIGN = 1, 2, 4
 SS_LEVEL_ALIGN = 3
@@ -55,7 +56,8 @@ class ss_config_t(C.Structure):
                 ("copy_path_in", C.c_uint32),
                 ("copy_workgroups", C.c_uint32), ("copy_workgroups_out", C.c_uint32),
                 ("copy_unroll", C.c_uint32), ("max_ops", C.c_uint32), ("max_events", C.c_uint32),
-                ("flags", C.c_uint32), ("engine_min_bytes_out", C.c_uint64)]
+                ("flags", C.c_uint32), ("engine_min_bytes_out", C.c_uint64),
+                ("out_streams", C.c_uint32), ("in_streams", C.c_uint32)]
 
 
 class ss_scan_result_t(C.Structure):
@@ -93,7 +95,10 @@ class ss_stats_t(C.Structure):
     _fields_ = [("bytes_out", C.c_uint64), ("bytes_in", C.c_uint64), ("kernel_batches", C.c_uint64),
                 ("engine_batches", C.c_uint64), ("free_waits", C.c_uint64), ("in_waits", C.c_uint64),
                 ("ops_recorded", C.c_uint64), ("events_recorded", C.c_uint64),
-                ("last_hip_error", C.c_int32), ("engine_batches_out", C.c_uint32)]
+                ("last_hip_error", C.c_int32), ("engine_batches_out", C.c_uint32),
+                ("match_levels", C.c_uint64 * 5), ("reuse_hist", C.c_uint32 * 16),
+                ("reuse_sum", C.c_uint64), ("reuse_count", C.c_uint64),
+                ("stall_free_ms", C.c_double), ("stall_wait_in_ms", C.c_double)]
 
 
 class ss_bw_t(C.Structure):
@@ -517,4 +522,5 @@ def ss_bw_probe(ctx, nbytes=1 << 30, reps=10):
 def ss_get_stats(ctx):
     st = ss_stats_t()
     _ck(_lib.ss_get_stats(ctx, C.byref(st)), "ss_get_stats")
-    return {f: getattr(st, f) for f, _ in ss_stats_t._fields_}
+    return {f: (list(getattr(st, f)) if hasattr(getattr(st, f), "__len__") else getattr(st, f))
+            for f, _ in ss_stats_t._fields_}

@@ -220,6 +220,7 @@ extern "C" int ss_align_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n_ref
     res->distance = n_ref + n_cur - 2 * lcs;
     res->n_keys = n_keys;
     ss_align_anchors(ref, n_ref, cur, ref_to_cur, anchors, n_anchors, new_idx, level, &res->n_unmatched);
+    for (uint32_t a = 0; a < n_anchors; ++a) ctx->stats.match_levels[level[a] <= SS_LEVEL_ALIGN ? level[a] : 4]++;
     return SS_OK;
   });
 }

@@ -9,7 +9,8 @@
 // small batch so that every workgroup of the grid has work), a small
 // persistent grid walks the chunks, and each workgroup looks its chunk's
 // descriptor up in a per-chunk table built when the schedule is loaded (two
-// dependent loads per chunk, no search, no LDS).  All
+// dependent loads per chunk, no search, no LDS), and the loads of one block are
+// issued before the stores of the block before it (software pipelining).  All
 // traffic is 16 bytes per lane, a wavefront touching 1 KiB of consecutive
 // addresses on both sides; a byte tail handles sizes that are not multiples of
 // 16.  The staging area is host memory mapped into the device address space,
@@ -24,42 +25,110 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// kUnroll 16-byte accesses are in flight per lane before the first store is issued.
+// One block of a chunk: at most SS_COPY_THREADS * kUnroll 16-byte vectors, plus (last block of a
+// tensor only) a tail of fewer than 16 bytes.
+struct CopyBlock {
+  const u32x4 *src;
+  u32x4 *dst;
+  uint32_t n16;      // vectors in this block
+  uint32_t tail;     // bytes after them (0..15)
+};
+
+// Walks the blocks one workgroup is responsible for: chunks blockIdx.x, blockIdx.x + gridDim.x, ...,
+// each chunk cut into blocks of SS_COPY_THREADS * kUnroll vectors.
 template <bool TO_HOST, uint32_t kUnroll>
-__global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
-    uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
-    const uint32_t *__restrict__ chunk0, const uint32_t *__restrict__ chunk_desc, uint32_t n_chunks,
-    uint32_t chunk_shift) {
-  const uint32_t chunk_bytes = 1u << chunk_shift;     // 4 KiB .. 64 KiB, chosen per batch
-  const uint32_t tid = threadIdx.x;
-  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+struct BlockWalk {
+  uint8_t *arena, *staging;
+  const ss_desc_t *descs;
+  const uint32_t *chunk0, *chunk_desc;
+  uint32_t n_chunks, chunk_shift;
+  uint32_t c;          // current chunk
+  uint32_t done16;     // vectors of the current chunk already handed out
+  uint32_t left16;     // vectors of the current chunk still to hand out
+  uint32_t tail;       // byte tail of the current chunk
+  const uint8_t *src;
+  uint8_t *dst;
+
+  __device__ bool open_chunk() {
+    if (c >= n_chunks) return false;
     // chunk_desc[c]: the descriptor chunk c belongs to; chunk0[d]: first chunk of descriptor d
     const uint32_t lo = chunk_desc[c];
     const ss_desc_t d = descs[lo];
     const uint64_t off = (uint64_t)(c - chunk0[lo]) << chunk_shift;
     const uint64_t left = d.nbytes - off;
-    const uint32_t n = left < chunk_bytes ? (uint32_t)left : chunk_bytes;
-    const uint8_t *src = TO_HOST ? arena + d.dev_off + off : staging + d.host_off + off;
-    uint8_t *dst = TO_HOST ? staging + d.host_off + off : arena + d.dev_off + off;
-
-    const u32x4 *src16 = reinterpret_cast<const u32x4 *>(src);
-    u32x4 *dst16 = reinterpret_cast<u32x4 *>(dst);
-    const uint32_t n16 = n >> 4;
-    for (uint32_t base = 0; base < n16; base += SS_COPY_THREADS * kUnroll) {
-      u32x4 v[kUnroll];
-#pragma unroll
-      for (uint32_t u = 0; u < kUnroll; ++u) {
-        const uint32_t i = base + u * SS_COPY_THREADS + tid;
-        if (i < n16) v[u] = __builtin_nontemporal_load(src16 + i);
-      }
-#pragma unroll
-      for (uint32_t u = 0; u < kUnroll; ++u) {
-        const uint32_t i = base + u * SS_COPY_THREADS + tid;
-        if (i < n16) __builtin_nontemporal_store(v[u], dst16 + i);
-      }
+    const uint32_t n = left < (1ull << chunk_shift) ? (uint32_t)left : (1u << chunk_shift);
+    src = TO_HOST ? arena + d.dev_off + off : staging + d.host_off + off;
+    dst = TO_HOST ? staging + d.host_off + off : arena + d.dev_off + off;
+    done16 = 0;
+    left16 = n >> 4;
+    tail = n & 15u;          // only the last chunk of a tensor can have one
+    return true;
+  }
+  // next block, or false when this workgroup has no more; a chunk of fewer than 16 bytes yields one
+  // block without vectors
+  __device__ bool next(CopyBlock &b) {
+    while (left16 == 0 && tail == 0) {
+      c += gridDim.x;
+      if (!open_chunk()) return false;
     }
-    const uint32_t tail = n & 15u;          // only the last chunk of a tensor can have one
-    if (tid < tail) dst[(n16 << 4) + tid] = src[(n16 << 4) + tid];
+    const uint32_t take = left16 < SS_COPY_THREADS * kUnroll ? left16 : SS_COPY_THREADS * kUnroll;
+    b.src = reinterpret_cast<const u32x4 *>(src) + done16;
+    b.dst = reinterpret_cast<u32x4 *>(dst) + done16;
+    b.n16 = take;
+    done16 += take;
+    left16 -= take;
+    b.tail = left16 == 0 ? tail : 0;
+    if (left16 == 0) tail = 0;
+    return true;
+  }
+};
+
+// Software-pipelined: the kUnroll loads per lane of the next block are issued before the stores of the
+// current one, so that each lane keeps requests on the host link in flight all the time (the link is a
+// long pipe: what saturates it is bytes in flight, and with this a dozen workgroups hold as many as
+// sixty-four did when loads and stores took turns).
+template <bool TO_HOST, uint32_t kUnroll>
+__global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
+    uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
+    const uint32_t *__restrict__ chunk0, const uint32_t *__restrict__ chunk_desc, uint32_t n_chunks,
+    uint32_t chunk_shift) {
+  const uint32_t tid = threadIdx.x;
+  BlockWalk<TO_HOST, kUnroll> w;
+  w.arena = arena; w.staging = staging; w.descs = descs; w.chunk0 = chunk0; w.chunk_desc = chunk_desc;
+  w.n_chunks = n_chunks; w.chunk_shift = chunk_shift;
+  w.c = blockIdx.x;
+  if (!w.open_chunk()) return;
+  CopyBlock cur, nxt;
+  if (!w.next(cur)) return;
+  u32x4 a[kUnroll], b[kUnroll];
+  uint8_t ta = 0, tb = 0;
+#pragma unroll
+  for (uint32_t u = 0; u < kUnroll; ++u) {
+    const uint32_t i = u * SS_COPY_THREADS + tid;
+    if (i < cur.n16) a[u] = __builtin_nontemporal_load(cur.src + i);
+  }
+  if (tid < cur.tail) ta = reinterpret_cast<const uint8_t *>(cur.src + cur.n16)[tid];
+  for (;;) {
+    const bool more = w.next(nxt);
+    if (more) {
+#pragma unroll
+      for (uint32_t u = 0; u < kUnroll; ++u) {
+        const uint32_t i = u * SS_COPY_THREADS + tid;
+        if (i < nxt.n16) b[u] = __builtin_nontemporal_load(nxt.src + i);
+      }
+      if (tid < nxt.tail) tb = reinterpret_cast<const uint8_t *>(nxt.src + nxt.n16)[tid];
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kUnroll; ++u) {
+      const uint32_t i = u * SS_COPY_THREADS + tid;
+      if (i < cur.n16) __builtin_nontemporal_store(a[u], cur.dst + i);
+    }
+    if (tid < cur.tail) reinterpret_cast<uint8_t *>(cur.dst + cur.n16)[tid] = ta;
+    if (!more) break;
+#pragma unroll
+    for (uint32_t u = 0; u < kUnroll; ++u) a[u] = b[u];
+    ta = tb;
+    cur = nxt;
   }
 }
 

@@ -36,7 +36,12 @@ struct ss_sched {
   std::unordered_map<uint32_t, uint32_t> out_of_tensor, in_of_tensor;  // tensor id -> descriptor index
   std::vector<uint32_t> out_batch_of, in_batch_of;                      // descriptor index -> batch
   std::vector<uint8_t> out_waited, in_waited, out_issued, in_issued;    // per batch, this iteration
-  std::vector<hipEvent_t> ev_out_done, ev_in_done, ev_out_start, ev_in_start;
+  // Per-batch events exist twice: iterations alternate between the two sets (`phase`, switched by the
+  // drain), so that the timing of the iteration drained last stays readable while the next one runs.
+  std::vector<hipEvent_t> ev_out_done[2], ev_in_done[2], ev_out_start[2], ev_in_start[2];
+  std::vector<hipEvent_t> ev_free_at, ev_wait_at;   // SS_CFG_STALL_TIMING: compute stream reaches the wait for the batch
+  int phase = 0;                                    // event set of the iteration being issued
+  bool drained_once = false;                        // set `phase ^ 1` holds a completed iteration
   ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
   uint32_t *d_out_chunk0 = nullptr, *d_in_chunk0 = nullptr;
   uint32_t *d_out_cdesc = nullptr, *d_in_cdesc = nullptr;
@@ -62,7 +67,11 @@ struct ss_ctx {
   // owned
   uint8_t *staging = nullptr;       // pinned, host address
   uint8_t *staging_dev = nullptr;   // same memory, device address
-  hipStream_t s_out = nullptr, s_in = nullptr, s_aux = nullptr;
+  // swap streams: kernel batches of a direction take its streams in turn (cfg.out_streams / in_streams of
+  // them), copy-engine batches always the first
+  static constexpr int kMaxSwapStreams = 4;
+  hipStream_t s_out[kMaxSwapStreams] = {}, s_in[kMaxSwapStreams] = {}, s_aux = nullptr;
+  uint32_t n_s_out = 1, n_s_in = 1;
   std::vector<hipEvent_t> ev_ring;  // compute-stream markers, used round-robin
   size_t ev_next = 0;
   // trace

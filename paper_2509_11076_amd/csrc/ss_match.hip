@@ -245,6 +245,59 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
     if (k && (!anchors || !new_idx || !level)) return SS_E_INVAL;
     if (n > kLenLimit || m > kLenLimit || k > (1u << 24)) return SS_E_INVAL;
     const bool hist = (flags & SS_MATCH_HISTOGRAM) != 0;
+    const bool aligned = (flags & SS_MATCH_ALIGN) != 0;
+    // verdict, stage machine and counters from the three sums: the same for both routes below
+    auto finish = [&](const uint64_t sm[3], uint32_t unm) {
+      res->dot = sm[0]; res->na = sm[1]; res->nb = sm[2];
+      bool similar;
+      if (n == 0 && m == 0) {
+        similar = true;
+      } else {
+        const uint64_t diff = n > m ? n - m : m - n;
+        const bool len_ok = 20ull * diff < (uint64_t)n;
+        // cos > 0.95  <=>  dot > 0 and 400 dot^2 > 361 na nb; sums < 2^59, so both sides < 2^127
+        const unsigned __int128 lhs = (unsigned __int128)400 * sm[0] * sm[0];
+        const unsigned __int128 rhs = (unsigned __int128)361 * sm[1] * sm[2];
+        similar = len_ok && sm[0] > 0 && lhs > rhs;
+      }
+      res->similar = similar ? 1u : 0u;
+      if (flags & SS_MATCH_STEP_STAGE) stage_step(ctx, similar);
+      res->stage = ctx->stage;
+      res->stable_step = ctx->stable_step;
+      res->n_unmatched = unm;
+      for (uint32_t a = 0; a < k; ++a) ctx->stats.match_levels[level[a] <= SS_LEVEL_ALIGN ? level[a] : 4]++;
+    };
+    // The current sequence IS the reference one (the Stable stage of a fixed operator sequence, Sec. 3):
+    // no search is needed.  Every operator is its own counterpart at the strictest level, the three sums
+    // coincide, and what remains of the definition (a landing place needs more than out_slot outputs, the
+    // lowest anchor index keeps a shared place) is evaluated here on the host in one pass, without a
+    // round trip to the GPU.  Results are those of the kernels below on the same input.
+    if (!hist && n == m && (n == 0 || std::memcmp(ref, cur, (size_t)n * sizeof(ss_op_t)) == 0)) {
+      uint64_t sq = 0;
+      for (uint32_t i = 0; i < n; ++i) {
+        if (cur[i].op_token >= kTokenLimit) return SS_E_INVAL;
+        sq += (uint64_t)cur[i].op_token * cur[i].op_token;
+      }
+      uint32_t unm = 0;
+      if (k) {
+        std::unordered_map<uint64_t, uint32_t> first;          // (operator, slot) -> lowest anchor index landing there
+        if (!aligned) first.reserve(2 * (size_t)k);
+        for (uint32_t a = 0; a < k; ++a) {
+          const uint32_t i = anchors[a].ref_op, sl = anchors[a].out_slot;
+          const bool lands = i < n && sl < cur[i].n_out && (aligned || cur[i].op_token != 0);
+          new_idx[a] = lands ? (int32_t)i : -1;
+          level[a] = lands ? (uint8_t)(aligned ? SS_LEVEL_ALIGN : 0) : (uint8_t)255;
+          if (lands && !aligned) {
+            auto ins = first.emplace(((uint64_t)i << 32) | sl, a);
+            if (!ins.second) { new_idx[a] = -1; level[a] = 255; }   // an earlier anchor owns the place
+          }
+          unm += new_idx[a] < 0;
+        }
+      }
+      const uint64_t sm[3] = {sq, sq, sq};
+      finish(sm, unm);
+      return SS_OK;
+    }
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += ss_align_up(bytes, 256); return o; };
     const size_t o_ref = take((size_t)n * sizeof(ss_op_t)), o_cur = take((size_t)m * sizeof(ss_op_t));
@@ -285,7 +338,6 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
       }
       SS_HIP(hipGetLastError());
     }
-    const bool aligned = (flags & SS_MATCH_ALIGN) != 0;
     if (k && !aligned) {
       const uint32_t grid = (k + 3) / 4;                    // 4 wavefronts (anchors) per workgroup
       hipLaunchKernelGGL(ss_anchor_kernel, dim3(grid), dim3(256), 0, s, dref, n, dcur, m,
@@ -312,30 +364,15 @@ extern "C" int ss_match_sequence(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, co
     std::memcpy(&fl, h + 32, 4);
     std::memcpy(&unm, h + 40, 4);
     if (fl & 1u) return SS_E_INVAL;                          // a token beyond 2^18
-    res->dot = sm[0]; res->na = sm[1]; res->nb = sm[2];
-    bool similar;
-    if (n == 0 && m == 0) {
-      similar = true;
-    } else {
-      const uint64_t diff = n > m ? n - m : m - n;
-      const bool len_ok = 20ull * diff < (uint64_t)n;
-      // cos > 0.95  <=>  dot > 0 and 400 dot^2 > 361 na nb; sums < 2^59, so both sides < 2^127
-      const unsigned __int128 lhs = (unsigned __int128)400 * sm[0] * sm[0];
-      const unsigned __int128 rhs = (unsigned __int128)361 * sm[1] * sm[2];
-      similar = len_ok && sm[0] > 0 && lhs > rhs;
-    }
-    res->similar = similar ? 1u : 0u;
-    if (flags & SS_MATCH_STEP_STAGE) stage_step(ctx, similar);
-    res->stage = ctx->stage;
-    res->stable_step = ctx->stable_step;
-    res->n_unmatched = (k && !aligned) ? unm : 0;
+    uint32_t n_unm = (k && !aligned) ? unm : 0;
     if (k && aligned) {                                      // the scratch is free again: the stream is idle
       std::vector<int32_t> ref_to_cur(n);
       uint32_t lcs = 0;
       rc = ss_align_core(ctx, ref, n, cur, m, ref_to_cur.data(), &lcs, nullptr);
       if (rc != SS_OK) return rc;
-      ss_align_anchors(ref, n, cur, ref_to_cur.data(), anchors, k, new_idx, level, &res->n_unmatched);
+      ss_align_anchors(ref, n, cur, ref_to_cur.data(), anchors, k, new_idx, level, &n_unm);
     }
+    finish(sm, n_unm);
     return SS_OK;
   });
 }

@@ -381,6 +381,18 @@ extern "C" int ss_apply_policy(ss_ctx *ctx, const ss_policy_item_t *policy, uint
     for (const ss_action_t &a : s.actions) s.act_start[2ull * a.op_idx + (a.kind >= SS_ACT_OUT ? 1 : 0) + 1]++;
     for (uint64_t g = 0; g < groups; ++g) s.act_start[g + 1] += s.act_start[g];
     s.have_actions = true;
+    // reuse interval of every kept item (Sec. 6.4): operators between issuing the swap-out and the release
+    std::memset(ctx->stats.reuse_hist, 0, sizeof(ctx->stats.reuse_hist));
+    ctx->stats.reuse_sum = ctx->stats.reuse_count = 0;
+    for (const ss_policy_item_t &it : ap.resolved) {
+      if (it.flags & (SS_F_UNMATCHED | SS_F_ORDER)) continue;
+      const uint64_t gap = (uint64_t)it.t_free - it.t_out;
+      uint32_t b = 0;
+      while (b < 15 && ((gap + 1) >> (b + 1))) ++b;
+      ctx->stats.reuse_hist[b]++;
+      ctx->stats.reuse_sum += gap;
+      ctx->stats.reuse_count++;
+    }
     return SS_OK;
   });
 }

@@ -83,6 +83,9 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (cfg.copy_workgroups_out == 0) cfg.copy_workgroups_out = cfg.copy_workgroups;
     if (cfg.copy_unroll == 0) cfg.copy_unroll = 8;
     if (cfg.copy_workgroups > 4096 || cfg.copy_workgroups_out > 4096 || cfg.copy_unroll > 8) return SS_E_INVAL;
+    if (cfg.out_streams == 0) cfg.out_streams = 2;
+    if (cfg.in_streams == 0) cfg.in_streams = 2;
+    if (cfg.out_streams > ss_ctx::kMaxSwapStreams || cfg.in_streams > ss_ctx::kMaxSwapStreams) return SS_E_INVAL;
 
     ss_ctx *ctx = new (std::nothrow) ss_ctx();
     if (!ctx) return SS_E_NOMEM;
@@ -110,8 +113,12 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->events, (size_t)cfg.max_events * sizeof(ss_event_t),
                                           hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
     // all streams at the default priority
-    if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
-    if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+    ctx->n_s_out = cfg.out_streams;
+    ctx->n_s_in = cfg.in_streams;
+    for (uint32_t i = 0; i < ctx->n_s_out && rc == SS_OK; ++i)
+      if ((e = hipStreamCreateWithFlags(&ctx->s_out[i], hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+    for (uint32_t i = 0; i < ctx->n_s_in && rc == SS_OK; ++i)
+      if ((e = hipStreamCreateWithFlags(&ctx->s_in[i], hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
     if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_aux, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
     for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
       hipEvent_t ev;
@@ -134,11 +141,24 @@ static void free_events(std::vector<hipEvent_t> &v) {
   v.clear();
 }
 
+// host joins every swap stream of both directions
+static int sync_swap_streams(ss_ctx *ctx) {
+  for (uint32_t i = 0; i < ctx->n_s_out; ++i)
+    if (ctx->s_out[i]) SS_HIP(hipStreamSynchronize(ctx->s_out[i]));
+  for (uint32_t i = 0; i < ctx->n_s_in; ++i)
+    if (ctx->s_in[i]) SS_HIP(hipStreamSynchronize(ctx->s_in[i]));
+  return SS_OK;
+}
+
 static void sched_release(ss_sched &s) {
-  free_events(s.ev_out_done);
-  free_events(s.ev_in_done);
-  free_events(s.ev_out_start);
-  free_events(s.ev_in_start);
+  for (int p = 0; p < 2; ++p) {
+    free_events(s.ev_out_done[p]);
+    free_events(s.ev_in_done[p]);
+    free_events(s.ev_out_start[p]);
+    free_events(s.ev_in_start[p]);
+  }
+  free_events(s.ev_free_at);
+  free_events(s.ev_wait_at);
   if (s.d_out) (void)hipFree(s.d_out);
   if (s.d_in) (void)hipFree(s.d_in);
   if (s.d_out_chunk0) (void)hipFree(s.d_out_chunk0);
@@ -155,13 +175,14 @@ static void sched_release(ss_sched &s) {
 
 extern "C" int ss_destroy(ss_ctx *ctx) {
   if (!ctx) return SS_E_INVAL;
-  if (ctx->s_out) (void)hipStreamSynchronize(ctx->s_out);
-  if (ctx->s_in) (void)hipStreamSynchronize(ctx->s_in);
+  (void)sync_swap_streams(ctx);
   if (ctx->s_aux) (void)hipStreamSynchronize(ctx->s_aux);
   sched_release(ctx->sched);
   for (hipEvent_t ev : ctx->ev_ring) (void)hipEventDestroy(ev);
-  if (ctx->s_out) (void)hipStreamDestroy(ctx->s_out);
-  if (ctx->s_in) (void)hipStreamDestroy(ctx->s_in);
+  for (int i = 0; i < ss_ctx::kMaxSwapStreams; ++i) {
+    if (ctx->s_out[i]) (void)hipStreamDestroy(ctx->s_out[i]);
+    if (ctx->s_in[i]) (void)hipStreamDestroy(ctx->s_in[i]);
+  }
   if (ctx->s_aux) (void)hipStreamDestroy(ctx->s_aux);
   if (ctx->staging) (void)hipHostFree(ctx->staging);
   if (ctx->ops) (void)hipHostFree(ctx->ops);
@@ -310,8 +331,7 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
           (n_in_batches == 0 || std::memcmp(s.in_start.data(), in_start, ((size_t)n_in_batches + 1) * 4) == 0);
       if (same) {
         // nothing of the previous iteration may still be in flight
-        SS_HIP(hipStreamSynchronize(ctx->s_out));
-        SS_HIP(hipStreamSynchronize(ctx->s_in));
+        if ((rc = sync_swap_streams(ctx)) != SS_OK) return rc;
         std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
         std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
         std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
@@ -333,8 +353,8 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
         if (iv[i].first < iv[i - 1].second) return SS_E_INVAL;
     }
     // nothing of the previous schedule may still be in flight
-    SS_HIP(hipStreamSynchronize(ctx->s_out));
-    SS_HIP(hipStreamSynchronize(ctx->s_in));
+    if ((rc = sync_swap_streams(ctx)) != SS_OK) return rc;
+    s.drained_once = false;      // the other event set belongs to the schedule that is being replaced
 
     s.loaded = false;
     s.out.assign(descs_out, descs_out + n_out);
@@ -374,13 +394,21 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
       if (cnt && total / cnt < ctx->cfg.engine_min_bytes_out) s.out_all_large = false;
     }
 
-    const unsigned evflags = ((ctx->cfg.flags & SS_CFG_TIMING) ? hipEventDefault : hipEventDisableTiming) |
+    const bool stall = (ctx->cfg.flags & SS_CFG_STALL_TIMING) != 0;
+    const unsigned evflags = ((ctx->cfg.flags & (SS_CFG_TIMING | SS_CFG_STALL_TIMING)) ? hipEventDefault
+                                                                                       : hipEventDisableTiming) |
                              fence_flag(ctx->cfg);
-    if ((rc = ensure_events(ctx, s.ev_out_done, n_out_batches, evflags)) != SS_OK) return rc;
-    if ((rc = ensure_events(ctx, s.ev_in_done, n_in_batches, evflags)) != SS_OK) return rc;
-    if (ctx->cfg.flags & SS_CFG_TIMING) {
-      if ((rc = ensure_events(ctx, s.ev_out_start, n_out_batches, evflags)) != SS_OK) return rc;
-      if ((rc = ensure_events(ctx, s.ev_in_start, n_in_batches, evflags)) != SS_OK) return rc;
+    if (stall) {
+      if ((rc = ensure_events(ctx, s.ev_free_at, n_out_batches, evflags)) != SS_OK) return rc;
+      if ((rc = ensure_events(ctx, s.ev_wait_at, n_in_batches, evflags)) != SS_OK) return rc;
+    }
+    for (int p = 0; p < 2; ++p) {
+      if ((rc = ensure_events(ctx, s.ev_out_done[p], n_out_batches, evflags)) != SS_OK) return rc;
+      if ((rc = ensure_events(ctx, s.ev_in_done[p], n_in_batches, evflags)) != SS_OK) return rc;
+      if (ctx->cfg.flags & SS_CFG_TIMING) {
+        if ((rc = ensure_events(ctx, s.ev_out_start[p], n_out_batches, evflags)) != SS_OK) return rc;
+        if ((rc = ensure_events(ctx, s.ev_in_start[p], n_in_batches, evflags)) != SS_OK) return rc;
+      }
     }
     // device copies of descriptors and chunk tables
     auto upload = [&](const std::vector<ss_desc_t> &d, const std::vector<uint32_t> &c, ss_desc_t *&dd,
@@ -491,30 +519,33 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
   if (batch + 1 >= s.out_start.size()) return SS_E_INVAL;
   if (s.out_issued[batch]) return SS_E_STATE;
   const uint32_t lo = s.out_start[batch], hi = s.out_start[batch + 1];
+  const bool engine = use_engine(ctx, ctx->cfg.copy_path, true, s.out, lo, hi);
+  // copy-kernel batches take the swap-out streams in turn; copy-engine batches stay on the first
+  hipStream_t so = engine ? ctx->s_out[0] : ctx->s_out[batch % ctx->n_s_out];
   // the tensors' last forward use is already enqueued on the compute stream: order after it
   hipEvent_t mark = next_marker(ctx);
   SS_HIP(hipEventRecord(mark, ctx->compute));
-  SS_HIP(hipStreamWaitEvent(ctx->s_out, mark, 0));
-  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_out_start[batch], ctx->s_out));
+  SS_HIP(hipStreamWaitEvent(so, mark, 0));
+  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_out_start[s.phase][batch], so));
   uint64_t bytes = 0;
   for (uint32_t i = lo; i < hi; ++i) bytes += s.out[i].nbytes;
-  if (use_engine(ctx, ctx->cfg.copy_path, true, s.out, lo, hi)) {
+  if (engine) {
     for (uint32_t i = lo; i < hi; ++i)
       if (s.out[i].nbytes)
         SS_HIP(hipMemcpyAsync(ctx->staging + s.out[i].host_off, ctx->arena + s.out[i].dev_off, s.out[i].nbytes,
-                              hipMemcpyDeviceToHost, ctx->s_out));
+                              hipMemcpyDeviceToHost, so));
     ctx->stats.engine_batches++;
     ctx->stats.engine_batches_out++;
     s.last_engine_out = batch;
   } else {
     const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
     const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
-    ss_launch_copy(ctx->s_out, ctx->cfg.copy_workgroups_out, ctx->cfg.copy_unroll, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
+    ss_launch_copy(so, ctx->cfg.copy_workgroups_out, ctx->cfg.copy_unroll, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
                    s.d_out_cdesc + s.out_cbase[batch], n_chunks, s.out_shift[batch]);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
-  SS_HIP(hipEventRecord(s.ev_out_done[batch], ctx->s_out));
+  SS_HIP(hipEventRecord(s.ev_out_done[s.phase][batch], so));
   s.out_issued[batch] = 1;
   ctx->stats.bytes_out += bytes;
   return SS_OK;
@@ -528,34 +559,42 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
   if (s.in_issued[batch]) return SS_E_STATE;
   const uint32_t lo = s.in_start[batch], hi = s.in_start[batch + 1];
   if (hi > lo && !s.out_issued[s.in_dep[batch]]) return SS_E_STATE;   // its data never left
+  const bool engine = use_engine(ctx, ctx->cfg.copy_path_in, false, s.in, lo, hi);
+  hipStream_t si = engine ? ctx->s_in[0] : ctx->s_in[batch % ctx->n_s_in];
   // destination blocks are free once the compute stream reaches this point
   hipEvent_t mark = next_marker(ctx);
   SS_HIP(hipEventRecord(mark, ctx->compute));
-  SS_HIP(hipStreamWaitEvent(ctx->s_in, mark, 0));
-  // staging slots must be completely written
-  if (hi > lo) SS_HIP(hipStreamWaitEvent(ctx->s_in, s.ev_out_done[s.in_dep[batch]], 0));
+  SS_HIP(hipStreamWaitEvent(si, mark, 0));
+  // staging slots must be completely written: the batch's tensors left in swap-out batches up to in_dep;
+  // with the swap-out batches spread over n streams, the last n of them up to in_dep cover every stream
+  // (each stream runs its own batches in order)
+  if (hi > lo) {
+    const uint32_t dep = s.in_dep[batch];
+    for (uint32_t back = 0; back < ctx->n_s_out && back <= dep; ++back)
+      if (s.out_issued[dep - back]) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][dep - back], 0));
+  }
   // a copy-engine swap-out collapses to a quarter of the link rate as soon as anything flows the
   // other way: no swap-in starts before the engine swap-outs issued so far have finished
   if (s.last_engine_out >= 0 && (hi <= lo || (int64_t)s.in_dep[batch] < s.last_engine_out))
-    SS_HIP(hipStreamWaitEvent(ctx->s_in, s.ev_out_done[(size_t)s.last_engine_out], 0));
-  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_in_start[batch], ctx->s_in));
+    SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)s.last_engine_out], 0));
+  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_in_start[s.phase][batch], si));
   uint64_t bytes = 0;
   for (uint32_t i = lo; i < hi; ++i) bytes += s.in[i].nbytes;
-  if (use_engine(ctx, ctx->cfg.copy_path_in, false, s.in, lo, hi)) {
+  if (engine) {
     for (uint32_t i = lo; i < hi; ++i)
       if (s.in[i].nbytes)
         SS_HIP(hipMemcpyAsync(ctx->arena + s.in[i].dev_off, ctx->staging + s.in[i].host_off, s.in[i].nbytes,
-                              hipMemcpyHostToDevice, ctx->s_in));
+                              hipMemcpyHostToDevice, si));
     ctx->stats.engine_batches++;
   } else {
     const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
     const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
-    ss_launch_copy(ctx->s_in, ctx->cfg.copy_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
+    ss_launch_copy(si, ctx->cfg.copy_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
                    s.d_in_cdesc + s.in_cbase[batch], n_chunks, s.in_shift[batch]);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
-  SS_HIP(hipEventRecord(s.ev_in_done[batch], ctx->s_in));
+  SS_HIP(hipEventRecord(s.ev_in_done[s.phase][batch], si));
   s.in_issued[batch] = 1;
   ctx->stats.bytes_in += bytes;
   return SS_OK;
@@ -572,8 +611,9 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
       const uint32_t b = s.out_batch_of[it->second];
       if (!s.out_issued[b]) return SS_E_STATE;   // releasing a block whose swap-out was never issued
       if (!s.out_waited[b]) {
+        if (ctx->cfg.flags & SS_CFG_STALL_TIMING) SS_HIP(hipEventRecord(s.ev_free_at[b], ctx->compute));
         // device-side: later compute-stream work starts only after the batch has left HBM
-        SS_HIP(hipStreamWaitEvent(ctx->compute, s.ev_out_done[b], 0));
+        SS_HIP(hipStreamWaitEvent(ctx->compute, s.ev_out_done[s.phase][b], 0));
         s.out_waited[b] = 1;
         ctx->stats.free_waits++;
       }
@@ -591,20 +631,44 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
       const uint32_t b = s.in_batch_of[it->second];
       if (!s.in_issued[b]) return SS_E_STATE;    // waiting for a swap-in that was never issued
       if (!s.in_waited[b]) {
-        SS_HIP(hipStreamWaitEvent(ctx->compute, s.ev_in_done[b], 0));
+        if (ctx->cfg.flags & SS_CFG_STALL_TIMING) SS_HIP(hipEventRecord(s.ev_wait_at[b], ctx->compute));
+        SS_HIP(hipStreamWaitEvent(ctx->compute, s.ev_in_done[s.phase][b], 0));
         s.in_waited[b] = 1;
         ctx->stats.in_waits++;
       }
       return SS_OK;
     }
     case SS_SYNC_DRAIN: {
-      SS_HIP(hipStreamSynchronize(ctx->s_out));
-      SS_HIP(hipStreamSynchronize(ctx->s_in));
+      {
+        const int rc = sync_swap_streams(ctx);
+        if (rc != SS_OK) return rc;
+      }
+      if ((ctx->cfg.flags & SS_CFG_STALL_TIMING) && s.loaded) {
+        // measurement mode: the compute stream is joined too, then every wait of this iteration is
+        // charged with the time from reaching it to the end of the batch it waited for
+        SS_HIP(hipStreamSynchronize(ctx->compute));
+        for (size_t b = 0; b < s.out_waited.size(); ++b)
+          if (s.out_waited[b]) {
+            float ms = 0.f;
+            SS_HIP(hipEventElapsedTime(&ms, s.ev_free_at[b], s.ev_out_done[s.phase][b]));
+            if (ms > 0.f) ctx->stats.stall_free_ms += ms;
+          }
+        for (size_t b = 0; b < s.in_waited.size(); ++b)
+          if (s.in_waited[b]) {
+            float ms = 0.f;
+            SS_HIP(hipEventElapsedTime(&ms, s.ev_wait_at[b], s.ev_in_done[s.phase][b]));
+            if (ms > 0.f) ctx->stats.stall_wait_in_ms += ms;
+          }
+      }
       std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
       std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
       std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
       std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
       s.last_engine_out = -1;
+      if (s.loaded) {              // the next iteration records into the other event set
+        s.phase ^= 1;
+        s.drained_once = true;
+      }
       return SS_OK;
     }
     default: return SS_E_INVAL;
@@ -636,8 +700,9 @@ extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms,
   if (!ctx || dir > 1) return SS_E_INVAL;
   if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
   ss_sched &s = ctx->sched;
-  auto &st = dir ? s.ev_in_start : s.ev_out_start;
-  auto &dn = dir ? s.ev_in_done : s.ev_out_done;
+  const int set = s.drained_once ? s.phase ^ 1 : s.phase;      // the iteration drained last
+  auto &st = dir ? s.ev_in_start[set] : s.ev_out_start[set];
+  auto &dn = dir ? s.ev_in_done[set] : s.ev_out_done[set];
   const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
   if (ms) {
     if (batch >= nb) return SS_E_INVAL;
@@ -645,7 +710,14 @@ extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms,
   }
   if (span_ms) {
     if (nb == 0) { *span_ms = 0.f; return SS_OK; }
-    SS_HIP(hipEventElapsedTime(span_ms, st[0], dn[nb - 1]));
+    // first start to last end: with several streams per direction the batches need not end in order
+    float best = 0.f;
+    for (size_t b = nb > 8 ? nb - 8 : 0; b < nb; ++b) {
+      float x = 0.f;
+      SS_HIP(hipEventElapsedTime(&x, st[0], dn[b]));
+      if (x > best) best = x;
+    }
+    *span_ms = best;
   }
   return SS_OK;
 }
@@ -657,7 +729,7 @@ extern "C" int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *don
   const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
   if (batch >= nb) return SS_E_INVAL;
   if (!(dir ? s.in_issued[batch] : s.out_issued[batch])) return SS_E_STATE;
-  const hipError_t e = hipEventQuery(dir ? s.ev_in_done[batch] : s.ev_out_done[batch]);
+  const hipError_t e = hipEventQuery(dir ? s.ev_in_done[s.phase][batch] : s.ev_out_done[s.phase][batch]);
   if (e == hipErrorNotReady) {
     (void)hipGetLastError();
     *done = 0;
@@ -672,12 +744,13 @@ extern "C" int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float 
   if (!ctx || dir > 1 || !start_ms || !end_ms) return SS_E_INVAL;
   if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
   ss_sched &s = ctx->sched;
-  auto &st = dir ? s.ev_in_start : s.ev_out_start;
-  auto &dn = dir ? s.ev_in_done : s.ev_out_done;
+  const int set = s.drained_once ? s.phase ^ 1 : s.phase;      // the iteration drained last
+  auto &st = dir ? s.ev_in_start[set] : s.ev_out_start[set];
+  auto &dn = dir ? s.ev_in_done[set] : s.ev_out_done[set];
   const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
   if (batch >= nb || s.out_start.size() < 2) return SS_E_INVAL;
-  SS_HIP(hipEventElapsedTime(start_ms, s.ev_out_start[0], st[batch]));
-  SS_HIP(hipEventElapsedTime(end_ms, s.ev_out_start[0], dn[batch]));
+  SS_HIP(hipEventElapsedTime(start_ms, s.ev_out_start[set][0], st[batch]));
+  SS_HIP(hipEventElapsedTime(end_ms, s.ev_out_start[set][0], dn[batch]));
   return SS_OK;
 }
 
@@ -692,8 +765,10 @@ extern "C" int ss_host_peek(ss_ctx *ctx, uint64_t host_off, uint64_t nbytes, con
 
 extern "C" int ss_staging_fill(ss_ctx *ctx, int byte) {
   if (!ctx) return SS_E_INVAL;
-  SS_HIP(hipStreamSynchronize(ctx->s_out));
-  SS_HIP(hipStreamSynchronize(ctx->s_in));
+  {
+    const int rc = sync_swap_streams(ctx);
+    if (rc != SS_OK) return rc;
+  }
   if (ctx->staging) std::memset(ctx->staging, byte, ctx->cfg.staging_bytes);
   return SS_OK;
 }
@@ -760,23 +835,23 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
         const bool d2h = (mode == 0 || mode == 2 || mode == 3 || mode == 5);
         const bool h2d = (mode == 1 || mode == 2 || mode == 4 || mode == 5);
         if (d2h) {
-          ck(hipEventRecord(a0, ctx->s_out));
+          ck(hipEventRecord(a0, ctx->s_out[0]));
           if (mode == 3 || mode == 5) {
-            ss_launch_copy(ctx->s_out, wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
+            ss_launch_copy(ctx->s_out[0], wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
             ck(hipGetLastError());
-          } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out));
-          ck(hipEventRecord(a1, ctx->s_out));
+          } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out[0]));
+          ck(hipEventRecord(a1, ctx->s_out[0]));
         }
         if (h2d) {
-          ck(hipEventRecord(b0, ctx->s_in));
+          ck(hipEventRecord(b0, ctx->s_in[0]));
           if (mode == 4 || mode == 5) {
-            ss_launch_copy(ctx->s_in, wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
+            ss_launch_copy(ctx->s_in[0], wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
             ck(hipGetLastError());
-          } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in));
-          ck(hipEventRecord(b1, ctx->s_in));
+          } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in[0]));
+          ck(hipEventRecord(b1, ctx->s_in[0]));
         }
-        ck(hipStreamSynchronize(ctx->s_out));
-        ck(hipStreamSynchronize(ctx->s_in));
+        ck(hipStreamSynchronize(ctx->s_out[0]));
+        ck(hipStreamSynchronize(ctx->s_in[0]));
         float ms;
         if (d2h && ck(hipEventElapsedTime(&ms, a0, a1)) && r >= 2) ta.push_back(ms);
         if (h2d && ck(hipEventElapsedTime(&ms, b0, b1)) && r >= 2) tb.push_back(ms);

@@ -358,7 +358,7 @@ def test_auto_path_of_the_swap_out_side_follows_the_smallest_batch(P, torch):
 def test_link_probe_and_batch_windows(P, torch):
     """ss_bw_probe reports all eight rates of the host link (loose sanity bounds: no figure of merit
     is asserted here); ss_batch_window orders the batches of a direction; argument errors"""
-    ctx = make_ctx(P, staging_bytes=8 << 20, flags=P.SS_CFG_TIMING)
+    ctx = make_ctx(P, staging_bytes=8 << 20, flags=P.SS_CFG_TIMING, out_streams=1, in_streams=1)
     try:
         bw = P.ss_bw_probe(ctx, 64 << 20, 3)
         assert set(bw) == {"d2h_gbps", "h2d_gbps", "bidir_d2h_gbps", "bidir_h2d_gbps", "kernel_d2h_gbps",

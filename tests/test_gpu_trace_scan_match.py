@@ -253,6 +253,40 @@ def test_match_perturbed_sequences(P, ctx, it):
     assert (lib_h["similar"], lib_h["dot"], lib_h["na"], lib_h["nb"]) == ora_h
 
 
+@pytest.mark.parametrize("flags_name", ["keyed", "aligned"])
+def test_match_of_a_sequence_with_itself_and_with_one_operator_changed(P, ctx, flags_name):
+    """the current sequence being the reference itself is answered on the host without the kernels; the
+    result is the oracle's all the same (anchors beyond the sequence, on output slots the operator does not
+    have, several on one place), and so is the kernels' answer once a single operator differs"""
+    ref, _, anchors, tr0, _ = traces_for_match(1)
+    n = len(ref)
+    extra = np.zeros(7, dtype=W.ANCHOR_DT)
+    extra[0] = (n + 3, 0)                                  # beyond the sequence
+    extra[1] = (int(anchors["ref_op"][0]), 200)            # a slot no operator has
+    extra[2] = anchors[4]; extra[3] = anchors[4]           # one place, three claimants with anchors[4] itself
+    extra[4] = (0, 0); extra[5] = (n - 1, 0); extra[6] = (n - 1, 1)
+    anc = np.concatenate([anchors, extra])
+    flags = P.SS_MATCH_ALIGN if flags_name == "aligned" else 0
+
+    def both(cur):
+        lib = P.ss_match_sequence(ctx, ref, cur, anc, flags=flags)
+        ora = oracle.match_sequence(ops_tuples(ref), ops_tuples(cur), anc.tolist())
+        if flags:
+            al = oracle.align_anchors(ops_tuples(ref), ops_tuples(cur), anc.tolist())
+            ora = dict(ora, new_idx=al["new_idx"], level=al["level"], n_unmatched=int((al["new_idx"] < 0).sum()))
+        assert np.array_equal(lib["new_idx"], ora["new_idx"]) and np.array_equal(lib["level"], ora["level"])
+        assert (lib["dot"], lib["na"], lib["nb"], lib["similar"], lib["n_unmatched"]) == \
+            (ora["dot"], ora["na"], ora["nb"], ora["similar"], ora["n_unmatched"])
+        return lib
+    same = both(ref.copy())
+    assert same["similar"] and same["dot"] == same["na"] == same["nb"]
+    assert (same["new_idx"][:len(anchors)] == anchors["ref_op"]).all()
+    cur = ref.copy()
+    cur["stack_hash"][n // 2] ^= 0x5A5A                    # one operator reached by another call path
+    near = both(cur)
+    assert near["similar"] and near["dot"] == same["dot"]
+
+
 def test_match_full_7b_shape_varying_sequence(P, ctx):
     ref, cur, anchors, tr0, tr1 = traces_for_match(2, W.config_shape(4))
     assert len(ref) > 1000 and len(anchors) > 400
