@@ -100,7 +100,12 @@ enum { SS_ACT_IN = 0, SS_ACT_WAIT_IN = 1, SS_ACT_OUT = 2, SS_ACT_FREE = 3 };
 typedef struct { uint32_t op_idx, kind, tensor_id, batch; } ss_action_t;          /* 16 B */
 
 /* ---- configuration -------------------------------------------------------- */
-enum { SS_PATH_AUTO = 0, SS_PATH_KERNEL = 1, SS_PATH_ENGINE = 2 };
+enum { SS_PATH_AUTO = 0, SS_PATH_KERNEL = 1, SS_PATH_ENGINE = 2,
+       SS_PATH_STAGED = 3 };  /* swap-out only: the copy kernel gathers consecutive batches into a slot of a ring
+                                 in HBM (the blocks can be released as soon as that is done), one copy-engine
+                                 transfer per slot carries them to the staging area.  Used for batches whose
+                                 staging slots are gap-free (sizes multiples of `align`, no guards) and fit a
+                                 ring slot; other batches leave as with SS_PATH_AUTO                        */
 enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch_ms)          */
        SS_CFG_POISON_FREE = 2,   /* overwrite a block with 0xDB when its FREE action runs     */
        SS_CFG_KEEP_LATE = 4,     /* keep items whose swap-out cannot finish before their first
@@ -138,11 +143,16 @@ typedef struct {
                                  that the copy engine falls far behind the link inside a running
                                  training step, above it it reaches the link peak and, unlike a copy
                                  kernel, does not delay the compute stream's launches); 0 = never   */
-  uint32_t out_streams;       /* streams the copy-kernel swap-out batches take in turn, 1..4 (0 = 2): with
-                                 two, a launch's set-up and its wait for free compute units hide behind the
-                                 launch before it, which is still moving data                      */
-  uint32_t in_streams;        /* the same for copy-kernel swap-in batches (0 = 2); copy-engine batches of
+  uint32_t out_streams;       /* streams the copy-kernel swap-out batches take in turn, 1..4 (0 = 1).  More than
+                                 one lets a launch's set-up hide behind the launch before it, but every stream
+                                 beyond the process's hardware queues (4 here, the compute stream included)
+                                 shares a queue with another and waits for that one's work            */
+  uint32_t in_streams;        /* the same for copy-kernel swap-in batches (0 = 1); copy-engine batches of
                                  either direction always use one stream                            */
+  uint64_t ring_bytes;        /* SS_PATH_STAGED: size of the HBM ring (0 = 512 MiB), allocated at ss_create  */
+  uint64_t ring_slot_bytes;   /* SS_PATH_STAGED: size of one ring slot = largest single transfer (0 = 128 MiB) */
+  uint32_t gather_workgroups; /* SS_PATH_STAGED: grid of the gather launches, HBM to HBM (0 = 256)          */
+  uint32_t reserved;
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */
@@ -202,6 +212,8 @@ typedef struct {
    * SS_SYNC_FREE / SS_SYNC_WAIT_IN (from the moment it reached the wait to the end of the batch it
    * waited for, 0 if that had already ended), summed over the iterations drained so far */
   double stall_free_ms, stall_wait_in_ms;
+  uint64_t ring_batches, ring_transfers; /* SS_PATH_STAGED: swap-out batches gathered into the HBM ring, and
+                                            copy-engine transfers that carried them out of it */
 } ss_stats_t;
 
 typedef struct {
@@ -483,14 +495,21 @@ int ss_host_peek(ss_ctx *ctx, uint64_t host_off, uint64_t nbytes, const void **p
 /* Fill the whole staging area with a byte (host side; for guard checks). */
 int ss_staging_fill(ss_ctx *ctx, int byte);
 
-/* Duration of a batch on its swap stream in ms (needs SS_CFG_TIMING and a
- * completed batch); dir 0 = out, 1 = in.  span_ms (nullable): first start to
- * last end over all batches of that direction enqueued since the last drain. */
+/* Duration of a batch on its swap stream in ms (needs SS_CFG_TIMING), in the iteration drained last;
+ * dir 0 = out, 1 = in, 2 = the copy-engine transfers out of the HBM ring (SS_PATH_STAGED; `batch`
+ * then counts the ring groups, see ss_ring_view).  A staged swap-out batch's own duration is that of
+ * its gather into the ring.  span_ms (nullable): first start to last end over all batches (transfers)
+ * of that direction. */
 int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms);
 
 /* Start and end of a batch on its swap stream, in ms since the start of swap-out batch 0 of
  * the same iteration (needs SS_CFG_TIMING; all batches involved must have completed). */
 int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *start_ms, float *end_ms);
+
+/* SS_PATH_STAGED: how the loaded schedule's swap-out batches were grouped.  n_groups ring groups;
+ * group_of (borrowed, one entry per swap-out batch) = the batch's group or -1 if it leaves directly;
+ * group_bytes (borrowed, n_groups entries) = bytes of each group's transfer. */
+int ss_ring_view(ss_ctx *ctx, uint32_t *n_groups, const int32_t **group_of, const uint64_t **group_bytes);
 
 /* Host-link bandwidth measured now: pinned hipMemcpy D2H, H2D, both at once,
  * and the same through the copy kernels; `bytes` per transfer, median of `reps`. */

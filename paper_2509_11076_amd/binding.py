@@ -38,7 +38,7 @@ ACTION_DT = np.dtype([("op_idx", "<u4"), ("kind", "<u4"), ("tensor_id", "<u4"), 
 SS_OK = 0
 SS_E_INVAL, SS_E_NOMEM, SS_E_HIP, SS_E_INFEASIBLE, SS_E_ORDER, SS_E_STATE, SS_E_CAPACITY = -1, -2, -3, -4, -6, -8, -9
 SS_ACT_IN, SS_ACT_WAIT_IN, SS_ACT_OUT, SS_ACT_FREE = 0, 1, 2, 3
-SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE = 0, 1, 2
+SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE, SS_PATH_STAGED = 0, 1, 2, 3
 SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE, SS_CFG_POLICY_POINTS = 1, 2, 4, 8, 16
 SS_CFG_STALL_TIMING = 32
 SS_SYNC_FREE, SS_SYNC_WAIT_IN, SS_SYNC_DRAIN = 0, 1, 2
@@ -57,7 +57,9 @@ class ss_config_t(C.Structure):
                 ("copy_workgroups", C.c_uint32), ("copy_workgroups_out", C.c_uint32),
                 ("copy_unroll", C.c_uint32), ("max_ops", C.c_uint32), ("max_events", C.c_uint32),
                 ("flags", C.c_uint32), ("engine_min_bytes_out", C.c_uint64),
-                ("out_streams", C.c_uint32), ("in_streams", C.c_uint32)]
+                ("out_streams", C.c_uint32), ("in_streams", C.c_uint32),
+                ("ring_bytes", C.c_uint64), ("ring_slot_bytes", C.c_uint64),
+                ("gather_workgroups", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ss_scan_result_t(C.Structure):
@@ -98,7 +100,8 @@ class ss_stats_t(C.Structure):
                 ("last_hip_error", C.c_int32), ("engine_batches_out", C.c_uint32),
                 ("match_levels", C.c_uint64 * 5), ("reuse_hist", C.c_uint32 * 16),
                 ("reuse_sum", C.c_uint64), ("reuse_count", C.c_uint64),
-                ("stall_free_ms", C.c_double), ("stall_wait_in_ms", C.c_double)]
+                ("stall_free_ms", C.c_double), ("stall_wait_in_ms", C.c_double),
+                ("ring_batches", C.c_uint64), ("ring_transfers", C.c_uint64)]
 
 
 class ss_bw_t(C.Structure):
@@ -162,6 +165,7 @@ _SIGS = {
     "ss_batch_ms": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
     "ss_batch_window": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
     "ss_bw_probe": [_P, C.c_uint64, C.c_uint32, C.POINTER(ss_bw_t)],
+    "ss_ring_view": [_P, C.POINTER(C.c_uint32), C.POINTER(_P), C.POINTER(_P)],
     "ss_get_stats": [_P, C.POINTER(ss_stats_t)],
 }
 for _name, _args in _SIGS.items():
@@ -511,6 +515,18 @@ def ss_batch_window(ctx, direction, batch):
     a, b = C.c_float(), C.c_float()
     _ck(_lib.ss_batch_window(ctx, int(direction), int(batch), C.byref(a), C.byref(b)), "ss_batch_window")
     return a.value, b.value
+
+
+def ss_ring_view(ctx):
+    """(group_of int32[n_out_batches], group_bytes uint64[n_groups]) as copies"""
+    n, g, gb = C.c_uint32(), _P(), _P()
+    _ck(_lib.ss_ring_view(ctx, C.byref(n), C.byref(g), C.byref(gb)), "ss_ring_view")
+    nob = len(ss_schedule_view(ctx)[0]) - 1
+    group_of = np.frombuffer((C.c_char * (4 * nob)).from_address(g.value), dtype=np.int32).copy() if nob and g.value \
+        else np.zeros(0, np.int32)
+    group_bytes = np.frombuffer((C.c_char * (8 * n.value)).from_address(gb.value), dtype=np.uint64).copy() \
+        if n.value else np.zeros(0, np.uint64)
+    return group_of, group_bytes
 
 
 def ss_bw_probe(ctx, nbytes=1 << 30, reps=10):

@@ -40,6 +40,27 @@ struct ss_sched {
   // drain), so that the timing of the iteration drained last stays readable while the next one runs.
   std::vector<hipEvent_t> ev_out_done[2], ev_in_done[2], ev_out_start[2], ev_in_start[2];
   std::vector<hipEvent_t> ev_free_at, ev_wait_at;   // SS_CFG_STALL_TIMING: compute stream reaches the wait for the batch
+  // Staged swap-out (SS_PATH_STAGED): consecutive batches whose staging slots form one gap-free range
+  // are gathered by the copy kernel into a slot of the HBM ring and leave in one copy-engine transfer.
+  struct out_group { uint32_t first, last; uint64_t host_lo, bytes; };
+  std::vector<out_group> groups;
+  std::vector<uint64_t> group_bytes;                // per group, for ss_ring_view
+  std::vector<int32_t> group_of;                    // per swap-out batch: its group, -1 = leaves directly
+  std::vector<int32_t> prev_direct;                 // per swap-out batch b: largest direct batch <= b, -1 = none
+  std::vector<hipEvent_t> ev_gathered[2];           // per batch: its bytes are in the ring (the block may be released)
+  std::vector<hipEvent_t> ev_flush_start[2];        // per group (SS_CFG_TIMING): its first transfer starts
+  std::vector<int32_t> done_ev_of;                  // per batch, this iteration: batch whose ev_out_done covers it; -1 = not sent yet
+  std::vector<int32_t> done_ev_of_drained;          // the same of the iteration drained last (for the timing calls)
+  std::vector<uint8_t> ring_state;                  // per batch, this iteration: 0 not issued, 1 in the ring, 2 sent (or left directly)
+  std::vector<uint32_t> group_pending;              // per group, this iteration: batches not issued yet
+  std::vector<uint8_t> group_gathered, group_started; // per group: has bytes in the ring that are not sent; first transfer recorded
+  std::vector<int32_t> group_last_flush_drained;    // the same of the iteration drained last
+  std::vector<int32_t> group_last_flush;            // per group: batch whose ev_out_done its latest transfer recorded, -1 = none
+  std::vector<int32_t> slot_owner;                  // per ring slot: group whose bytes it holds, -1 = none
+  std::vector<uint8_t> out_staged_drained;          // the same of the iteration drained last
+  std::vector<uint8_t> out_staged;                  // per batch, this iteration: it went through the ring
+  int64_t last_gather_batch = -1;                   // batch gathered most recently (its event is the latest on the swap-out stream)
+  int64_t last_flush_batch = -1;                    // batch whose ev_out_done the most recent transfer out of the ring recorded
   int phase = 0;                                    // event set of the iteration being issued
   bool drained_once = false;                        // set `phase ^ 1` holds a completed iteration
   ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
@@ -72,6 +93,9 @@ struct ss_ctx {
   static constexpr int kMaxSwapStreams = 4;
   hipStream_t s_out[kMaxSwapStreams] = {}, s_in[kMaxSwapStreams] = {}, s_aux = nullptr;
   uint32_t n_s_out = 1, n_s_in = 1;
+  hipStream_t s_flush = nullptr;    // copy-engine transfers out of the HBM ring
+  uint8_t *ring = nullptr;          // HBM ring of the staged swap-out path (cfg.ring_bytes, in slots of cfg.ring_slot_bytes)
+  uint32_t n_slots = 0;
   std::vector<hipEvent_t> ev_ring;  // compute-stream markers, used round-robin
   size_t ev_next = 0;
   // trace

@@ -77,14 +77,22 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (cfg_in) cfg = *cfg_in;
     if (cfg.align < 16 || (cfg.align & (cfg.align - 1)) || cfg.guard_bytes % cfg.align ||
         cfg.link_bytes_per_op == 0 || cfg.max_ops == 0 || cfg.max_events == 0 ||
-        cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_ENGINE || cfg.copy_path_in > SS_PATH_ENGINE)
+        cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_STAGED || cfg.copy_path_in > SS_PATH_ENGINE)
+      return SS_E_INVAL;
+    if (cfg.ring_slot_bytes == 0) cfg.ring_slot_bytes = 128ull << 20;
+    if (cfg.ring_bytes == 0) cfg.ring_bytes = 512ull << 20;
+    if (cfg.gather_workgroups == 0) cfg.gather_workgroups = 256;
+    if (cfg.gather_workgroups > 4096) return SS_E_INVAL;
+    if (cfg.copy_path == SS_PATH_STAGED &&
+        ((cfg.ring_slot_bytes & 255u) || cfg.ring_slot_bytes < 4096 || cfg.ring_bytes / cfg.ring_slot_bytes < 2 ||
+         cfg.ring_bytes / cfg.ring_slot_bytes > 64))
       return SS_E_INVAL;
     if (cfg.copy_workgroups == 0) cfg.copy_workgroups = default_workgroups();
     if (cfg.copy_workgroups_out == 0) cfg.copy_workgroups_out = cfg.copy_workgroups;
     if (cfg.copy_unroll == 0) cfg.copy_unroll = 8;
     if (cfg.copy_workgroups > 4096 || cfg.copy_workgroups_out > 4096 || cfg.copy_unroll > 8) return SS_E_INVAL;
-    if (cfg.out_streams == 0) cfg.out_streams = 2;
-    if (cfg.in_streams == 0) cfg.in_streams = 2;
+    if (cfg.out_streams == 0) cfg.out_streams = 1;
+    if (cfg.in_streams == 0) cfg.in_streams = 1;
     if (cfg.out_streams > ss_ctx::kMaxSwapStreams || cfg.in_streams > ss_ctx::kMaxSwapStreams) return SS_E_INVAL;
 
     ss_ctx *ctx = new (std::nothrow) ss_ctx();
@@ -113,13 +121,24 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->events, (size_t)cfg.max_events * sizeof(ss_event_t),
                                           hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
     // all streams at the default priority
-    ctx->n_s_out = cfg.out_streams;
+    ctx->n_s_out = cfg.copy_path == SS_PATH_STAGED ? 1 : cfg.out_streams;
     ctx->n_s_in = cfg.in_streams;
     for (uint32_t i = 0; i < ctx->n_s_out && rc == SS_OK; ++i)
       if ((e = hipStreamCreateWithFlags(&ctx->s_out[i], hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
     for (uint32_t i = 0; i < ctx->n_s_in && rc == SS_OK; ++i)
       if ((e = hipStreamCreateWithFlags(&ctx->s_in[i], hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
-    if (rc == SS_OK && (e = hipStreamCreateWithFlags(&ctx->s_aux, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+    // The trace kernels (scan, match, align) run on the first swap-in stream: it is idle between iterations,
+    // when they are called, and every further stream of the process has to share one of the few hardware
+    // queues (4 per process here) with another - a stream that shares its queue with the stream of the
+    // copy-engine transfers stands still for the length of every transfer.
+    ctx->s_aux = ctx->s_in[0];
+    if (rc == SS_OK && cfg.copy_path == SS_PATH_STAGED) {
+      ctx->n_s_out = 1;            // gathers and direct batches share one stream; transfers out of the ring have their own
+      ctx->n_slots = (uint32_t)(cfg.ring_bytes / cfg.ring_slot_bytes);
+      if ((e = hipStreamCreateWithFlags(&ctx->s_flush, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+      if (rc == SS_OK && (e = hipMalloc((void **)&ctx->ring, (size_t)ctx->n_slots * cfg.ring_slot_bytes)) != hipSuccess)
+        fail(SS_E_NOMEM, e);
+    }
     for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
       hipEvent_t ev;
       if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming | fence_flag(cfg))) != hipSuccess) fail(SS_E_HIP, e);
@@ -147,6 +166,7 @@ static int sync_swap_streams(ss_ctx *ctx) {
     if (ctx->s_out[i]) SS_HIP(hipStreamSynchronize(ctx->s_out[i]));
   for (uint32_t i = 0; i < ctx->n_s_in; ++i)
     if (ctx->s_in[i]) SS_HIP(hipStreamSynchronize(ctx->s_in[i]));
+  if (ctx->s_flush) SS_HIP(hipStreamSynchronize(ctx->s_flush));
   return SS_OK;
 }
 
@@ -156,6 +176,8 @@ static void sched_release(ss_sched &s) {
     free_events(s.ev_in_done[p]);
     free_events(s.ev_out_start[p]);
     free_events(s.ev_in_start[p]);
+    free_events(s.ev_gathered[p]);
+    free_events(s.ev_flush_start[p]);
   }
   free_events(s.ev_free_at);
   free_events(s.ev_wait_at);
@@ -176,14 +198,14 @@ static void sched_release(ss_sched &s) {
 extern "C" int ss_destroy(ss_ctx *ctx) {
   if (!ctx) return SS_E_INVAL;
   (void)sync_swap_streams(ctx);
-  if (ctx->s_aux) (void)hipStreamSynchronize(ctx->s_aux);
   sched_release(ctx->sched);
   for (hipEvent_t ev : ctx->ev_ring) (void)hipEventDestroy(ev);
   for (int i = 0; i < ss_ctx::kMaxSwapStreams; ++i) {
     if (ctx->s_out[i]) (void)hipStreamDestroy(ctx->s_out[i]);
     if (ctx->s_in[i]) (void)hipStreamDestroy(ctx->s_in[i]);
   }
-  if (ctx->s_aux) (void)hipStreamDestroy(ctx->s_aux);
+  if (ctx->s_flush) (void)hipStreamDestroy(ctx->s_flush);
+  if (ctx->ring) (void)hipFree(ctx->ring);
   if (ctx->staging) (void)hipHostFree(ctx->staging);
   if (ctx->ops) (void)hipHostFree(ctx->ops);
   if (ctx->events) (void)hipHostFree(ctx->events);
@@ -236,6 +258,20 @@ int ss_scratch_reserve(ss_ctx *ctx, size_t dev_bytes, size_t host_bytes) {
 }
 
 // ---- schedule ------------------------------------------------------------------
+
+// per-iteration state of the staged swap-out path
+static void ring_reset(ss_sched &s, uint32_t n_slots) {
+  std::fill(s.done_ev_of.begin(), s.done_ev_of.end(), -1);
+  std::fill(s.ring_state.begin(), s.ring_state.end(), 0);
+  for (size_t g = 0; g < s.groups.size(); ++g) {
+    s.group_pending[g] = s.groups[g].last - s.groups[g].first + 1;
+    s.group_gathered[g] = s.group_started[g] = 0;
+    s.group_last_flush[g] = -1;
+  }
+  s.slot_owner.assign(n_slots, -1);
+  std::fill(s.out_staged.begin(), s.out_staged.end(), 0);
+  s.last_flush_batch = s.last_gather_batch = -1;
+}
 
 static int check_descs(const ss_ctx *ctx, const ss_desc_t *d, uint32_t n) {
   for (uint32_t i = 0; i < n; ++i) {
@@ -337,6 +373,7 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
         std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
         std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
         s.last_engine_out = -1;
+        ring_reset(s, ctx->n_slots);
         return SS_OK;
       }
     }
@@ -386,13 +423,63 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     s.in_waited.assign(n_in_batches, 0);
     s.in_issued.assign(n_in_batches, 0);
     s.last_engine_out = -1;
+    // staged swap-out: group consecutive batches whose staging slots form one gap-free range (every size
+    // a multiple of the slot alignment, no guards) of at most one ring slot
+    s.groups.clear();
+    s.group_bytes.clear();
+    s.group_of.assign(n_out_batches, -1);
+    s.prev_direct.assign(n_out_batches, -1);
+    if (ctx->cfg.copy_path == SS_PATH_STAGED && ctx->ring) {
+      const uint64_t slot = ctx->cfg.ring_slot_bytes;
+      bool open = false;
+      for (uint32_t b = 0; b < n_out_batches; ++b) {
+        const uint32_t lo = s.out_start[b], hi = s.out_start[b + 1];
+        bool ok = hi > lo && ctx->cfg.guard_bytes == 0;
+        uint64_t total = 0;
+        for (uint32_t i = lo; i < hi && ok; ++i) {
+          ok = s.out[i].nbytes != 0 && s.out[i].nbytes % ctx->cfg.align == 0 &&
+               (i == lo || s.out[i].host_off == s.out[i - 1].host_off + s.out[i - 1].nbytes);
+          total += s.out[i].nbytes;
+        }
+        ok = ok && total <= slot;
+        if (!ok) { open = false; continue; }
+        if (open) {
+          ss_sched::out_group &g = s.groups.back();
+          if (s.out[lo].host_off == g.host_lo + g.bytes && g.bytes + total <= slot) {
+            g.last = b;
+            g.bytes += total;
+            s.group_of[b] = (int32_t)s.groups.size() - 1;
+            continue;
+          }
+        }
+        s.groups.push_back(ss_sched::out_group{b, b, s.out[lo].host_off, total});
+        s.group_of[b] = (int32_t)s.groups.size() - 1;
+        open = true;
+      }
+      for (const ss_sched::out_group &g : s.groups) s.group_bytes.push_back(g.bytes);
+    }
+    for (uint32_t b = 0, last = 0, have = 0; b < n_out_batches; ++b) {
+      if (s.group_of[b] < 0) { last = b; have = 1; }
+      s.prev_direct[b] = have ? (int32_t)last : -1;
+    }
+    // SS_PATH_AUTO (and the batches SS_PATH_STAGED leaves alone): one path for the whole swap-out side
     s.out_all_large = ctx->cfg.engine_min_bytes_out != 0 && n_out_batches != 0;
     for (uint32_t b = 0; b < n_out_batches && s.out_all_large; ++b) {
+      if (s.group_of[b] >= 0) continue;
       uint64_t total = 0;
       const uint32_t cnt = s.out_start[b + 1] - s.out_start[b];
       for (uint32_t i = s.out_start[b]; i < s.out_start[b + 1]; ++i) total += s.out[i].nbytes;
       if (cnt && total / cnt < ctx->cfg.engine_min_bytes_out) s.out_all_large = false;
     }
+    s.done_ev_of.assign(n_out_batches, -1);
+    s.done_ev_of_drained.assign(n_out_batches, -1);
+    s.out_staged.assign(n_out_batches, 0);
+    s.ring_state.assign(n_out_batches, 0);
+    s.group_pending.assign(s.groups.size(), 0);
+    s.group_gathered.assign(s.groups.size(), 0);
+    s.group_started.assign(s.groups.size(), 0);
+    s.group_last_flush.assign(s.groups.size(), -1);
+    ring_reset(s, ctx->n_slots);
 
     const bool stall = (ctx->cfg.flags & SS_CFG_STALL_TIMING) != 0;
     const unsigned evflags = ((ctx->cfg.flags & (SS_CFG_TIMING | SS_CFG_STALL_TIMING)) ? hipEventDefault
@@ -404,6 +491,11 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     }
     for (int p = 0; p < 2; ++p) {
       if ((rc = ensure_events(ctx, s.ev_out_done[p], n_out_batches, evflags)) != SS_OK) return rc;
+      if (!s.groups.empty()) {
+        if ((rc = ensure_events(ctx, s.ev_gathered[p], n_out_batches, evflags)) != SS_OK) return rc;
+        if ((ctx->cfg.flags & SS_CFG_TIMING) &&
+            (rc = ensure_events(ctx, s.ev_flush_start[p], s.groups.size(), evflags)) != SS_OK) return rc;
+      }
       if ((rc = ensure_events(ctx, s.ev_in_done[p], n_in_batches, evflags)) != SS_OK) return rc;
       if (ctx->cfg.flags & SS_CFG_TIMING) {
         if ((rc = ensure_events(ctx, s.ev_out_start[p], n_out_batches, evflags)) != SS_OK) return rc;
@@ -496,6 +588,7 @@ static bool use_engine(const ss_ctx *ctx, uint32_t path, bool to_host, const std
                        uint32_t lo, uint32_t hi) {
   if (path == SS_PATH_ENGINE) return true;
   if (path == SS_PATH_KERNEL) return false;
+  // SS_PATH_AUTO, and the batches SS_PATH_STAGED does not stage
   if (to_host) return ctx->sched.out_all_large;        // one path for the whole swap-out side (see above)
   if (hi <= lo) return false;
   uint64_t total = 0;
@@ -512,6 +605,106 @@ static hipEvent_t next_marker(ss_ctx *ctx) {
   return ev;
 }
 
+// Staged swap-out: send what group g has in the ring and has not sent yet.  Per batch, ring_state is
+// 0 = not issued, 1 = gathered into the ring, 2 = on its way to the staging area (or left directly).
+// Every maximal run of gathered batches goes in one copy-engine transfer, which waits for the gathers
+// and records the done-event of the run's last batch, standing for all of the run.
+static int ring_flush(ss_ctx *ctx, uint32_t g) {
+  ss_sched &s = ctx->sched;
+  const ss_sched::out_group &G = s.groups[g];
+  const uint8_t *slot = ctx->ring + (size_t)(g % ctx->n_slots) * ctx->cfg.ring_slot_bytes;
+  for (uint32_t b = G.first; b <= G.last;) {
+    if (s.ring_state[b] != 1) { ++b; continue; }
+    uint32_t e = b;
+    while (e <= G.last && s.ring_state[e] == 1) ++e;          // run [b, e)
+    const uint64_t lo = s.out[s.out_start[b]].host_off;
+    uint64_t bytes = 0;
+    for (uint32_t i = s.out_start[b]; i < s.out_start[e]; ++i) bytes += s.out[i].nbytes;
+    // the gathers run in issue order on one stream: the most recent one stands for all before it
+    SS_HIP(hipStreamWaitEvent(ctx->s_flush, s.ev_gathered[s.phase][(size_t)s.last_gather_batch], 0));
+    if ((ctx->cfg.flags & SS_CFG_TIMING) && !s.group_started[g]) SS_HIP(hipEventRecord(s.ev_flush_start[s.phase][g], ctx->s_flush));
+    s.group_started[g] = 1;
+    SS_HIP(hipMemcpyAsync(ctx->staging + lo, slot + (lo - G.host_lo), bytes, hipMemcpyDeviceToHost, ctx->s_flush));
+    SS_HIP(hipEventRecord(s.ev_out_done[s.phase][e - 1], ctx->s_flush));
+    for (uint32_t x = b; x < e; ++x) {
+      s.done_ev_of[x] = (int32_t)(e - 1);
+      s.ring_state[x] = 2;
+    }
+    s.last_flush_batch = e - 1;
+    s.group_last_flush[g] = (int32_t)(e - 1);
+    ctx->stats.ring_transfers++;
+    b = e;
+  }
+  return SS_OK;
+}
+
+// every gathered batch of every group is sent (before a swap-in that may need it, and at the drain)
+static int ring_flush_all(ss_ctx *ctx) {
+  ss_sched &s = ctx->sched;
+  for (uint32_t g = 0; g < s.groups.size(); ++g) {
+    if (!s.group_gathered[g]) continue;
+    const int rc = ring_flush(ctx, g);
+    if (rc != SS_OK) return rc;
+    s.group_gathered[g] = 0;
+  }
+  return SS_OK;
+}
+
+// Swap-out of a batch that goes through the ring: gather on the swap-out stream, transfer when every
+// batch of the group has been issued.  Returns 1 if the batch was handled here, 0 if it must leave
+// directly (its ring slot already belongs to a later group: batches issued out of order), or an error code.
+static int swap_out_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
+  ss_sched &s = ctx->sched;
+  const int32_t g = s.group_of[batch];
+  const ss_sched::out_group &G = s.groups[(size_t)g];
+  const uint32_t slot = (uint32_t)g % ctx->n_slots;
+  if (s.slot_owner[slot] > g) {
+    s.ring_state[batch] = 2;
+    if (s.group_pending[(size_t)g]) s.group_pending[(size_t)g]--;
+    return 0;
+  }
+  hipStream_t so = ctx->s_out[0];
+  if (s.slot_owner[slot] != g) {
+    if (s.slot_owner[slot] >= 0) {
+      // the slot still holds an earlier group: whatever of it has been gathered leaves now, and the first
+      // gather of this group waits until the slot's last transfer has read it
+      const uint32_t og = (uint32_t)s.slot_owner[slot];
+      const int rc = ring_flush(ctx, og);
+      if (rc != SS_OK) return rc;
+      s.group_gathered[og] = 0;
+      if (s.group_last_flush[og] >= 0)
+        SS_HIP(hipStreamWaitEvent(so, s.ev_out_done[s.phase][(size_t)s.group_last_flush[og]], 0));
+    }
+    s.slot_owner[slot] = g;
+  }
+  const uint32_t lo = s.out_start[batch], hi = s.out_start[batch + 1];
+  SS_HIP(hipStreamWaitEvent(so, mark, 0));
+  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_out_start[s.phase][batch], so));
+  // the kernel adds each descriptor's host_off to its staging pointer: point it so that the group's
+  // first byte lands on the first byte of the ring slot
+  uint8_t *base = (uint8_t *)((uintptr_t)ctx->ring + (uintptr_t)slot * ctx->cfg.ring_slot_bytes - (uintptr_t)G.host_lo);
+  const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
+  const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
+  ss_launch_copy(so, ctx->cfg.gather_workgroups, ctx->cfg.copy_unroll, true, ctx->arena, base, s.d_out + lo, c0,
+                 s.d_out_cdesc + s.out_cbase[batch], n_chunks, s.out_shift[batch]);
+  SS_HIP(hipGetLastError());
+  SS_HIP(hipEventRecord(s.ev_gathered[s.phase][batch], so));
+  s.out_issued[batch] = 1;
+  s.out_staged[batch] = 1;
+  s.ring_state[batch] = 1;
+  s.group_gathered[(size_t)g] = 1;
+  s.last_gather_batch = batch;
+  ctx->stats.kernel_batches++;
+  ctx->stats.ring_batches++;
+  if (s.group_pending[(size_t)g]) s.group_pending[(size_t)g]--;
+  if (s.group_pending[(size_t)g] == 0) {                       // the group is complete
+    const int rc = ring_flush(ctx, (uint32_t)g);
+    if (rc != SS_OK) return rc;
+    s.group_gathered[(size_t)g] = 0;
+  }
+  return 1;
+}
+
 extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
   if (!ctx) return SS_E_INVAL;
   ss_sched &s = ctx->sched;
@@ -525,6 +718,16 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
   // the tensors' last forward use is already enqueued on the compute stream: order after it
   hipEvent_t mark = next_marker(ctx);
   SS_HIP(hipEventRecord(mark, ctx->compute));
+  if (s.group_of[batch] >= 0) {
+    const int rc = swap_out_staged(ctx, batch, mark);
+    if (rc < 0) return rc;
+    if (rc == 1) {
+      uint64_t moved = 0;
+      for (uint32_t i = lo; i < hi; ++i) moved += s.out[i].nbytes;
+      ctx->stats.bytes_out += moved;
+      return SS_OK;
+    }
+  }
   SS_HIP(hipStreamWaitEvent(so, mark, 0));
   if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_out_start[s.phase][batch], so));
   uint64_t bytes = 0;
@@ -546,6 +749,7 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
     ctx->stats.kernel_batches++;
   }
   SS_HIP(hipEventRecord(s.ev_out_done[s.phase][batch], so));
+  s.done_ev_of[batch] = (int32_t)batch;
   s.out_issued[batch] = 1;
   ctx->stats.bytes_out += bytes;
   return SS_OK;
@@ -568,10 +772,19 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
   // staging slots must be completely written: the batch's tensors left in swap-out batches up to in_dep;
   // with the swap-out batches spread over n streams, the last n of them up to in_dep cover every stream
   // (each stream runs its own batches in order)
-  if (hi > lo) {
+  if (hi > lo && s.groups.empty()) {
     const uint32_t dep = s.in_dep[batch];
     for (uint32_t back = 0; back < ctx->n_s_out && back <= dep; ++back)
       if (s.out_issued[dep - back]) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][dep - back], 0));
+  } else if (hi > lo) {
+    // staged swap-out (one swap-out stream): what has been gathered so far leaves the ring now; the batch
+    // waits for the last direct batch up to in_dep and for the last transfer out of the ring (a copy-engine
+    // transfer towards the host must not meet one coming back anyway, see below)
+    const int rc = ring_flush_all(ctx);
+    if (rc != SS_OK) return rc;
+    const int32_t pd = s.prev_direct[s.in_dep[batch]];
+    if (pd >= 0 && s.out_issued[(size_t)pd]) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)pd], 0));
+    if (s.last_flush_batch >= 0) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)s.last_flush_batch], 0));
   }
   // a copy-engine swap-out collapses to a quarter of the link rate as soon as anything flows the
   // other way: no swap-in starts before the engine swap-outs issued so far have finished
@@ -612,8 +825,9 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
       if (!s.out_issued[b]) return SS_E_STATE;   // releasing a block whose swap-out was never issued
       if (!s.out_waited[b]) {
         if (ctx->cfg.flags & SS_CFG_STALL_TIMING) SS_HIP(hipEventRecord(s.ev_free_at[b], ctx->compute));
-        // device-side: later compute-stream work starts only after the batch has left HBM
-        SS_HIP(hipStreamWaitEvent(ctx->compute, s.ev_out_done[s.phase][b], 0));
+        // device-side: later compute-stream work starts only after the batch has left its blocks (for the
+        // staging area, or, staged, for the ring)
+        SS_HIP(hipStreamWaitEvent(ctx->compute, s.out_staged[b] ? s.ev_gathered[s.phase][b] : s.ev_out_done[s.phase][b], 0));
         s.out_waited[b] = 1;
         ctx->stats.free_waits++;
       }
@@ -640,7 +854,8 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
     }
     case SS_SYNC_DRAIN: {
       {
-        const int rc = sync_swap_streams(ctx);
+        int rc = s.loaded ? ring_flush_all(ctx) : SS_OK;      // staged batches whose group never completed
+        if (rc == SS_OK) rc = sync_swap_streams(ctx);
         if (rc != SS_OK) return rc;
       }
       if ((ctx->cfg.flags & SS_CFG_STALL_TIMING) && s.loaded) {
@@ -650,7 +865,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
         for (size_t b = 0; b < s.out_waited.size(); ++b)
           if (s.out_waited[b]) {
             float ms = 0.f;
-            SS_HIP(hipEventElapsedTime(&ms, s.ev_free_at[b], s.ev_out_done[s.phase][b]));
+            SS_HIP(hipEventElapsedTime(&ms, s.ev_free_at[b], s.out_staged[b] ? s.ev_gathered[s.phase][b] : s.ev_out_done[s.phase][b]));
             if (ms > 0.f) ctx->stats.stall_free_ms += ms;
           }
         for (size_t b = 0; b < s.in_waited.size(); ++b)
@@ -668,6 +883,10 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
       if (s.loaded) {              // the next iteration records into the other event set
         s.phase ^= 1;
         s.drained_once = true;
+        s.done_ev_of_drained = s.done_ev_of;
+        s.out_staged_drained = s.out_staged;
+        s.group_last_flush_drained = s.group_last_flush;
+        ring_reset(s, ctx->n_slots);
       }
       return SS_OK;
     }
@@ -696,28 +915,57 @@ extern "C" int ss_dispatch(ss_ctx *ctx, uint32_t op_idx, uint32_t when) {
   return SS_OK;
 }
 
+// Start / end event of unit `u` of direction `dir` in the iteration drained last: dir 0 swap-out batch
+// (a staged batch: its gather into the ring), 1 swap-in batch, 2 transfer of ring group u to the host.
+static int timing_events(ss_ctx *ctx, uint32_t dir, uint32_t u, hipEvent_t *st, hipEvent_t *dn) {
+  ss_sched &s = ctx->sched;
+  const int set = s.drained_once ? s.phase ^ 1 : s.phase;
+  const std::vector<uint8_t> &staged = s.drained_once ? s.out_staged_drained : s.out_staged;
+  if (dir == 0) {
+    if (u + 1 >= s.out_start.size()) return SS_E_INVAL;
+    *st = s.ev_out_start[set][u];
+    *dn = staged[u] ? s.ev_gathered[set][u] : s.ev_out_done[set][u];
+  } else if (dir == 1) {
+    if (u + 1 >= s.in_start.size()) return SS_E_INVAL;
+    *st = s.ev_in_start[set][u];
+    *dn = s.ev_in_done[set][u];
+  } else {
+    if (u >= s.groups.size()) return SS_E_INVAL;
+    const std::vector<int32_t> &lf = s.drained_once ? s.group_last_flush_drained : s.group_last_flush;
+    if (u >= lf.size() || lf[u] < 0) return SS_E_STATE;        // nothing of the group went through the ring
+    *st = s.ev_flush_start[set][u];
+    *dn = s.ev_out_done[set][(size_t)lf[u]];
+  }
+  return SS_OK;
+}
+
+static size_t timing_units(const ss_sched &s, uint32_t dir) {
+  return dir == 0 ? s.out_start.size() - 1 : dir == 1 ? s.in_start.size() - 1 : s.groups.size();
+}
+
 extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms) {
-  if (!ctx || dir > 1) return SS_E_INVAL;
+  if (!ctx || dir > 2) return SS_E_INVAL;
   if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
   ss_sched &s = ctx->sched;
-  const int set = s.drained_once ? s.phase ^ 1 : s.phase;      // the iteration drained last
-  auto &st = dir ? s.ev_in_start[set] : s.ev_out_start[set];
-  auto &dn = dir ? s.ev_in_done[set] : s.ev_out_done[set];
-  const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
+  const size_t nb = timing_units(s, dir);
+  hipEvent_t st, dn;
+  int rc;
   if (ms) {
-    if (batch >= nb) return SS_E_INVAL;
-    SS_HIP(hipEventElapsedTime(ms, st[batch], dn[batch]));
+    if ((rc = timing_events(ctx, dir, batch, &st, &dn)) != SS_OK) return rc;
+    SS_HIP(hipEventElapsedTime(ms, st, dn));
   }
   if (span_ms) {
-    if (nb == 0) { *span_ms = 0.f; return SS_OK; }
-    // first start to last end: with several streams per direction the batches need not end in order
-    float best = 0.f;
+    *span_ms = 0.f;
+    if (nb == 0) return SS_OK;
+    // first start to last end: with several streams per direction the units need not end in order
+    hipEvent_t st0, dn0;
+    if ((rc = timing_events(ctx, dir, 0, &st0, &dn0)) != SS_OK) return rc;
     for (size_t b = nb > 8 ? nb - 8 : 0; b < nb; ++b) {
       float x = 0.f;
-      SS_HIP(hipEventElapsedTime(&x, st[0], dn[b]));
-      if (x > best) best = x;
+      if (timing_events(ctx, dir, (uint32_t)b, &st, &dn) != SS_OK) continue;
+      SS_HIP(hipEventElapsedTime(&x, st0, dn));
+      if (x > *span_ms) *span_ms = x;
     }
-    *span_ms = best;
   }
   return SS_OK;
 }
@@ -729,7 +977,12 @@ extern "C" int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *don
   const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
   if (batch >= nb) return SS_E_INVAL;
   if (!(dir ? s.in_issued[batch] : s.out_issued[batch])) return SS_E_STATE;
-  const hipError_t e = hipEventQuery(dir ? s.ev_in_done[s.phase][batch] : s.ev_out_done[s.phase][batch]);
+  if (dir == 0 && s.done_ev_of[batch] < 0) {                  // gathered into the ring, not yet on its way to the host
+    *done = 0;
+    return SS_OK;
+  }
+  const hipError_t e = hipEventQuery(dir ? s.ev_in_done[s.phase][batch]
+                                         : s.ev_out_done[s.phase][(size_t)s.done_ev_of[batch]]);
   if (e == hipErrorNotReady) {
     (void)hipGetLastError();
     *done = 0;
@@ -741,16 +994,26 @@ extern "C" int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *don
 }
 
 extern "C" int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *start_ms, float *end_ms) {
-  if (!ctx || dir > 1 || !start_ms || !end_ms) return SS_E_INVAL;
+  if (!ctx || dir > 2 || !start_ms || !end_ms) return SS_E_INVAL;
   if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
   ss_sched &s = ctx->sched;
-  const int set = s.drained_once ? s.phase ^ 1 : s.phase;      // the iteration drained last
-  auto &st = dir ? s.ev_in_start[set] : s.ev_out_start[set];
-  auto &dn = dir ? s.ev_in_done[set] : s.ev_out_done[set];
-  const size_t nb = (dir ? s.in_start.size() : s.out_start.size()) - 1;
-  if (batch >= nb || s.out_start.size() < 2) return SS_E_INVAL;
-  SS_HIP(hipEventElapsedTime(start_ms, s.ev_out_start[set][0], st[batch]));
-  SS_HIP(hipEventElapsedTime(end_ms, s.ev_out_start[set][0], dn[batch]));
+  if (s.out_start.size() < 2) return SS_E_INVAL;
+  hipEvent_t st, dn, st0, dn0;
+  int rc;
+  if ((rc = timing_events(ctx, dir, batch, &st, &dn)) != SS_OK) return rc;
+  if ((rc = timing_events(ctx, 0, 0, &st0, &dn0)) != SS_OK) return rc;
+  SS_HIP(hipEventElapsedTime(start_ms, st0, st));
+  SS_HIP(hipEventElapsedTime(end_ms, st0, dn));
+  return SS_OK;
+}
+
+extern "C" int ss_ring_view(ss_ctx *ctx, uint32_t *n_groups, const int32_t **group_of, const uint64_t **group_bytes) {
+  if (!ctx) return SS_E_INVAL;
+  if (!ctx->sched.loaded) return SS_E_STATE;
+  const ss_sched &s = ctx->sched;
+  if (n_groups) *n_groups = (uint32_t)s.groups.size();
+  if (group_of) *group_of = s.group_of.data();
+  if (group_bytes) *group_bytes = s.group_bytes.data();
   return SS_OK;
 }
 

@@ -1,0 +1,169 @@
+"""GPU parity of the staged swap-out path (SS_PATH_STAGED: copy kernel gathers batches into an HBM ring,
+one copy-engine transfer per ring group carries them to the staging area) against the oracle's byte
+copies and against the run without swapping."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from workloads.arena import place_tensors
+from helpers import oracle_execute, assert_applied_equal
+
+pytestmark = pytest.mark.gpu
+INSTANT = 1 << 40
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2509_11076_amd.binding as B
+    return B
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+def make_ctx(P, **kw):
+    cfg = P.ss_config_default()
+    for k, v in kw.items():
+        setattr(cfg, k, v)
+    return P.ss_create(cfg)
+
+
+def random_arena(torch, nbytes, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    a = torch.randint(-2**62, 2**62, ((nbytes + 7) // 8,), dtype=torch.int64, device="cuda", generator=g)
+    return a.view(torch.uint8)[:nbytes]
+
+
+@pytest.mark.parametrize("bpo", [64 * 1024, INSTANT])
+@pytest.mark.parametrize("slot_kib,slots", [(512, 2), (1024, 3), (4096, 2)])
+def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots):
+    """configuration 1 with ring slots smaller than, about, and larger than a layer's swap set: staging
+    image and arena (with poison over released blocks) equal the oracle's, byte for byte"""
+    from paper_2509_11076_amd.executor import run_iteration
+    tr = W.build_trace(W.config_shape(1))
+    pol = W.config_swap_set(tr, 1)
+    idx = pol["ref_op"].astype(np.int64)
+    ap0 = oracle.apply_policy(pol, idx, tr.tensors, bpo)
+    swapped = {r[2]: (r[5], r[6]) for r in ap0["resolved"] if not r[3] & 3}
+    arena_bytes = place_tensors(tr.tensors, swapped=swapped)
+    ora = oracle.apply_policy(pol, idx, tr.tensors, bpo)
+    arena = random_arena(torch, arena_bytes, 2509)
+    host_arena = arena.cpu().numpy().copy()
+    ctx = make_ctx(P, staging_bytes=ora["staging_bytes"], link_bytes_per_op=bpo, copy_path=P.SS_PATH_STAGED,
+                   ring_slot_bytes=slot_kib << 10, ring_bytes=slots * (slot_kib << 10),
+                   flags=P.SS_CFG_POISON_FREE | P.SS_CFG_TIMING)
+    try:
+        P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+        for it in range(2):                     # the second iteration re-uses ring slots and event sets
+            lib = P.ss_apply_policy(ctx, pol, idx, tr.tensors)
+            assert_applied_equal(lib, P, ctx, ora)
+            group_of, group_bytes = P.ss_ring_view(ctx)
+            assert (group_of >= 0).all() and len(group_bytes) >= 1 and int(group_bytes.max()) <= slot_kib << 10
+            assert int(group_bytes.sum()) == sum(d[2] for d in ora["descs_out"])
+            P.ss_staging_fill(ctx, 0xA5)
+            staging = np.full(ora["staging_bytes"], 0xA5, dtype=np.uint8)
+            run_iteration(ctx, tr.n_ops, lib["actions"], None)
+            torch.cuda.synchronize()
+            oracle_execute(host_arena, staging, ora, poison=0xDB)
+            assert np.array_equal(P.ss_host_peek(ctx, 0, ora["staging_bytes"]), staging)
+            assert np.array_equal(arena.cpu().numpy(), host_arena)
+            for g in range(len(group_bytes)):
+                assert P.ss_batch_ms(ctx, 2, g)[0] > 0
+            assert P.ss_batch_ms(ctx, 2)[1] > 0 and P.ss_batch_ms(ctx, 0, 0)[0] > 0
+        st = P.ss_get_stats(ctx)
+        assert st["ring_batches"] == 2 * lib["n_out_batches"] and st["ring_transfers"] >= 2 * len(group_bytes)
+        assert st["bytes_out"] == st["bytes_in"] == 2 * sum(d[2] for d in ora["descs_out"])
+    finally:
+        P.ss_destroy(ctx)
+
+
+def test_ring_takes_only_gap_free_batches_and_the_rest_leaves_directly(P, torch):
+    """a schedule mixing batches the ring can take (sizes multiples of the alignment, consecutive slots)
+    with ragged ones and one larger than a slot; batches issued out of order; a release between the gather
+    and the transfer; swap-ins that need a group before it is complete"""
+    KiB = 1 << 10
+    sizes = [256 * KiB, 512 * KiB, 256 * KiB,          # batches 0, 1, 2: one group (slot 1 MiB)
+             300 * KiB + 5,                            # batch 3: ragged -> direct
+             256 * KiB, 256 * KiB,                     # batch 4 (two tensors): a group of its own with batch 5?
+             768 * KiB,                                # batch 5: fits the same slot together with batch 4? 512 + 768 > 1024 -> new group
+             2048 * KiB,                               # batch 6: larger than a slot -> direct
+             128 * KiB, 128 * KiB]                     # batches 7, 8: one group
+    starts = [0, 1, 2, 3, 4, 6, 7, 8, 9, 10]
+    n = len(sizes)
+    d = np.zeros(n, dtype=W.DESC_DT)
+    off = h = 0
+    for i, sz in enumerate(sizes):
+        d[i] = (off, h, sz, i, 0)
+        off += (sz + 4095) // 4096 * 4096 + 4096
+        h += (sz + 255) // 256 * 256
+    arena_bytes = off
+    arena = random_arena(torch, arena_bytes, 9)
+    host = arena.cpu().numpy().copy()
+    start = np.array(starts, dtype=np.uint32)
+    ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_STAGED, ring_slot_bytes=1024 * KiB, ring_bytes=2048 * KiB,
+                   flags=P.SS_CFG_TIMING)
+    try:
+        P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+        dep = np.arange(9, dtype=np.uint32)                    # swap-in batch b needs swap-out batch b only
+        P.ss_load_schedule(ctx, d, start, d, start, dep)
+        group_of, group_bytes = P.ss_ring_view(ctx)
+        assert group_of.tolist() == [0, 0, 0, -1, 1, 2, -1, 3, 3]
+        assert group_bytes.tolist() == [1024 * KiB, 512 * KiB, 768 * KiB, 256 * KiB]
+        for order in ([0, 1, 2, 3, 4, 5, 6, 7, 8], [1, 0, 2, 4, 3, 6, 5, 8, 7], [8, 7, 6, 5, 4, 3, 2, 1, 0]):
+            P.ss_staging_fill(ctx, 0x11)
+            for k, b in enumerate(order):
+                P.ss_swap_out(ctx, b)
+                if k == 1:                                         # release right after the gather
+                    lo = starts[order[0]]
+                    P.ss_sync(ctx, P.SS_SYNC_FREE, lo)
+                if k == 4:                                         # a swap-in while groups are still open
+                    P.ss_swap_in(ctx, order[0])
+            for b in range(9):
+                if b != order[0]:
+                    P.ss_swap_in(ctx, b)
+            assert P.ss_batch_done(ctx, 0, 3) in (True, False)
+            P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+            torch.cuda.synchronize()
+            staging = np.full(h, 0x11, dtype=np.uint8)
+            oracle.swap_out(host, staging, [tuple(int(x) for x in r) for r in d.tolist()])
+            assert np.array_equal(P.ss_host_peek(ctx, 0, h), staging), order
+            assert np.array_equal(arena.cpu().numpy(), host)
+    finally:
+        P.ss_destroy(ctx)
+    # guards switch the ring off altogether
+    ctx = make_ctx(P, staging_bytes=2 * h + 4096, copy_path=P.SS_PATH_STAGED, guard_bytes=256)
+    try:
+        P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+        d2 = d.copy()
+        d2["host_off"] = 256 + np.cumsum([0] + [(sz + 255) // 256 * 256 + 256 for sz in sizes[:-1]])
+        P.ss_load_schedule(ctx, d2, start, d2, start)
+        assert (P.ss_ring_view(ctx)[0] == -1).all()
+    finally:
+        P.ss_destroy(ctx)
+
+
+def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch):
+    """configuration 2, three iterations, every swap-out through the ring (all its sizes are multiples of
+    the alignment), blocks poisoned at their release: compute results equal the run without swapping"""
+    B = P
+    from workloads.harness import SwapRun
+    res = []
+    for swap in (False, True):
+        r = SwapRun(B, torch, 2, swap=swap, bpo=11 << 20, bpo_in=4760000, copy_path=B.SS_PATH_STAGED,
+                    copy_path_in=B.SS_PATH_AUTO, flags=(B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE) if swap else 0)
+        try:
+            for _ in range(3):
+                r.step() if swap else r.step_noswap()
+            res.append((r.compute.result(), B.ss_get_stats(r.ctx), r.bytes_each_way))
+        finally:
+            r.close()
+    (c0, g0), _, _ = res[0]
+    (c1, g1), st, moved = res[1]
+    assert np.array_equal(c0, c1) and np.array_equal(g0, g1)
+    assert st["bytes_out"] == st["bytes_in"] == 3 * moved and st["ring_batches"] == 3 * 120
+    assert 0 < st["ring_transfers"] < st["ring_batches"]

@@ -16,13 +16,17 @@ class ArenaPlan:
     arena_bytes: int         # high-water mark (including guards)
 
 
-def place_first_fit(start_op, end_op, nbytes, align=256, guard=0, capacity=None):
+def place_first_fit(start_op, end_op, nbytes, align=256, guard=0, capacity=None, reuse_delay=0):
     """Place intervals [start_op, end_op] (inclusive operator indices) of nbytes each.
 
     A block released after operator e can be taken by an interval starting at
     e + 1 or later, never by one starting at e.  Lowest-address-first fit;
     every block is preceded and followed by `guard` untouched bytes.  Raises
-    MemoryError if `capacity` is given and exceeded.
+    MemoryError if `capacity` is given and exceeded.  reuse_delay > 0 keeps a
+    released block out of the pool for that many more operators (an allocator
+    that does not hand a block straight back costs that much memory and lets
+    the producer of the next tensor run without waiting for the block's
+    previous owner to have left).
     """
     n = len(start_op)
     start_op = np.asarray(start_op, dtype=np.int64)
@@ -47,7 +51,7 @@ def place_first_fit(start_op, end_op, nbytes, align=256, guard=0, capacity=None)
 
     for k in order:
         t = start_op[k]
-        while rel < n and end_op[by_end[rel]] < t:
+        while rel < n and end_op[by_end[rel]] + reuse_delay < t:
             j = by_end[rel]
             release(int(offsets[j]) - guard, int(size[j]))
             rel += 1
@@ -67,7 +71,7 @@ def place_first_fit(start_op, end_op, nbytes, align=256, guard=0, capacity=None)
     return ArenaPlan(offsets=offsets.astype(np.uint64), arena_bytes=int(high))
 
 
-def place_tensors(tensors, swapped=None, align=256, guard=0, capacity=None):
+def place_tensors(tensors, swapped=None, align=256, guard=0, capacity=None, reuse_delay=0):
     """Fill dev_off / dev_off_in of a tensor table.
 
     swapped: optional dict tensor_id -> (t_free, t_in); such a tensor is
@@ -87,7 +91,7 @@ def place_tensors(tensors, swapped=None, align=256, guard=0, capacity=None):
         else:
             s.append(int(t["alloc_op"])); e.append(int(t["free_op"]))
             b.append(int(t["nbytes"])); who.append((i, 0))
-    plan = place_first_fit(s, e, b, align=align, guard=guard, capacity=capacity)
+    plan = place_first_fit(s, e, b, align=align, guard=guard, capacity=capacity, reuse_delay=reuse_delay)
     for (i, part), off in zip(who, plan.offsets):
         if part == 0:
             tensors["dev_off"][i] = off

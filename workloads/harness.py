@@ -23,7 +23,7 @@ class SwapRun:
     def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
                  copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
                  policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None, generator=None,
-                 policy_points=True):
+                 policy_points=True, reuse_delay=0):
         from .compute import SyntheticCompute
         self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
         if trace is not None:
@@ -96,7 +96,7 @@ class SwapRun:
         if cfgno == 5 and trace is None:
             self.arena_bytes = 64 * 10**9          # placement is prescribed by the configuration
         else:
-            self.arena_bytes = place_tensors(tr.tensors, swapped=swapped, guard=guard)
+            self.arena_bytes = place_tensors(tr.tensors, swapped=swapped, guard=guard, reuse_delay=reuse_delay)
         self.n_forced = int(((res["flags"] & B.SS_F_FORCED) != 0).sum())
         self.n_dropped = int(ap["n_dropped"])
         self.staging_bytes = max(4096, int(ap["staging_bytes"]))
