@@ -101,11 +101,15 @@ typedef struct { uint32_t op_idx, kind, tensor_id, batch; } ss_action_t;        
 
 /* ---- configuration -------------------------------------------------------- */
 enum { SS_PATH_AUTO = 0, SS_PATH_KERNEL = 1, SS_PATH_ENGINE = 2,
-       SS_PATH_STAGED = 3 };  /* swap-out only: the copy kernel gathers consecutive batches into a slot of a ring
-                                 in HBM (the blocks can be released as soon as that is done), one copy-engine
-                                 transfer per slot carries them to the staging area.  Used for batches whose
-                                 staging slots are gap-free (sizes multiples of `align`, no guards) and fit a
-                                 ring slot; other batches leave as with SS_PATH_AUTO                        */
+       SS_PATH_STAGED = 3 };  /* through a ring in HBM.  Swap-out: the copy kernel gathers consecutive batches into
+                                 a ring slot (their blocks can be released as soon as that is done) and one
+                                 copy-engine transfer per slot carries them to the staging area.  Swap-in: one
+                                 copy-engine transfer brings the staging range of several consecutive batches
+                                 into a ring slot, issued with the first of them (so the link runs ahead of the
+                                 blocks becoming free), and the copy kernel scatters each batch into its blocks at
+                                 the batch's own issue point.  Used for batches whose staging slots are gap-free
+                                 (sizes multiples of `align`, no guards) and fit a ring slot; other batches
+                                 move as with SS_PATH_AUTO                                                   */
 enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch_ms)          */
        SS_CFG_POISON_FREE = 2,   /* overwrite a block with 0xDB when its FREE action runs     */
        SS_CFG_KEEP_LATE = 4,     /* keep items whose swap-out cannot finish before their first
@@ -149,8 +153,11 @@ typedef struct {
                                  shares a queue with another and waits for that one's work            */
   uint32_t in_streams;        /* the same for copy-kernel swap-in batches (0 = 1); copy-engine batches of
                                  either direction always use one stream                            */
-  uint64_t ring_bytes;        /* SS_PATH_STAGED: size of the HBM ring (0 = 512 MiB), allocated at ss_create  */
-  uint64_t ring_slot_bytes;   /* SS_PATH_STAGED: size of one ring slot = largest single transfer (0 = 128 MiB) */
+  uint64_t ring_bytes;        /* SS_PATH_STAGED: size of the HBM ring of a direction (0 = 1 GiB), allocated at
+                                 ss_create, one per staged direction                                          */
+  uint64_t ring_slot_bytes;   /* SS_PATH_STAGED: size of one ring slot = largest single transfer (0 = 256 MiB:
+                                 transfers of 64-134 MB out of the ring were seen to fall to a quarter of the
+                                 link rate for four transfers in a row, 252 MB and larger never)              */
   uint32_t gather_workgroups; /* SS_PATH_STAGED: grid of the gather launches, HBM to HBM (0 = 256)          */
   uint32_t reserved;
 } ss_config_t;
@@ -214,6 +221,7 @@ typedef struct {
   double stall_free_ms, stall_wait_in_ms;
   uint64_t ring_batches, ring_transfers; /* SS_PATH_STAGED: swap-out batches gathered into the HBM ring, and
                                             copy-engine transfers that carried them out of it */
+  uint64_t ring_batches_in, ring_transfers_in; /* the same for swap-in: batches scattered out of the ring, transfers into it */
 } ss_stats_t;
 
 typedef struct {
@@ -496,9 +504,9 @@ int ss_host_peek(ss_ctx *ctx, uint64_t host_off, uint64_t nbytes, const void **p
 int ss_staging_fill(ss_ctx *ctx, int byte);
 
 /* Duration of a batch on its swap stream in ms (needs SS_CFG_TIMING), in the iteration drained last;
- * dir 0 = out, 1 = in, 2 = the copy-engine transfers out of the HBM ring (SS_PATH_STAGED; `batch`
- * then counts the ring groups, see ss_ring_view).  A staged swap-out batch's own duration is that of
- * its gather into the ring.  span_ms (nullable): first start to last end over all batches (transfers)
+ * dir 0 = out, 1 = in, 2 = the copy-engine transfers out of the swap-out ring, 3 = those into the
+ * swap-in ring (SS_PATH_STAGED; `batch` then counts the ring groups, see ss_ring_view).  A staged
+ * batch's own duration is that of its gather into / scatter out of the ring.  span_ms (nullable): first start to last end over all batches (transfers)
  * of that direction. */
 int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms);
 
@@ -506,10 +514,11 @@ int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *spa
  * the same iteration (needs SS_CFG_TIMING; all batches involved must have completed). */
 int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *start_ms, float *end_ms);
 
-/* SS_PATH_STAGED: how the loaded schedule's swap-out batches were grouped.  n_groups ring groups;
- * group_of (borrowed, one entry per swap-out batch) = the batch's group or -1 if it leaves directly;
- * group_bytes (borrowed, n_groups entries) = bytes of each group's transfer. */
-int ss_ring_view(ss_ctx *ctx, uint32_t *n_groups, const int32_t **group_of, const uint64_t **group_bytes);
+/* SS_PATH_STAGED: how the loaded schedule's batches of direction dir (0 = out, 1 = in) were grouped.
+ * n_groups ring groups; group_of (borrowed, one entry per batch of that direction) = the batch's group
+ * or -1 if it moves directly; group_bytes (borrowed, n_groups entries) = bytes of each group's transfer. */
+int ss_ring_view(ss_ctx *ctx, uint32_t dir, uint32_t *n_groups, const int32_t **group_of,
+                 const uint64_t **group_bytes);
 
 /* Host-link bandwidth measured now: pinned hipMemcpy D2H, H2D, both at once,
  * and the same through the copy kernels; `bytes` per transfer, median of `reps`. */

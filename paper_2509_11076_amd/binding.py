@@ -101,7 +101,8 @@ class ss_stats_t(C.Structure):
                 ("match_levels", C.c_uint64 * 5), ("reuse_hist", C.c_uint32 * 16),
                 ("reuse_sum", C.c_uint64), ("reuse_count", C.c_uint64),
                 ("stall_free_ms", C.c_double), ("stall_wait_in_ms", C.c_double),
-                ("ring_batches", C.c_uint64), ("ring_transfers", C.c_uint64)]
+                ("ring_batches", C.c_uint64), ("ring_transfers", C.c_uint64),
+                ("ring_batches_in", C.c_uint64), ("ring_transfers_in", C.c_uint64)]
 
 
 class ss_bw_t(C.Structure):
@@ -165,7 +166,7 @@ _SIGS = {
     "ss_batch_ms": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
     "ss_batch_window": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
     "ss_bw_probe": [_P, C.c_uint64, C.c_uint32, C.POINTER(ss_bw_t)],
-    "ss_ring_view": [_P, C.POINTER(C.c_uint32), C.POINTER(_P), C.POINTER(_P)],
+    "ss_ring_view": [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(_P), C.POINTER(_P)],
     "ss_get_stats": [_P, C.POINTER(ss_stats_t)],
 }
 for _name, _args in _SIGS.items():
@@ -517,11 +518,11 @@ def ss_batch_window(ctx, direction, batch):
     return a.value, b.value
 
 
-def ss_ring_view(ctx):
-    """(group_of int32[n_out_batches], group_bytes uint64[n_groups]) as copies"""
+def ss_ring_view(ctx, direction=0):
+    """(group_of int32[batches of that direction], group_bytes uint64[n_groups]) as copies"""
     n, g, gb = C.c_uint32(), _P(), _P()
-    _ck(_lib.ss_ring_view(ctx, C.byref(n), C.byref(g), C.byref(gb)), "ss_ring_view")
-    nob = len(ss_schedule_view(ctx)[0]) - 1
+    _ck(_lib.ss_ring_view(ctx, int(direction), C.byref(n), C.byref(g), C.byref(gb)), "ss_ring_view")
+    nob = len(ss_schedule_view(ctx)[1 if direction else 0]) - 1
     group_of = np.frombuffer((C.c_char * (4 * nob)).from_address(g.value), dtype=np.int32).copy() if nob and g.value \
         else np.zeros(0, np.int32)
     group_bytes = np.frombuffer((C.c_char * (8 * n.value)).from_address(gb.value), dtype=np.uint64).copy() \

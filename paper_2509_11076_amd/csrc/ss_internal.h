@@ -61,6 +61,20 @@ struct ss_sched {
   std::vector<uint8_t> out_staged;                  // per batch, this iteration: it went through the ring
   int64_t last_gather_batch = -1;                   // batch gathered most recently (its event is the latest on the swap-out stream)
   int64_t last_flush_batch = -1;                    // batch whose ev_out_done the most recent transfer out of the ring recorded
+  // Staged swap-in (copy_path_in = SS_PATH_STAGED): consecutive swap-in batches whose staging slots together
+  // form one gap-free range come back in one copy-engine transfer into a slot of a second HBM ring, issued
+  // with the group's first batch; each batch is then scattered from the ring into its blocks by the copy kernel
+  // at its own issue point.
+  struct in_group { uint32_t first, last; uint64_t host_lo, bytes; };
+  std::vector<in_group> in_groups;
+  std::vector<uint64_t> in_group_bytes;             // per group, for ss_ring_view
+  std::vector<int32_t> in_group_of;                 // per swap-in batch: its group, -1 = comes back directly
+  std::vector<std::vector<uint32_t>> in_group_outs; // per group: the swap-out batches its tensors left in
+  std::vector<uint8_t> in_group_state;              // per group, this iteration: 0 untouched, 1 fetched, 2 not usable (direct)
+  std::vector<int32_t> in_group_last_scatter;       // per group, this iteration: swap-in batch scattered most recently, -1 = none
+  std::vector<int32_t> in_slot_owner;               // per slot of the swap-in ring: group whose bytes it holds, -1 = none
+  std::vector<hipEvent_t> ev_fetched[2], ev_fetch_start[2];   // per group
+  std::vector<uint8_t> in_group_state_drained;
   int phase = 0;                                    // event set of the iteration being issued
   bool drained_once = false;                        // set `phase ^ 1` holds a completed iteration
   ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
@@ -95,6 +109,7 @@ struct ss_ctx {
   uint32_t n_s_out = 1, n_s_in = 1;
   hipStream_t s_flush = nullptr;    // copy-engine transfers out of the HBM ring
   uint8_t *ring = nullptr;          // HBM ring of the staged swap-out path (cfg.ring_bytes, in slots of cfg.ring_slot_bytes)
+  uint8_t *ring_in = nullptr;       // the same for the staged swap-in path
   uint32_t n_slots = 0;
   std::vector<hipEvent_t> ev_ring;  // compute-stream markers, used round-robin
   size_t ev_next = 0;

@@ -77,13 +77,13 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (cfg_in) cfg = *cfg_in;
     if (cfg.align < 16 || (cfg.align & (cfg.align - 1)) || cfg.guard_bytes % cfg.align ||
         cfg.link_bytes_per_op == 0 || cfg.max_ops == 0 || cfg.max_events == 0 ||
-        cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_STAGED || cfg.copy_path_in > SS_PATH_ENGINE)
+        cfg.max_ops > (1u << 23) || cfg.copy_path > SS_PATH_STAGED || cfg.copy_path_in > SS_PATH_STAGED)
       return SS_E_INVAL;
-    if (cfg.ring_slot_bytes == 0) cfg.ring_slot_bytes = 128ull << 20;
-    if (cfg.ring_bytes == 0) cfg.ring_bytes = 512ull << 20;
+    if (cfg.ring_slot_bytes == 0) cfg.ring_slot_bytes = 256ull << 20;
+    if (cfg.ring_bytes == 0) cfg.ring_bytes = 1024ull << 20;
     if (cfg.gather_workgroups == 0) cfg.gather_workgroups = 256;
     if (cfg.gather_workgroups > 4096) return SS_E_INVAL;
-    if (cfg.copy_path == SS_PATH_STAGED &&
+    if ((cfg.copy_path == SS_PATH_STAGED || cfg.copy_path_in == SS_PATH_STAGED) &&
         ((cfg.ring_slot_bytes & 255u) || cfg.ring_slot_bytes < 4096 || cfg.ring_bytes / cfg.ring_slot_bytes < 2 ||
          cfg.ring_bytes / cfg.ring_slot_bytes > 64))
       return SS_E_INVAL;
@@ -121,8 +121,9 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (rc == SS_OK && (e = hipHostMalloc((void **)&ctx->events, (size_t)cfg.max_events * sizeof(ss_event_t),
                                           hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
     // all streams at the default priority
-    ctx->n_s_out = cfg.copy_path == SS_PATH_STAGED ? 1 : cfg.out_streams;
-    ctx->n_s_in = cfg.in_streams;
+    const bool any_staged = cfg.copy_path == SS_PATH_STAGED || cfg.copy_path_in == SS_PATH_STAGED;
+    ctx->n_s_out = any_staged ? 1 : cfg.out_streams;
+    ctx->n_s_in = any_staged ? 1 : cfg.in_streams;
     for (uint32_t i = 0; i < ctx->n_s_out && rc == SS_OK; ++i)
       if ((e = hipStreamCreateWithFlags(&ctx->s_out[i], hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
     for (uint32_t i = 0; i < ctx->n_s_in && rc == SS_OK; ++i)
@@ -132,11 +133,16 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     // queues (4 per process here) with another - a stream that shares its queue with the stream of the
     // copy-engine transfers stands still for the length of every transfer.
     ctx->s_aux = ctx->s_in[0];
-    if (rc == SS_OK && cfg.copy_path == SS_PATH_STAGED) {
-      ctx->n_s_out = 1;            // gathers and direct batches share one stream; transfers out of the ring have their own
+    if (rc == SS_OK && (cfg.copy_path == SS_PATH_STAGED || cfg.copy_path_in == SS_PATH_STAGED)) {
+      // gathers / scatters and direct batches of a direction share that direction's one stream; the copy-engine
+      // transfers out of and into the rings share a third
       ctx->n_slots = (uint32_t)(cfg.ring_bytes / cfg.ring_slot_bytes);
       if ((e = hipStreamCreateWithFlags(&ctx->s_flush, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
-      if (rc == SS_OK && (e = hipMalloc((void **)&ctx->ring, (size_t)ctx->n_slots * cfg.ring_slot_bytes)) != hipSuccess)
+      if (rc == SS_OK && cfg.copy_path == SS_PATH_STAGED &&
+          (e = hipMalloc((void **)&ctx->ring, (size_t)ctx->n_slots * cfg.ring_slot_bytes)) != hipSuccess)
+        fail(SS_E_NOMEM, e);
+      if (rc == SS_OK && cfg.copy_path_in == SS_PATH_STAGED &&
+          (e = hipMalloc((void **)&ctx->ring_in, (size_t)ctx->n_slots * cfg.ring_slot_bytes)) != hipSuccess)
         fail(SS_E_NOMEM, e);
     }
     for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
@@ -178,6 +184,8 @@ static void sched_release(ss_sched &s) {
     free_events(s.ev_in_start[p]);
     free_events(s.ev_gathered[p]);
     free_events(s.ev_flush_start[p]);
+    free_events(s.ev_fetched[p]);
+    free_events(s.ev_fetch_start[p]);
   }
   free_events(s.ev_free_at);
   free_events(s.ev_wait_at);
@@ -206,6 +214,7 @@ extern "C" int ss_destroy(ss_ctx *ctx) {
   }
   if (ctx->s_flush) (void)hipStreamDestroy(ctx->s_flush);
   if (ctx->ring) (void)hipFree(ctx->ring);
+  if (ctx->ring_in) (void)hipFree(ctx->ring_in);
   if (ctx->staging) (void)hipHostFree(ctx->staging);
   if (ctx->ops) (void)hipHostFree(ctx->ops);
   if (ctx->events) (void)hipHostFree(ctx->events);
@@ -269,6 +278,9 @@ static void ring_reset(ss_sched &s, uint32_t n_slots) {
     s.group_last_flush[g] = -1;
   }
   s.slot_owner.assign(n_slots, -1);
+  s.in_slot_owner.assign(n_slots, -1);
+  std::fill(s.in_group_state.begin(), s.in_group_state.end(), 0);
+  std::fill(s.in_group_last_scatter.begin(), s.in_group_last_scatter.end(), -1);
   std::fill(s.out_staged.begin(), s.out_staged.end(), 0);
   s.last_flush_batch = s.last_gather_batch = -1;
 }
@@ -458,6 +470,51 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
       }
       for (const ss_sched::out_group &g : s.groups) s.group_bytes.push_back(g.bytes);
     }
+    // staged swap-in: consecutive batches whose staging slots together form one gap-free range (slots are
+    // pairwise disjoint, so: the range they span is as long as their sizes add up to) of at most one ring slot
+    s.in_groups.clear();
+    s.in_group_bytes.clear();
+    s.in_group_outs.clear();
+    s.in_group_of.assign(n_in_batches, -1);
+    if (ctx->cfg.copy_path_in == SS_PATH_STAGED && ctx->ring_in && ctx->cfg.guard_bytes == 0) {
+      const uint64_t slot = ctx->cfg.ring_slot_bytes;
+      for (uint32_t f = 0; f < n_in_batches;) {
+        uint64_t lo_off = ~0ull, hi_off = 0, total = 0;
+        int64_t best = -1;
+        uint64_t best_lo = 0, best_total = 0;
+        for (uint32_t e = f; e < n_in_batches; ++e) {
+          bool ok = s.in_start[e + 1] > s.in_start[e];
+          for (uint32_t i = s.in_start[e]; i < s.in_start[e + 1] && ok; ++i) {
+            ok = s.in[i].nbytes != 0 && s.in[i].nbytes % ctx->cfg.align == 0;
+            lo_off = std::min(lo_off, s.in[i].host_off);
+            hi_off = std::max(hi_off, s.in[i].host_off + s.in[i].nbytes);
+            total += s.in[i].nbytes;
+          }
+          if (!ok || total > slot) break;
+          if (hi_off - lo_off == total) { best = e; best_lo = lo_off; best_total = total; }
+        }
+        if (best < 0) { ++f; continue; }
+        const int32_t g = (int32_t)s.in_groups.size();
+        s.in_groups.push_back(ss_sched::in_group{f, (uint32_t)best, best_lo, best_total});
+        s.in_group_bytes.push_back(best_total);
+        std::vector<uint32_t> outs;
+        for (uint32_t b = f; b <= (uint32_t)best; ++b) {
+          s.in_group_of[b] = g;
+          for (uint32_t i = s.in_start[b]; i < s.in_start[b + 1]; ++i) {
+            auto it = s.out_of_tensor.find(s.in[i].tensor_id);
+            if (it != s.out_of_tensor.end()) outs.push_back(s.out_batch_of[it->second]);
+            else outs.push_back(s.in_dep[b]);
+          }
+        }
+        std::sort(outs.begin(), outs.end());
+        outs.erase(std::unique(outs.begin(), outs.end()), outs.end());
+        s.in_group_outs.push_back(std::move(outs));
+        f = (uint32_t)best + 1;
+      }
+    }
+    s.in_group_state.assign(s.in_groups.size(), 0);
+    s.in_group_state_drained.assign(s.in_groups.size(), 0);
+    s.in_group_last_scatter.assign(s.in_groups.size(), -1);
     for (uint32_t b = 0, last = 0, have = 0; b < n_out_batches; ++b) {
       if (s.group_of[b] < 0) { last = b; have = 1; }
       s.prev_direct[b] = have ? (int32_t)last : -1;
@@ -495,6 +552,11 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
         if ((rc = ensure_events(ctx, s.ev_gathered[p], n_out_batches, evflags)) != SS_OK) return rc;
         if ((ctx->cfg.flags & SS_CFG_TIMING) &&
             (rc = ensure_events(ctx, s.ev_flush_start[p], s.groups.size(), evflags)) != SS_OK) return rc;
+      }
+      if (!s.in_groups.empty()) {
+        if ((rc = ensure_events(ctx, s.ev_fetched[p], s.in_groups.size(), evflags)) != SS_OK) return rc;
+        if ((ctx->cfg.flags & SS_CFG_TIMING) &&
+            (rc = ensure_events(ctx, s.ev_fetch_start[p], s.in_groups.size(), evflags)) != SS_OK) return rc;
       }
       if ((rc = ensure_events(ctx, s.ev_in_done[p], n_in_batches, evflags)) != SS_OK) return rc;
       if (ctx->cfg.flags & SS_CFG_TIMING) {
@@ -755,6 +817,64 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
   return SS_OK;
 }
 
+// Swap-in of a batch that comes back through the ring.  With the first batch of its group the whole
+// group's staging range is fetched into a ring slot by one copy-engine transfer (which waits for the bytes
+// to be in the staging area and for the slot's previous readers, not for the compute stream: the blocks
+// need not be free yet); the batch itself is scattered from the ring into its blocks by the copy kernel,
+// after the compute stream has reached this point.  Returns 1 if handled, 0 if the batch must come back
+// directly, or an error code.
+static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
+  ss_sched &s = ctx->sched;
+  const uint32_t g = (uint32_t)s.in_group_of[batch];
+  const ss_sched::in_group &G = s.in_groups[g];
+  const uint32_t slot = g % ctx->n_slots;
+  if (s.in_group_state[g] == 2) return 0;
+  if (s.in_group_state[g] == 0) {
+    bool usable = s.in_slot_owner[slot] <= (int32_t)g;
+    for (uint32_t ob : s.in_group_outs[g]) usable = usable && s.out_issued[ob];   // every byte of the range is on its way
+    if (!usable) {
+      s.in_group_state[g] = 2;
+      return 0;
+    }
+    // what has been gathered leaves the swap-out ring first; those transfers precede this one on the same stream
+    int rc = ring_flush_all(ctx);
+    if (rc != SS_OK) return rc;
+    hipStream_t se = ctx->s_flush;
+    const int32_t pd = s.prev_direct[s.in_group_outs[g].back()];
+    if (pd >= 0 && s.out_issued[(size_t)pd]) SS_HIP(hipStreamWaitEvent(se, s.ev_out_done[s.phase][(size_t)pd], 0));
+    if (s.last_engine_out >= 0) SS_HIP(hipStreamWaitEvent(se, s.ev_out_done[s.phase][(size_t)s.last_engine_out], 0));
+    const int32_t og = s.in_slot_owner[slot];
+    if (og >= 0 && og != (int32_t)g && s.in_group_last_scatter[(size_t)og] >= 0)
+      SS_HIP(hipStreamWaitEvent(se, s.ev_in_done[s.phase][(size_t)s.in_group_last_scatter[(size_t)og]], 0));
+    s.in_slot_owner[slot] = (int32_t)g;
+    if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_fetch_start[s.phase][g], se));
+    SS_HIP(hipMemcpyAsync(ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes, ctx->staging + G.host_lo, G.bytes,
+                          hipMemcpyHostToDevice, se));
+    SS_HIP(hipEventRecord(s.ev_fetched[s.phase][g], se));
+    s.in_group_state[g] = 1;
+    ctx->stats.ring_transfers_in++;
+  } else if (s.in_slot_owner[slot] != (int32_t)g) {
+    return 0;                                   // the slot has been handed on: the staging area still holds the bytes
+  }
+  hipStream_t si = ctx->s_in[0];
+  const uint32_t lo = s.in_start[batch], hi = s.in_start[batch + 1];
+  SS_HIP(hipStreamWaitEvent(si, mark, 0));                                  // destination blocks are free from here on
+  SS_HIP(hipStreamWaitEvent(si, s.ev_fetched[s.phase][g], 0));
+  if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_in_start[s.phase][batch], si));
+  uint8_t *base = (uint8_t *)((uintptr_t)ctx->ring_in + (uintptr_t)slot * ctx->cfg.ring_slot_bytes - (uintptr_t)G.host_lo);
+  const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
+  const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
+  ss_launch_copy(si, ctx->cfg.gather_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, base, s.d_in + lo, c0,
+                 s.d_in_cdesc + s.in_cbase[batch], n_chunks, s.in_shift[batch]);
+  SS_HIP(hipGetLastError());
+  SS_HIP(hipEventRecord(s.ev_in_done[s.phase][batch], si));
+  s.in_issued[batch] = 1;
+  s.in_group_last_scatter[g] = (int32_t)batch;
+  ctx->stats.kernel_batches++;
+  ctx->stats.ring_batches_in++;
+  return 1;
+}
+
 extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
   if (!ctx) return SS_E_INVAL;
   ss_sched &s = ctx->sched;
@@ -768,6 +888,16 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
   // destination blocks are free once the compute stream reaches this point
   hipEvent_t mark = next_marker(ctx);
   SS_HIP(hipEventRecord(mark, ctx->compute));
+  if (hi > lo && s.in_group_of[batch] >= 0) {
+    const int rc = swap_in_staged(ctx, batch, mark);
+    if (rc < 0) return rc;
+    if (rc == 1) {
+      uint64_t moved = 0;
+      for (uint32_t i = lo; i < hi; ++i) moved += s.in[i].nbytes;
+      ctx->stats.bytes_in += moved;
+      return SS_OK;
+    }
+  }
   SS_HIP(hipStreamWaitEvent(si, mark, 0));
   // staging slots must be completely written: the batch's tensors left in swap-out batches up to in_dep;
   // with the swap-out batches spread over n streams, the last n of them up to in_dep cover every stream
@@ -886,6 +1016,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
         s.done_ev_of_drained = s.done_ev_of;
         s.out_staged_drained = s.out_staged;
         s.group_last_flush_drained = s.group_last_flush;
+        s.in_group_state_drained = s.in_group_state;
         ring_reset(s, ctx->n_slots);
       }
       return SS_OK;
@@ -929,6 +1060,12 @@ static int timing_events(ss_ctx *ctx, uint32_t dir, uint32_t u, hipEvent_t *st, 
     if (u + 1 >= s.in_start.size()) return SS_E_INVAL;
     *st = s.ev_in_start[set][u];
     *dn = s.ev_in_done[set][u];
+  } else if (dir == 3) {
+    if (u >= s.in_groups.size()) return SS_E_INVAL;
+    const std::vector<uint8_t> &st_ = s.drained_once ? s.in_group_state_drained : s.in_group_state;
+    if (st_[u] != 1) return SS_E_STATE;                        // the group did not come back through the ring
+    *st = s.ev_fetch_start[set][u];
+    *dn = s.ev_fetched[set][u];
   } else {
     if (u >= s.groups.size()) return SS_E_INVAL;
     const std::vector<int32_t> &lf = s.drained_once ? s.group_last_flush_drained : s.group_last_flush;
@@ -940,11 +1077,11 @@ static int timing_events(ss_ctx *ctx, uint32_t dir, uint32_t u, hipEvent_t *st, 
 }
 
 static size_t timing_units(const ss_sched &s, uint32_t dir) {
-  return dir == 0 ? s.out_start.size() - 1 : dir == 1 ? s.in_start.size() - 1 : s.groups.size();
+  return dir == 0 ? s.out_start.size() - 1 : dir == 1 ? s.in_start.size() - 1 : dir == 2 ? s.groups.size() : s.in_groups.size();
 }
 
 extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms) {
-  if (!ctx || dir > 2) return SS_E_INVAL;
+  if (!ctx || dir > 3) return SS_E_INVAL;
   if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
   ss_sched &s = ctx->sched;
   const size_t nb = timing_units(s, dir);
@@ -994,7 +1131,7 @@ extern "C" int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *don
 }
 
 extern "C" int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *start_ms, float *end_ms) {
-  if (!ctx || dir > 2 || !start_ms || !end_ms) return SS_E_INVAL;
+  if (!ctx || dir > 3 || !start_ms || !end_ms) return SS_E_INVAL;
   if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
   ss_sched &s = ctx->sched;
   if (s.out_start.size() < 2) return SS_E_INVAL;
@@ -1007,13 +1144,14 @@ extern "C" int ss_batch_window(ss_ctx *ctx, uint32_t dir, uint32_t batch, float 
   return SS_OK;
 }
 
-extern "C" int ss_ring_view(ss_ctx *ctx, uint32_t *n_groups, const int32_t **group_of, const uint64_t **group_bytes) {
-  if (!ctx) return SS_E_INVAL;
+extern "C" int ss_ring_view(ss_ctx *ctx, uint32_t dir, uint32_t *n_groups, const int32_t **group_of,
+                            const uint64_t **group_bytes) {
+  if (!ctx || dir > 1) return SS_E_INVAL;
   if (!ctx->sched.loaded) return SS_E_STATE;
   const ss_sched &s = ctx->sched;
-  if (n_groups) *n_groups = (uint32_t)s.groups.size();
-  if (group_of) *group_of = s.group_of.data();
-  if (group_bytes) *group_bytes = s.group_bytes.data();
+  if (n_groups) *n_groups = (uint32_t)(dir ? s.in_groups.size() : s.groups.size());
+  if (group_of) *group_of = dir ? s.in_group_of.data() : s.group_of.data();
+  if (group_bytes) *group_bytes = dir ? s.in_group_bytes.data() : s.group_bytes.data();
   return SS_OK;
 }
 

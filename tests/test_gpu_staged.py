@@ -41,7 +41,8 @@ def random_arena(torch, nbytes, seed):
 
 @pytest.mark.parametrize("bpo", [64 * 1024, INSTANT])
 @pytest.mark.parametrize("slot_kib,slots", [(512, 2), (1024, 3), (4096, 2)])
-def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots):
+@pytest.mark.parametrize("staged_in", [False, True])
+def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in):
     """configuration 1 with ring slots smaller than, about, and larger than a layer's swap set: staging
     image and arena (with poison over released blocks) equal the oracle's, byte for byte"""
     from paper_2509_11076_amd.executor import run_iteration
@@ -55,6 +56,7 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots):
     arena = random_arena(torch, arena_bytes, 2509)
     host_arena = arena.cpu().numpy().copy()
     ctx = make_ctx(P, staging_bytes=ora["staging_bytes"], link_bytes_per_op=bpo, copy_path=P.SS_PATH_STAGED,
+                   copy_path_in=P.SS_PATH_STAGED if staged_in else P.SS_PATH_AUTO,
                    ring_slot_bytes=slot_kib << 10, ring_bytes=slots * (slot_kib << 10),
                    flags=P.SS_CFG_POISON_FREE | P.SS_CFG_TIMING)
     try:
@@ -75,7 +77,17 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots):
             for g in range(len(group_bytes)):
                 assert P.ss_batch_ms(ctx, 2, g)[0] > 0
             assert P.ss_batch_ms(ctx, 2)[1] > 0 and P.ss_batch_ms(ctx, 0, 0)[0] > 0
+            in_group_of, in_group_bytes = P.ss_ring_view(ctx, 1)
+            if staged_in:
+                assert (in_group_of >= 0).all() and int(in_group_bytes.sum()) == int(group_bytes.sum())
+                assert int(in_group_bytes.max()) <= slot_kib << 10
+                for g in range(len(in_group_bytes)):
+                    assert P.ss_batch_ms(ctx, 3, g)[0] > 0
+            else:
+                assert len(in_group_bytes) == 0 and (in_group_of == -1).all()
         st = P.ss_get_stats(ctx)
+        assert (st["ring_batches_in"] == 2 * lib["n_in_batches"]) == staged_in
+        assert (st["ring_transfers_in"] == 2 * len(in_group_bytes)) and (st["ring_transfers_in"] > 0) == staged_in
         assert st["ring_batches"] == 2 * lib["n_out_batches"] and st["ring_transfers"] >= 2 * len(group_bytes)
         assert st["bytes_out"] == st["bytes_in"] == 2 * sum(d[2] for d in ora["descs_out"])
     finally:
@@ -105,36 +117,64 @@ def test_ring_takes_only_gap_free_batches_and_the_rest_leaves_directly(P, torch)
     arena = random_arena(torch, arena_bytes, 9)
     host = arena.cpu().numpy().copy()
     start = np.array(starts, dtype=np.uint32)
-    ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_STAGED, ring_slot_bytes=1024 * KiB, ring_bytes=2048 * KiB,
-                   flags=P.SS_CFG_TIMING)
-    try:
-        P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
-        dep = np.arange(9, dtype=np.uint32)                    # swap-in batch b needs swap-out batch b only
-        P.ss_load_schedule(ctx, d, start, d, start, dep)
-        group_of, group_bytes = P.ss_ring_view(ctx)
-        assert group_of.tolist() == [0, 0, 0, -1, 1, 2, -1, 3, 3]
-        assert group_bytes.tolist() == [1024 * KiB, 512 * KiB, 768 * KiB, 256 * KiB]
-        for order in ([0, 1, 2, 3, 4, 5, 6, 7, 8], [1, 0, 2, 4, 3, 6, 5, 8, 7], [8, 7, 6, 5, 4, 3, 2, 1, 0]):
-            P.ss_staging_fill(ctx, 0x11)
-            for k, b in enumerate(order):
-                P.ss_swap_out(ctx, b)
-                if k == 1:                                         # release right after the gather
-                    lo = starts[order[0]]
-                    P.ss_sync(ctx, P.SS_SYNC_FREE, lo)
-                if k == 4:                                         # a swap-in while groups are still open
-                    P.ss_swap_in(ctx, order[0])
-            for b in range(9):
-                if b != order[0]:
+    dep = np.arange(9, dtype=np.uint32)                        # swap-in batch b needs swap-out batch b only
+    rows = [tuple(int(x) for x in r) for r in d.tolist()]
+    for path_in in (P.SS_PATH_AUTO, P.SS_PATH_STAGED):
+        ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_STAGED, copy_path_in=path_in,
+                       ring_slot_bytes=1024 * KiB, ring_bytes=2048 * KiB, flags=P.SS_CFG_TIMING)
+        try:
+            P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+            P.ss_load_schedule(ctx, d, start, d, start, dep)
+            group_of, group_bytes = P.ss_ring_view(ctx)
+            assert group_of.tolist() == [0, 0, 0, -1, 1, 2, -1, 3, 3]
+            assert group_bytes.tolist() == [1024 * KiB, 512 * KiB, 768 * KiB, 256 * KiB]
+            in_group_of, in_group_bytes = P.ss_ring_view(ctx, 1)
+            if path_in == P.SS_PATH_STAGED:      # same slots, same rule: the same groups on the way back
+                assert in_group_of.tolist() == group_of.tolist() and in_group_bytes.tolist() == group_bytes.tolist()
+            else:
+                assert (in_group_of == -1).all()
+            for order in ([0, 1, 2, 3, 4, 5, 6, 7, 8], [1, 0, 2, 4, 3, 6, 5, 8, 7], [8, 7, 6, 5, 4, 3, 2, 1, 0]):
+                arena.copy_(torch.from_numpy(host).cuda())
+                P.ss_staging_fill(ctx, 0x11)
+                for k, b in enumerate(order):
+                    P.ss_swap_out(ctx, b)
+                    if k == 1:                                     # release right after the gather
+                        P.ss_sync(ctx, P.SS_SYNC_FREE, starts[order[0]])
+                for t in range(n):
+                    P.ss_sync(ctx, P.SS_SYNC_FREE, t)
+                arena.fill_(0x3C)                                  # compute stream: every released block is overwritten
+                for b in reversed(order):
                     P.ss_swap_in(ctx, b)
-            assert P.ss_batch_done(ctx, 0, 3) in (True, False)
+                for t in range(n):
+                    P.ss_sync(ctx, P.SS_SYNC_WAIT_IN, t)
+                assert P.ss_batch_done(ctx, 0, 3) in (True, False)
+                P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+                torch.cuda.synchronize()
+                staging = np.full(h, 0x11, dtype=np.uint8)
+                oracle.swap_out(host, staging, rows)
+                assert np.array_equal(P.ss_host_peek(ctx, 0, h), staging), order
+                want = np.full(arena_bytes, 0x3C, dtype=np.uint8)
+                oracle.swap_in(want, staging, rows)
+                assert np.array_equal(arena.cpu().numpy(), want), order
+            # a swap-in while the groups of the way out are still open: their gathered part leaves at once
+            arena.copy_(torch.from_numpy(host).cuda())
+            P.ss_staging_fill(ctx, 0x11)
+            for k, b in enumerate([0, 1, 4, 7]):
+                P.ss_swap_out(ctx, b)
+            P.ss_swap_in(ctx, 1)
+            P.ss_swap_in(ctx, 7)
+            for b in (2, 3, 5, 6, 8):
+                P.ss_swap_out(ctx, b)
+            for b in (0, 2, 3, 4, 5, 6, 8):
+                P.ss_swap_in(ctx, b)
             P.ss_sync(ctx, P.SS_SYNC_DRAIN)
             torch.cuda.synchronize()
             staging = np.full(h, 0x11, dtype=np.uint8)
-            oracle.swap_out(host, staging, [tuple(int(x) for x in r) for r in d.tolist()])
-            assert np.array_equal(P.ss_host_peek(ctx, 0, h), staging), order
+            oracle.swap_out(host, staging, rows)
+            assert np.array_equal(P.ss_host_peek(ctx, 0, h), staging)
             assert np.array_equal(arena.cpu().numpy(), host)
-    finally:
-        P.ss_destroy(ctx)
+        finally:
+            P.ss_destroy(ctx)
     # guards switch the ring off altogether
     ctx = make_ctx(P, staging_bytes=2 * h + 4096, copy_path=P.SS_PATH_STAGED, guard_bytes=256)
     try:
@@ -147,7 +187,8 @@ def test_ring_takes_only_gap_free_batches_and_the_rest_leaves_directly(P, torch)
         P.ss_destroy(ctx)
 
 
-def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch):
+@pytest.mark.parametrize("path_in", [0, 3])
+def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch, path_in):
     """configuration 2, three iterations, every swap-out through the ring (all its sizes are multiples of
     the alignment), blocks poisoned at their release: compute results equal the run without swapping"""
     B = P
@@ -155,7 +196,7 @@ def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch):
     res = []
     for swap in (False, True):
         r = SwapRun(B, torch, 2, swap=swap, bpo=11 << 20, bpo_in=4760000, copy_path=B.SS_PATH_STAGED,
-                    copy_path_in=B.SS_PATH_AUTO, flags=(B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE) if swap else 0)
+                    copy_path_in=path_in, flags=(B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE) if swap else 0)
         try:
             for _ in range(3):
                 r.step() if swap else r.step_noswap()
@@ -167,3 +208,4 @@ def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch):
     assert np.array_equal(c0, c1) and np.array_equal(g0, g1)
     assert st["bytes_out"] == st["bytes_in"] == 3 * moved and st["ring_batches"] == 3 * 120
     assert 0 < st["ring_transfers"] < st["ring_batches"]
+    assert (st["ring_batches_in"] > 0) == (path_in == 3) and st["ring_transfers_in"] <= st["ring_batches_in"]
