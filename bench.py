@@ -1,21 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the swap-executor hot path on one MI355X.
 
-A step is one training iteration of the synthetic 1.3B-shape decoder
-(configuration 2: hidden 2048, 24 layers, seq 2048, micro-batch 1, bf16; the
-activations of every other layer, about 3 GB, are swapped out after their last
-forward use and back before their first backward use) with the whole hot path
-in it: trace record per operator, sequence match, policy application, timeline
-scan, swap-out / release / swap-in / wait around the operators, drain.
-Activations are resident in HBM when the timed region starts.
+A step is one training iteration of a synthetic decoder with the whole hot path in it: trace
+record per operator, sequence match, policy application, timeline scan, swap-out / release /
+swap-in / wait around the operators, drain.  Activations are resident in HBM when the timed
+region starts.
 
-Prints ONE JSON line: swap GB/s (D2H + H2D bytes over step wall time), the
-host-link peak measured in the same run with pinned hipMemcpy, the step-time
-overhead against the same step without swapping, the roofline of the copy
-kernel (host link, and HBM for reference), and the CPU oracle timed on this
-box's host cores.
+Without --config the headline workload is configuration 3 (7B-shape decoder, 97 GiB of activations
+under a 48 GB budget, 56.5 GB swapped each way per step): --steps steps are timed after --warmup
+warm-up steps, and the other configurations (1, 2, 5 executed, 4 planned at full size), a generated
+policy under a memory limit, the stage loop of Algo. 1 and the profiler-hook overhead table are
+measured with small fixed step counts and attached as `sub_records`.  With --config N only that
+configuration is measured.
+
+Prints ONE JSON line.  `value` is D2H + H2D bytes over the step's wall time; the fractions of the
+host-link peak are given per direction against that direction's peak, measured in the same run
+with pinned hipMemcpy (`pct_of_link_peak`).  `roofline` names the mover of the dominant direction
+(copy kernel or copy engine) with its GB/s from HIP events, `cpu_baseline` is the CPU oracle timed
+on this machine's host cores.
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -25,49 +30,752 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# Memory traffic of one pack launch over its algorithmic bytes (read from HBM + written to the
-# host), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy of known size
-# (profiles/ss_copy_kernel_config2_hbm_traffic.md).
+# Memory traffic of one pack launch over its algorithmic bytes (read from HBM + written to the host),
+# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy of known size
+# (profiles/ss_copy_kernel_config2_hbm_traffic.md); a constant carried over from that profile, not a
+# counter of this run.
 PACK_TRAFFIC_RATIO = 1.011
+PACK_TRAFFIC_SOURCE = "profiles/ss_copy_kernel_config2_hbm_traffic.md"
+
+METRIC = "swap GB/s (D2H+H2D) as % of host-link peak; step-time overhead vs no-swap"
+WORKLOADS = {
+    1: "config 1: toy 2-layer block, layer-0 activations swapped",
+    2: "config 2: 1.3B-shape decoder (hidden 2048, 24 layers, seq 2048, mb 1, bf16), "
+       "activations of every other layer swapped, synthetic bf16 GEMMs on the compute stream",
+    3: "config 3: 7B-shape decoder (hidden 4096, 32 layers, seq 4096, mb 1, bf16), 97 GiB of activations "
+       "under a 48 GB budget, longest-idle-first policy, synthetic bf16 GEMMs on the compute stream",
+    5: "config 5: 20,000 tensors of 4 KiB..4 MiB at random places of a 64 GB arena, two random orders, "
+       "no compute stream work"}
 
 
-def cpu_baseline(cfgno, bpo):
-    """The oracle as it stands, one full step of the same workload on the host (1 thread)."""
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+# ---- CPU oracle legs ---------------------------------------------------------------------------------
+
+def _threaded_round_trip(oracle, arena, staging, ap, threads):
+    """the oracle's per-descriptor byte copies (swap_out of every descriptor, then swap_in of every
+    descriptor) with the descriptor lists dealt round-robin to `threads` threads; returns seconds"""
+    from concurrent.futures import ThreadPoolExecutor
+    outs = [ap["descs_out"][i::threads] for i in range(threads)]
+    ins = [ap["descs_in"][i::threads] for i in range(threads)]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        t0 = time.perf_counter()
+        list(ex.map(lambda d: oracle.swap_out(arena, staging, d), outs))
+        list(ex.map(lambda d: oracle.swap_in(arena, staging, d), ins))
+        return time.perf_counter() - t0
+
+
+def cpu_baseline(cfgno, bpo, budget_s=6.0):
+    """The oracle as it stands on the host cores, one step of the same workload: trace record, match,
+    apply, scan on one thread; the byte round trip on one thread (in schedule order) and once more with
+    min(16, cores) threads.  Configurations 1, 2, 5 in full; 3 and 4 on a 1/8 layer subset (4 of 32
+    layers, budget 6 GB), which moves 1/8 of the bytes at the same tensor sizes."""
     import numpy as np
     import oracle
     import workloads as W
+    from workloads import transformer as T
     from workloads.arena import place_tensors
-    record_oracle, ops_tuples, oracle_execute = oracle.record_trace, oracle.ops_tuples, oracle.execute_schedule
-    tr = W.build_trace(W.config_shape(cfgno))
-    pol = W.config_swap_set(tr, cfgno)
-    idx = pol["ref_op"].astype(np.int64)
-    ap0 = oracle.apply_policy(pol, idx, tr.tensors, bpo)
-    swapped = {r[2]: (r[5], r[6]) for r in ap0["resolved"] if not r[3] & 3}
-    arena_bytes = place_tensors(tr.tensors, swapped=swapped)
-    arena = np.zeros(arena_bytes, dtype=np.uint8)
-    arena[::4096] = 1                                   # touch the pages before timing
-    staging = np.zeros(ap0["staging_bytes"], dtype=np.uint8)
-    staging[::4096] = 1
-    reps, t_trace, t_bytes = 0, 0.0, 0.0
-    while reps < 10 and t_trace + t_bytes < 10.0:           # bounded: at most ten steps or ten seconds
+    cores = len(os.sched_getaffinity(0))
+    threads = max(1, min(16, cores))
+    subset = ""
+    if cfgno == 5:
+        tr, pol, arena_bytes = W.build_small_tensor_stress()
+        tr_cur = tr
+    elif cfgno in (3, 4):
+        shape = dataclasses.replace(T.config_shape(cfgno), layers=4)
+        subset = " on a 1/8 layer subset (4 of 32 layers, budget 6 GB; bytes per step are 1/8 of the full configuration's)"
+        tr = T.build_trace(shape)
+        rows, _ = oracle.greedy_policy(tr.tensors, tr.events, tr.n_ops, 0, 6 * 10**9, bpo, min_bytes=1 << 20)
+        pol = np.zeros(len(rows), dtype=W.POLICY_DT)
+        for i, r in enumerate(rows):
+            pol[i] = r
+        tr_cur = tr if cfgno == 3 else T.build_trace(shape, iteration=1, perturb=dict(p_drop=0.1, p_insert=0.1,
+                                                                                     moe_max=8, seq_jitter=0.15))
+        arena_bytes = None
+    else:
+        tr = T.build_trace(T.config_shape(cfgno))
+        pol = T.config_swap_set(tr, cfgno)
+        tr_cur, arena_bytes = tr, None
+    anchors = [(int(p["ref_op"]), int(p["out_slot"])) for p in pol]
+    ref_ops, _ = oracle.record_trace(oracle.TraceRecorder(), tr)
+    ref_t = oracle.ops_tuples(ref_ops)
+
+    def trace_work():
+        rec = oracle.TraceRecorder()
+        if tr_cur is not tr:
+            oracle.record_trace(rec, tr)            # same interning order as the reference iteration
+        t = [time.perf_counter()]
+        ops, ev = oracle.record_trace(rec, tr_cur)                                     # a1
+        t.append(time.perf_counter())
+        m = oracle.match_sequence(ref_t, oracle.ops_tuples(ops), anchors)              # a3
+        t.append(time.perf_counter())
+        ap = oracle.apply_policy(pol, m["new_idx"], tr_cur.tensors, bpo)               # a4
+        t.append(time.perf_counter())
+        oracle.timeline_scan(ev, ap["policy_events"], tr_cur.n_ops, 0, 1 << 62)        # a2
+        t.append(time.perf_counter())
+        return ap, [t[i + 1] - t[i] for i in range(4)], len(ev)
+    ap, dt, n_ev = trace_work()
+    swapped = {r[2]: (r[5], r[6]) for r in ap["resolved"] if not r[3] & 3}
+    if arena_bytes is None:
+        arena_bytes = place_tensors(tr_cur.tensors, swapped=swapped)
+        ap, dt, n_ev = trace_work()                  # descriptors with the placed offsets
+    arena = np.zeros(arena_bytes, dtype=np.uint8)        # pages are committed when first written
+    staging = np.zeros(max(1, ap["staging_bytes"]), dtype=np.uint8)
+    oracle.execute_schedule(arena, staging, ap)          # warm-up: commits the pages that are touched
+    reps, legs, t_bytes = 0, [0.0] * 4, 0.0
+    while reps < 10 and (reps == 0 or sum(legs) + t_bytes < budget_s):  # bounded: at most ten steps or budget_s seconds
+        if reps:
+            ap, dt, n_ev = trace_work()
         reps += 1
-        t0 = time.perf_counter()
-        ops, ev = record_oracle(oracle.TraceRecorder(), tr)                         # a1
-        anchors = [(int(p["ref_op"]), int(p["out_slot"])) for p in pol]
-        m = oracle.match_sequence(ops_tuples(ops), ops_tuples(ops), anchors)        # a3
-        ap = oracle.apply_policy(pol, m["new_idx"], tr.tensors, bpo)                # a4
-        oracle.timeline_scan(ev, ap["policy_events"], tr.n_ops, 0, 1 << 62)         # a2
         t1 = time.perf_counter()
-        oracle_execute(arena, staging, ap)                                          # a5-a7 (bytes)
-        t2 = time.perf_counter()
-        t_trace += t1 - t0
-        t_bytes += t2 - t1
-    t_trace, t_bytes = t_trace / reps, t_bytes / reps
+        oracle.execute_schedule(arena, staging, ap)                                    # a5-a7 (bytes)
+        t_bytes += time.perf_counter() - t1
+        legs = [a + b for a, b in zip(legs, dt)]
+    legs = [x / reps for x in legs]
+    t_bytes /= reps
+    t_trace = sum(legs)
     moved = 2 * sum(d[2] for d in ap["descs_out"])
+    t_thr = _threaded_round_trip(oracle, arena, staging, ap, threads) if moved else 0.0
+    n_ops = tr_cur.n_ops
     return {"value": round(moved / (t_trace + t_bytes) / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "%d full steps of the same workload (%.2f GB each way per step), mean per step: "
-                      "trace+match+apply+scan %.3f s, byte round trip %.3f s (%.2f GB/s alone); host has %d cores available"
-                      % (reps, moved / 2e9, t_trace, t_bytes, moved / t_bytes / 1e9, len(os.sched_getaffinity(0)))}
+            "sample": "%d step(s) of configuration %d%s, %.3f GB each way per step; mean per step on one thread: "
+                      "record+match+apply+scan %.4f s, byte round trip %.4f s; host has %d cores available"
+                      % (reps, cfgno, subset, moved / 2e9, t_trace, t_bytes, cores),
+            "byte_round_trip_gbps_1_thread": round(moved / t_bytes / 1e9, 3) if t_bytes > 0 else None,
+            "byte_round_trip_gbps_threads": round(moved / t_thr / 1e9, 3) if t_thr > 0 else None,
+            "threads": threads,
+            "trace_work_us_1_thread": {"record": round(legs[0] * 1e6, 1), "match": round(legs[1] * 1e6, 1),
+                                       "apply": round(legs[2] * 1e6, 1), "scan": round(legs[3] * 1e6, 1)},
+            "record_ops_per_s": round(n_ops / legs[0]) if legs[0] > 0 else None,
+            "scan_events_per_s": round((n_ev + len(ap["policy_events"])) / legs[3]) if legs[3] > 0 else None,
+            "operators": n_ops, "events": n_ev, "anchors": len(anchors)}
+
+
+def cpu_baseline_safe(cfgno, bpo, budget_s=6.0):
+    try:
+        return cpu_baseline(cfgno, bpo, budget_s)
+    except Exception as e:                              # the GPU figures stand on their own
+        return {"value": None, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                "sample": "failed: %s: %s" % (type(e).__name__, e)}
+
+
+# ---- modes that print a line of their own -------------------------------------------------------------
+
+def run_swap_only(B, torch, args, path, path_in):
+    from workloads.harness import SwapRun
+    run = SwapRun(B, torch, args.config or 2, swap=True, bpo=args.bpo if args.bpo > 0 else 10 << 20,
+                  bpo_in=4 << 20, copy_path=path, copy_path_in=path_in, copy_workgroups=args.workgroups,
+                  flags=B.SS_CFG_TIMING | B.SS_CFG_KEEP_LATE, compute=False)
+    for _ in range(args.warmup + args.steps):
+        run.step()
+        log("swap-only step done")
+    torch.cuda.synchronize()
+    out_ms = [x for x in B.ss_batch_ms_all(run.ctx, 0).tolist() if x >= 0]
+    nob = run.last["applied"]["n_out_batches"]
+    line = {"mode": "swap-only", "bytes_each_way": run.bytes_each_way, "out_batches": int(nob),
+            "in_batches": int(run.last["applied"]["n_in_batches"]),
+            "avg_pack_launch_ms": round(sum(out_ms) / len(out_ms), 4),
+            "bytes_per_pack_launch": run.bytes_each_way // nob}
+    run.close()
+    return line
+
+
+def record_config4(B, torch, np, iterations=20, cpu=True):
+    """varying sequences at full 7B size: what is measured is the per-iteration trace work (record is part
+    of the step itself; here: match or align, apply, scan, top-up) and where the anchors land; bytes are
+    not moved here (the larger iterations need more pinned staging than a host may give; execution at 7B
+    tensor sizes is covered by the GPU tests)"""
+    from workloads.harness import VaryingRun
+    from workloads import transformer as T
+    shape = T.config_shape(4)
+    pert = dict(p_drop=0.1, p_insert=0.1, moe_max=8, seq_jitter=0.15)
+    out, summary = {}, {}
+    for name, mf in (("keyed_ordinals", 0), ("aligned", B.SS_MATCH_ALIGN)):
+        run = VaryingRun(B, torch, shape, 48 * 10**9, 256 << 20, min_bytes=1 << 20, perturb=pert, compute=False,
+                         match_flags=mf)
+        tr0 = T.build_trace(shape)
+        rows = []
+        for it in range(iterations):
+            p = run.plan(it)
+            tr = p["trace"]
+            truth = {b: j for j, b in enumerate(tr.op_base) if b is not None}
+            want = np.array([truth.get(tr0.op_base[i], -1) for i in run.anchors["ref_op"].tolist()])
+            got = p["match"]["new_idx"]
+            rows.append(dict(it=it, ops=tr.n_ops, seq=tr.seq, similar=bool(p["match"]["similar"]),
+                             stage=int(p["match"]["stage"]), anchors=len(got),
+                             landed_on_true_operator=int((got == want).sum()),
+                             landed_elsewhere=int(((got != want) & (got >= 0)).sum()),
+                             unmatched=int((got < 0).sum()), carried=len(p["carried"]), topped_up=int(p["topped"]),
+                             peak_gb=round(p["scan"]["peak"] / 1e9, 2),
+                             host_ms={k: round(v, 3) for k, v in p["host_ms"].items()}))
+        run.close()
+        out[name] = rows
+        later = rows[1:]
+        n_anchor = sum(r["anchors"] for r in later)
+        summary[name] = {
+            "anchors_on_true_operator_or_correctly_gone_pct": round(
+                100 * sum(r["landed_on_true_operator"] for r in later) / max(1, n_anchor), 1),
+            "anchors_elsewhere_pct": round(100 * sum(r["landed_elsewhere"] for r in later) / max(1, n_anchor), 1),
+            "items_topped_up": sum(r["topped_up"] for r in later),
+            "max_peak_gb": max(r["peak_gb"] for r in later),
+            "host_ms_per_iteration": {k: round(sum(r["host_ms"][k] for r in later) / len(later), 3)
+                                      for k in later[0]["host_ms"]}}
+        log("config 4 planning, %s: %s" % (name, summary[name]))
+    work = [sum(r["host_ms"].values()) for r in out["aligned"][1:]]
+    rec = {"metric": "trace work per iteration (match or align, apply, scan, top-up), host wall ms",
+           "value": round(sum(work) / len(work), 3), "unit": "ms", "n_gpus": 1, "steps": iterations - 1, "warmup": 1,
+           "ms_per_step": round(sum(work) / len(work), 3), "higher_is_better": False, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+           "config": {"workload": "config 4: 7B-shape decoder, operator sequence perturbed every iteration (drop / "
+                                  "insert 0.1, 0-8 branch operators per layer, sequence length +-15 %), policy of "
+                                  "iteration 0 re-anchored online under a 48 GB budget; planning only"},
+           "summary": summary, "iterations": out}
+    if cpu:
+        rec["cpu_baseline"] = cpu_baseline_safe(4, 256 << 20)
+    return rec
+
+
+def record_staged(B, torch, bw, cfgno, limit_frac, steps):
+    from workloads.harness import StagedRun
+    from workloads import transformer as T
+    shape = T.config_shape(cfgno)
+    tr0 = T.build_trace(shape)
+    link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
+    run = StagedRun(B, torch, lambda it: tr0, limit_frac=limit_frac, link_bytes_per_s=link,
+                    g_fwd=shape.layers, g_bwd=shape.layers, min_bytes=1 << 16, flags=B.SS_CFG_TIMING)
+    lg = []
+    for it in range(9 + steps):
+        e = run.iteration(it)
+        e.pop("result")
+        lg.append(e)
+        log("iteration %d stage %d: %.1f ms, %d tensors, %.0f MB each way" %
+            (it, e["stage"], e["ms"], e["n_items"], e["bytes"] / 1e6))
+    run.close()
+    stable = [e for e in lg if e["stage"] == 2]
+    warm = [e for e in lg if e["stage"] == 0][1:]
+    t_stable = sum(e["ms"] for e in stable) / len(stable) * 1e-3
+    t_warm = sum(e["ms"] for e in warm) / len(warm) * 1e-3
+    return {
+        "metric": METRIC, "value": round(2 * stable[0]["bytes"] / t_stable / 1e9, 3), "unit": "GB/s", "n_gpus": 1,
+        "steps": len(stable), "warmup": 9, "ms_per_step": round(t_stable * 1e3, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "config %d trace under the stage loop of Algo. 1 (m = 2, n = 5): WarmUp without "
+                               "swapping, GenPolicy with one generated policy per iteration, Stable with the "
+                               "fastest; memory limit %.2f x the no-swap peak" % (cfgno, limit_frac),
+                   "policy_mode": "staged", "chosen_candidate": stable[0]["candidate"],
+                   "bytes_each_way": stable[0]["bytes"], "tensors_swapped": stable[0]["n_items"],
+                   "peak_bytes_with_policy": stable[0]["peak"]},
+        "step_time": {"warmup_noswap_ms": round(t_warm * 1e3, 3), "stable_ms": round(t_stable * 1e3, 3),
+                      "overhead_vs_noswap_pct": round(100 * (t_stable / t_warm - 1), 1)},
+        "iterations": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in e.items()} for e in lg],
+        "link_peak_measured": {k: round(v, 2) for k, v in bw.items()}}
+
+
+def record_path_table(B, torch, np, bw):
+    from workloads.layouts import DESC_DT
+    from workloads.rng import SplitMix64
+    arena_bytes = 8 << 30
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+    rows = []
+    for size in (4 << 10, 64 << 10, 1 << 20, 16 << 20, 256 << 20):
+        n = max(4, min(20000, (1 << 30) // size))
+        rng = SplitMix64(size, 3)
+        slots = arena_bytes // size
+        picks = sorted(set(rng.randint(slots) for _ in range(2 * n)))[:n]       # scattered, disjoint
+        rng2 = SplitMix64(size, 4)
+        order = sorted(range(len(picks)), key=lambda i: rng2.randint(1 << 30))  # shuffled issue order
+        d = np.zeros(len(picks), dtype=DESC_DT)
+        for k, i in enumerate(order):
+            d[k] = (picks[i] * size, k * size, size, k, 0)
+        start = np.array([0, len(d)], dtype=np.uint32)
+        row = {"tensor_bytes": size, "tensors": len(d), "batch_bytes": int(size * len(d))}
+        for pname, pcode in (("kernel", B.SS_PATH_KERNEL), ("engine", B.SS_PATH_ENGINE)):
+            cfg = B.ss_config_default()
+            cfg.staging_bytes = int(size * len(d))
+            cfg.copy_path = cfg.copy_path_in = pcode
+            cfg.flags = B.SS_CFG_TIMING
+            ctx = B.ss_create(cfg)
+            B.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+            B.ss_load_schedule(ctx, d, start, d, start)
+            out_ms, in_ms = [], []
+            for rep in range(4):
+                B.ss_swap_out(ctx, 0)
+                B.ss_swap_in(ctx, 0)
+                B.ss_sync(ctx, B.SS_SYNC_DRAIN)
+                if rep:
+                    out_ms.append(B.ss_batch_ms(ctx, 0, 0)[0])
+                    in_ms.append(B.ss_batch_ms(ctx, 1, 0)[0])
+            B.ss_destroy(ctx)
+            row[pname + "_d2h_gbps"] = round(row["batch_bytes"] / (min(out_ms) * 1e-3) / 1e9, 2)
+            row[pname + "_h2d_gbps"] = round(row["batch_bytes"] / (min(in_ms) * 1e-3) / 1e9, 2)
+        rows.append(row)
+        log(row)
+    return {"mode": "path-table", "link_peak_measured": {k: round(v, 2) for k, v in bw.items()}, "rows": rows}
+
+
+def record_reuse_interval(B, torch, np, bw, cfgno, path, path_in):
+    from paper_2509_11076_amd.executor import run_iteration_dispatch
+    from workloads.harness import SwapRun
+    link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
+    base = SwapRun(B, torch, cfgno, swap=False)
+    for _ in range(3):
+        base.step_noswap()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        base.step_noswap()
+    torch.cuda.synchronize()
+    t_ns = (time.perf_counter() - t0) / 5
+    n_ops = base.tr.n_ops
+    base.close()
+    del base
+    torch.cuda.empty_cache()
+    run = SwapRun(B, torch, cfgno, swap=True, bpo=max(1, int(link * 2 * t_ns / n_ops)),
+                  bpo_in=max(1, int(link * t_ns / n_ops)), copy_path=path, copy_path_in=path_in,
+                  flags=B.SS_CFG_TIMING | B.SS_CFG_KEEP_LATE)
+    for _ in range(3):
+        run.step()
+    torch.cuda.synchronize()
+    plan = run.plan()
+    acts = plan["applied"]["actions"]
+    issue_op, free_op = {}, {}
+    for op, kind, tid, batch in acts.tolist():
+        if kind == B.SS_ACT_OUT:
+            issue_op.setdefault(batch, op)
+        elif kind == B.SS_ACT_FREE:
+            free_op[batch] = max(free_op.get(batch, 0), op)
+    B.ss_trace_begin(run.ctx)
+    seen_done, pending, n_query, t_query = {}, [], 0, 0.0
+
+    def run_op(i):
+        nonlocal n_query, t_query
+        run.record(i)
+        run.compute.run_op(i)
+        # what a host-polled release does at every dispatch: query the events of blocks in flight
+        for b in sorted(issue_op):
+            if issue_op[b] < i and b not in seen_done and b not in pending:
+                pending.append(b)
+        q0 = time.perf_counter()
+        for b in list(pending):
+            n_query += 1
+            if B.ss_batch_done(run.ctx, 0, b):
+                seen_done[b] = i
+                pending.remove(b)
+        t_query += time.perf_counter() - q0
+    t0 = time.perf_counter()
+    run_iteration_dispatch(run.ctx, run.tr.n_ops, run_op, plan["points"])
+    torch.cuda.synchronize()
+    t_step = time.perf_counter() - t0
+    ours = np.array([free_op[b] - issue_op[b] for b in sorted(issue_op)])
+    stock = np.array([seen_done.get(b, run.tr.n_ops) - issue_op[b] for b in sorted(issue_op)])
+    n_ops = run.tr.n_ops
+    run.close()
+
+    def dist(a):
+        return {"mean": round(float(a.mean()), 1), "p50": int(np.percentile(a, 50)), "p90": int(np.percentile(a, 90)),
+                "p99": int(np.percentile(a, 99)), "max": int(a.max())}
+    return {"mode": "reuse-interval", "config": cfgno, "swap_out_batches": len(ours),
+            "ops_per_step": n_ops, "step_ms": round(t_step * 1e3, 2),
+            "device_side_release_ops": dist(ours), "host_polled_release_ops": dist(stock),
+            "host_polled_event_queries_per_step": n_query,
+            "host_polled_query_ms_per_step": round(t_query * 1e3, 3)}
+
+
+def record_hook_overhead(B, torch, shapes=None, steps=20, warmup=5):
+    """Overhead of the dispatch hook on a real PyTorch training step (the comparison of the paper's
+    profiler-overhead table, Sec. 6: no profiling, Lightweight mode, Detailed mode, PyTorch's built-in
+    profiler): a Llama-like decoder in plain PyTorch, bf16, AdamW; step = zero_grad, forward, loss,
+    backward, optimizer step."""
+    import paper_2509_11076_amd.torch_hook as H
+    from workloads.torch_model import Trainer
+    from torch.profiler import profile, ProfilerActivity
+    shapes = shapes or {"gpu_bound": dict(layers=12, hidden=1024, heads=16, seq=1024, batch=4, vocab=32000),
+                        "host_bound": dict(layers=12, hidden=256, heads=4, seq=128, batch=1, vocab=32000)}
+
+    def timed(fn, n, w):
+        for _ in range(w):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e3
+    out = {}
+    for sname, sh in shapes.items():
+        tr = Trainer(argparse.Namespace(**sh))
+        rows = {}
+        rows["no profiling"] = dict(ms_per_step=timed(tr.step, steps, warmup))
+        cfg = B.ss_config_default()
+        cfg.staging_bytes = 4096
+        cfg.max_ops = 1 << 18
+        cfg.max_events = 1 << 20
+        ctx = B.ss_create(cfg)
+        tr.hook = H
+        try:
+            for name, mode in (("hook, Lightweight mode", H.SS_HOOK_LIGHTWEIGHT), ("hook, Detailed mode", H.SS_HOOK_DETAILED)):
+                H.ss_hook_install(ctx, mode)
+                ms = timed(tr.step, steps, warmup)
+                ops, ev, _ = B.ss_trace_view(ctx)
+                rows[name] = dict(ms_per_step=ms, ops_per_step=len(ops), events_per_step=len(ev))
+            H.ss_hook_set_mode(H.SS_HOOK_OFF)
+            rows["hook installed, switched off"] = dict(ms_per_step=timed(tr.step, steps, warmup))
+        finally:
+            H.ss_hook_remove()
+            tr.hook = None
+            B.ss_destroy(ctx)
+        for name, kw in (("torch.profiler, CPU activity", dict()),
+                         ("torch.profiler, shapes+memory+stacks", dict(record_shapes=True, profile_memory=True, with_stack=True))):
+            for _ in range(2):
+                tr.step()
+            torch.cuda.synchronize()
+            n = max(3, steps // 4)
+            with profile(activities=[ProfilerActivity.CPU], **kw):
+                rows[name] = dict(ms_per_step=timed(tr.step, n, 1), steps=n)
+        base = rows["no profiling"]["ms_per_step"]
+        for r in rows.values():
+            r["overhead_pct"] = round(100 * (r["ms_per_step"] / base - 1), 1)
+            r["ms_per_step"] = round(r["ms_per_step"], 3)
+        out[sname] = {"workload": "Llama-like decoder, %(layers)d layers, hidden %(hidden)d, %(heads)d heads, seq %(seq)d, "
+                                  "batch %(batch)d, bf16, AdamW" % sh, "steps": steps, "warmup": warmup, "modes": rows}
+        log("hook overhead, %s: %s" % (sname, {k: v["overhead_pct"] for k, v in rows.items()}))
+        del tr
+        torch.cuda.empty_cache()
+    return {"mode": "hook-overhead", "paper_table_context": "the paper's testbed: Lightweight +0.9 %, Detailed +34.6 %, "
+            "PyTorch profiler +219.7 %", "shapes": out}
+
+
+# ---- the fixed-sequence configurations: 1, 2, 3, 5 ----------------------------------------------------
+
+def measure(B, torch, np, bw, o):
+    """one record for configuration o.config with o.steps timed steps after o.warmup warm-up steps"""
+    from workloads.harness import SwapRun
+    paths = {"auto": B.SS_PATH_AUTO, "kernel": B.SS_PATH_KERNEL, "engine": B.SS_PATH_ENGINE, "staged": B.SS_PATH_STAGED}
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    cfgno = o.config
+    bpo = o.bpo
+    workgroups_out = o.workgroups_out
+    extra = {}
+    if cfgno == 3:       # 7B shape under a 48 GB budget: greedy policy, link share fixed so that it fits
+        extra = dict(budget=48 * 10**9, min_bytes=1 << 20)
+        if bpo <= 0:
+            bpo = 256 << 20
+    if o.policy_mode == "generated":
+        # the paper's generator (Sec. 4) picks the swap set for a memory limit instead of the
+        # configuration prescribing it; one logical layer per decoder layer and phase
+        if cfgno not in (2, 3):
+            sys.exit("--policy-mode generated: configurations 2 and 3 only")
+        from workloads import transformer as T
+        shape = T.config_shape(cfgno)
+        extra = dict(min_bytes=1 << 16, generator=dict(g_fwd=shape.layers, g_bwd=shape.layers, c_num=1, c_den=1),
+                     policy_points=o.timing == "policy-points")
+        if cfgno == 2:
+            tr_ = T.build_trace(shape)
+            pcfg = B.ss_config_default()
+            pcfg.staging_bytes = 4096
+            sctx = B.ss_create(pcfg)
+            extra["budget"] = int(o.limit_frac * B.ss_timeline_scan(sctx, tr_.events, None, tr_.n_ops, 0, 1 << 62,
+                                                                    want_per_op=False)["peak"])
+            B.ss_destroy(sctx)
+            del tr_
+        else:
+            extra["budget"] = 48 * 10**9
+    has_compute = cfgno != 5
+    if cfgno == 5:       # small-tensor stress: no model around it
+        extra = dict(compute=False)
+        if bpo <= 0:
+            bpo = 256 << 20
+    # the same step without any swapping
+    if has_compute:
+        base = SwapRun(B, torch, cfgno, swap=False)
+        t_noswap = timed(base.step_noswap, o.steps, o.warmup)
+        base_n_ops = base.tr.n_ops
+        # forward / backward split of the no-swap step (two markers): operators of the forward pass are
+        # several times shorter than those of the backward pass, which Eq. 1's even spread ignores
+        ph = list(base.tr.op_phase)
+        first_bwd = ph.index(1) if 1 in ph else len(ph)
+        ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev3[0].record()
+        for i in range(base.tr.n_ops):
+            if i == first_bwd:
+                ev3[1].record()
+            base.compute.run_op(i)
+        if first_bwd == len(ph):
+            ev3[1].record()
+        ev3[2].record()
+        torch.cuda.synchronize()
+        t_fwd, t_bwd = ev3[0].elapsed_time(ev3[1]) * 1e-3, ev3[1].elapsed_time(ev3[2]) * 1e-3
+        n_fwd, n_bwd = max(1, first_bwd), max(1, len(ph) - first_bwd)
+        base.close()
+        del base
+        torch.cuda.empty_cache()
+        log("config %d: no-swap baseline done: %.1f ms/step" % (cfgno, t_noswap * 1e3))
+    else:
+        t_noswap, base_n_ops = 1e-9, 1
+        t_fwd = t_bwd = 0.0
+        n_fwd = n_bwd = 1
+
+    # Link model.  Eq. 1 spreads the measured iteration time evenly over the operators and Eq. 3
+    # turns bytes into time, so bytes-per-operator = link peak x iteration time / operators.  The
+    # iteration time under swapping is not known before swapping: as in the paper's GenPolicy stage
+    # (several policies are generated from successive measured iterations and the fastest is kept,
+    # Sec. 6), the model is re-fitted from the measured step time a few times and the best kept.
+    flags = B.SS_CFG_TIMING | (B.SS_CFG_KEEP_LATE if o.policy_mode == "execute-all" else 0)
+    link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
+    calib = []
+    # the swap-in queue is planned with the no-swap operator time: operators never run faster than that
+    bpo_in = max(1, int(link * t_noswap / base_n_ops)) if cfgno in (1, 2) else 0
+    if cfgno == 3:
+        # swap-ins planned at half the swap-out share: they are issued about twice as far ahead of their use,
+        # so the link starts bringing tensors back as soon as the first backward operators have freed room
+        # (2.25 s -> 2.16 s per step; at 112 MiB and below the budget no longer holds them)
+        bpo_in = o.bpo_in if o.bpo_in > 0 else 128 << 20
+    if o.policy_mode == "generated" and o.timing == "link-model" and bpo <= 0:
+        # swap-outs queue up during the forward pass, swap-ins during the backward pass: each queue gets
+        # that pass's measured bytes per operator (with 10 % margin); the generator's Eq. 1 keeps the
+        # whole-iteration average
+        extra["generator"]["bpo"] = max(1, int(link * t_noswap / base_n_ops))
+        bpo = max(1, int(0.9 * link * t_fwd / n_fwd))
+        bpo_in = max(1, int(0.9 * link * t_bwd / n_bwd))
+    if o.policy_mode == "generated" and o.timing == "policy-points" and o.phase_eq1 and has_compute:
+        # Eq. 1 per phase: a forward operator is several times shorter than a backward one here; the
+        # forward operators are cut into as many logical layers as still hold the largest candidate
+        from workloads import transformer as T
+        tab_ = T.build_trace(T.config_shape(cfgno)).tensors
+        keep_ = (tab_["first_bwd_use"] != 0xFFFFFFFF) & (tab_["last_fwd_use"] != 0xFFFFFFFF)
+        biggest = int(tab_["nbytes"][keep_].max())
+        f_bpo, b_bpo = max(1, int(link * t_fwd / n_fwd)), max(1, int(link * t_bwd / n_bwd))
+        extra["generator"]["phase_bytes_per_op"] = (f_bpo, b_bpo, b_bpo)
+        extra["generator"]["g_fwd"] = max(1, min(extra["generator"]["g_fwd"], int(n_fwd * f_bpo // (3 * biggest // 2))))
+        if bpo <= 0:
+            bpo = max(1, int(link * t_noswap / base_n_ops))      # not used by the generator's own points
+    path, path_in = paths[o.path], paths[o.path_in or o.path]
+
+    def make(bpo_, wgo=workgroups_out, p=None, p_in=None):
+        return SwapRun(B, torch, cfgno, swap=True, bpo=bpo_, bpo_in=bpo_in, copy_path=path if p is None else p,
+                       copy_path_in=path_in if p_in is None else p_in, copy_workgroups=o.workgroups,
+                       copy_workgroups_out=wgo, flags=flags, **extra)
+
+    def trial(label, **kw):
+        r = make(**kw)
+        t = timed(r.step, 3, 2)
+        forced, dropped = r.n_forced, r.n_dropped
+        r.close()
+        del r
+        torch.cuda.empty_cache()
+        log("config %d: %s -> %.1f ms/step" % (cfgno, label, t * 1e3))
+        return t, forced, dropped
+    if bpo <= 0:
+        bpo = max(1, int(link * t_noswap / base_n_ops))
+        for _ in range(max(1, o.calibrate)):
+            t_trial, forced, dropped = trial("link-model fit, %d bytes/op" % bpo, bpo_=bpo)
+            calib.append({"link_bytes_per_op": bpo, "ms_per_step": round(t_trial * 1e3, 2), "forced": forced,
+                          "dropped": dropped})
+            nxt = max(1, int(link * t_trial / base_n_ops))
+            if any(abs(nxt - c["link_bytes_per_op"]) < 0.03 * nxt for c in calib):
+                break
+            bpo = nxt
+        bpo = min(calib, key=lambda c: c["ms_per_step"])["link_bytes_per_op"]
+    # grid of the pack launches: a grid that saturates the link delays every kernel launched beside it,
+    # a small one (8 workgroups, about 3/4 of the link rate) hardly does; which wins depends on whether
+    # the step is bound by the link or by the compute stream, so both are measured and the faster kept.
+    # Likewise the route: directly between the blocks and the staging area (SS_PATH_AUTO), or through the
+    # rings in HBM with one copy-engine transfer per ring slot (SS_PATH_STAGED).  Configuration 3's tensors
+    # exceed a ring slot and all go by copy engine: nothing to choose there.
+    grid_fits, path_fits = [], []
+    if has_compute and cfgno != 3 and o.calibrate > 0:
+        if o.path == "auto" and o.path_in is None:
+            for name, p in (("auto", B.SS_PATH_AUTO), ("staged", B.SS_PATH_STAGED)):
+                t_trial = trial("route %s" % name, bpo_=bpo, p=p, p_in=p)[0]
+                path_fits.append({"route": name, "ms_per_step": round(t_trial * 1e3, 2)})
+            if path_fits[1]["ms_per_step"] < 0.99 * path_fits[0]["ms_per_step"]:
+                path = path_in = B.SS_PATH_STAGED
+        if workgroups_out == 0 and path != B.SS_PATH_STAGED:
+            for wgo in (0, 8):
+                t_trial = trial("pack grid %s" % (wgo or "default"), bpo_=bpo, wgo=wgo)[0]
+                grid_fits.append({"workgroups_out": wgo or "default", "ms_per_step": round(t_trial * 1e3, 2)})
+            if grid_fits[1]["ms_per_step"] < 0.98 * grid_fits[0]["ms_per_step"]:
+                workgroups_out = 8
+    run = make(bpo_=bpo, wgo=workgroups_out)
+    n_forced, n_dropped_setup, run_generated = run.n_forced, run.n_dropped, run.generated
+    for _ in range(o.warmup):
+        run.step()
+    torch.cuda.synchronize()
+    st0 = B.ss_get_stats(run.ctx)
+    # the timed region: nothing but the steps (per-batch events are read after it)
+    t0 = time.perf_counter()
+    for _ in range(o.steps):
+        run.step()
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / o.steps
+    st1 = B.ss_get_stats(run.ctx)
+    # per-launch durations from the HIP events recorded on the swap streams: those of the last timed step,
+    # and of up to three more steps run for this purpose alone
+    unit_ms = {0: [], 1: [], 2: [], 3: []}
+    spans = {0: [], 1: [], 2: [], 3: []}
+
+    def read_events():
+        for d in (0, 1, 2, 3):
+            ms = B.ss_batch_ms_all(run.ctx, d)
+            ms = ms[ms >= 0]
+            if len(ms):
+                unit_ms[d] += ms.tolist()
+                try:
+                    spans[d].append(B.ss_batch_ms(run.ctx, d)[1])
+                except B.SsError:                 # first unit of the direction did not run that way
+                    pass
+    read_events()
+    for _ in range(min(3, o.steps)):
+        run.step()
+        torch.cuda.synchronize()
+        read_events()
+    event_steps = 1 + min(3, o.steps)
+    st2 = B.ss_get_stats(run.ctx)
+    applied, match, scan = run.last["applied"], run.last["match"], run.last["scan"]
+    bytes_way = run.bytes_each_way
+    assert st1["bytes_out"] - st0["bytes_out"] == o.steps * bytes_way == st1["bytes_in"] - st0["bytes_in"]
+    n_ops = run.tr.n_ops
+    hl = run.host_ms_log[-o.steps:]
+    trace_work = {k: round(sum(h[k] for h in hl) / len(hl), 3) for k in ("match", "apply", "scan")}
+    n_events = len(run.tr.events)
+    reused = sum(1 for h in hl if h["apply"] == 0.0)
+    run.close()
+    del run
+    torch.cuda.empty_cache()
+
+    per_step = lambda k: (st1[k] - st0[k]) // o.steps
+    kernel_batches, engine_batches = per_step("kernel_batches"), per_step("engine_batches")
+    engine_out = per_step("engine_batches_out")
+    ring_out, ring_in = per_step("ring_batches"), per_step("ring_batches_in")
+    ring_tr_out, ring_tr_in = per_step("ring_transfers"), per_step("ring_transfers_in")
+    nob, nib = int(applied["n_out_batches"]), int(applied["n_in_batches"])
+    engine_in = engine_batches - engine_out
+
+    def mover(ring, engine, nb):
+        if ring and ring == nb:
+            return "copy kernel into the HBM ring + one copy-engine transfer per ring slot"
+        if ring:
+            return "mixed (ring and direct)"
+        if engine == nb:
+            return "copy engine"
+        return "copy kernel" if engine == 0 else "mixed (copy kernel and copy engine)"
+    out_by, in_by = mover(ring_out, engine_out, nob), mover(ring_in, engine_in, nib)
+
+    value = 2 * bytes_way / t_step / 1e9
+    # link-side units of a direction: the ring transfers if it went through the ring, else its batches
+    out_link_ms = unit_ms[2] if ring_out == nob and nob else unit_ms[0]
+    in_link_ms = unit_ms[3] if ring_in == nib and nib else unit_ms[1]
+    out_link_span = spans[2] if ring_out == nob and nob else spans[0]
+    in_link_span = spans[3] if ring_in == nib and nib else spans[1]
+    gb = lambda ms_total: bytes_way * event_steps / (ms_total * 1e-3) / 1e9 if ms_total > 0 else 0.0
+    d2h_busy, h2d_busy = gb(sum(out_link_ms)), gb(sum(in_link_ms))            # while a transfer / launch runs
+    d2h_span = bytes_way / (np.mean(out_link_span) * 1e-3) / 1e9 if out_link_span else 0.0   # first start .. last end
+    h2d_span = bytes_way / (np.mean(in_link_span) * 1e-3) / 1e9 if in_link_span else 0.0
+    t_floor = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9), bytes_way / (bw["h2d_gbps"] * 1e9))
+    # the last tensors to leave are the first needed back, so the two directions hardly overlap:
+    t_floor_serial = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9) + bytes_way / (bw["h2d_gbps"] * 1e9))
+    # roofline of the mover of the swap-out direction (the dominant one: it holds the forward pass back)
+    if out_by == "copy kernel":
+        kname, k_ms, k_peak = "ss_copy_kernel<to host>, pack launches (swap-out)", unit_ms[0], bw["d2h_gbps"]
+    elif ring_out:
+        kname, k_ms, k_peak = "copy-engine transfers out of the HBM ring (swap-out); gathers by ss_copy_kernel", unit_ms[2], bw["d2h_gbps"]
+    else:
+        kname, k_ms, k_peak = "copy engine, one hipMemcpyAsync per tensor (swap-out)", unit_ms[0], bw["d2h_gbps"]
+    if k_ms:
+        avg_launch_ms = sum(k_ms) / len(k_ms)
+        bytes_per_launch = bytes_way * event_steps / len(k_ms)
+        link_achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    else:
+        avg_launch_ms = bytes_per_launch = link_achieved = 0.0
+    roof = {"bound": "host_link", "achieved": round(link_achieved, 2), "peak": round(k_peak, 2), "unit": "GB/s",
+            "frac": round(link_achieved / k_peak, 4),
+            "traffic": int(PACK_TRAFFIC_RATIO * 2 * bytes_per_launch) if out_by == "copy kernel" else None,
+            "traffic_note": "derived, not a counter of this run: %.3f x the algorithmic bytes of a launch (HBM read + host "
+                            "write = 2 x bytes_per_launch), the ratio rocprofv3 FETCH_SIZE / WRITE_SIZE gave for the pack "
+                            "kernel (%s)" % (PACK_TRAFFIC_RATIO, PACK_TRAFFIC_SOURCE),
+            "mover": out_by, "kernel": kname, "avg_launch_ms": round(avg_launch_ms, 4),
+            "bytes_per_launch": int(bytes_per_launch), "launches_timed": len(k_ms),
+            "launches_timed_note": "HIP events of the last timed step and of %d further steps" % (event_steps - 1),
+            "hbm": {"achieved": round(link_achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(link_achieved / HBM_PEAK_GBPS, 5),
+                    "note": "HBM side of the same bytes (one HBM access per byte moved over the link); by design far from the HBM roofline"}}
+    if ring_out or ring_in:
+        g_ms = (unit_ms[0] if ring_out else []) + (unit_ms[1] if ring_in else [])
+        g_bytes = bytes_way * event_steps * (int(bool(ring_out)) + int(bool(ring_in)))
+        roof["ring_kernel"] = {"kernel": "ss_copy_kernel, HBM <-> HBM ring (gather / scatter)", "bound": "hbm",
+                               "achieved": round(2 * g_bytes / (sum(g_ms) * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                               "unit": "GB/s", "frac": round(2 * g_bytes / (sum(g_ms) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                               "launches_timed": len(g_ms), "avg_launch_ms": round(sum(g_ms) / len(g_ms), 4),
+                               "note": "read + write bytes of the launches over their summed durations"}
+    rec = {
+        "metric": METRIC, "value": round(value, 3), "unit": "GB/s",
+        "value_definition": "(D2H bytes + H2D bytes of a step) / step wall time; the per-direction shares of the link "
+                            "peak are in pct_of_link_peak, each against that direction's own measured peak",
+        "n_gpus": 1, "steps": o.steps, "warmup": o.warmup,
+        "ms_per_step": round(t_step * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": WORKLOADS[cfgno] + (" [swap set chosen by the policy generator for the memory limit instead]"
+                                                   if o.policy_mode == "generated" else ""),
+                   "ops_per_step": n_ops, "tensors_swapped": int(applied["n_kept"]),
+                   "bytes_each_way": bytes_way, "out_batches": nob, "in_batches": nib,
+                   "copy_path_out": {v: k for k, v in paths.items()}[path],
+                   "copy_path_in": {v: k for k, v in paths.items()}[path_in],
+                   "kernel_launches_per_step": int(kernel_batches), "engine_batches_per_step": int(engine_batches),
+                   "ring_transfers_per_step": {"out": int(ring_tr_out), "in": int(ring_tr_in)},
+                   "swap_out_by": out_by, "swap_in_by": in_by,
+                   "link_bytes_per_op": bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib,
+                   "route_fits": path_fits, "pack_grid_fits": grid_fits,
+                   "pack_workgroups": workgroups_out or o.workgroups or "default (64)", "policy_mode": o.policy_mode,
+                   "timing": o.timing if o.policy_mode == "generated" else "link-model",
+                   "generator_params": {k: v for k, v in extra.get("generator", {}).items()} or None,
+                   "noswap_forward_ms": round(t_fwd * 1e3, 2), "noswap_backward_ms": round(t_bwd * 1e3, 2),
+                   "memory_limit_bytes": extra.get("budget"), "generator": run_generated,
+                   "memory_limit_met": (int(scan["peak"]) <= extra["budget"]) if extra.get("budget") else None,
+                   "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),
+                   "stage": int(match["stage"]), "anchors_unmatched": int(match["n_unmatched"])},
+        "trace_work_host_ms_per_step": dict(trace_work, steps_reusing_the_loaded_schedule=reused,
+                                            note="wall time of the call incl. host<->device copies and synchronisation; "
+                                                 "%d operators, %d events, %d anchors; in the Stable stage an iteration whose "
+                                                 "anchors land where they did reuses the loaded schedule (apply and scan 0)"
+                                                 % (n_ops, n_events, int(applied["n_kept"]) + n_dropped_setup)),
+        "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
+        "pct_of_link_peak": {
+            "d2h_while_copying": round(100 * d2h_busy / bw["d2h_gbps"], 1),
+            "h2d_while_copying": round(100 * h2d_busy / bw["h2d_gbps"], 1),
+            "d2h_first_start_to_last_end": round(100 * d2h_span / bw["d2h_gbps"], 1),
+            "h2d_first_start_to_last_end": round(100 * h2d_span / bw["h2d_gbps"], 1),
+            "note": "each direction against its own one-direction peak; the two directions follow one another in the "
+                    "step (what leaves last is needed back first), so their sum over the whole step is not comparable "
+                    "with either peak"},
+        "step_time": {"noswap_ms": round(t_noswap * 1e3, 3), "swap_ms": round(t_step * 1e3, 3),
+                      "overhead_vs_noswap_pct": round(100 * (t_step / t_noswap - 1), 1),
+                      "target_overhead_pct": 5.0,
+                      "compute_stream_stall_ms": round((t_step - t_noswap) * 1e3, 3),
+                      "floor_ms": round(t_floor * 1e3, 3),
+                      "overhead_vs_floor_pct": round(100 * (t_step / t_floor - 1), 1),
+                      "floor_out_then_in_ms": round(t_floor_serial * 1e3, 3),
+                      "overhead_vs_floor_out_then_in_pct": round(100 * (t_step / t_floor_serial - 1), 1),
+                      "link_bound": bool(t_floor_serial > 1.05 * t_noswap)},
+        "roofline": roof,
+    }
+    if not has_compute:
+        for k in ("noswap_ms", "overhead_vs_noswap_pct", "compute_stream_stall_ms", "floor_ms", "overhead_vs_floor_pct"):
+            rec["step_time"][k] = None
+    if not o.no_cpu_baseline and o.policy_mode != "generated":
+        rec["cpu_baseline"] = cpu_baseline_safe(cfgno, bpo)
+    return rec
 
 
 def main():
@@ -75,10 +783,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
-                    help="2 is the headline workload; 1, 3, 5 report the other fixed-sequence configurations")
-    ap.add_argument("--path", default="auto", choices=["auto", "kernel", "engine"])
-    ap.add_argument("--path-in", default=None, choices=["auto", "kernel", "engine"],
+    ap.add_argument("--config", type=int, default=None, choices=[1, 2, 3, 4, 5],
+                    help="measure this configuration alone; default: configuration 3 as the headline and the "
+                         "others as sub-records")
+    ap.add_argument("--no-sub-records", action="store_true", help="default mode: the headline only")
+    ap.add_argument("--path", default="auto", choices=["auto", "kernel", "engine", "staged"])
+    ap.add_argument("--path-in", default=None, choices=["auto", "kernel", "engine", "staged"],
                     help="copy path of the swap-in direction (default: same as --path)")
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--workgroups-out", type=int, default=0,
@@ -86,6 +796,8 @@ def main():
     ap.add_argument("--bpo", type=int, default=0,
                     help="link model: bytes the link moves per operator; 0 = link peak x no-swap step time / "
                          "operators per step, both measured in this run (Eq. 1 and Eq. 3 of the paper)")
+    ap.add_argument("--bpo-in", type=int, default=0,
+                    help="configuration 3: the same for the swap-in queue (0 = as --bpo)")
     ap.add_argument("--policy-mode", default="execute-all", choices=["execute-all", "link-aware", "generated", "staged"],
                     help="execute-all: every tensor of the prescribed set is swapped even where the link "
                          "cannot hide it; link-aware: items whose swap-out cannot finish before their "
@@ -115,6 +827,9 @@ def main():
     ap.add_argument("--path-table", action="store_true",
                     help="GB/s of one batch of equal-size tensors at scattered arena offsets, per size class, "
                          "copy kernel against per-tensor copy-engine calls, both directions (no compute stream work)")
+    ap.add_argument("--hook-overhead", action="store_true",
+                    help="overhead of the dispatch hook on a real PyTorch training step: no profiling, Lightweight, "
+                         "Detailed, torch.profiler (the paper's profiler-overhead table)")
     ap.add_argument("--probe-reps", type=int, default=10)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -125,12 +840,15 @@ def main():
     import numpy as np
     import torch
     import paper_2509_11076_amd.binding as B
-    from workloads.harness import SwapRun
 
     torch.cuda.set_device(0)
-    paths = {"auto": B.SS_PATH_AUTO, "kernel": B.SS_PATH_KERNEL, "engine": B.SS_PATH_ENGINE}
-    path = paths[args.path]
-    path_in = paths[args.path_in or args.path]
+    paths = {"auto": B.SS_PATH_AUTO, "kernel": B.SS_PATH_KERNEL, "engine": B.SS_PATH_ENGINE, "staged": B.SS_PATH_STAGED}
+
+    def emit(line):
+        print(json.dumps(line), flush=True)
+
+    if args.hook_overhead:
+        return emit(record_hook_overhead(B, torch, steps=args.steps, warmup=args.warmup))
 
     # host-link peak, measured now (pinned hipMemcpy; 1 GiB transfers)
     pcfg = B.ss_config_default()
@@ -139,470 +857,82 @@ def main():
     pctx = B.ss_create(pcfg)
     bw = B.ss_bw_probe(pctx, 1 << 30, args.probe_reps)
     B.ss_destroy(pctx)
-    print("link probe done", file=sys.stderr, flush=True)
+    log("link probe done: D2H %.1f GB/s, H2D %.1f GB/s" % (bw["d2h_gbps"], bw["h2d_gbps"]))
 
     if args.swap_only:
-        run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo if args.bpo > 0 else 10 << 20,
-                      bpo_in=4 << 20, copy_path=path, copy_path_in=path_in, copy_workgroups=args.workgroups,
-                      flags=B.SS_CFG_TIMING | B.SS_CFG_KEEP_LATE, compute=False)
-        for _ in range(args.warmup + args.steps):
-            run.step()
-            print("swap-only step done", file=sys.stderr, flush=True)
-        torch.cuda.synchronize()
-        nob = run.last["applied"]["n_out_batches"]
-        out_ms = [B.ss_batch_ms(run.ctx, 0, b)[0] for b in range(nob)]
-        print(json.dumps({"mode": "swap-only", "bytes_each_way": run.bytes_each_way, "out_batches": int(nob),
-                          "in_batches": int(run.last["applied"]["n_in_batches"]),
-                          "avg_pack_launch_ms": round(sum(out_ms) / len(out_ms), 4),
-                          "bytes_per_pack_launch": run.bytes_each_way // nob}), flush=True)
-        run.close()
-        return
-
-    if args.config == 4:
-        # varying sequences at full 7B size: what is measured is the per-iteration trace work (record is
-        # part of the step itself; here: match or align, apply, scan, top-up) and where the anchors land;
-        # bytes are not moved (the larger iterations need more pinned staging than this host gives)
-        from workloads.harness import VaryingRun
-        from workloads import transformer as T
-        shape = T.config_shape(4)
-        pert = dict(p_drop=0.1, p_insert=0.1, moe_max=8, seq_jitter=0.15)
-        out = {}
-        for name, mf in (("keyed_ordinals", 0), ("aligned", B.SS_MATCH_ALIGN)):
-            run = VaryingRun(B, torch, shape, 48 * 10**9, 256 << 20, min_bytes=1 << 20, perturb=pert, compute=False,
-                             match_flags=mf)
-            tr0 = T.build_trace(shape)
-            rows = []
-            for it in range(20):
-                p = run.plan(it)
-                tr = p["trace"]
-                truth = {b: j for j, b in enumerate(tr.op_base) if b is not None}
-                want = np.array([truth.get(tr0.op_base[i], -1) for i in run.anchors["ref_op"].tolist()])
-                got = p["match"]["new_idx"]
-                rows.append(dict(it=it, ops=tr.n_ops, seq=tr.seq, similar=bool(p["match"]["similar"]),
-                                 stage=int(p["match"]["stage"]), anchors=len(got),
-                                 landed_on_true_operator=int((got == want).sum()),
-                                 landed_elsewhere=int(((got != want) & (got >= 0)).sum()),
-                                 unmatched=int((got < 0).sum()), carried=len(p["carried"]), topped_up=int(p["topped"]),
-                                 peak_gb=round(p["scan"]["peak"] / 1e9, 2),
-                                 host_ms={k: round(v, 3) for k, v in p["host_ms"].items()}))
-                print(name, rows[-1], file=sys.stderr, flush=True)
-            run.close()
-            out[name] = rows
-        work = [sum(r["host_ms"].values()) for r in out["aligned"][1:]]
-        print(json.dumps({
-            "metric": "trace work per iteration (match or align, apply, scan, top-up), host wall ms",
-            "value": round(sum(work) / len(work), 3), "unit": "ms", "n_gpus": 1, "steps": 19, "warmup": 1,
-            "ms_per_step": round(sum(work) / len(work), 3), "higher_is_better": False, "scaling": "weak",
-            "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-            "config": {"workload": "config 4: 7B-shape decoder, operator sequence perturbed every iteration (drop / "
-                                   "insert 0.1, 0-8 branch operators per layer, sequence length +-15 %), policy of "
-                                   "iteration 0 re-anchored online under a 48 GB budget; planning only"},
-            "iterations": out}), flush=True)
-        return
-
-    if args.policy_mode == "staged":
-        from workloads.harness import StagedRun
-        from workloads import transformer as T
-        if args.config not in (2, 3):
-            sys.exit("--policy-mode staged: configurations 2 and 3 only")
-        shape = T.config_shape(args.config)
-        tr0 = T.build_trace(shape)
-        link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
-        run = StagedRun(B, torch, lambda it: tr0, limit_frac=args.limit_frac, link_bytes_per_s=link,
-                        g_fwd=shape.layers, g_bwd=shape.layers, min_bytes=1 << 16, flags=B.SS_CFG_TIMING)
-        log = []
-        for it in range(9 + args.steps):
-            e = run.iteration(it)
-            e.pop("result")
-            log.append(e)
-            print("iteration %d stage %d: %.1f ms, %d tensors, %.0f MB each way" %
-                  (it, e["stage"], e["ms"], e["n_items"], e["bytes"] / 1e6), file=sys.stderr, flush=True)
-        run.close()
-        stable = [e for e in log if e["stage"] == 2]
-        warm = [e for e in log if e["stage"] == 0][1:]
-        t_stable = sum(e["ms"] for e in stable) / len(stable) * 1e-3
-        t_warm = sum(e["ms"] for e in warm) / len(warm) * 1e-3
-        print(json.dumps({
-            "metric": "swap GB/s (D2H+H2D) as % of host-link peak; step-time overhead vs no-swap",
-            "value": round(2 * stable[0]["bytes"] / t_stable / 1e9, 3), "unit": "GB/s", "n_gpus": 1,
-            "steps": len(stable), "warmup": 9, "ms_per_step": round(t_stable * 1e3, 3), "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-            "config": {"workload": "config %d trace under the stage loop of Algo. 1 (m = 2, n = 5): WarmUp without "
-                                   "swapping, GenPolicy with one generated policy per iteration, Stable with the "
-                                   "fastest; memory limit %.2f x the no-swap peak" % (args.config, args.limit_frac),
-                       "policy_mode": "staged", "chosen_candidate": stable[0]["candidate"],
-                       "bytes_each_way": stable[0]["bytes"], "tensors_swapped": stable[0]["n_items"],
-                       "peak_bytes_with_policy": stable[0]["peak"]},
-            "step_time": {"warmup_noswap_ms": round(t_warm * 1e3, 3), "stable_ms": round(t_stable * 1e3, 3),
-                          "overhead_vs_noswap_pct": round(100 * (t_stable / t_warm - 1), 1)},
-            "iterations": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in e.items()} for e in log],
-            "link_peak_measured": {k: round(v, 2) for k, v in bw.items()}}), flush=True)
-        return
-
+        return emit(run_swap_only(B, torch, args, paths[args.path], paths[args.path_in or args.path]))
     if args.path_table:
-        from workloads.layouts import DESC_DT
-        from workloads.rng import SplitMix64
-        arena_bytes = 8 << 30
-        arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
-        rows = []
-        for size in (4 << 10, 64 << 10, 1 << 20, 16 << 20, 256 << 20):
-            n = max(4, min(20000, (1 << 30) // size))
-            rng = SplitMix64(size, 3)
-            slots = arena_bytes // size
-            picks = sorted(set(rng.randint(slots) for _ in range(2 * n)))[:n]       # scattered, disjoint
-            rng2 = SplitMix64(size, 4)
-            order = sorted(range(len(picks)), key=lambda i: rng2.randint(1 << 30))  # shuffled issue order
-            d = np.zeros(len(picks), dtype=DESC_DT)
-            for k, i in enumerate(order):
-                d[k] = (picks[i] * size, k * size, size, k, 0)
-            start = np.array([0, len(d)], dtype=np.uint32)
-            row = {"tensor_bytes": size, "tensors": len(d), "batch_bytes": int(size * len(d))}
-            for pname, pcode in (("kernel", B.SS_PATH_KERNEL), ("engine", B.SS_PATH_ENGINE)):
-                cfg = B.ss_config_default()
-                cfg.staging_bytes = int(size * len(d))
-                cfg.copy_path = cfg.copy_path_in = pcode
-                cfg.flags = B.SS_CFG_TIMING
-                ctx = B.ss_create(cfg)
-                B.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
-                B.ss_load_schedule(ctx, d, start, d, start)
-                out_ms, in_ms = [], []
-                for rep in range(4):
-                    B.ss_swap_out(ctx, 0)
-                    B.ss_swap_in(ctx, 0)
-                    B.ss_sync(ctx, B.SS_SYNC_DRAIN)
-                    if rep:
-                        out_ms.append(B.ss_batch_ms(ctx, 0, 0)[0])
-                        in_ms.append(B.ss_batch_ms(ctx, 1, 0)[0])
-                B.ss_destroy(ctx)
-                row[pname + "_d2h_gbps"] = round(row["batch_bytes"] / (min(out_ms) * 1e-3) / 1e9, 2)
-                row[pname + "_h2d_gbps"] = round(row["batch_bytes"] / (min(in_ms) * 1e-3) / 1e9, 2)
-            rows.append(row)
-            print(row, file=sys.stderr, flush=True)
-        print(json.dumps({"mode": "path-table", "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
-                          "rows": rows}), flush=True)
-        return
-
+        return emit(record_path_table(B, torch, np, bw))
     if args.reuse_interval:
-        from paper_2509_11076_amd.executor import run_iteration_dispatch
-        link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
-        base = SwapRun(B, torch, args.config, swap=False)
-        for _ in range(3):
-            base.step_noswap()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(5):
-            base.step_noswap()
-        torch.cuda.synchronize()
-        t_ns = (time.perf_counter() - t0) / 5
-        n_ops = base.tr.n_ops
-        base.close()
-        del base
+        return emit(record_reuse_interval(B, torch, np, bw, args.config or 2, paths[args.path],
+                                          paths[args.path_in or args.path]))
+    if args.config == 4:
+        return emit(record_config4(B, torch, np, cpu=not args.no_cpu_baseline))
+    if args.policy_mode == "staged":
+        if (args.config or 2) not in (2, 3):
+            sys.exit("--policy-mode staged: configurations 2 and 3 only")
+        return emit(record_staged(B, torch, bw, args.config or 2, args.limit_frac, args.steps))
+    if args.config is not None:
+        return emit(measure(B, torch, np, bw, args))
+
+    # default: configuration 3 in full under the given step counts, the rest attached
+    def opts(**kw):
+        o = argparse.Namespace(**vars(args))
+        for k, v in kw.items():
+            setattr(o, k, v)
+        return o
+    t_all = time.perf_counter()
+    try:
+        head = measure(B, torch, np, bw, opts(config=3))
+    except (B.SsError, RuntimeError) as e:
+        # the host refuses 56.5 GB of pinned staging: the largest configuration that fits is the headline
+        log("configuration 3 could not be set up (%s): configuration 2 is the headline" % e)
         torch.cuda.empty_cache()
-        run = SwapRun(B, torch, args.config, swap=True, bpo=max(1, int(link * 2 * t_ns / n_ops)),
-                      bpo_in=max(1, int(link * t_ns / n_ops)), copy_path=path, copy_path_in=path_in,
-                      flags=B.SS_CFG_TIMING | B.SS_CFG_KEEP_LATE)
-        for _ in range(3):
-            run.step()
-        torch.cuda.synchronize()
-        plan = run.plan()
-        acts = plan["applied"]["actions"]
-        issue_op, free_op = {}, {}
-        for op, kind, tid, batch in acts.tolist():
-            if kind == B.SS_ACT_OUT:
-                issue_op.setdefault(batch, op)
-            elif kind == B.SS_ACT_FREE:
-                free_op[batch] = max(free_op.get(batch, 0), op)
-        B.ss_trace_begin(run.ctx)
-        seen_done, pending, n_query, t_query = {}, [], 0, 0.0
+        head = measure(B, torch, np, bw, opts(config=2))
+        head["config"]["headline_note"] = "configuration 3 could not be set up on this host (%s)" % e
+    if not args.no_sub_records:
+        subs = {}
 
-        def run_op(i):
-            nonlocal n_query, t_query
-            run.record(i)
-            run.compute.run_op(i)
-            # what a host-polled release does at every dispatch: query the events of blocks in flight
-            for b in sorted(issue_op):
-                if issue_op[b] < i and b not in seen_done and b not in pending:
-                    pending.append(b)
-            q0 = time.perf_counter()
-            for b in list(pending):
-                n_query += 1
-                if B.ss_batch_done(run.ctx, 0, b):
-                    seen_done[b] = i
-                    pending.remove(b)
-            t_query += time.perf_counter() - q0
-        t0 = time.perf_counter()
-        run_iteration_dispatch(run.ctx, run.tr.n_ops, run_op, plan["points"])
-        torch.cuda.synchronize()
-        t_step = time.perf_counter() - t0
-        ours = np.array([free_op[b] - issue_op[b] for b in sorted(issue_op)])
-        stock = np.array([seen_done.get(b, run.tr.n_ops) - issue_op[b] for b in sorted(issue_op)])
-        run.close()
-
-        def dist(a):
-            return {"mean": round(float(a.mean()), 1), "p50": int(np.percentile(a, 50)), "p90": int(np.percentile(a, 90)),
-                    "p99": int(np.percentile(a, 99)), "max": int(a.max())}
-        print(json.dumps({"mode": "reuse-interval", "config": args.config, "swap_out_batches": len(ours),
-                          "ops_per_step": run.tr.n_ops, "step_ms": round(t_step * 1e3, 2),
-                          "device_side_release_ops": dist(ours), "host_polled_release_ops": dist(stock),
-                          "host_polled_event_queries_per_step": n_query,
-                          "host_polled_query_ms_per_step": round(t_query * 1e3, 3)}), flush=True)
-        return
-
-    def timed(run, fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
-
-    extra = {}
-    if args.config == 3:       # 7B shape under a 48 GB budget: greedy policy, link share fixed so that it fits
-        extra = dict(budget=48 * 10**9, min_bytes=1 << 20)
-        if args.bpo <= 0:
-            args.bpo = 256 << 20
-    if args.policy_mode == "generated":
-        # the paper's generator (Sec. 4) picks the swap set for a memory limit instead of the
-        # configuration prescribing it; one logical layer per decoder layer and phase
-        if args.config not in (2, 3):
-            sys.exit("--policy-mode generated: configurations 2 and 3 only")
-        from workloads import transformer as T
-        shape = T.config_shape(args.config)
-        extra = dict(min_bytes=1 << 16, generator=dict(g_fwd=shape.layers, g_bwd=shape.layers, c_num=1, c_den=1),
-                     policy_points=args.timing == "policy-points")
-        if args.config == 2:
-            tr_ = T.build_trace(shape)
-            sctx = B.ss_create(pcfg)
-            extra["budget"] = int(args.limit_frac * B.ss_timeline_scan(sctx, tr_.events, None, tr_.n_ops, 0, 1 << 62,
-                                                                      want_per_op=False)["peak"])
-            B.ss_destroy(sctx)
-            del tr_
-        else:
-            extra["budget"] = 48 * 10**9
-    has_compute = args.config != 5
-    if args.config == 5:       # small-tensor stress: no model around it
-        extra = dict(compute=False)
-        if args.bpo <= 0:
-            args.bpo = 256 << 20
-    # the same step without any swapping
-    if has_compute:
-        base = SwapRun(B, torch, args.config, swap=False)
-        t_noswap = timed(base, base.step_noswap, args.steps, args.warmup)
-        base_n_ops = base.tr.n_ops
-        # forward / backward split of the no-swap step (two markers): operators of the forward pass are
-        # several times shorter than those of the backward pass, which Eq. 1's even spread ignores
-        ph = list(base.tr.op_phase)
-        first_bwd = ph.index(1) if 1 in ph else len(ph)
-        ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        ev3[0].record()
-        for i in range(base.tr.n_ops):
-            if i == first_bwd:
-                ev3[1].record()
-            base.compute.run_op(i)
-        if first_bwd == len(ph):
-            ev3[1].record()
-        ev3[2].record()
-        torch.cuda.synchronize()
-        t_fwd, t_bwd = ev3[0].elapsed_time(ev3[1]) * 1e-3, ev3[1].elapsed_time(ev3[2]) * 1e-3
-        n_fwd, n_bwd = max(1, first_bwd), max(1, len(ph) - first_bwd)
-        base.close()
-        del base
-        torch.cuda.empty_cache()
-        print("no-swap baseline done: %.1f ms/step" % (t_noswap * 1e3), file=sys.stderr, flush=True)
-    else:
-        t_noswap, base_n_ops = 1e-9, 1
-        t_fwd = t_bwd = 0.0
-        n_fwd = n_bwd = 1
-
-    # Link model.  Eq. 1 spreads the measured iteration time evenly over the operators and Eq. 3
-    # turns bytes into time, so bytes-per-operator = link peak x iteration time / operators.  The
-    # iteration time under swapping is not known before swapping: as in the paper's GenPolicy stage
-    # (several policies are generated from successive measured iterations and the fastest is kept,
-    # Sec. 6), the model is re-fitted from the measured step time a few times and the best kept.
-    flags = B.SS_CFG_TIMING | (B.SS_CFG_KEEP_LATE if args.policy_mode == "execute-all" else 0)
-    link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
-    calib = []
-    # the swap-in queue is planned with the no-swap operator time: operators never run faster than that
-    bpo_in = max(1, int(link * t_noswap / base_n_ops)) if args.config in (1, 2) else 0
-    if args.policy_mode == "generated" and args.timing == "link-model" and args.bpo <= 0:
-        # swap-outs queue up during the forward pass, swap-ins during the backward pass: each queue gets
-        # that pass's measured bytes per operator (with 10 % margin); the generator's Eq. 1 keeps the
-        # whole-iteration average
-        extra["generator"]["bpo"] = max(1, int(link * t_noswap / base_n_ops))
-        args.bpo = max(1, int(0.9 * link * t_fwd / n_fwd))
-        bpo_in = max(1, int(0.9 * link * t_bwd / n_bwd))
-    if args.policy_mode == "generated" and args.timing == "policy-points" and args.phase_eq1 and has_compute:
-        # Eq. 1 per phase: a forward operator is several times shorter than a backward one here; the
-        # forward operators are cut into as many logical layers as still hold the largest candidate
-        from workloads import transformer as T
-        tab_ = T.build_trace(T.config_shape(args.config)).tensors
-        keep_ = (tab_["first_bwd_use"] != 0xFFFFFFFF) & (tab_["last_fwd_use"] != 0xFFFFFFFF)
-        biggest = int(tab_["nbytes"][keep_].max())
-        f_bpo, b_bpo = max(1, int(link * t_fwd / n_fwd)), max(1, int(link * t_bwd / n_bwd))
-        extra["generator"]["phase_bytes_per_op"] = (f_bpo, b_bpo, b_bpo)
-        extra["generator"]["g_fwd"] = max(1, min(extra["generator"]["g_fwd"], int(n_fwd * f_bpo // (3 * biggest // 2))))
-        if args.bpo <= 0:
-            args.bpo = max(1, int(link * t_noswap / base_n_ops))      # not used by the generator's own points
-    if args.bpo <= 0:
-        bpo = max(1, int(link * t_noswap / base_n_ops))
-        for _ in range(max(1, args.calibrate)):
-            trial = SwapRun(B, torch, args.config, swap=True, bpo=bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
-                            copy_workgroups=args.workgroups, copy_workgroups_out=args.workgroups_out, flags=flags, **extra)
-            t_trial = timed(trial, trial.step, 3, 2)
-            calib.append({"link_bytes_per_op": bpo, "ms_per_step": round(t_trial * 1e3, 2),
-                          "forced": trial.n_forced, "dropped": trial.n_dropped})
-            print("link-model fit: %d bytes/op -> %.1f ms/step" % (bpo, t_trial * 1e3), file=sys.stderr, flush=True)
-            trial.close()
-            del trial
+        def sub(name, fn):
+            t0 = time.perf_counter()
+            try:
+                subs[name] = fn()
+            except Exception as e:
+                subs[name] = {"failed": "%s: %s" % (type(e).__name__, e)}
             torch.cuda.empty_cache()
-            nxt = max(1, int(link * t_trial / base_n_ops))
-            if any(abs(nxt - c["link_bytes_per_op"]) < 0.03 * nxt for c in calib):
-                break
-            bpo = nxt
-        args.bpo = min(calib, key=lambda c: c["ms_per_step"])["link_bytes_per_op"]
-    # grid of the pack launches: a grid that saturates the link delays every kernel launched beside it,
-    # a small one (8 workgroups, about 3/4 of the link rate) hardly does; which wins depends on whether
-    # the step is bound by the link or by the compute stream, so both are measured and the faster kept
-    grid_fits = []
-    if has_compute and args.workgroups_out == 0 and args.calibrate > 0:
-        for wgo in (0, 8):
-            trial = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path,
-                            copy_path_in=path_in, copy_workgroups=args.workgroups, copy_workgroups_out=wgo,
-                            flags=flags, **extra)
-            t_trial = timed(trial, trial.step, 3, 2)
-            grid_fits.append({"workgroups_out": wgo or "default", "ms_per_step": round(t_trial * 1e3, 2)})
-            print("pack grid fit: %s -> %.1f ms/step" % (wgo or "default", t_trial * 1e3), file=sys.stderr, flush=True)
-            trial.close()
-            del trial
-            torch.cuda.empty_cache()
-        if grid_fits[1]["ms_per_step"] < 0.98 * grid_fits[0]["ms_per_step"]:
-            args.workgroups_out = 8
-    run = SwapRun(B, torch, args.config, swap=True, bpo=args.bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
-                  copy_workgroups=args.workgroups, copy_workgroups_out=args.workgroups_out, flags=flags, **extra)
-    n_forced, n_dropped_setup, run_generated = run.n_forced, run.n_dropped, run.generated
-    st0 = None
-    for _ in range(args.warmup):
-        run.step()
-    torch.cuda.synchronize()
-    st0 = B.ss_get_stats(run.ctx)
-    out_ms, in_ms, out_span, in_span = [], [], [], []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run.step()
-        # per-launch durations from HIP events recorded on the swap streams (read after the drain)
-        nob, nib = run.last["applied"]["n_out_batches"], run.last["applied"]["n_in_batches"]
-        out_ms += [B.ss_batch_ms(run.ctx, 0, b)[0] for b in range(nob)]
-        in_ms += [B.ss_batch_ms(run.ctx, 1, b)[0] for b in range(nib)]
-        out_span.append(B.ss_batch_ms(run.ctx, 0)[1])
-        in_span.append(B.ss_batch_ms(run.ctx, 1)[1])
-    torch.cuda.synchronize()
-    t_step = (time.perf_counter() - t0) / args.steps
-    st1 = B.ss_get_stats(run.ctx)
-    applied, match, scan = run.last["applied"], run.last["match"], run.last["scan"]
-    bytes_way = run.bytes_each_way
-    assert st1["bytes_out"] - st0["bytes_out"] == args.steps * bytes_way == st1["bytes_in"] - st0["bytes_in"]
-    kernel_batches = st1["kernel_batches"] - st0["kernel_batches"]
-    engine_batches = st1["engine_batches"] - st0["engine_batches"]
-    n_ops = run.tr.n_ops
-    hl = run.host_ms_log[-args.steps:]
-    trace_work = {k: round(sum(h[k] for h in hl) / len(hl), 3) for k in ("match", "apply", "scan")}
-    n_events = len(run.tr.events)
-    run.close()
-
-    value = 2 * bytes_way / t_step / 1e9
-    d2h_busy = bytes_way * args.steps / (sum(out_ms) * 1e-3) / 1e9       # while a swap-out launch is running
-    h2d_busy = bytes_way * args.steps / (sum(in_ms) * 1e-3) / 1e9
-    d2h_span = bytes_way / (np.mean(out_span) * 1e-3) / 1e9               # first start .. last end of a step
-    h2d_span = bytes_way / (np.mean(in_span) * 1e-3) / 1e9
-    t_floor = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9), bytes_way / (bw["h2d_gbps"] * 1e9))
-    # the last tensors to leave are the first needed back (LIFO), so the two directions hardly overlap:
-    t_floor_serial = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9) + bytes_way / (bw["h2d_gbps"] * 1e9))
-    # roofline of the copy kernel: only the launches that really were kernel launches
-    n_out_l, n_in_l = len(out_ms), len(in_ms)
-    engine_out = st1["engine_batches_out"] - st0["engine_batches_out"]
-    out_by_kernel = engine_out == 0                               # a mix of paths does not occur on this side
-    engine_in = engine_batches - engine_out
-    in_by_kernel = engine_in == 0                                 # a mix of paths is left out of the figure
-    k_ms = (out_ms if out_by_kernel else []) + (in_ms if in_by_kernel else [])
-    k_bytes = bytes_way * args.steps * (int(out_by_kernel) + int(in_by_kernel))
-    if k_ms:
-        avg_launch_ms = sum(k_ms) / len(k_ms)
-        bytes_per_launch = k_bytes / len(k_ms)
-        link_achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
-    else:
-        avg_launch_ms = bytes_per_launch = link_achieved = 0.0
-    link_peak = max(bw["d2h_gbps"], bw["h2d_gbps"])
-    which = ("pack launches (swap-out)" if out_by_kernel else "") + \
-            (" and " if out_by_kernel and in_by_kernel else "") + ("unpack launches (swap-in)" if in_by_kernel else "")
-    line = {
-        "metric": "swap GB/s (D2H+H2D) as % of host-link peak; step-time overhead vs no-swap",
-        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(t_step * 1e3, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": {
-            1: "config 1: toy 2-layer block, layer-0 activations swapped",
-            2: "config 2: 1.3B-shape decoder (hidden 2048, 24 layers, seq 2048, mb 1, bf16), "
-               "activations of every other layer swapped, synthetic bf16 GEMMs on the compute stream",
-            3: "config 3: 7B-shape decoder (hidden 4096, 32 layers, seq 4096, mb 1, bf16), 97 GiB of activations "
-               "under a 48 GB budget, longest-idle-first policy, synthetic bf16 GEMMs on the compute stream",
-            5: "config 5: 20,000 tensors of 4 KiB..4 MiB at random places of a 64 GB arena, two random orders, "
-               "no compute stream work"}[args.config] +
-            (" [swap set chosen by the policy generator for the memory limit instead]"
-             if args.policy_mode == "generated" else ""),
-                   "ops_per_step": n_ops, "tensors_swapped": int(applied["n_kept"]),
-                   "bytes_each_way": bytes_way, "out_batches": int(applied["n_out_batches"]),
-                   "in_batches": int(applied["n_in_batches"]), "copy_path_out": args.path,
-                   "copy_path_in": args.path_in or args.path,
-                   "kernel_launches": int(kernel_batches), "engine_batches": int(engine_batches),
-                   "swap_out_by": "copy kernel" if out_by_kernel else "copy engine",
-                   "swap_in_by": "copy kernel" if in_by_kernel else ("copy engine" if engine_in == n_in_l else "both"),
-                   "link_bytes_per_op": args.bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib, "pack_grid_fits": grid_fits,
-                   "pack_workgroups": args.workgroups_out or args.workgroups or "default (64)", "policy_mode": args.policy_mode,
-                   "timing": args.timing if args.policy_mode == "generated" else "link-model",
-                   "generator_params": {k: v for k, v in extra.get("generator", {}).items()} or None,
-                   "noswap_forward_ms": round(t_fwd * 1e3, 2), "noswap_backward_ms": round(t_bwd * 1e3, 2),
-                   "memory_limit_bytes": extra.get("budget"), "generator": run_generated,
-                   "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),
-                   "stage": int(match["stage"]), "anchors_unmatched": int(match["n_unmatched"])},
-        "trace_work_host_ms_per_step": dict(trace_work, note="wall time of the call incl. host<->device copies and "
-                                            "synchronisation; %d operators, %d events, %d anchors"
-                                            % (n_ops, n_events, int(applied["n_kept"]) + n_dropped_setup)),
-        "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
-        "pct_of_link_peak": {
-            "d2h_while_copying": round(100 * d2h_busy / bw["d2h_gbps"], 1),
-            "h2d_while_copying": round(100 * h2d_busy / bw["h2d_gbps"], 1),
-            "d2h_first_start_to_last_end": round(100 * d2h_span / bw["d2h_gbps"], 1),
-            "h2d_first_start_to_last_end": round(100 * h2d_span / bw["h2d_gbps"], 1),
-            "whole_step_vs_one_direction": round(100 * value / link_peak, 1)},
-        "step_time": {"noswap_ms": round(t_noswap * 1e3, 3), "swap_ms": round(t_step * 1e3, 3),
-                      "overhead_vs_noswap_pct": round(100 * (t_step / t_noswap - 1), 1),
-                      "compute_stream_stall_ms": round((t_step - t_noswap) * 1e3, 3),
-                      "floor_ms": round(t_floor * 1e3, 3),
-                      "overhead_vs_floor_pct": round(100 * (t_step / t_floor - 1), 1),
-                      "floor_out_then_in_ms": round(t_floor_serial * 1e3, 3),
-                      "overhead_vs_floor_out_then_in_pct": round(100 * (t_step / t_floor_serial - 1), 1)},
-        "roofline": {"bound": "host_link", "achieved": round(link_achieved, 2), "peak": round(link_peak, 2),
-                     "unit": "GB/s", "frac": round(link_achieved / link_peak, 4),
-                     "traffic": int(PACK_TRAFFIC_RATIO * 2 * bytes_per_launch) if out_by_kernel else None,
-                     "traffic_note": "bytes per launch at the L2 (HBM read + host write), algorithmic = 2 x bytes_per_launch",
-                     "kernel": "ss_copy_kernel, " + (which or "no kernel launches in this run"),
-                     "avg_launch_ms": round(avg_launch_ms, 4), "bytes_per_launch": int(bytes_per_launch),
-                     "launches_timed": len(k_ms),
-                     "hbm": {"achieved": round(link_achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                             "frac": round(link_achieved / HBM_PEAK_GBPS, 5)}},
-    }
-    if not has_compute:
-        for k in ("noswap_ms", "overhead_vs_noswap_pct", "compute_stream_stall_ms", "floor_ms", "overhead_vs_floor_pct"):
-            line["step_time"][k] = None
-    if not args.no_cpu_baseline and args.config in (1, 2) and args.policy_mode != "generated":
-        try:
-            line["cpu_baseline"] = cpu_baseline(args.config, args.bpo)
-        except Exception as e:                              # the GPU figures above stand on their own
-            line["cpu_baseline"] = {"value": None, "unit": "GB/s", "cores": 1, "kind": "oracle",
-                                    "sample": "failed: %s: %s" % (type(e).__name__, e)}
-    print(json.dumps(line), flush=True)
+            log("sub-record %s done in %.1f s" % (name, time.perf_counter() - t0))
+        sub("config_1", lambda: measure(B, torch, np, bw, opts(config=1, steps=20, warmup=5)))
+        if "config 3" in head["config"]["workload"]:
+            sub("config_2", lambda: measure(B, torch, np, bw, opts(config=2, steps=10, warmup=3)))
+        sub("config_5", lambda: measure(B, torch, np, bw, opts(config=5, steps=3, warmup=1)))
+        sub("config_4_planning", lambda: record_config4(B, torch, np, cpu=not args.no_cpu_baseline))
+        sub("config_2_generated_policy_limit_0.95", lambda: measure(
+            B, torch, np, bw, opts(config=2, steps=10, warmup=3, policy_mode="generated", limit_frac=0.95,
+                                   timing="link-model")))
+        sub("config_2_stage_loop_limit_0.95", lambda: record_staged(B, torch, bw, 2, 0.95, 5))
+        sub("reuse_interval_config_2", lambda: record_reuse_interval(B, torch, np, bw, 2, B.SS_PATH_AUTO, B.SS_PATH_AUTO))
+        sub("hook_overhead", lambda: record_hook_overhead(B, torch, steps=10, warmup=3))
+        def compact(r):
+            """what the headline already says once (definitions, notes, the link peak) and per-iteration logs
+            are left out of the sub-records; the modes run on their own (--config N, --policy-mode staged) print them"""
+            if not isinstance(r, dict):
+                return r
+            drop = ("link_peak_measured", "value_definition", "note", "traffic_note", "launches_timed_note")
+            out = {}
+            for k, v in r.items():
+                if k in drop:
+                    continue
+                if k == "iterations":
+                    v = ([[e["stage"], round(e["ms"], 1)] for e in v] if isinstance(v, list) else
+                         {m: len(rows) for m, rows in v.items()})
+                    k = "iterations_stage_ms" if isinstance(v, list) else "iterations_planned"
+                out[k] = compact(v)
+            return out
+        subs = {k: compact(v) for k, v in subs.items()}
+        head["sub_records"] = subs
+        head["sub_records_note"] = ("measured after the headline's timed region in the same process, each with the step "
+                                    "counts its record states; whole run %.0f s" % (time.perf_counter() - t_all))
+    emit(head)
 
 
 if __name__ == "__main__":

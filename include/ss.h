@@ -449,7 +449,13 @@ typedef struct {
  * release point.  Operator phases are read from ops[].sig >> 16.
  * policy_out receives the items in the order they were committed, with t_out, t_free, t_in, t_use
  * filled (use SS_CFG_POLICY_POINTS to have ss_apply_policy keep them); in: capacity *n_policy,
- * out: count.  All arrays are host memory. */
+ * out: count.  All arrays are host memory.
+ * SS_OK does not by itself mean that the limit is kept: the simulator counts a tensor as gone from the
+ * operator after its last forward use, the release point fixed afterwards may lie later, so the scan of
+ * the finished policy (res->peak_with_policy, res->n_over_with_policy) can still show operators above
+ * the limit.  A caller that must not exceed the limit checks res->n_over_with_policy == 0 and otherwise
+ * lowers the limit, changes the parameters (ss_generate_policy_best ranks parameter sets by this count
+ * first) or tops the policy up with ss_greedy_policy(initial = the generated items). */
 int ss_generate_policy(ss_ctx *ctx, const ss_op_t *ops, uint32_t n_ops, const ss_tensor_t *tensors,
                        uint32_t n_tensors, const ss_event_t *ev, uint64_t n_ev, int64_t base, int64_t limit,
                        const ss_gen_params_t *params, ss_policy_item_t *policy_out, uint32_t *n_policy,
@@ -509,6 +515,11 @@ int ss_staging_fill(ss_ctx *ctx, int byte);
  * batch's own duration is that of its gather into / scatter out of the ring.  span_ms (nullable): first start to last end over all batches (transfers)
  * of that direction. */
 int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms, float *span_ms);
+
+/* The same for every unit of a direction in one call: ms[u] = duration of unit u, or -1 if it did not
+ * run that way in the iteration drained last (e.g. a ring group whose batches moved directly); in:
+ * capacity of ms, *n out: number of units (SS_E_CAPACITY if it exceeds the capacity). */
+int ss_batch_ms_all(ss_ctx *ctx, uint32_t dir, float *ms /* host, out */, uint32_t capacity, uint32_t *n);
 
 /* Start and end of a batch on its swap stream, in ms since the start of swap-out batch 0 of
  * the same iteration (needs SS_CFG_TIMING; all batches involved must have completed). */

@@ -33,8 +33,8 @@ def ops_tuples(ops):
 
 
 def execute_schedule(arena, staging, ap, poison=None, writes=None):
-    """Sequential reading of an action schedule on byte arrays (Sec. 5: the swap operations are
-    dispatched at their designated operators; inside one operator IN and WAIT_IN come before it,
+    """Sequential reading of an action schedule on byte arrays (Sec. 5: every swap is
+    issued at the operator its policy item fixed; inside one operator IN and WAIT_IN come before it,
     OUT and FREE after it).
 
     ap: apply_policy result.  poison: byte written over a block at its FREE action (or None).

@@ -1,7 +1,7 @@
 """Policy application, link timing, greedy policy, schedule checker (test oracle).
 
-Sec. 5 (first paragraph): the executor issues the policy's swap operations at
-their designated positions of the next iteration.  A policy item names a
+Sec. 5 (first paragraph): in the next iteration the executor issues every swap
+of the policy at the operator the policy fixed for it.  A policy item names a
 tensor (by features of its producing operator, Sec. 5.1) and three points:
 where its swap-out is issued (right after its last forward use, Sec. 4.3.2),
 where its block is released (after dispatching the operator that is running

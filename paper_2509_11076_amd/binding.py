@@ -164,6 +164,7 @@ _SIGS = {
     "ss_host_peek": [_P, C.c_uint64, C.c_uint64, C.POINTER(_P)],
     "ss_staging_fill": [_P, C.c_int],
     "ss_batch_ms": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
+    "ss_batch_ms_all": [_P, C.c_uint32, _P, C.c_uint32, C.POINTER(C.c_uint32)],
     "ss_batch_window": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
     "ss_bw_probe": [_P, C.c_uint64, C.c_uint32, C.POINTER(ss_bw_t)],
     "ss_ring_view": [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(_P), C.POINTER(_P)],
@@ -510,6 +511,14 @@ def ss_batch_ms(ctx, direction, batch=None):
     _ck(_lib.ss_batch_ms(ctx, int(direction), 0 if batch is None else int(batch),
                          C.byref(ms) if batch is not None else None, C.byref(span)), "ss_batch_ms")
     return (ms.value if batch is not None else None), span.value
+
+
+def ss_batch_ms_all(ctx, direction, capacity=65536):
+    """durations (ms) of every unit of a direction in the iteration drained last; -1 where a unit did not run"""
+    out = np.zeros(capacity, dtype=np.float32)
+    n = C.c_uint32()
+    _ck(_lib.ss_batch_ms_all(ctx, int(direction), out.ctypes.data_as(_P), capacity, C.byref(n)), "ss_batch_ms_all")
+    return out[:n.value].copy()
 
 
 def ss_batch_window(ctx, direction, batch):

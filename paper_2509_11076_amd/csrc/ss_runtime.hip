@@ -1107,6 +1107,21 @@ extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms,
   return SS_OK;
 }
 
+extern "C" int ss_batch_ms_all(ss_ctx *ctx, uint32_t dir, float *ms, uint32_t capacity, uint32_t *n) {
+  if (!ctx || dir > 3 || !n || (capacity && !ms)) return SS_E_INVAL;
+  if (!(ctx->cfg.flags & SS_CFG_TIMING) || !ctx->sched.loaded) return SS_E_STATE;
+  const size_t nb = timing_units(ctx->sched, dir);
+  *n = (uint32_t)nb;
+  if (nb > capacity) return SS_E_CAPACITY;
+  for (size_t u = 0; u < nb; ++u) {
+    hipEvent_t st, dn;
+    ms[u] = -1.f;                                   // a unit that did not run this way (see ss_batch_ms)
+    if (timing_events(ctx, dir, (uint32_t)u, &st, &dn) != SS_OK) continue;
+    SS_HIP(hipEventElapsedTime(&ms[u], st, dn));
+  }
+  return SS_OK;
+}
+
 extern "C" int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *done) {
   if (!ctx || dir > 1 || !done) return SS_E_INVAL;
   ss_sched &s = ctx->sched;

@@ -77,6 +77,11 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in):
             for g in range(len(group_bytes)):
                 assert P.ss_batch_ms(ctx, 2, g)[0] > 0
             assert P.ss_batch_ms(ctx, 2)[1] > 0 and P.ss_batch_ms(ctx, 0, 0)[0] > 0
+            # the same durations, every unit of a direction in one call
+            for dr, n_units in ((0, lib["n_out_batches"]), (1, lib["n_in_batches"]), (2, len(group_bytes))):
+                all_ms = P.ss_batch_ms_all(ctx, dr)
+                assert len(all_ms) == n_units
+                assert all_ms.tolist() == [np.float32(P.ss_batch_ms(ctx, dr, u)[0]) for u in range(n_units)]
             in_group_of, in_group_bytes = P.ss_ring_view(ctx, 1)
             if staged_in:
                 assert (in_group_of >= 0).all() and int(in_group_bytes.sum()) == int(group_bytes.sum())

@@ -389,6 +389,10 @@ def test_link_probe_and_batch_windows(P, torch):
         assert w[1][1] <= w[2][0]                                  # a swap-in starts after the swap-out it reads
         ms, span = P.ss_batch_ms(ctx, 0, 1)
         assert 0 < ms <= span
+        assert P.ss_batch_ms_all(ctx, 0).tolist() == [np.float32(P.ss_batch_ms(ctx, 0, b)[0]) for b in (0, 1)]
+        assert len(P.ss_batch_ms_all(ctx, 2)) == 0 and len(P.ss_batch_ms_all(ctx, 3)) == 0     # no ring groups
+        with pytest.raises(P.SsError):
+            P.ss_batch_ms_all(ctx, 1, capacity=1)
         with pytest.raises(P.SsError):
             P.ss_batch_window(ctx, 0, 2)
         assert torch.equal(arena, want)

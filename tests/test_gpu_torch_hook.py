@@ -16,7 +16,7 @@ def env():
     import torch
     import paper_2509_11076_amd.binding as B
     import paper_2509_11076_amd.torch_hook as H
-    from paper_2509_11076_amd.hook_overhead import Trainer
+    from workloads.torch_model import Trainer
     args = argparse.Namespace(vocab=1000, hidden=128, layers=3, heads=4, seq=64, batch=2)
     tr = Trainer(args)
     for _ in range(3):           # allocator and optimizer state settle
@@ -169,7 +169,7 @@ def test_detailed_mode_tensor_table_feeds_the_policy_generator(env):
     and events agree with each other, saved activations are found, and the policy generated from them
     equals the oracle's on the same table"""
     torch, B, H, _ = env
-    from paper_2509_11076_amd.hook_overhead import Trainer
+    from workloads.torch_model import Trainer
     # activations must outweigh parameters and gradients for swapping to lower the peak at all
     tr = Trainer(argparse.Namespace(vocab=1000, hidden=128, layers=3, heads=4, seq=256, batch=8))
     for _ in range(3):

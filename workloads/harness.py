@@ -23,7 +23,7 @@ class SwapRun:
     def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
                  copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
                  policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None, generator=None,
-                 policy_points=True, reuse_delay=0):
+                 policy_points=True, reuse_delay=0, strict_limit=False):
         from .compute import SyntheticCompute
         self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
         if trace is not None:
@@ -80,6 +80,13 @@ class SwapRun:
                 finally:
                     if gctx is not probe:
                         B.ss_destroy(gctx)
+                # the generator's simulator takes a tensor as gone right after its last forward use; the release
+                # point it fixes afterwards may come later, so a finished policy can still exceed the limit at
+                # some operators: the library says so in n_over_with_policy instead of failing
+                if strict_limit and self.generated["n_over_with_policy"]:
+                    raise RuntimeError("generated policy misses the memory limit at %d operators (peak %d > %d)"
+                                       % (self.generated["n_over_with_policy"], self.generated["peak_with_policy"],
+                                          self.budget))
             elif swap and pol is None:
                 pol, _ = B.ss_greedy_policy(probe, tr.tensors, tr.events, tr.n_ops, 0, self.budget, min_bytes)
             if not swap:
