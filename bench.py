@@ -291,10 +291,12 @@ def record_path_table(B, torch, np, bw):
             d[k] = (picks[i] * size, k * size, size, k, 0)
         start = np.array([0, len(d)], dtype=np.uint32)
         row = {"tensor_bytes": size, "tensors": len(d), "batch_bytes": int(size * len(d))}
-        for pname, pcode in (("kernel", B.SS_PATH_KERNEL), ("engine", B.SS_PATH_ENGINE)):
+        for pname, pcode, lookup in (("kernel", B.SS_PATH_KERNEL, 0), ("kernel_lds_lookup", B.SS_PATH_KERNEL, 1),
+                                     ("engine", B.SS_PATH_ENGINE, 0)):
             cfg = B.ss_config_default()
             cfg.staging_bytes = int(size * len(d))
             cfg.copy_path = cfg.copy_path_in = pcode
+            cfg.copy_desc_lookup = lookup
             cfg.flags = B.SS_CFG_TIMING
             ctx = B.ss_create(cfg)
             B.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
@@ -312,7 +314,103 @@ def record_path_table(B, torch, np, bw):
             row[pname + "_h2d_gbps"] = round(row["batch_bytes"] / (min(in_ms) * 1e-3) / 1e9, 2)
         rows.append(row)
         log(row)
-    return {"mode": "path-table", "link_peak_measured": {k: round(v, 2) for k, v in bw.items()}, "rows": rows}
+    return {"mode": "path-table", "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
+            "columns": "kernel: ss_copy_kernel with the per-chunk descriptor table (the default); kernel_lds_lookup: the "
+                       "same kernel with the batch's chunk-prefix table staged in LDS and searched per chunk; engine: one "
+                       "hipMemcpyAsync per tensor; best of three repetitions of one 1 GiB batch, GB/s",
+            "rows": rows}
+
+
+def record_mover_table(B, torch, np, bw, args):
+    """configuration 2 with every mover per direction inside the running step (copy kernel, copy engine, the
+    rings), and what each mover costs a compute stream that does not wait for it: the backward pass of the
+    no-swap step timed alone, beside copy-engine transfers, beside copy-kernel launches that saturate the
+    link, and with as many marker / wait pairs on the compute stream as the schedule has swap-in batches"""
+    from workloads.harness import SwapRun
+    rows = []
+    combos = [("kernel", "engine", {}), ("kernel", "kernel", {}), ("kernel", "kernel", dict(workgroups=16)),
+              ("engine", "engine", {}), ("engine", "kernel", {}), ("staged", "engine", {}), ("staged", "staged", {})]
+    for p_out, p_in, kw in combos:
+        o = argparse.Namespace(**vars(args))
+        o.config, o.path, o.path_in, o.calibrate, o.no_cpu_baseline = 2, p_out, p_in, 0, True
+        o.bpo = args.bpo if args.bpo > 0 else 11500000
+        o.steps, o.warmup = min(args.steps, 8), max(args.warmup, 11)      # the stage machine needs nine iterations to settle
+        for k, v in kw.items():
+            setattr(o, k, v)
+        r = measure(B, torch, np, bw, o)
+        rows.append({"swap_out": p_out, "swap_in": p_in, **kw, "ms_per_step": r["ms_per_step"],
+                     "overhead_vs_floor_out_then_in_pct": r["step_time"]["overhead_vs_floor_out_then_in_pct"],
+                     "d2h_pct_of_peak_while_copying": r["pct_of_link_peak"]["d2h_while_copying"],
+                     "h2d_pct_of_peak_while_copying": r["pct_of_link_peak"]["h2d_while_copying"],
+                     "d2h_pct_first_start_to_last_end": r["pct_of_link_peak"]["d2h_first_start_to_last_end"],
+                     "h2d_pct_first_start_to_last_end": r["pct_of_link_peak"]["h2d_first_start_to_last_end"]})
+        log("mover table: %s" % rows[-1])
+    # what a mover costs a compute stream that never waits for it
+    base = SwapRun(B, torch, 2, swap=False)
+    n = base.tr.n_ops
+    fb = list(base.tr.op_phase).index(1)
+    side = torch.cuda.Stream()
+    nbytes = 256 << 20
+    host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    dev = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    n_bg = 11                                      # background transfers of 256 MiB: about 50 ms of link traffic
+
+    def kernel_ctx():
+        from workloads.layouts import DESC_DT
+        cfg = B.ss_config_default()
+        cfg.staging_bytes = n_bg * nbytes
+        cfg.copy_path = cfg.copy_path_in = B.SS_PATH_KERNEL
+        c = B.ss_create(cfg)
+        B.ss_bind(c, dev.data_ptr(), nbytes, side.cuda_stream)       # its swap streams order after `side`, which stays empty
+        d = np.zeros(n_bg, dtype=DESC_DT)
+        for b in range(n_bg):
+            d[b] = (0, b * nbytes, nbytes, b, 0)
+        start = np.arange(n_bg + 1, dtype=np.uint32)
+        B.ss_load_schedule(c, d, start, d, start, np.arange(n_bg, dtype=np.uint32))
+        return c
+    kctx = kernel_ctx()
+
+    def backward_ms(mode, pairs=0):
+        cur = torch.cuda.current_stream()
+        e1, e2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        every = max(1, (n - fb) // pairs) if pairs else 0
+        if mode == "kernel_h2d":                   # the staging slots are filled first, outside the measurement
+            for b in range(n_bg):
+                B.ss_swap_out(kctx, b)
+            torch.cuda.synchronize()
+        for i in range(n):
+            if i == fb:
+                e1.record()
+                if mode == "engine_h2d":
+                    with torch.cuda.stream(side):
+                        for _ in range(n_bg):
+                            dev.copy_(host, non_blocking=True)
+                elif mode == "kernel_h2d":
+                    for b in range(n_bg):
+                        B.ss_swap_in(kctx, b)
+            if pairs and i >= fb and (i - fb) % every == 0:
+                m = torch.cuda.Event(); m.record(cur)
+                side.wait_event(m)
+                d = torch.cuda.Event(); d.record(side)
+                cur.wait_event(d)
+            base.compute.run_op(i)
+        e2.record()
+        torch.cuda.synchronize()
+        if mode == "kernel_h2d":
+            B.ss_sync(kctx, B.SS_SYNC_DRAIN)
+        return e1.elapsed_time(e2)
+    costs = {}
+    for label, mode, pairs in (("alone", None, 0), ("beside copy-engine transfers host to device", "engine_h2d", 0),
+                               ("beside ss_copy_kernel launches host to device (64 workgroups)", "kernel_h2d", 0),
+                               ("with 145 marker / wait pairs on the compute stream", None, 145)):
+        for _ in range(3):
+            backward_ms(mode, pairs)
+        costs[label] = round(float(np.median([backward_ms(mode, pairs) for _ in range(5)])), 2)
+        log("mover table: backward pass %s: %.2f ms" % (label, costs[label]))
+    B.ss_destroy(kctx)
+    base.close()
+    return {"mode": "mover-table", "workload": WORKLOADS[2], "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
+            "rows": rows, "noswap_backward_pass_ms": costs}
 
 
 def record_reuse_interval(B, torch, np, bw, cfgno, path, path_in):
@@ -637,6 +735,21 @@ def measure(B, torch, np, bw, o):
                 except B.SsError:                 # first unit of the direction did not run that way
                     pass
     read_events()
+    # GB/s per batch-size class (direct batches only: a batch that went through the ring is timed as its gather
+    # or scatter inside HBM), from the events of the last timed step
+    by_size = {}
+    for d, key, st_key in ((0, "descs_out", "out_start"), (1, "descs_in", "in_start")):
+        ms = B.ss_batch_ms_all(run.ctx, d)
+        starts = B.ss_schedule_view(run.ctx)[d]
+        csum = np.concatenate(([0], np.cumsum(run.last["applied"][key]["nbytes"].astype(np.int64))))
+        nb_ = csum[starts[1:]] - csum[starts[:-1]]
+        grp = B.ss_ring_view(run.ctx, d)[0]
+        for b in range(len(ms)):
+            if ms[b] <= 0 or (len(grp) and grp[b] >= 0) or starts[b + 1] == starts[b]:
+                continue
+            cls = 1 << max(0, int(nb_[b]) - 1).bit_length()           # next power of two
+            e = by_size.setdefault((d, cls), [0, 0, 0.0])
+            e[0] += 1; e[1] += int(nb_[b]); e[2] += float(ms[b])
     for _ in range(min(3, o.steps)):
         run.step()
         torch.cuda.synchronize()
@@ -769,6 +882,9 @@ def measure(B, torch, np, bw, o):
                       "overhead_vs_floor_out_then_in_pct": round(100 * (t_step / t_floor_serial - 1), 1),
                       "link_bound": bool(t_floor_serial > 1.05 * t_noswap)},
         "roofline": roof,
+        "gbps_by_batch_size": [{"direction": "out" if d == 0 else "in", "batch_bytes_up_to": cls, "batches": n,
+                                "gbps_while_running": round(tot / (ms * 1e-3) / 1e9, 2)}
+                               for (d, cls), (n, tot, ms) in sorted(by_size.items())],
     }
     if not has_compute:
         for k in ("noswap_ms", "overhead_vs_noswap_pct", "compute_stream_stall_ms", "floor_ms", "overhead_vs_floor_pct"):
@@ -827,6 +943,9 @@ def main():
     ap.add_argument("--path-table", action="store_true",
                     help="GB/s of one batch of equal-size tensors at scattered arena offsets, per size class, "
                          "copy kernel against per-tensor copy-engine calls, both directions (no compute stream work)")
+    ap.add_argument("--mover-table", action="store_true",
+                    help="configuration 2 with every mover per direction inside the step (copy kernel, copy engine, the "
+                         "HBM rings), and what each mover costs a compute stream that does not wait for it")
     ap.add_argument("--hook-overhead", action="store_true",
                     help="overhead of the dispatch hook on a real PyTorch training step: no profiling, Lightweight, "
                          "Detailed, torch.profiler (the paper's profiler-overhead table)")
@@ -863,6 +982,8 @@ def main():
         return emit(run_swap_only(B, torch, args, paths[args.path], paths[args.path_in or args.path]))
     if args.path_table:
         return emit(record_path_table(B, torch, np, bw))
+    if args.mover_table:
+        return emit(record_mover_table(B, torch, np, bw, args))
     if args.reuse_interval:
         return emit(record_reuse_interval(B, torch, np, bw, args.config or 2, paths[args.path],
                                           paths[args.path_in or args.path]))

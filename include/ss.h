@@ -159,7 +159,22 @@ typedef struct {
                                  transfers of 64-134 MB out of the ring were seen to fall to a quarter of the
                                  link rate for four transfers in a row, 252 MB and larger never)              */
   uint32_t gather_workgroups; /* SS_PATH_STAGED: grid of the gather launches, HBM to HBM (0 = 256)          */
-  uint32_t reserved;
+  uint32_t ring_taper;        /* SS_PATH_STAGED: 0 = group sizes are tapered at the ends of the iteration: the first
+                                 swap-out groups and the first swap-in groups grow from an eighth of a slot by
+                                 doubling (the first transfer leaves after a little of the forward pass instead
+                                 of a slot's worth; the backward pass resumes after the first small transfer),
+                                 and the last swap-in groups shrink (each at most half of what is still to come,
+                                 down to an eighth of a slot), so that little of the backward pass is left to
+                                 compute once the last transfer is back; a single batch is never split;
+                                 1 = every group as large as a slot allows                                   */
+  uint32_t copy_desc_lookup;  /* how a workgroup of the copy kernel finds the tensor a chunk belongs to: 0 = a
+                                 per-chunk index table in global memory (4 bytes per chunk, built when the
+                                 schedule is loaded; no search, no barrier), 1 = the batch's chunk-prefix table
+                                 staged in LDS and searched per chunk (batches of up to 8,191 tensors; longer
+                                 ones take the table).  Same bytes either way; 0 is faster on small tensors  */
+  uint32_t copy_cus;          /* 0 = the swap streams' kernels may run on every compute unit; n > 0 = only on n of
+                                 them (a compute-unit mask on those streams, spread over the dies), so that the
+                                 copy kernel's long-lived waves occupy those units and no others               */
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */
@@ -245,7 +260,8 @@ int ss_destroy(ss_ctx *ctx);
 
 /* Bind the caller's device arena [arena, arena + arena_bytes) and the compute
  * stream (a hipStream_t, e.g. torch.cuda.Stream.cuda_stream; NULL = the null
- * stream).  Every dev_off is relative to `arena`.  May be called again. */
+ * stream).  Every dev_off is relative to `arena`.  May be called again.
+ * arena = NULL with arena_bytes = 0 binds no arena: see ss_swap_out_from. */
 int ss_bind(ss_ctx *ctx, void *arena /* device */, uint64_t arena_bytes, void *compute_stream);
 
 /* ---- a1: trace record (Sec. 3) ------------------------------------------------ */
@@ -485,6 +501,19 @@ int ss_swap_out(ss_ctx *ctx, uint32_t batch);
  * here on) and for the swap-out batches it depends on, copies each tensor
  * from its staging slot into its dev_off, records the done-event. */
 int ss_swap_in(ss_ctx *ctx, uint32_t batch);
+
+/* The same two moves for tensors whose device addresses are only known when the batch is issued: blocks
+ * handed out by a framework's own allocator, as in the paper's setting, where the executor sits inside
+ * the framework's dispatch path (Sec. 5) and a swapped-in tensor lands wherever the allocator puts it.
+ * dev_src / dev_dst: host array with one device address per tensor of the batch, in the batch's descriptor
+ * order (nullable for an empty batch); each address 16-byte aligned and valid for the descriptor's nbytes.
+ * The descriptors' dev_off are replaced by these addresses for this and later iterations (relative to the
+ * bound arena; ss_bind(ctx, NULL, 0, stream) binds no arena, the offsets are then the addresses
+ * themselves, ss_load_schedule checks staging offsets only and the plain ss_swap_out / ss_swap_in refuse
+ * non-empty batches with SS_E_STATE).  Ordering, events, statistics and errors as ss_swap_out / ss_swap_in;
+ * SS_E_INVAL for a null or misaligned address or one outside a bound arena. */
+int ss_swap_out_from(ss_ctx *ctx, uint32_t batch, const void *const *dev_src /* host array of device addresses */);
+int ss_swap_in_to(ss_ctx *ctx, uint32_t batch, void *const *dev_dst /* host array of device addresses */);
 
 enum { SS_SYNC_FREE = 0,    /* id = tensor: compute stream waits (device-side) for that tensor's
                                swap-out; after this call its block may be given to later operators */

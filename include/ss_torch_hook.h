@@ -58,6 +58,22 @@ int ss_hook_remove(void);
  * nbytes = the size asked for; offsets are 0.  In: *n = capacity, out: count; SS_E_CAPACITY with
  * the needed count in *n if out is too small. */
 int ss_hook_tensor_table(ss_tensor_t *out /* host */, uint32_t *n);
+/* For an executor that runs inside the framework (Sec. 5: the swaps of a policy are issued at their
+ * operators of the running iteration; Sec. 5.1: a policy tensor is known by its producing operator and
+ * output slot).  ss_hook_current_op: the number of operators recorded so far in this iteration, i.e. the
+ * index the next dispatched operator will get.  ss_hook_block_of (Detailed mode): the tensor-table row, as
+ * filled so far, of the block of this iteration that contains device address dev_addr, and the block's
+ * start address (nullable); SS_E_INVAL if the address lies in no block allocated since
+ * ss_hook_begin_iteration (parameters, optimizer state, blocks of earlier iterations). */
+int ss_hook_current_op(uint32_t *n_ops /* host, out */);
+/* ss_hook_pause(1) ... ss_hook_pause(0) bracket work the executor does through the framework itself (views
+ * of a tensor it keeps, the block it asks the allocator for): operators dispatched in between are not
+ * recorded, so that the model's operators keep the indices the policy was made for, and blocks allocated in
+ * between get out_slot SS_NONE_OP and leave the running operator's slot count alone (their alloc / free
+ * events are recorded as usual).  Nests; SS_E_STATE on a resume without a pause. */
+int ss_hook_pause(int on);
+int ss_hook_block_of(const void *dev_addr /* device address, not dereferenced */, ss_tensor_t *row /* host, out */,
+                     uint64_t *block_addr /* host, out, nullable */);
 int ss_hook_get_stats(ss_hook_stats_t *out /* host, out */);
 
 #ifdef __cplusplus

@@ -59,7 +59,8 @@ class ss_config_t(C.Structure):
                 ("flags", C.c_uint32), ("engine_min_bytes_out", C.c_uint64),
                 ("out_streams", C.c_uint32), ("in_streams", C.c_uint32),
                 ("ring_bytes", C.c_uint64), ("ring_slot_bytes", C.c_uint64),
-                ("gather_workgroups", C.c_uint32), ("reserved", C.c_uint32)]
+                ("gather_workgroups", C.c_uint32), ("ring_taper", C.c_uint32),
+                ("copy_desc_lookup", C.c_uint32), ("copy_cus", C.c_uint32)]
 
 
 class ss_scan_result_t(C.Structure):
@@ -161,6 +162,8 @@ _SIGS = {
     "ss_swap_in": [_P, C.c_uint32],
     "ss_sync": [_P, C.c_uint32, C.c_uint32],
     "ss_dispatch": [_P, C.c_uint32, C.c_uint32],
+    "ss_swap_out_from": [_P, C.c_uint32, _P],
+    "ss_swap_in_to": [_P, C.c_uint32, _P],
     "ss_host_peek": [_P, C.c_uint64, C.c_uint64, C.POINTER(_P)],
     "ss_staging_fill": [_P, C.c_int],
     "ss_batch_ms": [_P, C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
@@ -229,7 +232,7 @@ def ss_destroy(ctx):
 
 
 def ss_bind(ctx, arena_ptr, arena_bytes, compute_stream):
-    _ck(_lib.ss_bind(ctx, _P(int(arena_ptr)), int(arena_bytes), _P(int(compute_stream or 0))), "ss_bind")
+    _ck(_lib.ss_bind(ctx, _P(int(arena_ptr or 0)), int(arena_bytes), _P(int(compute_stream or 0))), "ss_bind")
 
 
 def ss_intern_op(ctx, name, stack, dtype, n_out, phase):
@@ -481,6 +484,23 @@ def ss_swap_out(ctx, batch):
 
 def ss_swap_in(ctx, batch):
     _ck(_lib.ss_swap_in(ctx, int(batch)), "ss_swap_in")
+
+
+def _addr_array(addrs):
+    a = np.ascontiguousarray(addrs, dtype=np.uint64)
+    return a, (a.ctypes.data_as(_P) if len(a) else None)
+
+
+def ss_swap_out_from(ctx, batch, dev_src):
+    """dev_src: one device address per tensor of the batch"""
+    keep, p = _addr_array(dev_src)
+    _ck(_lib.ss_swap_out_from(ctx, int(batch), p), "ss_swap_out_from")
+
+
+def ss_swap_in_to(ctx, batch, dev_dst):
+    """dev_dst: one device address per tensor of the batch"""
+    keep, p = _addr_array(dev_dst)
+    _ck(_lib.ss_swap_in_to(ctx, int(batch), p), "ss_swap_in_to")
 
 
 def ss_sync(ctx, what, ident=0):

@@ -10,7 +10,11 @@
 // persistent grid walks the chunks, and each workgroup looks its chunk's
 // descriptor up in a per-chunk table built when the schedule is loaded (two
 // dependent loads per chunk, no search, no LDS), and the loads of one block are
-// issued before the stores of the block before it (software pipelining).  All
+// issued before the stores of the block before it (software pipelining).  A
+// second form of the kernel keeps the batch's chunk-prefix table in LDS and
+// searches it per chunk instead (copy_desc_lookup = 1): it exists so that the
+// two can be measured against each other; the per-chunk table is the default
+// because it is faster on small tensors and never slower.  All
 // traffic is 16 bytes per lane, a wavefront touching 1 KiB of consecutive
 // addresses on both sides; a byte tail handles sizes that are not multiples of
 // 16.  The staging area is host memory mapped into the device address space,
@@ -36,11 +40,15 @@ struct CopyBlock {
 
 // Walks the blocks one workgroup is responsible for: chunks blockIdx.x, blockIdx.x + gridDim.x, ...,
 // each chunk cut into blocks of SS_COPY_THREADS * kUnroll vectors.
-template <bool TO_HOST, uint32_t kUnroll>
+constexpr uint32_t kLdsPrefixMax = 8192;       // entries of the chunk-prefix table an LDS-lookup launch can hold (32 KiB)
+
+template <bool TO_HOST, uint32_t kUnroll, bool LDS_LOOKUP>
 struct BlockWalk {
   uint8_t *arena, *staging;
   const ss_desc_t *descs;
   const uint32_t *chunk0, *chunk_desc;
+  const uint32_t *lds_prefix;   // LDS_LOOKUP: chunk0[0 .. n_desc] staged in LDS
+  uint32_t n_desc;
   uint32_t n_chunks, chunk_shift;
   uint32_t c;          // current chunk
   uint32_t done16;     // vectors of the current chunk already handed out
@@ -52,9 +60,23 @@ struct BlockWalk {
   __device__ bool open_chunk() {
     if (c >= n_chunks) return false;
     // chunk_desc[c]: the descriptor chunk c belongs to; chunk0[d]: first chunk of descriptor d
-    const uint32_t lo = chunk_desc[c];
+    uint32_t lo, first;
+    if (LDS_LOOKUP) {
+      // the last descriptor whose first chunk is <= c (descriptors without bytes share their successor's
+      // first chunk and are skipped by taking the last)
+      uint32_t a = 0, b = n_desc;                 // invariant: prefix[a] <= c < prefix[b]
+      while (b - a > 1) {
+        const uint32_t m = (a + b) >> 1;
+        if (lds_prefix[m] <= c) a = m; else b = m;
+      }
+      lo = a;
+      first = lds_prefix[a];
+    } else {
+      lo = chunk_desc[c];
+      first = chunk0[lo];
+    }
     const ss_desc_t d = descs[lo];
-    const uint64_t off = (uint64_t)(c - chunk0[lo]) << chunk_shift;
+    const uint64_t off = (uint64_t)(c - first) << chunk_shift;
     const uint64_t left = d.nbytes - off;
     const uint32_t n = left < (1ull << chunk_shift) ? (uint32_t)left : (1u << chunk_shift);
     src = TO_HOST ? arena + d.dev_off + off : staging + d.host_off + off;
@@ -87,14 +109,20 @@ struct BlockWalk {
 // current one, so that each lane keeps requests on the host link in flight all the time (the link is a
 // long pipe: what saturates it is bytes in flight, and with this a dozen workgroups hold as many as
 // sixty-four did when loads and stores took turns).
-template <bool TO_HOST, uint32_t kUnroll>
+template <bool TO_HOST, uint32_t kUnroll, bool LDS_LOOKUP>
 __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
     uint8_t *__restrict__ arena, uint8_t *__restrict__ staging, const ss_desc_t *__restrict__ descs,
     const uint32_t *__restrict__ chunk0, const uint32_t *__restrict__ chunk_desc, uint32_t n_chunks,
-    uint32_t chunk_shift) {
+    uint32_t chunk_shift, uint32_t n_desc) {
   const uint32_t tid = threadIdx.x;
-  BlockWalk<TO_HOST, kUnroll> w;
+  __shared__ uint32_t prefix[LDS_LOOKUP ? kLdsPrefixMax : 1];
+  if (LDS_LOOKUP) {                               // n_desc + 1 <= kLdsPrefixMax is the launcher's business
+    for (uint32_t i = tid; i <= n_desc; i += SS_COPY_THREADS) prefix[i] = chunk0[i];
+    __syncthreads();
+  }
+  BlockWalk<TO_HOST, kUnroll, LDS_LOOKUP> w;
   w.arena = arena; w.staging = staging; w.descs = descs; w.chunk0 = chunk0; w.chunk_desc = chunk_desc;
+  w.lds_prefix = prefix; w.n_desc = n_desc;
   w.n_chunks = n_chunks; w.chunk_shift = chunk_shift;
   w.c = blockIdx.x;
   if (!w.open_chunk()) return;
@@ -147,12 +175,22 @@ __global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nby
 
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
                     uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,
-                    const uint32_t *d_chunk_desc, uint32_t n_chunks, uint32_t chunk_shift) {
+                    const uint32_t *d_chunk_desc, uint32_t n_chunks, uint32_t chunk_shift, uint32_t n_desc,
+                    bool lds_lookup) {
   if (n_chunks == 0) return;
   const dim3 grid(workgroups < n_chunks ? workgroups : n_chunks), block(SS_COPY_THREADS);
+  if (lds_lookup && n_desc != 0 && n_desc + 1 <= kLdsPrefixMax) {      // a batch too long for LDS takes the table
+    if (to_host)
+      hipLaunchKernelGGL((ss_copy_kernel<true, 8, true>), grid, block, 0, s, arena, staging, d_descs, d_chunk0,
+                         d_chunk_desc, n_chunks, chunk_shift, n_desc);
+    else
+      hipLaunchKernelGGL((ss_copy_kernel<false, 8, true>), grid, block, 0, s, arena, staging, d_descs, d_chunk0,
+                         d_chunk_desc, n_chunks, chunk_shift, n_desc);
+    return;
+  }
 #define SS_LAUNCH(TH, U)                                                                                  \
-  hipLaunchKernelGGL((ss_copy_kernel<TH, U>), grid, block, 0, s, arena, staging, d_descs, d_chunk0,        \
-                     d_chunk_desc, n_chunks, chunk_shift)
+  hipLaunchKernelGGL((ss_copy_kernel<TH, U, false>), grid, block, 0, s, arena, staging, d_descs, d_chunk0, \
+                     d_chunk_desc, n_chunks, chunk_shift, n_desc)
   if (to_host) {
     if (unroll <= 2) SS_LAUNCH(true, 2); else if (unroll <= 4) SS_LAUNCH(true, 4); else SS_LAUNCH(true, 8);
   } else {

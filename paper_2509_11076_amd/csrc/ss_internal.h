@@ -78,6 +78,8 @@ struct ss_sched {
   int phase = 0;                                    // event set of the iteration being issued
   bool drained_once = false;                        // set `phase ^ 1` holds a completed iteration
   ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
+  ss_desc_t *pin_out = nullptr, *pin_in = nullptr; // pinned host mirrors (source of the refresh when addresses arrive late)
+  size_t pin_cap_out = 0, pin_cap_in = 0;
   uint32_t *d_out_chunk0 = nullptr, *d_in_chunk0 = nullptr;
   uint32_t *d_out_cdesc = nullptr, *d_in_cdesc = nullptr;
   size_t d_cap_out = 0, d_cap_in = 0, d_ccap_out = 0, d_ccap_in = 0;
@@ -172,7 +174,8 @@ constexpr uint32_t SS_CHUNK_BYTES = 1u << SS_CHUNK_SHIFT;   // 64 KiB; small bat
 constexpr uint32_t SS_COPY_THREADS = 256;
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
                     uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,
-                    const uint32_t *d_chunk_desc, uint32_t n_chunks, uint32_t chunk_shift);
+                    const uint32_t *d_chunk_desc, uint32_t n_chunks, uint32_t chunk_shift, uint32_t n_desc,
+                    bool lds_lookup);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
 
 // sequence aligner (ss_align.hip): ref_to_cur has n entries

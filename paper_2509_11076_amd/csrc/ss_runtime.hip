@@ -82,7 +82,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (cfg.ring_slot_bytes == 0) cfg.ring_slot_bytes = 256ull << 20;
     if (cfg.ring_bytes == 0) cfg.ring_bytes = 1024ull << 20;
     if (cfg.gather_workgroups == 0) cfg.gather_workgroups = 256;
-    if (cfg.gather_workgroups > 4096) return SS_E_INVAL;
+    if (cfg.gather_workgroups > 4096 || cfg.ring_taper > 1 || cfg.copy_desc_lookup > 1) return SS_E_INVAL;
     if ((cfg.copy_path == SS_PATH_STAGED || cfg.copy_path_in == SS_PATH_STAGED) &&
         ((cfg.ring_slot_bytes & 255u) || cfg.ring_slot_bytes < 4096 || cfg.ring_bytes / cfg.ring_slot_bytes < 2 ||
          cfg.ring_bytes / cfg.ring_slot_bytes > 64))
@@ -124,10 +124,29 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     const bool any_staged = cfg.copy_path == SS_PATH_STAGED || cfg.copy_path_in == SS_PATH_STAGED;
     ctx->n_s_out = any_staged ? 1 : cfg.out_streams;
     ctx->n_s_in = any_staged ? 1 : cfg.in_streams;
+    // With copy_cus > 0 the swap streams may place their kernels only on that many compute units (bit i of the
+    // mask is compute unit i / n_xcd of die i % n_xcd on this part, so the first bits spread over the dies):
+    // the copy kernel's long-lived waves then keep the compute stream's workgroups off those units only.
+    // Streams with a unit mask are created non-blocking at the default priority like the others.
+    std::vector<uint32_t> cu_mask;
+    if (cfg.copy_cus) {
+      hipDeviceProp_t prop;
+      if ((e = hipGetDeviceProperties(&prop, ctx->device)) != hipSuccess) fail(SS_E_HIP, e);
+      else {
+        const uint32_t n_cu = (uint32_t)prop.multiProcessorCount;
+        if (cfg.copy_cus > n_cu) rc = SS_E_INVAL;
+        cu_mask.assign((n_cu + 31) / 32, 0u);
+        for (uint32_t i = 0; i < cfg.copy_cus && rc == SS_OK; ++i) cu_mask[i / 32] |= 1u << (i % 32);
+      }
+    }
+    auto make_stream = [&](hipStream_t *st) {
+      if (cu_mask.empty()) return hipStreamCreateWithFlags(st, hipStreamNonBlocking);
+      return hipExtStreamCreateWithCUMask(st, (uint32_t)cu_mask.size(), cu_mask.data());
+    };
     for (uint32_t i = 0; i < ctx->n_s_out && rc == SS_OK; ++i)
-      if ((e = hipStreamCreateWithFlags(&ctx->s_out[i], hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+      if ((e = make_stream(&ctx->s_out[i])) != hipSuccess) fail(SS_E_HIP, e);
     for (uint32_t i = 0; i < ctx->n_s_in && rc == SS_OK; ++i)
-      if ((e = hipStreamCreateWithFlags(&ctx->s_in[i], hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+      if ((e = make_stream(&ctx->s_in[i])) != hipSuccess) fail(SS_E_HIP, e);
     // The trace kernels (scan, match, align) run on the first swap-in stream: it is idle between iterations,
     // when they are called, and every further stream of the process has to share one of the few hardware
     // queues (4 per process here) with another - a stream that shares its queue with the stream of the
@@ -191,6 +210,10 @@ static void sched_release(ss_sched &s) {
   free_events(s.ev_wait_at);
   if (s.d_out) (void)hipFree(s.d_out);
   if (s.d_in) (void)hipFree(s.d_in);
+  if (s.pin_out) (void)hipHostFree(s.pin_out);
+  if (s.pin_in) (void)hipHostFree(s.pin_in);
+  s.pin_out = s.pin_in = nullptr;
+  s.pin_cap_out = s.pin_cap_in = 0;
   if (s.d_out_chunk0) (void)hipFree(s.d_out_chunk0);
   if (s.d_in_chunk0) (void)hipFree(s.d_in_chunk0);
   if (s.d_out_cdesc) (void)hipFree(s.d_out_cdesc);
@@ -225,6 +248,8 @@ extern "C" int ss_destroy(ss_ctx *ctx) {
 }
 
 extern "C" int ss_bind(ss_ctx *ctx, void *arena, uint64_t arena_bytes, void *compute_stream) {
+  // arena == NULL with arena_bytes == 0: no arena; every tensor's device address is given when its batch is
+  // issued (ss_swap_out_from / ss_swap_in_to)
   if (!ctx || (!arena && arena_bytes) || ((uintptr_t)arena & 15u)) return SS_E_INVAL;
   ctx->arena = (uint8_t *)arena;
   ctx->arena_bytes = arena_bytes;
@@ -286,9 +311,10 @@ static void ring_reset(ss_sched &s, uint32_t n_slots) {
 }
 
 static int check_descs(const ss_ctx *ctx, const ss_desc_t *d, uint32_t n) {
+  const bool no_arena = ctx->arena == nullptr;        // addresses come with the batches: nothing to check them against
   for (uint32_t i = 0; i < n; ++i) {
     if ((d[i].dev_off & 15u) || (d[i].host_off & 15u)) return SS_E_INVAL;
-    if (d[i].dev_off > ctx->arena_bytes || d[i].nbytes > ctx->arena_bytes - d[i].dev_off) return SS_E_INVAL;
+    if (!no_arena && (d[i].dev_off > ctx->arena_bytes || d[i].nbytes > ctx->arena_bytes - d[i].dev_off)) return SS_E_INVAL;
     if (d[i].host_off > ctx->cfg.staging_bytes || d[i].nbytes > ctx->cfg.staging_bytes - d[i].host_off)
       return SS_E_NOMEM;
     if (d[i].nbytes > (1ull << 40)) return SS_E_INVAL;
@@ -441,8 +467,19 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     s.group_bytes.clear();
     s.group_of.assign(n_out_batches, -1);
     s.prev_direct.assign(n_out_batches, -1);
+    // Group sizes are tapered at the two ends of the iteration where the link would otherwise wait for a
+    // full slot: the first swap-out groups double from kTaperMin up to a slot (a group leaves only once it is
+    // complete, so the link starts after the first small group instead of after a slot's worth of forward
+    // pass), the first swap-in groups double likewise (the backward pass goes on as soon as the first small
+    // group is back instead of after a whole slot), and the last swap-in groups halve down to kTaperMin (what
+    // the backward pass still has to compute once the last byte is back shrinks with the last group).
+    // kTaperMin is an eighth of a slot.
+    const uint64_t kTaperMin = std::max<uint64_t>(ctx->cfg.ring_slot_bytes / 8, 256);
+    const bool taper_in = ctx->cfg.ring_taper == 0, taper_out = taper_in;
     if (ctx->cfg.copy_path == SS_PATH_STAGED && ctx->ring) {
-      const uint64_t slot = ctx->cfg.ring_slot_bytes;
+      const uint64_t slot_full = ctx->cfg.ring_slot_bytes;
+      uint64_t grouped = 0;                       // bytes in the groups closed so far
+      uint64_t slot = taper_out ? std::min(slot_full, kTaperMin) : slot_full;
       bool open = false;
       for (uint32_t b = 0; b < n_out_batches; ++b) {
         const uint32_t lo = s.out_start[b], hi = s.out_start[b + 1];
@@ -453,7 +490,7 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
                (i == lo || s.out[i].host_off == s.out[i - 1].host_off + s.out[i - 1].nbytes);
           total += s.out[i].nbytes;
         }
-        ok = ok && total <= slot;
+        ok = ok && total <= slot_full;
         if (!ok) { open = false; continue; }
         if (open) {
           ss_sched::out_group &g = s.groups.back();
@@ -463,6 +500,8 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
             s.group_of[b] = (int32_t)s.groups.size() - 1;
             continue;
           }
+          grouped += g.bytes;
+          if (taper_out) slot = std::min(slot_full, std::max(kTaperMin, grouped));
         }
         s.groups.push_back(ss_sched::out_group{b, b, s.out[lo].host_off, total});
         s.group_of[b] = (int32_t)s.groups.size() - 1;
@@ -477,8 +516,13 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     s.in_group_outs.clear();
     s.in_group_of.assign(n_in_batches, -1);
     if (ctx->cfg.copy_path_in == SS_PATH_STAGED && ctx->ring_in && ctx->cfg.guard_bytes == 0) {
-      const uint64_t slot = ctx->cfg.ring_slot_bytes;
+      const uint64_t slot_full = ctx->cfg.ring_slot_bytes;
+      uint64_t in_grouped = 0;                    // bytes in the groups made so far
+      uint64_t remaining = 0;                     // bytes of the batches from f on
+      for (uint32_t i = 0; i < n_in; ++i) remaining += s.in[i].nbytes;
       for (uint32_t f = 0; f < n_in_batches;) {
+        const uint64_t slot = taper_in ? std::min(slot_full, std::min(std::max(kTaperMin, remaining / 2),
+                                                                      std::max(kTaperMin, in_grouped))) : slot_full;
         uint64_t lo_off = ~0ull, hi_off = 0, total = 0;
         int64_t best = -1;
         uint64_t best_lo = 0, best_total = 0;
@@ -490,10 +534,16 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
             hi_off = std::max(hi_off, s.in[i].host_off + s.in[i].nbytes);
             total += s.in[i].nbytes;
           }
-          if (!ok || total > slot) break;
+          if (!ok || total > (e == f ? slot_full : slot)) break;      // a single batch may fill a whole slot
           if (hi_off - lo_off == total) { best = e; best_lo = lo_off; best_total = total; }
         }
-        if (best < 0) { ++f; continue; }
+        if (best < 0) {
+          for (uint32_t i = s.in_start[f]; i < s.in_start[f + 1]; ++i) remaining -= s.in[i].nbytes;
+          ++f;
+          continue;
+        }
+        remaining -= best_total;
+        in_grouped += best_total;
         const int32_t g = (int32_t)s.in_groups.size();
         s.in_groups.push_back(ss_sched::in_group{f, (uint32_t)best, best_lo, best_total});
         s.in_group_bytes.push_back(best_total);
@@ -590,6 +640,26 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     };
     if ((rc = upload(s.out, s.out_chunk0, s.d_out, s.d_out_chunk0, s.d_cap_out)) != SS_OK) return rc;
     if ((rc = upload(s.in, s.in_chunk0, s.d_in, s.d_in_chunk0, s.d_cap_in)) != SS_OK) return rc;
+    // pinned mirrors of the descriptors, for batches whose addresses arrive when they are issued
+    auto mirror = [&](const std::vector<ss_desc_t> &d, ss_desc_t *&pin, size_t &cap) -> int {
+      if (d.size() > cap) {
+        if (pin) SS_HIP(hipHostFree(pin));
+        pin = nullptr; cap = 0;
+        const size_t want = d.size() + d.size() / 2 + 64;
+        hipError_t e = hipHostMalloc((void **)&pin, want * sizeof(ss_desc_t), hipHostMallocDefault);
+        if (e != hipSuccess) {
+          ctx->stats.last_hip_error = (int32_t)e;
+          ss_note_hip_error((int)e, __FILE__, __LINE__);
+          (void)hipGetLastError();
+          return SS_E_NOMEM;
+        }
+        cap = want;
+      }
+      if (!d.empty()) std::memcpy(pin, d.data(), d.size() * sizeof(ss_desc_t));
+      return SS_OK;
+    };
+    if ((rc = mirror(s.out, s.pin_out, s.pin_cap_out)) != SS_OK) return rc;
+    if ((rc = mirror(s.in, s.pin_in, s.pin_cap_in)) != SS_OK) return rc;
     auto upload_map = [&](const std::vector<uint32_t> &m, uint32_t *&dm, size_t &cap) -> int {
       if (m.empty()) return SS_OK;
       if (m.size() > cap) {
@@ -748,7 +818,7 @@ static int swap_out_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
   const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
   const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
   ss_launch_copy(so, ctx->cfg.gather_workgroups, ctx->cfg.copy_unroll, true, ctx->arena, base, s.d_out + lo, c0,
-                 s.d_out_cdesc + s.out_cbase[batch], n_chunks, s.out_shift[batch]);
+                 s.d_out_cdesc + s.out_cbase[batch], n_chunks, s.out_shift[batch], hi - lo, ctx->cfg.copy_desc_lookup == 1);
   SS_HIP(hipGetLastError());
   SS_HIP(hipEventRecord(s.ev_gathered[s.phase][batch], so));
   s.out_issued[batch] = 1;
@@ -767,8 +837,67 @@ static int swap_out_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
   return 1;
 }
 
+static int swap_out_batch(ss_ctx *ctx, uint32_t batch);
+static int swap_in_batch(ss_ctx *ctx, uint32_t batch);
+
 extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
   if (!ctx) return SS_E_INVAL;
+  if (ctx->bound && !ctx->arena && batch + 1 < ctx->sched.out_start.size() &&
+      ctx->sched.out_start[batch + 1] > ctx->sched.out_start[batch])
+    return SS_E_STATE;                              // no arena bound: the addresses must come with the call
+  return swap_out_batch(ctx, batch);
+}
+
+// Device addresses given at issue time.  The batch's descriptors take the addresses (as offsets from the
+// arena base, which is 0 when no arena is bound); a batch that the copy kernel moves reads its descriptors
+// from device memory, so the device copy is refreshed from a pinned mirror, on the stream the kernel runs
+// on and ahead of it.
+static int patch_addresses(ss_ctx *ctx, bool out, uint32_t batch, const void *const *dev) {
+  ss_sched &s = ctx->sched;
+  std::vector<ss_desc_t> &d = out ? s.out : s.in;
+  const std::vector<uint32_t> &start = out ? s.out_start : s.in_start;
+  if (batch + 1 >= start.size()) return SS_E_INVAL;
+  const uint32_t lo = start[batch], hi = start[batch + 1];
+  if (hi > lo && !dev) return SS_E_INVAL;
+  if (out ? s.out_issued[batch] : s.in_issued[batch]) return SS_E_STATE;
+  for (uint32_t i = lo; i < hi; ++i) {
+    const uintptr_t a = (uintptr_t)dev[i - lo], base = (uintptr_t)ctx->arena;
+    if (!a || (a & 15u) || a < base) return SS_E_INVAL;
+    if (ctx->arena && (a - base > ctx->arena_bytes || d[i].nbytes > ctx->arena_bytes - (a - base))) return SS_E_INVAL;
+  }
+  if (hi == lo) return SS_OK;
+  ss_desc_t *pin = out ? s.pin_out : s.pin_in;
+  ss_desc_t *dd = out ? s.d_out : s.d_in;
+  if (!pin || !dd) return SS_E_STATE;
+  for (uint32_t i = lo; i < hi; ++i) {
+    d[i].dev_off = (uint64_t)((uintptr_t)dev[i - lo] - (uintptr_t)ctx->arena);
+    pin[i] = d[i];
+  }
+  const bool engine = out ? use_engine(ctx, ctx->cfg.copy_path, true, s.out, lo, hi) && s.group_of[batch] < 0
+                          : use_engine(ctx, ctx->cfg.copy_path_in, false, s.in, lo, hi) && s.in_group_of[batch] < 0;
+  if (!engine) {
+    hipStream_t st = out ? ctx->s_out[s.group_of[batch] >= 0 ? 0 : batch % ctx->n_s_out]
+                         : ctx->s_in[s.in_group_of[batch] >= 0 ? 0 : batch % ctx->n_s_in];
+    SS_HIP(hipMemcpyAsync(dd + lo, pin + lo, (size_t)(hi - lo) * sizeof(ss_desc_t), hipMemcpyHostToDevice, st));
+  }
+  return SS_OK;
+}
+
+extern "C" int ss_swap_out_from(ss_ctx *ctx, uint32_t batch, const void *const *dev_src) {
+  if (!ctx) return SS_E_INVAL;
+  if (!ctx->sched.loaded || !ctx->bound) return SS_E_STATE;
+  const int rc = patch_addresses(ctx, true, batch, dev_src);
+  return rc != SS_OK ? rc : swap_out_batch(ctx, batch);
+}
+
+extern "C" int ss_swap_in_to(ss_ctx *ctx, uint32_t batch, void *const *dev_dst) {
+  if (!ctx) return SS_E_INVAL;
+  if (!ctx->sched.loaded || !ctx->bound) return SS_E_STATE;
+  const int rc = patch_addresses(ctx, false, batch, dev_dst);
+  return rc != SS_OK ? rc : swap_in_batch(ctx, batch);
+}
+
+static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
   ss_sched &s = ctx->sched;
   if (!s.loaded || !ctx->bound) return SS_E_STATE;
   if (batch + 1 >= s.out_start.size()) return SS_E_INVAL;
@@ -806,7 +935,7 @@ extern "C" int ss_swap_out(ss_ctx *ctx, uint32_t batch) {
     const uint32_t *c0 = s.d_out_chunk0 + lo + batch;
     const uint32_t n_chunks = s.out_chunk0[(size_t)hi + batch];
     ss_launch_copy(so, ctx->cfg.copy_workgroups_out, ctx->cfg.copy_unroll, true, ctx->arena, ctx->staging_dev, s.d_out + lo, c0,
-                   s.d_out_cdesc + s.out_cbase[batch], n_chunks, s.out_shift[batch]);
+                   s.d_out_cdesc + s.out_cbase[batch], n_chunks, s.out_shift[batch], hi - lo, ctx->cfg.copy_desc_lookup == 1);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
@@ -865,7 +994,7 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
   const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
   const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
   ss_launch_copy(si, ctx->cfg.gather_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, base, s.d_in + lo, c0,
-                 s.d_in_cdesc + s.in_cbase[batch], n_chunks, s.in_shift[batch]);
+                 s.d_in_cdesc + s.in_cbase[batch], n_chunks, s.in_shift[batch], hi - lo, ctx->cfg.copy_desc_lookup == 1);
   SS_HIP(hipGetLastError());
   SS_HIP(hipEventRecord(s.ev_in_done[s.phase][batch], si));
   s.in_issued[batch] = 1;
@@ -877,6 +1006,13 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
 
 extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
   if (!ctx) return SS_E_INVAL;
+  if (ctx->bound && !ctx->arena && batch + 1 < ctx->sched.in_start.size() &&
+      ctx->sched.in_start[batch + 1] > ctx->sched.in_start[batch])
+    return SS_E_STATE;                              // no arena bound: the addresses must come with the call
+  return swap_in_batch(ctx, batch);
+}
+
+static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
   ss_sched &s = ctx->sched;
   if (!s.loaded || !ctx->bound) return SS_E_STATE;
   if (batch + 1 >= s.in_start.size()) return SS_E_INVAL;
@@ -933,7 +1069,7 @@ extern "C" int ss_swap_in(ss_ctx *ctx, uint32_t batch) {
     const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
     const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
     ss_launch_copy(si, ctx->cfg.copy_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, ctx->staging_dev, s.d_in + lo, c0,
-                   s.d_in_cdesc + s.in_cbase[batch], n_chunks, s.in_shift[batch]);
+                   s.d_in_cdesc + s.in_cbase[batch], n_chunks, s.in_shift[batch], hi - lo, ctx->cfg.copy_desc_lookup == 1);
     SS_HIP(hipGetLastError());
     ctx->stats.kernel_batches++;
   }
@@ -1253,7 +1389,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
         if (d2h) {
           ck(hipEventRecord(a0, ctx->s_out[0]));
           if (mode == 3 || mode == 5) {
-            ss_launch_copy(ctx->s_out[0], wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
+            ss_launch_copy(ctx->s_out[0], wgo, ctx->cfg.copy_unroll, true, d0, h0d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT, 1, false);
             ck(hipGetLastError());
           } else ck(hipMemcpyAsync(h0, d0, bytes, hipMemcpyDeviceToHost, ctx->s_out[0]));
           ck(hipEventRecord(a1, ctx->s_out[0]));
@@ -1261,7 +1397,7 @@ extern "C" int ss_bw_probe(ss_ctx *ctx, uint64_t bytes, uint32_t reps, ss_bw_t *
         if (h2d) {
           ck(hipEventRecord(b0, ctx->s_in[0]));
           if (mode == 4 || mode == 5) {
-            ss_launch_copy(ctx->s_in[0], wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT);
+            ss_launch_copy(ctx->s_in[0], wg, ctx->cfg.copy_unroll, false, d1, h1d, dd, dc, dm, nchunks, SS_CHUNK_SHIFT, 1, false);
             ck(hipGetLastError());
           } else ck(hipMemcpyAsync(d1, h1, bytes, hipMemcpyHostToDevice, ctx->s_in[0]));
           ck(hipEventRecord(b1, ctx->s_in[0]));

@@ -30,6 +30,7 @@ struct Hook {
   ss_ctx *ctx = nullptr;
   std::atomic<int> mode{SS_HOOK_OFF};
   std::atomic<uint32_t> phase{0};             // set by the training loop: 0 forward, 1 backward, 2 optimizer
+  std::atomic<int> paused{0};                 // > 0: operators dispatched now are the executor's own, not the model's
   bool have_cb = false, have_tracker = false;
   at::CallbackHandle handle = 0;
   // operator name -> interned record, keyed by a 64-bit hash of the characters and verified by
@@ -101,7 +102,7 @@ uint32_t dtype_code(const at::Tensor &t) {
 
 std::unique_ptr<at::ObserverContext> on_start(const at::RecordFunction &fn) {
   const int mode = g.mode.load(std::memory_order_relaxed);
-  if (mode == SS_HOOK_OFF) return nullptr;
+  if (mode == SS_HOOK_OFF || g.paused.load(std::memory_order_relaxed) > 0) return nullptr;
   const uint32_t stack_hash = mode == SS_HOOK_DETAILED ? python_stack_hash() : 0u;
   std::lock_guard<std::mutex> lock(g.mu);
   if (!g.ctx) return nullptr;
@@ -198,7 +199,9 @@ void on_allocator(const c10::hip::HIPCachingAllocator::TraceEntry &e) {
       ss_trace_view(g.ctx, &ops, nullptr, nullptr, nullptr, nullptr);
       const bool fwd = (ops[op].sig >> 16) == 0;
       ss_tensor_t row{};
-      row.tensor_id = id; row.producer_op = op; row.out_slot = g.slot_next++; row.alloc_op = op;
+      // a block the executor itself asks for (a swapped tensor's new place) is nobody's output slot
+      const bool own = g.paused.load(std::memory_order_relaxed) > 0;
+      row.tensor_id = id; row.producer_op = op; row.out_slot = own ? SS_NONE_OP : g.slot_next++; row.alloc_op = op;
       row.last_fwd_use = fwd ? op : SS_NONE_OP; row.first_bwd_use = SS_NONE_OP; row.free_op = SS_NONE_OP;
       row.nbytes = (uint64_t)e.size_;
       g.by_addr[(uint64_t)e.addr_] = (uint32_t)g.table.size();
@@ -325,6 +328,34 @@ extern "C" int ss_hook_tensor_table(ss_tensor_t *out, uint32_t *n) {
     if (out[i].free_op == SS_NONE_OP && n_ops) out[i].free_op = n_ops - 1;   // still held when the iteration ends
   }
   *n = have;
+  return SS_OK;
+}
+
+extern "C" int ss_hook_pause(int on) {
+  if (on) g.paused.fetch_add(1);
+  else if (g.paused.load() > 0) g.paused.fetch_sub(1);
+  else return SS_E_STATE;
+  return SS_OK;
+}
+
+extern "C" int ss_hook_current_op(uint32_t *n_ops) {
+  if (!n_ops) return SS_E_INVAL;
+  std::lock_guard<std::mutex> lock(g.mu);
+  if (!g.ctx) return SS_E_STATE;
+  return ss_trace_view(g.ctx, nullptr, n_ops, nullptr, nullptr, nullptr);
+}
+
+extern "C" int ss_hook_block_of(const void *dev_addr, ss_tensor_t *row, uint64_t *block_addr) {
+  if (!dev_addr || !row) return SS_E_INVAL;
+  std::lock_guard<std::mutex> lock(g.mu);
+  if (!g.ctx) return SS_E_STATE;
+  const uint64_t p = (uint64_t)(uintptr_t)dev_addr;
+  auto it = g.by_addr.upper_bound(p);
+  if (it == g.by_addr.begin()) return SS_E_INVAL;
+  --it;
+  if (p >= it->first + g.table[it->second].nbytes) return SS_E_INVAL;    // not inside a block of this iteration
+  *row = g.table[it->second];
+  if (block_addr) *block_addr = it->first;
   return SS_OK;
 }
 

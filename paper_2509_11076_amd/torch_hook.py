@@ -23,7 +23,10 @@ class ss_hook_stats_t(C.Structure):
 _SIGS = {"ss_hook_install": [C.c_void_p, C.c_int], "ss_hook_set_mode": [C.c_int],
          "ss_hook_set_phase": [C.c_uint32], "ss_hook_begin_iteration": [], "ss_hook_remove": [],
          "ss_hook_get_stats": [C.POINTER(ss_hook_stats_t)],
-         "ss_hook_tensor_table": [C.c_void_p, C.POINTER(C.c_uint32)]}
+         "ss_hook_tensor_table": [C.c_void_p, C.POINTER(C.c_uint32)],
+         "ss_hook_current_op": [C.POINTER(C.c_uint32)],
+         "ss_hook_pause": [C.c_int],
+         "ss_hook_block_of": [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)]}
 for _n, _a in _SIGS.items():
     getattr(_lib, _n).argtypes = _a
     getattr(_lib, _n).restype = C.c_int
@@ -65,6 +68,28 @@ def ss_hook_tensor_table():
     if n.value:
         _ck(_lib.ss_hook_tensor_table(out.ctypes.data_as(C.c_void_p), C.byref(n)), "ss_hook_tensor_table")
     return out[:n.value]
+
+
+def ss_hook_current_op():
+    n = C.c_uint32()
+    _ck(_lib.ss_hook_current_op(C.byref(n)), "ss_hook_current_op")
+    return n.value
+
+
+def ss_hook_pause(on):
+    _ck(_lib.ss_hook_pause(1 if on else 0), "ss_hook_pause")
+
+
+def ss_hook_block_of(dev_addr):
+    """(tensor-table row, block start address) of the block of this iteration holding dev_addr, or None"""
+    import numpy as np
+    row = np.zeros(1, dtype=B.TENSOR_DT)
+    addr = C.c_uint64()
+    rc = _lib.ss_hook_block_of(C.c_void_p(int(dev_addr)), row.ctypes.data_as(C.c_void_p), C.byref(addr))
+    if rc == B.SS_E_INVAL:
+        return None
+    _ck(rc, "ss_hook_block_of")
+    return row[0], addr.value
 
 
 def ss_hook_get_stats():

@@ -41,8 +41,8 @@ def random_arena(torch, nbytes, seed):
 
 @pytest.mark.parametrize("bpo", [64 * 1024, INSTANT])
 @pytest.mark.parametrize("slot_kib,slots", [(512, 2), (1024, 3), (4096, 2)])
-@pytest.mark.parametrize("staged_in", [False, True])
-def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in):
+@pytest.mark.parametrize("staged_in,taper", [(False, 0), (True, 0), (True, 1)])
+def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, taper):
     """configuration 1 with ring slots smaller than, about, and larger than a layer's swap set: staging
     image and arena (with poison over released blocks) equal the oracle's, byte for byte"""
     from paper_2509_11076_amd.executor import run_iteration
@@ -57,7 +57,7 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in):
     host_arena = arena.cpu().numpy().copy()
     ctx = make_ctx(P, staging_bytes=ora["staging_bytes"], link_bytes_per_op=bpo, copy_path=P.SS_PATH_STAGED,
                    copy_path_in=P.SS_PATH_STAGED if staged_in else P.SS_PATH_AUTO,
-                   ring_slot_bytes=slot_kib << 10, ring_bytes=slots * (slot_kib << 10),
+                   ring_slot_bytes=slot_kib << 10, ring_bytes=slots * (slot_kib << 10), ring_taper=taper,
                    flags=P.SS_CFG_POISON_FREE | P.SS_CFG_TIMING)
     try:
         P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
@@ -88,6 +88,22 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in):
                 assert int(in_group_bytes.max()) <= slot_kib << 10
                 for g in range(len(in_group_bytes)):
                     assert P.ss_batch_ms(ctx, 3, g)[0] > 0
+                # group shapes: tapered, each swap-in group (of more than one batch) is at most half of what is
+                # still to come including itself, but never asked to be smaller than an eighth of a slot;
+                # untapered, a group ends only where the next batch would overflow the slot or leave a gap
+                sizes = in_group_bytes.tolist()
+                batches_in = np.bincount(in_group_of, minlength=len(sizes)).tolist()
+                for g, n in enumerate(sizes):
+                    cap = max((slot_kib << 10) // 8, min(sum(sizes[g:]) // 2, sum(sizes[:g])))
+                    if taper != 1 and batches_in[g] > 1:
+                        assert n <= cap
+                if taper == 1 and sum(sizes) > slot_kib << 10:
+                    assert max(sizes) > (slot_kib << 10) // 2
+                out_sizes = group_bytes.tolist()
+                batches_out = np.bincount(group_of, minlength=len(out_sizes)).tolist()
+                for g, n in enumerate(out_sizes):
+                    if taper == 0 and batches_out[g] > 1:
+                        assert n <= max((slot_kib << 10) // 8, sum(out_sizes[:g]))
             else:
                 assert len(in_group_bytes) == 0 and (in_group_of == -1).all()
         st = P.ss_get_stats(ctx)
@@ -124,18 +140,31 @@ def test_ring_takes_only_gap_free_batches_and_the_rest_leaves_directly(P, torch)
     start = np.array(starts, dtype=np.uint32)
     dep = np.arange(9, dtype=np.uint32)                        # swap-in batch b needs swap-out batch b only
     rows = [tuple(int(x) for x in r) for r in d.tolist()]
-    for path_in in (P.SS_PATH_AUTO, P.SS_PATH_STAGED):
+    for path_in, taper in ((P.SS_PATH_AUTO, 1), (P.SS_PATH_STAGED, 1), (P.SS_PATH_STAGED, 0)):
         ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_STAGED, copy_path_in=path_in,
-                       ring_slot_bytes=1024 * KiB, ring_bytes=2048 * KiB, flags=P.SS_CFG_TIMING)
+                       ring_slot_bytes=1024 * KiB, ring_bytes=2048 * KiB, ring_taper=taper, flags=P.SS_CFG_TIMING)
         try:
             P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
             P.ss_load_schedule(ctx, d, start, d, start, dep)
             group_of, group_bytes = P.ss_ring_view(ctx)
-            assert group_of.tolist() == [0, 0, 0, -1, 1, 2, -1, 3, 3]
-            assert group_bytes.tolist() == [1024 * KiB, 512 * KiB, 768 * KiB, 256 * KiB]
+            if taper == 1:
+                assert group_of.tolist() == [0, 0, 0, -1, 1, 2, -1, 3, 3]
+                assert group_bytes.tolist() == [1024 * KiB, 512 * KiB, 768 * KiB, 256 * KiB]
+            else:
+                # tapered: a swap-out group grows to at most what the groups before it hold (an eighth of a
+                # slot, 128 KiB, to begin with; one batch is never split)
+                assert group_of.tolist() == [0, 1, 2, -1, 3, 4, -1, 5, 5]
+                assert group_bytes.tolist() == [256 * KiB, 512 * KiB, 256 * KiB, 512 * KiB, 768 * KiB, 256 * KiB]
             in_group_of, in_group_bytes = P.ss_ring_view(ctx, 1)
-            if path_in == P.SS_PATH_STAGED:      # same slots, same rule: the same groups on the way back
+            if path_in == P.SS_PATH_STAGED and taper == 1:   # same slots, same rule: the same groups on the way back
                 assert in_group_of.tolist() == group_of.tolist() and in_group_bytes.tolist() == group_bytes.tolist()
+            elif path_in == P.SS_PATH_STAGED:
+                # tapered: a group takes at most as much as has gone before and at most half of what is still
+                # to come (never asked to be less than an eighth of a slot, 128 KiB; one batch is never split):
+                # batch 0 travels alone (nothing before it), batches 1 and 2 alone too (256 KiB, then 768 KiB
+                # before them: the next batch would not fit), the last two batches (256 KiB to come) one by one
+                assert in_group_of.tolist() == [0, 1, 2, -1, 3, 4, -1, 5, 6]
+                assert in_group_bytes.tolist() == [256 * KiB, 512 * KiB, 256 * KiB, 512 * KiB, 768 * KiB, 128 * KiB, 128 * KiB]
             else:
                 assert (in_group_of == -1).all()
             for order in ([0, 1, 2, 3, 4, 5, 6, 7, 8], [1, 0, 2, 4, 3, 6, 5, 8, 7], [8, 7, 6, 5, 4, 3, 2, 1, 0]):

@@ -196,6 +196,16 @@ def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
     ragged_round_trip(P, torch, path)
 
 
+@pytest.mark.parametrize("workgroups", [1, 7, 64, 4096])
+def test_descriptor_lookup_in_lds_moves_the_same_bytes(P, torch, workgroups):
+    """the form of the copy kernel that keeps the batch's chunk-prefix table in LDS and searches it per chunk:
+    ragged sizes (empty tensors among them, which share their successor's first chunk), empty batches,
+    batches of one tensor and of many, tensors of up to 40 chunks"""
+    ragged_round_trip(P, torch, "kernel", copy_desc_lookup=1, copy_workgroups=workgroups)
+    ragged_round_trip(P, torch, "kernel", seed=5, n=60, max_bytes=2500000, arena_bytes=256 << 20,
+                      copy_desc_lookup=1, copy_workgroups=workgroups)
+
+
 @pytest.mark.parametrize("workgroups,workgroups_out,unroll", [(1, 1, 1), (3, 5, 2), (64, 8, 4), (4096, 4096, 8), (0, 0, 0)])
 def test_every_launch_shape_within_the_limits_moves_the_same_bytes(P, torch, workgroups, workgroups_out, unroll):
     """grids from one workgroup to the maximum, every unroll depth, tensors of up to 40 chunks in batches
@@ -205,7 +215,8 @@ def test_every_launch_shape_within_the_limits_moves_the_same_bytes(P, torch, wor
     if workgroups == 0:
         ragged_round_trip(P, torch, "kernel", seed=6, n=60, max_bytes=300000, arena_bytes=64 << 20,
                           flags=P.SS_CFG_SYSTEM_FENCE)
-        for bad in (dict(copy_workgroups=4097), dict(copy_unroll=9), dict(copy_workgroups_out=5000)):
+        for bad in (dict(copy_workgroups=4097), dict(copy_unroll=9), dict(copy_workgroups_out=5000),
+                    dict(copy_desc_lookup=2), dict(ring_taper=2)):
             with pytest.raises(P.SsError) as e:
                 make_ctx(P, staging_bytes=4096, **bad)
             assert e.value.code == P.SS_E_INVAL

@@ -56,18 +56,29 @@ class Trainer:
         self.ids = torch.randint(0, args.vocab, (args.batch, args.seq), generator=g).to(device)
         self.tgt = torch.randint(0, args.vocab, (args.batch, args.seq), generator=g).to(device)
         self.hook = None
+        self.saved_hooks = None      # optional: a context-manager factory around forward + backward (autograd's
+                                     # saved-tensor hooks), and callbacks at the phase changes
+        self.on_phase = None
 
     def step(self):
+        import contextlib
         H = self.hook
         self.opt.zero_grad(set_to_none=True)
         if H:
             H.ss_hook_begin_iteration()
-        logits = self.model(self.ids)
-        loss = F.cross_entropy(logits.view(-1, logits.shape[-1]).float(), self.tgt.view(-1))
-        if H:
-            H.ss_hook_set_phase(1)
-        loss.backward()
+        with (self.saved_hooks() if self.saved_hooks else contextlib.nullcontext()):
+            logits = self.model(self.ids)
+            loss = F.cross_entropy(logits.view(-1, logits.shape[-1]).float(), self.tgt.view(-1))
+            if H:
+                H.ss_hook_set_phase(1)
+            if self.on_phase:
+                self.on_phase(1)
+            loss.backward()
         if H:
             H.ss_hook_set_phase(2)
+        if self.on_phase:
+            self.on_phase(2)
         self.opt.step()
+        if self.on_phase:
+            self.on_phase(3)
         return loss
