@@ -26,6 +26,11 @@ import os
 import sys
 import time
 
+# Every stream of the process beyond HIP's hardware queues (4 by default) shares a queue with another stream
+# and stands still while that one's work runs.  The library uses up to four streams of its own (swap-out,
+# swap-in, the ring transfers, and the trace kernels on the swap-in stream) beside the compute stream.
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
@@ -329,12 +334,19 @@ def record_mover_table(B, torch, np, bw, args):
     from workloads.harness import SwapRun
     rows = []
     combos = [("kernel", "engine", {}), ("kernel", "kernel", {}), ("kernel", "kernel", dict(workgroups=16)),
+              ("kernel", "kernel", dict(copy_cus=8)), ("kernel", "kernel", dict(copy_cus=16)),
+              ("kernel", "kernel", dict(copy_cus=64)),
               ("engine", "engine", {}), ("engine", "kernel", {}), ("staged", "engine", {}), ("staged", "staged", {})]
+    # the whole table runs on a compute stream of its own: swap streams with a compute-unit mask synchronise with
+    # the null stream (the runtime has no non-blocking form of them)
+    own = torch.cuda.Stream()
+    torch.cuda.set_stream(own)
     for p_out, p_in, kw in combos:
         o = argparse.Namespace(**vars(args))
-        o.config, o.path, o.path_in, o.calibrate, o.no_cpu_baseline = 2, p_out, p_in, 0, True
+        o.config, o.path, o.path_in, o.calibrate, o.no_cpu_baseline, o.no_stall_timing = 2, p_out, p_in, 0, True, True
         o.bpo = args.bpo if args.bpo > 0 else 11500000
         o.steps, o.warmup = min(args.steps, 8), max(args.warmup, 11)      # the stage machine needs nine iterations to settle
+        o.copy_cus = 0
         for k, v in kw.items():
             setattr(o, k, v)
         r = measure(B, torch, np, bw, o)
@@ -408,6 +420,7 @@ def record_mover_table(B, torch, np, bw, args):
         costs[label] = round(float(np.median([backward_ms(mode, pairs) for _ in range(5)])), 2)
         log("mover table: backward pass %s: %.2f ms" % (label, costs[label]))
     B.ss_destroy(kctx)
+    torch.cuda.set_stream(torch.cuda.default_stream())
     base.close()
     return {"mode": "mover-table", "workload": WORKLOADS[2], "link_peak_measured": {k: round(v, 2) for k, v in bw.items()},
             "rows": rows, "noswap_backward_pass_ms": costs}
@@ -545,6 +558,110 @@ def record_hook_overhead(B, torch, shapes=None, steps=20, warmup=5):
             "PyTorch profiler +219.7 %", "shapes": out}
 
 
+def record_torch_swap(B, torch, shape=None, limit_frac=0.8, steps=10, warmup=3):
+    """A policy generated from the hooked trace of a real PyTorch model and executed inside that model: a Llama-like
+    decoder in plain PyTorch (bf16, AdamW), one Detailed-mode iteration -> ss_generate_policy for a memory limit of
+    base + limit_frac x (peak - base) -> the executor around autograd's saved-tensor hooks, tensors moved with
+    ss_swap_out_from / ss_swap_in_to into blocks the caching allocator places."""
+    import copy
+    import paper_2509_11076_amd.torch_hook as H
+    from paper_2509_11076_amd.torch_executor import TorchSwapExecutor, BlockObserver, plan_from_profile
+    from workloads.torch_model import Trainer
+    sh = shape or dict(layers=12, hidden=1024, heads=16, seq=1024, batch=4, vocab=32000)
+    # attention through plain matmul and softmax kernels: every kernel of the step is deterministic, so the loss
+    # with and without swapping can be compared bit for bit (the fused attention kernels accumulate in an order
+    # that changes from run to run)
+    torch.backends.cuda.enable_flash_sdp(False)
+    torch.backends.cuda.enable_mem_efficient_sdp(False)
+    tr = Trainer(argparse.Namespace(**sh))
+
+    def timed(n, w):
+        for _ in range(w):
+            tr.step()
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            loss = tr.step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e3, torch.cuda.max_memory_allocated(), loss.detach().clone()
+    for _ in range(warmup):
+        tr.step()
+    snap = (copy.deepcopy(tr.model.state_dict()), copy.deepcopy(tr.opt.state_dict()))
+
+    def restore():
+        tr.model.load_state_dict(copy.deepcopy(snap[0]))
+        tr.opt.load_state_dict(copy.deepcopy(snap[1]))
+    ms_plain, peak_plain, loss_plain = timed(steps, 0)
+    cfg = B.ss_config_default()
+    cfg.staging_bytes = 0
+    cfg.max_ops, cfg.max_events = 1 << 18, 1 << 20
+    cfg.flags = B.SS_CFG_POLICY_POINTS
+    plan_ctx = exec_ctx = None
+    tr.hook = H
+    try:
+        # Eq. 1 / Eq. 3: link bytes per operator from the step just measured
+        plan_ctx = B.ss_create(cfg)
+        H.ss_hook_install(plan_ctx, H.SS_HOOK_DETAILED)
+        restore()
+        ms_detailed, _, _ = timed(max(3, steps // 2), 1)
+        restore()
+        tr.opt.zero_grad(set_to_none=True)
+        torch.cuda.synchronize()
+        base = torch.cuda.memory_stats()["requested_bytes.all.current"]
+        obs = BlockObserver()
+        tr.saved_hooks = lambda: torch.autograd.graph.saved_tensors_hooks(obs.pack, obs.unpack)
+        tr.step()
+        tr.saved_hooks = None
+        torch.cuda.synchronize()
+        ops, ev, _ = B.ss_trace_view(plan_ctx)
+        ops, ev = ops.copy(), ev.copy()
+        tab = H.ss_hook_tensor_table()
+        B.ss_destroy(plan_ctx)
+        cfg.link_bytes_per_op = max(1, int(57e9 * ms_plain * 1e-3 / max(1, len(ops))))
+        plan_ctx = B.ss_create(cfg)
+        no = B.ss_timeline_scan(plan_ctx, ev, None, len(ops), base, 1 << 62)
+        limit = base + int(limit_frac * (no["peak"] - base))
+        kept, descs_out, info, ap, pol = plan_from_profile(plan_ctx, ops, tab, ev, base, limit, sh["layers"], sh["layers"],
+                                                           min_bytes=1 << 20, observer=obs)
+        cfg2 = B.ss_config_default()
+        cfg2.staging_bytes = max(4096, int(ap["staging_bytes"]))
+        cfg2.max_ops, cfg2.max_events = cfg.max_ops, cfg.max_events
+        exec_ctx = B.ss_create(cfg2)
+        H.ss_hook_install(exec_ctx, H.SS_HOOK_DETAILED)
+        ex = TorchSwapExecutor(torch, exec_ctx, kept, descs_out, torch.cuda.current_stream())
+        tr.saved_hooks = ex.hooks
+        tr.on_phase = lambda ph: ex.end_iteration() if ph == 3 else ex.poll()
+        restore()
+        ms_swap, peak_swap, loss_swap = timed(steps, 0)
+        tr.saved_hooks = tr.on_phase = None
+        st = dict(ex.stats)
+    finally:
+        tr.saved_hooks = tr.on_phase = None
+        H.ss_hook_remove()
+        tr.hook = None
+        for c in (plan_ctx, exec_ctx):
+            if c is not None:
+                B.ss_destroy(c)
+        torch.backends.cuda.enable_flash_sdp(True)
+        torch.backends.cuda.enable_mem_efficient_sdp(True)
+    per_step = sum(int(x) for x in kept["nbytes"])
+    return {"mode": "torch-model-swap",
+            "workload": "Llama-like decoder in plain PyTorch, %(layers)d layers, hidden %(hidden)d, %(heads)d heads, seq %(seq)d, "
+                        "batch %(batch)d, bf16, AdamW, attention by matmul + softmax kernels; policy generated from its own hooked "
+                        "trace and executed inside it" % sh,
+            "steps": steps, "ops_per_step": int(len(ops)), "allocator_events_per_step": int(len(ev)),
+            "memory_limit_bytes": int(limit), "limit_frac_of_activation_peak": limit_frac,
+            "generator": info, "tensors_swapped": int(len(kept)), "bytes_each_way_per_step": per_step,
+            "executor": st,
+            "ms_per_step": {"no_hook_no_swap": round(ms_plain, 3), "detailed_hook_no_swap": round(ms_detailed, 3),
+                            "swapping": round(ms_swap, 3)},
+            "overhead_vs_no_swap_pct": round(100 * (ms_swap / ms_plain - 1), 1),
+            "allocator_peak_bytes": {"no_swap": int(peak_plain), "swapping": int(peak_swap),
+                                     "planned_with_policy": int(info["peak_with_policy"])},
+            "loss_after_the_same_steps_bit_equal": bool(torch.equal(loss_plain, loss_swap))}
+
+
 # ---- the fixed-sequence configurations: 1, 2, 3, 5 ----------------------------------------------------
 
 def measure(B, torch, np, bw, o):
@@ -660,11 +777,12 @@ def measure(B, torch, np, bw, o):
         if bpo <= 0:
             bpo = max(1, int(link * t_noswap / base_n_ops))      # not used by the generator's own points
     path, path_in = paths[o.path], paths[o.path_in or o.path]
+    window_in = o.engine_window if o.engine_window >= 0 else ((4, bw["h2d_gbps"] * 1e9, t_bwd) if has_compute else 0)
 
     def make(bpo_, wgo=workgroups_out, p=None, p_in=None):
         return SwapRun(B, torch, cfgno, swap=True, bpo=bpo_, bpo_in=bpo_in, copy_path=path if p is None else p,
                        copy_path_in=path_in if p_in is None else p_in, copy_workgroups=o.workgroups,
-                       copy_workgroups_out=wgo, flags=flags, **extra)
+                       copy_workgroups_out=wgo, flags=flags, cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in, engine_window_out=o.engine_window_out), **extra)
 
     def trial(label, **kw):
         r = make(**kw)
@@ -694,7 +812,7 @@ def measure(B, torch, np, bw, o):
     # exceed a ring slot and all go by copy engine: nothing to choose there.
     grid_fits, path_fits = [], []
     if has_compute and cfgno != 3 and o.calibrate > 0:
-        if o.path == "auto" and o.path_in is None:
+        if o.path == "auto" and o.path_in is None and cfgno == 2:
             for name, p in (("auto", B.SS_PATH_AUTO), ("staged", B.SS_PATH_STAGED)):
                 t_trial = trial("route %s" % name, bpo_=bpo, p=p, p_in=p)[0]
                 path_fits.append({"route": name, "ms_per_step": round(t_trial * 1e3, 2)})
@@ -708,6 +826,7 @@ def measure(B, torch, np, bw, o):
                 workgroups_out = 8
     run = make(bpo_=bpo, wgo=workgroups_out)
     n_forced, n_dropped_setup, run_generated = run.n_forced, run.n_dropped, run.generated
+    engine_window_used = run.engine_window_in
     for _ in range(o.warmup):
         run.step()
     torch.cuda.synchronize()
@@ -757,6 +876,19 @@ def measure(B, torch, np, bw, o):
     event_steps = 1 + min(3, o.steps)
     st2 = B.ss_get_stats(run.ctx)
     applied, match, scan = run.last["applied"], run.last["match"], run.last["scan"]
+    steps_all = o.warmup + o.steps + event_steps - 1
+    lib_stats = {
+        # anchors placed per matching level over all steps of this context: (token, stack, sig), (token, sig),
+        # (token), sequence alignment, unmatched
+        "anchors_by_match_level": dict(zip(("full_key", "token_sig", "token", "aligned", "unmatched"),
+                                           [int(x) for x in st2["match_levels"]])),
+        # memory-block reuse interval of the loaded schedule (Sec. 6.4): operators between issuing a tensor's
+        # swap-out and the release of its block; bucket b = floor(log2(interval + 1))
+        "reuse_interval_ops": {"mean": round(st2["reuse_sum"] / max(1, st2["reuse_count"]), 2),
+                               "log2_histogram": [int(x) for x in st2["reuse_hist"]]},
+        "free_waits_per_step": int(st2["free_waits"]) // max(1, steps_all),
+        "wait_in_waits_per_step": int(st2["in_waits"]) // max(1, steps_all),
+        "engine_window_waits_per_step": int(st2["engine_window_waits"]) // max(1, steps_all)}
     bytes_way = run.bytes_each_way
     assert st1["bytes_out"] - st0["bytes_out"] == o.steps * bytes_way == st1["bytes_in"] - st0["bytes_in"]
     n_ops = run.tr.n_ops
@@ -767,6 +899,26 @@ def measure(B, torch, np, bw, o):
     run.close()
     del run
     torch.cuda.empty_cache()
+    # time the compute stream spends inside the device-side waits: two more steps in the library's measurement
+    # mode (one more event on the compute stream before every wait; the drain joins the compute stream too)
+    if has_compute and not getattr(o, "no_stall_timing", False):
+        srun = SwapRun(B, torch, cfgno, swap=True, bpo=bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
+                       copy_workgroups=o.workgroups, copy_workgroups_out=workgroups_out, flags=flags | B.SS_CFG_STALL_TIMING,
+                       cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in,
+                                      engine_window_out=o.engine_window_out), **extra)
+        srun.step()
+        torch.cuda.synchronize()
+        a = B.ss_get_stats(srun.ctx)
+        for _ in range(2):
+            srun.step()
+        torch.cuda.synchronize()
+        b_ = B.ss_get_stats(srun.ctx)
+        lib_stats["compute_stream_wait_ms_per_step"] = {
+            "for_swap_outs_before_a_block_is_released": round((b_["stall_free_ms"] - a["stall_free_ms"]) / 2, 3),
+            "for_swap_ins_before_a_first_use": round((b_["stall_wait_in_ms"] - a["stall_wait_in_ms"]) / 2, 3)}
+        srun.close()
+        del srun
+        torch.cuda.empty_cache()
 
     per_step = lambda k: (st1[k] - st0[k]) // o.steps
     kernel_batches, engine_batches = per_step("kernel_batches"), per_step("engine_batches")
@@ -848,7 +1000,8 @@ def measure(B, torch, np, bw, o):
                    "kernel_launches_per_step": int(kernel_batches), "engine_batches_per_step": int(engine_batches),
                    "ring_transfers_per_step": {"out": int(ring_tr_out), "in": int(ring_tr_in)},
                    "swap_out_by": out_by, "swap_in_by": in_by,
-                   "link_bytes_per_op": bpo, "prefetch_bytes_per_op": bpo_in, "link_model_fits": calib,
+                   "link_bytes_per_op": bpo, "prefetch_bytes_per_op": bpo_in, "engine_window_in": engine_window_used,
+                   "link_model_fits": calib,
                    "route_fits": path_fits, "pack_grid_fits": grid_fits,
                    "pack_workgroups": workgroups_out or o.workgroups or "default (64)", "policy_mode": o.policy_mode,
                    "timing": o.timing if o.policy_mode == "generated" else "link-model",
@@ -882,6 +1035,7 @@ def measure(B, torch, np, bw, o):
                       "overhead_vs_floor_out_then_in_pct": round(100 * (t_step / t_floor_serial - 1), 1),
                       "link_bound": bool(t_floor_serial > 1.05 * t_noswap)},
         "roofline": roof,
+        "library_statistics": lib_stats,
         "gbps_by_batch_size": [{"direction": "out" if d == 0 else "in", "batch_bytes_up_to": cls, "batches": n,
                                 "gbps_while_running": round(tot / (ms * 1e-3) / 1e9, 2)}
                                for (d, cls), (n, tot, ms) in sorted(by_size.items())],
@@ -932,7 +1086,14 @@ def main():
     ap.add_argument("--limit-frac", type=float, default=0.7,
                     help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
+    ap.add_argument("--engine-window-out", type=int, default=0, help="the same for copy-engine swap-out batches")
+    ap.add_argument("--engine-window", type=int, default=-1,
+                    help="copy-engine swap-in batches outstanding at most (0 = no limit): the dispatch thread waits in "
+                         "ss_swap_in for the batch issued that many batches earlier; default: 4 where the swap-in bytes "
+                         "need more than 1.5 x the no-swap backward pass on the link, else no limit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stall-timing", action="store_true",
+                    help="leave out the two extra steps in the library's stall-measurement mode")
     ap.add_argument("--swap-only", action="store_true",
                     help="counter-collection mode: the same swap schedule without the compute stream's work, "
                          "no baseline, no link-model fitting (keeps a rocprofv3 --pmc run short)")
@@ -949,6 +1110,10 @@ def main():
     ap.add_argument("--hook-overhead", action="store_true",
                     help="overhead of the dispatch hook on a real PyTorch training step: no profiling, Lightweight, "
                          "Detailed, torch.profiler (the paper's profiler-overhead table)")
+    ap.add_argument("--torch-swap", action="store_true",
+                    help="a policy generated from the hooked trace of a real PyTorch model, executed inside that model "
+                         "(saved-tensor hooks, blocks placed by the caching allocator); memory limit = base + --limit-frac x "
+                         "(peak - base)")
     ap.add_argument("--probe-reps", type=int, default=10)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -968,6 +1133,8 @@ def main():
 
     if args.hook_overhead:
         return emit(record_hook_overhead(B, torch, steps=args.steps, warmup=args.warmup))
+    if args.torch_swap:
+        return emit(record_torch_swap(B, torch, limit_frac=args.limit_frac, steps=args.steps, warmup=args.warmup))
 
     # host-link peak, measured now (pinned hipMemcpy; 1 GiB transfers)
     pcfg = B.ss_config_default()
@@ -1027,12 +1194,16 @@ def main():
             sub("config_2", lambda: measure(B, torch, np, bw, opts(config=2, steps=10, warmup=3)))
         sub("config_5", lambda: measure(B, torch, np, bw, opts(config=5, steps=3, warmup=1)))
         sub("config_4_planning", lambda: record_config4(B, torch, np, cpu=not args.no_cpu_baseline))
+        sub("config_2_generated_policy_limit_0.97", lambda: measure(
+            B, torch, np, bw, opts(config=2, steps=10, warmup=3, policy_mode="generated", limit_frac=0.97,
+                                   timing="link-model")))
         sub("config_2_generated_policy_limit_0.95", lambda: measure(
             B, torch, np, bw, opts(config=2, steps=10, warmup=3, policy_mode="generated", limit_frac=0.95,
                                    timing="link-model")))
         sub("config_2_stage_loop_limit_0.95", lambda: record_staged(B, torch, bw, 2, 0.95, 5))
         sub("reuse_interval_config_2", lambda: record_reuse_interval(B, torch, np, bw, 2, B.SS_PATH_AUTO, B.SS_PATH_AUTO))
         sub("hook_overhead", lambda: record_hook_overhead(B, torch, steps=10, warmup=3))
+        sub("torch_model_swap", lambda: record_torch_swap(B, torch, limit_frac=0.9, steps=10, warmup=3))
         def compact(r):
             """what the headline already says once (definitions, notes, the link peak) and per-iteration logs
             are left out of the sub-records; the modes run on their own (--config N, --policy-mode staged) print them"""

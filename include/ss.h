@@ -174,7 +174,17 @@ typedef struct {
                                  ones take the table).  Same bytes either way; 0 is faster on small tensors  */
   uint32_t copy_cus;          /* 0 = the swap streams' kernels may run on every compute unit; n > 0 = only on n of
                                  them (a compute-unit mask on those streams, spread over the dies), so that the
-                                 copy kernel's long-lived waves occupy those units and no others               */
+                                 copy kernel's long-lived waves occupy those units and no others.  The runtime
+                                 creates such streams in its blocking form only: they synchronise with the null
+                                 stream, so the compute stream bound must be another one.  Measured: masks of 8
+                                 to 64 units do not change what a link-saturating copy kernel costs the compute
+                                 stream; kept for measurement                                                */
+  uint32_t engine_window_in;  /* copy-engine swap-in batches outstanding at most (0 = no limit): ss_swap_in returns
+                                 only once the engine swap-in batch issued this many batches earlier has finished.
+                                 Copy-engine transfers queued behind more than a few others run at a fraction of
+                                 the link rate; the dispatch thread waits only where the compute stream is waiting
+                                 for the same transfers                                                      */
+  uint32_t engine_window_out; /* the same for copy-engine swap-out batches and ss_swap_out                     */
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */
@@ -237,6 +247,7 @@ typedef struct {
   uint64_t ring_batches, ring_transfers; /* SS_PATH_STAGED: swap-out batches gathered into the HBM ring, and
                                             copy-engine transfers that carried them out of it */
   uint64_t ring_batches_in, ring_transfers_in; /* the same for swap-in: batches scattered out of the ring, transfers into it */
+  uint64_t engine_window_waits;         /* times ss_swap_in / ss_swap_out waited for an earlier engine batch (engine_window_*) */
 } ss_stats_t;
 
 typedef struct {

@@ -60,7 +60,8 @@ class ss_config_t(C.Structure):
                 ("out_streams", C.c_uint32), ("in_streams", C.c_uint32),
                 ("ring_bytes", C.c_uint64), ("ring_slot_bytes", C.c_uint64),
                 ("gather_workgroups", C.c_uint32), ("ring_taper", C.c_uint32),
-                ("copy_desc_lookup", C.c_uint32), ("copy_cus", C.c_uint32)]
+                ("copy_desc_lookup", C.c_uint32), ("copy_cus", C.c_uint32),
+                ("engine_window_in", C.c_uint32), ("engine_window_out", C.c_uint32)]
 
 
 class ss_scan_result_t(C.Structure):
@@ -103,7 +104,8 @@ class ss_stats_t(C.Structure):
                 ("reuse_sum", C.c_uint64), ("reuse_count", C.c_uint64),
                 ("stall_free_ms", C.c_double), ("stall_wait_in_ms", C.c_double),
                 ("ring_batches", C.c_uint64), ("ring_transfers", C.c_uint64),
-                ("ring_batches_in", C.c_uint64), ("ring_transfers_in", C.c_uint64)]
+                ("ring_batches_in", C.c_uint64), ("ring_transfers_in", C.c_uint64),
+                ("engine_window_waits", C.c_uint64)]
 
 
 class ss_bw_t(C.Structure):

@@ -85,6 +85,8 @@ struct ss_sched {
   size_t d_cap_out = 0, d_cap_in = 0, d_ccap_out = 0, d_ccap_in = 0;
   bool out_all_large = false;                     // every swap-out batch reaches engine_min_bytes_out (mean tensor size)
   int64_t last_engine_out = -1;                   // last swap-out batch of this iteration that went by copy engine
+  std::vector<uint32_t> engine_in_issued;         // swap-in batches of this iteration that went by copy engine, in issue order
+  std::vector<uint32_t> engine_out_issued;        // the same for swap-out
   bool loaded = false;
   // the action schedule of the last ss_apply_policy, for ss_dispatch: actions in schedule order and,
   // per operator, where its "before" and "after" runs start (act_start has 2 * n + 1 entries)

@@ -308,6 +308,8 @@ static void ring_reset(ss_sched &s, uint32_t n_slots) {
   std::fill(s.in_group_last_scatter.begin(), s.in_group_last_scatter.end(), -1);
   std::fill(s.out_staged.begin(), s.out_staged.end(), 0);
   s.last_flush_batch = s.last_gather_batch = -1;
+  s.engine_in_issued.clear();
+  s.engine_out_issued.clear();
 }
 
 static int check_descs(const ss_ctx *ctx, const ss_desc_t *d, uint32_t n) {
@@ -924,6 +926,12 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
   uint64_t bytes = 0;
   for (uint32_t i = lo; i < hi; ++i) bytes += s.out[i].nbytes;
   if (engine) {
+    if (ctx->cfg.engine_window_out && s.engine_out_issued.size() >= ctx->cfg.engine_window_out) {   // see swap_in_batch
+      const uint32_t old = s.engine_out_issued[s.engine_out_issued.size() - ctx->cfg.engine_window_out];
+      SS_HIP(hipEventSynchronize(s.ev_out_done[s.phase][old]));
+      ctx->stats.engine_window_waits++;
+    }
+    s.engine_out_issued.push_back(batch);
     for (uint32_t i = lo; i < hi; ++i)
       if (s.out[i].nbytes)
         SS_HIP(hipMemcpyAsync(ctx->staging + s.out[i].host_off, ctx->arena + s.out[i].dev_off, s.out[i].nbytes,
@@ -1060,6 +1068,16 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
   uint64_t bytes = 0;
   for (uint32_t i = lo; i < hi; ++i) bytes += s.in[i].nbytes;
   if (engine) {
+    // Flow control: copy-engine transfers queued behind more than a few others run at a fraction of the link
+    // rate, so with engine_window_in = w the call does not return before the engine swap-in batch issued w
+    // batches earlier has finished: at most w of them are outstanding.  The host waits here only where the
+    // link is the bottleneck anyway (the compute stream is waiting for those same transfers).
+    if (ctx->cfg.engine_window_in && s.engine_in_issued.size() >= ctx->cfg.engine_window_in) {
+      const uint32_t old = s.engine_in_issued[s.engine_in_issued.size() - ctx->cfg.engine_window_in];
+      SS_HIP(hipEventSynchronize(s.ev_in_done[s.phase][old]));
+      ctx->stats.engine_window_waits++;
+    }
+    s.engine_in_issued.push_back(batch);
     for (uint32_t i = lo; i < hi; ++i)
       if (s.in[i].nbytes)
         SS_HIP(hipMemcpyAsync(ctx->arena + s.in[i].dev_off, ctx->staging + s.in[i].host_off, s.in[i].nbytes,

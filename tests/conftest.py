@@ -2,6 +2,9 @@ import os
 import sys
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+# a test with a compute stream of its own beside the library's four streams needs more than HIP's four
+# hardware queues per process, or two of the streams share one and take turns
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
 
 
 def pytest_configure(config):

@@ -187,6 +187,7 @@ def ragged_round_trip(P, torch, path, seed=3, n=40, max_bytes=200000, arena_byte
         oracle.swap_in(host_arena, staging, descs_in.tolist())
         assert np.array_equal(P.ss_host_peek(ctx, 0, staging_bytes), staging)
         assert np.array_equal(arena.cpu().numpy(), host_arena)
+        return P.ss_get_stats(ctx)
     finally:
         P.ss_destroy(ctx)
 
@@ -194,6 +195,15 @@ def ragged_round_trip(P, torch, path, seed=3, n=40, max_bytes=200000, arena_byte
 @pytest.mark.parametrize("path", ["kernel", "engine"])
 def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
     ragged_round_trip(P, torch, path)
+
+
+@pytest.mark.parametrize("window", [1, 2, 5])
+def test_engine_swap_in_window_bounds_what_is_outstanding(P, torch, window):
+    """engine_window_in = w: ss_swap_in waits for the engine batch issued w batches earlier; same bytes, and the
+    number of waits is what the three swap-in batches of the schedule give"""
+    st = ragged_round_trip(P, torch, "engine", engine_window_in=window)
+    assert st["engine_window_waits"] == max(0, 3 - window)
+    assert ragged_round_trip(P, torch, "kernel", engine_window_in=window)["engine_window_waits"] == 0
 
 
 @pytest.mark.parametrize("workgroups", [1, 7, 64, 4096])
@@ -215,6 +225,11 @@ def test_every_launch_shape_within_the_limits_moves_the_same_bytes(P, torch, wor
     if workgroups == 0:
         ragged_round_trip(P, torch, "kernel", seed=6, n=60, max_bytes=300000, arena_bytes=64 << 20,
                           flags=P.SS_CFG_SYSTEM_FENCE)
+        # swap streams confined to 16 compute units by a unit mask
+        ragged_round_trip(P, torch, "kernel", seed=7, n=60, max_bytes=300000, arena_bytes=64 << 20, copy_cus=16)
+        with pytest.raises(P.SsError) as e:
+            make_ctx(P, staging_bytes=4096, copy_cus=100000)
+        assert e.value.code == P.SS_E_INVAL
         for bad in (dict(copy_workgroups=4097), dict(copy_unroll=9), dict(copy_workgroups_out=5000),
                     dict(copy_desc_lookup=2), dict(ring_taper=2)):
             with pytest.raises(P.SsError) as e:

@@ -23,7 +23,7 @@ class SwapRun:
     def __init__(self, B, torch, cfgno, swap=True, bpo=64 << 20, budget=None, min_bytes=0, compute=True,
                  copy_path=0, copy_workgroups=0, flags=0, seed=2509, gemm_scale=1.0, guard=0, trace=None,
                  policy=None, engine_min_bytes=None, bpo_in=0, copy_workgroups_out=0, copy_unroll=0, copy_path_in=None, generator=None,
-                 policy_points=True, reuse_delay=0, strict_limit=False):
+                 policy_points=True, reuse_delay=0, strict_limit=False, cfg_extra=None):
         from .compute import SyntheticCompute
         self.B, self.torch, self.cfgno, self.swap = B, torch, cfgno, swap
         if trace is not None:
@@ -53,6 +53,12 @@ class SwapRun:
         cfg.max_events = max(1 << 20, len(tr.events))
         if engine_min_bytes is not None:
             cfg.engine_min_bytes = engine_min_bytes
+        self.engine_window_auto = None
+        for k, v in (cfg_extra or {}).items():      # further fields of ss_config_t by name
+            if k == "engine_window_in" and isinstance(v, tuple):
+                self.engine_window_auto = v         # (window, link bytes per second, backward pass seconds): decided below
+            else:
+                setattr(cfg, k, v)
         self.budget = budget if budget is not None else (1 << 62)
         self.stream = torch.cuda.current_stream()
 
@@ -108,6 +114,12 @@ class SwapRun:
         self.n_dropped = int(ap["n_dropped"])
         self.staging_bytes = max(4096, int(ap["staging_bytes"]))
         cfg.staging_bytes = self.staging_bytes
+        if self.engine_window_auto is not None:
+            # flow control of the copy-engine swap-ins pays only where the link, not the backward pass, sets the
+            # pace: there the dispatch thread may wait for transfers without starving the compute stream
+            window, link_bps, t_bwd = self.engine_window_auto
+            cfg.engine_window_in = window if int(ap["bytes_out"]) / link_bps > 1.5 * t_bwd else 0
+        self.engine_window_in = int(cfg.engine_window_in)
         self.ctx = B.ss_create(cfg)
         # the library interns per context: same strings, same order, same integers
         for i in range(tr.n_ops):
