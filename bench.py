@@ -29,7 +29,7 @@ import time
 # Every stream of the process beyond HIP's hardware queues (4 by default) shares a queue with another stream
 # and stands still while that one's work runs.  The library uses up to four streams of its own (swap-out,
 # swap-in, the ring transfers, and the trace kernels on the swap-in stream) beside the compute stream.
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
+os.environ["GPU_MAX_HW_QUEUES"] = str(max(8, int(os.environ.get("GPU_MAX_HW_QUEUES") or 0)))
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
@@ -593,6 +593,8 @@ def record_torch_swap(B, torch, shape=None, limit_frac=0.8, steps=10, warmup=3):
         tr.model.load_state_dict(copy.deepcopy(snap[0]))
         tr.opt.load_state_dict(copy.deepcopy(snap[1]))
     ms_plain, peak_plain, loss_plain = timed(steps, 0)
+    restore()
+    _, _, loss_again = timed(steps, 0)           # is the step itself reproducible?  only then does bit equality mean anything
     cfg = B.ss_config_default()
     cfg.staging_bytes = 0
     cfg.max_ops, cfg.max_events = 1 << 18, 1 << 20
@@ -659,7 +661,9 @@ def record_torch_swap(B, torch, shape=None, limit_frac=0.8, steps=10, warmup=3):
             "overhead_vs_no_swap_pct": round(100 * (ms_swap / ms_plain - 1), 1),
             "allocator_peak_bytes": {"no_swap": int(peak_plain), "swapping": int(peak_swap),
                                      "planned_with_policy": int(info["peak_with_policy"])},
-            "loss_after_the_same_steps_bit_equal": bool(torch.equal(loss_plain, loss_swap))}
+            "loss_without_swapping_reproducible_bit_for_bit": bool(torch.equal(loss_plain, loss_again)),
+            "loss_after_the_same_steps_bit_equal": bool(torch.equal(loss_plain, loss_swap)),
+            "loss": {"no_swap": float(loss_plain), "no_swap_again": float(loss_again), "swapping": float(loss_swap)}}
 
 
 # ---- the fixed-sequence configurations: 1, 2, 3, 5 ----------------------------------------------------

@@ -160,6 +160,38 @@ __global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_kernel(
   }
 }
 
+// One tensor given by its two addresses (no descriptor table): for batches whose device addresses arrive with
+// the call.  Chunks of 64 KiB are dealt round-robin to the workgroups; within a chunk every lane keeps kUnroll
+// 16-byte loads in flight before it stores them; the last chunk ends with a byte tail.
+template <uint32_t kUnroll>
+__global__ __launch_bounds__(SS_COPY_THREADS) void ss_copy_flat_kernel(const uint8_t *__restrict__ src,
+                                                                       uint8_t *__restrict__ dst, uint64_t nbytes) {
+  const uint32_t tid = threadIdx.x;
+  const uint64_t n_chunks = (nbytes + SS_CHUNK_BYTES - 1) >> SS_CHUNK_SHIFT;
+  for (uint64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const uint64_t off = c << SS_CHUNK_SHIFT;
+    const uint64_t left = nbytes - off;
+    const uint32_t n = left < SS_CHUNK_BYTES ? (uint32_t)left : SS_CHUNK_BYTES;
+    const u32x4 *s16 = reinterpret_cast<const u32x4 *>(src + off);
+    u32x4 *d16 = reinterpret_cast<u32x4 *>(dst + off);
+    const uint32_t n16 = n >> 4;
+    for (uint32_t base = 0; base < n16; base += SS_COPY_THREADS * kUnroll) {
+      u32x4 v[kUnroll];
+#pragma unroll
+      for (uint32_t u = 0; u < kUnroll; ++u) {
+        const uint32_t i = base + u * SS_COPY_THREADS + tid;
+        if (i < n16) v[u] = __builtin_nontemporal_load(s16 + i);
+      }
+#pragma unroll
+      for (uint32_t u = 0; u < kUnroll; ++u) {
+        const uint32_t i = base + u * SS_COPY_THREADS + tid;
+        if (i < n16) __builtin_nontemporal_store(v[u], d16 + i);
+      }
+    }
+    if (tid < (n & 15u)) dst[off + ((uint64_t)n16 << 4) + tid] = src[off + ((uint64_t)n16 << 4) + tid];
+  }
+}
+
 __global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nbytes, uint32_t word) {
   // dst is 16-byte aligned (checked by the caller)
   const uint64_t n16 = nbytes >> 4;
@@ -197,6 +229,13 @@ void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to
     if (unroll <= 2) SS_LAUNCH(false, 2); else if (unroll <= 4) SS_LAUNCH(false, 4); else SS_LAUNCH(false, 8);
   }
 #undef SS_LAUNCH
+}
+
+void ss_launch_copy_flat(hipStream_t s, uint32_t workgroups, const uint8_t *src, uint8_t *dst, uint64_t nbytes) {
+  if (nbytes == 0) return;
+  const uint64_t n_chunks = (nbytes + SS_CHUNK_BYTES - 1) >> SS_CHUNK_SHIFT;
+  const dim3 grid((uint32_t)(workgroups < n_chunks ? workgroups : n_chunks)), block(SS_COPY_THREADS);
+  hipLaunchKernelGGL((ss_copy_flat_kernel<8>), grid, block, 0, s, src, dst, nbytes);
 }
 
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value) {

@@ -78,8 +78,7 @@ struct ss_sched {
   int phase = 0;                                    // event set of the iteration being issued
   bool drained_once = false;                        // set `phase ^ 1` holds a completed iteration
   ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
-  ss_desc_t *pin_out = nullptr, *pin_in = nullptr; // pinned host mirrors (source of the refresh when addresses arrive late)
-  size_t pin_cap_out = 0, pin_cap_in = 0;
+  bool flat_next = false;                         // the batch being issued got its device addresses with the call
   uint32_t *d_out_chunk0 = nullptr, *d_in_chunk0 = nullptr;
   uint32_t *d_out_cdesc = nullptr, *d_in_cdesc = nullptr;
   size_t d_cap_out = 0, d_cap_in = 0, d_ccap_out = 0, d_ccap_in = 0;
@@ -178,6 +177,8 @@ void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to
                     uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,
                     const uint32_t *d_chunk_desc, uint32_t n_chunks, uint32_t chunk_shift, uint32_t n_desc,
                     bool lds_lookup);
+// one tensor by its two addresses, no descriptor table (16-byte aligned on both sides)
+void ss_launch_copy_flat(hipStream_t s, uint32_t workgroups, const uint8_t *src, uint8_t *dst, uint64_t nbytes);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
 
 // sequence aligner (ss_align.hip): ref_to_cur has n entries

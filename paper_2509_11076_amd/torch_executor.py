@@ -97,6 +97,7 @@ class TorchSwapExecutor:
         self.stats = dict(swapped_out=0, freed=0, swapped_in=0, returned_resident=0, bytes_out=0, bytes_in=0,
                           not_seen=0)
         self.capture = None          # optional: callable(item index, tensor) right before its swap-out is issued
+        self.before_release = None   # optional: callable(item index, tensor) right before its block is given back
         self.begin_iteration()
 
     # ---- per iteration -------------------------------------------------------------------------------
@@ -198,6 +199,8 @@ class TorchSwapExecutor:
             if self.state.get(k) == OUT_ISSUED:
                 # the compute stream waits on the device for the copy; from here on the block may be reused
                 B.ss_sync(self.ctx, B.SS_SYNC_FREE, int(it["tensor_id"][k]))
+                if self.before_release is not None:
+                    self.before_release(k, self.held[k])
                 del self.held[k]
                 self.state[k] = FREED
                 self.stats["freed"] += 1

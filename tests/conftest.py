@@ -4,7 +4,7 @@ import sys
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 # a test with a compute stream of its own beside the library's four streams needs more than HIP's four
 # hardware queues per process, or two of the streams share one and take turns
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
+os.environ["GPU_MAX_HW_QUEUES"] = str(max(8, int(os.environ.get("GPU_MAX_HW_QUEUES") or 0)))
 
 
 def pytest_configure(config):
