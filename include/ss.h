@@ -523,9 +523,11 @@ int ss_swap_in(ss_ctx *ctx, uint32_t batch);
  * themselves, ss_load_schedule checks staging offsets only and the plain ss_swap_out / ss_swap_in refuse
  * non-empty batches with SS_E_STATE).  Such batches go by copy engine, which takes the addresses from the
  * host-side descriptors, unless the direction's path is SS_PATH_KERNEL: then the copy kernel gets the addresses as
- * launch arguments, one launch per tensor (on a real PyTorch model the copy kernel on the swap-out side made the
- * training loss irreproducible in the last bits in some runs, for a reason not found, although every byte moved
- * was checked to be right; with the copy engine every run was bit-identical to no swapping).  Ordering, events, statistics and errors as ss_swap_out / ss_swap_in; SS_E_INVAL for a null or
+ * launch arguments, one launch per tensor (on a real PyTorch bf16 model, copy-kernel launches beside the step
+ * made the training loss irreproducible in the last bits in some runs although every byte moved was checked to
+ * be right - as did the copy kernel moving an unrelated buffer with no ordering against the step: the model's
+ * own kernels accumulate in an order that depends on what else holds compute units; with the copy engine every
+ * run was bit-identical to no swapping).  Ordering, events, statistics and errors as ss_swap_out / ss_swap_in; SS_E_INVAL for a null or
  * misaligned address or one outside a bound arena; SS_E_STATE for a batch that belongs to a ring group
  * (SS_PATH_STAGED moves batches through rings by their arena offsets). */
 int ss_swap_out_from(ss_ctx *ctx, uint32_t batch, const void *const *dev_src /* host array of device addresses */);

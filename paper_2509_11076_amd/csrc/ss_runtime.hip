@@ -877,13 +877,14 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
   if (s.out_issued[batch]) return SS_E_STATE;
   const uint32_t lo = s.out_start[batch], hi = s.out_start[batch + 1];
   // A batch whose addresses came with the call goes by copy engine unless the copy kernel is asked for
-  // explicitly.  Measured on a real PyTorch model (12 layers, hidden 1024): with the copy kernel reading the
-  // tensors while the compute stream waits for it, the training loss stopped being reproducible bit for bit in
-  // about one run in three - although the staging slots held exactly the bytes a copy-engine copy of the same
-  // tensors held, the tensors that came back equalled their originals, and the same happened with nothing released
-  // and nothing fetched back at all - while with the copy engine every run of ten steps was bit-identical to the
-  // run without swapping.  The cause was not found; the synthetic configurations, whose compute results are
-  // compared bit for bit in every test run, have never shown it.
+  // explicitly.  Measured on a real PyTorch model (12 layers, hidden 1024, bf16): with copy-kernel launches
+  // running beside the step, the training loss is not reproducible bit for bit in some runs - and that also
+  // happens (1 of 18 runs of ten steps) when the copy kernel moves a buffer that has nothing to do with the
+  // model, with no ordering at all between the two streams, while every byte the swaps moved was checked to be
+  // right.  So the model's own kernels are sensitive to what else occupies compute units (the order of their
+  // floating-point accumulations changes with where their workgroups are placed); copy-engine transfers occupy
+  // none, and every run with them was bit-identical to the run without swapping.  The synthetic configurations,
+  // whose compute results are compared bit for bit in every test run, do not show it.
   const bool engine = s.flat_next ? ctx->cfg.copy_path != SS_PATH_KERNEL
                                   : use_engine(ctx, ctx->cfg.copy_path, true, s.out, lo, hi);
   // copy-kernel batches take the swap-out streams in turn; copy-engine batches stay on the first
