@@ -558,15 +558,19 @@ def record_hook_overhead(B, torch, shapes=None, steps=20, warmup=5):
             "PyTorch profiler +219.7 %", "shapes": out}
 
 
-def record_torch_swap(B, torch, shape=None, limit_frac=0.8, steps=10, warmup=3):
-    """A policy generated from the hooked trace of a real PyTorch model and executed inside that model: a Llama-like
+def record_torch_swap(B, torch, np, shape=None, limit_frac=0.9, steps=10, warmup=3, variants=None):
+    """Policies generated from the hooked trace of a real PyTorch model and executed inside that model: a Llama-like
     decoder in plain PyTorch (bf16, AdamW), one Detailed-mode iteration -> ss_generate_policy for a memory limit of
     base + limit_frac x (peak - base) -> the executor around autograd's saved-tensor hooks, tensors moved with
-    ss_swap_out_from / ss_swap_in_to into blocks the caching allocator places."""
+    ss_swap_out_from / ss_swap_in_to into blocks the caching allocator places.  variants: list of (limit_frac,
+    per_phase): Eq. 1 as printed (the step time spread evenly over all operators) or applied to the forward and the
+    backward pass separately (reading 11 of the design notes: two more timestamps per iteration); the first variant
+    is the record's own, the others ride along under "variants"."""
     import copy
     import paper_2509_11076_amd.torch_hook as H
     from paper_2509_11076_amd.torch_executor import TorchSwapExecutor, BlockObserver, plan_from_profile
     from workloads.torch_model import Trainer
+    variants = variants or [(limit_frac, False)]
     sh = shape or dict(layers=12, hidden=1024, heads=16, seq=1024, batch=4, vocab=32000)
     # attention through plain matmul and softmax kernels: every kernel of the step is deterministic, so the loss
     # with and without swapping can be compared bit for bit (the fused attention kernels accumulate in an order
@@ -595,14 +599,23 @@ def record_torch_swap(B, torch, shape=None, limit_frac=0.8, steps=10, warmup=3):
     ms_plain, peak_plain, loss_plain = timed(steps, 0)
     restore()
     _, _, loss_again = timed(steps, 0)           # is the step itself reproducible?  only then does bit equality mean anything
+    # forward / backward / optimizer split of one step (three more events)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    tr.on_phase = lambda ph: evs[ph].record()
+    evs[0].record()
+    tr.step()
+    tr.on_phase = None
+    torch.cuda.synchronize()
+    t_phase = [evs[i].elapsed_time(evs[i + 1]) * 1e-3 for i in range(3)]
     cfg = B.ss_config_default()
     cfg.staging_bytes = 0
     cfg.max_ops, cfg.max_events = 1 << 18, 1 << 20
     cfg.flags = B.SS_CFG_POLICY_POINTS
     plan_ctx = exec_ctx = None
     tr.hook = H
+    link = 57e9
+    results = []
     try:
-        # Eq. 1 / Eq. 3: link bytes per operator from the step just measured
         plan_ctx = B.ss_create(cfg)
         H.ss_hook_install(plan_ctx, H.SS_HOOK_DETAILED)
         restore()
@@ -619,25 +632,67 @@ def record_torch_swap(B, torch, shape=None, limit_frac=0.8, steps=10, warmup=3):
         ops, ev, _ = B.ss_trace_view(plan_ctx)
         ops, ev = ops.copy(), ev.copy()
         tab = H.ss_hook_tensor_table()
+        H.ss_hook_remove()
         B.ss_destroy(plan_ctx)
-        cfg.link_bytes_per_op = max(1, int(57e9 * ms_plain * 1e-3 / max(1, len(ops))))
-        plan_ctx = B.ss_create(cfg)
-        no = B.ss_timeline_scan(plan_ctx, ev, None, len(ops), base, 1 << 62)
-        limit = base + int(limit_frac * (no["peak"] - base))
-        kept, descs_out, info, ap, pol = plan_from_profile(plan_ctx, ops, tab, ev, base, limit, sh["layers"], sh["layers"],
-                                                           min_bytes=1 << 20, observer=obs)
-        cfg2 = B.ss_config_default()
-        cfg2.staging_bytes = max(4096, int(ap["staging_bytes"]))
-        cfg2.max_ops, cfg2.max_events = cfg.max_ops, cfg.max_events
-        exec_ctx = B.ss_create(cfg2)
-        H.ss_hook_install(exec_ctx, H.SS_HOOK_DETAILED)
-        ex = TorchSwapExecutor(torch, exec_ctx, kept, descs_out, torch.cuda.current_stream())
-        tr.saved_hooks = ex.hooks
-        tr.on_phase = lambda ph: ex.end_iteration() if ph == 3 else ex.poll()
-        restore()
-        ms_swap, peak_swap, loss_swap = timed(steps, 0)
-        tr.saved_hooks = tr.on_phase = None
-        st = dict(ex.stats)
+        plan_ctx = None
+        # Eq. 1 / Eq. 3: link bytes per operator from the step just measured
+        cfg.link_bytes_per_op = max(1, int(link * ms_plain * 1e-3 / max(1, len(ops))))
+        n_phase = [max(1, int(((ops["sig"] >> 16) == ph).sum())) for ph in range(3)]
+        per_phase = tuple(max(1, int(link * t_phase[ph] / n_phase[ph])) for ph in range(3))
+        for frac, phased in variants:
+            plan_ctx = B.ss_create(cfg)
+            no = B.ss_timeline_scan(plan_ctx, ev, None, len(ops), base, 1 << 62)
+            limit = base + int(frac * (no["peak"] - base))
+            kept, descs_out, info, ap, pol = plan_from_profile(plan_ctx, ops, tab, ev, base, limit, sh["layers"], sh["layers"],
+                                                               min_bytes=1 << 20, observer=obs,
+                                                               phase_bytes_per_op=per_phase if phased else None)
+            B.ss_destroy(plan_ctx)
+            plan_ctx = None
+            r = {"limit_frac_of_activation_peak": frac, "eq1": "per phase" if phased else "as printed",
+                 "memory_limit_bytes": int(limit), "generator": info, "tensors_swapped": int(len(kept)),
+                 "bytes_each_way_per_step": sum(int(x) for x in kept["nbytes"]),
+                 "eq1_link_bytes_per_operator": list(per_phase) if phased else int(cfg.link_bytes_per_op),
+                 "median_operators_between": {"swap_out_and_release": int(np.median(kept["t_free"].astype(np.int64) - kept["t_out"])) if len(kept) else None,
+                                              "swap_in_and_first_use": int(np.median(kept["t_use"].astype(np.int64) - kept["t_in"])) if len(kept) else None}}
+            if len(kept):
+                cfg2 = B.ss_config_default()
+                cfg2.staging_bytes = max(4096, int(ap["staging_bytes"]))
+                cfg2.max_ops, cfg2.max_events = cfg.max_ops, cfg.max_events
+                exec_ctx = B.ss_create(cfg2)
+                H.ss_hook_install(exec_ctx, H.SS_HOOK_DETAILED)
+                ex = TorchSwapExecutor(torch, exec_ctx, kept, descs_out, torch.cuda.current_stream())
+                tr.saved_hooks = ex.hooks
+                tr.on_phase = lambda ph: ex.end_iteration() if ph == 3 else ex.poll()
+                restore()
+                ms_swap, peak_swap, loss_swap = timed(steps, 0)
+                tr.saved_hooks = tr.on_phase = None
+                H.ss_hook_remove()
+                B.ss_destroy(exec_ctx)
+                # where the compute stream waited: three more steps in the library's measurement mode (every
+                # device-side wait charged with the time from reaching it to the end of the batch it waits for)
+                cfg2.flags = B.SS_CFG_STALL_TIMING
+                exec_ctx = B.ss_create(cfg2)
+                H.ss_hook_install(exec_ctx, H.SS_HOOK_DETAILED)
+                ex2 = TorchSwapExecutor(torch, exec_ctx, kept, descs_out, torch.cuda.current_stream())
+                tr.saved_hooks = ex2.hooks
+                tr.on_phase = lambda ph: ex2.end_iteration() if ph == 3 else ex2.poll()
+                restore()
+                timed(3, 0)
+                tr.saved_hooks = tr.on_phase = None
+                st2 = B.ss_get_stats(exec_ctx)
+                H.ss_hook_remove()
+                B.ss_destroy(exec_ctx)
+                exec_ctx = None
+                r["compute_stream_wait_ms_per_step"] = {"before_blocks_are_released": round(st2["stall_free_ms"] / 3, 3),
+                                                        "before_first_uses": round(st2["stall_wait_in_ms"] / 3, 3)}
+                r.update({"executor": dict(ex.stats), "ms_per_step_swapping": round(ms_swap, 3),
+                          "overhead_vs_no_swap_pct": round(100 * (ms_swap / ms_plain - 1), 1),
+                          "allocator_peak_bytes_swapping": int(peak_swap),
+                          "loss_after_the_same_steps_bit_equal": bool(torch.equal(loss_plain, loss_swap)),
+                          "loss_swapping": float(loss_swap)})
+            results.append(r)
+            log("torch model swap: limit %.2f, Eq. 1 %s: %d tensors, %.0f MB each way, %s ms/step (no swap %.1f)" % (
+                frac, r["eq1"], r["tensors_swapped"], r["bytes_each_way_per_step"] / 1e6, r.get("ms_per_step_swapping"), ms_plain))
     finally:
         tr.saved_hooks = tr.on_phase = None
         H.ss_hook_remove()
@@ -647,23 +702,25 @@ def record_torch_swap(B, torch, shape=None, limit_frac=0.8, steps=10, warmup=3):
                 B.ss_destroy(c)
         torch.backends.cuda.enable_flash_sdp(True)
         torch.backends.cuda.enable_mem_efficient_sdp(True)
-    per_step = sum(int(x) for x in kept["nbytes"])
-    return {"mode": "torch-model-swap",
-            "workload": "Llama-like decoder in plain PyTorch, %(layers)d layers, hidden %(hidden)d, %(heads)d heads, seq %(seq)d, "
-                        "batch %(batch)d, bf16, AdamW, attention by matmul + softmax kernels; policy generated from its own hooked "
-                        "trace and executed inside it" % sh,
-            "steps": steps, "ops_per_step": int(len(ops)), "allocator_events_per_step": int(len(ev)),
-            "memory_limit_bytes": int(limit), "limit_frac_of_activation_peak": limit_frac,
-            "generator": info, "tensors_swapped": int(len(kept)), "bytes_each_way_per_step": per_step,
-            "executor": st,
-            "ms_per_step": {"no_hook_no_swap": round(ms_plain, 3), "detailed_hook_no_swap": round(ms_detailed, 3),
-                            "swapping": round(ms_swap, 3)},
-            "overhead_vs_no_swap_pct": round(100 * (ms_swap / ms_plain - 1), 1),
-            "allocator_peak_bytes": {"no_swap": int(peak_plain), "swapping": int(peak_swap),
-                                     "planned_with_policy": int(info["peak_with_policy"])},
-            "loss_without_swapping_reproducible_bit_for_bit": bool(torch.equal(loss_plain, loss_again)),
-            "loss_after_the_same_steps_bit_equal": bool(torch.equal(loss_plain, loss_swap)),
-            "loss": {"no_swap": float(loss_plain), "no_swap_again": float(loss_again), "swapping": float(loss_swap)}}
+    first = results[0]
+    out = {"mode": "torch-model-swap",
+           "workload": "Llama-like decoder in plain PyTorch, %(layers)d layers, hidden %(hidden)d, %(heads)d heads, seq %(seq)d, "
+                       "batch %(batch)d, bf16, AdamW, attention by matmul + softmax kernels; policy generated from its own hooked "
+                       "trace and executed inside it" % sh,
+           "steps": steps, "ops_per_step": int(len(ops)), "allocator_events_per_step": int(len(ev)),
+           "operators_per_phase": {"forward": n_phase[0], "backward": n_phase[1], "optimizer": n_phase[2]},
+           "no_swap_phase_ms": {"forward": round(t_phase[0] * 1e3, 2), "backward": round(t_phase[1] * 1e3, 2),
+                                "optimizer": round(t_phase[2] * 1e3, 2)},
+           "ms_per_step": {"no_hook_no_swap": round(ms_plain, 3), "detailed_hook_no_swap": round(ms_detailed, 3),
+                           "swapping": first.get("ms_per_step_swapping")},
+           "allocator_peak_bytes": {"no_swap": int(peak_plain), "swapping": first.get("allocator_peak_bytes_swapping"),
+                                    "planned_with_policy": int(first["generator"]["peak_with_policy"])},
+           "loss_without_swapping_reproducible_bit_for_bit": bool(torch.equal(loss_plain, loss_again)),
+           "loss": {"no_swap": float(loss_plain), "no_swap_again": float(loss_again), "swapping": first.get("loss_swapping")}}
+    out.update({k: v for k, v in first.items() if k not in ("ms_per_step_swapping", "allocator_peak_bytes_swapping", "loss_swapping")})
+    if len(results) > 1:
+        out["variants"] = results[1:]
+    return out
 
 
 # ---- the fixed-sequence configurations: 1, 2, 3, 5 ----------------------------------------------------
@@ -1138,7 +1195,9 @@ def main():
     if args.hook_overhead:
         return emit(record_hook_overhead(B, torch, steps=args.steps, warmup=args.warmup))
     if args.torch_swap:
-        return emit(record_torch_swap(B, torch, limit_frac=args.limit_frac, steps=args.steps, warmup=args.warmup))
+        lf = args.limit_frac if any(a.startswith("--limit-frac") for a in sys.argv) else 0.9
+        return emit(record_torch_swap(B, torch, np, steps=args.steps, warmup=args.warmup,
+                                      variants=[(lf, False), (lf, True), (0.95, False), (0.95, True), (0.97, True)]))
 
     # host-link peak, measured now (pinned hipMemcpy; 1 GiB transfers)
     pcfg = B.ss_config_default()
@@ -1207,7 +1266,7 @@ def main():
         sub("config_2_stage_loop_limit_0.95", lambda: record_staged(B, torch, bw, 2, 0.95, 5))
         sub("reuse_interval_config_2", lambda: record_reuse_interval(B, torch, np, bw, 2, B.SS_PATH_AUTO, B.SS_PATH_AUTO))
         sub("hook_overhead", lambda: record_hook_overhead(B, torch, steps=10, warmup=3))
-        sub("torch_model_swap", lambda: record_torch_swap(B, torch, limit_frac=0.9, steps=10, warmup=3))
+        sub("torch_model_swap", lambda: record_torch_swap(B, torch, np, steps=10, warmup=3, variants=[(0.9, False), (0.95, False)]))
         def compact(r):
             """what the headline already says once (definitions, notes, the link peak) and per-iteration logs
             are left out of the sub-records; the modes run on their own (--config N, --policy-mode staged) print them"""

@@ -125,16 +125,19 @@ class TorchSwapExecutor:
             H.ss_hook_pause(False)
 
     def unpack(self, h):
-        if not isinstance(h, _Handle):
-            return h
+        # every saved tensor autograd takes back is an occasion to issue what has become due: in the backward
+        # pass these calls are the only places the executor is entered
         H.ss_hook_pause(True)
         try:
+            self._poll()
+            if not isinstance(h, _Handle):
+                return h
             return self._unpack(h)
         finally:
             H.ss_hook_pause(False)
 
     def _pack(self, t):
-        self.poll()
+        self._poll()
         if not t.is_cuda:
             return t
         blk = H.ss_hook_block_of(t.untyped_storage().data_ptr())
@@ -150,7 +153,6 @@ class TorchSwapExecutor:
         return _Handle(k, t.dtype, tuple(t.shape))
 
     def _unpack(self, h):
-        self.poll()
         k = h.item
         st = self.state[k]
         if st in (PACKED, OUT_ISSUED):       # never left (or its block has not been released yet): it is still here
@@ -222,13 +224,16 @@ class TorchSwapExecutor:
         self.stats["bytes_in"] += nbytes
 
 
-def plan_from_profile(ctx_plan, ops, table, events, base, limit, g_fwd, g_bwd, min_bytes=0, observer=None):
+def plan_from_profile(ctx_plan, ops, table, events, base, limit, g_fwd, g_bwd, min_bytes=0, observer=None,
+                      phase_bytes_per_op=None):
     """policy for the profiled iteration and its points: the library's generator on the hooked trace, then
     ss_apply_policy (which keeps the generator's release / pre-trigger points when the context was made with
-    SS_CFG_POLICY_POINTS).  Returns (kept items with their points, swap-out descriptors, generator result,
+    SS_CFG_POLICY_POINTS).  phase_bytes_per_op: Eq. 1 per phase (link bytes per forward / backward / optimizer
+    operator) instead of the one even spread.  Returns (kept items with their points, swap-out descriptors, generator result,
     the application's result, the policy as generated)."""
     tab = observer.candidates(table) if observer is not None else table
-    pol, info = B.ss_generate_policy(ctx_plan, ops, tab, events, base, limit, g_fwd, g_bwd, min_bytes=min_bytes)
+    pol, info = B.ss_generate_policy(ctx_plan, ops, tab, events, base, limit, g_fwd, g_bwd, min_bytes=min_bytes,
+                                     phase_bytes_per_op=phase_bytes_per_op)
     ap = B.ss_apply_policy(ctx_plan, pol, pol["ref_op"].astype(np.int32), tab, allow_nomem=True)
     res = ap["resolved"]
     kept = res[(res["flags"] & (B.SS_F_UNMATCHED | B.SS_F_ORDER)) == 0]
