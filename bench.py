@@ -27,9 +27,12 @@ import sys
 import time
 
 # Every stream of the process beyond HIP's hardware queues (4 by default) shares a queue with another stream
-# and stands still while that one's work runs.  The library uses up to four streams of its own (swap-out,
-# swap-in, the ring transfers, and the trace kernels on the swap-in stream) beside the compute stream.
-os.environ["GPU_MAX_HW_QUEUES"] = str(max(8, int(os.environ.get("GPU_MAX_HW_QUEUES") or 0)))
+# and stands still while that one's work runs; when it is the compute stream that a swap stream shares with,
+# a step of configuration 2 takes 211-239 ms instead of 119 ms.  The library uses up to three streams of its own
+# (swap-out, swap-in, the ring transfers; the trace kernels run on the swap-in stream) beside the compute
+# stream, and this process keeps a few more alive (PyTorch's pooled side streams of the measurement modes), so
+# the limit is raised to 32, above any count of live streams reached here.
+os.environ["GPU_MAX_HW_QUEUES"] = str(max(32, int(os.environ.get("GPU_MAX_HW_QUEUES") or 0)))
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
@@ -670,7 +673,7 @@ def record_torch_swap(B, torch, np, shape=None, limit_frac=0.9, steps=10, warmup
                 B.ss_destroy(exec_ctx)
                 # where the compute stream waited: three more steps in the library's measurement mode (every
                 # device-side wait charged with the time from reaching it to the end of the batch it waits for)
-                cfg2.flags = B.SS_CFG_STALL_TIMING
+                cfg2.flags = B.SS_CFG_STALL_TIMING | B.SS_CFG_TIMING
                 exec_ctx = B.ss_create(cfg2)
                 H.ss_hook_install(exec_ctx, H.SS_HOOK_DETAILED)
                 ex2 = TorchSwapExecutor(torch, exec_ctx, kept, descs_out, torch.cuda.current_stream())
@@ -680,6 +683,13 @@ def record_torch_swap(B, torch, np, shape=None, limit_frac=0.9, steps=10, warmup
                 timed(3, 0)
                 tr.saved_hooks = tr.on_phase = None
                 st2 = B.ss_get_stats(exec_ctx)
+                nb = kept["nbytes"].astype(np.float64)
+                rate = {}
+                for d_, name in ((0, "d2h"), (1, "h2d")):
+                    ms = B.ss_batch_ms_all(exec_ctx, d_)[:len(kept)].astype(np.float64)
+                    ok = ms > 0
+                    rate[name] = round(float(nb[ok].sum() / ms[ok].sum() / 1e6), 2) if ok.any() else None
+                r["transfer_gbps_while_copying"] = rate
                 H.ss_hook_remove()
                 B.ss_destroy(exec_ctx)
                 exec_ctx = None

@@ -111,6 +111,7 @@ struct ss_ctx {
   hipStream_t s_out[kMaxSwapStreams] = {}, s_in[kMaxSwapStreams] = {}, s_aux = nullptr;
   uint32_t n_s_out = 1, n_s_in = 1;
   hipStream_t s_flush = nullptr;    // copy-engine transfers out of the HBM ring
+  bool pooled_streams = true;       // the swap streams go back to the process-wide pool at ss_destroy
   uint8_t *ring = nullptr;          // HBM ring of the staged swap-out path (cfg.ring_bytes, in slots of cfg.ring_slot_bytes)
   uint8_t *ring_in = nullptr;       // the same for the staged swap-in path
   uint32_t n_slots = 0;

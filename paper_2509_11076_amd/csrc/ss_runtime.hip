@@ -5,6 +5,7 @@
 // by making the compute stream wait on the device instead of polling events on
 // the host).
 #include <algorithm>
+#include <mutex>
 #include <cstring>
 
 #include "ss_internal.h"
@@ -67,6 +68,37 @@ static uint32_t default_workgroups() { return 64; }
 static unsigned fence_flag(const ss_config_t &cfg) {
   return (cfg.flags & SS_CFG_SYSTEM_FENCE) ? 0u : (unsigned)hipEventDisableSystemFence;
 }
+
+// Swap streams are kept for the life of the process and handed from a destroyed context to the next one that
+// asks for the same role (device, direction, index): where the runtime places a new stream (its hardware queue,
+// the copy engine its transfers go to) changes with every stream created, and with it how much a transfer costs
+// the kernels that run beside it - a step of a PyTorch model measured at 34 ms took 42 ms in a later context of
+// the same process, with nothing else changed.  With the streams kept, every context of a process runs where the
+// first one did.
+namespace {
+struct pooled_stream { int device; int role; hipStream_t st; };
+std::mutex g_pool_mu;
+std::vector<pooled_stream> g_pool;      // streams not in use by a live context
+
+hipError_t pool_take(int device, int role, hipStream_t *st) {
+  {
+    std::lock_guard<std::mutex> lock(g_pool_mu);
+    for (size_t i = 0; i < g_pool.size(); ++i)
+      if (g_pool[i].device == device && g_pool[i].role == role) {
+        *st = g_pool[i].st;
+        g_pool.erase(g_pool.begin() + (long)i);
+        return hipSuccess;
+      }
+  }
+  return hipStreamCreateWithFlags(st, hipStreamNonBlocking);      // default priority
+}
+
+void pool_give(int device, int role, hipStream_t st) {
+  std::lock_guard<std::mutex> lock(g_pool_mu);
+  g_pool.push_back({device, role, st});
+}
+constexpr int kRoleOut = 0, kRoleIn = 16, kRoleFlush = 32;
+}  // namespace
 
 extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
   return ss_guard([&]() -> int {
@@ -139,14 +171,15 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
         for (uint32_t i = 0; i < cfg.copy_cus && rc == SS_OK; ++i) cu_mask[i / 32] |= 1u << (i % 32);
       }
     }
-    auto make_stream = [&](hipStream_t *st) {
-      if (cu_mask.empty()) return hipStreamCreateWithFlags(st, hipStreamNonBlocking);
+    ctx->pooled_streams = cu_mask.empty();          // streams with a unit mask are this context's own
+    auto make_stream = [&](hipStream_t *st, int role) {
+      if (cu_mask.empty()) return pool_take(ctx->device, role, st);
       return hipExtStreamCreateWithCUMask(st, (uint32_t)cu_mask.size(), cu_mask.data());
     };
     for (uint32_t i = 0; i < ctx->n_s_out && rc == SS_OK; ++i)
-      if ((e = make_stream(&ctx->s_out[i])) != hipSuccess) fail(SS_E_HIP, e);
+      if ((e = make_stream(&ctx->s_out[i], kRoleOut + (int)i)) != hipSuccess) fail(SS_E_HIP, e);
     for (uint32_t i = 0; i < ctx->n_s_in && rc == SS_OK; ++i)
-      if ((e = make_stream(&ctx->s_in[i])) != hipSuccess) fail(SS_E_HIP, e);
+      if ((e = make_stream(&ctx->s_in[i], kRoleIn + (int)i)) != hipSuccess) fail(SS_E_HIP, e);
     // The trace kernels (scan, match, align) run on the first swap-in stream: it is idle between iterations,
     // when they are called, and every further stream of the process has to share one of the few hardware
     // queues (4 per process here) with another - a stream that shares its queue with the stream of the
@@ -156,7 +189,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
       // gathers / scatters and direct batches of a direction share that direction's one stream; the copy-engine
       // transfers out of and into the rings share a third
       ctx->n_slots = (uint32_t)(cfg.ring_bytes / cfg.ring_slot_bytes);
-      if ((e = hipStreamCreateWithFlags(&ctx->s_flush, hipStreamNonBlocking)) != hipSuccess) fail(SS_E_HIP, e);
+      if ((e = pool_take(ctx->device, kRoleFlush, &ctx->s_flush)) != hipSuccess) fail(SS_E_HIP, e);
       if (rc == SS_OK && cfg.copy_path == SS_PATH_STAGED &&
           (e = hipMalloc((void **)&ctx->ring, (size_t)ctx->n_slots * cfg.ring_slot_bytes)) != hipSuccess)
         fail(SS_E_NOMEM, e);
@@ -227,11 +260,11 @@ extern "C" int ss_destroy(ss_ctx *ctx) {
   (void)sync_swap_streams(ctx);
   sched_release(ctx->sched);
   for (hipEvent_t ev : ctx->ev_ring) (void)hipEventDestroy(ev);
-  for (int i = 0; i < ss_ctx::kMaxSwapStreams; ++i) {
-    if (ctx->s_out[i]) (void)hipStreamDestroy(ctx->s_out[i]);
-    if (ctx->s_in[i]) (void)hipStreamDestroy(ctx->s_in[i]);
+  for (int i = 0; i < ss_ctx::kMaxSwapStreams; ++i) {       // joined above: nothing is pending on them
+    if (ctx->s_out[i]) ctx->pooled_streams ? pool_give(ctx->device, kRoleOut + i, ctx->s_out[i]) : (void)hipStreamDestroy(ctx->s_out[i]);
+    if (ctx->s_in[i]) ctx->pooled_streams ? pool_give(ctx->device, kRoleIn + i, ctx->s_in[i]) : (void)hipStreamDestroy(ctx->s_in[i]);
   }
-  if (ctx->s_flush) (void)hipStreamDestroy(ctx->s_flush);
+  if (ctx->s_flush) pool_give(ctx->device, kRoleFlush, ctx->s_flush);
   if (ctx->ring) (void)hipFree(ctx->ring);
   if (ctx->ring_in) (void)hipFree(ctx->ring_in);
   if (ctx->staging) (void)hipHostFree(ctx->staging);

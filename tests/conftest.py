@@ -2,9 +2,9 @@ import os
 import sys
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
-# a test with a compute stream of its own beside the library's four streams needs more than HIP's four
-# hardware queues per process, or two of the streams share one and take turns
-os.environ["GPU_MAX_HW_QUEUES"] = str(max(8, int(os.environ.get("GPU_MAX_HW_QUEUES") or 0)))
+# streams beyond HIP's hardware queues per process (four by default) share a queue with another stream and take
+# turns with it; the test process keeps many streams alive over its run, so the limit is raised well above them
+os.environ["GPU_MAX_HW_QUEUES"] = str(max(32, int(os.environ.get("GPU_MAX_HW_QUEUES") or 0)))
 
 
 def pytest_configure(config):
