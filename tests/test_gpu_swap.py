@@ -426,6 +426,74 @@ def test_link_probe_and_batch_windows(P, torch):
         P.ss_destroy(ctx)
 
 
+def test_contexts_alive_together_and_one_after_the_other_move_their_own_bytes(P, torch):
+    """swap streams are handed from a destroyed context to the next one; two contexts alive at once get streams of
+    their own: interleaved swaps of both, in both copy paths and through the rings, against oracle.swap_out /
+    swap_in of the same bytes, then a third context made after the first was destroyed"""
+    n, k = 1 << 20, 6
+
+    def setup(seed, path):
+        ctx = make_ctx(P, staging_bytes=k * n, copy_path=path, copy_path_in=path, ring_slot_bytes=2 * n, ring_bytes=4 * n)
+        arena = random_arena(torch, k * n, seed)
+        d = np.zeros(k, dtype=W.DESC_DT)
+        for t in range(k):
+            d[t] = ((k - 1 - t) * n, t * n, n, t, 0)            # staging order reverses the arena order
+        start = np.arange(k + 1, dtype=np.uint32)
+        P.ss_bind(ctx, arena.data_ptr(), k * n, torch.cuda.current_stream().cuda_stream)
+        P.ss_load_schedule(ctx, d, start, d, start)
+        return ctx, arena, d
+
+    def check(ctx, arena, d, before):
+        descs = [tuple(int(x) for x in r) for r in d.tolist()]
+        staging = np.zeros(k * n, dtype=np.uint8)
+        oracle.swap_out(before, staging, descs)
+        assert np.array_equal(P.ss_host_peek(ctx, 0, k * n), staging)
+        back = np.zeros(k * n, dtype=np.uint8)
+        oracle.swap_in(back, staging, descs)
+        assert np.array_equal(arena.cpu().numpy(), back)
+
+    a = setup(1, P.SS_PATH_KERNEL)
+    b = setup(2, P.SS_PATH_STAGED)
+    before = [x[1].cpu().numpy().copy() for x in (a, b)]
+    for t in range(k):
+        for ctx, _, _ in (a, b):
+            P.ss_swap_out(ctx, t)
+    for ctx, arena, _ in (a, b):
+        for t in range(k):
+            P.ss_sync(ctx, P.SS_SYNC_FREE, t)
+        arena.zero_()                                           # on the compute stream, after the device-side waits
+    for t in range(k):
+        for ctx, _, _ in (a, b):
+            P.ss_swap_in(ctx, t)
+    for ctx, _, _ in (a, b):
+        for t in range(k):
+            P.ss_sync(ctx, P.SS_SYNC_WAIT_IN, t)
+        P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+    torch.cuda.synchronize()
+    check(*a, before[0])
+    check(*b, before[1])
+    P.ss_destroy(a[0])
+    c = setup(3, P.SS_PATH_ENGINE)                              # takes over the first context's streams
+    try:
+        before_c = c[1].cpu().numpy().copy()
+        for t in range(k):
+            P.ss_swap_out(c[0], t)
+        for t in range(k):
+            P.ss_sync(c[0], P.SS_SYNC_FREE, t)
+        c[1].zero_()
+        for t in range(k):
+            P.ss_swap_in(c[0], t)
+        for t in range(k):
+            P.ss_sync(c[0], P.SS_SYNC_WAIT_IN, t)
+        P.ss_sync(c[0], P.SS_SYNC_DRAIN)
+        torch.cuda.synchronize()
+        check(*c, before_c)
+        assert P.ss_get_stats(b[0])["ring_batches"] > 0         # the second context went through its rings meanwhile
+    finally:
+        P.ss_destroy(b[0])
+        P.ss_destroy(c[0])
+
+
 @pytest.mark.timeout(300)
 def test_copy_kernel_on_gib_tensors_and_a_batch_above_4_gib(P, torch):
     """the copy kernel itself (both directions forced to it) on tensors of the budgeted configurations'
