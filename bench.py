@@ -793,16 +793,22 @@ def measure(B, torch, np, bw, o):
         ph = list(base.tr.op_phase)
         first_bwd = ph.index(1) if 1 in ph else len(ph)
         ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev_op = [torch.cuda.Event(enable_timing=True) for _ in range(base.tr.n_ops)]     # one more pass, an event per operator
         ev3[0].record()
         for i in range(base.tr.n_ops):
             if i == first_bwd:
                 ev3[1].record()
             base.compute.run_op(i)
+            ev_op[i].record()
         if first_bwd == len(ph):
             ev3[1].record()
         ev3[2].record()
         torch.cuda.synchronize()
         t_fwd, t_bwd = ev3[0].elapsed_time(ev3[1]) * 1e-3, ev3[1].elapsed_time(ev3[2]) * 1e-3
+        # no-swap time at which each operator has finished, scaled to the timed no-swap step (the events cost a little)
+        t_done_noswap = np.array([ev3[0].elapsed_time(e) for e in ev_op]) * 1e-3
+        t_done_noswap *= t_noswap / max(t_done_noswap[-1], 1e-9)
+        del ev_op
         n_fwd, n_bwd = max(1, first_bwd), max(1, len(ph) - first_bwd)
         base.close()
         del base
@@ -810,6 +816,7 @@ def measure(B, torch, np, bw, o):
         log("config %d: no-swap baseline done: %.1f ms/step" % (cfgno, t_noswap * 1e3))
     else:
         t_noswap, base_n_ops = 1e-9, 1
+        t_done_noswap = None
         t_fwd = t_bwd = 0.0
         n_fwd = n_bwd = 1
 
@@ -1022,6 +1029,18 @@ def measure(B, torch, np, bw, o):
     t_floor = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9), bytes_way / (bw["h2d_gbps"] * 1e9))
     # the last tensors to leave are the first needed back, so the two directions hardly overlap:
     t_floor_serial = max(t_noswap, bytes_way / (bw["d2h_gbps"] * 1e9) + bytes_way / (bw["h2d_gbps"] * 1e9))
+    # ... and the schedule has two ends the link cannot help with: nothing can leave before the operator after
+    # which the first swap-out is issued, and what follows the first use of the tensor that comes back last runs
+    # after the last byte has arrived (both taken from the step without swapping)
+    t_floor_sched = None
+    if t_done_noswap is not None and len(applied["actions"]):
+        a_ = applied["actions"]
+        outs_, uses_ = a_["op_idx"][a_["kind"] == B.SS_ACT_OUT], a_["op_idx"][a_["kind"] == B.SS_ACT_WAIT_IN]
+        if len(outs_) and len(uses_) and t_floor_serial > t_noswap:
+            head = float(t_done_noswap[min(int(outs_.min()), len(t_done_noswap) - 1)])
+            last_use = min(int(uses_.max()), len(t_done_noswap) - 1)
+            tail = float(t_done_noswap[-1] - (t_done_noswap[last_use - 1] if last_use > 0 else 0.0))
+            t_floor_sched = t_floor_serial + head + tail
     # roofline of the mover of the swap-out direction (the dominant one: it holds the forward pass back)
     if out_by == "copy kernel":
         kname, k_ms, k_peak = "ss_copy_kernel<to host>, pack launches (swap-out)", unit_ms[0], bw["d2h_gbps"]
@@ -1104,6 +1123,12 @@ def measure(B, torch, np, bw, o):
                       "overhead_vs_floor_pct": round(100 * (t_step / t_floor - 1), 1),
                       "floor_out_then_in_ms": round(t_floor_serial * 1e3, 3),
                       "overhead_vs_floor_out_then_in_pct": round(100 * (t_step / t_floor_serial - 1), 1),
+                      "floor_out_then_in_with_schedule_ends_ms": None if t_floor_sched is None else round(t_floor_sched * 1e3, 3),
+                      "overhead_vs_floor_with_schedule_ends_pct": None if t_floor_sched is None else round(100 * (t_step / t_floor_sched - 1), 1),
+                      "floor_note": "floor_out_then_in = bytes / D2H peak + bytes / H2D peak (what leaves last is needed back "
+                                    "first); with_schedule_ends adds, from the step without swapping, the time before the "
+                                    "operator the first swap-out follows and the time from the first use of the last "
+                                    "tensor to come back to the end of the step",
                       "link_bound": bool(t_floor_serial > 1.05 * t_noswap)},
         "roofline": roof,
         "library_statistics": lib_stats,
@@ -1282,7 +1307,7 @@ def main():
             are left out of the sub-records; the modes run on their own (--config N, --policy-mode staged) print them"""
             if not isinstance(r, dict):
                 return r
-            drop = ("link_peak_measured", "value_definition", "note", "traffic_note", "launches_timed_note")
+            drop = ("link_peak_measured", "value_definition", "note", "traffic_note", "launches_timed_note", "floor_note")
             out = {}
             for k, v in r.items():
                 if k in drop:
