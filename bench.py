@@ -567,7 +567,7 @@ def record_torch_swap(B, torch, np, shape=None, limit_frac=0.9, steps=10, warmup
     base + limit_frac x (peak - base) -> the executor around autograd's saved-tensor hooks, tensors moved with
     ss_swap_out_from / ss_swap_in_to into blocks the caching allocator places.  variants: list of (limit_frac,
     per_phase): Eq. 1 as printed (the step time spread evenly over all operators) or applied to the forward and the
-    backward pass separately (reading 11 of the design notes: two more timestamps per iteration); the first variant
+    backward pass separately (two more timestamps per iteration); the first variant
     is the record's own, the others ride along under "variants"."""
     import copy
     import paper_2509_11076_amd.torch_hook as H
