@@ -38,8 +38,11 @@ its steps, the order Eq. 2 prescribes, invariants and brute force):
  * SetFreeTime (Sec. 4.3.2): items in swap-out order (last forward use, then tensor id).  From
    the layer of the last forward use forward to the layer before the swap-in layer, the first
    layer with T_remaining > S takes the swap-out; none -> the layer before the swap-in layer
-   (flag LATE).  The block is released after the last operator of that layer (Sec. 5.2), but
-   never before the operator after the last forward use.
+   (flag LATE).  The swap-out is triggered right after the last forward use (Sec. 4.3.2, first
+   sentence), so of that use's own layer only the operators that follow the use can carry it:
+   there the test is min(T_remaining, bpo * operators of the layer after the use) > S.  The
+   block is released after the last operator of the layer found (Sec. 5.2), but never before
+   the operator after the last forward use.
 """
 NONE_OP = 0xFFFFFFFF
 F_LATE = 4
@@ -66,7 +69,7 @@ def logical_layers(phases, g_fwd, g_bwd, bpo):
             lo, hi = g * len(idx) // G, (g + 1) * len(idx) // G
             if hi > lo:
                 layers.append(dict(first=idx[lo], end=idx[hi - 1] + 1, type=ph,
-                                   remaining=bpo3[ph] * (hi - lo), ops=idx[lo:hi]))
+                                   remaining=bpo3[ph] * (hi - lo), ops=idx[lo:hi], bpo=bpo3[ph]))
     layers.sort(key=lambda L: L["first"])
     layer_of = [0] * n
     for li, L in enumerate(layers):
@@ -154,7 +157,10 @@ def generate_policy(tensors, per_op_memory, phases, limit, bpo, g_fwd, g_bwd, c_
         last = c["L_in"] - 1
         found = None
         for L in range(L0, last + 1):
-            if layers[L]["remaining"] > S:
+            avail = layers[L]["remaining"]
+            if L == L0:                        # only what follows the last forward use within its own layer
+                avail = min(avail, layers[L]["bpo"] * sum(1 for op in layers[L]["ops"] if op > lf))
+            if avail > S:
                 found = L
                 break
         if found is None:

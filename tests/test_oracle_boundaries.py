@@ -240,13 +240,13 @@ def test_a_layer_takes_a_transfer_only_if_strictly_more_time_remains():
 def test_swap_in_search_visits_every_layer_on_its_way_down():
     # two tensors of 300 bytes, both needed; 301 link bytes per one-operator layer.  The first takes the
     # layer before the use (11) and leaves 1 byte there; the second finds the next layer down (10).
-    # Swap-outs likewise: layer 2 takes the first, layer 3 the second (released after operator 3 either
-    # way: not before the operator following the last forward use)
+    # Swap-outs likewise: the layer of the last forward use (2) has no operator after that use, so layer 3
+    # takes the first (released after operator 3) and layer 4 the second (released after operator 4)
     tab = table([(0, 2, 12, 13, 300), (1, 2, 12, 13, 300), (6, 6, W.NONE_OP, 6, 500)])
     mem = live_set_peak(tab, {}, 16, 0)
     items, info = oracle.generate_policy(tab, mem, [0] * 8 + [1] * 8, 650, 301, 64, 64)
-    assert items == [(0, 0, 0, 0, 2, 3, 11, 12, 300), (1, 0, 1, 0, 2, 3, 10, 12, 300)]
-    assert [L[3] for L in info["layers"]][2:4] == [1, 1] and [L[3] for L in info["layers"]][10:12] == [1, 1]
+    assert items == [(0, 0, 0, 0, 2, 3, 11, 12, 300), (1, 0, 1, 0, 2, 4, 10, 12, 300)]
+    assert [L[3] for L in info["layers"]][2:5] == [301, 1, 1] and [L[3] for L in info["layers"]][10:12] == [1, 1]
 
 
 def test_fallback_layer_when_use_and_last_forward_use_sit_in_neighbouring_layers():

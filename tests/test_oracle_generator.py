@@ -63,13 +63,14 @@ def test_hand_worked_generation():
     #    Entries 3..17 drop by 250: 8 and 15 vanish, 9..14 keep 40.
     # B: use 20 in layer [18,21); last spanned entry 14 in layer [12,15); layer [15,18) has 300 > 100:
     #    swap-in before operator 15.  Entries 9..14 vanish: the list is empty, C is never looked at.
-    # SetFreeTime, swap-out order A then B: A's last forward use 1 is in layer [0,3) with 300 > 250:
-    #    released after operator 2 (50 left).  B: layer [0,3) has 50, not more than 100; layer [3,6) has
-    #    300: released after operator 5.
-    assert got[0] == (0, 0, 0, 0, 1, 2, 18, 22, 250)
-    assert got[1] == (1, 0, 1, 0, 2, 5, 15, 20, 100)
+    # SetFreeTime, swap-out order A then B.  A's last forward use 1 is in layer [0,3): only operator 2 follows
+    #    it there, worth 100 link bytes, not more than 250; layer [3,6) has 300 > 250: released after operator 5
+    #    (50 left there).  B's last forward use 2 is the last operator of layer [0,3): nothing of that layer
+    #    follows it; layer [3,6) has 50, not more than 100; layer [6,9) has 300: released after operator 8.
+    assert got[0] == (0, 0, 0, 0, 1, 5, 18, 22, 250)
+    assert got[1] == (1, 0, 1, 0, 2, 8, 15, 20, 100)
     assert info["residual"] == {}
-    assert [L[3] for L in info["layers"]] == [50, 200, 300, 300, 300, 200, 50, 300]
+    assert [L[3] for L in info["layers"]] == [300, 50, 200, 300, 300, 200, 50, 300]
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -208,11 +209,19 @@ def test_best_of_several_parameter_sets():
         oracle.generate_policy(tab, mem, phases, 400, 100, 4, 4, min_bytes=1000)
     with pytest.raises(Infeasible):
         oracle.generate_policy(tab, mem, phases, 400, 100, 1, 1)
-    # 80 link bytes per operator: 4 + 4 layers leave 8 operators over the limit (A is released late),
-    # 3 + 3 and 3 + 4 layers keep it, both with one LATE item and the same bytes: the lower index wins
+    # 80 link bytes per operator.  4 + 4 layers (240 each): no layer holds A, it goes LATE into [18,21) and its
+    # swap-out into [15,18): released after operator 17, all 8 operators stay over the limit.  3 + 3 layers (320
+    # each): A before operator 16, B LATE beside it; swap-outs: of A's own layer [0,4) only operators 2 and 3
+    # follow its last use (160, not more than 250), so [4,8) takes it (released after 7, 70 left); B: one operator
+    # of [0,4) follows (80), [4,8) has 70, [8,12) takes it (released after 11): operators 9..11 hold 690 - 250 =
+    # 440, three over the limit.  3 + 4 layers: the same release points (A LATE before 18, B before 15), the same
+    # three operators.  Equal on all counts: the lower index wins.
     sets80 = [dict(g_fwd=4, g_bwd=4), dict(g_fwd=3, g_bwd=3), dict(g_fwd=3, g_bwd=4)]
     items, chosen, info = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 80, sets80)
-    assert chosen == 1 and (info["n_over"], info["n_late"], info["bytes"]) == (0, 1, 350)
+    assert chosen == 1 and (info["n_over"], info["n_late"], info["bytes"]) == (3, 1, 350)
+    assert {it[2]: (it[5], it[6]) for it in items} == {0: (7, 16), 1: (11, 16)}
+    got2 = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 80, sets80[2:])
+    assert {it[2]: (it[5], it[6]) for it in got2[0]} == {0: (7, 18), 1: (11, 15)} and got2[2]["n_over"] == 3
     assert oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 80, sets80[:1])[2]["n_over"] == 8
     # 90 per operator: both keep the limit; 4 + 6 layers need one LATE item, 4 + 4 none: fewer LATE wins
     items, chosen, info = oracle.generate_policy_best(tab, ev, 24, 0, phases, 400, 90,
@@ -223,7 +232,7 @@ def test_best_of_several_parameter_sets():
 def test_per_phase_time_moves_release_points_later_in_a_fast_forward_pass():
     """the hand-worked trace with forward operators three times shorter than the average: a forward
     layer of 3 operators now has room for 3 x 34 = 102 bytes only, so A (250 bytes) finds no forward
-    layer and is released late, B (100) fits the first layer"""
+    layer and is released late, B (100) fits the layer after the one its last use ends"""
     phases = [0] * 12 + [1] * 12
     tab = table([(0, 1, 22, 23, 250), (1, 2, 20, 21, 100), (9, 10, 13, 14, 40), (8, 8, W.NONE_OP, 15, 300)])
     mem = live_set_peak(tab, {}, 24, 0)
@@ -231,11 +240,11 @@ def test_per_phase_time_moves_release_points_later_in_a_fast_forward_pass():
     got = {it[2]: it for it in items}
     # swap-ins as before (backward layers have 3 x 166 = 498): A before operator 18, B before operator 15.
     # swap-outs in order A, B: A's layer [0,3) has 102, not more than 250; neither has any forward layer;
-    # backward layers [12,15) has 498: A is released after operator 14 - inside the peak.  B then: layer
-    # [0,3) 102 > 100: that layer ends with operator 2, B's own last forward use, so the release comes
-    # after the operator that follows it, 3.
+    # backward layers [12,15) has 498: A is released after operator 14 - inside the peak.  B then: its last
+    # forward use 2 ends layer [0,3), nothing of that layer follows it; layer [3,6) has 102 > 100: released
+    # after operator 5.
     assert got[0] == (0, 0, 0, 0, 1, 14, 18, 22, 250)
-    assert got[1] == (1, 0, 1, 0, 2, 3, 15, 20, 100)
+    assert got[1] == (1, 0, 1, 0, 2, 5, 15, 20, 100)
     pe = sorted([(it[5], it[2], -it[8]) for it in items] + [(it[6], it[2], it[8]) for it in items], key=lambda e: e[0])
     ev = W.transformer.events_of(tab)
     after = oracle.timeline_scan(ev, pe, 24, 0, 400)
