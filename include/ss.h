@@ -472,7 +472,8 @@ typedef struct {
  * (Eq. 1 gives a layer link_bytes_per_op x its operator count, Eq. 3 makes a transfer cost its
  * size), never back into the peak period, subtracts the tensor from the entries it covers, and
  * repeats until no entry is left (SS_E_INFEASIBLE when candidates run out first); finally every
- * swap-out is given the first layer with time left from its last forward use on, which fixes the
+ * swap-out is given the first layer with time left from its last forward use on (of that use's own
+ * layer only the operators after the use count: the swap-out starts there, Sec. 4.3.2), which fixes the
  * release point.  Operator phases are read from ops[].sig >> 16.
  * policy_out receives the items in the order they were committed, with t_out, t_free, t_in, t_use
  * filled (use SS_CFG_POLICY_POINTS to have ss_apply_policy keep them); in: capacity *n_policy,

@@ -15,6 +15,7 @@ struct Layer {
   uint32_t first, end;     // operators [first, end)
   uint32_t type;           // 0 forward, 1 backward, 2 optimizer
   int64_t remaining;       // link bytes still free in this layer
+  uint64_t bpo;            // link bytes one operator of this layer is worth (Eq. 1)
 };
 
 struct Chosen {
@@ -41,7 +42,7 @@ void build_layers(const std::vector<uint32_t> &phase, uint32_t g_fwd, uint32_t g
       const size_t lo = (size_t)(g * idx.size() / G), hi = (size_t)((g + 1) * idx.size() / G);
       if (hi <= lo) continue;
       Raw r;
-      r.L = Layer{idx[lo], idx[hi - 1] + 1, ph, (int64_t)(bpo[ph] * (hi - lo))};
+      r.L = Layer{idx[lo], idx[hi - 1] + 1, ph, (int64_t)(bpo[ph] * (hi - lo)), bpo[ph]};
       r.ops.assign(idx.begin() + lo, idx.begin() + hi);
       raw.push_back(std::move(r));
     }
@@ -171,8 +172,18 @@ static int generate_core(uint64_t bpo, const ss_op_t *ops, uint32_t n_ops, const
     const uint32_t L0 = layer_of[t.last_fwd_use];
     const int64_t last = (int64_t)c.layer_in - 1;
     int64_t found = -1;
-    for (int64_t L = L0; L <= last; ++L)
-      if (layers[(size_t)L].remaining > (int64_t)t.nbytes) { found = L; break; }
+    for (int64_t L = L0; L <= last; ++L) {
+      int64_t avail = layers[(size_t)L].remaining;
+      if (L == (int64_t)L0) {
+        // the swap-out starts right after the last forward use: of that use's own layer only the operators
+        // that follow it can carry the transfer
+        uint64_t after = 0;
+        for (uint64_t op = (uint64_t)t.last_fwd_use + 1; op < layers[(size_t)L].end; ++op)
+          after += layer_of[op] == (uint32_t)L;
+        avail = std::min<int64_t>(avail, (int64_t)(layers[(size_t)L].bpo * after));
+      }
+      if (avail > (int64_t)t.nbytes) { found = L; break; }
+    }
     if (found < 0) {
       found = std::max<int64_t>(L0, last);
       c.late = true;

@@ -126,7 +126,7 @@ def test_generator_boundaries(P):
     assert gen(P, tab, phases, limit, BIG, min_bytes=301) is None
     # every layer visited on the way down
     tab = table([(0, 2, 12, 13, 300), (1, 2, 12, 13, 300), (6, 6, W.NONE_OP, 6, 500)])
-    assert gen(P, tab, [0] * 8 + [1] * 8, 650, 301) == [(0, 0, 0, 0, 2, 3, 11, 12, 300), (1, 0, 1, 0, 2, 3, 10, 12, 300)]
+    assert gen(P, tab, [0] * 8 + [1] * 8, 650, 301) == [(0, 0, 0, 0, 2, 3, 11, 12, 300), (1, 0, 1, 0, 2, 4, 10, 12, 300)]
     # fallback layer between neighbouring layers
     tab = table([(0, 1, 6, 7, 300), (3, 3, W.NONE_OP, 3, 200)])
     assert gen(P, tab, [0] * 4 + [1] * 4, 400, 10, g=1) == [(0, 0, 0, oracle.F_LATE, 1, 3, 4, 6, 300)]
