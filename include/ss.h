@@ -263,8 +263,13 @@ typedef struct {
  * auto paths, 65536 operators, 1048576 events). */
 int ss_config_default(ss_config_t *cfg /* host, out */);
 
-/* Create a context on the current HIP device: allocates pinned staging, the
- * swap-out / swap-in / auxiliary streams, and pinned trace arrays.
+/* Create a context on the current HIP device: allocates pinned staging and pinned trace arrays and takes
+ * the swap-out / swap-in (/ ring-transfer) streams (Sec. 5.2: the swaps run on streams of their own).
+ * The streams are non-blocking, at the default priority, and kept for the life of the process: ss_destroy
+ * hands them to the next context that asks for the same role, so every context of a process runs on the
+ * streams the first one got (where the runtime places a new stream changes how much a transfer costs the
+ * kernels beside it; streams with a compute-unit mask, copy_cus > 0, are the context's own).  Contexts
+ * alive at the same time get different streams.
  * SS_E_NOMEM if pinned memory is refused. */
 int ss_create(ss_ctx **out /* host, out */, const ss_config_t *cfg /* host, nullable */);
 int ss_destroy(ss_ctx *ctx);
