@@ -11,6 +11,7 @@
 // iteration (thousands of operators, up to 10^5 events) the work is latency-bound;
 // keeping one scan inside one workgroup makes a batch of scans (one per candidate
 // policy) a single launch.
+#include <algorithm>
 #include <cstring>
 
 #include "ss_internal.h"
@@ -79,29 +80,16 @@ __device__ inline int event_class(bool policy, int64_t delta) {
   return policy ? (delta >= 0 ? 0 : 3) : (delta >= 0 ? 1 : 2);
 }
 
-__device__ __forceinline__ void scan_body(const ScanArgs &a) {
-  __shared__ int64_t wsum[kWaves];
-  __shared__ int64_t red_val[kWaves];
-  __shared__ uint32_t red_idx[kWaves];
-  __shared__ uint32_t red_cnt[kWaves];
-  __shared__ uint32_t s_flags;
+// phase 1: gather class sums and counts per operator (integer atomics: any order, same result).
+// Neighbouring events mostly belong to the same operator, and 64 lanes adding to one address are
+// served one after the other: so each wavefront first folds every run of equal operators among its
+// 64 consecutive events (two wavefront prefix sums, two ballots) and only the first lane of a run
+// adds the run's totals.  Workgroup `wg` of `n_wg` takes every n_wg-th stretch of events; the
+// accumulators must have been cleared before any workgroup starts.  Returns this lane's share of the
+// flags (bit 0: operator out of range, bit 1: list not in operator order).
+__device__ __forceinline__ uint32_t gather_events(const ScanArgs &a, uint32_t wg, uint32_t n_wg) {
   const uint32_t tid = threadIdx.x;
   const uint32_t n = a.n_ops;
-  if (tid == 0) s_flags = 0;
-
-  // phase 0: clear the per-operator accumulators
-  for (uint64_t i = tid; i < 4ull * n; i += kThreads) {
-    a.csum[i] = 0;
-    a.ccnt[i] = 0;
-  }
-  __threadfence();
-  __syncthreads();
-
-  // phase 1: gather class sums and counts per operator (integer atomics: any order, same result).
-  // Neighbouring events mostly belong to the same operator, and 64 lanes adding to one address are
-  // served one after the other: so each wavefront first folds every run of equal operators among its
-  // 64 consecutive events (two wavefront prefix sums, two ballots) and only the first lane of a run
-  // adds the run's totals.
   uint32_t bad = 0;
   const int lane = tid & 63;
   const uint64_t below = lane ? (~0ull >> (64 - lane)) : 0ull;           // bits of the lanes before this one
@@ -110,7 +98,7 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a) {
     const uint64_t cnt = list ? a.n_pe : a.n_ev;
     const int cpos = list ? 0 : 1, cneg = list ? 3 : 2;
     constexpr int kAhead = 4;            // events in flight per lane: the loop is bound by load latency
-    for (uint64_t g0 = 0; g0 < cnt; g0 += (uint64_t)kAhead * kThreads) {
+    for (uint64_t g0 = (uint64_t)wg * kAhead * kThreads; g0 < cnt; g0 += (uint64_t)n_wg * kAhead * kThreads) {
       ss_event_t xs[kAhead];
       uint32_t before0[kAhead];          // lane 0 only: operator of the event before the wavefront's first
 #pragma unroll
@@ -170,7 +158,30 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a) {
       }
     }
   }
-  if (bad) atomicOr(&s_flags, bad);
+  return bad;
+}
+
+// `gathered`: phases 0 and 1 have been done by launches before this one (a.flags holds their flags)
+__device__ __forceinline__ void scan_body(const ScanArgs &a, bool gathered) {
+  __shared__ int64_t wsum[kWaves];
+  __shared__ int64_t red_val[kWaves];
+  __shared__ uint32_t red_idx[kWaves];
+  __shared__ uint32_t red_cnt[kWaves];
+  __shared__ uint32_t s_flags;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t n = a.n_ops;
+  if (tid == 0) s_flags = gathered ? *a.flags : 0;
+  if (!gathered) {
+    // phase 0: clear the per-operator accumulators
+    for (uint64_t i = tid; i < 4ull * n; i += kThreads) {
+      a.csum[i] = 0;
+      a.ccnt[i] = 0;
+    }
+    __threadfence();
+    __syncthreads();
+    const uint32_t bad = gather_events(a, 0, 1);
+    if (bad) atomicOr(&s_flags, bad);
+  }
   __threadfence();
   __syncthreads();
   const uint32_t flags = s_flags;
@@ -316,12 +327,48 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a) {
   }
 }
 
-__global__ __launch_bounds__(kThreads) void ss_scan_kernel(ScanArgs a) { scan_body(a); }
+__global__ __launch_bounds__(kThreads) void ss_scan_kernel(ScanArgs a) { scan_body(a, false); }
 
 // one workgroup per scan: candidate policies against the same trace in a single launch
 __global__ __launch_bounds__(kThreads) void ss_scan_batch_kernel(const ScanArgs *__restrict__ args) {
   const ScanArgs a = args[blockIdx.x];
-  scan_body(a);
+  scan_body(a, false);
+}
+
+// Long traces: the gather is the part that grows with the number of events (one workgroup takes 1.6 us per
+// thousand events), and it is the part that splits: the accumulators are cleared by one launch, gathered
+// into by a launch of many workgroups, and the rest (the scan over the operators, the timeline) runs in one
+// workgroup as before.
+__global__ __launch_bounds__(kThreads) void ss_scan_clear_kernel(ScanArgs a) {
+  const uint64_t total = 4ull * a.n_ops;
+  for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (uint64_t)gridDim.x * kThreads) {
+    a.csum[i] = 0;
+    a.ccnt[i] = 0;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) *a.flags = 0;
+}
+
+__global__ __launch_bounds__(kThreads) void ss_scan_gather_kernel(ScanArgs a) {
+  const uint32_t bad = gather_events(a, blockIdx.x, gridDim.x);
+  if (bad) atomicOr(a.flags, bad);
+}
+
+__global__ __launch_bounds__(kThreads) void ss_scan_finish_kernel(ScanArgs a) { scan_body(a, true); }
+
+constexpr uint64_t kSplitFromEvents = 32768;     // below this one workgroup is as fast as three launches
+
+void launch_scan(hipStream_t s, const ScanArgs &a) {
+  const uint64_t E = a.n_ev + a.n_pe;
+  if (E < kSplitFromEvents) {
+    hipLaunchKernelGGL(ss_scan_kernel, dim3(1), dim3(kThreads), 0, s, a);
+    return;
+  }
+  const uint64_t per_wg = 4ull * kThreads;         // one pass of the gather loop per workgroup
+  const uint32_t g_clear = (uint32_t)std::min<uint64_t>(256, (4ull * a.n_ops + kThreads - 1) / kThreads + 1);
+  const uint32_t g_gather = (uint32_t)std::min<uint64_t>(512, (std::max(a.n_ev, a.n_pe) + per_wg - 1) / per_wg);
+  hipLaunchKernelGGL(ss_scan_clear_kernel, dim3(g_clear), dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL(ss_scan_gather_kernel, dim3(g_gather), dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL(ss_scan_finish_kernel, dim3(1), dim3(kThreads), 0, s, a);
 }
 
 }  // namespace
@@ -409,7 +456,7 @@ extern "C" int ss_timeline_scan_static(ss_ctx *ctx, void *stream, const ss_event
   a.per_op = d_per_op; a.mre = d_mre; a.timeline = d_timeline;
   a.res = d_res;
   a.res_flags = 1;
-  hipLaunchKernelGGL(ss_scan_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream, a);
+  launch_scan((hipStream_t)stream, a);
   SS_HIP(hipGetLastError());
   return SS_OK;
 }
@@ -520,7 +567,7 @@ extern "C" int ss_timeline_scan(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev
     a.per_op = (int64_t *)(d + o_perop); a.mre = (int64_t *)(d + o_mre);
     a.timeline = (int64_t *)(d + o_tl);
     a.res = (ss_scan_result_t *)(d + o_res); a.flags = (uint32_t *)(d + o_flags);
-    hipLaunchKernelGGL(ss_scan_kernel, dim3(1), dim3(kThreads), 0, s, a);
+    launch_scan(s, a);
     SS_HIP(hipGetLastError());
     uint8_t *h = (uint8_t *)ctx->h_scratch;            // pinned: result + flags
     SS_HIP(hipMemcpyAsync(h, d + o_res, sizeof(ss_scan_result_t), hipMemcpyDeviceToHost, s));

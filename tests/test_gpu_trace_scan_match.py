@@ -418,6 +418,22 @@ def test_scan_long_runs_of_one_operator_sorted_and_not(P, ctx):
     lib = P.ss_timeline_scan(ctx, moved, pe, n_ops, 11, 1 << 28)
     assert_scan_equal(lib, ora, timeline=False)
     assert lib["sorted"] == 0
+    # at this length the gather runs in many workgroups: their flags must come together as in one
+    with pytest.raises(P.SsError) as e:
+        P.ss_timeline_scan(ctx, moved, pe, n_ops, 11, 1 << 28, want_timeline=True)
+    assert e.value.code == P.SS_E_ORDER
+    bad = ev.copy()
+    bad["op_idx"][len(bad) - 7] = n_ops                                 # one event beyond the last operator, far into the list
+    with pytest.raises(P.SsError) as e:
+        P.ss_timeline_scan(ctx, bad, pe, n_ops, 11, 1 << 28)
+    assert e.value.code == P.SS_E_INVAL
+    bad_pe = pe.copy()
+    bad_pe["op_idx"][-1] = n_ops + 5
+    with pytest.raises(P.SsError) as e:
+        P.ss_timeline_scan(ctx, ev, bad_pe, n_ops, 11, 1 << 28)
+    assert e.value.code == P.SS_E_INVAL
+    again = P.ss_timeline_scan(ctx, ev, pe, n_ops, 11, 1 << 28, want_timeline=True)       # and nothing is left behind
+    assert_scan_equal(again, ora)
 
 
 # ------------------------------------------------------------------ apply policy / greedy
