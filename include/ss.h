@@ -345,7 +345,7 @@ int ss_timeline_scan_batch(ss_ctx *ctx, const ss_event_t *ev, uint64_t n_ev, con
  * that forbid hipMalloc): the scan of ss_timeline_scan with nothing allocated, copied or waited
  * for.  Inputs and outputs are the caller's DEVICE arrays (same meaning, sizes and nullability as
  * above; d_res is required); the kernel's scratch is a static device array of 9.75 MiB that every GPU
- * the library runs on holds until the process ends.  The call enqueues one kernel on `stream` (a
+ * the library runs on holds until the process ends.  The call enqueues one kernel (three from 32,768 events on) on `stream` (a
  * hipStream_t of the context's device, which must be current; NULL = the null stream) and returns;
  * results are valid once that stream has reached the kernel's end.
  * Limits: n_ops <= 65,536 and n_ev + n_pe <= 262,144, else SS_E_CAPACITY (nothing is enqueued).

@@ -378,7 +378,7 @@ void launch_scan(hipStream_t s, const ScanArgs &a) {
 // Same kernel, but its scratch (per-operator class sums and counts, entry totals, event
 // positions, per-event class prefixes) lives in a static device array instead of memory the
 // library allocates, and inputs and outputs are the caller's device arrays: the call only
-// enqueues one kernel on the caller's stream.
+// enqueues the scan's kernels (one, or three for a long trace) on the caller's stream.
 
 constexpr uint32_t kStaticMaxOps = 65536;
 constexpr uint64_t kStaticMaxEvents = 262144;
