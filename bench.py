@@ -343,6 +343,14 @@ def record_mover_table(B, torch, np, bw, args):
     # the whole table runs on a compute stream of its own: swap streams with a compute-unit mask synchronise with
     # the null stream (the runtime has no non-blocking form of them)
     own = torch.cuda.Stream()
+    # the side stream of the last part is made and used now, before any context of the library exists: where a
+    # stream lands among the hardware queues decides what a wait between two of them costs (40 us or 0.9 ms per
+    # round trip were measured for the same loop)
+    side = torch.cuda.Stream()
+    for st_ in (own, side):
+        with torch.cuda.stream(st_):
+            torch.zeros(1, device="cuda")
+    torch.cuda.synchronize()
     torch.cuda.set_stream(own)
     for p_out, p_in, kw in combos:
         o = argparse.Namespace(**vars(args))
@@ -364,7 +372,6 @@ def record_mover_table(B, torch, np, bw, args):
     base = SwapRun(B, torch, 2, swap=False)
     n = base.tr.n_ops
     fb = list(base.tr.op_phase).index(1)
-    side = torch.cuda.Stream()
     nbytes = 256 << 20
     host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
     dev = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
