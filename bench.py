@@ -436,6 +436,105 @@ def record_mover_table(B, torch, np, bw, args):
             "rows": rows, "noswap_backward_pass_ms": costs}
 
 
+def record_transfer_cost_table(B, torch, np):
+    """What 2.6-2.8 GB of host-to-device (and device-to-host) traffic costs a compute stream that nothing orders
+    against it: the backward pass of configuration 2 without swapping, timed with HIP events, beside copy-engine
+    transfers with and without another command on their stream, and beside the library's swap-ins by copy engine and by
+    copy kernel, in few large and in many small batches."""
+    from workloads.harness import SwapRun
+    from workloads.layouts import DESC_DT
+    side = torch.cuda.Stream()          # made first: where a stream lands among the hardware queues matters
+    with torch.cuda.stream(side):
+        torch.zeros(1, device="cuda")
+    torch.cuda.synchronize()
+    base = SwapRun(B, torch, 2, swap=False)
+    n = base.tr.n_ops
+    fb = list(base.tr.op_phase).index(1)
+    M = 1 << 20
+    host = torch.empty(2816 * M, dtype=torch.uint8, pin_memory=True)
+    dev = torch.empty(2816 * M, dtype=torch.uint8, device="cuda")
+
+    def backward_ms(traffic):
+        e1, e2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(n):
+            if i == fb:
+                e1.record()
+                if traffic is not None:
+                    traffic()
+            base.compute.run_op(i)
+        e2.record()
+        torch.cuda.synchronize()
+        return e1.elapsed_time(e2)
+
+    def best(traffic, after=None):
+        out = []
+        for _ in range(4):
+            out.append(backward_ms(traffic))
+            if after is not None:
+                after()
+        return round(min(out[1:]), 2)
+
+    def plain(d2h, extra):
+        def go():
+            with torch.cuda.stream(side):
+                for k in range(11):
+                    a, b = host[k * 256 * M:(k + 1) * 256 * M], dev[k * 256 * M:(k + 1) * 256 * M]
+                    (a.copy_(b, non_blocking=True) if d2h else b.copy_(a, non_blocking=True))
+                    if extra == "event":
+                        torch.cuda.Event().record(side)
+                    elif extra == "kernel":
+                        dev[:64].zero_()
+        return go
+    rows = [{"traffic": "none", "backward_pass_ms": best(None)}]
+    for d2h in (False, True):
+        for extra, what in ((None, "nothing else on their stream"), ("event", "an event recorded on their stream after each"),
+                            ("kernel", "a one-block kernel on their stream after each")):
+            rows.append({"traffic": "11 copy-engine transfers of 256 MiB %s (PyTorch copy_), %s" % (
+                "device to host" if d2h else "host to device", what), "backward_pass_ms": best(plain(d2h, extra))})
+            log("transfer cost table: %s" % rows[-1])
+    del host
+    for path, pname in ((B.SS_PATH_ENGINE, "copy engine"), (B.SS_PATH_KERNEL, "ss_copy_kernel")):
+        for nb in (11, 33, 132):
+            nbytes = (2640 // nb) * M
+            cfg = B.ss_config_default()
+            cfg.staging_bytes = nb * nbytes
+            cfg.copy_path = B.SS_PATH_KERNEL
+            cfg.copy_path_in = path
+            c = B.ss_create(cfg)
+            try:
+                B.ss_bind(c, dev.data_ptr(), nb * nbytes, side.cuda_stream)      # ordered after `side`, which stays empty
+                d = np.zeros(nb, dtype=DESC_DT)
+                for b in range(nb):
+                    d[b] = (b * nbytes, b * nbytes, nbytes, b, 0)
+                st = np.arange(nb + 1, dtype=np.uint32)
+                B.ss_load_schedule(c, d, st, d, st, np.arange(nb, dtype=np.uint32))
+
+                def fill():
+                    for b in range(nb):
+                        B.ss_swap_out(c, b)
+                    torch.cuda.synchronize()
+
+                def go():
+                    for b in range(nb):
+                        B.ss_swap_in(c, b)
+
+                def after():
+                    B.ss_sync(c, B.SS_SYNC_DRAIN)
+                    fill()
+                fill()
+                ms = best(go, after)
+                B.ss_sync(c, B.SS_SYNC_DRAIN)
+                rows.append({"traffic": "the library's swap-ins by %s, %d batches of %d MiB (a marker wait before, a done-event after each)"
+                                        % (pname, nb, nbytes // M), "backward_pass_ms": ms})
+                log("transfer cost table: %s" % rows[-1])
+            finally:
+                B.ss_destroy(c)
+    base.close()
+    return {"mode": "transfer-cost-table",
+            "workload": "backward pass of configuration 2 without swapping (350 operators) beside 2.6-2.8 GB of traffic that "
+                        "nothing orders against it; HIP events on the compute stream, best of three", "rows": rows}
+
+
 def record_reuse_interval(B, torch, np, bw, cfgno, path, path_in):
     from paper_2509_11076_amd.executor import run_iteration_dispatch
     from workloads.harness import SwapRun
@@ -1207,6 +1306,9 @@ def main():
     ap.add_argument("--path-table", action="store_true",
                     help="GB/s of one batch of equal-size tensors at scattered arena offsets, per size class, "
                          "copy kernel against per-tensor copy-engine calls, both directions (no compute stream work)")
+    ap.add_argument("--transfer-cost-table", action="store_true",
+                    help="what copy-engine transfers (with and without another command on their stream) and the library's "
+                         "swap-ins by engine and by kernel cost a compute stream that nothing orders against them")
     ap.add_argument("--mover-table", action="store_true",
                     help="configuration 2 with every mover per direction inside the step (copy kernel, copy engine, the "
                          "HBM rings), and what each mover costs a compute stream that does not wait for it")
@@ -1254,6 +1356,8 @@ def main():
         return emit(run_swap_only(B, torch, args, paths[args.path], paths[args.path_in or args.path]))
     if args.path_table:
         return emit(record_path_table(B, torch, np, bw))
+    if args.transfer_cost_table:
+        return emit(record_transfer_cost_table(B, torch, np))
     if args.mover_table:
         return emit(record_mover_table(B, torch, np, bw, args))
     if args.reuse_interval:
