@@ -480,7 +480,7 @@ def record_transfer_cost_table(B, torch, np):
                 for k in range(11):
                     a, b = host[k * 256 * M:(k + 1) * 256 * M], dev[k * 256 * M:(k + 1) * 256 * M]
                     (a.copy_(b, non_blocking=True) if d2h else b.copy_(a, non_blocking=True))
-                    if extra == "event":
+                    if extra == "event" or (extra == "event_first" and k == 0) or (extra == "event_last" and k == 10):
                         torch.cuda.Event().record(side)
                     elif extra == "kernel":
                         dev[:64].zero_()
@@ -488,7 +488,11 @@ def record_transfer_cost_table(B, torch, np):
     rows = [{"traffic": "none", "backward_pass_ms": best(None)}]
     for d2h in (False, True):
         for extra, what in ((None, "nothing else on their stream"), ("event", "an event recorded on their stream after each"),
+                            ("event_last", "one event recorded after the last of them"),
+                            ("event_first", "one event recorded after the first of them"),
                             ("kernel", "a one-block kernel on their stream after each")):
+            if d2h and extra in ("event_last", "event_first"):
+                continue
             rows.append({"traffic": "11 copy-engine transfers of 256 MiB %s (PyTorch copy_), %s" % (
                 "device to host" if d2h else "host to device", what), "backward_pass_ms": best(plain(d2h, extra))})
             log("transfer cost table: %s" % rows[-1])
