@@ -1,8 +1,8 @@
 """Walk one iteration's action schedule around the caller's operators.
 
-Sec. 5 (first paragraph) of the SmartSwap paper: the executor issues the
-policy's swap operations at their designated positions of the iteration.  This
-module only sequences calls into libss (swap-out, release, swap-in, wait) around
+Sec. 5 (first paragraph) of the SmartSwap paper: each swap operation of the
+policy belongs to one operator of the iteration, and the executor issues it when
+the iteration gets there.  This module only sequences calls into libss (swap-out, release, swap-in, wait) around
 a caller-supplied `run_op(i)` that enqueues operator i on the compute stream.
 It holds no arithmetic of the method.
 """
