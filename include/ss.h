@@ -46,7 +46,9 @@ enum {
   /* -5 and -7 are not used */
   SS_E_ORDER = -6,      /* events not in operator order where that is required */
   SS_E_STATE = -8,      /* call out of sequence (e.g. swap before a schedule is loaded) */
-  SS_E_CAPACITY = -9    /* a caller-provided output array or a configured maximum is too small */
+  SS_E_CAPACITY = -9,   /* a caller-provided output array or a configured maximum is too small */
+  SS_E_TIMEOUT = -10    /* SS_CFG_BARE_RING: a stream gave up waiting for a ring transfer (flag_wait_ms); the
+                           bytes moved in this iteration are not to be trusted */
 };
 
 /* ---- records (all little-endian, naturally aligned, no padding) ---------- */
@@ -120,9 +122,22 @@ enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch
        SS_CFG_POLICY_POINTS = 16,/* ss_apply_policy keeps each item's own t_free / t_in (as made by
                                     ss_generate_policy), moved along with the tensor's last forward /
                                     first backward use, instead of re-timing with the link model  */
-       SS_CFG_STALL_TIMING = 32 };/* measurement mode: one more event on the compute stream before every
+       SS_CFG_STALL_TIMING = 32, /* measurement mode: one more event on the compute stream before every
                                     device-side wait, and SS_SYNC_DRAIN also waits for the compute stream
                                     and adds the waits' durations to ss_stats_t.stall_*_ms          */
+       SS_CFG_BARE_RING = 64 };  /* SS_PATH_STAGED: the copy-engine transfers out of and into the rings are
+                                    enqueued with nothing before and nothing behind them on their stream
+                                    but other such transfers.  A copy-engine transfer that shares its stream
+                                    with an event record or a wait slows the kernels of every other stream
+                                    by 11-16 % for as long as it runs; a stream of transfers only does
+                                    not.  So a thread of the library's own holds each transfer back on the
+                                    host until what it has to wait for is complete, and its completion is
+                                    published by a second small transfer behind it that writes a sequence
+                                    number into device memory; a stream that needs the transfer's bytes
+                                    waits for that number in a one-wave kernel which polls it, sleeping in
+                                    between, and gives up after flag_wait_ms (SS_SYNC_DRAIN then returns
+                                    SS_E_TIMEOUT).  The transfers themselves carry no events: ss_batch_ms
+                                    and its like return SS_E_STATE for directions 2 and 3               */
 
 typedef struct {
   uint64_t staging_bytes;     /* pinned host staging to allocate at ss_create                */
@@ -185,6 +200,9 @@ typedef struct {
                                  the link rate; the dispatch thread waits only where the compute stream is waiting
                                  for the same transfers                                                      */
   uint32_t engine_window_out; /* the same for copy-engine swap-out batches and ss_swap_out                     */
+  uint32_t flag_wait_ms;      /* SS_CFG_BARE_RING: longest a stream polls for a transfer's sequence number before it
+                                 gives up and goes on, in ms (0 = 30,000; at most 600,000)                    */
+  uint32_t reserved0;
 } ss_config_t;
 
 /* ---- results ---------------------------------------------------------------- */

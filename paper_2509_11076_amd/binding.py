@@ -37,10 +37,12 @@ ACTION_DT = np.dtype([("op_idx", "<u4"), ("kind", "<u4"), ("tensor_id", "<u4"), 
 
 SS_OK = 0
 SS_E_INVAL, SS_E_NOMEM, SS_E_HIP, SS_E_INFEASIBLE, SS_E_ORDER, SS_E_STATE, SS_E_CAPACITY = -1, -2, -3, -4, -6, -8, -9
+SS_E_TIMEOUT = -10
 SS_ACT_IN, SS_ACT_WAIT_IN, SS_ACT_OUT, SS_ACT_FREE = 0, 1, 2, 3
 SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE, SS_PATH_STAGED = 0, 1, 2, 3
 SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE, SS_CFG_POLICY_POINTS = 1, 2, 4, 8, 16
 SS_CFG_STALL_TIMING = 32
+SS_CFG_BARE_RING = 64
 SS_SYNC_FREE, SS_SYNC_WAIT_IN, SS_SYNC_DRAIN = 0, 1, 2
 SS_MATCH_STEP_STAGE, SS_MATCH_HISTOGRAM, SS_MATCH_ALIGN = 1, 2, 4
 SS_LEVEL_ALIGN = 3
@@ -61,7 +63,8 @@ class ss_config_t(C.Structure):
                 ("ring_bytes", C.c_uint64), ("ring_slot_bytes", C.c_uint64),
                 ("gather_workgroups", C.c_uint32), ("ring_taper", C.c_uint32),
                 ("copy_desc_lookup", C.c_uint32), ("copy_cus", C.c_uint32),
-                ("engine_window_in", C.c_uint32), ("engine_window_out", C.c_uint32)]
+                ("engine_window_in", C.c_uint32), ("engine_window_out", C.c_uint32),
+                ("flag_wait_ms", C.c_uint32), ("reserved0", C.c_uint32)]
 
 
 class ss_scan_result_t(C.Structure):

@@ -203,7 +203,28 @@ __global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nby
   if (blockIdx.x == 0 && threadIdx.x < (nbytes & 15u)) dst[(n16 << 4) + threadIdx.x] = (uint8_t)word;
 }
 
+// Holds its stream until the sequence number at `flag` (device memory, written by a copy-engine transfer) has
+// reached `want`.  One wave; its first lane polls with system-scope loads, which see what the copy engine wrote
+// without a kernel boundary in between, and sleeps between polls so that it takes next to no issue slots from
+// the waves beside it.  The wait is bounded: after `limit_ticks` of the 100 MHz wall clock the lane sets *timeouts
+// (pinned host memory, touched on this path only) and the kernel ends like any other.
+__global__ void ss_wait_flag_kernel(const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *timeouts) {
+  if (threadIdx.x != 0) return;
+  const uint64_t t0 = wall_clock64();
+  while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < want) {
+    if (wall_clock64() - t0 > limit_ticks) {
+      __hip_atomic_store(timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      return;
+    }
+    __builtin_amdgcn_s_sleep(32);
+  }
+}
+
 }  // namespace
+
+void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *timeouts) {
+  hipLaunchKernelGGL(ss_wait_flag_kernel, dim3(1), dim3(64), 0, s, flag, want, limit_ticks, timeouts);
+}
 
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,
                     uint8_t *staging, const ss_desc_t *d_descs, const uint32_t *d_chunk0,

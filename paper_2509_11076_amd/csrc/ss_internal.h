@@ -75,6 +75,11 @@ struct ss_sched {
   std::vector<int32_t> in_slot_owner;               // per slot of the swap-in ring: group whose bytes it holds, -1 = none
   std::vector<hipEvent_t> ev_fetched[2], ev_fetch_start[2];   // per group
   std::vector<uint8_t> in_group_state_drained;
+  // SS_CFG_BARE_RING: sequence numbers of the ring transfers in place of their events (0 = none)
+  std::vector<uint64_t> flush_seq;                  // per swap-out batch, this iteration: the transfer that carries it
+  std::vector<uint64_t> group_last_flush_seq;       // per swap-out group: its latest transfer
+  std::vector<uint64_t> fetch_seq;                  // per swap-in group: its transfer into the ring
+  uint64_t last_flush_seq = 0;                      // the most recent transfer out of the ring
   int phase = 0;                                    // event set of the iteration being issued
   bool drained_once = false;                        // set `phase ^ 1` holds a completed iteration
   ss_desc_t *d_out = nullptr, *d_in = nullptr;    // device copies of the descriptors
@@ -93,6 +98,8 @@ struct ss_sched {
   std::vector<uint32_t> act_start;
   bool have_actions = false;
 };
+
+struct ss_engine_queue;   // SS_CFG_BARE_RING: the thread that issues the ring transfers, and its state (ss_runtime.hip)
 
 struct ss_ctx {
   ss_config_t cfg;
@@ -115,6 +122,7 @@ struct ss_ctx {
   uint8_t *ring = nullptr;          // HBM ring of the staged swap-out path (cfg.ring_bytes, in slots of cfg.ring_slot_bytes)
   uint8_t *ring_in = nullptr;       // the same for the staged swap-in path
   uint32_t n_slots = 0;
+  ss_engine_queue *eq = nullptr;    // SS_CFG_BARE_RING
   std::vector<hipEvent_t> ev_ring;  // compute-stream markers, used round-robin
   size_t ev_next = 0;
   // trace
@@ -181,6 +189,8 @@ void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to
 // one tensor by its two addresses, no descriptor table (16-byte aligned on both sides)
 void ss_launch_copy_flat(hipStream_t s, uint32_t workgroups, const uint8_t *src, uint8_t *dst, uint64_t nbytes);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
+// one wave that holds stream s until *flag >= want (ss_wait_flag_kernel; bounded by limit_ticks of 10 ns)
+void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *timeouts);
 
 // sequence aligner (ss_align.hip): ref_to_cur has n entries
 int ss_align_core(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, const ss_op_t *cur, uint32_t m,

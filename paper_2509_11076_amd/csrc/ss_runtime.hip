@@ -5,8 +5,12 @@
 // by making the compute stream wait on the device instead of polling events on
 // the host).
 #include <algorithm>
-#include <mutex>
+#include <atomic>
+#include <condition_variable>
 #include <cstring>
+#include <deque>
+#include <mutex>
+#include <thread>
 
 #include "ss_internal.h"
 
@@ -36,6 +40,7 @@ extern "C" const char *ss_strerror(int code) {
     case SS_E_ORDER: return "events not in operator order";
     case SS_E_STATE: return "call out of sequence";
     case SS_E_CAPACITY: return "output array or configured capacity too small";
+    case SS_E_TIMEOUT: return "a stream gave up waiting for a ring transfer";
     default: return "unknown error";
   }
 }
@@ -100,6 +105,163 @@ void pool_give(int device, int role, hipStream_t st) {
 constexpr int kRoleOut = 0, kRoleIn = 16, kRoleFlush = 32;
 }  // namespace
 
+// ---- SS_CFG_BARE_RING: the ring transfers, issued by a thread of the library's own -------------------
+//
+// What the dispatch thread would put before a transfer on its stream (waits for events) the thread does on the
+// host: it takes the jobs in the order they were pushed, waits for each job's events (all recorded before the
+// push), and only then enqueues the transfer, followed by a transfer of kFlagBytes whose first word is the job's
+// sequence number, into the flag in device memory.  The stream thus carries copy-engine transfers and nothing
+// else.  Sequence numbers grow by one per job for the life of the context; the stream runs its transfers in
+// order, so "flag >= n" means that job n and every job before it are complete.  Every dependency of a job is on
+// work issued before it was pushed, and none of that work waits for a later job, so the queue cannot block
+// itself; a job whose events are late only holds back the jobs behind it.
+struct ss_engine_job {
+  hipEvent_t pre[3];
+  int n_pre;
+  void *dst;
+  const void *src;
+  size_t bytes;
+  hipMemcpyKind kind;
+  uint64_t seq;
+};
+
+struct ss_engine_queue {
+  static constexpr size_t kFlagBytes = 65536;   // an 8-byte transfer is done by a kernel of the runtime, not by the copy engine
+  static constexpr uint64_t kSources = 32;      // source buffers of the flag transfers, reused in turn
+  int device = 0;
+  hipStream_t stream = nullptr;                 // the context's stream for ring transfers
+  uint64_t *d_flag = nullptr;                   // device memory, kFlagBytes; first word = last complete job
+  uint8_t *h_src = nullptr;                     // pinned, kSources * kFlagBytes
+  uint32_t *h_timeouts = nullptr, *d_timeouts = nullptr;   // a pinned word and its device address
+  uint64_t limit_ticks = 0;                     // bound of a wait, in ticks of 10 ns
+  std::thread th;
+  std::mutex mu;
+  std::condition_variable cv, cv_idle;
+  std::deque<ss_engine_job> q;
+  bool stop = false, busy = false, started = false;
+  uint64_t next_seq = 1;                        // dispatch thread
+  uint64_t enqueued_seq = 0;                    // last job handed to the stream (under mu)
+  uint64_t synced_seq = 0;                      // the thread's own: jobs up to here are known to be complete
+  std::atomic<int> hip_error{0};                // first HIP error the thread met
+  uint64_t waited_out = 0, waited_in = 0;       // dispatch thread: highest number a wait on the swap-out / swap-in stream covers
+};
+
+static void engine_thread(ss_engine_queue *q) {
+  auto note = [q](hipError_t e) {
+    if (e == hipSuccess) return;
+    int none = 0;
+    q->hip_error.compare_exchange_strong(none, (int)e);
+    (void)hipGetLastError();
+  };
+  note(hipSetDevice(q->device));
+  for (;;) {
+    ss_engine_job job;
+    {
+      std::unique_lock<std::mutex> lk(q->mu);
+      q->cv.wait(lk, [q] { return q->stop || !q->q.empty(); });
+      if (q->q.empty()) return;                 // asked to stop, nothing left
+      job = q->q.front();
+      q->q.pop_front();
+      q->busy = true;
+    }
+    for (int i = 0; i < job.n_pre; ++i) note(hipEventSynchronize(job.pre[i]));
+    if (job.seq > q->synced_seq + ss_engine_queue::kSources) {    // the source buffer's previous transfer may still be queued
+      note(hipStreamSynchronize(q->stream));
+      q->synced_seq = job.seq - 1;
+    }
+    uint64_t *src = (uint64_t *)(q->h_src + (size_t)(job.seq % ss_engine_queue::kSources) * ss_engine_queue::kFlagBytes);
+    *src = job.seq;
+    if (job.bytes) note(hipMemcpyAsync(job.dst, job.src, job.bytes, job.kind, q->stream));
+    // published even after a failure, so that nothing waits for this job in vain
+    note(hipMemcpyAsync(q->d_flag, src, ss_engine_queue::kFlagBytes, hipMemcpyHostToDevice, q->stream));
+    {
+      std::lock_guard<std::mutex> lk(q->mu);
+      q->enqueued_seq = job.seq;
+      q->busy = false;
+      if (q->q.empty()) q->cv_idle.notify_all();
+    }
+  }
+}
+
+static void eq_destroy(ss_ctx *ctx) {
+  ss_engine_queue *q = ctx->eq;
+  if (!q) return;
+  if (q->started) {
+    {
+      std::lock_guard<std::mutex> lk(q->mu);
+      q->stop = true;
+    }
+    q->cv.notify_all();
+    q->th.join();
+    (void)hipStreamSynchronize(q->stream);
+  }
+  if (q->d_flag) (void)hipFree(q->d_flag);
+  if (q->h_src) (void)hipHostFree(q->h_src);
+  if (q->h_timeouts) (void)hipHostFree(q->h_timeouts);
+  delete q;
+  ctx->eq = nullptr;
+}
+
+static int eq_create(ss_ctx *ctx) {
+  ss_engine_queue *q = new (std::nothrow) ss_engine_queue();
+  if (!q) return SS_E_NOMEM;
+  ctx->eq = q;
+  q->device = ctx->device;
+  q->stream = ctx->s_flush;
+  q->limit_ticks = (uint64_t)(ctx->cfg.flag_wait_ms ? ctx->cfg.flag_wait_ms : 30000u) * 100000ull;
+  if (hipMalloc((void **)&q->d_flag, ss_engine_queue::kFlagBytes) != hipSuccess ||
+      hipHostMalloc((void **)&q->h_src, ss_engine_queue::kSources * ss_engine_queue::kFlagBytes, hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc((void **)&q->h_timeouts, 64, hipHostMallocMapped) != hipSuccess) {
+    (void)hipGetLastError();
+    return SS_E_NOMEM;
+  }
+  std::memset(q->h_src, 0, ss_engine_queue::kSources * ss_engine_queue::kFlagBytes);
+  *q->h_timeouts = 0;
+  SS_HIP(hipHostGetDevicePointer((void **)&q->d_timeouts, q->h_timeouts, 0));
+  SS_HIP(hipMemcpy(q->d_flag, q->h_src, ss_engine_queue::kFlagBytes, hipMemcpyHostToDevice));
+  q->th = std::thread(engine_thread, q);
+  q->started = true;
+  return SS_OK;
+}
+
+// hands a transfer to the thread; returns its sequence number
+static uint64_t eq_push(ss_ctx *ctx, void *dst, const void *src, size_t bytes, hipMemcpyKind kind,
+                        const hipEvent_t *pre, int n_pre) {
+  ss_engine_queue *q = ctx->eq;
+  ss_engine_job job{};
+  for (int i = 0; i < n_pre && i < 3; ++i) job.pre[i] = pre[i];
+  job.n_pre = n_pre < 3 ? n_pre : 3;
+  job.dst = dst;
+  job.src = src;
+  job.bytes = bytes;
+  job.kind = kind;
+  {
+    std::lock_guard<std::mutex> lk(q->mu);
+    job.seq = q->next_seq++;
+    q->q.push_back(job);
+  }
+  q->cv.notify_one();
+  return job.seq;
+}
+
+// every job pushed so far is on the stream
+static void eq_wait_idle(ss_ctx *ctx) {
+  ss_engine_queue *q = ctx->eq;
+  if (!q || !q->started) return;
+  std::unique_lock<std::mutex> lk(q->mu);
+  q->cv_idle.wait(lk, [q] { return q->q.empty() && !q->busy; });
+}
+
+// stream st goes on only once job `seq` is complete (one wait per stream covers every earlier job)
+static int eq_stream_wait(ss_ctx *ctx, hipStream_t st, uint64_t seq, uint64_t *covered) {
+  if (seq == 0 || *covered >= seq) return SS_OK;
+  ss_engine_queue *q = ctx->eq;
+  ss_launch_wait_flag(st, q->d_flag, seq, q->limit_ticks, q->d_timeouts);
+  SS_HIP(hipGetLastError());
+  *covered = seq;
+  return SS_OK;
+}
+
 extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
   return ss_guard([&]() -> int {
     if (!out) return SS_E_INVAL;
@@ -123,6 +285,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (cfg.copy_workgroups_out == 0) cfg.copy_workgroups_out = cfg.copy_workgroups;
     if (cfg.copy_unroll == 0) cfg.copy_unroll = 8;
     if (cfg.copy_workgroups > 4096 || cfg.copy_workgroups_out > 4096 || cfg.copy_unroll > 8) return SS_E_INVAL;
+    if (cfg.flag_wait_ms > 600000u) return SS_E_INVAL;
     if (cfg.out_streams == 0) cfg.out_streams = 1;
     if (cfg.in_streams == 0) cfg.in_streams = 1;
     if (cfg.out_streams > ss_ctx::kMaxSwapStreams || cfg.in_streams > ss_ctx::kMaxSwapStreams) return SS_E_INVAL;
@@ -196,6 +359,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
       if (rc == SS_OK && cfg.copy_path_in == SS_PATH_STAGED &&
           (e = hipMalloc((void **)&ctx->ring_in, (size_t)ctx->n_slots * cfg.ring_slot_bytes)) != hipSuccess)
         fail(SS_E_NOMEM, e);
+      if (rc == SS_OK && (cfg.flags & SS_CFG_BARE_RING)) rc = eq_create(ctx);
     }
     for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
       hipEvent_t ev;
@@ -220,6 +384,7 @@ static void free_events(std::vector<hipEvent_t> &v) {
 
 // host joins every swap stream of both directions
 static int sync_swap_streams(ss_ctx *ctx) {
+  eq_wait_idle(ctx);                  // the ring transfers pushed so far are on their stream
   for (uint32_t i = 0; i < ctx->n_s_out; ++i)
     if (ctx->s_out[i]) SS_HIP(hipStreamSynchronize(ctx->s_out[i]));
   for (uint32_t i = 0; i < ctx->n_s_in; ++i)
@@ -258,6 +423,7 @@ static void sched_release(ss_sched &s) {
 extern "C" int ss_destroy(ss_ctx *ctx) {
   if (!ctx) return SS_E_INVAL;
   (void)sync_swap_streams(ctx);
+  eq_destroy(ctx);
   sched_release(ctx->sched);
   for (hipEvent_t ev : ctx->ev_ring) (void)hipEventDestroy(ev);
   for (int i = 0; i < ss_ctx::kMaxSwapStreams; ++i) {       // joined above: nothing is pending on them
@@ -337,6 +503,10 @@ static void ring_reset(ss_sched &s, uint32_t n_slots) {
   std::fill(s.in_group_last_scatter.begin(), s.in_group_last_scatter.end(), -1);
   std::fill(s.out_staged.begin(), s.out_staged.end(), 0);
   s.last_flush_batch = s.last_gather_batch = -1;
+  std::fill(s.flush_seq.begin(), s.flush_seq.end(), 0);
+  std::fill(s.group_last_flush_seq.begin(), s.group_last_flush_seq.end(), 0);
+  std::fill(s.fetch_seq.begin(), s.fetch_seq.end(), 0);
+  s.last_flush_seq = 0;
   s.engine_in_issued.clear();
   s.engine_out_issued.clear();
 }
@@ -617,6 +787,9 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     s.group_gathered.assign(s.groups.size(), 0);
     s.group_started.assign(s.groups.size(), 0);
     s.group_last_flush.assign(s.groups.size(), -1);
+    s.flush_seq.assign(n_out_batches, 0);
+    s.group_last_flush_seq.assign(s.groups.size(), 0);
+    s.fetch_seq.assign(s.in_groups.size(), 0);
     ring_reset(s, ctx->n_slots);
 
     const bool stall = (ctx->cfg.flags & SS_CFG_STALL_TIMING) != 0;
@@ -764,13 +937,22 @@ static int ring_flush(ss_ctx *ctx, uint32_t g) {
     uint64_t bytes = 0;
     for (uint32_t i = s.out_start[b]; i < s.out_start[e]; ++i) bytes += s.out[i].nbytes;
     // the gathers run in issue order on one stream: the most recent one stands for all before it
-    SS_HIP(hipStreamWaitEvent(ctx->s_flush, s.ev_gathered[s.phase][(size_t)s.last_gather_batch], 0));
-    if ((ctx->cfg.flags & SS_CFG_TIMING) && !s.group_started[g]) SS_HIP(hipEventRecord(s.ev_flush_start[s.phase][g], ctx->s_flush));
-    s.group_started[g] = 1;
-    SS_HIP(hipMemcpyAsync(ctx->staging + lo, slot + (lo - G.host_lo), bytes, hipMemcpyDeviceToHost, ctx->s_flush));
-    SS_HIP(hipEventRecord(s.ev_out_done[s.phase][e - 1], ctx->s_flush));
+    uint64_t seq = 0;
+    if (ctx->eq) {
+      seq = eq_push(ctx, ctx->staging + lo, slot + (lo - G.host_lo), bytes, hipMemcpyDeviceToHost,
+                    &s.ev_gathered[s.phase][(size_t)s.last_gather_batch], 1);
+      s.group_last_flush_seq[g] = s.last_flush_seq = seq;
+      s.group_started[g] = 1;
+    } else {
+      SS_HIP(hipStreamWaitEvent(ctx->s_flush, s.ev_gathered[s.phase][(size_t)s.last_gather_batch], 0));
+      if ((ctx->cfg.flags & SS_CFG_TIMING) && !s.group_started[g]) SS_HIP(hipEventRecord(s.ev_flush_start[s.phase][g], ctx->s_flush));
+      s.group_started[g] = 1;
+      SS_HIP(hipMemcpyAsync(ctx->staging + lo, slot + (lo - G.host_lo), bytes, hipMemcpyDeviceToHost, ctx->s_flush));
+      SS_HIP(hipEventRecord(s.ev_out_done[s.phase][e - 1], ctx->s_flush));
+    }
     for (uint32_t x = b; x < e; ++x) {
       s.done_ev_of[x] = (int32_t)(e - 1);
+      s.flush_seq[x] = seq;
       s.ring_state[x] = 2;
     }
     s.last_flush_batch = e - 1;
@@ -815,8 +997,12 @@ static int swap_out_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
       const int rc = ring_flush(ctx, og);
       if (rc != SS_OK) return rc;
       s.group_gathered[og] = 0;
-      if (s.group_last_flush[og] >= 0)
+      if (ctx->eq) {
+        const int rw = eq_stream_wait(ctx, so, s.group_last_flush_seq[og], &ctx->eq->waited_out);
+        if (rw != SS_OK) return rw;
+      } else if (s.group_last_flush[og] >= 0) {
         SS_HIP(hipStreamWaitEvent(so, s.ev_out_done[s.phase][(size_t)s.group_last_flush[og]], 0));
+      }
     }
     s.slot_owner[slot] = g;
   }
@@ -998,16 +1184,24 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
     if (rc != SS_OK) return rc;
     hipStream_t se = ctx->s_flush;
     const int32_t pd = s.prev_direct[s.in_group_outs[g].back()];
-    if (pd >= 0 && s.out_issued[(size_t)pd]) SS_HIP(hipStreamWaitEvent(se, s.ev_out_done[s.phase][(size_t)pd], 0));
-    if (s.last_engine_out >= 0) SS_HIP(hipStreamWaitEvent(se, s.ev_out_done[s.phase][(size_t)s.last_engine_out], 0));
     const int32_t og = s.in_slot_owner[slot];
+    hipEvent_t pre[3];
+    int n_pre = 0;
+    if (pd >= 0 && s.out_issued[(size_t)pd]) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)pd];
+    if (s.last_engine_out >= 0) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)s.last_engine_out];
     if (og >= 0 && og != (int32_t)g && s.in_group_last_scatter[(size_t)og] >= 0)
-      SS_HIP(hipStreamWaitEvent(se, s.ev_in_done[s.phase][(size_t)s.in_group_last_scatter[(size_t)og]], 0));
+      pre[n_pre++] = s.ev_in_done[s.phase][(size_t)s.in_group_last_scatter[(size_t)og]];
     s.in_slot_owner[slot] = (int32_t)g;
-    if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_fetch_start[s.phase][g], se));
-    SS_HIP(hipMemcpyAsync(ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes, ctx->staging + G.host_lo, G.bytes,
-                          hipMemcpyHostToDevice, se));
-    SS_HIP(hipEventRecord(s.ev_fetched[s.phase][g], se));
+    if (ctx->eq) {
+      s.fetch_seq[g] = eq_push(ctx, ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes, ctx->staging + G.host_lo, G.bytes,
+                               hipMemcpyHostToDevice, pre, n_pre);
+    } else {
+      for (int i = 0; i < n_pre; ++i) SS_HIP(hipStreamWaitEvent(se, pre[i], 0));
+      if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_fetch_start[s.phase][g], se));
+      SS_HIP(hipMemcpyAsync(ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes, ctx->staging + G.host_lo, G.bytes,
+                            hipMemcpyHostToDevice, se));
+      SS_HIP(hipEventRecord(s.ev_fetched[s.phase][g], se));
+    }
     s.in_group_state[g] = 1;
     ctx->stats.ring_transfers_in++;
   } else if (s.in_slot_owner[slot] != (int32_t)g) {
@@ -1016,7 +1210,12 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
   hipStream_t si = ctx->s_in[0];
   const uint32_t lo = s.in_start[batch], hi = s.in_start[batch + 1];
   SS_HIP(hipStreamWaitEvent(si, mark, 0));                                  // destination blocks are free from here on
-  SS_HIP(hipStreamWaitEvent(si, s.ev_fetched[s.phase][g], 0));
+  if (ctx->eq) {
+    const int rw = eq_stream_wait(ctx, si, s.fetch_seq[g], &ctx->eq->waited_in);
+    if (rw != SS_OK) return rw;
+  } else {
+    SS_HIP(hipStreamWaitEvent(si, s.ev_fetched[s.phase][g], 0));
+  }
   if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_in_start[s.phase][batch], si));
   uint8_t *base = (uint8_t *)((uintptr_t)ctx->ring_in + (uintptr_t)slot * ctx->cfg.ring_slot_bytes - (uintptr_t)G.host_lo);
   const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
@@ -1079,7 +1278,12 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
     if (rc != SS_OK) return rc;
     const int32_t pd = s.prev_direct[s.in_dep[batch]];
     if (pd >= 0 && s.out_issued[(size_t)pd]) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)pd], 0));
-    if (s.last_flush_batch >= 0) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)s.last_flush_batch], 0));
+    if (ctx->eq) {
+      const int rw = eq_stream_wait(ctx, si, s.last_flush_seq, &ctx->eq->waited_in);
+      if (rw != SS_OK) return rw;
+    } else if (s.last_flush_batch >= 0) {
+      SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)s.last_flush_batch], 0));
+    }
   }
   // a copy-engine swap-out collapses to a quarter of the link rate as soon as anything flows the
   // other way: no swap-in starts before the engine swap-outs issued so far have finished
@@ -1164,10 +1368,22 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
       return SS_OK;
     }
     case SS_SYNC_DRAIN: {
+      int late = SS_OK;             // what the iteration's ring transfers ran into; reported once the state is reset
       {
         int rc = s.loaded ? ring_flush_all(ctx) : SS_OK;      // staged batches whose group never completed
         if (rc == SS_OK) rc = sync_swap_streams(ctx);
         if (rc != SS_OK) return rc;
+        if (ctx->eq) {
+          const int he = ctx->eq->hip_error.exchange(0);
+          if (he) {
+            ctx->stats.last_hip_error = (int32_t)he;
+            late = SS_E_HIP;
+          }
+          if (*(volatile uint32_t *)ctx->eq->h_timeouts) {
+            *(volatile uint32_t *)ctx->eq->h_timeouts = 0;
+            late = SS_E_TIMEOUT;
+          }
+        }
       }
       if ((ctx->cfg.flags & SS_CFG_STALL_TIMING) && s.loaded) {
         // measurement mode: the compute stream is joined too, then every wait of this iteration is
@@ -1200,7 +1416,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
         s.in_group_state_drained = s.in_group_state;
         ring_reset(s, ctx->n_slots);
       }
-      return SS_OK;
+      return late;
     }
     default: return SS_E_INVAL;
   }
@@ -1241,6 +1457,8 @@ static int timing_events(ss_ctx *ctx, uint32_t dir, uint32_t u, hipEvent_t *st, 
     if (u + 1 >= s.in_start.size()) return SS_E_INVAL;
     *st = s.ev_in_start[set][u];
     *dn = s.ev_in_done[set][u];
+  } else if (ctx->eq) {
+    return SS_E_STATE;                                         // bare ring transfers carry no events
   } else if (dir == 3) {
     if (u >= s.in_groups.size()) return SS_E_INVAL;
     const std::vector<uint8_t> &st_ = s.drained_once ? s.in_group_state_drained : s.in_group_state;
@@ -1314,8 +1532,18 @@ extern "C" int ss_batch_done(ss_ctx *ctx, uint32_t dir, uint32_t batch, int *don
     *done = 0;
     return SS_OK;
   }
-  const hipError_t e = hipEventQuery(dir ? s.ev_in_done[s.phase][batch]
-                                         : s.ev_out_done[s.phase][(size_t)s.done_ev_of[batch]]);
+  hipError_t e;
+  if (dir == 0 && ctx->eq && s.flush_seq[batch]) {
+    // no event of its own: complete once its transfer is on the stream and the stream has nothing left to do
+    bool on_stream;
+    {
+      std::lock_guard<std::mutex> lk(ctx->eq->mu);
+      on_stream = ctx->eq->enqueued_seq >= s.flush_seq[batch];
+    }
+    e = on_stream ? hipStreamQuery(ctx->s_flush) : hipErrorNotReady;
+  } else {
+    e = hipEventQuery(dir ? s.ev_in_done[s.phase][batch] : s.ev_out_done[s.phase][(size_t)s.done_ev_of[batch]]);
+  }
   if (e == hipErrorNotReady) {
     (void)hipGetLastError();
     *done = 0;

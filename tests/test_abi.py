@@ -55,6 +55,24 @@ def test_record_layouts_match_the_header_sizes():
         assert a == b
 
 
+def test_configuration_record_has_the_librarys_size():
+    """ss_config_default clears the whole record before it sets the defaults: on a buffer of 0xFF bytes it
+    rewrites exactly as many bytes as the binding's record is long"""
+    import paper_2509_11076_amd.binding as B
+    n = ctypes.sizeof(B.ss_config_t)
+    buf = (ctypes.c_ubyte * (n + 64))(*([0xFF] * (n + 64)))
+    lib = ctypes.CDLL(B.LIB_PATH)
+    lib.ss_config_default.argtypes = [ctypes.c_void_p]
+    assert lib.ss_config_default(ctypes.addressof(buf)) == 0
+    raw = bytes(buf)
+    assert raw[n:] == b"\xff" * 64 and raw[n - 8:n] == b"\x00" * 8      # flag_wait_ms and the reserved word: 0
+    header = open(os.path.join(ROOT, "include", "ss.h")).read()
+    body = re.search(r"typedef struct \{([^}]*)\} ss_config_t;", re.sub(r"/\*.*?\*/", "", header, flags=re.S)).group(1)
+    names = re.findall(r"\b(?:uint64_t|uint32_t)\s+([a-z_0-9, ]+);", body)
+    fields = [x.strip() for grp in names for x in grp.split(",")]
+    assert fields == [f for f, _ in B.ss_config_t._fields_]
+
+
 def test_host_only_calls_work_without_a_gpu():
     import paper_2509_11076_amd.binding as B
     cfg = B.ss_config_default()

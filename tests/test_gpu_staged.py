@@ -42,9 +42,11 @@ def random_arena(torch, nbytes, seed):
 @pytest.mark.parametrize("bpo", [64 * 1024, INSTANT])
 @pytest.mark.parametrize("slot_kib,slots", [(512, 2), (1024, 3), (4096, 2)])
 @pytest.mark.parametrize("staged_in,taper", [(False, 0), (True, 0), (True, 1)])
-def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, taper):
+@pytest.mark.parametrize("bare", [False, True])
+def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, taper, bare):
     """configuration 1 with ring slots smaller than, about, and larger than a layer's swap set: staging
-    image and arena (with poison over released blocks) equal the oracle's, byte for byte"""
+    image and arena (with poison over released blocks) equal the oracle's, byte for byte; the same with the
+    ring transfers issued bare by the library's own thread (SS_CFG_BARE_RING)"""
     from paper_2509_11076_amd.executor import run_iteration
     tr = W.build_trace(W.config_shape(1))
     pol = W.config_swap_set(tr, 1)
@@ -58,7 +60,7 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
     ctx = make_ctx(P, staging_bytes=ora["staging_bytes"], link_bytes_per_op=bpo, copy_path=P.SS_PATH_STAGED,
                    copy_path_in=P.SS_PATH_STAGED if staged_in else P.SS_PATH_AUTO,
                    ring_slot_bytes=slot_kib << 10, ring_bytes=slots * (slot_kib << 10), ring_taper=taper,
-                   flags=P.SS_CFG_POISON_FREE | P.SS_CFG_TIMING)
+                   flags=P.SS_CFG_POISON_FREE | P.SS_CFG_TIMING | (P.SS_CFG_BARE_RING if bare else 0))
     try:
         P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
         for it in range(2):                     # the second iteration re-uses ring slots and event sets
@@ -75,10 +77,16 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
             assert np.array_equal(P.ss_host_peek(ctx, 0, ora["staging_bytes"]), staging)
             assert np.array_equal(arena.cpu().numpy(), host_arena)
             for g in range(len(group_bytes)):
-                assert P.ss_batch_ms(ctx, 2, g)[0] > 0
-            assert P.ss_batch_ms(ctx, 2)[1] > 0 and P.ss_batch_ms(ctx, 0, 0)[0] > 0
+                if bare:                               # bare transfers carry no events
+                    with pytest.raises(P.SsError) as ei:
+                        P.ss_batch_ms(ctx, 2, g)
+                    assert ei.value.code == P.SS_E_STATE
+                else:
+                    assert P.ss_batch_ms(ctx, 2, g)[0] > 0
+            assert bare or P.ss_batch_ms(ctx, 2)[1] > 0
+            assert P.ss_batch_ms(ctx, 0, 0)[0] > 0
             # the same durations, every unit of a direction in one call
-            for dr, n_units in ((0, lib["n_out_batches"]), (1, lib["n_in_batches"]), (2, len(group_bytes))):
+            for dr, n_units in ((0, lib["n_out_batches"]), (1, lib["n_in_batches"])) + (() if bare else ((2, len(group_bytes)),)):
                 all_ms = P.ss_batch_ms_all(ctx, dr)
                 assert len(all_ms) == n_units
                 assert all_ms.tolist() == [np.float32(P.ss_batch_ms(ctx, dr, u)[0]) for u in range(n_units)]
@@ -87,7 +95,7 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
                 assert (in_group_of >= 0).all() and int(in_group_bytes.sum()) == int(group_bytes.sum())
                 assert int(in_group_bytes.max()) <= slot_kib << 10
                 for g in range(len(in_group_bytes)):
-                    assert P.ss_batch_ms(ctx, 3, g)[0] > 0
+                    assert bare or P.ss_batch_ms(ctx, 3, g)[0] > 0
                 # group shapes: tapered, each swap-in group (of more than one batch) is at most half of what is
                 # still to come including itself, but never asked to be smaller than an eighth of a slot;
                 # untapered, a group ends only where the next batch would overflow the slot or leave a gap
@@ -140,9 +148,11 @@ def test_ring_takes_only_gap_free_batches_and_the_rest_leaves_directly(P, torch)
     start = np.array(starts, dtype=np.uint32)
     dep = np.arange(9, dtype=np.uint32)                        # swap-in batch b needs swap-out batch b only
     rows = [tuple(int(x) for x in r) for r in d.tolist()]
-    for path_in, taper in ((P.SS_PATH_AUTO, 1), (P.SS_PATH_STAGED, 1), (P.SS_PATH_STAGED, 0)):
+    for path_in, taper, bare in ((P.SS_PATH_AUTO, 1, 0), (P.SS_PATH_STAGED, 1, 0), (P.SS_PATH_STAGED, 0, 0),
+                                 (P.SS_PATH_AUTO, 1, 1), (P.SS_PATH_STAGED, 1, 1), (P.SS_PATH_STAGED, 0, 1)):
         ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_STAGED, copy_path_in=path_in,
-                       ring_slot_bytes=1024 * KiB, ring_bytes=2048 * KiB, ring_taper=taper, flags=P.SS_CFG_TIMING)
+                       ring_slot_bytes=1024 * KiB, ring_bytes=2048 * KiB, ring_taper=taper,
+                       flags=P.SS_CFG_TIMING | (P.SS_CFG_BARE_RING if bare else 0))
         try:
             P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
             P.ss_load_schedule(ctx, d, start, d, start, dep)
@@ -221,8 +231,8 @@ def test_ring_takes_only_gap_free_batches_and_the_rest_leaves_directly(P, torch)
         P.ss_destroy(ctx)
 
 
-@pytest.mark.parametrize("path_in", [0, 3])
-def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch, path_in):
+@pytest.mark.parametrize("path_in,bare", [(0, 0), (3, 0), (0, 1), (3, 1)])
+def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch, path_in, bare):
     """configuration 2, three iterations, every swap-out through the ring (all its sizes are multiples of
     the alignment), blocks poisoned at their release: compute results equal the run without swapping"""
     B = P
@@ -230,7 +240,8 @@ def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch, path_in):
     res = []
     for swap in (False, True):
         r = SwapRun(B, torch, 2, swap=swap, bpo=11 << 20, bpo_in=4760000, copy_path=B.SS_PATH_STAGED,
-                    copy_path_in=path_in, flags=(B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE) if swap else 0)
+                    copy_path_in=path_in,
+                    flags=(B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE | (B.SS_CFG_BARE_RING if bare else 0)) if swap else 0)
         try:
             for _ in range(3):
                 r.step() if swap else r.step_noswap()
@@ -243,3 +254,52 @@ def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch, path_in):
     assert st["bytes_out"] == st["bytes_in"] == 3 * moved and st["ring_batches"] == 3 * 120
     assert 0 < st["ring_transfers"] < st["ring_batches"]
     assert (st["ring_batches_in"] > 0) == (path_in == 3) and st["ring_transfers_in"] <= st["ring_batches_in"]
+
+
+def test_bare_ring_wait_gives_up_after_its_limit_and_the_drain_says_so(P, torch):
+    """SS_CFG_BARE_RING with a wait limit of 1 ms and ring transfers of 64 MiB (a little over 1 ms each, queued
+    one behind the other): the streams that wait for them give up and go on, every kernel ends normally, and
+    SS_SYNC_DRAIN reports SS_E_TIMEOUT; with the default limit the same schedule moves the oracle's bytes.  The
+    context stays usable after the error."""
+    M = 1 << 20
+    nb, sz = 6, 64 * M
+    d = np.zeros(nb, dtype=W.DESC_DT)
+    for b in range(nb):
+        d[b] = (b * sz, b * sz, sz, b, 0)
+    start = np.arange(nb + 1, dtype=np.uint32)
+    rows = [tuple(int(x) for x in r) for r in d.tolist()]
+    arena = random_arena(torch, nb * sz, 77)
+    host = arena.cpu().numpy().copy()
+    with pytest.raises(P.SsError):
+        make_ctx(P, staging_bytes=4096, flag_wait_ms=600001)
+    for limit in (1, 0):
+        ctx = make_ctx(P, staging_bytes=nb * sz, copy_path=P.SS_PATH_STAGED, copy_path_in=P.SS_PATH_STAGED,
+                       ring_slot_bytes=sz, ring_bytes=2 * sz, ring_taper=1, flags=P.SS_CFG_BARE_RING, flag_wait_ms=limit)
+        try:
+            P.ss_bind(ctx, arena.data_ptr(), nb * sz, torch.cuda.current_stream().cuda_stream)
+            P.ss_load_schedule(ctx, d, start, d, start, np.arange(nb, dtype=np.uint32))
+            for it in range(2):
+                arena.copy_(torch.from_numpy(host).cuda())
+                for b in range(nb):
+                    P.ss_swap_out(ctx, b)
+                for t in range(nb):
+                    P.ss_sync(ctx, P.SS_SYNC_FREE, t)
+                arena.fill_(0x3C)
+                for b in reversed(range(nb)):
+                    P.ss_swap_in(ctx, b)
+                for t in range(nb):
+                    P.ss_sync(ctx, P.SS_SYNC_WAIT_IN, t)
+                if limit:
+                    with pytest.raises(P.SsError) as ei:
+                        P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+                    assert ei.value.code == P.SS_E_TIMEOUT
+                    torch.cuda.synchronize()
+                else:
+                    P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+                    torch.cuda.synchronize()
+                    staging = np.zeros(nb * sz, dtype=np.uint8)
+                    oracle.swap_out(host, staging, rows)
+                    assert np.array_equal(P.ss_host_peek(ctx, 0, nb * sz), staging)
+                    assert np.array_equal(arena.cpu().numpy(), host)
+        finally:
+            P.ss_destroy(ctx)
