@@ -936,6 +936,8 @@ def measure(B, torch, np, bw, o):
     # (several policies are generated from successive measured iterations and the fastest is kept,
     # Sec. 6), the model is re-fitted from the measured step time a few times and the best kept.
     flags = B.SS_CFG_TIMING | (B.SS_CFG_KEEP_LATE if o.policy_mode == "execute-all" else 0)
+    if getattr(o, "bare_ring", -1) == 1:
+        flags |= B.SS_CFG_BARE_RING
     link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
     calib = []
     # the swap-in queue is planned with the no-swap operator time: operators never run faster than that
@@ -1293,6 +1295,9 @@ def main():
                     help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
     ap.add_argument("--engine-window-out", type=int, default=0, help="the same for copy-engine swap-out batches")
+    ap.add_argument("--bare-ring", type=int, default=-1,
+                    help="ring route: 1 = ring transfers issued bare by the library's own thread (SS_CFG_BARE_RING), "
+                         "0 = with events on their stream, -1 = both are tried and the faster kept")
     ap.add_argument("--engine-window", type=int, default=-1,
                     help="copy-engine swap-in batches outstanding at most (0 = no limit): the dispatch thread waits in "
                          "ss_swap_in for the batch issued that many batches earlier; default: 4 where the swap-in bytes "

@@ -136,8 +136,11 @@ enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch
                                     number into device memory; a stream that needs the transfer's bytes
                                     waits for that number in a one-wave kernel which polls it, sleeping in
                                     between, and gives up after flag_wait_ms (SS_SYNC_DRAIN then returns
-                                    SS_E_TIMEOUT).  The transfers themselves carry no events: ss_batch_ms
-                                    and its like return SS_E_STATE for directions 2 and 3               */
+                                    SS_E_TIMEOUT).  The transfers themselves carry no events: with
+                                    SS_CFG_TIMING their durations (ss_batch_ms, directions 2 and 3) are taken
+                                    on the host's clock by a second thread that watches a copy of the
+                                    sequence number arrive in pinned memory, and ss_batch_window has none
+                                    for them (SS_E_STATE).  Without SS_PATH_STAGED the flag does nothing    */
 
 typedef struct {
   uint64_t staging_bytes;     /* pinned host staging to allocate at ss_create                */

@@ -6,6 +6,7 @@
 // the host).
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <cstring>
 #include <deque>
@@ -123,6 +124,7 @@ struct ss_engine_job {
   size_t bytes;
   hipMemcpyKind kind;
   uint64_t seq;
+  uint32_t dir, unit;            // what ss_batch_ms calls it: direction 2 or 3, ring group
 };
 
 struct ss_engine_queue {
@@ -144,7 +146,39 @@ struct ss_engine_queue {
   uint64_t synced_seq = 0;                      // the thread's own: jobs up to here are known to be complete
   std::atomic<int> hip_error{0};                // first HIP error the thread met
   uint64_t waited_out = 0, waited_in = 0;       // dispatch thread: highest number a wait on the swap-out / swap-in stream covers
+  // SS_CFG_TIMING: the transfers carry no events, so their times are taken on the host's clock.  A third
+  // transfer behind each job copies the flag into pinned host memory, and a second thread, which makes no HIP
+  // call at all, notes when it sees each number arrive.  A job starts when it is enqueued or when the job
+  // before it is complete, whichever is later.
+  bool timing = false;
+  uint64_t *h_done = nullptr;                   // pinned, kFlagBytes; first word = last job seen complete by the host
+  std::thread observer;
+  std::atomic<bool> stop_observer{false};
+  struct rec { uint64_t seq; uint32_t dir, unit; double t_enq, t_done; };
+  std::vector<rec> recs;                        // the jobs of the iteration being issued (under mu)
+  uint64_t observed = 0;                        // under mu
+  std::vector<double> unit_start[2], unit_end[2];   // iteration drained last: per ring group, ms on the host's clock; < 0 = none
 };
+
+static double host_ms() {
+  return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+static void observer_thread(ss_engine_queue *q) {
+  uint64_t last = 0;
+  while (!q->stop_observer.load(std::memory_order_relaxed)) {
+    const uint64_t v = *(volatile uint64_t *)q->h_done;
+    if (v > last) {
+      const double t = host_ms();
+      std::lock_guard<std::mutex> lk(q->mu);
+      for (auto &r : q->recs)
+        if (r.seq > last && r.seq <= v) r.t_done = t;
+      q->observed = last = v;
+    } else {
+      std::this_thread::yield();
+    }
+  }
+}
 
 static void engine_thread(ss_engine_queue *q) {
   auto note = [q](hipError_t e) {
@@ -174,8 +208,10 @@ static void engine_thread(ss_engine_queue *q) {
     if (job.bytes) note(hipMemcpyAsync(job.dst, job.src, job.bytes, job.kind, q->stream));
     // published even after a failure, so that nothing waits for this job in vain
     note(hipMemcpyAsync(q->d_flag, src, ss_engine_queue::kFlagBytes, hipMemcpyHostToDevice, q->stream));
+    if (q->timing) note(hipMemcpyAsync(q->h_done, q->d_flag, ss_engine_queue::kFlagBytes, hipMemcpyDeviceToHost, q->stream));
     {
       std::lock_guard<std::mutex> lk(q->mu);
+      if (q->timing) q->recs.push_back({job.seq, job.dir, job.unit, host_ms(), -1.0});
       q->enqueued_seq = job.seq;
       q->busy = false;
       if (q->q.empty()) q->cv_idle.notify_all();
@@ -194,7 +230,12 @@ static void eq_destroy(ss_ctx *ctx) {
     q->cv.notify_all();
     q->th.join();
     (void)hipStreamSynchronize(q->stream);
+    if (q->timing) {
+      q->stop_observer.store(true);
+      q->observer.join();
+    }
   }
+  if (q->h_done) (void)hipHostFree(q->h_done);
   if (q->d_flag) (void)hipFree(q->d_flag);
   if (q->h_src) (void)hipHostFree(q->h_src);
   if (q->h_timeouts) (void)hipHostFree(q->h_timeouts);
@@ -219,6 +260,15 @@ static int eq_create(ss_ctx *ctx) {
   *q->h_timeouts = 0;
   SS_HIP(hipHostGetDevicePointer((void **)&q->d_timeouts, q->h_timeouts, 0));
   SS_HIP(hipMemcpy(q->d_flag, q->h_src, ss_engine_queue::kFlagBytes, hipMemcpyHostToDevice));
+  if (ctx->cfg.flags & SS_CFG_TIMING) {
+    if (hipHostMalloc((void **)&q->h_done, ss_engine_queue::kFlagBytes, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return SS_E_NOMEM;
+    }
+    std::memset(q->h_done, 0, ss_engine_queue::kFlagBytes);
+    q->timing = true;
+    q->observer = std::thread(observer_thread, q);
+  }
   q->th = std::thread(engine_thread, q);
   q->started = true;
   return SS_OK;
@@ -226,7 +276,7 @@ static int eq_create(ss_ctx *ctx) {
 
 // hands a transfer to the thread; returns its sequence number
 static uint64_t eq_push(ss_ctx *ctx, void *dst, const void *src, size_t bytes, hipMemcpyKind kind,
-                        const hipEvent_t *pre, int n_pre) {
+                        const hipEvent_t *pre, int n_pre, uint32_t dir, uint32_t unit) {
   ss_engine_queue *q = ctx->eq;
   ss_engine_job job{};
   for (int i = 0; i < n_pre && i < 3; ++i) job.pre[i] = pre[i];
@@ -235,6 +285,8 @@ static uint64_t eq_push(ss_ctx *ctx, void *dst, const void *src, size_t bytes, h
   job.src = src;
   job.bytes = bytes;
   job.kind = kind;
+  job.dir = dir;
+  job.unit = unit;
   {
     std::lock_guard<std::mutex> lk(q->mu);
     job.seq = q->next_seq++;
@@ -940,7 +992,7 @@ static int ring_flush(ss_ctx *ctx, uint32_t g) {
     uint64_t seq = 0;
     if (ctx->eq) {
       seq = eq_push(ctx, ctx->staging + lo, slot + (lo - G.host_lo), bytes, hipMemcpyDeviceToHost,
-                    &s.ev_gathered[s.phase][(size_t)s.last_gather_batch], 1);
+                    &s.ev_gathered[s.phase][(size_t)s.last_gather_batch], 1, 2, g);
       s.group_last_flush_seq[g] = s.last_flush_seq = seq;
       s.group_started[g] = 1;
     } else {
@@ -1194,7 +1246,7 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
     s.in_slot_owner[slot] = (int32_t)g;
     if (ctx->eq) {
       s.fetch_seq[g] = eq_push(ctx, ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes, ctx->staging + G.host_lo, G.bytes,
-                               hipMemcpyHostToDevice, pre, n_pre);
+                               hipMemcpyHostToDevice, pre, n_pre, 3, g);
     } else {
       for (int i = 0; i < n_pre; ++i) SS_HIP(hipStreamWaitEvent(se, pre[i], 0));
       if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_fetch_start[s.phase][g], se));
@@ -1328,6 +1380,36 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
   return SS_OK;
 }
 
+// SS_CFG_BARE_RING with SS_CFG_TIMING, at the drain (every transfer is complete): the host-clock times of the
+// iteration's ring transfers, folded per ring group
+static void eq_harvest(ss_ctx *ctx) {
+  ss_engine_queue *q = ctx->eq;
+  if (!q || !q->timing) return;
+  const ss_sched &s = ctx->sched;
+  for (int i = 0; i < 20000; ++i) {             // the observer is at most a few microseconds behind
+    {
+      std::lock_guard<std::mutex> lk(q->mu);
+      if (q->observed >= q->enqueued_seq) break;
+    }
+    std::this_thread::sleep_for(std::chrono::microseconds(10));
+  }
+  std::lock_guard<std::mutex> lk(q->mu);
+  q->unit_start[0].assign(s.groups.size(), -1.0);
+  q->unit_end[0].assign(s.groups.size(), -1.0);
+  q->unit_start[1].assign(s.in_groups.size(), -1.0);
+  q->unit_end[1].assign(s.in_groups.size(), -1.0);
+  double prev_done = -1.0;
+  for (const auto &r : q->recs) {
+    const double start = r.t_enq > prev_done ? r.t_enq : prev_done;
+    prev_done = r.t_done;
+    const int d = r.dir == 3 ? 1 : 0;
+    if (r.t_done < 0 || r.unit >= q->unit_start[d].size()) continue;
+    if (q->unit_start[d][r.unit] < 0) q->unit_start[d][r.unit] = start;
+    if (r.t_done > q->unit_end[d][r.unit]) q->unit_end[d][r.unit] = r.t_done;
+  }
+  q->recs.clear();
+}
+
 extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
   if (!ctx) return SS_E_INVAL;
   ss_sched &s = ctx->sched;
@@ -1374,6 +1456,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
         if (rc == SS_OK) rc = sync_swap_streams(ctx);
         if (rc != SS_OK) return rc;
         if (ctx->eq) {
+          eq_harvest(ctx);
           const int he = ctx->eq->hip_error.exchange(0);
           if (he) {
             ctx->stats.last_hip_error = (int32_t)he;
@@ -1458,7 +1541,7 @@ static int timing_events(ss_ctx *ctx, uint32_t dir, uint32_t u, hipEvent_t *st, 
     *st = s.ev_in_start[set][u];
     *dn = s.ev_in_done[set][u];
   } else if (ctx->eq) {
-    return SS_E_STATE;                                         // bare ring transfers carry no events
+    return SS_E_STATE;                                         // bare ring transfers carry no events (host clock: bare_unit_ms)
   } else if (dir == 3) {
     if (u >= s.in_groups.size()) return SS_E_INVAL;
     const std::vector<uint8_t> &st_ = s.drained_once ? s.in_group_state_drained : s.in_group_state;
@@ -1475,6 +1558,23 @@ static int timing_events(ss_ctx *ctx, uint32_t dir, uint32_t u, hipEvent_t *st, 
   return SS_OK;
 }
 
+// SS_CFG_BARE_RING: duration of ring transfer unit u of direction dir (2, 3) in the iteration drained last,
+// and its end relative to the start of unit 0, on the host's clock
+static int bare_unit_ms(ss_ctx *ctx, uint32_t dir, uint32_t u, float *ms, float *end_from_first) {
+  ss_engine_queue *q = ctx->eq;
+  if (!q->timing) return SS_E_STATE;
+  std::lock_guard<std::mutex> lk(q->mu);
+  const std::vector<double> &st = q->unit_start[dir - 2], &en = q->unit_end[dir - 2];
+  if (u >= st.size()) return SS_E_INVAL;
+  if (st[u] < 0 || en[u] < 0) return SS_E_STATE;
+  if (ms) *ms = (float)(en[u] - st[u]);
+  if (end_from_first) {
+    if (st[0] < 0) return SS_E_STATE;
+    *end_from_first = (float)(en[u] - st[0]);
+  }
+  return SS_OK;
+}
+
 static size_t timing_units(const ss_sched &s, uint32_t dir) {
   return dir == 0 ? s.out_start.size() - 1 : dir == 1 ? s.in_start.size() - 1 : dir == 2 ? s.groups.size() : s.in_groups.size();
 }
@@ -1486,6 +1586,19 @@ extern "C" int ss_batch_ms(ss_ctx *ctx, uint32_t dir, uint32_t batch, float *ms,
   const size_t nb = timing_units(s, dir);
   hipEvent_t st, dn;
   int rc;
+  if (ctx->eq && dir >= 2) {
+    if (ms && (rc = bare_unit_ms(ctx, dir, batch, ms, nullptr)) != SS_OK) return rc;
+    if (span_ms) {
+      *span_ms = 0.f;
+      if (nb == 0) return SS_OK;
+      if ((rc = bare_unit_ms(ctx, dir, 0, nullptr, span_ms)) != SS_OK) return rc;
+      for (size_t b = nb > 8 ? nb - 8 : 0; b < nb; ++b) {
+        float x = 0.f;
+        if (bare_unit_ms(ctx, dir, (uint32_t)b, nullptr, &x) == SS_OK && x > *span_ms) *span_ms = x;
+      }
+    }
+    return SS_OK;
+  }
   if (ms) {
     if ((rc = timing_events(ctx, dir, batch, &st, &dn)) != SS_OK) return rc;
     SS_HIP(hipEventElapsedTime(ms, st, dn));
@@ -1515,6 +1628,10 @@ extern "C" int ss_batch_ms_all(ss_ctx *ctx, uint32_t dir, float *ms, uint32_t ca
   for (size_t u = 0; u < nb; ++u) {
     hipEvent_t st, dn;
     ms[u] = -1.f;                                   // a unit that did not run this way (see ss_batch_ms)
+    if (ctx->eq && dir >= 2) {
+      if (bare_unit_ms(ctx, dir, (uint32_t)u, &ms[u], nullptr) != SS_OK) ms[u] = -1.f;
+      continue;
+    }
     if (timing_events(ctx, dir, (uint32_t)u, &st, &dn) != SS_OK) continue;
     SS_HIP(hipEventElapsedTime(&ms[u], st, dn));
   }

@@ -77,16 +77,17 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
             assert np.array_equal(P.ss_host_peek(ctx, 0, ora["staging_bytes"]), staging)
             assert np.array_equal(arena.cpu().numpy(), host_arena)
             for g in range(len(group_bytes)):
-                if bare:                               # bare transfers carry no events
-                    with pytest.raises(P.SsError) as ei:
-                        P.ss_batch_ms(ctx, 2, g)
-                    assert ei.value.code == P.SS_E_STATE
-                else:
-                    assert P.ss_batch_ms(ctx, 2, g)[0] > 0
-            assert bare or P.ss_batch_ms(ctx, 2)[1] > 0
-            assert P.ss_batch_ms(ctx, 0, 0)[0] > 0
+                assert P.ss_batch_ms(ctx, 2, g)[0] > 0          # bare: on the host's clock
+            assert P.ss_batch_ms(ctx, 2)[1] > 0 and P.ss_batch_ms(ctx, 0, 0)[0] > 0
+            if bare:                                   # no events on the transfers: nothing to place them among the batches
+                with pytest.raises(P.SsError) as ei:
+                    P.ss_batch_window(ctx, 2, 0)
+                assert ei.value.code == P.SS_E_STATE
+            else:
+                w = P.ss_batch_window(ctx, 2, 0)
+                assert w[1] > w[0] >= 0
             # the same durations, every unit of a direction in one call
-            for dr, n_units in ((0, lib["n_out_batches"]), (1, lib["n_in_batches"])) + (() if bare else ((2, len(group_bytes)),)):
+            for dr, n_units in ((0, lib["n_out_batches"]), (1, lib["n_in_batches"]), (2, len(group_bytes))):
                 all_ms = P.ss_batch_ms_all(ctx, dr)
                 assert len(all_ms) == n_units
                 assert all_ms.tolist() == [np.float32(P.ss_batch_ms(ctx, dr, u)[0]) for u in range(n_units)]
@@ -95,7 +96,7 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
                 assert (in_group_of >= 0).all() and int(in_group_bytes.sum()) == int(group_bytes.sum())
                 assert int(in_group_bytes.max()) <= slot_kib << 10
                 for g in range(len(in_group_bytes)):
-                    assert bare or P.ss_batch_ms(ctx, 3, g)[0] > 0
+                    assert P.ss_batch_ms(ctx, 3, g)[0] > 0
                 # group shapes: tapered, each swap-in group (of more than one batch) is at most half of what is
                 # still to come including itself, but never asked to be smaller than an eighth of a slot;
                 # untapered, a group ends only where the next batch would overflow the slot or leave a gap
