@@ -969,10 +969,12 @@ def measure(B, torch, np, bw, o):
     path, path_in = paths[o.path], paths[o.path_in or o.path]
     window_in = o.engine_window if o.engine_window >= 0 else ((4, bw["h2d_gbps"] * 1e9, t_bwd) if has_compute else 0)
 
+    more_cfg = {k: int(v, 0) for k, v in (kv.split("=", 1) for kv in getattr(o, "cfg", []))}
+
     def make(bpo_, wgo=workgroups_out, p=None, p_in=None):
         return SwapRun(B, torch, cfgno, swap=True, bpo=bpo_, bpo_in=bpo_in, copy_path=path if p is None else p,
                        copy_path_in=path_in if p_in is None else p_in, copy_workgroups=o.workgroups,
-                       copy_workgroups_out=wgo, flags=flags, cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in, engine_window_out=o.engine_window_out), **extra)
+                       copy_workgroups_out=wgo, flags=flags, cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in, engine_window_out=o.engine_window_out, **more_cfg), **extra)
 
     def trial(label, **kw):
         r = make(**kw)
@@ -1095,7 +1097,7 @@ def measure(B, torch, np, bw, o):
         srun = SwapRun(B, torch, cfgno, swap=True, bpo=bpo, bpo_in=bpo_in, copy_path=path, copy_path_in=path_in,
                        copy_workgroups=o.workgroups, copy_workgroups_out=workgroups_out, flags=flags | B.SS_CFG_STALL_TIMING,
                        cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in,
-                                      engine_window_out=o.engine_window_out), **extra)
+                                      engine_window_out=o.engine_window_out, **more_cfg), **extra)
         srun.step()
         torch.cuda.synchronize()
         a = B.ss_get_stats(srun.ctx)
@@ -1295,6 +1297,9 @@ def main():
                     help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
     ap.add_argument("--engine-window-out", type=int, default=0, help="the same for copy-engine swap-out batches")
+    ap.add_argument("--cfg", action="append", default=[], metavar="FIELD=VALUE",
+                    help="set a further field of the library's configuration record by name (integer value), e.g. "
+                         "--cfg ring_slot_bytes=134217728; may be given several times")
     ap.add_argument("--bare-ring", type=int, default=-1,
                     help="ring route: 1 = ring transfers issued bare by the library's own thread (SS_CFG_BARE_RING), "
                          "0 = with events on their stream, -1 = both are tried and the faster kept")

@@ -184,7 +184,11 @@ typedef struct {
                                  and the last swap-in groups shrink (each at most half of what is still to come,
                                  down to an eighth of a slot), so that little of the backward pass is left to
                                  compute once the last transfer is back; a single batch is never split;
-                                 1 = every group as large as a slot allows                                   */
+                                 1 = every group as large as a slot allows; n = 2..16 = as 0, but a last swap-in
+                                 group takes at most 1/n of what is still to come: where the operators that use
+                                 a group take a fraction r of the time the link needs for the next one, groups
+                                 that halve arrive faster than they are used up and the work piles up behind the
+                                 last one; n >= 1 / (1 - r) keeps the compute stream level with the link       */
   uint32_t copy_desc_lookup;  /* how a workgroup of the copy kernel finds the tensor a chunk belongs to: 0 = a
                                  per-chunk index table in global memory (4 bytes per chunk, built when the
                                  schedule is loaded; no search, no barrier), 1 = the batch's chunk-prefix table
@@ -204,7 +208,8 @@ typedef struct {
                                  for the same transfers                                                      */
   uint32_t engine_window_out; /* the same for copy-engine swap-out batches and ss_swap_out                     */
   uint32_t flag_wait_ms;      /* SS_CFG_BARE_RING: longest a stream polls for a transfer's sequence number before it
-                                 gives up and goes on, in ms (0 = 30,000; at most 600,000)                    */
+                                 gives up and goes on, in ms (0 = 10,000; at most 600,000).  Once one wait has given
+                                 up, no later wait of the iteration polls at all                            */
   uint32_t reserved0;
 } ss_config_t;
 

@@ -206,13 +206,18 @@ __global__ __launch_bounds__(256) void ss_fill_kernel(uint8_t *dst, uint64_t nby
 // Holds its stream until the sequence number at `flag` (device memory, written by a copy-engine transfer) has
 // reached `want`.  One wave; its first lane polls with system-scope loads, which see what the copy engine wrote
 // without a kernel boundary in between, and sleeps between polls so that it takes next to no issue slots from
-// the waves beside it.  The wait is bounded: after `limit_ticks` of the 100 MHz wall clock the lane sets *timeouts
-// (pinned host memory, touched on this path only) and the kernel ends like any other.
-__global__ void ss_wait_flag_kernel(const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *timeouts) {
+// the waves beside it.  The wait is bounded: after `limit_ticks` of the 100 MHz wall clock the lane sets *gave_up
+// (device memory) and *timeouts (pinned host memory, touched on this path only) and the kernel ends like any
+// other; while *gave_up is set no later wait polls at all, so a transfer that never comes costs one limit, not
+// one per wait.
+__global__ void ss_wait_flag_kernel(const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *gave_up,
+                                    uint32_t *timeouts) {
   if (threadIdx.x != 0) return;
   const uint64_t t0 = wall_clock64();
   while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < want) {
+    if (__hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
     if (wall_clock64() - t0 > limit_ticks) {
+      __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       return;
     }
@@ -222,8 +227,9 @@ __global__ void ss_wait_flag_kernel(const uint64_t *flag, uint64_t want, uint64_
 
 }  // namespace
 
-void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *timeouts) {
-  hipLaunchKernelGGL(ss_wait_flag_kernel, dim3(1), dim3(64), 0, s, flag, want, limit_ticks, timeouts);
+void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *gave_up,
+                         uint32_t *timeouts) {
+  hipLaunchKernelGGL(ss_wait_flag_kernel, dim3(1), dim3(64), 0, s, flag, want, limit_ticks, gave_up, timeouts);
 }
 
 void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to_host, uint8_t *arena,

@@ -190,7 +190,8 @@ void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to
 void ss_launch_copy_flat(hipStream_t s, uint32_t workgroups, const uint8_t *src, uint8_t *dst, uint64_t nbytes);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
 // one wave that holds stream s until *flag >= want (ss_wait_flag_kernel; bounded by limit_ticks of 10 ns)
-void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *timeouts);
+void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *gave_up,
+                         uint32_t *timeouts);
 
 // sequence aligner (ss_align.hip): ref_to_cur has n entries
 int ss_align_core(ss_ctx *ctx, const ss_op_t *ref, uint32_t n, const ss_op_t *cur, uint32_t m,

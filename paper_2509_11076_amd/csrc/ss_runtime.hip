@@ -135,6 +135,7 @@ struct ss_engine_queue {
   uint64_t *d_flag = nullptr;                   // device memory, kFlagBytes; first word = last complete job
   uint8_t *h_src = nullptr;                     // pinned, kSources * kFlagBytes
   uint32_t *h_timeouts = nullptr, *d_timeouts = nullptr;   // a pinned word and its device address
+  uint32_t *d_gave_up = nullptr;                // device memory: a wait ran into its limit; later waits do not poll
   uint64_t limit_ticks = 0;                     // bound of a wait, in ticks of 10 ns
   std::thread th;
   std::mutex mu;
@@ -237,6 +238,7 @@ static void eq_destroy(ss_ctx *ctx) {
   }
   if (q->h_done) (void)hipHostFree(q->h_done);
   if (q->d_flag) (void)hipFree(q->d_flag);
+  if (q->d_gave_up) (void)hipFree(q->d_gave_up);
   if (q->h_src) (void)hipHostFree(q->h_src);
   if (q->h_timeouts) (void)hipHostFree(q->h_timeouts);
   delete q;
@@ -249,17 +251,19 @@ static int eq_create(ss_ctx *ctx) {
   ctx->eq = q;
   q->device = ctx->device;
   q->stream = ctx->s_flush;
-  q->limit_ticks = (uint64_t)(ctx->cfg.flag_wait_ms ? ctx->cfg.flag_wait_ms : 30000u) * 100000ull;
+  q->limit_ticks = (uint64_t)(ctx->cfg.flag_wait_ms ? ctx->cfg.flag_wait_ms : 10000u) * 100000ull;
   if (hipMalloc((void **)&q->d_flag, ss_engine_queue::kFlagBytes) != hipSuccess ||
+      hipMalloc((void **)&q->d_gave_up, 256) != hipSuccess ||
       hipHostMalloc((void **)&q->h_src, ss_engine_queue::kSources * ss_engine_queue::kFlagBytes, hipHostMallocDefault) != hipSuccess ||
       hipHostMalloc((void **)&q->h_timeouts, 64, hipHostMallocMapped) != hipSuccess) {
     (void)hipGetLastError();
     return SS_E_NOMEM;
   }
   std::memset(q->h_src, 0, ss_engine_queue::kSources * ss_engine_queue::kFlagBytes);
-  *q->h_timeouts = 0;
+  std::memset(q->h_timeouts, 0, 64);
   SS_HIP(hipHostGetDevicePointer((void **)&q->d_timeouts, q->h_timeouts, 0));
   SS_HIP(hipMemcpy(q->d_flag, q->h_src, ss_engine_queue::kFlagBytes, hipMemcpyHostToDevice));
+  SS_HIP(hipMemcpy(q->d_gave_up, q->h_timeouts + 4, 4, hipMemcpyHostToDevice));       // a word that stays zero
   if (ctx->cfg.flags & SS_CFG_TIMING) {
     if (hipHostMalloc((void **)&q->h_done, ss_engine_queue::kFlagBytes, hipHostMallocDefault) != hipSuccess) {
       (void)hipGetLastError();
@@ -308,7 +312,7 @@ static void eq_wait_idle(ss_ctx *ctx) {
 static int eq_stream_wait(ss_ctx *ctx, hipStream_t st, uint64_t seq, uint64_t *covered) {
   if (seq == 0 || *covered >= seq) return SS_OK;
   ss_engine_queue *q = ctx->eq;
-  ss_launch_wait_flag(st, q->d_flag, seq, q->limit_ticks, q->d_timeouts);
+  ss_launch_wait_flag(st, q->d_flag, seq, q->limit_ticks, q->d_gave_up, q->d_timeouts);
   SS_HIP(hipGetLastError());
   *covered = seq;
   return SS_OK;
@@ -328,7 +332,7 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
     if (cfg.ring_slot_bytes == 0) cfg.ring_slot_bytes = 256ull << 20;
     if (cfg.ring_bytes == 0) cfg.ring_bytes = 1024ull << 20;
     if (cfg.gather_workgroups == 0) cfg.gather_workgroups = 256;
-    if (cfg.gather_workgroups > 4096 || cfg.ring_taper > 1 || cfg.copy_desc_lookup > 1) return SS_E_INVAL;
+    if (cfg.gather_workgroups > 4096 || cfg.ring_taper > 16 || cfg.copy_desc_lookup > 1) return SS_E_INVAL;
     if ((cfg.copy_path == SS_PATH_STAGED || cfg.copy_path_in == SS_PATH_STAGED) &&
         ((cfg.ring_slot_bytes & 255u) || cfg.ring_slot_bytes < 4096 || cfg.ring_bytes / cfg.ring_slot_bytes < 2 ||
          cfg.ring_bytes / cfg.ring_slot_bytes > 64))
@@ -724,11 +728,15 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     // full slot: the first swap-out groups double from kTaperMin up to a slot (a group leaves only once it is
     // complete, so the link starts after the first small group instead of after a slot's worth of forward
     // pass), the first swap-in groups double likewise (the backward pass goes on as soon as the first small
-    // group is back instead of after a whole slot), and the last swap-in groups halve down to kTaperMin (what
-    // the backward pass still has to compute once the last byte is back shrinks with the last group).
-    // kTaperMin is an eighth of a slot.
+    // group is back instead of after a whole slot), and the last swap-in groups shrink down to kTaperMin, each
+    // at most 1/n of what is still to come (what the backward pass still has to compute once the last byte is
+    // back shrinks with the last group; n = 2 halves them, which is right when the operators that use a group
+    // take far less time than the link needs for the next one; when they take a fraction r of it, a group
+    // must not be smaller than r times the one before, or the compute stream falls behind while the small
+    // groups arrive and catches up only after the last one: n >= 1 / (1 - r)).  kTaperMin is an eighth of a slot.
     const uint64_t kTaperMin = std::max<uint64_t>(ctx->cfg.ring_slot_bytes / 8, 256);
-    const bool taper_in = ctx->cfg.ring_taper == 0, taper_out = taper_in;
+    const bool taper_in = ctx->cfg.ring_taper != 1, taper_out = taper_in;
+    const uint64_t taper_den = ctx->cfg.ring_taper >= 2 ? ctx->cfg.ring_taper : 2;
     if (ctx->cfg.copy_path == SS_PATH_STAGED && ctx->ring) {
       const uint64_t slot_full = ctx->cfg.ring_slot_bytes;
       uint64_t grouped = 0;                       // bytes in the groups closed so far
@@ -774,7 +782,7 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
       uint64_t remaining = 0;                     // bytes of the batches from f on
       for (uint32_t i = 0; i < n_in; ++i) remaining += s.in[i].nbytes;
       for (uint32_t f = 0; f < n_in_batches;) {
-        const uint64_t slot = taper_in ? std::min(slot_full, std::min(std::max(kTaperMin, remaining / 2),
+        const uint64_t slot = taper_in ? std::min(slot_full, std::min(std::max(kTaperMin, remaining / taper_den),
                                                                       std::max(kTaperMin, in_grouped))) : slot_full;
         uint64_t lo_off = ~0ull, hi_off = 0, total = 0;
         int64_t best = -1;
@@ -1464,6 +1472,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
           }
           if (*(volatile uint32_t *)ctx->eq->h_timeouts) {
             *(volatile uint32_t *)ctx->eq->h_timeouts = 0;
+            SS_HIP(hipMemcpy(ctx->eq->d_gave_up, ctx->eq->h_timeouts + 4, 4, hipMemcpyHostToDevice));   // every stream is idle
             late = SS_E_TIMEOUT;
           }
         }

@@ -41,7 +41,7 @@ def random_arena(torch, nbytes, seed):
 
 @pytest.mark.parametrize("bpo", [64 * 1024, INSTANT])
 @pytest.mark.parametrize("slot_kib,slots", [(512, 2), (1024, 3), (4096, 2)])
-@pytest.mark.parametrize("staged_in,taper", [(False, 0), (True, 0), (True, 1)])
+@pytest.mark.parametrize("staged_in,taper", [(False, 0), (True, 0), (True, 1), (True, 4)])
 @pytest.mark.parametrize("bare", [False, True])
 def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, taper, bare):
     """configuration 1 with ring slots smaller than, about, and larger than a layer's swap set: staging
@@ -97,13 +97,14 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
                 assert int(in_group_bytes.max()) <= slot_kib << 10
                 for g in range(len(in_group_bytes)):
                     assert P.ss_batch_ms(ctx, 3, g)[0] > 0
-                # group shapes: tapered, each swap-in group (of more than one batch) is at most half of what is
-                # still to come including itself, but never asked to be smaller than an eighth of a slot;
+                # group shapes: tapered, each swap-in group (of more than one batch) is at most half (a taper of
+                # n >= 2: 1/n) of what is still to come including itself, but never asked to be smaller than an
+                # eighth of a slot;
                 # untapered, a group ends only where the next batch would overflow the slot or leave a gap
                 sizes = in_group_bytes.tolist()
                 batches_in = np.bincount(in_group_of, minlength=len(sizes)).tolist()
                 for g, n in enumerate(sizes):
-                    cap = max((slot_kib << 10) // 8, min(sum(sizes[g:]) // 2, sum(sizes[:g])))
+                    cap = max((slot_kib << 10) // 8, min(sum(sizes[g:]) // max(2, taper), sum(sizes[:g])))
                     if taper != 1 and batches_in[g] > 1:
                         assert n <= cap
                 if taper == 1 and sum(sizes) > slot_kib << 10:
@@ -111,7 +112,7 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
                 out_sizes = group_bytes.tolist()
                 batches_out = np.bincount(group_of, minlength=len(out_sizes)).tolist()
                 for g, n in enumerate(out_sizes):
-                    if taper == 0 and batches_out[g] > 1:
+                    if taper != 1 and batches_out[g] > 1:
                         assert n <= max((slot_kib << 10) // 8, sum(out_sizes[:g]))
             else:
                 assert len(in_group_bytes) == 0 and (in_group_of == -1).all()
@@ -273,6 +274,8 @@ def test_bare_ring_wait_gives_up_after_its_limit_and_the_drain_says_so(P, torch)
     host = arena.cpu().numpy().copy()
     with pytest.raises(P.SsError):
         make_ctx(P, staging_bytes=4096, flag_wait_ms=600001)
+    with pytest.raises(P.SsError):
+        make_ctx(P, staging_bytes=4096, ring_taper=17)
     for limit in (1, 0):
         ctx = make_ctx(P, staging_bytes=nb * sz, copy_path=P.SS_PATH_STAGED, copy_path_in=P.SS_PATH_STAGED,
                        ring_slot_bytes=sz, ring_bytes=2 * sz, ring_taper=1, flags=P.SS_CFG_BARE_RING, flag_wait_ms=limit)
