@@ -971,10 +971,10 @@ def measure(B, torch, np, bw, o):
 
     more_cfg = {k: int(v, 0) for k, v in (kv.split("=", 1) for kv in getattr(o, "cfg", []))}
 
-    def make(bpo_, wgo=workgroups_out, p=None, p_in=None):
+    def make(bpo_, wgo=workgroups_out, p=None, p_in=None, fl=None):
         return SwapRun(B, torch, cfgno, swap=True, bpo=bpo_, bpo_in=bpo_in, copy_path=path if p is None else p,
                        copy_path_in=path_in if p_in is None else p_in, copy_workgroups=o.workgroups,
-                       copy_workgroups_out=wgo, flags=flags, cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in, engine_window_out=o.engine_window_out, **more_cfg), **extra)
+                       copy_workgroups_out=wgo, flags=flags if fl is None else fl, cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in, engine_window_out=o.engine_window_out, **more_cfg), **extra)
 
     def trial(label, **kw):
         r = make(**kw)
@@ -1002,14 +1002,23 @@ def measure(B, torch, np, bw, o):
     # Likewise the route: directly between the blocks and the staging area (SS_PATH_AUTO), or through the
     # rings in HBM with one copy-engine transfer per ring slot (SS_PATH_STAGED).  Configuration 3's tensors
     # exceed a ring slot and all go by copy engine: nothing to choose there.
-    grid_fits, path_fits = [], []
+    grid_fits, path_fits, bare_fits = [], [], []
     if has_compute and cfgno != 3 and o.calibrate > 0:
         if o.path == "auto" and o.path_in is None and cfgno == 2:
             for name, p in (("auto", B.SS_PATH_AUTO), ("staged", B.SS_PATH_STAGED)):
-                t_trial = trial("route %s" % name, bpo_=bpo, p=p, p_in=p)[0]
+                fl_ = flags | (B.SS_CFG_BARE_RING if p == B.SS_PATH_STAGED and getattr(o, "bare_ring", -1) != 0 else 0)
+                t_trial = trial("route %s" % name, bpo_=bpo, p=p, p_in=p, fl=fl_)[0]
                 path_fits.append({"route": name, "ms_per_step": round(t_trial * 1e3, 2)})
             if path_fits[1]["ms_per_step"] < 0.99 * path_fits[0]["ms_per_step"]:
                 path = path_in = B.SS_PATH_STAGED
+        if B.SS_PATH_STAGED in (path, path_in) and getattr(o, "bare_ring", -1) < 0:
+            # the ring's copy-engine transfers with events on their stream, or bare and issued by the library's
+            # own thread (SS_CFG_BARE_RING)
+            for name, fl in (("with events", flags), ("bare", flags | B.SS_CFG_BARE_RING)):
+                t_trial = trial("ring transfers %s" % name, bpo_=bpo, p=path, p_in=path_in, fl=fl)[0]
+                bare_fits.append({"ring_transfers": name, "ms_per_step": round(t_trial * 1e3, 2)})
+            if bare_fits[1]["ms_per_step"] < 0.995 * bare_fits[0]["ms_per_step"]:
+                flags |= B.SS_CFG_BARE_RING
         if workgroups_out == 0 and path != B.SS_PATH_STAGED:
             for wgo in (0, 8):
                 t_trial = trial("pack grid %s" % (wgo or "default"), bpo_=bpo, wgo=wgo)[0]
@@ -1176,7 +1185,10 @@ def measure(B, torch, np, bw, o):
                             "kernel (%s)" % (PACK_TRAFFIC_RATIO, PACK_TRAFFIC_SOURCE),
             "mover": out_by, "kernel": kname, "avg_launch_ms": round(avg_launch_ms, 4),
             "bytes_per_launch": int(bytes_per_launch), "launches_timed": len(k_ms),
-            "launches_timed_note": "HIP events of the last timed step and of %d further steps" % (event_steps - 1),
+            "launches_timed_note": ("HIP events of the last timed step and of %d further steps" % (event_steps - 1)) + (
+                "; the ring's bare copy-engine transfers carry no events and are timed on the host's clock (a copy of each "
+                "transfer's sequence number arriving in pinned memory, watched by a thread that makes no HIP call)"
+                if flags & B.SS_CFG_BARE_RING and B.SS_PATH_STAGED in (path, path_in) else ""),
             "hbm": {"achieved": round(link_achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(link_achieved / HBM_PEAK_GBPS, 5),
                     "note": "HBM side of the same bytes (one HBM access per byte moved over the link); by design far from the HBM roofline"}}
@@ -1206,7 +1218,9 @@ def measure(B, torch, np, bw, o):
                    "swap_out_by": out_by, "swap_in_by": in_by,
                    "link_bytes_per_op": bpo, "prefetch_bytes_per_op": bpo_in, "engine_window_in": engine_window_used,
                    "link_model_fits": calib,
-                   "route_fits": path_fits, "pack_grid_fits": grid_fits,
+                   "route_fits": path_fits, "pack_grid_fits": grid_fits, "ring_transfer_fits": bare_fits,
+                   "ring_transfers": ("bare, issued by the library's own thread" if flags & B.SS_CFG_BARE_RING
+                                      else "with events on their stream") if B.SS_PATH_STAGED in (path, path_in) else None,
                    "pack_workgroups": workgroups_out or o.workgroups or "default (64)", "policy_mode": o.policy_mode,
                    "timing": o.timing if o.policy_mode == "generated" else "link-model",
                    "generator_params": {k: v for k, v in extra.get("generator", {}).items()} or None,

@@ -72,7 +72,13 @@ struct ss_sched {
   std::vector<std::vector<uint32_t>> in_group_outs; // per group: the swap-out batches its tensors left in
   std::vector<uint8_t> in_group_state;              // per group, this iteration: 0 untouched, 1 fetched, 2 not usable (direct)
   std::vector<int32_t> in_group_last_scatter;       // per group, this iteration: swap-in batch scattered most recently, -1 = none
-  std::vector<int32_t> in_slot_owner;               // per slot of the swap-in ring: group whose bytes it holds, -1 = none
+  // Consecutive swap-in groups share a ring slot while they fit together (a "pack"): the small groups at the two
+  // ends of the iteration would otherwise each hold a whole slot, and the link could run only a few small
+  // transfers ahead of the compute stream.
+  std::vector<int32_t> in_pack_of;                  // per swap-in group: its pack; pack p lives in slot p % n_slots
+  std::vector<uint64_t> in_pack_off;                // per swap-in group: where it starts inside the slot
+  std::vector<int32_t> in_pack_last_scatter;        // per pack, this iteration: swap-in batch scattered most recently, -1 = none
+  std::vector<int32_t> in_slot_owner;               // per slot of the swap-in ring: pack whose bytes it holds, -1 = none
   std::vector<hipEvent_t> ev_fetched[2], ev_fetch_start[2];   // per group
   std::vector<uint8_t> in_group_state_drained;
   // SS_CFG_BARE_RING: sequence numbers of the ring transfers in place of their events (0 = none)

@@ -129,7 +129,7 @@ struct ss_engine_job {
 
 struct ss_engine_queue {
   static constexpr size_t kFlagBytes = 65536;   // an 8-byte transfer is done by a kernel of the runtime, not by the copy engine
-  static constexpr uint64_t kSources = 32;      // source buffers of the flag transfers, reused in turn
+  static constexpr uint64_t kSources = 256;     // source buffers of the flag transfers, reused in turn
   int device = 0;
   hipStream_t stream = nullptr;                 // the context's stream for ring transfers
   uint64_t *d_flag = nullptr;                   // device memory, kFlagBytes; first word = last complete job
@@ -144,7 +144,7 @@ struct ss_engine_queue {
   bool stop = false, busy = false, started = false;
   uint64_t next_seq = 1;                        // dispatch thread
   uint64_t enqueued_seq = 0;                    // last job handed to the stream (under mu)
-  uint64_t synced_seq = 0;                      // the thread's own: jobs up to here are known to be complete
+  uint64_t synced_seq = 0;                      // jobs up to here are known to be complete (the thread's own while it works; set by the drain while it idles)
   std::atomic<int> hip_error{0};                // first HIP error the thread met
   uint64_t waited_out = 0, waited_in = 0;       // dispatch thread: highest number a wait on the swap-out / swap-in stream covers
   // SS_CFG_TIMING: the transfers carry no events, so their times are taken on the host's clock.  A third
@@ -557,6 +557,7 @@ static void ring_reset(ss_sched &s, uint32_t n_slots) {
   s.in_slot_owner.assign(n_slots, -1);
   std::fill(s.in_group_state.begin(), s.in_group_state.end(), 0);
   std::fill(s.in_group_last_scatter.begin(), s.in_group_last_scatter.end(), -1);
+  std::fill(s.in_pack_last_scatter.begin(), s.in_pack_last_scatter.end(), -1);
   std::fill(s.out_staged.begin(), s.out_staged.end(), 0);
   s.last_flush_batch = s.last_gather_batch = -1;
   std::fill(s.flush_seq.begin(), s.flush_seq.end(), 0);
@@ -822,6 +823,26 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
         s.in_group_outs.push_back(std::move(outs));
         f = (uint32_t)best + 1;
       }
+      // packs: consecutive groups share a slot while they fit together
+      s.in_pack_of.assign(s.in_groups.size(), 0);
+      s.in_pack_off.assign(s.in_groups.size(), 0);
+      int32_t pack = -1;
+      uint64_t used = slot_full;
+      for (size_t g = 0; g < s.in_groups.size(); ++g) {
+        const uint64_t need = ss_align_up(s.in_groups[g].bytes, 256);
+        if (used + need > slot_full) {
+          ++pack;
+          used = 0;
+        }
+        s.in_pack_of[g] = pack;
+        s.in_pack_off[g] = used;
+        used += need;
+      }
+      s.in_pack_last_scatter.assign((size_t)(pack + 1), -1);
+    } else {
+      s.in_pack_of.clear();
+      s.in_pack_off.clear();
+      s.in_pack_last_scatter.clear();
     }
     s.in_group_state.assign(s.in_groups.size(), 0);
     s.in_group_state_drained.assign(s.in_groups.size(), 0);
@@ -1230,10 +1251,12 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
   ss_sched &s = ctx->sched;
   const uint32_t g = (uint32_t)s.in_group_of[batch];
   const ss_sched::in_group &G = s.in_groups[g];
-  const uint32_t slot = g % ctx->n_slots;
+  const int32_t pack = s.in_pack_of[g];
+  const uint32_t slot = (uint32_t)pack % ctx->n_slots;
+  uint8_t *const home = ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes + s.in_pack_off[g];   // the group's place in the ring
   if (s.in_group_state[g] == 2) return 0;
   if (s.in_group_state[g] == 0) {
-    bool usable = s.in_slot_owner[slot] <= (int32_t)g;
+    bool usable = s.in_slot_owner[slot] <= pack;
     for (uint32_t ob : s.in_group_outs[g]) usable = usable && s.out_issued[ob];   // every byte of the range is on its way
     if (!usable) {
       s.in_group_state[g] = 2;
@@ -1244,27 +1267,25 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
     if (rc != SS_OK) return rc;
     hipStream_t se = ctx->s_flush;
     const int32_t pd = s.prev_direct[s.in_group_outs[g].back()];
-    const int32_t og = s.in_slot_owner[slot];
+    const int32_t op = s.in_slot_owner[slot];           // the pack the slot held so far (this one, if a group of it came before)
     hipEvent_t pre[3];
     int n_pre = 0;
     if (pd >= 0 && s.out_issued[(size_t)pd]) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)pd];
     if (s.last_engine_out >= 0) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)s.last_engine_out];
-    if (og >= 0 && og != (int32_t)g && s.in_group_last_scatter[(size_t)og] >= 0)
-      pre[n_pre++] = s.ev_in_done[s.phase][(size_t)s.in_group_last_scatter[(size_t)og]];
-    s.in_slot_owner[slot] = (int32_t)g;
+    if (op >= 0 && op != pack && s.in_pack_last_scatter[(size_t)op] >= 0)
+      pre[n_pre++] = s.ev_in_done[s.phase][(size_t)s.in_pack_last_scatter[(size_t)op]];
+    s.in_slot_owner[slot] = pack;
     if (ctx->eq) {
-      s.fetch_seq[g] = eq_push(ctx, ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes, ctx->staging + G.host_lo, G.bytes,
-                               hipMemcpyHostToDevice, pre, n_pre, 3, g);
+      s.fetch_seq[g] = eq_push(ctx, home, ctx->staging + G.host_lo, G.bytes, hipMemcpyHostToDevice, pre, n_pre, 3, g);
     } else {
       for (int i = 0; i < n_pre; ++i) SS_HIP(hipStreamWaitEvent(se, pre[i], 0));
       if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_fetch_start[s.phase][g], se));
-      SS_HIP(hipMemcpyAsync(ctx->ring_in + (size_t)slot * ctx->cfg.ring_slot_bytes, ctx->staging + G.host_lo, G.bytes,
-                            hipMemcpyHostToDevice, se));
+      SS_HIP(hipMemcpyAsync(home, ctx->staging + G.host_lo, G.bytes, hipMemcpyHostToDevice, se));
       SS_HIP(hipEventRecord(s.ev_fetched[s.phase][g], se));
     }
     s.in_group_state[g] = 1;
     ctx->stats.ring_transfers_in++;
-  } else if (s.in_slot_owner[slot] != (int32_t)g) {
+  } else if (s.in_slot_owner[slot] != pack) {
     return 0;                                   // the slot has been handed on: the staging area still holds the bytes
   }
   hipStream_t si = ctx->s_in[0];
@@ -1277,7 +1298,7 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
     SS_HIP(hipStreamWaitEvent(si, s.ev_fetched[s.phase][g], 0));
   }
   if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_in_start[s.phase][batch], si));
-  uint8_t *base = (uint8_t *)((uintptr_t)ctx->ring_in + (uintptr_t)slot * ctx->cfg.ring_slot_bytes - (uintptr_t)G.host_lo);
+  uint8_t *base = (uint8_t *)((uintptr_t)home - (uintptr_t)G.host_lo);
   const uint32_t *c0 = s.d_in_chunk0 + lo + batch;
   const uint32_t n_chunks = s.in_chunk0[(size_t)hi + batch];
   ss_launch_copy(si, ctx->cfg.gather_workgroups, ctx->cfg.copy_unroll, false, ctx->arena, base, s.d_in + lo, c0,
@@ -1286,6 +1307,7 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
   SS_HIP(hipEventRecord(s.ev_in_done[s.phase][batch], si));
   s.in_issued[batch] = 1;
   s.in_group_last_scatter[g] = (int32_t)batch;
+  s.in_pack_last_scatter[(size_t)pack] = (int32_t)batch;
   ctx->stats.kernel_batches++;
   ctx->stats.ring_batches_in++;
   return 1;
@@ -1464,6 +1486,10 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
         if (rc == SS_OK) rc = sync_swap_streams(ctx);
         if (rc != SS_OK) return rc;
         if (ctx->eq) {
+          {
+            std::lock_guard<std::mutex> lk(ctx->eq->mu);          // the thread is idle and its stream empty
+            ctx->eq->synced_seq = ctx->eq->enqueued_seq;
+          }
           eq_harvest(ctx);
           const int he = ctx->eq->hip_error.exchange(0);
           if (he) {

@@ -231,7 +231,7 @@ def test_every_launch_shape_within_the_limits_moves_the_same_bytes(P, torch, wor
             make_ctx(P, staging_bytes=4096, copy_cus=100000)
         assert e.value.code == P.SS_E_INVAL
         for bad in (dict(copy_workgroups=4097), dict(copy_unroll=9), dict(copy_workgroups_out=5000),
-                    dict(copy_desc_lookup=2), dict(ring_taper=2)):
+                    dict(copy_desc_lookup=2), dict(ring_taper=17)):
             with pytest.raises(P.SsError) as e:
                 make_ctx(P, staging_bytes=4096, **bad)
             assert e.value.code == P.SS_E_INVAL
