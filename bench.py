@@ -339,7 +339,8 @@ def record_mover_table(B, torch, np, bw, args):
     combos = [("kernel", "engine", {}), ("kernel", "kernel", {}), ("kernel", "kernel", dict(workgroups=16)),
               ("kernel", "kernel", dict(copy_cus=8)), ("kernel", "kernel", dict(copy_cus=16)),
               ("kernel", "kernel", dict(copy_cus=64)),
-              ("engine", "engine", {}), ("engine", "kernel", {}), ("staged", "engine", {}), ("staged", "staged", {})]
+              ("engine", "engine", {}), ("engine", "kernel", {}), ("staged", "engine", {}), ("staged", "staged", {}),
+              ("staged", "staged", dict(bare_ring=1))]
     # the whole table runs on a compute stream of its own: swap streams with a compute-unit mask synchronise with
     # the null stream (the runtime has no non-blocking form of them)
     own = torch.cuda.Stream()
@@ -357,7 +358,7 @@ def record_mover_table(B, torch, np, bw, args):
         o.config, o.path, o.path_in, o.calibrate, o.no_cpu_baseline, o.no_stall_timing = 2, p_out, p_in, 0, True, True
         o.bpo = args.bpo if args.bpo > 0 else 11500000
         o.steps, o.warmup = min(args.steps, 8), max(args.warmup, 11)      # the stage machine needs nine iterations to settle
-        o.copy_cus = 0
+        o.copy_cus, o.bare_ring = 0, 0
         for k, v in kw.items():
             setattr(o, k, v)
         r = measure(B, torch, np, bw, o)
