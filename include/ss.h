@@ -296,6 +296,9 @@ int ss_config_default(ss_config_t *cfg /* host, out */);
  * streams the first one got (where the runtime places a new stream changes how much a transfer costs the
  * kernels beside it; streams with a compute-unit mask, copy_cus > 0, are the context's own).  Contexts
  * alive at the same time get different streams.
+ * With SS_CFG_BARE_RING and a ring route the context also starts a host thread of its own that issues the
+ * ring transfers (and, with SS_CFG_TIMING, a second one that watches them complete); both end in ss_destroy.
+ * The calls on one context still have to come from one thread at a time.
  * SS_E_NOMEM if pinned memory is refused. */
 int ss_create(ss_ctx **out /* host, out */, const ss_config_t *cfg /* host, nullable */);
 int ss_destroy(ss_ctx *ctx);
