@@ -307,3 +307,79 @@ def test_bare_ring_wait_gives_up_after_its_limit_and_the_drain_says_so(P, torch)
                     assert np.array_equal(arena.cpu().numpy(), host)
         finally:
             P.ss_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_schedules_through_the_rings_both_ways_of_issuing_the_transfers(P, torch, seed):
+    """random mixtures of ring-eligible and ragged batches, random slot sizes and counts, tapers 0 / 1 / 4, swap-outs
+    in schedule order or shuffled, swap-ins in reverse or shuffled order (each after its swap-out), with events
+    behind the ring transfers and bare: staging image and arena equal the oracle's, and both ways of issuing move
+    the same bytes"""
+    rng = np.random.default_rng(1000 + seed)
+    KiB = 1 << 10
+    n_batches = int(rng.integers(6, 20))
+    sizes, starts = [], [0]
+    for b in range(n_batches):
+        k = int(rng.integers(1, 4))
+        ragged = rng.random() < 0.2
+        for _ in range(k):
+            sz = int(rng.integers(1, 9)) * 64 * KiB
+            if ragged:
+                sz += int(rng.integers(1, 200))
+            sizes.append(sz)
+        starts.append(len(sizes))
+    n = len(sizes)
+    d = np.zeros(n, dtype=W.DESC_DT)
+    off = h = 0
+    for i, sz in enumerate(sizes):
+        d[i] = (off, h, sz, i, 0)
+        off += (sz + 4095) // 4096 * 4096 + 4096
+        h += (sz + 255) // 256 * 256
+    arena_bytes = off
+    arena = random_arena(torch, arena_bytes, 300 + seed)
+    host = arena.cpu().numpy().copy()
+    start = np.array(starts, dtype=np.uint32)
+    dep = np.arange(n_batches, dtype=np.uint32)
+    rows = [tuple(int(x) for x in r) for r in d.tolist()]
+    slot = int(rng.choice([512, 1024, 2048])) * KiB
+    slots = int(rng.integers(2, 5))
+    taper = int(rng.choice([0, 1, 4]))
+    path_in = int(rng.choice([P.SS_PATH_AUTO, P.SS_PATH_STAGED]))
+    order_out = list(range(n_batches))
+    if rng.random() < 0.5:
+        rng.shuffle(order_out)
+    order_in = list(reversed(range(n_batches)))
+    if rng.random() < 0.5:
+        rng.shuffle(order_in)
+    want_staging = np.full(h, 0x11, dtype=np.uint8)
+    oracle.swap_out(host, want_staging, rows)
+    want_arena = np.full(arena_bytes, 0x3C, dtype=np.uint8)
+    oracle.swap_in(want_arena, want_staging, rows)
+    stats = []
+    for bare in (0, 1):
+        ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_STAGED, copy_path_in=path_in, ring_slot_bytes=slot,
+                       ring_bytes=slots * slot, ring_taper=taper, flags=P.SS_CFG_BARE_RING if bare else 0)
+        try:
+            P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+            P.ss_load_schedule(ctx, d, start, d, start, dep)
+            for it in range(2):
+                arena.copy_(torch.from_numpy(host).cuda())
+                P.ss_staging_fill(ctx, 0x11)
+                for b in order_out:
+                    P.ss_swap_out(ctx, b)
+                for t in range(n):
+                    P.ss_sync(ctx, P.SS_SYNC_FREE, t)
+                arena.fill_(0x3C)                      # compute stream: every released block is overwritten
+                for b in order_in:
+                    P.ss_swap_in(ctx, b)
+                for t in range(n):
+                    P.ss_sync(ctx, P.SS_SYNC_WAIT_IN, t)
+                P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+                torch.cuda.synchronize()
+                assert np.array_equal(P.ss_host_peek(ctx, 0, h), want_staging), (seed, bare, it)
+                assert np.array_equal(arena.cpu().numpy(), want_arena), (seed, bare, it)
+            st = P.ss_get_stats(ctx)
+            stats.append((st["bytes_out"], st["bytes_in"], st["ring_batches"], st["ring_batches_in"]))
+        finally:
+            P.ss_destroy(ctx)
+    assert stats[0] == stats[1] and stats[0][0] == 2 * sum(sizes)
