@@ -77,7 +77,8 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
             assert np.array_equal(P.ss_host_peek(ctx, 0, ora["staging_bytes"]), staging)
             assert np.array_equal(arena.cpu().numpy(), host_arena)
             for g in range(len(group_bytes)):
-                assert P.ss_batch_ms(ctx, 2, g)[0] > 0          # bare: on the host's clock
+                # bare: on the host's clock, where two short transfers may be seen complete in the same look
+                assert P.ss_batch_ms(ctx, 2, g)[0] >= 0 if bare else P.ss_batch_ms(ctx, 2, g)[0] > 0
             assert P.ss_batch_ms(ctx, 2)[1] > 0 and P.ss_batch_ms(ctx, 0, 0)[0] > 0
             if bare:                                   # no events on the transfers: nothing to place them among the batches
                 with pytest.raises(P.SsError) as ei:
@@ -96,7 +97,7 @@ def test_toy_config_through_the_ring(P, torch, bpo, slot_kib, slots, staged_in, 
                 assert (in_group_of >= 0).all() and int(in_group_bytes.sum()) == int(group_bytes.sum())
                 assert int(in_group_bytes.max()) <= slot_kib << 10
                 for g in range(len(in_group_bytes)):
-                    assert P.ss_batch_ms(ctx, 3, g)[0] > 0
+                    assert P.ss_batch_ms(ctx, 3, g)[0] >= 0 if bare else P.ss_batch_ms(ctx, 3, g)[0] > 0
                 # group shapes: tapered, each swap-in group (of more than one batch) is at most half (a taper of
                 # n >= 2: 1/n) of what is still to come including itself, but never asked to be smaller than an
                 # eighth of a slot;
