@@ -206,13 +206,16 @@ static void engine_thread(ss_engine_queue *q) {
     }
     uint64_t *src = (uint64_t *)(q->h_src + (size_t)(job.seq % ss_engine_queue::kSources) * ss_engine_queue::kFlagBytes);
     *src = job.seq;
+    if (q->timing) {                            // noted before the transfer can complete: the watching thread looks it up
+      std::lock_guard<std::mutex> lk(q->mu);
+      q->recs.push_back({job.seq, job.dir, job.unit, host_ms(), -1.0});
+    }
     if (job.bytes) note(hipMemcpyAsync(job.dst, job.src, job.bytes, job.kind, q->stream));
     // published even after a failure, so that nothing waits for this job in vain
     note(hipMemcpyAsync(q->d_flag, src, ss_engine_queue::kFlagBytes, hipMemcpyHostToDevice, q->stream));
     if (q->timing) note(hipMemcpyAsync(q->h_done, q->d_flag, ss_engine_queue::kFlagBytes, hipMemcpyDeviceToHost, q->stream));
     {
       std::lock_guard<std::mutex> lk(q->mu);
-      if (q->timing) q->recs.push_back({job.seq, job.dir, job.unit, host_ms(), -1.0});
       q->enqueued_seq = job.seq;
       q->busy = false;
       if (q->q.empty()) q->cv_idle.notify_all();
