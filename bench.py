@@ -475,17 +475,45 @@ def record_transfer_cost_table(B, torch, np):
                 after()
         return round(min(out[1:]), 2)
 
+    flag_host = {nb: torch.zeros(nb, dtype=torch.uint8, pin_memory=True) for nb in (8, 65536)}
+    flag_dev = {nb: torch.zeros(nb, dtype=torch.uint8, device="cuda") for nb in (8, 65536)}
+
+    def transfer(k, d2h):
+        a, b = host[k * 256 * M:(k + 1) * 256 * M], dev[k * 256 * M:(k + 1) * 256 * M]
+        (a.copy_(b, non_blocking=True) if d2h else b.copy_(a, non_blocking=True))
+
     def plain(d2h, extra):
         def go():
             with torch.cuda.stream(side):
                 for k in range(11):
-                    a, b = host[k * 256 * M:(k + 1) * 256 * M], dev[k * 256 * M:(k + 1) * 256 * M]
-                    (a.copy_(b, non_blocking=True) if d2h else b.copy_(a, non_blocking=True))
+                    transfer(k, (k % 2 == 0) if d2h == "mixed" else d2h)
                     if extra == "event" or (extra == "event_first" and k == 0) or (extra == "event_last" and k == 10):
                         torch.cuda.Event().record(side)
                     elif extra == "kernel":
                         dev[:64].zero_()
+                    elif extra in ("flag8", "flag64k"):       # a second, small transfer behind each: a sequence number
+                        nb = 8 if extra == "flag8" else 65536
+                        flag_dev[nb].copy_(flag_host[nb], non_blocking=True)
         return go
+
+    def threaded(d2h):
+        """the transfers issued by a second host thread that waits for their stream after each"""
+        import threading
+        box = {}
+
+        def work():
+            with torch.cuda.stream(side):
+                for k in range(11):
+                    transfer(k, d2h)
+                    side.synchronize()
+
+        def go():
+            box["t"] = threading.Thread(target=work)
+            box["t"].start()
+
+        def join():
+            box["t"].join()
+        return go, join
     rows = [{"traffic": "none", "backward_pass_ms": best(None)}]
     for d2h in (False, True):
         for extra, what in ((None, "nothing else on their stream"), ("event", "an event recorded on their stream after each"),
@@ -497,6 +525,20 @@ def record_transfer_cost_table(B, torch, np):
             rows.append({"traffic": "11 copy-engine transfers of 256 MiB %s (PyTorch copy_), %s" % (
                 "device to host" if d2h else "host to device", what), "backward_pass_ms": best(plain(d2h, extra))})
             log("transfer cost table: %s" % rows[-1])
+    # what signalling completion through memory costs instead: a small transfer of a sequence number behind each
+    # transfer, both directions on one stream, the transfers issued by a thread that waits for each on the host
+    for d2h, extra, what in ((False, "flag64k", "host to device, each followed by a host-to-device transfer of 64 KiB"),
+                             (False, "flag8", "host to device, each followed by a host-to-device transfer of 8 bytes"),
+                             (True, "flag64k", "device to host, each followed by a host-to-device transfer of 64 KiB"),
+                             ("mixed", None, "alternately device to host and host to device on one stream, nothing else on it")):
+        rows.append({"traffic": "11 copy-engine transfers of 256 MiB %s" % what, "backward_pass_ms": best(plain(d2h, extra))})
+        log("transfer cost table: %s" % rows[-1])
+    for d2h in (False, True):
+        go_, join_ = threaded(d2h)
+        rows.append({"traffic": "11 copy-engine transfers of 256 MiB %s, issued by a second host thread that waits for "
+                                "their stream after each" % ("device to host" if d2h else "host to device"),
+                     "backward_pass_ms": best(go_, join_)})
+        log("transfer cost table: %s" % rows[-1])
     del host
     for path, pname in ((B.SS_PATH_ENGINE, "copy engine"), (B.SS_PATH_KERNEL, "ss_copy_kernel")):
         for nb in (11, 33, 132):
