@@ -140,7 +140,12 @@ enum { SS_CFG_TIMING = 1,        /* record start/stop events per batch (ss_batch
                                     SS_CFG_TIMING their durations (ss_batch_ms, directions 2 and 3) are taken
                                     on the host's clock by a second thread that watches a copy of the
                                     sequence number arrive in pinned memory, and ss_batch_window has none
-                                    for them (SS_E_STATE).  Without SS_PATH_STAGED the flag does nothing    */
+                                    for them (SS_E_STATE).  Batches that do not go through a ring then move
+                                    by copy kernel, never by copy engine, and the caller should not enqueue
+                                    copy-engine transfers of its own behind waits for swapped-in tensors: a
+                                    transfer whose turn has not come holds up the engine's queue, in which
+                                    the sequence numbers travel (the waits are bounded, so the worst case is
+                                    SS_E_TIMEOUT).  Without SS_PATH_STAGED the flag does nothing            */
 
 typedef struct {
   uint64_t staging_bytes;     /* pinned host staging to allocate at ss_create                */

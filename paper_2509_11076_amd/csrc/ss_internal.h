@@ -46,7 +46,7 @@ struct ss_sched {
   std::vector<out_group> groups;
   std::vector<uint64_t> group_bytes;                // per group, for ss_ring_view
   std::vector<int32_t> group_of;                    // per swap-out batch: its group, -1 = leaves directly
-  std::vector<int32_t> prev_direct;                 // per swap-out batch b: largest direct batch <= b, -1 = none
+  int64_t last_direct_out = -1;                     // swap-out batch that left directly (not through the ring) most recently, this iteration
   std::vector<hipEvent_t> ev_gathered[2];           // per batch: its bytes are in the ring (the block may be released)
   std::vector<hipEvent_t> ev_flush_start[2];        // per group (SS_CFG_TIMING): its first transfer starts
   std::vector<int32_t> done_ev_of;                  // per batch, this iteration: batch whose ev_out_done covers it; -1 = not sent yet

@@ -161,6 +161,40 @@ struct ss_engine_queue {
   std::vector<double> unit_start[2], unit_end[2];   // iteration drained last: per ring group, ms on the host's clock; < 0 = none
 };
 
+// Contexts that are still alive when the process ends (an exception on the caller's side, say) would leave
+// their threads running while the runtime unmaps the pinned memory they look at.  This library's static objects
+// are destroyed before those of the runtime it depends on, so the threads are stopped here: the watching thread
+// always (it never blocks), the issuing thread if it is idle (else it is left to the process's end).
+namespace {
+std::mutex g_live_mu;
+std::vector<ss_engine_queue *> g_live;
+struct live_queues_reaper {
+  ~live_queues_reaper() {
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    for (ss_engine_queue *q : g_live) {
+      if (q->timing && q->observer.joinable()) {
+        q->stop_observer.store(true);
+        q->observer.join();
+      }
+      bool idle;
+      {
+        std::lock_guard<std::mutex> lk(q->mu);
+        idle = q->q.empty() && !q->busy;
+        if (idle) q->stop = true;
+      }
+      if (!q->th.joinable()) continue;
+      if (idle) {
+        q->cv.notify_all();
+        q->th.join();
+      } else {
+        q->th.detach();
+      }
+    }
+    g_live.clear();
+  }
+} g_live_queues_reaper;
+}  // namespace
+
 static double host_ms() {
   return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
@@ -226,6 +260,10 @@ static void engine_thread(ss_engine_queue *q) {
 static void eq_destroy(ss_ctx *ctx) {
   ss_engine_queue *q = ctx->eq;
   if (!q) return;
+  {
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    g_live.erase(std::remove(g_live.begin(), g_live.end(), q), g_live.end());
+  }
   if (q->started) {
     {
       std::lock_guard<std::mutex> lk(q->mu);
@@ -278,6 +316,10 @@ static int eq_create(ss_ctx *ctx) {
   }
   q->th = std::thread(engine_thread, q);
   q->started = true;
+  {
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    g_live.push_back(q);
+  }
   return SS_OK;
 }
 
@@ -562,7 +604,7 @@ static void ring_reset(ss_sched &s, uint32_t n_slots) {
   std::fill(s.in_group_last_scatter.begin(), s.in_group_last_scatter.end(), -1);
   std::fill(s.in_pack_last_scatter.begin(), s.in_pack_last_scatter.end(), -1);
   std::fill(s.out_staged.begin(), s.out_staged.end(), 0);
-  s.last_flush_batch = s.last_gather_batch = -1;
+  s.last_flush_batch = s.last_gather_batch = s.last_direct_out = -1;
   std::fill(s.flush_seq.begin(), s.flush_seq.end(), 0);
   std::fill(s.group_last_flush_seq.begin(), s.group_last_flush_seq.end(), 0);
   std::fill(s.fetch_seq.begin(), s.fetch_seq.end(), 0);
@@ -727,7 +769,6 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     s.groups.clear();
     s.group_bytes.clear();
     s.group_of.assign(n_out_batches, -1);
-    s.prev_direct.assign(n_out_batches, -1);
     // Group sizes are tapered at the two ends of the iteration where the link would otherwise wait for a
     // full slot: the first swap-out groups double from kTaperMin up to a slot (a group leaves only once it is
     // complete, so the link starts after the first small group instead of after a slot's worth of forward
@@ -850,10 +891,6 @@ extern "C" int ss_load_schedule(ss_ctx *ctx, const ss_desc_t *descs_out, uint32_
     s.in_group_state.assign(s.in_groups.size(), 0);
     s.in_group_state_drained.assign(s.in_groups.size(), 0);
     s.in_group_last_scatter.assign(s.in_groups.size(), -1);
-    for (uint32_t b = 0, last = 0, have = 0; b < n_out_batches; ++b) {
-      if (s.group_of[b] < 0) { last = b; have = 1; }
-      s.prev_direct[b] = have ? (int32_t)last : -1;
-    }
     // SS_PATH_AUTO (and the batches SS_PATH_STAGED leaves alone): one path for the whole swap-out side
     s.out_all_large = ctx->cfg.engine_min_bytes_out != 0 && n_out_batches != 0;
     for (uint32_t b = 0; b < n_out_batches && s.out_all_large; ++b) {
@@ -1188,7 +1225,12 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
   // floating-point accumulations changes with where their workgroups are placed); copy-engine transfers occupy
   // none, and every run with them was bit-identical to the run without swapping.  The synthetic configurations,
   // whose compute results are compared bit for bit in every test run, do not show it.
-  const bool engine = s.flat_next ? ctx->cfg.copy_path != SS_PATH_KERNEL
+  // With bare ring transfers no batch goes by copy engine outside the rings: its transfer would sit on a swap
+  // stream behind the kernels that wait for ring transfers, and a copy-engine transfer whose turn has not come
+  // holds up the engine's queue - the queue in which the awaited transfer's sequence number travels.  (Seen: a
+  // 96 MiB batch beside 64 MiB ring slots, by copy engine behind such a wait, stood until the wait gave up.)
+  const bool engine = ctx->eq ? false
+                    : s.flat_next ? ctx->cfg.copy_path != SS_PATH_KERNEL
                                   : use_engine(ctx, ctx->cfg.copy_path, true, s.out, lo, hi);
   // copy-kernel batches take the swap-out streams in turn; copy-engine batches stay on the first
   hipStream_t so = engine ? ctx->s_out[0] : ctx->s_out[batch % ctx->n_s_out];
@@ -1240,6 +1282,7 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
   SS_HIP(hipEventRecord(s.ev_out_done[s.phase][batch], so));
   s.done_ev_of[batch] = (int32_t)batch;
   s.out_issued[batch] = 1;
+  s.last_direct_out = batch;
   ctx->stats.bytes_out += bytes;
   return SS_OK;
 }
@@ -1269,12 +1312,17 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
     int rc = ring_flush_all(ctx);
     if (rc != SS_OK) return rc;
     hipStream_t se = ctx->s_flush;
-    const int32_t pd = s.prev_direct[s.in_group_outs[g].back()];
+    // Tensors of the range that left directly (a batch the ring does not take, or one whose slot had gone to a
+    // later group when it was issued): the direct batches share the swap-out stream with the gathers and run in
+    // issue order, so the one issued most recently stands for all of them.
+    bool left_directly = false;
+    for (uint32_t ob : s.in_group_outs[g]) left_directly = left_directly || !s.out_staged[ob];
+    const int64_t pd = left_directly ? s.last_direct_out : -1;
     const int32_t op = s.in_slot_owner[slot];           // the pack the slot held so far (this one, if a group of it came before)
     hipEvent_t pre[3];
     int n_pre = 0;
-    if (pd >= 0 && s.out_issued[(size_t)pd]) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)pd];
-    if (s.last_engine_out >= 0) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)s.last_engine_out];
+    if (pd >= 0) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)pd];
+    if (s.last_engine_out >= 0 && s.last_engine_out != pd) pre[n_pre++] = s.ev_out_done[s.phase][(size_t)s.last_engine_out];
     if (op >= 0 && op != pack && s.in_pack_last_scatter[(size_t)op] >= 0)
       pre[n_pre++] = s.ev_in_done[s.phase][(size_t)s.in_pack_last_scatter[(size_t)op]];
     s.in_slot_owner[slot] = pack;
@@ -1331,7 +1379,8 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
   if (s.in_issued[batch]) return SS_E_STATE;
   const uint32_t lo = s.in_start[batch], hi = s.in_start[batch + 1];
   if (hi > lo && !s.out_issued[s.in_dep[batch]]) return SS_E_STATE;   // its data never left
-  const bool engine = s.flat_next ? ctx->cfg.copy_path_in != SS_PATH_KERNEL          // see swap_out_batch
+  const bool engine = ctx->eq ? false                                                // see swap_out_batch
+                    : s.flat_next ? ctx->cfg.copy_path_in != SS_PATH_KERNEL
                                   : use_engine(ctx, ctx->cfg.copy_path_in, false, s.in, lo, hi);
   hipStream_t si = engine ? ctx->s_in[0] : ctx->s_in[batch % ctx->n_s_in];
   // destination blocks are free once the compute stream reaches this point
@@ -1357,12 +1406,12 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
       if (s.out_issued[dep - back]) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][dep - back], 0));
   } else if (hi > lo) {
     // staged swap-out (one swap-out stream): what has been gathered so far leaves the ring now; the batch
-    // waits for the last direct batch up to in_dep and for the last transfer out of the ring (a copy-engine
-    // transfer towards the host must not meet one coming back anyway, see below)
+    // waits for the direct batch issued most recently (they run in issue order on the swap-out stream, so it
+    // stands for every direct batch so far, whichever of them the tensors left in) and for the last transfer
+    // out of the ring (a copy-engine transfer towards the host must not meet one coming back anyway, see below)
     const int rc = ring_flush_all(ctx);
     if (rc != SS_OK) return rc;
-    const int32_t pd = s.prev_direct[s.in_dep[batch]];
-    if (pd >= 0 && s.out_issued[(size_t)pd]) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)pd], 0));
+    if (s.last_direct_out >= 0) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)s.last_direct_out], 0));
     if (ctx->eq) {
       const int rw = eq_stream_wait(ctx, si, s.last_flush_seq, &ctx->eq->waited_in);
       if (rw != SS_OK) return rw;
