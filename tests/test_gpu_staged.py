@@ -384,3 +384,53 @@ def test_random_schedules_through_the_rings_both_ways_of_issuing_the_transfers(P
         finally:
             P.ss_destroy(ctx)
     assert stats[0] == stats[1] and stats[0][0] == 2 * sum(sizes)
+
+
+def test_batches_outside_the_rings_go_by_copy_kernel_when_ring_transfers_are_bare(P, torch):
+    """8 MiB ring slots, batches of 4 and 8 MiB through the rings and batches of 16 MiB that fit no slot: with events
+    behind the ring transfers the large ones go by copy engine in both directions (their tensors reach
+    engine_min_bytes), with bare ring transfers by copy kernel - a copy-engine transfer behind a kernel that waits
+    for a ring transfer would hold up the queue the awaited sequence number travels in.  Same bytes either way."""
+    M = 1 << 20
+    sizes = [4 * M, 8 * M, 16 * M, 4 * M, 4 * M, 16 * M, 8 * M, 16 * M, 4 * M]
+    n = len(sizes)
+    d = np.zeros(n, dtype=W.DESC_DT)
+    off = 0
+    for i, sz in enumerate(sizes):
+        d[i] = (off, off, sz, i, 0)
+        off += sz
+    start = np.arange(n + 1, dtype=np.uint32)
+    rows = [tuple(int(x) for x in r) for r in d.tolist()]
+    arena = random_arena(torch, off, 41)
+    host = arena.cpu().numpy().copy()
+    want_staging = np.zeros(off, dtype=np.uint8)
+    oracle.swap_out(host, want_staging, rows)
+    for bare in (0, 1):
+        ctx = make_ctx(P, staging_bytes=off, copy_path=P.SS_PATH_STAGED, copy_path_in=P.SS_PATH_STAGED,
+                       ring_slot_bytes=8 * M, ring_bytes=32 * M, ring_taper=1, engine_min_bytes_out=4 * M,
+                       flags=P.SS_CFG_BARE_RING if bare else 0)
+        try:
+            P.ss_bind(ctx, arena.data_ptr(), off, torch.cuda.current_stream().cuda_stream)
+            P.ss_load_schedule(ctx, d, start, d, start, np.arange(n, dtype=np.uint32))
+            assert [int(g >= 0) for g in P.ss_ring_view(ctx)[0]] == [int(sz <= 8 * M) for sz in sizes]
+            for it in range(3):
+                arena.copy_(torch.from_numpy(host).cuda())
+                for b in range(n):
+                    P.ss_swap_out(ctx, b)
+                for t in range(n):
+                    P.ss_sync(ctx, P.SS_SYNC_FREE, t)
+                arena.fill_(0x3C)
+                for b in reversed(range(n)):
+                    P.ss_swap_in(ctx, b)
+                for t in range(n):
+                    P.ss_sync(ctx, P.SS_SYNC_WAIT_IN, t)
+                P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+                torch.cuda.synchronize()
+                assert np.array_equal(P.ss_host_peek(ctx, 0, off), want_staging), (bare, it)
+                assert np.array_equal(arena.cpu().numpy(), host), (bare, it)
+            st = P.ss_get_stats(ctx)
+            # (swap-ins are issued in reverse here, so a group whose slot has gone to a later one comes back directly)
+            assert st["ring_batches"] == 3 * 6 and 0 < st["ring_batches_in"] <= 3 * 6
+            assert st["engine_batches"] == 0 if bare else st["engine_batches"] >= 3 * 6
+        finally:
+            P.ss_destroy(ctx)
