@@ -1100,11 +1100,18 @@ def measure(B, torch, np, bw, o):
     # per-launch durations from the HIP events recorded on the swap streams: those of the last timed step,
     # and of up to three more steps run for this purpose alone
     unit_ms = {0: [], 1: [], 2: [], 3: []}
+    ring_kernel_ms = {0: [], 1: []}          # gathers into / scatters out of the rings
     spans = {0: [], 1: [], 2: [], 3: []}
 
     def read_events():
         for d in (0, 1, 2, 3):
             ms = B.ss_batch_ms_all(run.ctx, d)
+            if d < 2:            # a batch that went through a ring is timed as its gather / scatter inside HBM: not a link figure
+                grp_ = B.ss_ring_view(run.ctx, d)[0]
+                if len(grp_) == len(ms):
+                    in_ring = ms[grp_ >= 0]
+                    ring_kernel_ms[d] += in_ring[in_ring >= 0].tolist()
+                    ms = ms[grp_ < 0]
             ms = ms[ms >= 0]
             if len(ms):
                 unit_ms[d] += ms.tolist()
@@ -1199,10 +1206,12 @@ def measure(B, torch, np, bw, o):
 
     value = 2 * bytes_way / t_step / 1e9
     # link-side units of a direction: the ring transfers if it went through the ring, else its batches
-    out_link_ms = unit_ms[2] if ring_out == nob and nob else unit_ms[0]
-    in_link_ms = unit_ms[3] if ring_in == nib and nib else unit_ms[1]
-    out_link_span = spans[2] if ring_out == nob and nob else spans[0]
-    in_link_span = spans[3] if ring_in == nib and nib else spans[1]
+    # what crosses the link: the batches that move directly, and the ring transfers
+    out_link_ms = unit_ms[0] + unit_ms[2]
+    in_link_ms = unit_ms[1] + unit_ms[3]
+    both = lambda a, b: [max(x, y) for x, y in zip(a, b)] if a and b and len(a) == len(b) else (a or b)
+    out_link_span = both(spans[2], spans[0]) if ring_out else spans[0]
+    in_link_span = both(spans[3], spans[1]) if ring_in else spans[1]
     gb = lambda ms_total: bytes_way * event_steps / (ms_total * 1e-3) / 1e9 if ms_total > 0 else 0.0
     d2h_busy, h2d_busy = gb(sum(out_link_ms)), gb(sum(in_link_ms))            # while a transfer / launch runs
     d2h_span = bytes_way / (np.mean(out_link_span) * 1e-3) / 1e9 if out_link_span else 0.0   # first start .. last end
@@ -1252,8 +1261,8 @@ def measure(B, torch, np, bw, o):
             "hbm": {"achieved": round(link_achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(link_achieved / HBM_PEAK_GBPS, 5),
                     "note": "HBM side of the same bytes (one HBM access per byte moved over the link); by design far from the HBM roofline"}}
-    if ring_out or ring_in:
-        g_ms = (unit_ms[0] if ring_out else []) + (unit_ms[1] if ring_in else [])
+    if (ring_out and ring_kernel_ms[0]) or (ring_in and ring_kernel_ms[1]):
+        g_ms = (ring_kernel_ms[0] if ring_out else []) + (ring_kernel_ms[1] if ring_in else [])
         g_bytes = bytes_way * event_steps * (int(bool(ring_out)) + int(bool(ring_in)))
         roof["ring_kernel"] = {"kernel": "ss_copy_kernel, HBM <-> HBM ring (gather / scatter)", "bound": "hbm",
                                "achieved": round(2 * g_bytes / (sum(g_ms) * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
