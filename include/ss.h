@@ -550,7 +550,8 @@ int ss_swap_out(ss_ctx *ctx, uint32_t batch);
 /* Enqueue swap-in batch `batch`: the swap-in stream waits for everything
  * enqueued so far on the compute stream (the destination blocks are free from
  * here on) and for the swap-out batches it depends on, copies each tensor
- * from its staging slot into its dev_off, records the done-event. */
+ * from its staging slot into its dev_off, records the done-event.  Swap-out batches are normally issued in
+ * index order (ss_dispatch does); if they were not, the batch waits for every swap-out issued so far. */
 int ss_swap_in(ss_ctx *ctx, uint32_t batch);
 
 /* The same two moves for tensors whose device addresses are only known when the batch is issued: blocks

@@ -47,6 +47,11 @@ struct ss_sched {
   std::vector<uint64_t> group_bytes;                // per group, for ss_ring_view
   std::vector<int32_t> group_of;                    // per swap-out batch: its group, -1 = leaves directly
   int64_t last_direct_out = -1;                     // swap-out batch that left directly (not through the ring) most recently, this iteration
+  // swap-out batches issued out of index order (this iteration): a swap-in then waits for the batch issued most
+  // recently on every swap-out stream instead of for the batches up to in_dep
+  int64_t max_out_issued = -1;
+  bool out_of_order = false;
+  int64_t last_out_on[4] = {-1, -1, -1, -1};        // per swap-out stream: batch issued on it most recently
   std::vector<hipEvent_t> ev_gathered[2];           // per batch: its bytes are in the ring (the block may be released)
   std::vector<hipEvent_t> ev_flush_start[2];        // per group (SS_CFG_TIMING): its first transfer starts
   std::vector<int32_t> done_ev_of;                  // per batch, this iteration: batch whose ev_out_done covers it; -1 = not sent yet

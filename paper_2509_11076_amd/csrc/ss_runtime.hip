@@ -604,7 +604,9 @@ static void ring_reset(ss_sched &s, uint32_t n_slots) {
   std::fill(s.in_group_last_scatter.begin(), s.in_group_last_scatter.end(), -1);
   std::fill(s.in_pack_last_scatter.begin(), s.in_pack_last_scatter.end(), -1);
   std::fill(s.out_staged.begin(), s.out_staged.end(), 0);
-  s.last_flush_batch = s.last_gather_batch = s.last_direct_out = -1;
+  s.last_flush_batch = s.last_gather_batch = s.last_direct_out = s.max_out_issued = -1;
+  s.out_of_order = false;
+  for (int64_t &x : s.last_out_on) x = -1;
   std::fill(s.flush_seq.begin(), s.flush_seq.end(), 0);
   std::fill(s.group_last_flush_seq.begin(), s.group_last_flush_seq.end(), 0);
   std::fill(s.fetch_seq.begin(), s.fetch_seq.end(), 0);
@@ -1283,6 +1285,9 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
   s.done_ev_of[batch] = (int32_t)batch;
   s.out_issued[batch] = 1;
   s.last_direct_out = batch;
+  if ((int64_t)batch < s.max_out_issued) s.out_of_order = true;
+  else s.max_out_issued = batch;
+  s.last_out_on[engine ? 0 : batch % ctx->n_s_out] = batch;
   ctx->stats.bytes_out += bytes;
   return SS_OK;
 }
@@ -1400,7 +1405,12 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
   // staging slots must be completely written: the batch's tensors left in swap-out batches up to in_dep;
   // with the swap-out batches spread over n streams, the last n of them up to in_dep cover every stream
   // (each stream runs its own batches in order)
-  if (hi > lo && s.groups.empty()) {
+  if (hi > lo && s.groups.empty() && s.out_of_order) {
+    // swap-outs were not issued in index order: "up to in_dep" says nothing about what ran before what, so the
+    // batch waits for the one issued most recently on every swap-out stream (everything issued so far)
+    for (uint32_t k = 0; k < ctx->n_s_out; ++k)
+      if (s.last_out_on[k] >= 0) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][(size_t)s.last_out_on[k]], 0));
+  } else if (hi > lo && s.groups.empty()) {
     const uint32_t dep = s.in_dep[batch];
     for (uint32_t back = 0; back < ctx->n_s_out && back <= dep; ++back)
       if (s.out_issued[dep - back]) SS_HIP(hipStreamWaitEvent(si, s.ev_out_done[s.phase][dep - back], 0));

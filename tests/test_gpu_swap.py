@@ -159,7 +159,7 @@ def ragged_schedule(seed, n, arena_bytes, max_bytes):
     return descs, host + 256
 
 
-def ragged_round_trip(P, torch, path, seed=3, n=40, max_bytes=200000, arena_bytes=8 << 20, **cfg):
+def ragged_round_trip(P, torch, path, seed=3, n=40, max_bytes=200000, arena_bytes=8 << 20, reverse_out=False, **cfg):
     descs, staging_bytes = ragged_schedule(seed, n, arena_bytes // 2, max_bytes)
     n = len(descs)
     out_start = np.array([0, 0, 7, 7, 20, n, n], dtype=np.uint32)       # batches 0, 2 and 5 are empty
@@ -180,7 +180,8 @@ def ragged_round_trip(P, torch, path, seed=3, n=40, max_bytes=200000, arena_byte
         # the compute stream (the null stream here) lags 2-3 ms behind the calls: a swap-in that is not ordered
         # after the swap-outs it depends on reads the fill pattern
         torch.cuda._sleep(2000000)
-        for b in range(len(out_start) - 1):
+        order = range(len(out_start) - 1)
+        for b in (reversed(order) if reverse_out else order):
             P.ss_swap_out(ctx, b)
         for b in range(len(in_start) - 1):
             P.ss_swap_in(ctx, b)
@@ -198,6 +199,10 @@ def ragged_round_trip(P, torch, path, seed=3, n=40, max_bytes=200000, arena_byte
 @pytest.mark.parametrize("path", ["kernel", "engine"])
 def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
     ragged_round_trip(P, torch, path)
+    # swap-outs issued against their index order, on one swap-out stream and on three: a swap-in then waits for
+    # whatever has been issued, not for "the batches up to the last one it needs"
+    ragged_round_trip(P, torch, path, reverse_out=True)
+    ragged_round_trip(P, torch, path, reverse_out=True, out_streams=3, in_streams=2)
 
 
 @pytest.mark.parametrize("window", [1, 2, 5])
