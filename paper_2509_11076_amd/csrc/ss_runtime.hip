@@ -1384,6 +1384,11 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
   if (s.in_issued[batch]) return SS_E_STATE;
   const uint32_t lo = s.in_start[batch], hi = s.in_start[batch + 1];
   if (hi > lo && !s.out_issued[s.in_dep[batch]]) return SS_E_STATE;   // its data never left
+  if (s.out_of_order)      // swap-outs issued against their index order: the last one needed says nothing about the others
+    for (uint32_t i = lo; i < hi; ++i) {
+      auto it = s.out_of_tensor.find(s.in[i].tensor_id);
+      if (it != s.out_of_tensor.end() && !s.out_issued[s.out_batch_of[it->second]]) return SS_E_STATE;
+    }
   const bool engine = ctx->eq ? false                                                // see swap_out_batch
                     : s.flat_next ? ctx->cfg.copy_path_in != SS_PATH_KERNEL
                                   : use_engine(ctx, ctx->cfg.copy_path_in, false, s.in, lo, hi);

@@ -308,6 +308,21 @@ def test_schedule_validation_and_call_order_errors(P, torch):
         P.ss_sync(ctx, P.SS_SYNC_DRAIN)
         st = P.ss_get_stats(ctx)
         assert st["free_waits"] == 1 and st["in_waits"] == 1 and st["bytes_out"] == 2 * 8192
+        # swap-outs issued against their index order: the swap-in that needs all three is refused until all three
+        # have been issued (in index order the last one needed stands for the others)
+        d3 = np.zeros(3, dtype=W.DESC_DT)
+        for i in range(3):
+            d3[i] = (i * 8192, i * 4096, 4096, i, 0)
+        P.ss_load_schedule(ctx, d3, np.arange(4, dtype=np.uint32), d3, np.array([0, 3], dtype=np.uint32),
+                           np.array([2], dtype=np.uint32))
+        P.ss_swap_out(ctx, 2)
+        P.ss_swap_out(ctx, 0)
+        with pytest.raises(P.SsError) as e:
+            P.ss_swap_in(ctx, 0)
+        assert e.value.code == P.SS_E_STATE
+        P.ss_swap_out(ctx, 1)
+        P.ss_swap_in(ctx, 0)
+        P.ss_sync(ctx, P.SS_SYNC_DRAIN)
     finally:
         P.ss_destroy(ctx)
 
