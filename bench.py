@@ -1015,6 +1015,12 @@ def measure(B, torch, np, bw, o):
     more_cfg = {k: int(v, 0) for k, v in (kv.split("=", 1) for kv in getattr(o, "cfg", []))}
 
     def make(bpo_, wgo=workgroups_out, p=None, p_in=None, fl=None):
+        r_ = make_(bpo_, wgo, p, p_in, fl)
+        if getattr(o, "iteration_end", "drain") == "nowait":
+            r_.iteration_end = B.SS_SYNC_ITERATION_END
+        return r_
+
+    def make_(bpo_, wgo, p, p_in, fl):
         return SwapRun(B, torch, cfgno, swap=True, bpo=bpo_, bpo_in=bpo_in, copy_path=path if p is None else p,
                        copy_path_in=path_in if p_in is None else p_in, copy_workgroups=o.workgroups,
                        copy_workgroups_out=wgo, flags=flags if fl is None else fl, cfg_extra=dict(copy_cus=getattr(o, "copy_cus", 0), engine_window_in=window_in, engine_window_out=o.engine_window_out, **more_cfg), **extra)
@@ -1085,6 +1091,7 @@ def measure(B, torch, np, bw, o):
         run.step()
     torch.cuda.synchronize()
     t_step = (time.perf_counter() - t0) / o.steps
+    run.iteration_end = None                # what follows reads events and the staging area: the host waits again
     st1 = B.ss_get_stats(run.ctx)
     steps_before_events = o.warmup + o.steps
     if separate_timing:
@@ -1380,6 +1387,9 @@ def main():
                     help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
     ap.add_argument("--engine-window-out", type=int, default=0, help="the same for copy-engine swap-out batches")
+    ap.add_argument("--iteration-end", default="drain", choices=["drain", "nowait"],
+                    help="how a timed step ends: drain = the host waits for the swap streams (SS_SYNC_DRAIN), nowait = it "
+                         "does not, the next step is ordered behind this one on the device (SS_SYNC_ITERATION_END)")
     ap.add_argument("--cfg", action="append", default=[], metavar="FIELD=VALUE",
                     help="set a further field of the library's configuration record by name (integer value), e.g. "
                          "--cfg ring_slot_bytes=134217728; may be given several times")

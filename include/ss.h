@@ -577,7 +577,19 @@ int ss_swap_in_to(ss_ctx *ctx, uint32_t batch, void *const *dev_dst /* host arra
 enum { SS_SYNC_FREE = 0,    /* id = tensor: compute stream waits (device-side) for that tensor's
                                swap-out; after this call its block may be given to later operators */
        SS_SYNC_WAIT_IN = 1, /* id = tensor: compute stream waits (device-side) for its swap-in     */
-       SS_SYNC_DRAIN = 2 }; /* host waits for both swap streams; surfaces asynchronous errors      */
+       SS_SYNC_DRAIN = 2,   /* host waits for both swap streams; surfaces asynchronous errors      */
+       SS_SYNC_ITERATION_END = 3 };
+                            /* ends the iteration like SS_SYNC_DRAIN (batches may be issued again, the
+                               other set of events is used) without making the host wait for it: the swap
+                               streams' work of the next iteration is ordered behind this one's on the
+                               device (staging slots and ring slots are not reused before their readers
+                               are done).  The host waits only for the iteration BEFORE this one, so one
+                               iteration at most is outstanding; what that one ran into (SS_E_HIP,
+                               SS_E_TIMEOUT) is returned here, one call late.  A training loop whose host
+                               thread runs ahead of the GPU keeps doing so (Sec. 5.2 asks the same of the
+                               release of blocks); ss_host_peek and the timing calls want SS_SYNC_DRAIN
+                               first.  With SS_CFG_STALL_TIMING, or SS_CFG_TIMING beside bare ring
+                               transfers, the call is SS_SYNC_DRAIN                                    */
 int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id);
 
 /* The executor's step at one operator (Sec. 5, first paragraph): issues, in schedule order, every action that the schedule loaded by the last ss_apply_policy holds for

@@ -134,6 +134,12 @@ struct ss_ctx {
   uint8_t *ring_in = nullptr;       // the same for the staged swap-in path
   uint32_t n_slots = 0;
   ss_engine_queue *eq = nullptr;    // SS_CFG_BARE_RING
+  // SS_SYNC_ITERATION_END: end-of-iteration events of the swap streams, two sets used in turn (out streams 0..3,
+  // in streams 4..7, ring-transfer stream 8); at most one iteration is outstanding behind the one being issued
+  hipEvent_t ev_iter[2][9] = {};
+  bool iter_pending[2] = {false, false};
+  uint64_t iter_last_seq[2] = {0, 0};
+  int iter_set = 0;
   std::vector<hipEvent_t> ev_ring;  // compute-stream markers, used round-robin
   size_t ev_next = 0;
   // trace

@@ -353,6 +353,14 @@ static void eq_wait_idle(ss_ctx *ctx) {
   q->cv_idle.wait(lk, [q] { return q->q.empty() && !q->busy; });
 }
 
+// job `seq` and every job before it have been handed to the stream
+static void eq_wait_enqueued(ss_ctx *ctx, uint64_t seq) {
+  ss_engine_queue *q = ctx->eq;
+  if (!q || !q->started || seq == 0) return;
+  std::unique_lock<std::mutex> lk(q->mu);
+  while (q->enqueued_seq < seq) q->cv_idle.wait_for(lk, std::chrono::microseconds(100));
+}
+
 // stream st goes on only once job `seq` is complete (one wait per stream covers every earlier job)
 static int eq_stream_wait(ss_ctx *ctx, hipStream_t st, uint64_t seq, uint64_t *covered) {
   if (seq == 0 || *covered >= seq) return SS_OK;
@@ -527,6 +535,9 @@ extern "C" int ss_destroy(ss_ctx *ctx) {
   eq_destroy(ctx);
   sched_release(ctx->sched);
   for (hipEvent_t ev : ctx->ev_ring) (void)hipEventDestroy(ev);
+  for (int p = 0; p < 2; ++p)
+    for (int k = 0; k < 9; ++k)
+      if (ctx->ev_iter[p][k]) (void)hipEventDestroy(ctx->ev_iter[p][k]);
   for (int i = 0; i < ss_ctx::kMaxSwapStreams; ++i) {       // joined above: nothing is pending on them
     if (ctx->s_out[i]) ctx->pooled_streams ? pool_give(ctx->device, kRoleOut + i, ctx->s_out[i]) : (void)hipStreamDestroy(ctx->s_out[i]);
     if (ctx->s_in[i]) ctx->pooled_streams ? pool_give(ctx->device, kRoleIn + i, ctx->s_in[i]) : (void)hipStreamDestroy(ctx->s_in[i]);
@@ -1546,12 +1557,83 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
       }
       return SS_OK;
     }
+    case SS_SYNC_ITERATION_END: {
+      if (!s.loaded || (ctx->cfg.flags & SS_CFG_STALL_TIMING) || (ctx->eq && ctx->eq->timing))
+        return ss_sync(ctx, SS_SYNC_DRAIN, id);
+      int late = SS_OK;
+      int rc = ring_flush_all(ctx);
+      if (rc != SS_OK) return rc;
+      const int cur = ctx->iter_set, prev = cur ^ 1;
+      // the iteration before this one has to be over: the next one records into its set of events
+      if (ctx->iter_pending[prev]) {
+        for (int k = 0; k < 9; ++k)
+          if (ctx->ev_iter[prev][k]) SS_HIP(hipEventSynchronize(ctx->ev_iter[prev][k]));
+        eq_wait_enqueued(ctx, ctx->iter_last_seq[prev]);
+        ctx->iter_pending[prev] = false;
+      }
+      if (ctx->eq) {
+        const int he = ctx->eq->hip_error.exchange(0);
+        if (he) {
+          ctx->stats.last_hip_error = (int32_t)he;
+          late = SS_E_HIP;
+        }
+        if (*(volatile uint32_t *)ctx->eq->h_timeouts) {      // of the iteration before: everything of it has run
+          *(volatile uint32_t *)ctx->eq->h_timeouts = 0;
+          SS_HIP(hipMemcpy(ctx->eq->d_gave_up, ctx->eq->h_timeouts + 4, 4, hipMemcpyHostToDevice));
+          late = SS_E_TIMEOUT;
+        }
+      }
+      // where this iteration ends on every swap stream
+      auto end_of = [&](int k, hipStream_t st) -> int {
+        if (!ctx->ev_iter[cur][k])
+          SS_HIP(hipEventCreateWithFlags(&ctx->ev_iter[cur][k], hipEventDisableTiming | fence_flag(ctx->cfg)));
+        SS_HIP(hipEventRecord(ctx->ev_iter[cur][k], st));
+        return SS_OK;
+      };
+      for (uint32_t i = 0; i < ctx->n_s_out; ++i)
+        if ((rc = end_of((int)i, ctx->s_out[i])) != SS_OK) return rc;
+      for (uint32_t i = 0; i < ctx->n_s_in; ++i)
+        if ((rc = end_of(4 + (int)i, ctx->s_in[i])) != SS_OK) return rc;
+      if (ctx->s_flush && !ctx->eq && (rc = end_of(8, ctx->s_flush)) != SS_OK) return rc;
+      // The next iteration's swap-outs write staging slots and ring slots that this iteration's swap-ins and ring
+      // transfers still read: every swap-out stream goes on only after the swap-in streams and the ring transfers of
+      // this iteration; the ring transfers of the next iteration (into slots this iteration's scatters read) only
+      // after the swap-in streams.  Swap-ins follow their own swap-outs as always.
+      for (uint32_t i = 0; i < ctx->n_s_out; ++i) {
+        for (uint32_t j = 0; j < ctx->n_s_in; ++j) SS_HIP(hipStreamWaitEvent(ctx->s_out[i], ctx->ev_iter[cur][4 + j], 0));
+        if (ctx->s_flush && !ctx->eq) SS_HIP(hipStreamWaitEvent(ctx->s_out[i], ctx->ev_iter[cur][8], 0));
+      }
+      if (ctx->eq) {
+        const uint64_t last = ctx->eq->next_seq - 1;           // only this thread pushes
+        if ((rc = eq_stream_wait(ctx, ctx->s_out[0], last, &ctx->eq->waited_out)) != SS_OK) return rc;
+        // a transfer of nothing that the thread holds back until the scatters are done: what is pushed later follows it
+        ctx->iter_last_seq[cur] = eq_push(ctx, nullptr, nullptr, 0, hipMemcpyHostToDevice, &ctx->ev_iter[cur][4], 1, 3, 0);
+      } else if (ctx->s_flush) {
+        for (uint32_t j = 0; j < ctx->n_s_in; ++j) SS_HIP(hipStreamWaitEvent(ctx->s_flush, ctx->ev_iter[cur][4 + j], 0));
+      }
+      ctx->iter_pending[cur] = true;
+      ctx->iter_set ^= 1;
+      std::fill(s.out_waited.begin(), s.out_waited.end(), 0);
+      std::fill(s.in_waited.begin(), s.in_waited.end(), 0);
+      std::fill(s.out_issued.begin(), s.out_issued.end(), 0);
+      std::fill(s.in_issued.begin(), s.in_issued.end(), 0);
+      s.last_engine_out = -1;
+      s.phase ^= 1;
+      s.drained_once = true;
+      s.done_ev_of_drained = s.done_ev_of;
+      s.out_staged_drained = s.out_staged;
+      s.group_last_flush_drained = s.group_last_flush;
+      s.in_group_state_drained = s.in_group_state;
+      ring_reset(s, ctx->n_slots);
+      return late;
+    }
     case SS_SYNC_DRAIN: {
       int late = SS_OK;             // what the iteration's ring transfers ran into; reported once the state is reset
       {
         int rc = s.loaded ? ring_flush_all(ctx) : SS_OK;      // staged batches whose group never completed
         if (rc == SS_OK) rc = sync_swap_streams(ctx);
         if (rc != SS_OK) return rc;
+        ctx->iter_pending[0] = ctx->iter_pending[1] = false;   // every stream is idle
         if (ctx->eq) {
           {
             std::lock_guard<std::mutex> lk(ctx->eq->mu);          // the thread is idle and its stream empty

@@ -69,9 +69,11 @@ def dispatch_points(actions):
             frozenset(np.unique(actions["op_idx"][late]).tolist()))
 
 
-def run_iteration_dispatch(ctx, n_ops, run_op, points):
+def run_iteration_dispatch(ctx, n_ops, run_op, points, end=None):
     """Execute one iteration of the schedule that the last ss_apply_policy loaded, with ss_dispatch:
-    one library call per side of an operator that has actions, the actions themselves issued natively."""
+    one library call per side of an operator that has actions, the actions themselves issued natively.
+    `end`: how the iteration ends, SS_SYNC_DRAIN (the host waits for the swap streams; default) or
+    SS_SYNC_ITERATION_END (it does not: the next iteration is ordered behind this one on the device)."""
     before, after = points
     for i in range(n_ops):
         if i in before:
@@ -80,4 +82,4 @@ def run_iteration_dispatch(ctx, n_ops, run_op, points):
             run_op(i)
         if i in after:
             B.ss_dispatch(ctx, i, 1)
-    B.ss_sync(ctx, B.SS_SYNC_DRAIN, 0)
+    B.ss_sync(ctx, B.SS_SYNC_DRAIN if end is None else end, 0)

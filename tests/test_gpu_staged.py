@@ -439,3 +439,75 @@ def test_batches_outside_the_rings_go_by_copy_kernel_when_ring_transfers_are_bar
             assert st["engine_batches"] == 0 if bare else st["engine_batches"] >= 3 * 6
         finally:
             P.ss_destroy(ctx)
+
+
+@pytest.mark.parametrize("route", ["auto", "rings with events", "rings bare"])
+def test_iterations_that_end_without_a_host_wait_equal_no_swapping(P, torch, route):
+    """configuration 2, twelve iterations ended with SS_SYNC_ITERATION_END (the host runs on; staging slots and ring
+    slots are reused by the next iteration only behind this one's readers, on the device), blocks poisoned at
+    their release, then one drain: compute results equal the run without swapping, and the staging area holds the
+    last iteration's bytes"""
+    B = P
+    from workloads.harness import SwapRun
+    staged = route != "auto"
+    flags = B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE | (B.SS_CFG_BARE_RING if route == "rings bare" else 0)
+    res = []
+    for swap in (False, True):
+        r = SwapRun(B, torch, 2, swap=swap, bpo=11 << 20, bpo_in=4760000,
+                    copy_path=B.SS_PATH_STAGED if staged else B.SS_PATH_AUTO,
+                    copy_path_in=B.SS_PATH_STAGED if staged else B.SS_PATH_AUTO, flags=flags if swap else 0)
+        try:
+            if swap:
+                r.iteration_end = B.SS_SYNC_ITERATION_END
+            for _ in range(12):
+                r.step() if swap else r.step_noswap()
+            if swap:
+                r.drain()
+            res.append((r.compute.result(), B.ss_get_stats(r.ctx), r.bytes_each_way))
+        finally:
+            r.close()
+    (c0, g0), _, _ = res[0]
+    (c1, g1), st, moved = res[1]
+    assert np.array_equal(c0, c1) and np.array_equal(g0, g1)
+    assert st["bytes_out"] == st["bytes_in"] == 12 * moved
+    assert (st["ring_batches"] > 0) == staged
+
+
+@pytest.mark.parametrize("path,bare", [(1, 0), (2, 0), (3, 0), (3, 1)])
+def test_toy_config_iterations_without_a_host_wait_against_the_oracle(P, torch, path, bare):
+    """configuration 1, five iterations ended with SS_SYNC_ITERATION_END and one drain, by copy kernel, by copy
+    engine and through rings of two small slots (with events and bare): staging image and arena (with poison over
+    released blocks) equal the oracle's after as many iterations; the compute stream lags behind the calls"""
+    from paper_2509_11076_amd.executor import run_iteration_dispatch, dispatch_points
+    tr = W.build_trace(W.config_shape(1))
+    pol = W.config_swap_set(tr, 1)
+    idx = pol["ref_op"].astype(np.int64)
+    bpo = 64 * 1024
+    ap0 = oracle.apply_policy(pol, idx, tr.tensors, bpo)
+    swapped = {r[2]: (r[5], r[6]) for r in ap0["resolved"] if not r[3] & 3}
+    arena_bytes = place_tensors(tr.tensors, swapped=swapped)
+    ora = oracle.apply_policy(pol, idx, tr.tensors, bpo)
+    arena = random_arena(torch, arena_bytes, 2509)
+    host_arena = arena.cpu().numpy().copy()
+    ctx = make_ctx(P, staging_bytes=ora["staging_bytes"], link_bytes_per_op=bpo, copy_path=path, copy_path_in=path,
+                   ring_slot_bytes=512 << 10, ring_bytes=1024 << 10,
+                   flags=P.SS_CFG_POISON_FREE | (P.SS_CFG_BARE_RING if bare else 0))
+    try:
+        P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
+        lib = P.ss_apply_policy(ctx, pol, idx, tr.tensors)
+        assert_applied_equal(lib, P, ctx, ora)
+        points = dispatch_points(lib["actions"])
+        P.ss_staging_fill(ctx, 0xA5)
+        staging = np.full(ora["staging_bytes"], 0xA5, dtype=np.uint8)
+        for it in range(5):
+            torch.cuda._sleep(1000000)
+            run_iteration_dispatch(ctx, tr.n_ops, None, points, end=P.SS_SYNC_ITERATION_END)
+            oracle_execute(host_arena, staging, ora, poison=0xDB)
+        P.ss_sync(ctx, P.SS_SYNC_DRAIN)
+        torch.cuda.synchronize()
+        assert np.array_equal(P.ss_host_peek(ctx, 0, ora["staging_bytes"]), staging)
+        assert np.array_equal(arena.cpu().numpy(), host_arena)
+        st = P.ss_get_stats(ctx)
+        assert st["bytes_out"] == st["bytes_in"] == 5 * sum(d[2] for d in ora["descs_out"])
+    finally:
+        P.ss_destroy(ctx)

@@ -139,6 +139,7 @@ class SwapRun:
         # and before the operator itself, after_op(i) after the operator and before the actions after it
         self.before_op = self.after_op = None
         self.reuse_stable = True
+        self.iteration_end = None           # B.SS_SYNC_ITERATION_END: the host does not wait at the end of an iteration
 
     def close(self):
         if self.ctx is not None:
@@ -189,7 +190,11 @@ class SwapRun:
                 comp.run_op(i)
             if post is not None:
                 post(i)
-        run_iteration_dispatch(self.ctx, self.tr.n_ops, run_op, plan["points"])
+        run_iteration_dispatch(self.ctx, self.tr.n_ops, run_op, plan["points"], end=self.iteration_end)
+
+    def drain(self):
+        """host waits for everything the swap streams still have (after iterations ended without waiting)"""
+        self.B.ss_sync(self.ctx, self.B.SS_SYNC_DRAIN, 0)
 
     def step_noswap(self):
         """the same operators with no swap executor at all (baseline for the overhead figure)"""
