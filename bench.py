@@ -1142,10 +1142,19 @@ def measure(B, torch, np, bw, o):
             cls = 1 << max(0, int(nb_[b]) - 1).bit_length()           # next power of two
             e = by_size.setdefault((d, cls), [0, 0, 0.0])
             e[0] += 1; e[1] += int(nb_[b]); e[2] += float(ms[b])
+    phase_ms = []                           # forward / backward pass of these steps on the compute stream (two markers)
     for _ in range(min(3, o.steps)):
+        if has_compute:
+            pe = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            run.before_op = lambda i, pe=pe: (pe[0].record() if i == 0 else pe[1].record() if i == first_bwd else None)
         run.step()
+        if has_compute:
+            pe[2].record()
         torch.cuda.synchronize()
+        if has_compute and 0 < first_bwd < run.tr.n_ops:
+            phase_ms.append((pe[0].elapsed_time(pe[1]), pe[1].elapsed_time(pe[2])))
         read_events()
+    run.before_op = None
     event_steps = 1 + min(3, o.steps)
     st2 = B.ss_get_stats(run.ctx)
     applied, match, scan = run.last["applied"], run.last["match"], run.last["scan"]
@@ -1301,6 +1310,8 @@ def measure(B, torch, np, bw, o):
                    "timing": o.timing if o.policy_mode == "generated" else "link-model",
                    "generator_params": {k: v for k, v in extra.get("generator", {}).items()} or None,
                    "noswap_forward_ms": round(t_fwd * 1e3, 2), "noswap_backward_ms": round(t_bwd * 1e3, 2),
+                   "swap_forward_ms": round(float(np.mean([p_[0] for p_ in phase_ms])), 2) if phase_ms else None,
+                   "swap_backward_ms": round(float(np.mean([p_[1] for p_ in phase_ms])), 2) if phase_ms else None,
                    "memory_limit_bytes": extra.get("budget"), "generator": run_generated,
                    "memory_limit_met": (int(scan["peak"]) <= extra["budget"]) if extra.get("budget") else None,
                    "tensors_forced_late": n_forced, "tensors_dropped": n_dropped_setup, "peak_bytes_with_policy": int(scan["peak"]),
