@@ -43,6 +43,7 @@ SS_PATH_AUTO, SS_PATH_KERNEL, SS_PATH_ENGINE, SS_PATH_STAGED = 0, 1, 2, 3
 SS_CFG_TIMING, SS_CFG_POISON_FREE, SS_CFG_KEEP_LATE, SS_CFG_SYSTEM_FENCE, SS_CFG_POLICY_POINTS = 1, 2, 4, 8, 16
 SS_CFG_STALL_TIMING = 32
 SS_CFG_BARE_RING = 64
+SS_CFG_MEMORY_MARKERS = 128
 SS_SYNC_FREE, SS_SYNC_WAIT_IN, SS_SYNC_DRAIN, SS_SYNC_ITERATION_END = 0, 1, 2, 3
 SS_MATCH_STEP_STAGE, SS_MATCH_HISTOGRAM, SS_MATCH_ALIGN = 1, 2, 4
 SS_LEVEL_ALIGN = 3

@@ -225,7 +225,17 @@ __global__ void ss_wait_flag_kernel(const uint64_t *flag, uint64_t want, uint64_
   }
 }
 
+// Stores `value` at `flag` (device memory): where the stream it runs on stands, for ss_wait_flag_kernel on another
+// stream.  Everything enqueued before it on its stream has completed and is visible when the store is.
+__global__ void ss_mark_kernel(uint64_t *flag, uint64_t value) {
+  __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 }  // namespace
+
+void ss_launch_mark(hipStream_t s, uint64_t *flag, uint64_t value) {
+  hipLaunchKernelGGL(ss_mark_kernel, dim3(1), dim3(1), 0, s, flag, value);
+}
 
 void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *gave_up,
                          uint32_t *timeouts) {

@@ -134,6 +134,12 @@ struct ss_ctx {
   uint8_t *ring_in = nullptr;       // the same for the staged swap-in path
   uint32_t n_slots = 0;
   ss_engine_queue *eq = nullptr;    // SS_CFG_BARE_RING
+  // SS_CFG_MEMORY_MARKERS: the compute stream's position as a running count in device memory
+  uint64_t *d_mark = nullptr;       // device, 256 bytes; first word = count of the last marker the compute stream has passed
+  uint64_t mark_count = 0;          // markers issued so far
+  uint32_t *d_mark_gave_up = nullptr;                       // device: a wait for a marker ran into its limit
+  uint32_t *h_mark_timeouts = nullptr, *d_mark_timeouts = nullptr;   // pinned word and its device address
+  uint64_t mark_limit_ticks = 0;
   // SS_SYNC_ITERATION_END: end-of-iteration events of the swap streams, two sets used in turn (out streams 0..3,
   // in streams 4..7, ring-transfer stream 8); at most one iteration is outstanding behind the one being issued
   hipEvent_t ev_iter[2][9] = {};
@@ -206,6 +212,8 @@ void ss_launch_copy(hipStream_t s, uint32_t workgroups, uint32_t unroll, bool to
 // one tensor by its two addresses, no descriptor table (16-byte aligned on both sides)
 void ss_launch_copy_flat(hipStream_t s, uint32_t workgroups, const uint8_t *src, uint8_t *dst, uint64_t nbytes);
 void ss_launch_fill(hipStream_t s, uint8_t *dst, uint64_t nbytes, uint8_t value);
+// one thread that stores value at *flag once everything before it on stream s is complete (ss_mark_kernel)
+void ss_launch_mark(hipStream_t s, uint64_t *flag, uint64_t value);
 // one wave that holds stream s until *flag >= want (ss_wait_flag_kernel; bounded by limit_ticks of 10 ns)
 void ss_launch_wait_flag(hipStream_t s, const uint64_t *flag, uint64_t want, uint64_t limit_ticks, uint32_t *gave_up,
                          uint32_t *timeouts);

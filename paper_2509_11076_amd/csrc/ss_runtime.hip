@@ -470,6 +470,18 @@ extern "C" int ss_create(ss_ctx **out, const ss_config_t *cfg_in) {
         fail(SS_E_NOMEM, e);
       if (rc == SS_OK && (cfg.flags & SS_CFG_BARE_RING)) rc = eq_create(ctx);
     }
+    if (rc == SS_OK && (cfg.flags & SS_CFG_MEMORY_MARKERS)) {
+      ctx->mark_limit_ticks = (uint64_t)(cfg.flag_wait_ms ? cfg.flag_wait_ms : 10000u) * 100000ull;
+      if ((e = hipMalloc((void **)&ctx->d_mark, 256)) != hipSuccess) fail(SS_E_NOMEM, e);
+      else if ((e = hipMalloc((void **)&ctx->d_mark_gave_up, 256)) != hipSuccess) fail(SS_E_NOMEM, e);
+      else if ((e = hipHostMalloc((void **)&ctx->h_mark_timeouts, 256, hipHostMallocMapped)) != hipSuccess) fail(SS_E_NOMEM, e);
+      else {
+        std::memset(ctx->h_mark_timeouts, 0, 256);
+        if ((e = hipHostGetDevicePointer((void **)&ctx->d_mark_timeouts, ctx->h_mark_timeouts, 0)) != hipSuccess) fail(SS_E_HIP, e);
+        else if ((e = hipMemcpy(ctx->d_mark, ctx->h_mark_timeouts, 256, hipMemcpyHostToDevice)) != hipSuccess) fail(SS_E_HIP, e);
+        else if ((e = hipMemcpy(ctx->d_mark_gave_up, ctx->h_mark_timeouts, 256, hipMemcpyHostToDevice)) != hipSuccess) fail(SS_E_HIP, e);
+      }
+    }
     for (int i = 0; i < 2048 && rc == SS_OK; ++i) {
       hipEvent_t ev;
       if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming | fence_flag(cfg))) != hipSuccess) fail(SS_E_HIP, e);
@@ -543,6 +555,9 @@ extern "C" int ss_destroy(ss_ctx *ctx) {
     if (ctx->s_in[i]) ctx->pooled_streams ? pool_give(ctx->device, kRoleIn + i, ctx->s_in[i]) : (void)hipStreamDestroy(ctx->s_in[i]);
   }
   if (ctx->s_flush) pool_give(ctx->device, kRoleFlush, ctx->s_flush);
+  if (ctx->d_mark) (void)hipFree(ctx->d_mark);
+  if (ctx->d_mark_gave_up) (void)hipFree(ctx->d_mark_gave_up);
+  if (ctx->h_mark_timeouts) (void)hipHostFree(ctx->h_mark_timeouts);
   if (ctx->ring) (void)hipFree(ctx->ring);
   if (ctx->ring_in) (void)hipFree(ctx->ring_in);
   if (ctx->staging) (void)hipHostFree(ctx->staging);
@@ -1055,6 +1070,38 @@ static hipEvent_t next_marker(ss_ctx *ctx) {
   return ev;
 }
 
+// Where the compute stream stands when a batch is issued, in one of two forms, made when first needed (the
+// dispatch thread enqueues nothing on the compute stream in between, so "now" is the same point either way).
+// An event recorded on the compute stream that the swap stream waits for; or, with SS_CFG_MEMORY_MARKERS and a
+// kernel as the consumer, a one-thread kernel on the compute stream that stores a running count in device memory
+// and a bounded wait kernel on the swap stream.  An event of the compute stream that another stream waits for
+// costs the compute stream about 0.13 ms here (nine of them: 1.3 ms of a 59 ms step; recorded but not waited
+// for, or waited for but recorded long ago: nothing); the one-thread kernel a few microseconds.  A copy-engine
+// transfer is never put behind a wait kernel (it would hold up the engine's queue): those keep the event.
+struct ss_marker {
+  hipEvent_t ev = nullptr;
+  uint64_t count = 0;
+};
+
+static int wait_for_compute(ss_ctx *ctx, ss_marker &m, hipStream_t st, bool consumer_is_kernel) {
+  if (ctx->d_mark && consumer_is_kernel) {
+    if (!m.count) {
+      m.count = ++ctx->mark_count;
+      ss_launch_mark(ctx->compute, ctx->d_mark, m.count);
+      SS_HIP(hipGetLastError());
+    }
+    ss_launch_wait_flag(st, ctx->d_mark, m.count, ctx->mark_limit_ticks, ctx->d_mark_gave_up, ctx->d_mark_timeouts);
+    SS_HIP(hipGetLastError());
+    return SS_OK;
+  }
+  if (!m.ev) {
+    m.ev = next_marker(ctx);
+    SS_HIP(hipEventRecord(m.ev, ctx->compute));
+  }
+  SS_HIP(hipStreamWaitEvent(st, m.ev, 0));
+  return SS_OK;
+}
+
 // Staged swap-out: send what group g has in the ring and has not sent yet.  Per batch, ring_state is
 // 0 = not issued, 1 = gathered into the ring, 2 = on its way to the staging area (or left directly).
 // Every maximal run of gathered batches goes in one copy-engine transfer, which waits for the gathers
@@ -1112,7 +1159,7 @@ static int ring_flush_all(ss_ctx *ctx) {
 // Swap-out of a batch that goes through the ring: gather on the swap-out stream, transfer when every
 // batch of the group has been issued.  Returns 1 if the batch was handled here, 0 if it must leave
 // directly (its ring slot already belongs to a later group: batches issued out of order), or an error code.
-static int swap_out_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
+static int swap_out_staged(ss_ctx *ctx, uint32_t batch, ss_marker &mark) {
   ss_sched &s = ctx->sched;
   const int32_t g = s.group_of[batch];
   const ss_sched::out_group &G = s.groups[(size_t)g];
@@ -1141,7 +1188,10 @@ static int swap_out_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
     s.slot_owner[slot] = g;
   }
   const uint32_t lo = s.out_start[batch], hi = s.out_start[batch + 1];
-  SS_HIP(hipStreamWaitEvent(so, mark, 0));
+  {
+    const int rm = wait_for_compute(ctx, mark, so, true);
+    if (rm != SS_OK) return rm;
+  }
   if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_out_start[s.phase][batch], so));
   // the kernel adds each descriptor's host_off to its staging pointer: point it so that the group's
   // first byte lands on the first byte of the ring slot
@@ -1248,8 +1298,7 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
   // copy-kernel batches take the swap-out streams in turn; copy-engine batches stay on the first
   hipStream_t so = engine ? ctx->s_out[0] : ctx->s_out[batch % ctx->n_s_out];
   // the tensors' last forward use is already enqueued on the compute stream: order after it
-  hipEvent_t mark = next_marker(ctx);
-  SS_HIP(hipEventRecord(mark, ctx->compute));
+  ss_marker mark;
   if (s.group_of[batch] >= 0) {
     const int rc = swap_out_staged(ctx, batch, mark);
     if (rc < 0) return rc;
@@ -1260,7 +1309,10 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
       return SS_OK;
     }
   }
-  SS_HIP(hipStreamWaitEvent(so, mark, 0));
+  {
+    const int rm = wait_for_compute(ctx, mark, so, !engine);
+    if (rm != SS_OK) return rm;
+  }
   if (ctx->cfg.flags & SS_CFG_TIMING) SS_HIP(hipEventRecord(s.ev_out_start[s.phase][batch], so));
   uint64_t bytes = 0;
   for (uint32_t i = lo; i < hi; ++i) bytes += s.out[i].nbytes;
@@ -1309,7 +1361,7 @@ static int swap_out_batch(ss_ctx *ctx, uint32_t batch) {
 // need not be free yet); the batch itself is scattered from the ring into its blocks by the copy kernel,
 // after the compute stream has reached this point.  Returns 1 if handled, 0 if the batch must come back
 // directly, or an error code.
-static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
+static int swap_in_staged(ss_ctx *ctx, uint32_t batch, ss_marker &mark) {
   ss_sched &s = ctx->sched;
   const uint32_t g = (uint32_t)s.in_group_of[batch];
   const ss_sched::in_group &G = s.in_groups[g];
@@ -1357,7 +1409,10 @@ static int swap_in_staged(ss_ctx *ctx, uint32_t batch, hipEvent_t mark) {
   }
   hipStream_t si = ctx->s_in[0];
   const uint32_t lo = s.in_start[batch], hi = s.in_start[batch + 1];
-  SS_HIP(hipStreamWaitEvent(si, mark, 0));                                  // destination blocks are free from here on
+  {
+    const int rm = wait_for_compute(ctx, mark, si, true);                   // destination blocks are free from here on
+    if (rm != SS_OK) return rm;
+  }
   if (ctx->eq) {
     const int rw = eq_stream_wait(ctx, si, s.fetch_seq[g], &ctx->eq->waited_in);
     if (rw != SS_OK) return rw;
@@ -1405,8 +1460,7 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
                                   : use_engine(ctx, ctx->cfg.copy_path_in, false, s.in, lo, hi);
   hipStream_t si = engine ? ctx->s_in[0] : ctx->s_in[batch % ctx->n_s_in];
   // destination blocks are free once the compute stream reaches this point
-  hipEvent_t mark = next_marker(ctx);
-  SS_HIP(hipEventRecord(mark, ctx->compute));
+  ss_marker mark;
   if (hi > lo && s.in_group_of[batch] >= 0) {
     const int rc = swap_in_staged(ctx, batch, mark);
     if (rc < 0) return rc;
@@ -1417,7 +1471,10 @@ static int swap_in_batch(ss_ctx *ctx, uint32_t batch) {
       return SS_OK;
     }
   }
-  SS_HIP(hipStreamWaitEvent(si, mark, 0));
+  {
+    const int rm = wait_for_compute(ctx, mark, si, !engine);
+    if (rm != SS_OK) return rm;
+  }
   // staging slots must be completely written: the batch's tensors left in swap-out batches up to in_dep;
   // with the swap-out batches spread over n streams, the last n of them up to in_dep cover every stream
   // (each stream runs its own batches in order)
@@ -1518,6 +1575,15 @@ static void eq_harvest(ss_ctx *ctx) {
   q->recs.clear();
 }
 
+// a wait for a compute-stream marker gave up during the iteration that has just run
+static int marker_timeouts(ss_ctx *ctx, int *late) {
+  if (!ctx->h_mark_timeouts || !*(volatile uint32_t *)ctx->h_mark_timeouts) return SS_OK;
+  *(volatile uint32_t *)ctx->h_mark_timeouts = 0;
+  SS_HIP(hipMemcpy(ctx->d_mark_gave_up, ctx->h_mark_timeouts + 4, 4, hipMemcpyHostToDevice));
+  *late = SS_E_TIMEOUT;
+  return SS_OK;
+}
+
 extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
   if (!ctx) return SS_E_INVAL;
   ss_sched &s = ctx->sched;
@@ -1583,6 +1649,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
           late = SS_E_TIMEOUT;
         }
       }
+      if ((rc = marker_timeouts(ctx, &late)) != SS_OK) return rc;
       // where this iteration ends on every swap stream
       auto end_of = [&](int k, hipStream_t st) -> int {
         if (!ctx->ev_iter[cur][k])
@@ -1651,6 +1718,7 @@ extern "C" int ss_sync(ss_ctx *ctx, uint32_t what, uint32_t id) {
             late = SS_E_TIMEOUT;
           }
         }
+        if ((rc = marker_timeouts(ctx, &late)) != SS_OK) return rc;
       }
       if ((ctx->cfg.flags & SS_CFG_STALL_TIMING) && s.loaded) {
         // measurement mode: the compute stream is joined too, then every wait of this iteration is

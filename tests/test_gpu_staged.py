@@ -235,7 +235,7 @@ def test_ring_takes_only_gap_free_batches_and_the_rest_leaves_directly(P, torch)
         P.ss_destroy(ctx)
 
 
-@pytest.mark.parametrize("path_in,bare", [(0, 0), (3, 0), (0, 1), (3, 1)])
+@pytest.mark.parametrize("path_in,bare", [(0, 0), (3, 0), (0, 1), (3, 1), (3, 3), (0, 2)])
 def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch, path_in, bare):
     """configuration 2, three iterations, every swap-out through the ring (all its sizes are multiples of
     the alignment), blocks poisoned at their release: compute results equal the run without swapping"""
@@ -245,7 +245,8 @@ def test_1p3b_shape_step_through_the_ring_equals_no_swapping(P, torch, path_in, 
     for swap in (False, True):
         r = SwapRun(B, torch, 2, swap=swap, bpo=11 << 20, bpo_in=4760000, copy_path=B.SS_PATH_STAGED,
                     copy_path_in=path_in,
-                    flags=(B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE | (B.SS_CFG_BARE_RING if bare else 0)) if swap else 0)
+                    flags=(B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE | (B.SS_CFG_BARE_RING if bare & 1 else 0) |
+                           (B.SS_CFG_MEMORY_MARKERS if bare & 2 else 0)) if swap else 0)    # bare: 1 = bare ring transfers, 2 = memory markers
         try:
             for _ in range(3):
                 r.step() if swap else r.step_noswap()
@@ -358,9 +359,9 @@ def test_random_schedules_through_the_rings_both_ways_of_issuing_the_transfers(P
     want_arena = np.full(arena_bytes, 0x3C, dtype=np.uint8)
     oracle.swap_in(want_arena, want_staging, rows)
     stats = []
-    for bare in (0, 1):
+    for bare in (0, P.SS_CFG_BARE_RING, P.SS_CFG_BARE_RING | P.SS_CFG_MEMORY_MARKERS, P.SS_CFG_MEMORY_MARKERS):
         ctx = make_ctx(P, staging_bytes=h, copy_path=P.SS_PATH_STAGED, copy_path_in=path_in, ring_slot_bytes=slot,
-                       ring_bytes=slots * slot, ring_taper=taper, flags=P.SS_CFG_BARE_RING if bare else 0)
+                       ring_bytes=slots * slot, ring_taper=taper, flags=bare)
         try:
             P.ss_bind(ctx, arena.data_ptr(), arena_bytes, torch.cuda.current_stream().cuda_stream)
             P.ss_load_schedule(ctx, d, start, d, start, dep)
@@ -388,7 +389,7 @@ def test_random_schedules_through_the_rings_both_ways_of_issuing_the_transfers(P
             stats.append((st["bytes_out"], st["bytes_in"], st["ring_batches"], st["ring_batches_in"]))
         finally:
             P.ss_destroy(ctx)
-    assert stats[0] == stats[1] and stats[0][0] == 2 * sum(sizes)
+    assert all(x == stats[0] for x in stats) and stats[0][0] == 2 * sum(sizes)
 
 
 def test_batches_outside_the_rings_go_by_copy_kernel_when_ring_transfers_are_bare(P, torch):
@@ -441,7 +442,7 @@ def test_batches_outside_the_rings_go_by_copy_kernel_when_ring_transfers_are_bar
             P.ss_destroy(ctx)
 
 
-@pytest.mark.parametrize("route", ["auto", "rings with events", "rings bare"])
+@pytest.mark.parametrize("route", ["auto", "rings with events", "rings bare", "rings bare, memory markers", "auto, memory markers"])
 def test_iterations_that_end_without_a_host_wait_equal_no_swapping(P, torch, route):
     """configuration 2, twelve iterations ended with SS_SYNC_ITERATION_END (the host runs on; staging slots and ring
     slots are reused by the next iteration only behind this one's readers, on the device), blocks poisoned at
@@ -449,8 +450,9 @@ def test_iterations_that_end_without_a_host_wait_equal_no_swapping(P, torch, rou
     last iteration's bytes"""
     B = P
     from workloads.harness import SwapRun
-    staged = route != "auto"
-    flags = B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE | (B.SS_CFG_BARE_RING if route == "rings bare" else 0)
+    staged = not route.startswith("auto")
+    flags = (B.SS_CFG_POISON_FREE | B.SS_CFG_KEEP_LATE | (B.SS_CFG_BARE_RING if "bare" in route else 0) |
+             (B.SS_CFG_MEMORY_MARKERS if "markers" in route else 0))
     res = []
     for swap in (False, True):
         r = SwapRun(B, torch, 2, swap=swap, bpo=11 << 20, bpo_in=4760000,

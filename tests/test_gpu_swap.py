@@ -203,6 +203,9 @@ def test_ragged_sizes_empty_batches_and_other_destination(P, torch, path):
     # whatever has been issued, not for "the batches up to the last one it needs"
     ragged_round_trip(P, torch, path, reverse_out=True)
     ragged_round_trip(P, torch, path, reverse_out=True, out_streams=3, in_streams=2)
+    # the compute stream's position published through device memory instead of an event (copy-kernel batches only)
+    ragged_round_trip(P, torch, path, flags=P.SS_CFG_MEMORY_MARKERS)
+    ragged_round_trip(P, torch, path, flags=P.SS_CFG_MEMORY_MARKERS, reverse_out=True, out_streams=3, in_streams=2)
 
 
 @pytest.mark.parametrize("window", [1, 2, 5])
