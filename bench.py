@@ -981,6 +981,8 @@ def measure(B, torch, np, bw, o):
     flags = B.SS_CFG_TIMING | (B.SS_CFG_KEEP_LATE if o.policy_mode == "execute-all" else 0)
     if getattr(o, "bare_ring", -1) == 1:
         flags |= B.SS_CFG_BARE_RING
+    if getattr(o, "memory_markers", -1) == 1:
+        flags |= B.SS_CFG_MEMORY_MARKERS
     link = min(bw["d2h_gbps"], bw["h2d_gbps"]) * 1e9
     calib = []
     # the swap-in queue is planned with the no-swap operator time: operators never run faster than that
@@ -1051,7 +1053,7 @@ def measure(B, torch, np, bw, o):
     # Likewise the route: directly between the blocks and the staging area (SS_PATH_AUTO), or through the
     # rings in HBM with one copy-engine transfer per ring slot (SS_PATH_STAGED).  Configuration 3's tensors
     # exceed a ring slot and all go by copy engine: nothing to choose there.
-    grid_fits, path_fits, bare_fits = [], [], []
+    grid_fits, path_fits, bare_fits, marker_fits = [], [], [], []
     if has_compute and cfgno != 3 and o.calibrate > 0:
         if o.path == "auto" and o.path_in is None and cfgno == 2:
             for name, p in (("auto", B.SS_PATH_AUTO), ("staged", B.SS_PATH_STAGED)):
@@ -1068,6 +1070,13 @@ def measure(B, torch, np, bw, o):
                 bare_fits.append({"ring_transfers": name, "ms_per_step": round(t_trial * 1e3, 2)})
             if bare_fits[1]["ms_per_step"] < 0.995 * bare_fits[0]["ms_per_step"]:
                 flags |= B.SS_CFG_BARE_RING
+        if getattr(o, "memory_markers", -1) < 0 and cfgno != 1:
+            # markers of the compute stream's position: events that the swap streams wait for, or a count in device memory
+            for name, fl in (("events", flags), ("device memory", flags | B.SS_CFG_MEMORY_MARKERS)):
+                t_trial = trial("markers through %s" % name, bpo_=bpo, p=path, p_in=path_in, fl=fl)[0]
+                marker_fits.append({"markers": name, "ms_per_step": round(t_trial * 1e3, 2)})
+            if marker_fits[1]["ms_per_step"] < 0.995 * marker_fits[0]["ms_per_step"]:
+                flags |= B.SS_CFG_MEMORY_MARKERS
         if workgroups_out == 0 and path != B.SS_PATH_STAGED:
             for wgo in (0, 8):
                 t_trial = trial("pack grid %s" % (wgo or "default"), bpo_=bpo, wgo=wgo)[0]
@@ -1303,7 +1312,8 @@ def measure(B, torch, np, bw, o):
                    "swap_out_by": out_by, "swap_in_by": in_by,
                    "link_bytes_per_op": bpo, "prefetch_bytes_per_op": bpo_in, "engine_window_in": engine_window_used,
                    "link_model_fits": calib,
-                   "route_fits": path_fits, "pack_grid_fits": grid_fits, "ring_transfer_fits": bare_fits,
+                   "route_fits": path_fits, "pack_grid_fits": grid_fits, "ring_transfer_fits": bare_fits, "marker_fits": marker_fits,
+                   "markers": "a count in device memory (SS_CFG_MEMORY_MARKERS)" if flags & B.SS_CFG_MEMORY_MARKERS else "events",
                    "ring_transfers": ("bare, issued by the library's own thread" if flags & B.SS_CFG_BARE_RING
                                       else "with events on their stream") if B.SS_PATH_STAGED in (path, path_in) else None,
                    "pack_workgroups": workgroups_out or o.workgroups or "default (64)", "policy_mode": o.policy_mode,
@@ -1398,6 +1408,9 @@ def main():
                     help="--policy-mode generated, configuration 2: memory limit as a fraction of the no-swap peak")
     ap.add_argument("--calibrate", type=int, default=4, help="at most this many re-fits of the link model")
     ap.add_argument("--engine-window-out", type=int, default=0, help="the same for copy-engine swap-out batches")
+    ap.add_argument("--memory-markers", type=int, default=-1,
+                    help="1 = the compute stream's position reaches the swap streams' kernel batches through device memory "
+                         "(SS_CFG_MEMORY_MARKERS), 0 = through events, -1 = both are tried and the faster kept")
     ap.add_argument("--iteration-end", default="drain", choices=["drain", "nowait"],
                     help="how a timed step ends: drain = the host waits for the swap streams (SS_SYNC_DRAIN), nowait = it "
                          "does not, the next step is ordered behind this one on the device (SS_SYNC_ITERATION_END)")
