@@ -1029,7 +1029,7 @@ def measure(B, torch, np, bw, o):
 
     def trial(label, **kw):
         r = make(**kw)
-        t = timed(r.step, 3, 2)
+        t = timed(r.step, 3 if t_noswap > 0.02 else 40, 2 if t_noswap > 0.02 else 12)     # short steps: more of them
         forced, dropped = r.n_forced, r.n_dropped
         r.close()
         del r
@@ -1070,7 +1070,7 @@ def measure(B, torch, np, bw, o):
                 bare_fits.append({"ring_transfers": name, "ms_per_step": round(t_trial * 1e3, 2)})
             if bare_fits[1]["ms_per_step"] < 0.995 * bare_fits[0]["ms_per_step"]:
                 flags |= B.SS_CFG_BARE_RING
-        if getattr(o, "memory_markers", -1) < 0 and cfgno != 1:
+        if getattr(o, "memory_markers", -1) < 0:
             # markers of the compute stream's position: events that the swap streams wait for, or a count in device memory
             for name, fl in (("events", flags), ("device memory", flags | B.SS_CFG_MEMORY_MARKERS)):
                 t_trial = trial("markers through %s" % name, bpo_=bpo, p=path, p_in=path_in, fl=fl)[0]
